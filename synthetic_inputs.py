@@ -1,0 +1,144 @@
+"""Seeded synthetic inputs for the MGRIT-GRU workloads.
+
+This module only draws random tensors (shapes, value distributions and the
+rounding of inputs to a storage type).  It holds none of the method's
+arithmetic: no GRU cell, no relaxation, no projection.  Both the CPU oracle's
+tests and the HIP path's tests/bench take their inputs from here so that the two
+sides see bit-identical host arrays.
+
+Draw order (fixed, from ``numpy.random.default_rng(seed)``):
+    x, W, U, b_i, b_h, h0, dL_dhT, W_o, b_o, labels
+Gate order in the stacked 3H dimension is r, z, n (Eq. 1 of the paper).
+
+The public-benchmark inputs the paper trains on (HMDB51 ResNet features,
+UCI-HAR accelerometer traces) are not available here; these seeded tensors of
+the same shapes stand in for them.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field, replace
+from typing import Dict, Optional
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Workload:
+    """One named configuration: sizes, MGRIT hierarchy and value recipe."""
+
+    name: str
+    T: int
+    B: int
+    D: int
+    H: int
+    cf: int
+    levels: int
+    fwd_iters: int
+    bwd_iters: int
+    dtype: str = "fp32"          # "fp32" | "bf16" (x, W, U rounded to bf16)
+    x_dist: str = "normal"       # "normal" | "normal0.1" | "relu_normal"
+    w_dist: str = "xavier"       # "xavier" | "normal0.1"
+    n_classes: int = 51
+    seed: int = 0
+
+    def twin(self, coarsest_steps: int = 8) -> "Workload":
+        """Reduced twin: same B, D, H, cf, levels; T = coarsest_steps*cf^(levels-1)."""
+        T = coarsest_steps * self.cf ** (self.levels - 1)
+        return replace(self, name=self.name + "-twin", T=T)
+
+
+# The five configurations of the benchmark spec, in order (C1..C5).
+WORKLOADS: Dict[str, Workload] = {
+    "C1": Workload("C1", T=64, B=2, D=16, H=32, cf=4, levels=2, fwd_iters=3, bwd_iters=3,
+                   x_dist="normal0.1", w_dist="normal0.1"),
+    "C2": Workload("C2", T=1024, B=16, D=512, H=256, cf=4, levels=2, fwd_iters=8, bwd_iters=0),
+    "C3": Workload("C3", T=2048, B=32, D=1024, H=512, cf=4, levels=3, fwd_iters=2, bwd_iters=2),
+    "C4": Workload("C4", T=4096, B=8, D=2048, H=1024, cf=8, levels=3, fwd_iters=2, bwd_iters=1,
+                   dtype="bf16", x_dist="relu_normal"),
+    "C5": Workload("C5", T=16384, B=4, D=1024, H=1024, cf=4, levels=4, fwd_iters=2, bwd_iters=2),
+}
+
+
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """Round fp32 values to the nearest bf16 (ties to even); result stays fp32."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    bits = a.view(np.uint32).astype(np.uint64)
+    lsb = (bits >> 16) & 1
+    rounded = ((bits + 0x7FFF + lsb) >> 16) << 16
+    return rounded.astype(np.uint32).view(np.float32).reshape(a.shape)
+
+
+def to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """Upper 16 bits of already bf16-representable fp32 values, as uint16."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return (a.view(np.uint32) >> 16).astype(np.uint16).reshape(a.shape)
+
+
+def _xavier(rng: np.random.Generator, fan_out: int, fan_in: int, n_gates: int) -> np.ndarray:
+    # Per gate matrix [fan_out, fan_in] ~ U(+-sqrt(6/(fan_in+fan_out))), gates stacked on rows.
+    bound = np.sqrt(6.0 / (fan_in + fan_out))
+    return rng.uniform(-bound, bound, size=(n_gates * fan_out, fan_in))
+
+
+def make_inputs(wl: Workload, seed: Optional[int] = None) -> Dict[str, np.ndarray]:
+    """Draw every tensor of a workload.  All arrays are C-contiguous float32
+    (labels int64).  For ``dtype == "bf16"`` x, W and U hold bf16-representable
+    values (so an fp64 oracle and a bf16 kernel read the same numbers)."""
+    rng = np.random.default_rng(wl.seed if seed is None else seed)
+    T, B, D, H = wl.T, wl.B, wl.D, wl.H
+
+    if wl.x_dist == "normal":
+        x = rng.standard_normal((T, B, D))
+    elif wl.x_dist == "normal0.1":
+        x = 0.1 * rng.standard_normal((T, B, D))
+    elif wl.x_dist == "relu_normal":
+        x = np.maximum(rng.standard_normal((T, B, D)), 0.0)
+    else:
+        raise ValueError(wl.x_dist)
+
+    if wl.w_dist == "xavier":
+        W = _xavier(rng, H, D, 3)
+        U = _xavier(rng, H, H, 3)
+        b_i = np.zeros(3 * H)
+        b_h = np.zeros(3 * H)
+    elif wl.w_dist == "normal0.1":
+        W = 0.1 * rng.standard_normal((3 * H, D))
+        U = 0.1 * rng.standard_normal((3 * H, H))
+        b_i = 0.1 * rng.standard_normal(3 * H)
+        b_h = 0.1 * rng.standard_normal(3 * H)
+    else:
+        raise ValueError(wl.w_dist)
+
+    h0 = np.zeros((B, H))
+    dL_dhT = rng.standard_normal((B, H)) / np.sqrt(H)
+    W_o = _xavier(rng, wl.n_classes, H, 1)
+    b_o = np.zeros(wl.n_classes)
+    labels = rng.integers(0, wl.n_classes, size=B)
+
+    out = {
+        "x": x, "W": W, "U": U, "b_i": b_i, "b_h": b_h, "h0": h0,
+        "dL_dhT": dL_dhT, "W_o": W_o, "b_o": b_o,
+    }
+    out = {k: np.ascontiguousarray(v, dtype=np.float32) for k, v in out.items()}
+    if wl.dtype == "bf16":
+        for k in ("x", "W", "U"):
+            out[k] = round_to_bf16(out[k])
+    out["labels"] = labels.astype(np.int64)
+    return out
+
+
+def random_small(seed: int, T: int, B: int, D: int, H: int, scale: float = 0.5,
+                 h0_random: bool = True) -> Dict[str, np.ndarray]:
+    """Small dense random problem (all parameters and h0 nonzero) for oracle
+    pins and edge-case parity tests."""
+    rng = np.random.default_rng(seed)
+    d = {
+        "x": rng.standard_normal((T, B, D)),
+        "W": scale * rng.standard_normal((3 * H, D)),
+        "U": scale * rng.standard_normal((3 * H, H)),
+        "b_i": scale * rng.standard_normal(3 * H),
+        "b_h": scale * rng.standard_normal(3 * H),
+        "h0": (rng.standard_normal((B, H)) if h0_random else np.zeros((B, H))),
+        "dL_dhT": rng.standard_normal((B, H)),
+    }
+    return {k: np.ascontiguousarray(v, dtype=np.float32) for k, v in d.items()}

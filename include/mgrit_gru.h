@@ -1,0 +1,168 @@
+/*
+ * mgrit_gru.h -- C ABI of the MI355X (gfx950) MGRIT-GRU library.
+ *
+ * Parallel-in-time forward and backward propagation of a one-layer GRU with
+ * the multigrid-reduction-in-time (MGRIT) cycle of Moon & Cyr, "Parallel
+ * Training of GRU Networks with a Multi-Grid Solver for Long Sequences"
+ * (ICLR 2022), next to the serial time-step scan it replaces.
+ *
+ * Common conventions
+ * ------------------
+ * - Every data pointer is a DEVICE pointer unless the comment says "host".
+ *   All arrays are dense row-major with the last index contiguous.
+ * - x[T,B,D]: row t-1 holds x_t, t = 1..T.  State arrays have T+1 rows
+ *   [(T+1),B,H]: row t holds h_t (or the adjoint w_t), row 0 is the initial
+ *   condition (Sec. 3.1 notation; the paper fixes h_0 = 0, here it is passed).
+ * - Parameters are those of the Classic GRU (Eq. 1), gates stacked in the
+ *   order r, z, n:  W[3H,D] = (W_ir;W_iz;W_in), U[3H,H] = (W_hr;W_hz;W_hn),
+ *   b_i[3H] = (b_ir;b_iz;b_in), b_h[3H] = (b_hr;b_hz;b_hn).  b_hn sits inside
+ *   r*(W_hn h + b_hn), so the two bias sets cannot be merged.
+ * - dtype 0: x, W, U are float.  dtype 1: x, W, U are bf16 (uint16 bit
+ *   patterns); biases, states, projections, accumulation and every output
+ *   stay float.
+ * - Level l of the hierarchy has N_l = T / cf^l steps and step size cf^l
+ *   (Sec. 3.3); `levels` counts the fine level (three levels over 128 steps
+ *   with cf = 4 are grids of 128, 32 and 8 steps).  cf^(levels-1) must divide T.
+ * - Ownership: the caller owns every buffer including the workspace.  The
+ *   library never allocates or frees device memory and never synchronises the
+ *   device; all work is enqueued on `stream` (a hipStream_t passed as void*;
+ *   NULL is the default stream).  Outputs are overwritten, never accumulated.
+ * - Errors: every entry point returns 0 on success or a negative MGRIT_E_*
+ *   code.  Arguments are validated on the host before anything is launched, so
+ *   a failing call leaves all buffers untouched.  No exception crosses the ABI.
+ *   mgrit_gru_strerror() names a code.
+ * - Calls that share a workspace must be ordered on one stream.
+ */
+#ifndef MGRIT_GRU_H
+#define MGRIT_GRU_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define MGRIT_API __attribute__((visibility("default")))
+#else
+#define MGRIT_API
+#endif
+
+enum {
+  MGRIT_OK = 0,
+  MGRIT_E_NULL = -1,        /* a required pointer is NULL */
+  MGRIT_E_SIZE = -2,        /* T, B, D, H, cf, levels or iters out of range */
+  MGRIT_E_HIERARCHY = -3,   /* cf^(levels-1) does not divide T */
+  MGRIT_E_ENUM = -4,        /* unknown propagator / dtype / fine_relax / flags */
+  MGRIT_E_WORKSPACE = -5,   /* workspace smaller than mgrit_gru_workspace_bytes */
+  MGRIT_E_ALIGN = -6,       /* H or D not a multiple of 4 (float dtype) / 8 (bf16), or
+                               a pointer not 16-byte aligned */
+  MGRIT_E_LAUNCH = -7,      /* the HIP runtime refused a launch */
+  MGRIT_E_UNSUPPORTED = -8  /* a valid request this build has no kernel for */
+};
+
+enum { MGRIT_PROP_IMPLICIT = 0,   /* Eq. 16, the paper's propagator on all levels */
+       MGRIT_PROP_CLASSIC = 1 };  /* Eq. 3 (explicit Euler; Classic GRU when step = 1) */
+enum { MGRIT_F32 = 0, MGRIT_BF16 = 1 };
+
+/* flags */
+enum {
+  /* The workspace already holds the input projection of these x, W, b_i (left
+   * there by an earlier call with the same sizes and dtype): skip recomputing
+   * it.  The paper likewise computes per-step input features once and reuses
+   * them on coarse grids and in back-propagation (Appendix A.3.2). */
+  MGRIT_REUSE_PROJECTION = 1
+};
+
+typedef struct {
+  int32_t T, B, D, H;   /* sequence length, batch, input width, hidden width */
+  int32_t cf;           /* coarsening factor (Sec. 3.1), >= 1 */
+  int32_t levels;       /* grid levels including the fine one, >= 1; 1 = serial */
+  int32_t iters;        /* MGRIT cycles applied by this call (Remark 1), >= 0 */
+  int32_t fine_relax;   /* level-0 relaxation in Alg. 2 line 1: 0 = F, 1 = FCF
+                           (Eq. 8); coarser levels always use FCF */
+  int32_t propagator;   /* MGRIT_PROP_* */
+  int32_t dtype;        /* MGRIT_F32 / MGRIT_BF16 */
+  int32_t flags;        /* MGRIT_REUSE_PROJECTION or 0 */
+} mgrit_gru_cfg;
+
+/* Bytes of device workspace one call needs (host-only computation).  The same
+ * workspace serves every entry point; its first bytes hold the input
+ * projection P[T,B,3H] (float) so that MGRIT_REUSE_PROJECTION works across
+ * calls.  cfg: host pointer.  bytes: host pointer, receives the size. */
+MGRIT_API int mgrit_gru_workspace_bytes(const mgrit_gru_cfg* cfg, size_t* bytes);
+
+/* Serial forward propagation h_t = Phi_1(x_t, h_{t-1}), t = 1..T: the solution
+ * of f(h) = 0 in Eq. 4, with Phi the step selected by cfg->propagator (Eq. 16 or
+ * Eq. 3).  cf, levels, iters, fine_relax are ignored.
+ *   h0[B,H] in; h_out[(T+1),B,H] out (row 0 receives h0). */
+MGRIT_API int gru_serial_scan(const mgrit_gru_cfg* cfg, const void* W, const void* U,
+                    const float* b_i, const float* b_h, const void* x,
+                    const float* h0, float* h_out,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* MGRIT forward propagation: cfg->iters applications of MGProp (Alg. 2, made
+ * recursive over cfg->levels as in Remark 2, coarse equation Eq. 11, coarsest
+ * level solved by serial propagation) to the iterate in h_inout.
+ *   h_inout[(T+1),B,H]: initial guess in (Alg. 3 uses zeros), iterate out; row 0
+ *     is overwritten with h0.
+ *   resnorm_out[iters] (device, may be NULL): 2-norm of the level-0 residual
+ *     (Eq. 4) at the coarse points after the relaxation of Alg. 2 line 1, one
+ *     value per cycle (the residual at F-points is zero there). */
+MGRIT_API int mgrit_gru_forward(const mgrit_gru_cfg* cfg, const void* W, const void* U,
+                      const float* b_i, const float* b_h, const void* x,
+                      const float* h0, float* h_inout, float* resnorm_out,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* Serial back-propagation through time for a loss on h_T (discrete adjoint of
+ * the step, Appendix A.2): w_T = dL_dhT, w_{t-1} = (dPhi_1/dh)^T(x_t,h_{t-1}) w_t,
+ * and the parameter gradients g = sum_t w_t dh_t/dTheta (Alg. 3, gradient line).
+ *   h[(T+1),B,H] in: forward states (linearisation points).
+ *   w_out[(T+1),B,H] out; row 0 is dL/dh_0.
+ *   dW[3H,D], dU[3H,H], db_i[3H], db_h[3H] out (float). */
+MGRIT_API int gru_serial_scan_backward(const mgrit_gru_cfg* cfg, const void* W, const void* U,
+                             const float* b_i, const float* b_h, const void* x,
+                             const float* h, const float* dL_dhT, float* w_out,
+                             float* dW, float* dU, float* db_i, float* db_h,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* MGRIT back-propagation: cfg->iters applications of MGBackProp, i.e. the same
+ * cycle run on the adjoint recurrence in reversed time (Appendix A.1 last
+ * paragraph, A.2 last paragraph; Alg. 3 backward block), each level step being
+ * the transposed Jacobian of that level's forward step linearised at the given
+ * forward iterate h; then the parameter gradients from the final w.
+ *   w_inout[(T+1),B,H]: initial guess in (Alg. 3 uses zeros), iterate out; row T
+ *     is overwritten with dL_dhT.
+ *   resnorm_out[iters] (device, may be NULL): as in mgrit_gru_forward, for the
+ *     adjoint level-0 equation.
+ *   dW, dU, db_i, db_h: as in gru_serial_scan_backward; any of them may be NULL
+ *     only if all four are NULL (then no gradients are formed). */
+MGRIT_API int mgrit_gru_backward(const mgrit_gru_cfg* cfg, const void* W, const void* U,
+                       const float* b_i, const float* b_h, const void* x,
+                       const float* h, const float* dL_dhT, float* w_inout,
+                       float* resnorm_out,
+                       float* dW, float* dU, float* db_i, float* db_h,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* Name of an error code (host string with static storage). */
+MGRIT_API const char* mgrit_gru_strerror(int code);
+
+/* Kernel timing for benchmarks.  While enabled, every launch of the fused
+ * step kernels (the dominant kernels: recurrent contraction + gates) is
+ * bracketed by HIP events on the launch stream.  mgrit_gru_profile_read
+ * synchronises those events and returns, per kernel class, the number of
+ * launches, their summed duration in milliseconds and their summed
+ * algorithmic flops and bytes; it then clears the record.  Event objects are
+ * host-side and created on demand; nothing here touches device memory.
+ *   kind: 0 = forward step (Phi), 1 = adjoint step (Phi^T), 2 = projection GEMM,
+ *         3 = weight-gradient GEMMs.
+ * All out-pointers are host pointers. */
+MGRIT_API int mgrit_gru_profile_enable(int on);
+MGRIT_API int mgrit_gru_profile_read(int kind, int64_t* launches, double* ms,
+                           double* flops, double* bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MGRIT_GRU_H */

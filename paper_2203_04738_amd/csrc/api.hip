@@ -1,0 +1,581 @@
+// C ABI of the MGRIT-GRU library: argument validation, workspace layout and the
+// host-side level drivers that enqueue the kernels of one MGRIT cycle
+// (Alg. 2 of the paper, recursive per Remark 2) for the forward recurrence and
+// for its adjoint in reversed time.
+#include <cstdint>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "common.h"
+
+namespace mg {
+
+constexpr int MAX_LEVELS = 24;
+
+// ---------------------------------------------------------------------------
+// profiling brackets
+// ---------------------------------------------------------------------------
+struct ProfRec {
+  int kind;
+  hipEvent_t e0, e1;
+  double flops, bytes;
+};
+static bool g_prof = false;
+static std::mutex g_prof_mu;
+static std::vector<ProfRec> g_recs;
+
+void prof_begin(int kind, hipStream_t s) {
+  if (!g_prof) return;
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  ProfRec r;
+  r.kind = kind;
+  r.flops = r.bytes = 0;
+  if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) return;
+  (void)hipEventRecord(r.e0, s);
+  g_recs.push_back(r);
+}
+
+void prof_end(int kind, double flops, double bytes, hipStream_t s) {
+  if (!g_prof) return;
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (g_recs.empty() || g_recs.back().kind != kind) return;
+  g_recs.back().flops = flops;
+  g_recs.back().bytes = bytes;
+  (void)hipEventRecord(g_recs.back().e1, s);
+}
+
+// ---------------------------------------------------------------------------
+// validation and workspace layout (host only)
+// ---------------------------------------------------------------------------
+struct Layout {
+  int L;
+  long long N[MAX_LEVELS];        // steps on level l
+  long long S[MAX_LEVELS];        // step size cf^l
+  size_t P;                       // offsets in bytes
+  size_t u[MAX_LEVELS], g[MAX_LEVELS];
+  size_t tmp;                     // cf == 1 only: Jacobi scratch for the C-sweep
+  size_t norm;
+  size_t kap[MAX_LEVELS];
+  size_t UT, part;
+  size_t total;
+};
+
+static size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+static int check_cfg(const mgrit_gru_cfg* c, bool need_hierarchy) {
+  if (!c) return MGRIT_E_NULL;
+  if (c->T < 1 || c->B < 1 || c->D < 1 || c->H < 1) return MGRIT_E_SIZE;
+  if ((long long)c->T * c->B > (1LL << 30)) return MGRIT_E_SIZE;
+  if (c->iters < 0) return MGRIT_E_SIZE;
+  if (c->propagator != MGRIT_PROP_IMPLICIT && c->propagator != MGRIT_PROP_CLASSIC)
+    return MGRIT_E_ENUM;
+  if (c->dtype != MGRIT_F32 && c->dtype != MGRIT_BF16) return MGRIT_E_ENUM;
+  if (c->flags & ~MGRIT_REUSE_PROJECTION) return MGRIT_E_ENUM;
+  if (need_hierarchy) {
+    if (c->cf < 1 || c->levels < 1 || c->levels > MAX_LEVELS) return MGRIT_E_SIZE;
+    if (c->fine_relax != 0 && c->fine_relax != 1) return MGRIT_E_ENUM;
+    long long s = 1;
+    for (int l = 1; l < c->levels; ++l) {
+      s *= c->cf;
+      if (s > c->T) return MGRIT_E_HIERARCHY;
+    }
+    if (c->T % s != 0) return MGRIT_E_HIERARCHY;
+  }
+  const int mult = c->dtype == MGRIT_BF16 ? 8 : 4;
+  if (c->H % mult != 0 || c->D % mult != 0) return MGRIT_E_ALIGN;
+  if (c->dtype == MGRIT_BF16) return MGRIT_E_UNSUPPORTED;
+  return MGRIT_OK;
+}
+
+static int make_layout(const mgrit_gru_cfg* c, Layout* lay) {
+  std::memset(lay, 0, sizeof(*lay));
+  const int L = c->levels < 1 ? 1 : c->levels;
+  lay->L = L;
+  long long s = 1;
+  for (int l = 0; l < L; ++l) {
+    lay->S[l] = s;
+    lay->N[l] = c->T / s;
+    s *= c->cf;
+  }
+  const size_t BH = (size_t)c->B * c->H * sizeof(float);
+  size_t off = 0;
+  lay->P = off;
+  off = align_up(off + (size_t)c->T * c->B * 3 * c->H * sizeof(float));
+  for (int l = 1; l < L; ++l) {
+    lay->u[l] = off;
+    off = align_up(off + (size_t)(lay->N[l] + 1) * BH);
+    lay->g[l] = off;
+    off = align_up(off + (size_t)(lay->N[l] + 1) * BH);
+  }
+  lay->tmp = off;
+  if (c->cf == 1 && L > 1) off = align_up(off + (size_t)(c->T + 1) * BH);
+  lay->norm = off;
+  off = align_up(off + (size_t)(c->iters > 0 ? c->iters : 1) * sizeof(double));
+  for (int l = 0; l < L; ++l) {
+    lay->kap[l] = off;
+    off = align_up(off + (size_t)(lay->N[l] + 1) * BH * (l == 0 ? 5 : 4));
+  }
+  lay->UT = off;
+  off = align_up(off + (size_t)3 * c->H * c->H * sizeof(float));
+  lay->part = off;
+  off = align_up(off + grad_partial_floats(c->T, c->B, c->D, c->H) * sizeof(float));
+  lay->total = off;
+  return MGRIT_OK;
+}
+
+static bool misaligned(const void* p) { return ((uintptr_t)p & 15) != 0; }
+
+#define CHECK_HIP(expr)                          \
+  do {                                           \
+    if ((expr) != hipSuccess) return MGRIT_E_LAUNCH; \
+  } while (0)
+
+// ---------------------------------------------------------------------------
+// forward drivers
+// ---------------------------------------------------------------------------
+struct FwdCtx {
+  const mgrit_gru_cfg* c;
+  const Layout* lay;
+  const float *U, *b_h, *P;
+  float* ul[MAX_LEVELS];
+  float* gl[MAX_LEVELS];
+  float* tmp;
+  double* norm;     // accumulator of the current cycle (may be null)
+  hipStream_t s;
+};
+
+static PhiArgs phi_base(const FwdCtx& x, int l) {
+  PhiArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.U = x.U;
+  a.b_h = x.b_h;
+  a.P = x.P;
+  a.u_in = x.ul[l];
+  a.u = x.ul[l];
+  a.g = x.gl[l];
+  a.B = x.c->B;
+  a.H = x.c->H;
+  a.gamma = (float)x.lay->S[l];
+  a.propagator = x.c->propagator;
+  return a;
+}
+
+// F-relaxation (Alg. 1) or, with include_c, FC-relaxation on level l: sub-step j
+// advances every interval from point i*cf+j-1 to i*cf+j.  All intervals move in one
+// launch, so the C-sweep reads only values written by earlier launches (Jacobi in
+// the coarse points).
+static int relax_fwd(const FwdCtx& x, int l, bool include_c) {
+  const long long cf = x.c->cf, S = x.lay->S[l];
+  const int nint = (int)(x.lay->N[l] / cf);
+  for (long long j = 1; j < cf + (include_c ? 1 : 0); ++j) {
+    PhiArgs a = phi_base(x, l);
+    a.mode = STEP_RELAX;
+    a.nk = nint;
+    a.in = Idx{j - 1, cf};
+    a.o = Idx{j, cf};
+    a.p = Idx{j * S - 1, cf * S};
+    const bool overlap = (cf == 1);   // reads and writes would share points
+    if (overlap) a.u = x.tmp;
+    CHECK_HIP(launch_phi_step(a, x.s));
+    if (overlap)
+      CHECK_HIP(launch_copy_points(x.ul[l], x.tmp, a.o, a.o, nint, (long long)a.B * a.H, x.s));
+  }
+  return MGRIT_OK;
+}
+
+static int vcycle_fwd(const FwdCtx& x, int l) {
+  const long long cf = x.c->cf, S = x.lay->S[l], N = x.lay->N[l];
+  const int L = x.lay->L;
+  if (l == L - 1) {
+    // coarsest level: serial propagation (Appendix A.1)
+    for (long long k = 1; k <= N; ++k) {
+      PhiArgs a = phi_base(x, l);
+      a.mode = STEP_RELAX;
+      a.nk = 1;
+      a.in = Idx{k - 1, 0};
+      a.o = Idx{k, 0};
+      a.p = Idx{k * S - 1, 0};
+      CHECK_HIP(launch_phi_step(a, x.s));
+    }
+    return MGRIT_OK;
+  }
+  int rc;
+  // Alg. 2 line 1
+  if (l == 0 && x.c->fine_relax == 0) {
+    if ((rc = relax_fwd(x, l, false))) return rc;
+  } else {
+    if ((rc = relax_fwd(x, l, true))) return rc;
+    if ((rc = relax_fwd(x, l, false))) return rc;
+  }
+  const int Nc = (int)(N / cf);
+  const long long Sc = x.lay->S[l + 1];
+  {  // lines 2-3: residual at the coarse points, restricted state
+    PhiArgs a = phi_base(x, l);
+    a.mode = STEP_RESID;
+    a.nk = Nc;
+    a.in = Idx{cf - 1, cf};
+    a.o = Idx{cf, cf};
+    a.p = Idx{cf * S - 1, cf * S};
+    a.a = Idx{1, 1};
+    a.uc = x.ul[l + 1];
+    a.gc = x.gl[l + 1];
+    a.norm = l == 0 ? x.norm : nullptr;
+    CHECK_HIP(launch_phi_step(a, x.s));
+  }
+  {  // line 4, right-hand side of Eq. 11: g_c = A_c(R u') - R r
+    PhiArgs a = phi_base(x, l + 1);
+    a.mode = STEP_RHS;
+    a.nk = Nc;
+    a.in = Idx{0, 1};
+    a.o = Idx{1, 1};
+    a.p = Idx{Sc - 1, Sc};
+    CHECK_HIP(launch_phi_step(a, x.s));
+  }
+  if ((rc = vcycle_fwd(x, l + 1))) return rc;
+  // line 5 at the coarse points: u'_{cf j} + (v_j - u'_{cf j}) = v_j.  F-points
+  // would receive the same correction but are overwritten by line 6.
+  CHECK_HIP(launch_copy_points(x.ul[l], x.ul[l + 1], Idx{cf, cf}, Idx{1, 1}, Nc,
+                               (long long)x.c->B * x.c->H, x.s));
+  // line 6
+  return relax_fwd(x, l, false);
+}
+
+static int run_projection(const mgrit_gru_cfg* c, const void* W, const float* b_i, const void* x,
+                          float* P, hipStream_t s) {
+  if (c->flags & MGRIT_REUSE_PROJECTION) return MGRIT_OK;
+  CHECK_HIP(launch_projection((const float*)x, (const float*)W, b_i, P, (long long)c->T * c->B,
+                              3 * c->H, c->D, s));
+  return MGRIT_OK;
+}
+
+static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, const void* U,
+                        const float* b_i, const float* b_h, const void* x, const float* h0,
+                        float* h, float* resnorm, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_cfg(cin, !serial);
+  if (rc) return rc;
+  if (!W || !U || !b_i || !b_h || !x || !h0 || !h || !ws) return MGRIT_E_NULL;
+  if (misaligned(W) || misaligned(U) || misaligned(x) || misaligned(h0) || misaligned(h) ||
+      misaligned(ws))
+    return MGRIT_E_ALIGN;
+  mgrit_gru_cfg c = *cin;
+  if (serial) {
+    c.levels = 1;
+    c.cf = 1;
+    c.iters = 1;
+    c.fine_relax = 1;
+  }
+  Layout lay;
+  make_layout(&c, &lay);
+  if (ws_bytes < lay.total) return MGRIT_E_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  char* base = (char*)ws;
+
+  FwdCtx ctx;
+  ctx.c = &c;
+  ctx.lay = &lay;
+  ctx.U = (const float*)U;
+  ctx.b_h = b_h;
+  ctx.P = (const float*)(base + lay.P);
+  ctx.s = s;
+  ctx.tmp = (float*)(base + lay.tmp);
+  ctx.ul[0] = h;
+  ctx.gl[0] = nullptr;
+  for (int l = 1; l < lay.L; ++l) {
+    ctx.ul[l] = (float*)(base + lay.u[l]);
+    ctx.gl[l] = (float*)(base + lay.g[l]);
+  }
+  double* norm = (double*)(base + lay.norm);
+
+  if ((rc = run_projection(&c, W, b_i, x, (float*)(base + lay.P), s))) return rc;
+  const long long BH = (long long)c.B * c.H;
+  for (int l = 0; l < lay.L; ++l)   // point 0 of every level is the initial condition
+    CHECK_HIP(launch_copy_points(ctx.ul[l], h0, Idx{0, 0}, Idx{0, 0}, 1, BH, s));
+  if (resnorm && c.iters > 0) CHECK_HIP(launch_fill_f64(norm, c.iters, 0.0, s));
+  for (int it = 0; it < c.iters; ++it) {
+    ctx.norm = resnorm ? norm + it : nullptr;
+    if ((rc = vcycle_fwd(ctx, 0))) return rc;
+  }
+  if (resnorm && !serial) CHECK_HIP(launch_sqrt_to_float(norm, resnorm, c.iters, s));
+  return MGRIT_OK;
+}
+
+// ---------------------------------------------------------------------------
+// adjoint drivers (time reversed: point N_l is fixed, steps run k -> k-1)
+// ---------------------------------------------------------------------------
+struct BwdCtx {
+  const mgrit_gru_cfg* c;
+  const Layout* lay;
+  const float* UT;
+  const float* kap[MAX_LEVELS];
+  float* wl[MAX_LEVELS];
+  float* gl[MAX_LEVELS];
+  float* tmp;
+  double* norm;
+  hipStream_t s;
+};
+
+static AdjArgs adj_base(const BwdCtx& x, int l) {
+  AdjArgs a;
+  std::memset(&a, 0, sizeof(a));
+  a.UT = x.UT;
+  a.kap = x.kap[l];
+  a.kw = (l == 0 ? 5 : 4) * x.c->H;
+  a.w_in = x.wl[l];
+  a.w = x.wl[l];
+  a.g = x.gl[l];
+  a.B = x.c->B;
+  a.H = x.c->H;
+  return a;
+}
+
+// Relaxation of the reversed recurrence: interval i hangs below coarse point
+// (i+1)*cf; sub-step j moves from point (i+1)cf-j+1 to (i+1)cf-j with the
+// coefficients of level step (i+1)cf-j+1.
+static int relax_bwd(const BwdCtx& x, int l, bool include_c) {
+  const long long cf = x.c->cf;
+  const int nint = (int)(x.lay->N[l] / cf);
+  for (long long j = 1; j < cf + (include_c ? 1 : 0); ++j) {
+    AdjArgs a = adj_base(x, l);
+    a.mode = STEP_RELAX;
+    a.nk = nint;
+    a.in = Idx{cf - j + 1, cf};
+    a.k = a.in;
+    a.o = Idx{cf - j, cf};
+    const bool overlap = (cf == 1);
+    if (overlap) a.w = x.tmp;
+    CHECK_HIP(launch_adj_step(a, x.s));
+    if (overlap)
+      CHECK_HIP(launch_copy_points(x.wl[l], x.tmp, a.o, a.o, nint, (long long)a.B * a.H, x.s));
+  }
+  return MGRIT_OK;
+}
+
+static int vcycle_bwd(const BwdCtx& x, int l) {
+  const long long cf = x.c->cf, N = x.lay->N[l];
+  const int L = x.lay->L;
+  if (l == L - 1) {
+    for (long long k = N; k >= 1; --k) {
+      AdjArgs a = adj_base(x, l);
+      a.mode = STEP_RELAX;
+      a.nk = 1;
+      a.in = Idx{k, 0};
+      a.k = Idx{k, 0};
+      a.o = Idx{k - 1, 0};
+      CHECK_HIP(launch_adj_step(a, x.s));
+    }
+    return MGRIT_OK;
+  }
+  int rc;
+  if (l == 0 && x.c->fine_relax == 0) {
+    if ((rc = relax_bwd(x, l, false))) return rc;
+  } else {
+    if ((rc = relax_bwd(x, l, true))) return rc;
+    if ((rc = relax_bwd(x, l, false))) return rc;
+  }
+  const int Nc = (int)(N / cf);
+  {  // residual at coarse points i*cf, i = 0..Nc-1, and restriction
+    AdjArgs a = adj_base(x, l);
+    a.mode = STEP_RESID;
+    a.nk = Nc;
+    a.in = Idx{1, cf};
+    a.k = Idx{1, cf};
+    a.o = Idx{0, cf};
+    a.a = Idx{0, 1};
+    a.wc = x.wl[l + 1];
+    a.gc = x.gl[l + 1];
+    a.norm = l == 0 ? x.norm : nullptr;
+    CHECK_HIP(launch_adj_step(a, x.s));
+  }
+  {  // coarse right-hand side
+    AdjArgs a = adj_base(x, l + 1);
+    a.mode = STEP_RHS;
+    a.nk = Nc;
+    a.in = Idx{1, 1};
+    a.k = Idx{1, 1};
+    a.o = Idx{0, 1};
+    CHECK_HIP(launch_adj_step(a, x.s));
+  }
+  if ((rc = vcycle_bwd(x, l + 1))) return rc;
+  CHECK_HIP(launch_copy_points(x.wl[l], x.wl[l + 1], Idx{0, cf}, Idx{0, 1}, Nc,
+                               (long long)x.c->B * x.c->H, x.s));
+  return relax_bwd(x, l, false);
+}
+
+static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, const void* U,
+                         const float* b_i, const float* b_h, const void* x, const float* h,
+                         const float* dL_dhT, float* w, float* resnorm, float* dW, float* dU,
+                         float* db_i, float* db_h, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_cfg(cin, !serial);
+  if (rc) return rc;
+  if (!W || !U || !b_i || !b_h || !x || !h || !dL_dhT || !w || !ws) return MGRIT_E_NULL;
+  const int ngrad = (dW != nullptr) + (dU != nullptr) + (db_i != nullptr) + (db_h != nullptr);
+  if (ngrad != 0 && ngrad != 4) return MGRIT_E_NULL;
+  if (serial && ngrad != 4) return MGRIT_E_NULL;
+  if (misaligned(W) || misaligned(U) || misaligned(x) || misaligned(h) || misaligned(dL_dhT) ||
+      misaligned(w) || misaligned(ws) || misaligned(dW) || misaligned(dU))
+    return MGRIT_E_ALIGN;
+  mgrit_gru_cfg c = *cin;
+  if (serial) {
+    c.levels = 1;
+    c.cf = 1;
+    c.iters = 1;
+    c.fine_relax = 1;
+  }
+  Layout lay;
+  make_layout(&c, &lay);
+  if (ws_bytes < lay.total) return MGRIT_E_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  char* base = (char*)ws;
+  const float* P = (const float*)(base + lay.P);
+  const long long BH = (long long)c.B * c.H;
+
+  if ((rc = run_projection(&c, W, b_i, x, (float*)(base + lay.P), s))) return rc;
+  CHECK_HIP(launch_transpose((const float*)U, (float*)(base + lay.UT), 3 * c.H, c.H, s));
+
+  BwdCtx ctx;
+  ctx.c = &c;
+  ctx.lay = &lay;
+  ctx.UT = (const float*)(base + lay.UT);
+  ctx.s = s;
+  ctx.tmp = (float*)(base + lay.tmp);
+  ctx.wl[0] = w;
+  ctx.gl[0] = nullptr;
+  for (int l = 0; l < lay.L; ++l) {
+    ctx.kap[l] = (const float*)(base + lay.kap[l]);
+    if (l > 0) {
+      ctx.wl[l] = (float*)(base + lay.u[l]);
+      ctx.gl[l] = (float*)(base + lay.g[l]);
+    }
+    // coefficient vectors of every step of level l: step k is linearised at the
+    // forward state of level point k-1 (fine point (k-1)*S) and input x_{k*S}
+    PhiArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.U = (const float*)U;
+    a.b_h = b_h;
+    a.P = P;
+    a.u_in = h;
+    a.uc = (float*)(base + lay.kap[l]);
+    a.kappa_width = (l == 0 ? 5 : 4) * c.H;
+    a.B = c.B;
+    a.H = c.H;
+    a.gamma = (float)lay.S[l];
+    a.propagator = c.propagator;
+    a.mode = STEP_KAPPA;
+    a.nk = (int)lay.N[l];
+    a.in = Idx{0, lay.S[l]};
+    a.p = Idx{lay.S[l] - 1, lay.S[l]};
+    a.o = Idx{1, 1};
+    CHECK_HIP(launch_phi_step(a, s));
+    // the terminal condition w_T = dL/dh_T is the fixed end point of every level
+    CHECK_HIP(launch_copy_points(ctx.wl[l], dL_dhT, Idx{lay.N[l], 0}, Idx{0, 0}, 1, BH, s));
+  }
+  double* norm = (double*)(base + lay.norm);
+  if (resnorm && c.iters > 0) CHECK_HIP(launch_fill_f64(norm, c.iters, 0.0, s));
+  for (int it = 0; it < c.iters; ++it) {
+    ctx.norm = resnorm ? norm + it : nullptr;
+    if ((rc = vcycle_bwd(ctx, 0))) return rc;
+  }
+  if (resnorm && !serial) CHECK_HIP(launch_sqrt_to_float(norm, resnorm, c.iters, s));
+  if (ngrad == 4)
+    CHECK_HIP(launch_param_grads(ctx.kap[0], w, h, (const float*)x, dW, dU, db_i, db_h,
+                                 (float*)(base + lay.part), c.T, c.B, c.D, c.H, s));
+  return MGRIT_OK;
+}
+
+}  // namespace mg
+
+// ---------------------------------------------------------------------------
+// exported symbols
+// ---------------------------------------------------------------------------
+using namespace mg;
+
+extern "C" {
+
+int mgrit_gru_workspace_bytes(const mgrit_gru_cfg* cfg, size_t* bytes) {
+  if (!bytes) return MGRIT_E_NULL;
+  int rc = check_cfg(cfg, true);
+  if (rc) return rc;
+  Layout lay;
+  make_layout(cfg, &lay);
+  *bytes = lay.total;
+  return MGRIT_OK;
+}
+
+int gru_serial_scan(const mgrit_gru_cfg* cfg, const void* W, const void* U, const float* b_i,
+                    const float* b_h, const void* x, const float* h0, float* h_out,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+  return forward_impl(cfg, true, W, U, b_i, b_h, x, h0, h_out, nullptr, workspace,
+                      workspace_bytes, stream);
+}
+
+int mgrit_gru_forward(const mgrit_gru_cfg* cfg, const void* W, const void* U, const float* b_i,
+                      const float* b_h, const void* x, const float* h0, float* h_inout,
+                      float* resnorm_out, void* workspace, size_t workspace_bytes, void* stream) {
+  return forward_impl(cfg, false, W, U, b_i, b_h, x, h0, h_inout, resnorm_out, workspace,
+                      workspace_bytes, stream);
+}
+
+int gru_serial_scan_backward(const mgrit_gru_cfg* cfg, const void* W, const void* U,
+                             const float* b_i, const float* b_h, const void* x, const float* h,
+                             const float* dL_dhT, float* w_out, float* dW, float* dU, float* db_i,
+                             float* db_h, void* workspace, size_t workspace_bytes, void* stream) {
+  return backward_impl(cfg, true, W, U, b_i, b_h, x, h, dL_dhT, w_out, nullptr, dW, dU, db_i,
+                       db_h, workspace, workspace_bytes, stream);
+}
+
+int mgrit_gru_backward(const mgrit_gru_cfg* cfg, const void* W, const void* U, const float* b_i,
+                       const float* b_h, const void* x, const float* h, const float* dL_dhT,
+                       float* w_inout, float* resnorm_out, float* dW, float* dU, float* db_i,
+                       float* db_h, void* workspace, size_t workspace_bytes, void* stream) {
+  return backward_impl(cfg, false, W, U, b_i, b_h, x, h, dL_dhT, w_inout, resnorm_out, dW, dU,
+                       db_i, db_h, workspace, workspace_bytes, stream);
+}
+
+const char* mgrit_gru_strerror(int code) {
+  switch (code) {
+    case MGRIT_OK: return "ok";
+    case MGRIT_E_NULL: return "null pointer";
+    case MGRIT_E_SIZE: return "size out of range";
+    case MGRIT_E_HIERARCHY: return "cf^(levels-1) does not divide T";
+    case MGRIT_E_ENUM: return "unknown enum or flag value";
+    case MGRIT_E_WORKSPACE: return "workspace too small";
+    case MGRIT_E_ALIGN: return "width not a multiple of 4 (8 for bf16) or pointer not 16-byte aligned";
+    case MGRIT_E_LAUNCH: return "HIP launch failed";
+    case MGRIT_E_UNSUPPORTED: return "unsupported configuration";
+    default: return "unknown error";
+  }
+}
+
+int mgrit_gru_profile_enable(int on) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  g_prof = on != 0;
+  return MGRIT_OK;
+}
+
+int mgrit_gru_profile_read(int kind, int64_t* launches, double* ms, double* flops, double* bytes) {
+  if (!launches || !ms || !flops || !bytes) return MGRIT_E_NULL;
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  *launches = 0;
+  *ms = *flops = *bytes = 0.0;
+  std::vector<ProfRec> keep;
+  for (auto& r : g_recs) {
+    if (r.kind != kind) {
+      keep.push_back(r);
+      continue;
+    }
+    float t = 0.f;
+    if (hipEventSynchronize(r.e1) == hipSuccess && hipEventElapsedTime(&t, r.e0, r.e1) == hipSuccess) {
+      *launches += 1;
+      *ms += t;
+      *flops += r.flops;
+      *bytes += r.bytes;
+    }
+    (void)hipEventDestroy(r.e0);
+    (void)hipEventDestroy(r.e1);
+  }
+  g_recs.swap(keep);
+  return MGRIT_OK;
+}
+
+}  // extern "C"

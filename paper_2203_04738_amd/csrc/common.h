@@ -1,0 +1,86 @@
+// Internal declarations shared by the library's translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/mgrit_gru.h"
+
+namespace mg {
+
+// Affine index of launch point i into an array of [*, B, width] blocks.
+struct Idx {
+  long long off, str;
+  __host__ __device__ inline long long at(long long i) const { return off + i * str; }
+};
+
+enum StepMode {
+  STEP_RELAX = 0,   // out[o] = step(in) + g[o]                       (Alg. 1 update; coarsest solve)
+  STEP_RESID = 1,   // r = cur[o] - step(in) - g[o];  gc[a] = -r; uc[a] = cur[o]; norm += r^2
+                    //                                                 (Alg. 2 lines 2-3)
+  STEP_RHS = 2,     // g[o] = cur[o] - step(in) + g[o]                 (Eq. 11 right-hand side)
+  STEP_KAPPA = 3    // forward only: adjoint coefficient vectors of the step
+};
+
+// One launch of the fused forward step  Phi_gamma(x, h) over nk level points.
+struct PhiArgs {
+  const float* U;      // [3H,H]
+  const float* b_h;    // [3H]
+  const float* P;      // [T,B,3H] input projection
+  const float* u_in;   // state array the step reads from
+  float* u;            // level state array (out for RELAX, cur for RESID/RHS)
+  float* g;            // level right-hand side array (may be null = 0); RHS writes it
+  float* uc;           // RESID: coarse state array   | KAPPA: coefficient array
+  float* gc;           // RESID: coarse right-hand side array
+  double* norm;        // RESID: sum of r^2 (may be null)
+  Idx in, p, o, a;     // point indices: input state, projection row, out/cur/g, coarse
+  int nk, B, H;
+  int kappa_width;     // KAPPA: 4H or 5H floats per (point, b)
+  float gamma;
+  int propagator;
+  int mode;
+};
+
+// One launch of the fused adjoint step  w_out = (dPhi/dh)^T w_in  over nk points.
+struct AdjArgs {
+  const float* UT;     // [H,3H] transposed recurrent weights
+  const float* kap;    // coefficient array of this level, [*,B,kw]: k_r,k_z,k_q,k_d(,k_n)
+  const float* w_in;   // adjoint array the step reads from
+  float* w;            // level adjoint array (out / cur)
+  float* g;            // level right-hand side (may be null)
+  float* wc;           // RESID: coarse adjoint array
+  float* gc;           // RESID: coarse right-hand side
+  double* norm;
+  Idx in, k, o, a;     // point indices: input adjoint, coefficient row, out/cur/g, coarse
+  int nk, B, H, kw;
+  int mode;
+};
+
+hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s);
+hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s);
+
+// P[M,N] = X[M,K] W[N,K]^T + bias[N]
+hipError_t launch_projection(const float* X, const float* W, const float* bias, float* P,
+                             long long M, int N, int K, hipStream_t s);
+// UT[H,3H] = U[3H,H]^T
+hipError_t launch_transpose(const float* U, float* UT, int rows, int cols, hipStream_t s);
+
+// Weight gradients (Alg. 3 gradient line) from the level-0 coefficients kap0[(T+1),B,5H]
+// (row t = step t), the adjoint w[(T+1),B,H], the states h[(T+1),B,H] and x[T,B,D].
+// part: scratch of grad_partial_floats(...) floats.
+size_t grad_partial_floats(int T, int B, int D, int H);
+hipError_t launch_param_grads(const float* kap0, const float* w, const float* h, const float* x,
+                              float* dW, float* dU, float* db_i, float* db_h, float* part,
+                              int T, int B, int D, int H, hipStream_t s);
+
+hipError_t launch_fill_f64(double* p, long long n, double v, hipStream_t s);
+// dst[(d.off + i*d.str), :, :] = src[(s.off + i*s.str), :, :] for i < nk; blocks of `block` floats
+hipError_t launch_copy_points(float* dst, const float* src, Idx d, Idx s, int nk, long long block,
+                              hipStream_t st);
+hipError_t launch_sqrt_to_float(const double* acc, float* out, int n, hipStream_t s);
+
+// profiling brackets (see mgrit_gru_profile_enable)
+void prof_begin(int kind, hipStream_t s);
+void prof_end(int kind, double flops, double bytes, hipStream_t s);
+
+}  // namespace mg

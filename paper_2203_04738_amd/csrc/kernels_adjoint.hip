@@ -1,0 +1,355 @@
+// Adjoint kernels: the fused transposed-Jacobian level step
+//   w_out = k_d*w + U_r^T(k_r*w) + U_z^T(k_z*w) + U_n^T(k_q*w)
+// (discrete adjoint of Eq. 16 / Eq. 3, Appendix A.2) with the same MGRIT
+// epilogues as the forward step, the transposition of U it contracts with, and
+// the parameter-gradient reductions of Alg. 3's gradient line.
+#include "common.h"
+#include "gemm_core.h"
+
+namespace mg {
+
+// ---------------------------------------------------------------------------
+// Adjoint level step: out[R,H] = (kap[:, 0:3H] * (w,w,w))[R,3H] . UT[H,3H]^T + k_d*w
+// ---------------------------------------------------------------------------
+template <class C>
+__global__ __launch_bounds__(C::NT) void adj_step_kernel(AdjArgs a) {
+  __shared__ __attribute__((aligned(16))) float lds[C::LDS_FLOATS];
+  const int H = a.H, B = a.B, K = 3 * a.H;
+  const long long R = (long long)a.nk * B;
+  const long long m0 = (long long)blockIdx.x * C::TM;
+  const int n0 = blockIdx.y * C::TN;
+  const int tid = threadIdx.x;
+
+  const float* krow[C::A_CHUNKS];
+  const float* wrow[C::A_CHUNKS];
+  const float* brow[C::B_CHUNKS];
+#pragma unroll
+  for (int s = 0; s < C::A_CHUNKS; ++s) {
+    long long r = m0 + (tid + s * C::NT) / (TK / 4);
+    if (r < R) {
+      long long pt = r / B;
+      int b = (int)(r - pt * B);
+      krow[s] = a.kap + (a.k.at(pt) * B + b) * (long long)a.kw;
+      wrow[s] = a.w_in + (a.in.at(pt) * B + b) * H;
+    } else {
+      krow[s] = nullptr;
+      wrow[s] = nullptr;
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < C::B_CHUNKS; ++s) {
+    int j = n0 + (tid + s * C::NT) / (TK / 4);
+    brow[s] = j < H ? a.UT + (long long)j * K : nullptr;
+  }
+  Acc<C> acc;
+  acc.zero();
+  gemm_nt_tile<C>(
+      acc, K,
+      [&](int s, int, int k) {
+        if (!krow[s] || k >= K) return zero4();
+        int kk = k >= 2 * H ? k - 2 * H : (k >= H ? k - H : k);
+        return ldg4(krow[s] + k) * ldg4(wrow[s] + kk);
+      },
+      [&](int s, int, int k) { return (brow[s] && k < K) ? ldg4(brow[s] + k) : zero4(); }, lds);
+
+  double nrm = 0.0;
+#pragma unroll
+  for (int ba = 0; ba < C::BM; ++ba)
+#pragma unroll
+    for (int bb = 0; bb < C::BN; ++bb) {
+      int row, col;
+      acc_coord<C>(ba, bb, 0, row, col);
+      const int j = n0 + col;
+      if (j >= H) continue;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        acc_coord<C>(ba, bb, e, row, col);
+        const long long r = m0 + row;
+        if (r >= R) continue;
+        const long long pt = r / B;
+        const int b = (int)(r - pt * B);
+        const float kd = a.kap[(a.k.at(pt) * B + b) * (long long)a.kw + 3 * H + j];
+        const float wv = a.w_in[(a.in.at(pt) * B + b) * H + j];
+        const float wn = kd * wv + acc.v[0][ba][bb][e];
+        const long long oi = (a.o.at(pt) * B + b) * H + j;
+        if (a.mode == STEP_RELAX) {
+          a.w[oi] = a.g ? wn + a.g[oi] : wn;
+        } else if (a.mode == STEP_RESID) {
+          const float cur = a.w[oi];
+          const float res = a.g ? cur - wn - a.g[oi] : cur - wn;
+          const long long ai = (a.a.at(pt) * B + b) * H + j;
+          a.gc[ai] = -res;
+          a.wc[ai] = cur;
+          nrm += (double)res * (double)res;
+        } else {  // STEP_RHS
+          a.g[oi] = (a.w[oi] - wn) + a.g[oi];
+        }
+      }
+    }
+  if (a.mode == STEP_RESID && a.norm) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) nrm += __shfl_down(nrm, off, 64);
+    if ((tid & 63) == 0) atomicAdd(a.norm, nrm);
+  }
+}
+
+typedef TileCfg<2, 2, 2, 2, 1> AdjBig;    // 128 x 128, 256 threads
+typedef TileCfg<2, 1, 1, 1, 1> AdjMid;    //  64 x 32, 128 threads
+typedef TileCfg<1, 1, 1, 1, 1> AdjSmall;  //  32 x 32, 64 threads
+
+template <class C>
+static void launch_adj_cfg(const AdjArgs& a, hipStream_t s) {
+  const long long R = (long long)a.nk * a.B;
+  dim3 grid((unsigned)((R + C::TM - 1) / C::TM), (unsigned)((a.H + C::TN - 1) / C::TN));
+  hipLaunchKernelGGL(adj_step_kernel<C>, grid, dim3(C::NT), 0, s, a);
+}
+
+hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s) {
+  if (a.nk <= 0) return hipSuccess;
+  const long long R = (long long)a.nk * a.B;
+  auto tiles = [&](int tm, int tn) { return ((R + tm - 1) / tm) * ((a.H + tn - 1) / tn); };
+  prof_begin(1, s);
+  if (tiles(AdjBig::TM, AdjBig::TN) >= 512)
+    launch_adj_cfg<AdjBig>(a, s);
+  else if (R > 32 && tiles(AdjMid::TM, AdjMid::TN) >= 256)
+    launch_adj_cfg<AdjMid>(a, s);
+  else
+    launch_adj_cfg<AdjSmall>(a, s);
+  prof_end(1, 6.0 * (double)R * a.H * a.H, 28.0 * (double)R * a.H, s);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// UT[cols, rows] = U[rows, cols]^T
+// ---------------------------------------------------------------------------
+__global__ void transpose_kernel(const float* __restrict__ U, float* __restrict__ UT, int rows,
+                                 int cols) {
+  __shared__ float t[32][33];
+  const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+  for (int i = ty; i < 32; i += 8) {
+    int r = r0 + i, c = c0 + tx;
+    t[i][tx] = (r < rows && c < cols) ? U[(long long)r * cols + c] : 0.f;
+  }
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8) {
+    int c = c0 + i, r = r0 + tx;
+    if (r < rows && c < cols) UT[(long long)c * rows + r] = t[tx][i];
+  }
+}
+
+hipError_t launch_transpose(const float* U, float* UT, int rows, int cols, hipStream_t s) {
+  dim3 grid((cols + 31) / 32, (rows + 31) / 32);
+  hipLaunchKernelGGL(transpose_kernel, grid, dim3(256), 0, s, U, UT, rows, cols);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Parameter gradients: dU = S^T Hprev, dW = Sx^T X, db_h = colsum S, db_i = colsum Sx
+// with S[k, g*H+j] = kap0[k][g*H+j] * w[k][j] (gates r, z, q) and Sx the same
+// except that its third block uses k_n (stored at 4H..5H) instead of k_q.
+// Row k = (t-1)*B + b for step t = 1..T: kap0 and w rows are offset by one time
+// point, Hprev = h[t-1] and X = x[t-1] are not.
+// ---------------------------------------------------------------------------
+constexpr int GTK = 16;            // K-slice (rows of the sum) per iteration
+constexpr int GT = 128;            // output tile is GT x GT
+constexpr int GLD = GT + 32;       // LDS row stride in floats
+
+struct GradArgs {
+  const float* kap0;   // [(T+1),B,5H]
+  const float* w;      // [(T+1),B,H]
+  const float* Bm;     // h[(T+1),B,H] or x[T,B,D]; row k as is
+  float* part;         // [splits][3H][N]
+  long long Ktot;      // T*B
+  long long Kper;      // rows per split (multiple of GTK)
+  int B, H, N;         // N = H (dU) or D (dW)
+  int third_off;       // 2H (k_q, dU) or 4H (k_n, dW)
+};
+
+__global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
+  __shared__ __attribute__((aligned(16))) float As[GTK * GLD];
+  __shared__ __attribute__((aligned(16))) float Bs[GTK * GLD];
+  const int H = a.H, N = a.N, M = 3 * a.H;
+  const int m0 = blockIdx.x * GT, n0 = blockIdx.y * GT;
+  const long long kbeg = (long long)blockIdx.z * a.Kper;
+  long long kend = kbeg + a.Kper;
+  if (kend > a.Ktot) kend = a.Ktot;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1, li = lane & 31, lh = lane >> 5;
+  const long long rowoff = a.B;   // kap0 / w rows are one time point ahead
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // each thread stages 2 float4 of A and 2 of B per slice: slice row = q/32, col4 = q%32
+  floatx4 ra[2], rb[2];
+  auto fetch = [&](long long k0) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      int q = tid + s * 256;
+      int kr = q >> 5, c4 = q & 31;
+      long long k = k0 + kr;
+      int m = m0 + c4 * 4, n = n0 + c4 * 4;
+      if (k < kend && m < M) {
+        int g = m / H, j = m - g * H;
+        int src = g == 2 ? a.third_off + j : m;
+        ra[s] = ldg4(a.kap0 + (k + rowoff) * (5LL * H) + src) * ldg4(a.w + (k + rowoff) * H + j);
+      } else {
+        ra[s] = zero4();
+      }
+      rb[s] = (k < kend && n < N) ? ldg4(a.Bm + k * N + n) : zero4();
+    }
+  };
+  auto stash = [&]() {
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      int q = tid + s * 256;
+      int kr = q >> 5, c4 = q & 31;
+      *reinterpret_cast<floatx4*>(&As[kr * GLD + c4 * 4]) = ra[s];
+      *reinterpret_cast<floatx4*>(&Bs[kr * GLD + c4 * 4]) = rb[s];
+    }
+  };
+
+  if (kbeg < kend) {
+    fetch(kbeg);
+    stash();
+    __syncthreads();
+    for (long long k0 = kbeg; k0 < kend; k0 += GTK) {
+      const bool more = k0 + GTK < kend;
+      if (more) fetch(k0 + GTK);
+#pragma unroll
+      for (int p = 0; p < GTK / 2; ++p) {
+        float av[2], bv[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) av[i] = As[(2 * p + lh) * GLD + wm * 64 + i * 32 + li];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) bv[j] = Bs[(2 * p + lh) * GLD + wn * 64 + j * 32 + li];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+      }
+      __syncthreads();
+      if (more) {
+        stash();
+        __syncthreads();
+      }
+    }
+  }
+  float* out = a.part + (long long)blockIdx.z * M * N;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        int m = m0 + wm * 64 + i * 32 + 8 * (e / 4) + 4 * lh + (e & 3);
+        int n = n0 + wn * 64 + j * 32 + li;
+        if (m < M && n < N) out[(long long)m * N + n] = acc[i][j][e];
+      }
+}
+
+__global__ void reduce_partials_kernel(const float* __restrict__ part, float* __restrict__ out,
+                                       long long n, int splits) {
+  long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float s = 0.f;
+  for (int z = 0; z < splits; ++z) s += part[(long long)z * n + i];
+  out[i] = s;
+}
+
+// Column sums over rows k of the 4H virtual columns (k_r w, k_z w, k_q w, k_n w).
+constexpr int BIAS_SPLITS = 128;
+__global__ void bias_partial_kernel(const float* __restrict__ kap0, const float* __restrict__ w,
+                                    float* __restrict__ part, long long Ktot, int B, int H) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;   // virtual column
+  if (c >= 4 * H) return;
+  const int g = c / H, j = c - g * H;
+  const int src = g == 3 ? 4 * H + j : c;
+  const long long per = (Ktot + BIAS_SPLITS - 1) / BIAS_SPLITS;
+  long long kb = (long long)blockIdx.y * per, ke = kb + per;
+  if (ke > Ktot) ke = Ktot;
+  float s = 0.f;
+  for (long long k = kb; k < ke; ++k)
+    s += kap0[(k + B) * (5LL * H) + src] * w[(k + B) * H + j];
+  part[(long long)blockIdx.y * 4 * H + c] = s;
+}
+
+__global__ void bias_reduce_kernel(const float* __restrict__ part, float* __restrict__ db_i,
+                                   float* __restrict__ db_h, int H) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= 4 * H) return;
+  float s = 0.f;
+  for (int z = 0; z < BIAS_SPLITS; ++z) s += part[(long long)z * 4 * H + c];
+  if (c < 2 * H) {
+    db_h[c] = s;
+    db_i[c] = s;
+  } else if (c < 3 * H) {
+    db_h[c] = s;            // k_q w
+  } else {
+    db_i[c - H] = s;        // k_n w -> third block of db_i
+  }
+}
+
+static int grad_splits(long long Ktot, int M, int N) {
+  long long tiles = (long long)((M + GT - 1) / GT) * ((N + GT - 1) / GT);
+  long long want = (1024 + tiles - 1) / tiles;
+  long long maxs = (Ktot + 4 * GTK - 1) / (4 * GTK);   // at least 4 slices per split
+  if (want > maxs) want = maxs;
+  if (want < 1) want = 1;
+  if (want > 256) want = 256;
+  return (int)want;
+}
+
+size_t grad_partial_floats(int T, int B, int D, int H) {
+  const long long Ktot = (long long)T * B;
+  size_t su = (size_t)grad_splits(Ktot, 3 * H, H) * 3 * H * H;
+  size_t sw = (size_t)grad_splits(Ktot, 3 * H, D) * 3 * H * D;
+  size_t sb = (size_t)BIAS_SPLITS * 4 * H;
+  return (su > sw ? su : sw) + sb;
+}
+
+hipError_t launch_param_grads(const float* kap0, const float* w, const float* h, const float* x,
+                              float* dW, float* dU, float* db_i, float* db_h, float* part,
+                              int T, int B, int D, int H, hipStream_t s) {
+  const long long Ktot = (long long)T * B;
+  const int M = 3 * H;
+  prof_begin(3, s);
+  for (int which = 0; which < 2; ++which) {
+    GradArgs a;
+    a.kap0 = kap0;
+    a.w = w;
+    a.Bm = which == 0 ? h : x;
+    a.N = which == 0 ? H : D;
+    a.third_off = which == 0 ? 2 * H : 4 * H;
+    a.part = part;
+    a.Ktot = Ktot;
+    a.B = B;
+    a.H = H;
+    const int splits = grad_splits(Ktot, M, a.N);
+    long long per = (Ktot + splits - 1) / splits;
+    a.Kper = (per + GTK - 1) / GTK * GTK;
+    dim3 grid((M + GT - 1) / GT, (a.N + GT - 1) / GT, splits);
+    hipLaunchKernelGGL(grad_gemm_kernel, grid, dim3(256), 0, s, a);
+    const long long n = (long long)M * a.N;
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                       part, which == 0 ? dU : dW, n, splits);
+  }
+  size_t su = (size_t)grad_splits(Ktot, M, H) * M * H, sw = (size_t)grad_splits(Ktot, M, D) * M * D;
+  float* bpart = part + (su > sw ? su : sw);
+  hipLaunchKernelGGL(bias_partial_kernel, dim3((4 * H + 255) / 256, BIAS_SPLITS), dim3(256), 0, s,
+                     kap0, w, bpart, Ktot, B, H);
+  hipLaunchKernelGGL(bias_reduce_kernel, dim3((4 * H + 255) / 256), dim3(256), 0, s, bpart, db_i,
+                     db_h, H);
+  prof_end(3, 2.0 * (double)Ktot * M * (H + D),
+           4.0 * (double)Ktot * (5.0 * H + H + H + D), s);
+  return hipGetLastError();
+}
+
+}  // namespace mg

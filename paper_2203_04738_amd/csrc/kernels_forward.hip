@@ -1,0 +1,207 @@
+// Forward kernels: input projection GEMM and the fused GRU level step
+// Phi_gamma(x, h) (Eq. 1 gates + Eq. 16 / Eq. 3 update) with the MGRIT epilogues
+// (relaxation update of Alg. 1, residual + restriction of Alg. 2 lines 2-3, the
+// right-hand side of Eq. 11, and the adjoint coefficient vectors).
+#include "common.h"
+#include "gemm_core.h"
+
+namespace mg {
+
+// ---------------------------------------------------------------------------
+// Projection: P[M,N] = X[M,K] W[N,K]^T + bias[N]       (input half of Eq. 1)
+// ---------------------------------------------------------------------------
+typedef TileCfg<2, 2, 2, 2, 1> ProjCfg;   // 128 x 128 tile, 256 threads
+
+__global__ __launch_bounds__(ProjCfg::NT) void projection_kernel(
+    const float* __restrict__ X, const float* __restrict__ W, const float* __restrict__ bias,
+    float* __restrict__ P, long long M, int N, int K) {
+  typedef ProjCfg C;
+  __shared__ __attribute__((aligned(16))) float lds[C::LDS_FLOATS];
+  const long long m0 = (long long)blockIdx.x * C::TM;
+  const int n0 = blockIdx.y * C::TN;
+  const int tid = threadIdx.x;
+
+  const float* arow[C::A_CHUNKS];
+  const float* brow[C::B_CHUNKS];
+#pragma unroll
+  for (int s = 0; s < C::A_CHUNKS; ++s) {
+    long long r = m0 + (tid + s * C::NT) / (TK / 4);
+    arow[s] = r < M ? X + r * K : nullptr;
+  }
+#pragma unroll
+  for (int s = 0; s < C::B_CHUNKS; ++s) {
+    int r = n0 + (tid + s * C::NT) / (TK / 4);
+    brow[s] = r < N ? W + (long long)r * K : nullptr;
+  }
+  Acc<C> acc;
+  acc.zero();
+  gemm_nt_tile<C>(
+      acc, K,
+      [&](int s, int, int k) { return (arow[s] && k < K) ? ldg4(arow[s] + k) : zero4(); },
+      [&](int s, int, int k) { return (brow[s] && k < K) ? ldg4(brow[s] + k) : zero4(); }, lds);
+
+#pragma unroll
+  for (int a = 0; a < C::BM; ++a)
+#pragma unroll
+    for (int b = 0; b < C::BN; ++b) {
+      int row, col;
+      acc_coord<C>(a, b, 0, row, col);
+      const int n = n0 + col;
+      if (n >= N) continue;
+      const float bv = bias[n];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        acc_coord<C>(a, b, e, row, col);
+        const long long m = m0 + row;
+        if (m < M) P[m * N + n] = acc.v[0][a][b][e] + bv;
+      }
+    }
+}
+
+hipError_t launch_projection(const float* X, const float* W, const float* bias, float* P,
+                             long long M, int N, int K, hipStream_t s) {
+  typedef ProjCfg C;
+  dim3 grid((unsigned)((M + C::TM - 1) / C::TM), (unsigned)((N + C::TN - 1) / C::TN));
+  prof_begin(2, s);
+  hipLaunchKernelGGL(projection_kernel, grid, dim3(C::NT), 0, s, X, W, bias, P, M, N, K);
+  prof_end(2, 2.0 * (double)M * N * K, 4.0 * ((double)M * K + (double)N * K + (double)M * N), s);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Fused level step
+// ---------------------------------------------------------------------------
+__device__ inline float sigmoidf_(float a) { return 1.0f / (1.0f + expf(-a)); }
+
+template <class C>
+__global__ __launch_bounds__(C::NT) void phi_step_kernel(PhiArgs a) {
+  __shared__ __attribute__((aligned(16))) float lds[C::LDS_FLOATS];
+  const int H = a.H, B = a.B;
+  const long long R = (long long)a.nk * B;
+  const long long m0 = (long long)blockIdx.x * C::TM;
+  const int n0 = blockIdx.y * C::TN;
+  const int tid = threadIdx.x;
+
+  // A rows: states of the points this tile covers (row = point*B + b).
+  const float* arow[C::A_CHUNKS];
+  const float* brow[C::B_CHUNKS];
+#pragma unroll
+  for (int s = 0; s < C::A_CHUNKS; ++s) {
+    long long r = m0 + (tid + s * C::NT) / (TK / 4);
+    if (r < R) {
+      long long pt = r / B;
+      int b = (int)(r - pt * B);
+      arow[s] = a.u_in + (a.in.at(pt) * B + b) * H;
+    } else {
+      arow[s] = nullptr;
+    }
+  }
+  // B rows: for gate g the rows n0.. of U_g.
+#pragma unroll
+  for (int s = 0; s < C::B_CHUNKS; ++s) {
+    int tr = (tid + s * C::NT) / (TK / 4);
+    int g = tr / C::TN, j = n0 + tr % C::TN;
+    brow[s] = j < H ? a.U + ((long long)g * H + j) * H : nullptr;
+  }
+  Acc<C> acc;
+  acc.zero();
+  gemm_nt_tile<C>(
+      acc, H,
+      [&](int s, int, int k) { return (arow[s] && k < H) ? ldg4(arow[s] + k) : zero4(); },
+      [&](int s, int, int k) { return (brow[s] && k < H) ? ldg4(brow[s] + k) : zero4(); }, lds);
+
+  const float gamma = a.gamma;
+  const bool implicit = a.propagator == MGRIT_PROP_IMPLICIT;
+  double nrm = 0.0;
+#pragma unroll
+  for (int ba = 0; ba < C::BM; ++ba)
+#pragma unroll
+    for (int bb = 0; bb < C::BN; ++bb) {
+      int row, col;
+      acc_coord<C>(ba, bb, 0, row, col);
+      const int j = n0 + col;
+      if (j >= H) continue;
+      const float bhr = a.b_h[j], bhz = a.b_h[H + j], bhn = a.b_h[2 * H + j];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        acc_coord<C>(ba, bb, e, row, col);
+        const long long r = m0 + row;
+        if (r >= R) continue;
+        const long long pt = r / B;
+        const int b = (int)(r - pt * B);
+        const float* pp = a.P + (a.p.at(pt) * B + b) * (3LL * H);
+        const float h = a.u_in[(a.in.at(pt) * B + b) * H + j];
+        const float rg = sigmoidf_(pp[j] + acc.v[0][ba][bb][e] + bhr);
+        const float zg = sigmoidf_(pp[H + j] + acc.v[1][ba][bb][e] + bhz);
+        const float q = acc.v[2][ba][bb][e] + bhn;
+        const float n = tanhf(pp[2 * H + j] + rg * q);
+        const float c = 1.0f - zg;
+        const float d = 1.0f + gamma * c;
+        const float hn = implicit ? (h + gamma * c * n) / d : h + gamma * c * (n - h);
+        const long long oi = (a.o.at(pt) * B + b) * H + j;
+        if (a.mode == STEP_RELAX) {
+          a.u[oi] = a.g ? hn + a.g[oi] : hn;
+        } else if (a.mode == STEP_RESID) {
+          const float cur = a.u[oi];
+          const float res = a.g ? cur - hn - a.g[oi] : cur - hn;
+          const long long ai = (a.a.at(pt) * B + b) * H + j;
+          a.gc[ai] = -res;
+          a.uc[ai] = cur;
+          nrm += (double)res * (double)res;
+        } else if (a.mode == STEP_RHS) {
+          a.g[oi] = (a.u[oi] - hn) + a.g[oi];
+        } else {  // STEP_KAPPA: coefficients of the transposed Jacobian of this step
+          float kd, dn, dz;
+          if (implicit) {
+            kd = 1.0f / d;
+            dn = gamma * c / d;
+            dz = -gamma * (n - hn) / d;
+          } else {
+            kd = 1.0f - gamma * c;
+            dn = gamma * c;
+            dz = -gamma * (n - h);
+          }
+          const float kn = dn * (1.0f - n * n);
+          float* kp = a.uc + (a.o.at(pt) * B + b) * (long long)a.kappa_width;
+          kp[j] = kn * q * rg * (1.0f - rg);
+          kp[H + j] = dz * zg * (1.0f - zg);
+          kp[2 * H + j] = kn * rg;
+          kp[3 * H + j] = kd;
+          if (a.kappa_width >= 5 * H) kp[4 * H + j] = kn;
+        }
+      }
+    }
+  if (a.mode == STEP_RESID && a.norm) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) nrm += __shfl_down(nrm, off, 64);
+    if ((tid & 63) == 0) atomicAdd(a.norm, nrm);
+  }
+}
+
+typedef TileCfg<2, 2, 2, 1, 3> PhiBig;    // 128 rows x 64 hidden columns (x3 gates), 256 threads
+typedef TileCfg<2, 1, 1, 1, 3> PhiMid;    //  64 rows x 32 hidden columns, 128 threads
+typedef TileCfg<1, 1, 1, 1, 3> PhiSmall;  //  32 rows x 32 hidden columns, 64 threads
+
+template <class C>
+static void launch_phi_cfg(const PhiArgs& a, hipStream_t s) {
+  const long long R = (long long)a.nk * a.B;
+  dim3 grid((unsigned)((R + C::TM - 1) / C::TM), (unsigned)((a.H + C::TN - 1) / C::TN));
+  hipLaunchKernelGGL(phi_step_kernel<C>, grid, dim3(C::NT), 0, s, a);
+}
+
+hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s) {
+  if (a.nk <= 0) return hipSuccess;
+  const long long R = (long long)a.nk * a.B;
+  auto tiles = [&](int tm, int tn) { return ((R + tm - 1) / tm) * ((a.H + tn - 1) / tn); };
+  prof_begin(0, s);
+  if (tiles(PhiBig::TM, PhiBig::TN) >= 512)
+    launch_phi_cfg<PhiBig>(a, s);
+  else if (R > 32 && tiles(PhiMid::TM, PhiMid::TN) >= 256)
+    launch_phi_cfg<PhiMid>(a, s);
+  else
+    launch_phi_cfg<PhiSmall>(a, s);
+  prof_end(0, 6.0 * (double)R * a.H * a.H, 20.0 * (double)R * a.H, s);
+  return hipGetLastError();
+}
+
+}  // namespace mg

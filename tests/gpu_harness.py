@@ -1,0 +1,110 @@
+"""Runs the HIP path (through the Python binding of the C ABI) on host arrays and
+returns host arrays.  Test helper: marshalling only."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2203_04738_amd as mg
+from paper_2203_04738_amd.binding import MGRIT_REUSE_PROJECTION, MgritGruCfg
+
+DEV = "cuda:0"
+
+
+def to_dev(d, dtype="fp32"):
+    t = {}
+    for k, v in d.items():
+        if k == "labels":
+            continue
+        tv = torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(DEV)
+        if dtype == "bf16" and k in ("x", "W", "U"):
+            tv = tv.to(torch.bfloat16)
+        t[k] = tv
+    return t
+
+
+class GpuRun:
+    def __init__(self, d, cf=1, levels=1, fine_relax=1, propagator=0, dtype="fp32"):
+        self.t = to_dev(d, dtype)
+        T, B, D = d["x"].shape
+        H = d["U"].shape[1]
+        self.T, self.B, self.D, self.H = T, B, D, H
+        self.kw = dict(cf=cf, levels=levels, fine_relax=fine_relax, propagator=propagator,
+                       dtype=0 if dtype == "fp32" else 1)
+        cfg = self.cfg(iters=64)
+        self.ws = torch.empty(mg.mgrit_gru_workspace_bytes(cfg), dtype=torch.uint8, device=DEV)
+
+    def cfg(self, iters=1, flags=0):
+        return MgritGruCfg(self.T, self.B, self.D, self.H, iters=iters, flags=flags, **self.kw)
+
+    def _p(self):
+        t = self.t
+        return t["W"], t["U"], t["b_i"], t["b_h"], t["x"]
+
+    def serial_scan(self):
+        h = torch.full((self.T + 1, self.B, self.H), float("nan"), device=DEV)
+        mg.gru_serial_scan(self.cfg(), *self._p(), self.t["h0"], h, self.ws)
+        torch.cuda.synchronize()
+        return h.cpu().numpy()
+
+    def forward_iterates(self, iters, h_init=None, per_call=1):
+        """Calls mgrit_gru_forward repeatedly with `per_call` cycles each and returns
+        the iterate after every call plus all residual norms."""
+        h = torch.zeros(self.T + 1, self.B, self.H, device=DEV)
+        if h_init is not None:
+            h.copy_(torch.from_numpy(np.ascontiguousarray(h_init, dtype=np.float32)))
+        its, norms = [], []
+        done = 0
+        while done < iters:
+            n = min(per_call, iters - done)
+            res = torch.full((n,), float("nan"), device=DEV)
+            flags = MGRIT_REUSE_PROJECTION if done > 0 else 0
+            mg.mgrit_gru_forward(self.cfg(n, flags), *self._p(), self.t["h0"], h, res, self.ws)
+            torch.cuda.synchronize()
+            its.append(h.cpu().numpy().copy())
+            norms += res.cpu().numpy().tolist()
+            done += n
+        self.h_dev = h
+        return its, norms
+
+    def _grads(self):
+        H, D = self.H, self.D
+        nan = float("nan")
+        return (torch.full((3 * H, D), nan, device=DEV), torch.full((3 * H, H), nan, device=DEV),
+                torch.full((3 * H,), nan, device=DEV), torch.full((3 * H,), nan, device=DEV))
+
+    def serial_backward(self, h):
+        hd = torch.from_numpy(np.ascontiguousarray(h, dtype=np.float32)).to(DEV)
+        w = torch.full((self.T + 1, self.B, self.H), float("nan"), device=DEV)
+        g = self._grads()
+        mg.gru_serial_scan_backward(self.cfg(), *self._p(), hd, self.t["dL_dhT"], w, *g, self.ws)
+        torch.cuda.synchronize()
+        return (w.cpu().numpy(),) + tuple(a.cpu().numpy() for a in g)
+
+    def backward_iterates(self, h, iters, per_call=1):
+        hd = torch.from_numpy(np.ascontiguousarray(h, dtype=np.float32)).to(DEV)
+        w = torch.zeros(self.T + 1, self.B, self.H, device=DEV)
+        its, norms, grads = [], [], None
+        done = 0
+        while done < iters:
+            n = min(per_call, iters - done)
+            res = torch.full((n,), float("nan"), device=DEV)
+            g = self._grads()
+            mg.mgrit_gru_backward(self.cfg(n), *self._p(), hd, self.t["dL_dhT"], w, res, *g,
+                                  self.ws)
+            torch.cuda.synchronize()
+            its.append(w.cpu().numpy().copy())
+            norms += res.cpu().numpy().tolist()
+            grads = tuple(a.cpu().numpy() for a in g)
+            done += n
+        return its, norms, grads
+
+
+def rel_err(got, ref):
+    """max |got - ref| / max |ref| over a tensor (states cross zero, so element-wise
+    ratios are meaningless)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    assert np.all(np.isfinite(got)), "non-finite output"
+    return float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-300))

@@ -1,0 +1,91 @@
+"""Host-side checks of the C-ABI library: it loads, exports every symbol the header
+declares, and rejects bad arguments before touching the GPU (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2203_04738_amd as mg
+from paper_2203_04738_amd.binding import MgritGruCfg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mgrit_gru.h")).read()
+    return re.findall(r"MGRIT_API\s+[\w\s\*]+?\b(\w+)\s*\(", text)
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    names = _declared_symbols()
+    assert set(names) >= {"mgrit_gru_forward", "mgrit_gru_backward", "gru_serial_scan",
+                          "gru_serial_scan_backward", "mgrit_gru_workspace_bytes"}
+    L = mg.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_cfg_struct_matches_header_field_order():
+    text = open(os.path.join(ROOT, "include", "mgrit_gru.h")).read()
+    body = text[text.index("typedef struct {"):text.index("} mgrit_gru_cfg;")]
+    fields = []
+    for line in body.splitlines():
+        m = re.match(r"\s*int32_t\s+([\w,\s]+);", line)
+        if m:
+            fields += [f.strip() for f in m.group(1).split(",")]
+    assert fields == [f for f, _ in MgritGruCfg._fields_]
+
+
+def _ws(cfg):
+    n = ctypes.c_size_t(0)
+    rc = mg.lib().mgrit_gru_workspace_bytes(ctypes.byref(cfg), ctypes.byref(n))
+    return rc, n.value
+
+
+def test_workspace_size_and_validation_codes():
+    rc, n = _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, iters=3))
+    assert rc == 0 and n >= 64 * 2 * 96 * 4
+    assert _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=4, iters=1))[0] == 0    # coarsest level: 1 step
+    assert _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=5, iters=1))[0] == -3
+    assert _ws(MgritGruCfg(60, 2, 16, 32, cf=4, levels=3, iters=1))[0] == -3
+    assert _ws(MgritGruCfg(0, 2, 16, 32))[0] == -2
+    assert _ws(MgritGruCfg(64, 2, 16, 32, cf=0, levels=2))[0] == -2
+    assert _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=0))[0] == -2
+    assert _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, iters=-1))[0] == -2
+    assert _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, propagator=2))[0] == -4
+    assert _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, dtype=7))[0] == -4
+    assert _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, fine_relax=2))[0] == -4
+    assert _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, flags=8))[0] == -4
+    assert _ws(MgritGruCfg(64, 2, 16, 30, cf=4, levels=2))[0] == -6
+    assert _ws(MgritGruCfg(64, 2, 9, 32, cf=4, levels=2))[0] == -6
+    assert mg.lib().mgrit_gru_workspace_bytes(None, None) == -1
+
+
+def test_entry_points_reject_null_and_small_workspace_without_a_gpu():
+    L = mg.lib()
+    cfg = MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, iters=1)
+    # null data pointers: refused on the host, nothing is launched
+    assert L.gru_serial_scan(ctypes.byref(cfg), None, None, None, None, None, None, None,
+                             None, 0, None) == -1
+    assert L.mgrit_gru_forward(ctypes.byref(cfg), None, None, None, None, None, None, None, None,
+                               None, 0, None) == -1
+    assert L.mgrit_gru_backward(ctypes.byref(cfg), None, None, None, None, None, None, None, None,
+                                None, None, None, None, None, None, 0, None) == -1
+    # fake but aligned addresses with a too-small workspace: refused before any launch
+    p = 4096
+    assert L.mgrit_gru_forward(ctypes.byref(cfg), p, p, p, p, p, p, p, None, p, 16, None) == -5
+    assert L.gru_serial_scan(ctypes.byref(cfg), p, p, p, p, p, p, p, p, 16, None) == -5
+    # misaligned pointer
+    assert L.mgrit_gru_forward(ctypes.byref(cfg), p + 4, p, p, p, p, p, p, None, p, 1 << 30,
+                               None) == -6
+    # gradients: all four or none
+    assert L.mgrit_gru_backward(ctypes.byref(cfg), p, p, p, p, p, p, p, p, None, p, None, None,
+                                None, p, 1 << 30, None) == -1
+
+
+def test_strerror_names_codes():
+    assert mg.mgrit_gru_strerror(0) == "ok"
+    assert "divide" in mg.mgrit_gru_strerror(-3)
+    with pytest.raises(mg.MgritGruError):
+        mg.mgrit_gru_workspace_bytes(MgritGruCfg(60, 2, 16, 32, cf=4, levels=3))

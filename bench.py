@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the MGRIT-GRU hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one synthetic batch: input
+projection, `fwd_iters` MGRIT cycles of forward propagation, the loss head
+(cross-entropy through a linear layer, outside the library), `bwd_iters` MGRIT
+cycles of the adjoint and the parameter gradients.  All inputs are resident in
+HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MI355X_PEAK = {"hbm_GBps": 8000.0, "fp32_TFLOPs": 157.3, "bf16_TFLOPs": 2500.0}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C3", help="C1..C5 (BASELINE.json configs in order)")
+    ap.add_argument("--fwd-iters", type=int, default=None)
+    ap.add_argument("--bwd-iters", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-serial", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline(wl, fwd_iters, bwd_iters):
+    """The CPU oracle as it stands, timed on the reduced twin of the workload
+    (same B, D, H, cf, levels; T = 8*cf^(levels-1)); work is linear in T."""
+    import numpy as np
+    from oracle import mgrit_gru_oracle as orc
+    from synthetic_inputs import make_inputs
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    def run(tw):
+        d = make_inputs(tw)
+        P = (d["W"], d["U"], d["b_i"], d["b_h"])
+        z = np.zeros((tw.T + 1, tw.B, tw.H))
+        t0 = time.perf_counter()
+        h, _ = orc.mgrit_forward(*P, d["x"], d["h0"], z, tw.cf, tw.levels, fwd_iters)
+        if bwd_iters > 0:
+            _, g = orc.cross_entropy_head(h[-1], d["W_o"], d["b_o"], d["labels"])
+            orc.mgrit_backward(*P, d["x"], h, g, z, tw.cf, tw.levels, bwd_iters)
+        return time.perf_counter() - t0
+
+    unit = wl.cf ** (wl.levels - 1)
+    n_max = wl.T // unit
+    n = min(8, n_max)
+    tw = wl.twin(n)
+    dt = run(tw)
+    if dt < 8.0 and n < n_max:
+        # enlarge the sample towards ~15 s of CPU work (never beyond the full workload)
+        n = int(min(n_max, max(n + 1, n * 15.0 / max(dt, 1e-3))))
+        tw = wl.twin(n)
+        dt = run(tw)
+    return {"value": tw.T * tw.B / dt, "unit": "time-steps*batch/s", "cores": int(cores),
+            "kind": "oracle",
+            "sample": f"reduced-T twin of {wl.name}: T={tw.T} (of {wl.T}), B={tw.B}, D={tw.D}, "
+                      f"H={tw.H}, cf={tw.cf}, levels={tw.levels}, {fwd_iters} fwd + {bwd_iters} "
+                      f"bwd cycles, numpy float64, {dt:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2203_04738_amd as mg
+    from paper_2203_04738_amd.binding import MGRIT_REUSE_PROJECTION, MgritGruCfg
+    from synthetic_inputs import WORKLOADS, make_inputs
+
+    wl = WORKLOADS[args.workload]
+    fwd_iters = wl.fwd_iters if args.fwd_iters is None else args.fwd_iters
+    bwd_iters = wl.bwd_iters if args.bwd_iters is None else args.bwd_iters
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    d = make_inputs(wl)
+    T, B, D, H = wl.T, wl.B, wl.D, wl.H
+    in_dt = torch.float32 if wl.dtype == "fp32" else torch.bfloat16
+    t = {k: torch.from_numpy(v).to(dev) for k, v in d.items()}
+    for k in ("x", "W", "U"):
+        t[k] = t[k].to(in_dt)
+    dtype_code = 0 if wl.dtype == "fp32" else 1
+
+    def cfg(iters, flags=0, levels=wl.levels):
+        return MgritGruCfg(T, B, D, H, cf=wl.cf, levels=levels, iters=iters, fine_relax=1,
+                           propagator=0, dtype=dtype_code, flags=flags)
+
+    ws = torch.empty(mg.mgrit_gru_workspace_bytes(cfg(max(fwd_iters, bwd_iters, 1))),
+                     dtype=torch.uint8, device=dev)
+    h = torch.zeros(T + 1, B, H, device=dev)
+    w = torch.zeros(T + 1, B, H, device=dev)
+    dW = torch.empty(3 * H, D, device=dev)
+    dU = torch.empty(3 * H, H, device=dev)
+    dbi = torch.empty(3 * H, device=dev)
+    dbh = torch.empty(3 * H, device=dev)
+    res_f = torch.zeros(max(fwd_iters, 1), device=dev)
+    res_b = torch.zeros(max(bwd_iters, 1), device=dev)
+    Wp = (t["W"], t["U"], t["b_i"], t["b_h"], t["x"])
+    W_o, b_o, labels = t["W_o"], t["b_o"], t["labels"]
+
+    def loss_head():
+        # linear head + mean cross-entropy on h_T and its gradient (outside the library)
+        logits = h[T] @ W_o.T + b_o
+        p = torch.softmax(logits, dim=1)
+        p[torch.arange(B, device=dev), labels] -= 1.0
+        return (p / B) @ W_o
+
+    def mgrit_step():
+        h.zero_()
+        mg.mgrit_gru_forward(cfg(fwd_iters), *Wp, t["h0"], h, res_f, ws)
+        if bwd_iters > 0:
+            g = loss_head()
+            w.zero_()
+            mg.mgrit_gru_backward(cfg(bwd_iters, MGRIT_REUSE_PROJECTION), *Wp, h, g, w, res_b,
+                                  dW, dU, dbi, dbh, ws)
+
+    def serial_step():
+        mg.gru_serial_scan(cfg(1), *Wp, t["h0"], h, ws)
+        if bwd_iters > 0:
+            g = loss_head()
+            mg.gru_serial_scan_backward(cfg(1, MGRIT_REUSE_PROJECTION), *Wp, h, g, w, dW, dU, dbi,
+                                        dbh, ws)
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    sec = timed(mgrit_step, args.steps, args.warmup)
+    resf = res_f.cpu().numpy().tolist()[:fwd_iters]
+    resb = res_b.cpu().numpy().tolist()[:bwd_iters]
+
+    # per-kernel durations from HIP events on the launch stream, over the same K steps
+    mg.mgrit_gru_profile_enable(True)
+    for _ in range(args.steps):
+        mgrit_step()
+    torch.cuda.synchronize()
+    mg.mgrit_gru_profile_enable(False)
+    names = {0: "phi_step (fused forward level step)", 1: "adj_step (fused adjoint level step)",
+             2: "projection GEMM", 3: "weight-gradient GEMMs + bias sums"}
+    kernels = {}
+    for kind, nm in names.items():
+        n, ms, fl, by = mg.mgrit_gru_profile_read(kind)
+        if n:
+            kernels[nm] = {"launches_per_step": n / args.steps, "ms_per_step": ms / args.steps,
+                           "avg_launch_us": 1e3 * ms / n, "TFLOPs": fl / ms / 1e9,
+                           "algorithmic_GBps": by / ms / 1e6}
+    dom = kernels.get(names[0])
+    peak = MI355X_PEAK["fp32_TFLOPs"] if wl.dtype == "fp32" else MI355X_PEAK["bf16_TFLOPs"]
+    roofline = None
+    if dom:
+        roofline = {"kernel": names[0], "bound": "mfma", "achieved": dom["TFLOPs"], "peak": peak,
+                    "unit": "TFLOP/s", "frac": dom["TFLOPs"] / peak, "traffic": None,
+                    "avg_launch_us": dom["avg_launch_us"],
+                    "launches_per_step": dom["launches_per_step"]}
+
+    serial = None
+    if not args.no_serial:
+        s_steps = max(1, min(args.steps, 3))
+        ssec = timed(serial_step, s_steps, 1)
+        serial = {"value": T * B / ssec, "unit": "time-steps*batch/s", "ms_per_step": 1e3 * ssec,
+                  "what": "gru_serial_scan + gru_serial_scan_backward on the same GPU",
+                  "mgrit_speedup": ssec / sec}
+
+    out = {
+        "metric": "GRU time-steps x batch / sec, MGRIT fwd+bwd (1 GPU)",
+        "value": T * B / sec,
+        "unit": "time-steps*batch/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": 1e3 * sec,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if wl.dtype == "fp32" else "bf16-in/f32-state",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: T={T} B={B} D={D} H={H} cf={wl.cf} levels={wl.levels} "
+                               f"fwd_iters={fwd_iters} bwd_iters={bwd_iters} FCF implicit-GRU",
+                   "seed": wl.seed},
+        "residual_fwd": resf,
+        "residual_bwd": resb,
+        "roofline": roofline,
+        "kernels": kernels,
+        "serial_gpu": serial,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, fwd_iters, bwd_iters)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

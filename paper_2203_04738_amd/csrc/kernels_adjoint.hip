@@ -5,12 +5,36 @@
 // the parameter-gradient reductions of Alg. 3's gradient line.
 #include "common.h"
 #include "gemm_core.h"
+#include "skinny.h"
 
 namespace mg {
 
 // ---------------------------------------------------------------------------
 // Adjoint level step: out[R,H] = (kap[:, 0:3H] * (w,w,w))[R,3H] . UT[H,3H]^T + k_d*w
 // ---------------------------------------------------------------------------
+// Output of one element of the adjoint step: row (point pt, batch b), column j, given
+// the contraction  sum_g (U_g^T (k_g * w))_j.
+__device__ inline void adj_epilogue(const AdjArgs& a, long long pt, int b, int j, float dot,
+                                    double& nrm) {
+  const int H = a.H, B = a.B;
+  const float kd = a.kap[(a.k.at(pt) * B + b) * (long long)a.kw + 3 * H + j];
+  const float wv = a.w_in[(a.in.at(pt) * B + b) * H + j];
+  const float wn = kd * wv + dot;
+  const long long oi = (a.o.at(pt) * B + b) * H + j;
+  if (a.mode == STEP_RELAX) {
+    a.w[oi] = a.g ? wn + a.g[oi] : wn;
+  } else if (a.mode == STEP_RESID) {
+    const float cur = a.w[oi];
+    const float res = a.g ? cur - wn - a.g[oi] : cur - wn;
+    const long long ai = (a.a.at(pt) * B + b) * H + j;
+    a.gc[ai] = -res;
+    a.wc[ai] = cur;
+    nrm += (double)res * (double)res;
+  } else {  // STEP_RHS
+    a.g[oi] = (a.w[oi] - wn) + a.g[oi];
+  }
+}
+
 template <class C>
 __global__ __launch_bounds__(C::NT) void adj_step_kernel(AdjArgs a) {
   __shared__ __attribute__((aligned(16))) float lds[C::LDS_FLOATS];
@@ -68,22 +92,7 @@ __global__ __launch_bounds__(C::NT) void adj_step_kernel(AdjArgs a) {
         if (r >= R) continue;
         const long long pt = r / B;
         const int b = (int)(r - pt * B);
-        const float kd = a.kap[(a.k.at(pt) * B + b) * (long long)a.kw + 3 * H + j];
-        const float wv = a.w_in[(a.in.at(pt) * B + b) * H + j];
-        const float wn = kd * wv + acc.v[0][ba][bb][e];
-        const long long oi = (a.o.at(pt) * B + b) * H + j;
-        if (a.mode == STEP_RELAX) {
-          a.w[oi] = a.g ? wn + a.g[oi] : wn;
-        } else if (a.mode == STEP_RESID) {
-          const float cur = a.w[oi];
-          const float res = a.g ? cur - wn - a.g[oi] : cur - wn;
-          const long long ai = (a.a.at(pt) * B + b) * H + j;
-          a.gc[ai] = -res;
-          a.wc[ai] = cur;
-          nrm += (double)res * (double)res;
-        } else {  // STEP_RHS
-          a.g[oi] = (a.w[oi] - wn) + a.g[oi];
-        }
+        adj_epilogue(a, pt, b, j, acc.v[0][ba][bb][e], nrm);
       }
     }
   if (a.mode == STEP_RESID && a.norm) {
@@ -91,6 +100,56 @@ __global__ __launch_bounds__(C::NT) void adj_step_kernel(AdjArgs a) {
     for (int off = 32; off > 0; off >>= 1) nrm += __shfl_down(nrm, off, 64);
     if ((tid & 63) == 0) atomicAdd(a.norm, nrm);
   }
+}
+
+// Few-row variant (coarsest-level solve, serial BPTT): see skinny.h
+template <int CT>
+__global__ __launch_bounds__(SK_NT) void adj_skinny_kernel(AdjArgs a) {
+  __shared__ float red[SK_NT * CT];
+  const int H = a.H, B = a.B, K = 3 * a.H;
+  const int R = a.nk * B;
+  const int r0 = blockIdx.y * SK_MAXROWS;
+  const int rows_here = min(SK_MAXROWS, R - r0);
+  const int Rp = sk_row_pad(rows_here);
+  const int ksl = SK_NT / Rp;
+  const int tid = threadIdx.x;
+  const int ks = tid % ksl, bl = tid / ksl;
+  const int j0 = blockIdx.x * CT;
+  const bool live = bl < rows_here;
+
+  const float* krow = nullptr;
+  const float* wrow = nullptr;
+  if (live) {
+    const int r = r0 + bl;
+    const long long pt = r / B;
+    const int b = r - (int)pt * B;
+    krow = a.kap + (a.k.at(pt) * B + b) * (long long)a.kw;
+    wrow = a.w_in + (a.in.at(pt) * B + b) * H;
+  }
+  const float* urow[CT];
+#pragma unroll
+  for (int u = 0; u < CT; ++u) urow[u] = a.UT + (long long)min(j0 + u, H - 1) * K;
+  float acc[CT];
+  skinny_partial<CT>(acc, K, ks, ksl, live, urow, [&](int k) {
+    const int kk = k >= 2 * H ? k - 2 * H : (k >= H ? k - H : k);
+    return ldg4(krow + k) * ldg4(wrow + kk);
+  });
+#pragma unroll
+  for (int u = 0; u < CT; ++u) red[(bl * CT + u) * ksl + ks] = acc[u];
+  __syncthreads();
+
+  double nrm = 0.0;
+  if (tid < rows_here * CT) {
+    const int bl2 = tid / CT, c = tid % CT;
+    const int j = j0 + c;
+    if (j < H) {
+      const int r = r0 + bl2;
+      const long long pt = r / B;
+      const int b = r - (int)pt * B;
+      adj_epilogue(a, pt, b, j, skinny_sum<CT>(red, bl2, c, ksl), nrm);
+    }
+  }
+  if (a.mode == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
 }
 
 typedef TileCfg<2, 2, 2, 2, 1> AdjBig;    // 128 x 128, 256 threads
@@ -109,7 +168,16 @@ hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s) {
   const long long R = (long long)a.nk * a.B;
   auto tiles = [&](int tm, int tn) { return ((R + tm - 1) / tm) * ((a.H + tn - 1) / tn); };
   prof_begin(1, s);
-  if (tiles(AdjBig::TM, AdjBig::TN) >= 512)
+  if (R <= 2 * SK_MAXROWS) {
+    const int ct = a.H >= 512 ? 4 : (a.H >= 256 ? 2 : 1);
+    dim3 grid((unsigned)((a.H + ct - 1) / ct), (unsigned)((R + SK_MAXROWS - 1) / SK_MAXROWS));
+    if (ct == 4)
+      hipLaunchKernelGGL(adj_skinny_kernel<4>, grid, dim3(SK_NT), 0, s, a);
+    else if (ct == 2)
+      hipLaunchKernelGGL(adj_skinny_kernel<2>, grid, dim3(SK_NT), 0, s, a);
+    else
+      hipLaunchKernelGGL(adj_skinny_kernel<1>, grid, dim3(SK_NT), 0, s, a);
+  } else if (tiles(AdjBig::TM, AdjBig::TN) >= 512)
     launch_adj_cfg<AdjBig>(a, s);
   else if (R > 32 && tiles(AdjMid::TM, AdjMid::TN) >= 256)
     launch_adj_cfg<AdjMid>(a, s);

@@ -4,6 +4,7 @@
 // right-hand side of Eq. 11, and the adjoint coefficient vectors).
 #include "common.h"
 #include "gemm_core.h"
+#include "skinny.h"
 
 namespace mg {
 
@@ -73,6 +74,56 @@ hipError_t launch_projection(const float* X, const float* W, const float* bias, 
 // ---------------------------------------------------------------------------
 __device__ inline float sigmoidf_(float a) { return 1.0f / (1.0f + expf(-a)); }
 
+// Gates of Eq. 1, the update of Eq. 16 / Eq. 3 and the mode-specific output for one
+// element: row (point pt, batch b), hidden column j, given the three recurrent
+// contractions (U_r h)_j, (U_z h)_j, (U_n h)_j.
+__device__ inline void phi_epilogue(const PhiArgs& a, long long pt, int b, int j, float sr,
+                                    float sz, float sn, double& nrm) {
+  const int H = a.H, B = a.B;
+  const float gamma = a.gamma;
+  const bool implicit = a.propagator == MGRIT_PROP_IMPLICIT;
+  const float* pp = a.P + (a.p.at(pt) * B + b) * (3LL * H);
+  const float h = a.u_in[(a.in.at(pt) * B + b) * H + j];
+  const float rg = sigmoidf_(pp[j] + sr + a.b_h[j]);
+  const float zg = sigmoidf_(pp[H + j] + sz + a.b_h[H + j]);
+  const float q = sn + a.b_h[2 * H + j];
+  const float n = tanhf(pp[2 * H + j] + rg * q);
+  const float c = 1.0f - zg;
+  const float d = 1.0f + gamma * c;
+  const float hn = implicit ? (h + gamma * c * n) / d : h + gamma * c * (n - h);
+  const long long oi = (a.o.at(pt) * B + b) * H + j;
+  if (a.mode == STEP_RELAX) {
+    a.u[oi] = a.g ? hn + a.g[oi] : hn;
+  } else if (a.mode == STEP_RESID) {
+    const float cur = a.u[oi];
+    const float res = a.g ? cur - hn - a.g[oi] : cur - hn;
+    const long long ai = (a.a.at(pt) * B + b) * H + j;
+    a.gc[ai] = -res;
+    a.uc[ai] = cur;
+    nrm += (double)res * (double)res;
+  } else if (a.mode == STEP_RHS) {
+    a.g[oi] = (a.u[oi] - hn) + a.g[oi];
+  } else {  // STEP_KAPPA: coefficients of the transposed Jacobian of this step
+    float kd, dn, dz;
+    if (implicit) {
+      kd = 1.0f / d;
+      dn = gamma * c / d;
+      dz = -gamma * (n - hn) / d;
+    } else {
+      kd = 1.0f - gamma * c;
+      dn = gamma * c;
+      dz = -gamma * (n - h);
+    }
+    const float kn = dn * (1.0f - n * n);
+    float* kp = a.uc + (a.o.at(pt) * B + b) * (long long)a.kappa_width;
+    kp[j] = kn * q * rg * (1.0f - rg);
+    kp[H + j] = dz * zg * (1.0f - zg);
+    kp[2 * H + j] = kn * rg;
+    kp[3 * H + j] = kd;
+    if (a.kappa_width >= 5 * H) kp[4 * H + j] = kn;
+  }
+}
+
 template <class C>
 __global__ __launch_bounds__(C::NT) void phi_step_kernel(PhiArgs a) {
   __shared__ __attribute__((aligned(16))) float lds[C::LDS_FLOATS];
@@ -110,8 +161,6 @@ __global__ __launch_bounds__(C::NT) void phi_step_kernel(PhiArgs a) {
       [&](int s, int, int k) { return (arow[s] && k < H) ? ldg4(arow[s] + k) : zero4(); },
       [&](int s, int, int k) { return (brow[s] && k < H) ? ldg4(brow[s] + k) : zero4(); }, lds);
 
-  const float gamma = a.gamma;
-  const bool implicit = a.propagator == MGRIT_PROP_IMPLICIT;
   double nrm = 0.0;
 #pragma unroll
   for (int ba = 0; ba < C::BM; ++ba)
@@ -121,7 +170,6 @@ __global__ __launch_bounds__(C::NT) void phi_step_kernel(PhiArgs a) {
       acc_coord<C>(ba, bb, 0, row, col);
       const int j = n0 + col;
       if (j >= H) continue;
-      const float bhr = a.b_h[j], bhz = a.b_h[H + j], bhn = a.b_h[2 * H + j];
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         acc_coord<C>(ba, bb, e, row, col);
@@ -129,46 +177,8 @@ __global__ __launch_bounds__(C::NT) void phi_step_kernel(PhiArgs a) {
         if (r >= R) continue;
         const long long pt = r / B;
         const int b = (int)(r - pt * B);
-        const float* pp = a.P + (a.p.at(pt) * B + b) * (3LL * H);
-        const float h = a.u_in[(a.in.at(pt) * B + b) * H + j];
-        const float rg = sigmoidf_(pp[j] + acc.v[0][ba][bb][e] + bhr);
-        const float zg = sigmoidf_(pp[H + j] + acc.v[1][ba][bb][e] + bhz);
-        const float q = acc.v[2][ba][bb][e] + bhn;
-        const float n = tanhf(pp[2 * H + j] + rg * q);
-        const float c = 1.0f - zg;
-        const float d = 1.0f + gamma * c;
-        const float hn = implicit ? (h + gamma * c * n) / d : h + gamma * c * (n - h);
-        const long long oi = (a.o.at(pt) * B + b) * H + j;
-        if (a.mode == STEP_RELAX) {
-          a.u[oi] = a.g ? hn + a.g[oi] : hn;
-        } else if (a.mode == STEP_RESID) {
-          const float cur = a.u[oi];
-          const float res = a.g ? cur - hn - a.g[oi] : cur - hn;
-          const long long ai = (a.a.at(pt) * B + b) * H + j;
-          a.gc[ai] = -res;
-          a.uc[ai] = cur;
-          nrm += (double)res * (double)res;
-        } else if (a.mode == STEP_RHS) {
-          a.g[oi] = (a.u[oi] - hn) + a.g[oi];
-        } else {  // STEP_KAPPA: coefficients of the transposed Jacobian of this step
-          float kd, dn, dz;
-          if (implicit) {
-            kd = 1.0f / d;
-            dn = gamma * c / d;
-            dz = -gamma * (n - hn) / d;
-          } else {
-            kd = 1.0f - gamma * c;
-            dn = gamma * c;
-            dz = -gamma * (n - h);
-          }
-          const float kn = dn * (1.0f - n * n);
-          float* kp = a.uc + (a.o.at(pt) * B + b) * (long long)a.kappa_width;
-          kp[j] = kn * q * rg * (1.0f - rg);
-          kp[H + j] = dz * zg * (1.0f - zg);
-          kp[2 * H + j] = kn * rg;
-          kp[3 * H + j] = kd;
-          if (a.kappa_width >= 5 * H) kp[4 * H + j] = kn;
-        }
+        phi_epilogue(a, pt, b, j, acc.v[0][ba][bb][e], acc.v[1][ba][bb][e], acc.v[2][ba][bb][e],
+                     nrm);
       }
     }
   if (a.mode == STEP_RESID && a.norm) {
@@ -176,6 +186,59 @@ __global__ __launch_bounds__(C::NT) void phi_step_kernel(PhiArgs a) {
     for (int off = 32; off > 0; off >>= 1) nrm += __shfl_down(nrm, off, 64);
     if ((tid & 63) == 0) atomicAdd(a.norm, nrm);
   }
+}
+
+// ---------------------------------------------------------------------------
+// Few-row variant (coarsest-level propagation, serial scan): see skinny.h
+// ---------------------------------------------------------------------------
+template <int CT>
+__global__ __launch_bounds__(SK_NT) void phi_skinny_kernel(PhiArgs a) {
+  constexpr int NU = 3 * CT;
+  __shared__ float red[SK_NT * NU];
+  const int H = a.H, B = a.B;
+  const int R = a.nk * B;
+  const int r0 = blockIdx.y * SK_MAXROWS;
+  const int rows_here = min(SK_MAXROWS, R - r0);
+  const int Rp = sk_row_pad(rows_here);
+  const int ksl = SK_NT / Rp;
+  const int tid = threadIdx.x;
+  const int ks = tid % ksl, bl = tid / ksl;
+  const int j0 = blockIdx.x * CT;
+  const bool live = bl < rows_here;
+
+  const float* hrow = nullptr;
+  if (live) {
+    const int r = r0 + bl;
+    const long long pt = r / B;
+    const int b = r - (int)pt * B;
+    hrow = a.u_in + (a.in.at(pt) * B + b) * H;
+  }
+  const float* urow[NU];
+#pragma unroll
+  for (int u = 0; u < NU; ++u) {
+    const int g = u / CT, j = min(j0 + u % CT, H - 1);
+    urow[u] = a.U + ((long long)g * H + j) * H;
+  }
+  float acc[NU];
+  skinny_partial<NU>(acc, H, ks, ksl, live, urow, [&](int k) { return ldg4(hrow + k); });
+#pragma unroll
+  for (int u = 0; u < NU; ++u) red[(bl * NU + u) * ksl + ks] = acc[u];
+  __syncthreads();
+
+  double nrm = 0.0;
+  if (tid < rows_here * CT) {
+    const int bl2 = tid / CT, c = tid % CT;
+    const int j = j0 + c;
+    if (j < H) {
+      const int r = r0 + bl2;
+      const long long pt = r / B;
+      const int b = r - (int)pt * B;
+      phi_epilogue(a, pt, b, j, skinny_sum<NU>(red, bl2, c, ksl),
+                   skinny_sum<NU>(red, bl2, CT + c, ksl), skinny_sum<NU>(red, bl2, 2 * CT + c, ksl),
+                   nrm);
+    }
+  }
+  if (a.mode == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
 }
 
 typedef TileCfg<2, 2, 2, 1, 3> PhiBig;    // 128 rows x 64 hidden columns (x3 gates), 256 threads
@@ -194,7 +257,16 @@ hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s) {
   const long long R = (long long)a.nk * a.B;
   auto tiles = [&](int tm, int tn) { return ((R + tm - 1) / tm) * ((a.H + tn - 1) / tn); };
   prof_begin(0, s);
-  if (tiles(PhiBig::TM, PhiBig::TN) >= 512)
+  if (R <= 2 * SK_MAXROWS) {
+    const int ct = a.H >= 1024 ? 4 : (a.H >= 512 ? 2 : 1);
+    dim3 grid((unsigned)((a.H + ct - 1) / ct), (unsigned)((R + SK_MAXROWS - 1) / SK_MAXROWS));
+    if (ct == 4)
+      hipLaunchKernelGGL(phi_skinny_kernel<4>, grid, dim3(SK_NT), 0, s, a);
+    else if (ct == 2)
+      hipLaunchKernelGGL(phi_skinny_kernel<2>, grid, dim3(SK_NT), 0, s, a);
+    else
+      hipLaunchKernelGGL(phi_skinny_kernel<1>, grid, dim3(SK_NT), 0, s, a);
+  } else if (tiles(PhiBig::TM, PhiBig::TN) >= 512)
     launch_phi_cfg<PhiBig>(a, s);
   else if (R > 32 && tiles(PhiMid::TM, PhiMid::TN) >= 256)
     launch_phi_cfg<PhiMid>(a, s);

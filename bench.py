@@ -162,8 +162,11 @@ def main():
         mgrit_step()
     torch.cuda.synchronize()
     mg.mgrit_gru_profile_enable(False)
-    names = {0: "phi_step (fused forward level step)", 1: "adj_step (fused adjoint level step)",
-             2: "projection GEMM", 3: "weight-gradient GEMMs + bias sums"}
+    names = {0: "phi_step (fused forward level step, MFMA tiles)",
+             1: "adj_step (fused adjoint level step, MFMA tiles)",
+             2: "projection GEMM", 3: "weight-gradient GEMMs + bias sums",
+             4: "phi_skinny (few-row forward step, coarsest level)",
+             5: "adj_skinny (few-row adjoint step, coarsest level)"}
     kernels = {}
     for kind, nm in names.items():
         n, ms, fl, by = mg.mgrit_gru_profile_read(kind)

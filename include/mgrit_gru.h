@@ -155,8 +155,9 @@ MGRIT_API const char* mgrit_gru_strerror(int code);
  * launches, their summed duration in milliseconds and their summed
  * algorithmic flops and bytes; it then clears the record.  Event objects are
  * host-side and created on demand; nothing here touches device memory.
- *   kind: 0 = forward step (Phi), 1 = adjoint step (Phi^T), 2 = projection GEMM,
- *         3 = weight-gradient GEMMs.
+ *   kind: 0 = forward step (Phi) on MFMA tiles, 1 = adjoint step (Phi^T) on MFMA tiles,
+ *         2 = projection GEMM, 3 = weight-gradient GEMMs, 4 / 5 = forward / adjoint step
+ *         in the few-row form used by the serial scan and the coarsest-level solve.
  * All out-pointers are host pointers. */
 MGRIT_API int mgrit_gru_profile_enable(int on);
 MGRIT_API int mgrit_gru_profile_read(int kind, int64_t* launches, double* ms,

@@ -167,7 +167,8 @@ hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s) {
   if (a.nk <= 0) return hipSuccess;
   const long long R = (long long)a.nk * a.B;
   auto tiles = [&](int tm, int tn) { return ((R + tm - 1) / tm) * ((a.H + tn - 1) / tn); };
-  prof_begin(1, s);
+  const int kind = R <= 2 * SK_MAXROWS ? 5 : 1;
+  prof_begin(kind, s);
   if (R <= 2 * SK_MAXROWS) {
     const int ct = a.H >= 512 ? 4 : (a.H >= 256 ? 2 : 1);
     dim3 grid((unsigned)((a.H + ct - 1) / ct), (unsigned)((R + SK_MAXROWS - 1) / SK_MAXROWS));
@@ -183,7 +184,7 @@ hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s) {
     launch_adj_cfg<AdjMid>(a, s);
   else
     launch_adj_cfg<AdjSmall>(a, s);
-  prof_end(1, 6.0 * (double)R * a.H * a.H, 28.0 * (double)R * a.H, s);
+  prof_end(kind, 6.0 * (double)R * a.H * a.H, 28.0 * (double)R * a.H, s);
   return hipGetLastError();
 }
 

@@ -256,7 +256,8 @@ hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s) {
   if (a.nk <= 0) return hipSuccess;
   const long long R = (long long)a.nk * a.B;
   auto tiles = [&](int tm, int tn) { return ((R + tm - 1) / tm) * ((a.H + tn - 1) / tn); };
-  prof_begin(0, s);
+  const int kind = R <= 2 * SK_MAXROWS ? 4 : 0;
+  prof_begin(kind, s);
   if (R <= 2 * SK_MAXROWS) {
     const int ct = a.H >= 1024 ? 4 : (a.H >= 512 ? 2 : 1);
     dim3 grid((unsigned)((a.H + ct - 1) / ct), (unsigned)((R + SK_MAXROWS - 1) / SK_MAXROWS));
@@ -272,7 +273,7 @@ hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s) {
     launch_phi_cfg<PhiMid>(a, s);
   else
     launch_phi_cfg<PhiSmall>(a, s);
-  prof_end(0, 6.0 * (double)R * a.H * a.H, 20.0 * (double)R * a.H, s);
+  prof_end(kind, 6.0 * (double)R * a.H * a.H, 20.0 * (double)R * a.H, s);
   return hipGetLastError();
 }
 

@@ -11,7 +11,7 @@
 
 namespace mg {
 
-constexpr int SK_NT = 256;       // threads per workgroup
+constexpr int SK_NT = 1024;      // threads per workgroup
 constexpr int SK_MAXROWS = 32;   // rows per workgroup pass
 
 // rows padded to a power of two <= 32
@@ -27,19 +27,38 @@ __host__ __device__ inline int sk_row_pad(int rows) {
 template <int NU, class GetA>
 __device__ inline void skinny_partial(float (&acc)[NU], int K, int ks, int ksl, bool live,
                                       const float* const (&urow)[NU], GetA getA) {
+  // several independent slices are fetched before any is consumed, so that the
+  // loop pays one memory round trip per UNR slices
+  constexpr int UNR = NU > 4 ? 2 : 4;
 #pragma unroll
   for (int u = 0; u < NU; ++u) acc[u] = 0.f;
   if (!live) return;
-  for (int k = ks * 4; k < K; k += ksl * 4) {
-    const floatx4 a = getA(k);
+  const int stride = ksl * 4;
+  for (int k = ks * 4; k < K; k += stride * UNR) {
+    floatx4 a[UNR];
+    floatx4 w[UNR][NU];
 #pragma unroll
-    for (int u = 0; u < NU; ++u) {
-      const floatx4 w = ldg4(urow[u] + k);
-      acc[u] = fmaf(a[0], w[0], acc[u]);
-      acc[u] = fmaf(a[1], w[1], acc[u]);
-      acc[u] = fmaf(a[2], w[2], acc[u]);
-      acc[u] = fmaf(a[3], w[3], acc[u]);
+    for (int i = 0; i < UNR; ++i) {
+      const int kk = k + i * stride;
+      if (kk < K) {
+        a[i] = getA(kk);
+#pragma unroll
+        for (int u = 0; u < NU; ++u) w[i][u] = ldg4(urow[u] + kk);
+      } else {
+        a[i] = zero4();
+#pragma unroll
+        for (int u = 0; u < NU; ++u) w[i][u] = zero4();
+      }
     }
+#pragma unroll
+    for (int i = 0; i < UNR; ++i)
+#pragma unroll
+      for (int u = 0; u < NU; ++u) {
+        acc[u] = fmaf(a[i][0], w[i][u][0], acc[u]);
+        acc[u] = fmaf(a[i][1], w[i][u][1], acc[u]);
+        acc[u] = fmaf(a[i][2], w[i][u][2], acc[u]);
+        acc[u] = fmaf(a[i][3], w[i][u][3], acc[u]);
+      }
   }
 }
 

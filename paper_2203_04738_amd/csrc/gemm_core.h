@@ -3,13 +3,18 @@
 //
 // C[TM x (NG*TN)] += A[TM x K] * B[(NG*TN) x K]^T with both operands
 // K-contiguous in memory ("NT" form).  The tile is staged through LDS in
-// K-slices of TK = 32 floats and consumed by v_mfma_f32_32x32x2_f32:
+// K-slices of TK floats and consumed by v_mfma_f32_32x32x2_f32:
 //   - operand A: lane l supplies A[i = l%32][k = l/32]
 //   - operand B: lane l supplies B[k = l/32][j = l%32]
 //   - result:    register v of lane l holds D[i = 8*(v/4) + 4*(l/32) + v%4][j = l%32]
 // A lane reads four consecutive k (one ds_read_b128) and feeds four MFMAs; the
 // two half-waves take k-offsets 0..3 and 4..7 of every group of eight, so A and
 // B agree on which k each MFMA contracts.
+//
+// Pipeline: the global loads of slice kt+1 are issued into registers before the
+// MFMAs of slice kt; with NBUF = 2 they are written to the other LDS buffer
+// after the MFMAs and one barrier per slice suffices.  Inside a slice the LDS
+// fragments of k-group c+1 are read while the MFMAs of group c issue.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -19,21 +24,33 @@ namespace mg {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int TK = 32;        // K-slice staged per iteration
-constexpr int LDS_PAD = 4;    // floats; keeps rows 16-byte aligned and spreads banks
-constexpr int LDS_LD = TK + LDS_PAD;
+__device__ inline floatx4 ldg4(const float* p) { return *reinterpret_cast<const floatx4*>(p); }
+__device__ inline floatx4 zero4() {
+  floatx4 z = {0.f, 0.f, 0.f, 0.f};
+  return z;
+}
+struct Identity4 {
+  __device__ inline floatx4 operator()(const floatx4& v) const { return v; }
+};
 
-template <int WM_, int WN_, int BM_, int BN_, int NG_>
+constexpr int LDS_PAD = 4;    // floats; keeps rows 16-byte aligned and spreads banks
+
+template <int WM_, int WN_, int BM_, int BN_, int NG_, int TK_ = 32, int NBUF_ = 1>
 struct TileCfg {
-  static constexpr int WM = WM_, WN = WN_, BM = BM_, BN = BN_, NG = NG_;
+  static constexpr int WM = WM_, WN = WN_, BM = BM_, BN = BN_, NG = NG_, TK = TK_, NBUF = NBUF_;
   static constexpr int NWAVES = WM * WN;
   static constexpr int NT = NWAVES * 64;
   static constexpr int TM = WM * BM * 32;
   static constexpr int TN = WN * BN * 32;       // per gate group
   static constexpr int BROWS = NG * TN;
-  static constexpr int A_CHUNKS = (TM * (TK / 4) + NT - 1) / NT;     // float4 per thread
-  static constexpr int B_CHUNKS = (BROWS * (TK / 4) + NT - 1) / NT;
-  static constexpr int LDS_FLOATS = (TM + BROWS) * LDS_LD;
+  static constexpr int LD = TK + LDS_PAD;       // LDS row stride in floats
+  static constexpr int CPR = TK / 4;            // float4 chunks per tile row
+  static constexpr int A_CHUNKS = (TM * CPR) / NT;     // float4 per thread
+  static constexpr int B_CHUNKS = (BROWS * CPR) / NT;
+  static constexpr int BUF_FLOATS = (TM + BROWS) * LD;
+  static constexpr int LDS_FLOATS = NBUF * BUF_FLOATS;
+  static_assert((TM * CPR) % NT == 0 && (BROWS * CPR) % NT == 0, "tile rows must divide evenly");
+  static_assert(TK % 8 == 0, "TK must be a multiple of 8");
 };
 
 // Accumulators of one wave: acc[g][bm][bn] is a 32x32 block.
@@ -52,15 +69,21 @@ struct Acc {
   }
 };
 
-// One pass over K.  LoadA(s, row_in_tile, k) and LoadB(s, row_in_tile, k) return
-// the float4 at columns k..k+3 of that tile row (zeros outside the matrix); k is a
-// multiple of 4 and s is the index of the calling thread's chunk (its tile row is
-// fixed for the whole pass, so callers can keep one base pointer per chunk:
-// chunk s of thread tid covers tile row (tid + s*NT)/8).
-template <class C, class LoadA, class LoadB>
-__device__ inline void gemm_nt_tile(Acc<C>& acc, int K, LoadA loadA, LoadB loadB, float* lds) {
-  float* As = lds;
-  float* Bs = lds + C::TM * LDS_LD;
+// Tile row covered by chunk s of this thread (fixed for the whole pass).
+template <class C>
+__device__ inline int chunk_row(int s) { return (threadIdx.x + s * C::NT) / C::CPR; }
+
+// One pass over K.
+//   loadA(s, k) / loadB(s, k): raw global load(s) for the calling thread's chunk s
+//     at columns k..k+3 of its tile row (k a multiple of 4, always < K: the core
+//     clamps it).  The returned value (any trivially copyable type) stays in
+//     registers while the MFMAs of the current slice run.
+//   finA(raw) / finB(raw): turn the raw value into the float4 that goes to LDS;
+//     they run after the MFMAs, so nothing waits on the loads before that.
+// KTAIL: K is not a multiple of TK; columns >= K are zero-filled.
+template <class C, bool KTAIL, class LoadA, class LoadB, class FinA, class FinB>
+__device__ inline void gemm_nt_tile(Acc<C>& acc, int K, LoadA loadA, LoadB loadB, FinA finA,
+                                    FinB finB, float* lds) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
@@ -68,75 +91,121 @@ __device__ inline void gemm_nt_tile(Acc<C>& acc, int K, LoadA loadA, LoadB loadB
   const int wn = wave % C::WN;
   const int li = lane & 31;
   const int lh = lane >> 5;
+  constexpr int NC = C::TK / 8;          // k-groups of eight per slice
+  constexpr int NB = C::NG * C::BN;      // B fragments per k-group
 
-  floatx4 ra[C::A_CHUNKS];
-  floatx4 rb[C::B_CHUNKS];
+  decltype(loadA(0, 0)) ra[C::A_CHUNKS];
+  decltype(loadB(0, 0)) rb[C::B_CHUNKS];
 
   auto fetch = [&](int k0) {
 #pragma unroll
     for (int s = 0; s < C::A_CHUNKS; ++s) {
-      int q = tid + s * C::NT;
-      int row = q / (TK / 4), c4 = q % (TK / 4);
-      if (C::TM * (TK / 4) % C::NT == 0 || row < C::TM) ra[s] = loadA(s, row, k0 + c4 * 4);
+      int k = k0 + ((tid + s * C::NT) % C::CPR) * 4;
+      if (KTAIL && k >= K) k = K - 4;
+      ra[s] = loadA(s, k);
     }
 #pragma unroll
     for (int s = 0; s < C::B_CHUNKS; ++s) {
-      int q = tid + s * C::NT;
-      int row = q / (TK / 4), c4 = q % (TK / 4);
-      if (C::BROWS * (TK / 4) % C::NT == 0 || row < C::BROWS) rb[s] = loadB(s, row, k0 + c4 * 4);
+      int k = k0 + ((tid + s * C::NT) % C::CPR) * 4;
+      if (KTAIL && k >= K) k = K - 4;
+      rb[s] = loadB(s, k);
     }
   };
-  auto stash = [&]() {
+  auto stash = [&](float* buf, int k0) {
+    float* As = buf;
+    float* Bs = buf + C::TM * C::LD;
 #pragma unroll
     for (int s = 0; s < C::A_CHUNKS; ++s) {
-      int q = tid + s * C::NT;
-      int row = q / (TK / 4), c4 = q % (TK / 4);
-      if (C::TM * (TK / 4) % C::NT == 0 || row < C::TM)
-        *reinterpret_cast<floatx4*>(&As[row * LDS_LD + c4 * 4]) = ra[s];
+      const int q = tid + s * C::NT;
+      floatx4 v = finA(ra[s]);
+      if (KTAIL && k0 + (q % C::CPR) * 4 >= K) v = zero4();
+      *reinterpret_cast<floatx4*>(&As[(q / C::CPR) * C::LD + (q % C::CPR) * 4]) = v;
     }
 #pragma unroll
     for (int s = 0; s < C::B_CHUNKS; ++s) {
-      int q = tid + s * C::NT;
-      int row = q / (TK / 4), c4 = q % (TK / 4);
-      if (C::BROWS * (TK / 4) % C::NT == 0 || row < C::BROWS)
-        *reinterpret_cast<floatx4*>(&Bs[row * LDS_LD + c4 * 4]) = rb[s];
+      const int q = tid + s * C::NT;
+      floatx4 v = finB(rb[s]);
+      if (KTAIL && k0 + (q % C::CPR) * 4 >= K) v = zero4();
+      *reinterpret_cast<floatx4*>(&Bs[(q / C::CPR) * C::LD + (q % C::CPR) * 4]) = v;
     }
   };
-
-  const int nkt = (K + TK - 1) / TK;
-  fetch(0);
-  stash();
-  __syncthreads();
-  for (int kt = 0; kt < nkt; ++kt) {
-    if (kt + 1 < nkt) fetch((kt + 1) * TK);
+  // fragment addresses of this lane inside a buffer (k-group 0)
+  const int a_off = ((wm * C::BM) * 32 + li) * C::LD + lh * 4;
+  const int b_off = C::TM * C::LD + ((wn * C::BN) * 32 + li) * C::LD + lh * 4;
+  auto read_frags = [&](const float* buf, int c, floatx4 (&fa)[C::BM], floatx4 (&fb)[NB]) {
 #pragma unroll
-    for (int c = 0; c < TK / 8; ++c) {
-      floatx4 a4[C::BM];
+    for (int a = 0; a < C::BM; ++a)
+      fa[a] = *reinterpret_cast<const floatx4*>(&buf[a_off + a * 32 * C::LD + c * 8]);
 #pragma unroll
-      for (int a = 0; a < C::BM; ++a)
-        a4[a] = *reinterpret_cast<const floatx4*>(
-            &As[((wm * C::BM + a) * 32 + li) * LDS_LD + c * 8 + lh * 4]);
+    for (int g = 0; g < C::NG; ++g)
+#pragma unroll
+      for (int b = 0; b < C::BN; ++b)
+        fb[g * C::BN + b] = *reinterpret_cast<const floatx4*>(
+            &buf[b_off + (g * C::TN + b * 32) * C::LD + c * 8]);
+  };
+  auto mma = [&](const floatx4 (&fa)[C::BM], const floatx4 (&fb)[NB]) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
 #pragma unroll
       for (int g = 0; g < C::NG; ++g)
 #pragma unroll
-        for (int b = 0; b < C::BN; ++b) {
-          floatx4 b4 = *reinterpret_cast<const floatx4*>(
-              &Bs[(g * C::TN + (wn * C::BN + b) * 32 + li) * LDS_LD + c * 8 + lh * 4]);
+        for (int b = 0; b < C::BN; ++b)
 #pragma unroll
-          for (int a = 0; a < C::BM; ++a) {
+          for (int a = 0; a < C::BM; ++a)
+            acc.v[g][a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                fa[a][e], fb[g * C::BN + b][e], acc.v[g][a][b], 0, 0, 0);
+  };
+
+  const int nkt = (K + C::TK - 1) / C::TK;
+  fetch(0);
+  stash(lds, 0);
+  __syncthreads();
+  for (int kt = 0; kt < nkt; ++kt) {
+    const float* cur = lds + (C::NBUF == 2 ? (kt & 1) * C::BUF_FLOATS : 0);
+    float* nxt = lds + (C::NBUF == 2 ? ((kt + 1) & 1) * C::BUF_FLOATS : 0);
+    const bool more = kt + 1 < nkt;
+    if (more) fetch((kt + 1) * C::TK);
+    // the loads above stay in flight across the MFMAs; their consumers are below
+    __builtin_amdgcn_sched_barrier(0);
+    floatx4 fa[2][C::BM];
+    floatx4 fb[2][NB];
+    read_frags(cur, 0, fa[0], fb[0]);
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-              acc.v[g][a][b] =
-                  __builtin_amdgcn_mfma_f32_32x32x2f32(a4[a][e], b4[e], acc.v[g][a][b], 0, 0, 0);
-          }
-        }
+    for (int c = 0; c < NC; ++c) {
+      if (c + 1 < NC) read_frags(cur, c + 1, fa[(c + 1) & 1], fb[(c + 1) & 1]);
+      mma(fa[c & 1], fb[c & 1]);
     }
-    __syncthreads();
-    if (kt + 1 < nkt) {
-      stash();
+    __builtin_amdgcn_sched_barrier(0);
+    if (C::NBUF == 2) {
+      if (more) stash(nxt, (kt + 1) * C::TK);
       __syncthreads();
+    } else {
+      __syncthreads();
+      if (more) {
+        stash(nxt, (kt + 1) * C::TK);
+        __syncthreads();
+      }
     }
   }
+}
+
+// XCD-aware tile order.  Workgroups are dispatched round-robin over the 8 XCDs
+// (workgroup id % 8), each with its own L2.  Row tile rt is pinned to XCD rt % 8
+// and, inside an XCD, consecutive workgroups walk the column tiles of one row
+// tile, so the A rows of a row tile are fetched into one L2 only and the
+// workgroups resident on an XCD share a small set of A tiles.
+// The 1-D grid has 8 * ncol * ceil(nrow / 8) workgroups; returns false for the
+// padding ones.
+constexpr int NXCD = 8;
+__host__ __device__ inline long long xcd_grid(long long nrow, int ncol) {
+  return ((nrow + NXCD - 1) / NXCD) * NXCD * ncol;
+}
+__device__ inline bool xcd_tile(long long bid, long long nrow, int ncol, long long& rt, int& ct) {
+  const int xcd = (int)(bid % NXCD);
+  const long long j = bid / NXCD;
+  ct = (int)(j % ncol);
+  rt = (j / ncol) * NXCD + xcd;
+  return rt < nrow;
 }
 
 // Coordinates of accumulator element e of block (a, b) of this wave inside the
@@ -148,12 +217,6 @@ __device__ inline void acc_coord(int a, int b, int e, int& row, int& col) {
   const int wm = wave / C::WN, wn = wave % C::WN;
   row = (wm * C::BM + a) * 32 + 8 * (e / 4) + 4 * (lane >> 5) + (e & 3);
   col = (wn * C::BN + b) * 32 + (lane & 31);
-}
-
-__device__ inline floatx4 ldg4(const float* p) { return *reinterpret_cast<const floatx4*>(p); }
-__device__ inline floatx4 zero4() {
-  floatx4 z = {0.f, 0.f, 0.f, 0.f};
-  return z;
 }
 
 }  // namespace mg

@@ -35,13 +35,20 @@ __device__ inline void adj_epilogue(const AdjArgs& a, long long pt, int b, int j
   }
 }
 
+struct KapW {
+  floatx4 kap, w;
+};
+
 template <class C>
 __global__ __launch_bounds__(C::NT) void adj_step_kernel(AdjArgs a) {
   __shared__ __attribute__((aligned(16))) float lds[C::LDS_FLOATS];
   const int H = a.H, B = a.B, K = 3 * a.H;
   const long long R = (long long)a.nk * B;
-  const long long m0 = (long long)blockIdx.x * C::TM;
-  const int n0 = blockIdx.y * C::TN;
+  long long rt;
+  int ct;
+  if (!xcd_tile(blockIdx.x, (R + C::TM - 1) / C::TM, (H + C::TN - 1) / C::TN, rt, ct)) return;
+  const long long m0 = rt * C::TM;
+  const int n0 = ct * C::TN;
   const int tid = threadIdx.x;
 
   const float* krow[C::A_CHUNKS];
@@ -49,32 +56,33 @@ __global__ __launch_bounds__(C::NT) void adj_step_kernel(AdjArgs a) {
   const float* brow[C::B_CHUNKS];
 #pragma unroll
   for (int s = 0; s < C::A_CHUNKS; ++s) {
-    long long r = m0 + (tid + s * C::NT) / (TK / 4);
-    if (r < R) {
-      long long pt = r / B;
-      int b = (int)(r - pt * B);
-      krow[s] = a.kap + (a.k.at(pt) * B + b) * (long long)a.kw;
-      wrow[s] = a.w_in + (a.in.at(pt) * B + b) * H;
-    } else {
-      krow[s] = nullptr;
-      wrow[s] = nullptr;
-    }
+    long long r = m0 + chunk_row<C>(s);
+    if (r >= R) r = R - 1;     // clamped rows are never stored
+    const long long pt = r / B;
+    const int b = (int)(r - pt * B);
+    krow[s] = a.kap + (a.k.at(pt) * B + b) * (long long)a.kw;
+    wrow[s] = a.w_in + (a.in.at(pt) * B + b) * H;
   }
 #pragma unroll
   for (int s = 0; s < C::B_CHUNKS; ++s) {
-    int j = n0 + (tid + s * C::NT) / (TK / 4);
-    brow[s] = j < H ? a.UT + (long long)j * K : nullptr;
+    int j = n0 + chunk_row<C>(s);
+    if (j >= H) j = H - 1;
+    brow[s] = a.UT + (long long)j * K;
   }
   Acc<C> acc;
   acc.zero();
-  gemm_nt_tile<C>(
-      acc, K,
-      [&](int s, int, int k) {
-        if (!krow[s] || k >= K) return zero4();
-        int kk = k >= 2 * H ? k - 2 * H : (k >= H ? k - H : k);
-        return ldg4(krow[s] + k) * ldg4(wrow[s] + kk);
-      },
-      [&](int s, int, int k) { return (brow[s] && k < K) ? ldg4(brow[s] + k) : zero4(); }, lds);
+  // A operand: kappa and w stay raw in registers during the MFMAs of the current
+  // slice and are multiplied when the slice is written to LDS
+  auto la = [&](int s, int k) {
+    const int kk = k >= 2 * H ? k - 2 * H : (k >= H ? k - H : k);
+    return KapW{ldg4(krow[s] + k), ldg4(wrow[s] + kk)};
+  };
+  auto lb = [&](int s, int k) { return ldg4(brow[s] + k); };
+  auto fa = [](const KapW& r) { return r.kap * r.w; };
+  if (K % C::TK == 0)
+    gemm_nt_tile<C, false>(acc, K, la, lb, fa, Identity4(), lds);
+  else
+    gemm_nt_tile<C, true>(acc, K, la, lb, fa, Identity4(), lds);
 
   double nrm = 0.0;
 #pragma unroll
@@ -159,7 +167,7 @@ typedef TileCfg<1, 1, 1, 1, 1> AdjSmall;  //  32 x 32, 64 threads
 template <class C>
 static void launch_adj_cfg(const AdjArgs& a, hipStream_t s) {
   const long long R = (long long)a.nk * a.B;
-  dim3 grid((unsigned)((R + C::TM - 1) / C::TM), (unsigned)((a.H + C::TN - 1) / C::TN));
+  dim3 grid((unsigned)xcd_grid((R + C::TM - 1) / C::TM, (a.H + C::TN - 1) / C::TN));
   hipLaunchKernelGGL(adj_step_kernel<C>, grid, dim3(C::NT), 0, s, a);
 }
 

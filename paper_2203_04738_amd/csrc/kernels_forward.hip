@@ -18,28 +18,35 @@ __global__ __launch_bounds__(ProjCfg::NT) void projection_kernel(
     float* __restrict__ P, long long M, int N, int K) {
   typedef ProjCfg C;
   __shared__ __attribute__((aligned(16))) float lds[C::LDS_FLOATS];
-  const long long m0 = (long long)blockIdx.x * C::TM;
-  const int n0 = blockIdx.y * C::TN;
+  long long rt;
+  int ct;
+  if (!xcd_tile(blockIdx.x, (M + C::TM - 1) / C::TM, (N + C::TN - 1) / C::TN, rt, ct)) return;
+  const long long m0 = rt * C::TM;
+  const int n0 = ct * C::TN;
   const int tid = threadIdx.x;
 
+  // rows beyond the matrix are clamped to its last row (their results are never
+  // stored); k beyond K contributes zeros
   const float* arow[C::A_CHUNKS];
   const float* brow[C::B_CHUNKS];
 #pragma unroll
   for (int s = 0; s < C::A_CHUNKS; ++s) {
-    long long r = m0 + (tid + s * C::NT) / (TK / 4);
-    arow[s] = r < M ? X + r * K : nullptr;
+    long long r = m0 + chunk_row<C>(s);
+    arow[s] = X + (r < M ? r : M - 1) * K;
   }
 #pragma unroll
   for (int s = 0; s < C::B_CHUNKS; ++s) {
-    int r = n0 + (tid + s * C::NT) / (TK / 4);
-    brow[s] = r < N ? W + (long long)r * K : nullptr;
+    int r = n0 + chunk_row<C>(s);
+    brow[s] = W + (long long)(r < N ? r : N - 1) * K;
   }
   Acc<C> acc;
   acc.zero();
-  gemm_nt_tile<C>(
-      acc, K,
-      [&](int s, int, int k) { return (arow[s] && k < K) ? ldg4(arow[s] + k) : zero4(); },
-      [&](int s, int, int k) { return (brow[s] && k < K) ? ldg4(brow[s] + k) : zero4(); }, lds);
+  auto la = [&](int s, int k) { return ldg4(arow[s] + k); };
+  auto lb = [&](int s, int k) { return ldg4(brow[s] + k); };
+  if (K % C::TK == 0)
+    gemm_nt_tile<C, false>(acc, K, la, lb, Identity4(), Identity4(), lds);
+  else
+    gemm_nt_tile<C, true>(acc, K, la, lb, Identity4(), Identity4(), lds);
 
 #pragma unroll
   for (int a = 0; a < C::BM; ++a)
@@ -62,7 +69,7 @@ __global__ __launch_bounds__(ProjCfg::NT) void projection_kernel(
 hipError_t launch_projection(const float* X, const float* W, const float* bias, float* P,
                              long long M, int N, int K, hipStream_t s) {
   typedef ProjCfg C;
-  dim3 grid((unsigned)((M + C::TM - 1) / C::TM), (unsigned)((N + C::TN - 1) / C::TN));
+  dim3 grid((unsigned)xcd_grid((M + C::TM - 1) / C::TM, (N + C::TN - 1) / C::TN));
   prof_begin(2, s);
   hipLaunchKernelGGL(projection_kernel, grid, dim3(C::NT), 0, s, X, W, bias, P, M, N, K);
   prof_end(2, 2.0 * (double)M * N * K, 4.0 * ((double)M * K + (double)N * K + (double)M * N), s);
@@ -72,7 +79,19 @@ hipError_t launch_projection(const float* X, const float* W, const float* bias, 
 // ---------------------------------------------------------------------------
 // Fused level step
 // ---------------------------------------------------------------------------
-__device__ inline float sigmoidf_(float a) { return 1.0f / (1.0f + expf(-a)); }
+// Gate nonlinearities on the hardware exp2 / reciprocal units (each within 1 ulp):
+// absolute error of sigmoid and tanh about 1e-7, far inside the fp32 parity bar,
+// at a fraction of the instruction count of the library routines.
+__device__ inline float fast_rcp(float a) { return __builtin_amdgcn_rcpf(a); }
+__device__ inline float sigmoidf_(float a) {
+  return fast_rcp(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896341f * a));
+}
+__device__ inline float tanhf_(float a) {
+  // tanh(a) = sign(a) (1 - e)/(1 + e), e = exp(-2|a|) in (0, 1]
+  const float e = __builtin_amdgcn_exp2f(-2.88539008177792681f * fabsf(a));
+  const float t = (1.0f - e) * fast_rcp(1.0f + e);
+  return copysignf(t, a);
+}
 
 // Gates of Eq. 1, the update of Eq. 16 / Eq. 3 and the mode-specific output for one
 // element: row (point pt, batch b), hidden column j, given the three recurrent
@@ -87,10 +106,11 @@ __device__ inline void phi_epilogue(const PhiArgs& a, long long pt, int b, int j
   const float rg = sigmoidf_(pp[j] + sr + a.b_h[j]);
   const float zg = sigmoidf_(pp[H + j] + sz + a.b_h[H + j]);
   const float q = sn + a.b_h[2 * H + j];
-  const float n = tanhf(pp[2 * H + j] + rg * q);
+  const float n = tanhf_(pp[2 * H + j] + rg * q);
   const float c = 1.0f - zg;
   const float d = 1.0f + gamma * c;
-  const float hn = implicit ? (h + gamma * c * n) / d : h + gamma * c * (n - h);
+  const float rd = fast_rcp(d);
+  const float hn = implicit ? (h + gamma * c * n) * rd : h + gamma * c * (n - h);
   const long long oi = (a.o.at(pt) * B + b) * H + j;
   if (a.mode == STEP_RELAX) {
     a.u[oi] = a.g ? hn + a.g[oi] : hn;
@@ -106,9 +126,9 @@ __device__ inline void phi_epilogue(const PhiArgs& a, long long pt, int b, int j
   } else {  // STEP_KAPPA: coefficients of the transposed Jacobian of this step
     float kd, dn, dz;
     if (implicit) {
-      kd = 1.0f / d;
-      dn = gamma * c / d;
-      dz = -gamma * (n - hn) / d;
+      kd = rd;
+      dn = gamma * c * rd;
+      dz = -gamma * (n - hn) * rd;
     } else {
       kd = 1.0f - gamma * c;
       dn = gamma * c;
@@ -129,37 +149,42 @@ __global__ __launch_bounds__(C::NT) void phi_step_kernel(PhiArgs a) {
   __shared__ __attribute__((aligned(16))) float lds[C::LDS_FLOATS];
   const int H = a.H, B = a.B;
   const long long R = (long long)a.nk * B;
-  const long long m0 = (long long)blockIdx.x * C::TM;
-  const int n0 = blockIdx.y * C::TN;
+  long long rt;
+  int ct;
+  if (!xcd_tile(blockIdx.x, (R + C::TM - 1) / C::TM, (H + C::TN - 1) / C::TN, rt, ct)) return;
+  const long long m0 = rt * C::TM;
+  const int n0 = ct * C::TN;
   const int tid = threadIdx.x;
 
-  // A rows: states of the points this tile covers (row = point*B + b).
+  // A rows: states of the points this tile covers (row = point*B + b); rows beyond
+  // the launch are clamped to its last row and never stored.
   const float* arow[C::A_CHUNKS];
   const float* brow[C::B_CHUNKS];
 #pragma unroll
   for (int s = 0; s < C::A_CHUNKS; ++s) {
-    long long r = m0 + (tid + s * C::NT) / (TK / 4);
-    if (r < R) {
-      long long pt = r / B;
-      int b = (int)(r - pt * B);
-      arow[s] = a.u_in + (a.in.at(pt) * B + b) * H;
-    } else {
-      arow[s] = nullptr;
-    }
+    long long r = m0 + chunk_row<C>(s);
+    if (r >= R) r = R - 1;
+    const long long pt = r / B;
+    const int b = (int)(r - pt * B);
+    arow[s] = a.u_in + (a.in.at(pt) * B + b) * H;
   }
   // B rows: for gate g the rows n0.. of U_g.
 #pragma unroll
   for (int s = 0; s < C::B_CHUNKS; ++s) {
-    int tr = (tid + s * C::NT) / (TK / 4);
-    int g = tr / C::TN, j = n0 + tr % C::TN;
-    brow[s] = j < H ? a.U + ((long long)g * H + j) * H : nullptr;
+    const int tr = chunk_row<C>(s);
+    const int g = tr / C::TN;
+    int j = n0 + tr % C::TN;
+    if (j >= H) j = H - 1;
+    brow[s] = a.U + ((long long)g * H + j) * H;
   }
   Acc<C> acc;
   acc.zero();
-  gemm_nt_tile<C>(
-      acc, H,
-      [&](int s, int, int k) { return (arow[s] && k < H) ? ldg4(arow[s] + k) : zero4(); },
-      [&](int s, int, int k) { return (brow[s] && k < H) ? ldg4(brow[s] + k) : zero4(); }, lds);
+  auto la = [&](int s, int k) { return ldg4(arow[s] + k); };
+  auto lb = [&](int s, int k) { return ldg4(brow[s] + k); };
+  if (H % C::TK == 0)
+    gemm_nt_tile<C, false>(acc, H, la, lb, Identity4(), Identity4(), lds);
+  else
+    gemm_nt_tile<C, true>(acc, H, la, lb, Identity4(), Identity4(), lds);
 
   double nrm = 0.0;
 #pragma unroll
@@ -248,7 +273,7 @@ typedef TileCfg<1, 1, 1, 1, 3> PhiSmall;  //  32 rows x 32 hidden columns, 64 th
 template <class C>
 static void launch_phi_cfg(const PhiArgs& a, hipStream_t s) {
   const long long R = (long long)a.nk * a.B;
-  dim3 grid((unsigned)((R + C::TM - 1) / C::TM), (unsigned)((a.H + C::TN - 1) / C::TN));
+  dim3 grid((unsigned)xcd_grid((R + C::TM - 1) / C::TM, (a.H + C::TN - 1) / C::TN));
   hipLaunchKernelGGL(phi_step_kernel<C>, grid, dim3(C::NT), 0, s, a);
 }
 

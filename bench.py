@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--bwd-iters", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-serial", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="run one 256 MiB device-to-device copy first: the known-size kernel that "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     return ap.parse_args()
 
 
@@ -151,6 +154,13 @@ def main():
             fn()
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
+
+    if args.pmc_calibration:
+        src = torch.ones(64 << 20, device=dev)          # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     sec = timed(mgrit_step, args.steps, args.warmup)
     resf = res_f.cpu().numpy().tolist()[:fwd_iters]

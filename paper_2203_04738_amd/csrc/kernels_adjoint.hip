@@ -14,6 +14,7 @@ namespace mg {
 // ---------------------------------------------------------------------------
 // Output of one element of the adjoint step: row (point pt, batch b), column j, given
 // the contraction  sum_g (U_g^T (k_g * w))_j.
+template <int MODE>
 __device__ inline void adj_epilogue(const AdjArgs& a, long long pt, int b, int j, float dot,
                                     double& nrm) {
   const int H = a.H, B = a.B;
@@ -21,9 +22,9 @@ __device__ inline void adj_epilogue(const AdjArgs& a, long long pt, int b, int j
   const float wv = a.w_in[(a.in.at(pt) * B + b) * H + j];
   const float wn = kd * wv + dot;
   const long long oi = (a.o.at(pt) * B + b) * H + j;
-  if (a.mode == STEP_RELAX) {
+  if (MODE == STEP_RELAX) {
     a.w[oi] = a.g ? wn + a.g[oi] : wn;
-  } else if (a.mode == STEP_RESID) {
+  } else if (MODE == STEP_RESID) {
     const float cur = a.w[oi];
     const float res = a.g ? cur - wn - a.g[oi] : cur - wn;
     const long long ai = (a.a.at(pt) * B + b) * H + j;
@@ -39,7 +40,7 @@ struct KapW {
   floatx4 kap, w;
 };
 
-template <class C>
+template <class C, int MODE>
 __global__ __launch_bounds__(C::NT) void adj_step_kernel(AdjArgs a) {
   __shared__ __attribute__((aligned(16))) float lds[C::LDS_FLOATS];
   const int H = a.H, B = a.B, K = 3 * a.H;
@@ -100,10 +101,10 @@ __global__ __launch_bounds__(C::NT) void adj_step_kernel(AdjArgs a) {
         if (r >= R) continue;
         const long long pt = r / B;
         const int b = (int)(r - pt * B);
-        adj_epilogue(a, pt, b, j, acc.v[0][ba][bb][e], nrm);
+        adj_epilogue<MODE>(a, pt, b, j, acc.v[0][ba][bb][e], nrm);
       }
     }
-  if (a.mode == STEP_RESID && a.norm) {
+  if (MODE == STEP_RESID && a.norm) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) nrm += __shfl_down(nrm, off, 64);
     if ((tid & 63) == 0) atomicAdd(a.norm, nrm);
@@ -111,7 +112,7 @@ __global__ __launch_bounds__(C::NT) void adj_step_kernel(AdjArgs a) {
 }
 
 // Few-row variant (coarsest-level solve, serial BPTT): see skinny.h
-template <int CT>
+template <int CT, int MODE>
 __global__ __launch_bounds__(SK_NT) void adj_skinny_kernel(AdjArgs a) {
   __shared__ float red[SK_NT * CT];
   const int H = a.H, B = a.B, K = 3 * a.H;
@@ -154,10 +155,10 @@ __global__ __launch_bounds__(SK_NT) void adj_skinny_kernel(AdjArgs a) {
       const int r = r0 + bl2;
       const long long pt = r / B;
       const int b = r - (int)pt * B;
-      adj_epilogue(a, pt, b, j, skinny_sum<CT>(red, bl2, c, ksl), nrm);
+      adj_epilogue<MODE>(a, pt, b, j, skinny_sum<CT>(red, bl2, c, ksl), nrm);
     }
   }
-  if (a.mode == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
+  if (MODE == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
 }
 
 typedef TileCfg<2, 2, 2, 2, 1> AdjBig;    // 128 x 128, 256 threads
@@ -168,7 +169,22 @@ template <class C>
 static void launch_adj_cfg(const AdjArgs& a, hipStream_t s) {
   const long long R = (long long)a.nk * a.B;
   dim3 grid((unsigned)xcd_grid((R + C::TM - 1) / C::TM, (a.H + C::TN - 1) / C::TN));
-  hipLaunchKernelGGL(adj_step_kernel<C>, grid, dim3(C::NT), 0, s, a);
+  if (a.mode == STEP_RELAX)
+    hipLaunchKernelGGL((adj_step_kernel<C, STEP_RELAX>), grid, dim3(C::NT), 0, s, a);
+  else if (a.mode == STEP_RESID)
+    hipLaunchKernelGGL((adj_step_kernel<C, STEP_RESID>), grid, dim3(C::NT), 0, s, a);
+  else
+    hipLaunchKernelGGL((adj_step_kernel<C, STEP_RHS>), grid, dim3(C::NT), 0, s, a);
+}
+
+template <int CT>
+static void launch_adj_skinny(const AdjArgs& a, dim3 grid, hipStream_t s) {
+  if (a.mode == STEP_RELAX)
+    hipLaunchKernelGGL((adj_skinny_kernel<CT, STEP_RELAX>), grid, dim3(SK_NT), 0, s, a);
+  else if (a.mode == STEP_RESID)
+    hipLaunchKernelGGL((adj_skinny_kernel<CT, STEP_RESID>), grid, dim3(SK_NT), 0, s, a);
+  else
+    hipLaunchKernelGGL((adj_skinny_kernel<CT, STEP_RHS>), grid, dim3(SK_NT), 0, s, a);
 }
 
 hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s) {
@@ -181,11 +197,11 @@ hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s) {
     const int ct = a.H >= 512 ? 4 : (a.H >= 256 ? 2 : 1);
     dim3 grid((unsigned)((a.H + ct - 1) / ct), (unsigned)((R + SK_MAXROWS - 1) / SK_MAXROWS));
     if (ct == 4)
-      hipLaunchKernelGGL(adj_skinny_kernel<4>, grid, dim3(SK_NT), 0, s, a);
+      launch_adj_skinny<4>(a, grid, s);
     else if (ct == 2)
-      hipLaunchKernelGGL(adj_skinny_kernel<2>, grid, dim3(SK_NT), 0, s, a);
+      launch_adj_skinny<2>(a, grid, s);
     else
-      hipLaunchKernelGGL(adj_skinny_kernel<1>, grid, dim3(SK_NT), 0, s, a);
+      launch_adj_skinny<1>(a, grid, s);
   } else if (tiles(AdjBig::TM, AdjBig::TN) >= 512)
     launch_adj_cfg<AdjBig>(a, s);
   else if (R > 32 && tiles(AdjMid::TM, AdjMid::TN) >= 256)

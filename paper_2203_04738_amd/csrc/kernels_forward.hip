@@ -96,6 +96,7 @@ __device__ inline float tanhf_(float a) {
 // Gates of Eq. 1, the update of Eq. 16 / Eq. 3 and the mode-specific output for one
 // element: row (point pt, batch b), hidden column j, given the three recurrent
 // contractions (U_r h)_j, (U_z h)_j, (U_n h)_j.
+template <int MODE>
 __device__ inline void phi_epilogue(const PhiArgs& a, long long pt, int b, int j, float sr,
                                     float sz, float sn, double& nrm) {
   const int H = a.H, B = a.B;
@@ -112,16 +113,16 @@ __device__ inline void phi_epilogue(const PhiArgs& a, long long pt, int b, int j
   const float rd = fast_rcp(d);
   const float hn = implicit ? (h + gamma * c * n) * rd : h + gamma * c * (n - h);
   const long long oi = (a.o.at(pt) * B + b) * H + j;
-  if (a.mode == STEP_RELAX) {
+  if (MODE == STEP_RELAX) {
     a.u[oi] = a.g ? hn + a.g[oi] : hn;
-  } else if (a.mode == STEP_RESID) {
+  } else if (MODE == STEP_RESID) {
     const float cur = a.u[oi];
     const float res = a.g ? cur - hn - a.g[oi] : cur - hn;
     const long long ai = (a.a.at(pt) * B + b) * H + j;
     a.gc[ai] = -res;
     a.uc[ai] = cur;
     nrm += (double)res * (double)res;
-  } else if (a.mode == STEP_RHS) {
+  } else if (MODE == STEP_RHS) {
     a.g[oi] = (a.u[oi] - hn) + a.g[oi];
   } else {  // STEP_KAPPA: coefficients of the transposed Jacobian of this step
     float kd, dn, dz;
@@ -144,7 +145,7 @@ __device__ inline void phi_epilogue(const PhiArgs& a, long long pt, int b, int j
   }
 }
 
-template <class C>
+template <class C, int MODE>
 __global__ __launch_bounds__(C::NT) void phi_step_kernel(PhiArgs a) {
   __shared__ __attribute__((aligned(16))) float lds[C::LDS_FLOATS];
   const int H = a.H, B = a.B;
@@ -202,11 +203,11 @@ __global__ __launch_bounds__(C::NT) void phi_step_kernel(PhiArgs a) {
         if (r >= R) continue;
         const long long pt = r / B;
         const int b = (int)(r - pt * B);
-        phi_epilogue(a, pt, b, j, acc.v[0][ba][bb][e], acc.v[1][ba][bb][e], acc.v[2][ba][bb][e],
+        phi_epilogue<MODE>(a, pt, b, j, acc.v[0][ba][bb][e], acc.v[1][ba][bb][e], acc.v[2][ba][bb][e],
                      nrm);
       }
     }
-  if (a.mode == STEP_RESID && a.norm) {
+  if (MODE == STEP_RESID && a.norm) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) nrm += __shfl_down(nrm, off, 64);
     if ((tid & 63) == 0) atomicAdd(a.norm, nrm);
@@ -216,7 +217,7 @@ __global__ __launch_bounds__(C::NT) void phi_step_kernel(PhiArgs a) {
 // ---------------------------------------------------------------------------
 // Few-row variant (coarsest-level propagation, serial scan): see skinny.h
 // ---------------------------------------------------------------------------
-template <int CT>
+template <int CT, int MODE>
 __global__ __launch_bounds__(SK_NT) void phi_skinny_kernel(PhiArgs a) {
   constexpr int NU = 3 * CT;
   __shared__ float red[SK_NT * NU];
@@ -258,12 +259,12 @@ __global__ __launch_bounds__(SK_NT) void phi_skinny_kernel(PhiArgs a) {
       const int r = r0 + bl2;
       const long long pt = r / B;
       const int b = r - (int)pt * B;
-      phi_epilogue(a, pt, b, j, skinny_sum<NU>(red, bl2, c, ksl),
+      phi_epilogue<MODE>(a, pt, b, j, skinny_sum<NU>(red, bl2, c, ksl),
                    skinny_sum<NU>(red, bl2, CT + c, ksl), skinny_sum<NU>(red, bl2, 2 * CT + c, ksl),
                    nrm);
     }
   }
-  if (a.mode == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
+  if (MODE == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
 }
 
 typedef TileCfg<2, 2, 2, 1, 3> PhiBig;    // 128 rows x 64 hidden columns (x3 gates), 256 threads
@@ -274,7 +275,36 @@ template <class C>
 static void launch_phi_cfg(const PhiArgs& a, hipStream_t s) {
   const long long R = (long long)a.nk * a.B;
   dim3 grid((unsigned)xcd_grid((R + C::TM - 1) / C::TM, (a.H + C::TN - 1) / C::TN));
-  hipLaunchKernelGGL(phi_step_kernel<C>, grid, dim3(C::NT), 0, s, a);
+  switch (a.mode) {
+    case STEP_RELAX:
+      hipLaunchKernelGGL((phi_step_kernel<C, STEP_RELAX>), grid, dim3(C::NT), 0, s, a);
+      break;
+    case STEP_RESID:
+      hipLaunchKernelGGL((phi_step_kernel<C, STEP_RESID>), grid, dim3(C::NT), 0, s, a);
+      break;
+    case STEP_RHS:
+      hipLaunchKernelGGL((phi_step_kernel<C, STEP_RHS>), grid, dim3(C::NT), 0, s, a);
+      break;
+    default:
+      hipLaunchKernelGGL((phi_step_kernel<C, STEP_KAPPA>), grid, dim3(C::NT), 0, s, a);
+  }
+}
+
+template <int CT>
+static void launch_phi_skinny(const PhiArgs& a, dim3 grid, hipStream_t s) {
+  switch (a.mode) {
+    case STEP_RELAX:
+      hipLaunchKernelGGL((phi_skinny_kernel<CT, STEP_RELAX>), grid, dim3(SK_NT), 0, s, a);
+      break;
+    case STEP_RESID:
+      hipLaunchKernelGGL((phi_skinny_kernel<CT, STEP_RESID>), grid, dim3(SK_NT), 0, s, a);
+      break;
+    case STEP_RHS:
+      hipLaunchKernelGGL((phi_skinny_kernel<CT, STEP_RHS>), grid, dim3(SK_NT), 0, s, a);
+      break;
+    default:
+      hipLaunchKernelGGL((phi_skinny_kernel<CT, STEP_KAPPA>), grid, dim3(SK_NT), 0, s, a);
+  }
 }
 
 hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s) {
@@ -287,11 +317,11 @@ hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s) {
     const int ct = a.H >= 1024 ? 4 : (a.H >= 512 ? 2 : 1);
     dim3 grid((unsigned)((a.H + ct - 1) / ct), (unsigned)((R + SK_MAXROWS - 1) / SK_MAXROWS));
     if (ct == 4)
-      hipLaunchKernelGGL(phi_skinny_kernel<4>, grid, dim3(SK_NT), 0, s, a);
+      launch_phi_skinny<4>(a, grid, s);
     else if (ct == 2)
-      hipLaunchKernelGGL(phi_skinny_kernel<2>, grid, dim3(SK_NT), 0, s, a);
+      launch_phi_skinny<2>(a, grid, s);
     else
-      hipLaunchKernelGGL(phi_skinny_kernel<1>, grid, dim3(SK_NT), 0, s, a);
+      launch_phi_skinny<1>(a, grid, s);
   } else if (tiles(PhiBig::TM, PhiBig::TN) >= 512)
     launch_phi_cfg<PhiBig>(a, s);
   else if (R > 32 && tiles(PhiMid::TM, PhiMid::TN) >= 256)

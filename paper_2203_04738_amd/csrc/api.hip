@@ -165,10 +165,14 @@ static PhiArgs phi_base(const FwdCtx& x, int l) {
 // advances every interval from point i*cf+j-1 to i*cf+j.  All intervals move in one
 // launch, so the C-sweep reads only values written by earlier launches (Jacobi in
 // the coarse points).
-static int relax_fwd(const FwdCtx& x, int l, bool include_c) {
+static int relax_fwd(const FwdCtx& x, int l, bool include_c, bool f_points_current = false) {
   const long long cf = x.c->cf, S = x.lay->S[l];
   const int nint = (int)(x.lay->N[l] / cf);
-  for (long long j = 1; j < cf + (include_c ? 1 : 0); ++j) {
+  // f_points_current: the F-points already equal the propagation of their coarse
+  // points (they were written by the closing F-relaxation of the previous cycle of
+  // this call and nothing changed since), so recomputing them would reproduce the
+  // same bits; only the C-sweep remains.
+  for (long long j = f_points_current ? cf : 1; j < cf + (include_c ? 1 : 0); ++j) {
     PhiArgs a = phi_base(x, l);
     a.mode = STEP_RELAX;
     a.nk = nint;
@@ -184,7 +188,7 @@ static int relax_fwd(const FwdCtx& x, int l, bool include_c) {
   return MGRIT_OK;
 }
 
-static int vcycle_fwd(const FwdCtx& x, int l) {
+static int vcycle_fwd(const FwdCtx& x, int l, bool f_points_current = false) {
   const long long cf = x.c->cf, S = x.lay->S[l], N = x.lay->N[l];
   const int L = x.lay->L;
   if (l == L - 1) {
@@ -202,10 +206,11 @@ static int vcycle_fwd(const FwdCtx& x, int l) {
   }
   int rc;
   // Alg. 2 line 1
+  const bool cur = l == 0 && f_points_current;
   if (l == 0 && x.c->fine_relax == 0) {
-    if ((rc = relax_fwd(x, l, false))) return rc;
+    if ((rc = relax_fwd(x, l, false, cur))) return rc;
   } else {
-    if ((rc = relax_fwd(x, l, true))) return rc;
+    if ((rc = relax_fwd(x, l, true, cur))) return rc;
     if ((rc = relax_fwd(x, l, false))) return rc;
   }
   const int Nc = (int)(N / cf);
@@ -294,7 +299,7 @@ static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, co
   if (resnorm && c.iters > 0) CHECK_HIP(launch_fill_f64(norm, c.iters, 0.0, s));
   for (int it = 0; it < c.iters; ++it) {
     ctx.norm = resnorm ? norm + it : nullptr;
-    if ((rc = vcycle_fwd(ctx, 0))) return rc;
+    if ((rc = vcycle_fwd(ctx, 0, it > 0))) return rc;
   }
   if (resnorm && !serial) CHECK_HIP(launch_sqrt_to_float(norm, resnorm, c.iters, s));
   return MGRIT_OK;
@@ -332,10 +337,10 @@ static AdjArgs adj_base(const BwdCtx& x, int l) {
 // Relaxation of the reversed recurrence: interval i hangs below coarse point
 // (i+1)*cf; sub-step j moves from point (i+1)cf-j+1 to (i+1)cf-j with the
 // coefficients of level step (i+1)cf-j+1.
-static int relax_bwd(const BwdCtx& x, int l, bool include_c) {
+static int relax_bwd(const BwdCtx& x, int l, bool include_c, bool f_points_current = false) {
   const long long cf = x.c->cf;
   const int nint = (int)(x.lay->N[l] / cf);
-  for (long long j = 1; j < cf + (include_c ? 1 : 0); ++j) {
+  for (long long j = f_points_current ? cf : 1; j < cf + (include_c ? 1 : 0); ++j) {
     AdjArgs a = adj_base(x, l);
     a.mode = STEP_RELAX;
     a.nk = nint;
@@ -351,7 +356,7 @@ static int relax_bwd(const BwdCtx& x, int l, bool include_c) {
   return MGRIT_OK;
 }
 
-static int vcycle_bwd(const BwdCtx& x, int l) {
+static int vcycle_bwd(const BwdCtx& x, int l, bool f_points_current = false) {
   const long long cf = x.c->cf, N = x.lay->N[l];
   const int L = x.lay->L;
   if (l == L - 1) {
@@ -367,10 +372,11 @@ static int vcycle_bwd(const BwdCtx& x, int l) {
     return MGRIT_OK;
   }
   int rc;
+  const bool cur = l == 0 && f_points_current;
   if (l == 0 && x.c->fine_relax == 0) {
-    if ((rc = relax_bwd(x, l, false))) return rc;
+    if ((rc = relax_bwd(x, l, false, cur))) return rc;
   } else {
-    if ((rc = relax_bwd(x, l, true))) return rc;
+    if ((rc = relax_bwd(x, l, true, cur))) return rc;
     if ((rc = relax_bwd(x, l, false))) return rc;
   }
   const int Nc = (int)(N / cf);
@@ -474,7 +480,7 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
   if (resnorm && c.iters > 0) CHECK_HIP(launch_fill_f64(norm, c.iters, 0.0, s));
   for (int it = 0; it < c.iters; ++it) {
     ctx.norm = resnorm ? norm + it : nullptr;
-    if ((rc = vcycle_bwd(ctx, 0))) return rc;
+    if ((rc = vcycle_bwd(ctx, 0, it > 0))) return rc;
   }
   if (resnorm && !serial) CHECK_HIP(launch_sqrt_to_float(norm, resnorm, c.iters, s));
   if (ngrad == 4)

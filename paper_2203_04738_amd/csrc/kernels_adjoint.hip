@@ -12,28 +12,49 @@ namespace mg {
 // ---------------------------------------------------------------------------
 // Adjoint level step: out[R,H] = (kap[:, 0:3H] * (w,w,w))[R,3H] . UT[H,3H]^T + k_d*w
 // ---------------------------------------------------------------------------
+// Operands of one output element that do not depend on the contraction.
+struct AdjEpiIn {
+  float kd, wv, gval, cur;
+};
+
+template <int MODE>
+__device__ inline AdjEpiIn adj_epi_load(const AdjArgs& a, long long pt, int b, int j) {
+  const int H = a.H, B = a.B;
+  AdjEpiIn e;
+  e.kd = a.kap[(a.k.at(pt) * B + b) * (long long)a.kw + 3 * H + j];
+  e.wv = a.w_in[(a.in.at(pt) * B + b) * H + j];
+  const long long oi = (a.o.at(pt) * B + b) * H + j;
+  e.gval = a.g ? a.g[oi] : 0.f;
+  e.cur = (MODE == STEP_RESID || MODE == STEP_RHS) ? a.w[oi] : 0.f;
+  return e;
+}
+
 // Output of one element of the adjoint step: row (point pt, batch b), column j, given
 // the contraction  sum_g (U_g^T (k_g * w))_j.
 template <int MODE>
-__device__ inline void adj_epilogue(const AdjArgs& a, long long pt, int b, int j, float dot,
-                                    double& nrm) {
+__device__ inline void adj_epi_finish(const AdjArgs& a, long long pt, int b, int j, float dot,
+                                      const AdjEpiIn& e, double& nrm) {
   const int H = a.H, B = a.B;
-  const float kd = a.kap[(a.k.at(pt) * B + b) * (long long)a.kw + 3 * H + j];
-  const float wv = a.w_in[(a.in.at(pt) * B + b) * H + j];
-  const float wn = kd * wv + dot;
+  const float wn = e.kd * e.wv + dot;
   const long long oi = (a.o.at(pt) * B + b) * H + j;
   if (MODE == STEP_RELAX) {
-    a.w[oi] = a.g ? wn + a.g[oi] : wn;
+    a.w[oi] = wn + e.gval;
   } else if (MODE == STEP_RESID) {
-    const float cur = a.w[oi];
-    const float res = a.g ? cur - wn - a.g[oi] : cur - wn;
+    const float res = e.cur - wn - e.gval;
     const long long ai = (a.a.at(pt) * B + b) * H + j;
     a.gc[ai] = -res;
-    a.wc[ai] = cur;
+    a.wc[ai] = e.cur;
     nrm += (double)res * (double)res;
   } else {  // STEP_RHS
-    a.g[oi] = (a.w[oi] - wn) + a.g[oi];
+    a.g[oi] = (e.cur - wn) + e.gval;
   }
+}
+
+template <int MODE>
+__device__ inline void adj_epilogue(const AdjArgs& a, long long pt, int b, int j, float dot,
+                                    double& nrm) {
+  const AdjEpiIn e = adj_epi_load<MODE>(a, pt, b, j);
+  adj_epi_finish<MODE>(a, pt, b, j, dot, e, nrm);
 }
 
 struct KapW {
@@ -126,6 +147,18 @@ __global__ __launch_bounds__(SK_NT) void adj_skinny_kernel(AdjArgs a) {
   const int j0 = blockIdx.x * CT;
   const bool live = bl < rows_here;
 
+  const bool epi = tid < rows_here * CT && j0 + tid % CT < H;
+  long long e_pt = 0;
+  int e_b = 0, e_j = 0;
+  AdjEpiIn ein = {};
+  if (epi) {
+    const int r = r0 + tid / CT;
+    e_pt = r / B;
+    e_b = r - (int)e_pt * B;
+    e_j = j0 + tid % CT;
+    ein = adj_epi_load<MODE>(a, e_pt, e_b, e_j);
+  }
+
   const float* krow = nullptr;
   const float* wrow = nullptr;
   if (live) {
@@ -148,16 +181,8 @@ __global__ __launch_bounds__(SK_NT) void adj_skinny_kernel(AdjArgs a) {
   __syncthreads();
 
   double nrm = 0.0;
-  if (tid < rows_here * CT) {
-    const int bl2 = tid / CT, c = tid % CT;
-    const int j = j0 + c;
-    if (j < H) {
-      const int r = r0 + bl2;
-      const long long pt = r / B;
-      const int b = r - (int)pt * B;
-      adj_epilogue<MODE>(a, pt, b, j, skinny_sum<CT>(red, bl2, c, ksl), nrm);
-    }
-  }
+  if (epi)
+    adj_epi_finish<MODE>(a, e_pt, e_b, e_j, skinny_sum<CT>(red, tid / CT, tid % CT, ksl), ein, nrm);
   if (MODE == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
 }
 

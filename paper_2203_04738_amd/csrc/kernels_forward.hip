@@ -93,37 +93,60 @@ __device__ inline float tanhf_(float a) {
   return copysignf(t, a);
 }
 
+// Operands of one output element that do not depend on the contraction: they are
+// loaded separately so that the few-row kernel can fetch them before its dot
+// products instead of after.
+struct PhiEpiIn {
+  float pr, pz, pn, h, bhr, bhz, bhn, gval, cur;
+};
+
+template <int MODE>
+__device__ inline PhiEpiIn phi_epi_load(const PhiArgs& a, long long pt, int b, int j) {
+  const int H = a.H, B = a.B;
+  PhiEpiIn e;
+  const float* pp = a.P + (a.p.at(pt) * B + b) * (3LL * H);
+  e.pr = pp[j];
+  e.pz = pp[H + j];
+  e.pn = pp[2 * H + j];
+  e.h = a.u_in[(a.in.at(pt) * B + b) * H + j];
+  e.bhr = a.b_h[j];
+  e.bhz = a.b_h[H + j];
+  e.bhn = a.b_h[2 * H + j];
+  const long long oi = (a.o.at(pt) * B + b) * H + j;
+  e.gval = (MODE != STEP_KAPPA && a.g) ? a.g[oi] : 0.f;
+  e.cur = (MODE == STEP_RESID || MODE == STEP_RHS) ? a.u[oi] : 0.f;
+  return e;
+}
+
 // Gates of Eq. 1, the update of Eq. 16 / Eq. 3 and the mode-specific output for one
 // element: row (point pt, batch b), hidden column j, given the three recurrent
 // contractions (U_r h)_j, (U_z h)_j, (U_n h)_j.
 template <int MODE>
-__device__ inline void phi_epilogue(const PhiArgs& a, long long pt, int b, int j, float sr,
-                                    float sz, float sn, double& nrm) {
+__device__ inline void phi_epi_finish(const PhiArgs& a, long long pt, int b, int j, float sr,
+                                      float sz, float sn, const PhiEpiIn& e, double& nrm) {
   const int H = a.H, B = a.B;
   const float gamma = a.gamma;
   const bool implicit = a.propagator == MGRIT_PROP_IMPLICIT;
-  const float* pp = a.P + (a.p.at(pt) * B + b) * (3LL * H);
-  const float h = a.u_in[(a.in.at(pt) * B + b) * H + j];
-  const float rg = sigmoidf_(pp[j] + sr + a.b_h[j]);
-  const float zg = sigmoidf_(pp[H + j] + sz + a.b_h[H + j]);
-  const float q = sn + a.b_h[2 * H + j];
-  const float n = tanhf_(pp[2 * H + j] + rg * q);
+  const float h = e.h;
+  const float rg = sigmoidf_(e.pr + sr + e.bhr);
+  const float zg = sigmoidf_(e.pz + sz + e.bhz);
+  const float q = sn + e.bhn;
+  const float n = tanhf_(e.pn + rg * q);
   const float c = 1.0f - zg;
   const float d = 1.0f + gamma * c;
   const float rd = fast_rcp(d);
   const float hn = implicit ? (h + gamma * c * n) * rd : h + gamma * c * (n - h);
   const long long oi = (a.o.at(pt) * B + b) * H + j;
   if (MODE == STEP_RELAX) {
-    a.u[oi] = a.g ? hn + a.g[oi] : hn;
+    a.u[oi] = hn + e.gval;
   } else if (MODE == STEP_RESID) {
-    const float cur = a.u[oi];
-    const float res = a.g ? cur - hn - a.g[oi] : cur - hn;
+    const float res = e.cur - hn - e.gval;
     const long long ai = (a.a.at(pt) * B + b) * H + j;
     a.gc[ai] = -res;
-    a.uc[ai] = cur;
+    a.uc[ai] = e.cur;
     nrm += (double)res * (double)res;
   } else if (MODE == STEP_RHS) {
-    a.g[oi] = (a.u[oi] - hn) + a.g[oi];
+    a.g[oi] = (e.cur - hn) + e.gval;
   } else {  // STEP_KAPPA: coefficients of the transposed Jacobian of this step
     float kd, dn, dz;
     if (implicit) {
@@ -143,6 +166,13 @@ __device__ inline void phi_epilogue(const PhiArgs& a, long long pt, int b, int j
     kp[3 * H + j] = kd;
     if (a.kappa_width >= 5 * H) kp[4 * H + j] = kn;
   }
+}
+
+template <int MODE>
+__device__ inline void phi_epilogue(const PhiArgs& a, long long pt, int b, int j, float sr,
+                                    float sz, float sn, double& nrm) {
+  const PhiEpiIn e = phi_epi_load<MODE>(a, pt, b, j);
+  phi_epi_finish<MODE>(a, pt, b, j, sr, sz, sn, e, nrm);
 }
 
 template <class C, int MODE>
@@ -232,6 +262,20 @@ __global__ __launch_bounds__(SK_NT) void phi_skinny_kernel(PhiArgs a) {
   const int j0 = blockIdx.x * CT;
   const bool live = bl < rows_here;
 
+  // this thread's output element (if any): its operands are requested first so
+  // that their latency overlaps the dot products
+  const bool epi = tid < rows_here * CT && j0 + tid % CT < H;
+  long long e_pt = 0;
+  int e_b = 0, e_j = 0;
+  PhiEpiIn ein = {};
+  if (epi) {
+    const int r = r0 + tid / CT;
+    e_pt = r / B;
+    e_b = r - (int)e_pt * B;
+    e_j = j0 + tid % CT;
+    ein = phi_epi_load<MODE>(a, e_pt, e_b, e_j);
+  }
+
   const float* hrow = nullptr;
   if (live) {
     const int r = r0 + bl;
@@ -252,17 +296,11 @@ __global__ __launch_bounds__(SK_NT) void phi_skinny_kernel(PhiArgs a) {
   __syncthreads();
 
   double nrm = 0.0;
-  if (tid < rows_here * CT) {
+  if (epi) {
     const int bl2 = tid / CT, c = tid % CT;
-    const int j = j0 + c;
-    if (j < H) {
-      const int r = r0 + bl2;
-      const long long pt = r / B;
-      const int b = r - (int)pt * B;
-      phi_epilogue<MODE>(a, pt, b, j, skinny_sum<NU>(red, bl2, c, ksl),
-                   skinny_sum<NU>(red, bl2, CT + c, ksl), skinny_sum<NU>(red, bl2, 2 * CT + c, ksl),
-                   nrm);
-    }
+    phi_epi_finish<MODE>(a, e_pt, e_b, e_j, skinny_sum<NU>(red, bl2, c, ksl),
+                         skinny_sum<NU>(red, bl2, CT + c, ksl),
+                         skinny_sum<NU>(red, bl2, 2 * CT + c, ksl), ein, nrm);
   }
   if (MODE == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
 }

@@ -29,7 +29,7 @@ __device__ inline void skinny_partial(float (&acc)[NU], int K, int ks, int ksl, 
                                       const float* const (&urow)[NU], GetA getA) {
   // several independent slices are fetched before any is consumed, so that the
   // loop pays one memory round trip per UNR slices
-  constexpr int UNR = NU > 4 ? 2 : 4;
+  constexpr int UNR = NU >= 12 ? 1 : (NU >= 5 ? 2 : 4);
 #pragma unroll
   for (int u = 0; u < NU; ++u) acc[u] = 0.f;
   if (!live) return;

@@ -84,7 +84,6 @@ static int check_cfg(const mgrit_gru_cfg* c, bool need_hierarchy) {
   }
   const int mult = c->dtype == MGRIT_BF16 ? 8 : 4;
   if (c->H % mult != 0 || c->D % mult != 0) return MGRIT_E_ALIGN;
-  if (c->dtype == MGRIT_BF16) return MGRIT_E_UNSUPPORTED;
   return MGRIT_OK;
 }
 
@@ -137,7 +136,8 @@ static bool misaligned(const void* p) { return ((uintptr_t)p & 15) != 0; }
 struct FwdCtx {
   const mgrit_gru_cfg* c;
   const Layout* lay;
-  const float *U, *b_h, *P;
+  const void* U;
+  const float *b_h, *P;
   float* ul[MAX_LEVELS];
   float* gl[MAX_LEVELS];
   float* tmp;
@@ -158,6 +158,7 @@ static PhiArgs phi_base(const FwdCtx& x, int l) {
   a.H = x.c->H;
   a.gamma = (float)x.lay->S[l];
   a.propagator = x.c->propagator;
+  a.bf16 = x.c->dtype == MGRIT_BF16;
   return a;
 }
 
@@ -249,8 +250,8 @@ static int vcycle_fwd(const FwdCtx& x, int l, bool f_points_current = false) {
 static int run_projection(const mgrit_gru_cfg* c, const void* W, const float* b_i, const void* x,
                           float* P, hipStream_t s) {
   if (c->flags & MGRIT_REUSE_PROJECTION) return MGRIT_OK;
-  CHECK_HIP(launch_projection((const float*)x, (const float*)W, b_i, P, (long long)c->T * c->B,
-                              3 * c->H, c->D, s));
+  CHECK_HIP(launch_projection(x, W, b_i, P, (long long)c->T * c->B, 3 * c->H, c->D,
+                              c->dtype == MGRIT_BF16, s));
   return MGRIT_OK;
 }
 
@@ -279,7 +280,7 @@ static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, co
   FwdCtx ctx;
   ctx.c = &c;
   ctx.lay = &lay;
-  ctx.U = (const float*)U;
+  ctx.U = U;
   ctx.b_h = b_h;
   ctx.P = (const float*)(base + lay.P);
   ctx.s = s;
@@ -311,7 +312,7 @@ static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, co
 struct BwdCtx {
   const mgrit_gru_cfg* c;
   const Layout* lay;
-  const float* UT;
+  const void* UT;
   const float* kap[MAX_LEVELS];
   float* wl[MAX_LEVELS];
   float* gl[MAX_LEVELS];
@@ -331,6 +332,7 @@ static AdjArgs adj_base(const BwdCtx& x, int l) {
   a.g = x.gl[l];
   a.B = x.c->B;
   a.H = x.c->H;
+  a.bf16 = x.c->dtype == MGRIT_BF16;
   return a;
 }
 
@@ -437,12 +439,13 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
   const long long BH = (long long)c.B * c.H;
 
   if ((rc = run_projection(&c, W, b_i, x, (float*)(base + lay.P), s))) return rc;
-  CHECK_HIP(launch_transpose((const float*)U, (float*)(base + lay.UT), 3 * c.H, c.H, s));
+  const int bf16 = c.dtype == MGRIT_BF16;
+  CHECK_HIP(launch_transpose(U, base + lay.UT, 3 * c.H, c.H, bf16, s));
 
   BwdCtx ctx;
   ctx.c = &c;
   ctx.lay = &lay;
-  ctx.UT = (const float*)(base + lay.UT);
+  ctx.UT = base + lay.UT;
   ctx.s = s;
   ctx.tmp = (float*)(base + lay.tmp);
   ctx.wl[0] = w;
@@ -457,7 +460,8 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
     // forward state of level point k-1 (fine point (k-1)*S) and input x_{k*S}
     PhiArgs a;
     std::memset(&a, 0, sizeof(a));
-    a.U = (const float*)U;
+    a.U = U;
+    a.bf16 = bf16;
     a.b_h = b_h;
     a.P = P;
     a.u_in = h;
@@ -484,8 +488,8 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
   }
   if (resnorm && !serial) CHECK_HIP(launch_sqrt_to_float(norm, resnorm, c.iters, s));
   if (ngrad == 4)
-    CHECK_HIP(launch_param_grads(ctx.kap[0], w, h, (const float*)x, dW, dU, db_i, db_h,
-                                 (float*)(base + lay.part), c.T, c.B, c.D, c.H, s));
+    CHECK_HIP(launch_param_grads(ctx.kap[0], w, h, x, dW, dU, db_i, db_h,
+                                 (float*)(base + lay.part), c.T, c.B, c.D, c.H, bf16, s));
   return MGRIT_OK;
 }
 

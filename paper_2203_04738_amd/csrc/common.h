@@ -24,7 +24,7 @@ enum StepMode {
 
 // One launch of the fused forward step  Phi_gamma(x, h) over nk level points.
 struct PhiArgs {
-  const float* U;      // [3H,H]
+  const void* U;       // [3H,H], float or bf16 (see bf16)
   const float* b_h;    // [3H]
   const float* P;      // [T,B,3H] input projection
   const float* u_in;   // state array the step reads from
@@ -39,11 +39,12 @@ struct PhiArgs {
   float gamma;
   int propagator;
   int mode;
+  int bf16;            // 1: U is bf16 and the contraction runs on the bf16 MFMA path
 };
 
 // One launch of the fused adjoint step  w_out = (dPhi/dh)^T w_in  over nk points.
 struct AdjArgs {
-  const float* UT;     // [H,3H] transposed recurrent weights
+  const void* UT;      // [H,3H] transposed recurrent weights, float or bf16
   const float* kap;    // coefficient array of this level, [*,B,kw]: k_r,k_z,k_q,k_d(,k_n)
   const float* w_in;   // adjoint array the step reads from
   float* w;            // level adjoint array (out / cur)
@@ -54,24 +55,27 @@ struct AdjArgs {
   Idx in, k, o, a;     // point indices: input adjoint, coefficient row, out/cur/g, coarse
   int nk, B, H, kw;
   int mode;
+  int bf16;
 };
 
 hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s);
 hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s);
 
 // P[M,N] = X[M,K] W[N,K]^T + bias[N]
-hipError_t launch_projection(const float* X, const float* W, const float* bias, float* P,
-                             long long M, int N, int K, hipStream_t s);
-// UT[H,3H] = U[3H,H]^T
-hipError_t launch_transpose(const float* U, float* UT, int rows, int cols, hipStream_t s);
+// X, W: float (bf16 = 0) or bf16 (bf16 = 1)
+hipError_t launch_projection(const void* X, const void* W, const float* bias, float* P,
+                             long long M, int N, int K, int bf16, hipStream_t s);
+// UT[H,3H] = U[3H,H]^T; elements are 4 bytes (bf16 = 0) or 2 bytes
+hipError_t launch_transpose(const void* U, void* UT, int rows, int cols, int bf16, hipStream_t s);
 
 // Weight gradients (Alg. 3 gradient line) from the level-0 coefficients kap0[(T+1),B,5H]
 // (row t = step t), the adjoint w[(T+1),B,H], the states h[(T+1),B,H] and x[T,B,D].
 // part: scratch of grad_partial_floats(...) floats.
 size_t grad_partial_floats(int T, int B, int D, int H);
-hipError_t launch_param_grads(const float* kap0, const float* w, const float* h, const float* x,
+// x: float (bf16 = 0) or bf16 (bf16 = 1)
+hipError_t launch_param_grads(const float* kap0, const float* w, const float* h, const void* x,
                               float* dW, float* dU, float* db_i, float* db_h, float* part,
-                              int T, int B, int D, int H, hipStream_t s);
+                              int T, int B, int D, int H, int bf16, hipStream_t s);
 
 hipError_t launch_fill_f64(double* p, long long n, double v, hipStream_t s);
 // dst[(d.off + i*d.str), :, :] = src[(s.off + i*s.str), :, :] for i < nk; blocks of `block` floats

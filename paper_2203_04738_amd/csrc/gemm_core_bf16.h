@@ -1,0 +1,194 @@
+// Workgroup-tile bf16 MFMA contraction core for gfx950 (CDNA4): the same "NT"
+// tile product as gemm_core.h, consumed by v_mfma_f32_32x32x16_bf16 with fp32
+// accumulation, for the variant whose inputs and weights are stored in bf16.
+//
+// Operand B (weights) is bf16 in memory.  Operand A is either bf16 in memory
+// (the input sequence x) or fp32 (hidden states, adjoint values): an fp32 operand
+// is written to LDS as TWO bf16 tiles, hi = bf16(a) and lo = bf16(a - hi), and
+// each block gets two MFMAs, hi*B + lo*B.  That keeps 16 mantissa bits of the
+// fp32 state in the product, so the only rounding the method sees beyond fp32 is
+// the one already present in the stored bf16 weights.
+//
+// A lane supplies eight consecutive k of its row (one ds_read_b128) per MFMA, the
+// two half-waves taking k-offsets 0..7 and 8..15 of each group of sixteen; A and B
+// use the same assignment, so the contraction is independent of how the
+// instruction numbers k inside a lane.
+#pragma once
+#include "gemm_core.h"
+
+namespace mg {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned short bf16_t;     // storage type of bf16 arrays at the ABI
+
+struct F32x8 {
+  floatx4 lo4, hi4;                // columns k..k+3 and k+4..k+7
+};
+
+__device__ inline bf16x8 ldg8h(const bf16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
+
+__device__ inline void split_bf16(const F32x8& v, bf16x8& hi, bf16x8& lo) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    hi[i] = (__bf16)v.lo4[i];
+    hi[4 + i] = (__bf16)v.hi4[i];
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    lo[i] = (__bf16)(v.lo4[i] - (float)hi[i]);
+    lo[4 + i] = (__bf16)(v.hi4[i] - (float)hi[4 + i]);
+  }
+}
+
+template <int WM_, int WN_, int BM_, int BN_, int NG_, bool SPLIT_A_>
+struct TileCfgB {
+  static constexpr int WM = WM_, WN = WN_, BM = BM_, BN = BN_, NG = NG_;
+  static constexpr bool SPLIT_A = SPLIT_A_;
+  static constexpr int TK = 64;                 // bf16 elements per K-slice
+  static constexpr int NA = SPLIT_A ? 2 : 1;    // A tiles in LDS
+  static constexpr int NWAVES = WM * WN;
+  static constexpr int NT = NWAVES * 64;
+  static constexpr int TM = WM * BM * 32;
+  static constexpr int TN = WN * BN * 32;
+  static constexpr int BROWS = NG * TN;
+  static constexpr int LD = TK + 8;             // LDS row stride in elements (144 bytes)
+  static constexpr int CPR = TK / 8;            // 16-byte chunks per tile row
+  static constexpr int A_CHUNKS = (TM * CPR) / NT;
+  static constexpr int B_CHUNKS = (BROWS * CPR) / NT;
+  static constexpr int LDS_ELEMS = (NA * TM + BROWS) * LD;
+  static_assert((TM * CPR) % NT == 0 && (BROWS * CPR) % NT == 0, "tile rows must divide evenly");
+};
+
+template <class C>
+__device__ inline int chunk_row_b(int s) { return (threadIdx.x + s * C::NT) / C::CPR; }
+
+// One pass over K (elements; a multiple of 8).
+//   loadA(s, k): raw global load(s) for columns k..k+7 of the tile row of chunk s;
+//   finA(raw): -> bf16x8 (SPLIT_A false) or F32x8 (SPLIT_A true), applied when the
+//              slice is written to LDS;
+//   loadB(s, k): -> bf16x8.
+template <class C, bool KTAIL, class LoadA, class LoadB, class FinA>
+__device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB loadB, FinA finA,
+                                         bf16_t* lds) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wm = wave / C::WN;
+  const int wn = wave % C::WN;
+  const int li = lane & 31;
+  const int lh = lane >> 5;
+  constexpr int NC = C::TK / 16;
+  constexpr int NB = C::NG * C::BN;
+  constexpr int NFA = C::NA * C::BM;
+
+  decltype(loadA(0, 0)) ra[C::A_CHUNKS];
+  bf16x8 rb[C::B_CHUNKS];
+
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int s = 0; s < C::A_CHUNKS; ++s) {
+      int k = k0 + ((tid + s * C::NT) % C::CPR) * 8;
+      if (KTAIL && k >= K) k = K - 8;
+      ra[s] = loadA(s, k);
+    }
+#pragma unroll
+    for (int s = 0; s < C::B_CHUNKS; ++s) {
+      int k = k0 + ((tid + s * C::NT) % C::CPR) * 8;
+      if (KTAIL && k >= K) k = K - 8;
+      rb[s] = loadB(s, k);
+    }
+  };
+  bf16_t* As = lds;                               // hi (or only) A tile, then lo tile
+  bf16_t* Bs = lds + C::NA * C::TM * C::LD;
+  auto stash = [&](int k0) {
+    bf16x8 z;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) z[i] = (__bf16)0.f;
+#pragma unroll
+    for (int s = 0; s < C::A_CHUNKS; ++s) {
+      const int q = tid + s * C::NT;
+      const int off = (q / C::CPR) * C::LD + (q % C::CPR) * 8;
+      const bool dead = KTAIL && k0 + (q % C::CPR) * 8 >= K;
+      if constexpr (C::SPLIT_A) {
+        bf16x8 hi, lo;
+        split_bf16(finA(ra[s]), hi, lo);
+        *reinterpret_cast<bf16x8*>(&As[off]) = dead ? z : hi;
+        *reinterpret_cast<bf16x8*>(&As[C::TM * C::LD + off]) = dead ? z : lo;
+      } else {
+        *reinterpret_cast<bf16x8*>(&As[off]) = dead ? z : finA(ra[s]);
+      }
+    }
+#pragma unroll
+    for (int s = 0; s < C::B_CHUNKS; ++s) {
+      const int q = tid + s * C::NT;
+      const bool dead = KTAIL && k0 + (q % C::CPR) * 8 >= K;
+      *reinterpret_cast<bf16x8*>(&Bs[(q / C::CPR) * C::LD + (q % C::CPR) * 8]) = dead ? z : rb[s];
+    }
+  };
+  const int a_off = ((wm * C::BM) * 32 + li) * C::LD + lh * 8;
+  const int b_off = ((wn * C::BN) * 32 + li) * C::LD + lh * 8;
+  auto read_frags = [&](int c, bf16x8 (&fa)[NFA], bf16x8 (&fb)[NB]) {
+#pragma unroll
+    for (int t = 0; t < C::NA; ++t)
+#pragma unroll
+      for (int a = 0; a < C::BM; ++a)
+        fa[t * C::BM + a] = *reinterpret_cast<const bf16x8*>(
+            &As[t * C::TM * C::LD + a_off + a * 32 * C::LD + c * 16]);
+#pragma unroll
+    for (int g = 0; g < C::NG; ++g)
+#pragma unroll
+      for (int b = 0; b < C::BN; ++b)
+        fb[g * C::BN + b] = *reinterpret_cast<const bf16x8*>(
+            &Bs[b_off + (g * C::TN + b * 32) * C::LD + c * 16]);
+  };
+  auto mma = [&](const bf16x8 (&fa)[NFA], const bf16x8 (&fb)[NB]) {
+#pragma unroll
+    for (int t = 0; t < C::NA; ++t)
+#pragma unroll
+      for (int g = 0; g < C::NG; ++g)
+#pragma unroll
+        for (int b = 0; b < C::BN; ++b)
+#pragma unroll
+          for (int a = 0; a < C::BM; ++a)
+            acc.v[g][a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                fa[t * C::BM + a], fb[g * C::BN + b], acc.v[g][a][b], 0, 0, 0);
+  };
+
+  const int nkt = (K + C::TK - 1) / C::TK;
+  fetch(0);
+  stash(0);
+  __syncthreads();
+  for (int kt = 0; kt < nkt; ++kt) {
+    const bool more = kt + 1 < nkt;
+    if (more) fetch((kt + 1) * C::TK);
+    __builtin_amdgcn_sched_barrier(0);
+    bf16x8 fa[2][NFA];
+    bf16x8 fb[2][NB];
+    read_frags(0, fa[0], fb[0]);
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+      if (c + 1 < NC) read_frags(c + 1, fa[(c + 1) & 1], fb[(c + 1) & 1]);
+      mma(fa[c & 1], fb[c & 1]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    if (more) {
+      stash((kt + 1) * C::TK);
+      __syncthreads();
+    }
+  }
+}
+
+// Element loads for the vector-FMA kernels: four consecutive weights as floats.
+__device__ inline floatx4 ldg4w(const float* p) { return ldg4(p); }
+__device__ inline floatx4 ldg4w(const bf16_t* p) {
+  const uint2 r = *reinterpret_cast<const uint2*>(p);
+  floatx4 v;
+  v[0] = __uint_as_float(r.x << 16);
+  v[1] = __uint_as_float(r.x & 0xffff0000u);
+  v[2] = __uint_as_float(r.y << 16);
+  v[3] = __uint_as_float(r.y & 0xffff0000u);
+  return v;
+}
+
+}  // namespace mg

@@ -5,6 +5,7 @@
 // the parameter-gradient reductions of Alg. 3's gradient line.
 #include "common.h"
 #include "gemm_core.h"
+#include "gemm_core_bf16.h"
 #include "skinny.h"
 
 namespace mg {
@@ -89,7 +90,7 @@ __global__ __launch_bounds__(C::NT) void adj_step_kernel(AdjArgs a) {
   for (int s = 0; s < C::B_CHUNKS; ++s) {
     int j = n0 + chunk_row<C>(s);
     if (j >= H) j = H - 1;
-    brow[s] = a.UT + (long long)j * K;
+    brow[s] = (const float*)a.UT + (long long)j * K;
   }
   Acc<C> acc;
   acc.zero();
@@ -132,8 +133,84 @@ __global__ __launch_bounds__(C::NT) void adj_step_kernel(AdjArgs a) {
   }
 }
 
+// bf16 weights: the fp32 products kappa*w are split into hi + lo bf16 tiles.
+struct KapW8 {
+  floatx4 k0, k1, w0, w1;
+};
+
+template <class C, int MODE>
+__global__ __launch_bounds__(C::NT) void adj_step_kernel_bf16(AdjArgs a) {
+  __shared__ __attribute__((aligned(16))) bf16_t lds[C::LDS_ELEMS];
+  const int H = a.H, B = a.B, K = 3 * a.H;
+  const long long R = (long long)a.nk * B;
+  long long rt;
+  int ct;
+  if (!xcd_tile(blockIdx.x, (R + C::TM - 1) / C::TM, (H + C::TN - 1) / C::TN, rt, ct)) return;
+  const long long m0 = rt * C::TM;
+  const int n0 = ct * C::TN;
+  const int tid = threadIdx.x;
+  const bf16_t* UT = (const bf16_t*)a.UT;
+
+  const float* krow[C::A_CHUNKS];
+  const float* wrow[C::A_CHUNKS];
+  const bf16_t* brow[C::B_CHUNKS];
+#pragma unroll
+  for (int s = 0; s < C::A_CHUNKS; ++s) {
+    long long r = m0 + chunk_row_b<C>(s);
+    if (r >= R) r = R - 1;
+    const long long pt = r / B;
+    const int b = (int)(r - pt * B);
+    krow[s] = a.kap + (a.k.at(pt) * B + b) * (long long)a.kw;
+    wrow[s] = a.w_in + (a.in.at(pt) * B + b) * H;
+  }
+#pragma unroll
+  for (int s = 0; s < C::B_CHUNKS; ++s) {
+    int j = n0 + chunk_row_b<C>(s);
+    if (j >= H) j = H - 1;
+    brow[s] = UT + (long long)j * K;
+  }
+  Acc<C> acc;
+  acc.zero();
+  auto la = [&](int s, int k) {
+    const int kk = k >= 2 * H ? k - 2 * H : (k >= H ? k - H : k);
+    return KapW8{ldg4(krow[s] + k), ldg4(krow[s] + k + 4), ldg4(wrow[s] + kk),
+                 ldg4(wrow[s] + kk + 4)};
+  };
+  auto lb = [&](int s, int k) { return ldg8h(brow[s] + k); };
+  auto fa = [](const KapW8& r) { return F32x8{r.k0 * r.w0, r.k1 * r.w1}; };
+  if (K % C::TK == 0)
+    gemm_nt_tile_bf16<C, false>(acc, K, la, lb, fa, lds);
+  else
+    gemm_nt_tile_bf16<C, true>(acc, K, la, lb, fa, lds);
+
+  double nrm = 0.0;
+#pragma unroll
+  for (int ba = 0; ba < C::BM; ++ba)
+#pragma unroll
+    for (int bb = 0; bb < C::BN; ++bb) {
+      int row, col;
+      acc_coord<C>(ba, bb, 0, row, col);
+      const int j = n0 + col;
+      if (j >= H) continue;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        acc_coord<C>(ba, bb, e, row, col);
+        const long long r = m0 + row;
+        if (r >= R) continue;
+        const long long pt = r / B;
+        const int b = (int)(r - pt * B);
+        adj_epilogue<MODE>(a, pt, b, j, acc.v[0][ba][bb][e], nrm);
+      }
+    }
+  if (MODE == STEP_RESID && a.norm) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) nrm += __shfl_down(nrm, off, 64);
+    if ((tid & 63) == 0) atomicAdd(a.norm, nrm);
+  }
+}
+
 // Few-row variant (coarsest-level solve, serial BPTT): see skinny.h
-template <int CT, int MODE>
+template <int CT, int MODE, class WT>
 __global__ __launch_bounds__(SK_NT) void adj_skinny_kernel(AdjArgs a) {
   __shared__ float red[SK_NT * CT];
   const int H = a.H, B = a.B, K = 3 * a.H;
@@ -168,11 +245,11 @@ __global__ __launch_bounds__(SK_NT) void adj_skinny_kernel(AdjArgs a) {
     krow = a.kap + (a.k.at(pt) * B + b) * (long long)a.kw;
     wrow = a.w_in + (a.in.at(pt) * B + b) * H;
   }
-  const float* urow[CT];
+  const WT* urow[CT];
 #pragma unroll
-  for (int u = 0; u < CT; ++u) urow[u] = a.UT + (long long)min(j0 + u, H - 1) * K;
+  for (int u = 0; u < CT; ++u) urow[u] = (const WT*)a.UT + (long long)min(j0 + u, H - 1) * K;
   float acc[CT];
-  skinny_partial<CT>(acc, K, ks, ksl, live, urow, [&](int k) {
+  skinny_partial<CT, WT>(acc, K, ks, ksl, live, urow, [&](int k) {
     const int kk = k >= 2 * H ? k - 2 * H : (k >= H ? k - H : k);
     return ldg4(krow + k) * ldg4(wrow + kk);
   });
@@ -189,27 +266,49 @@ __global__ __launch_bounds__(SK_NT) void adj_skinny_kernel(AdjArgs a) {
 typedef TileCfg<2, 2, 2, 2, 1> AdjBig;    // 128 x 128, 256 threads
 typedef TileCfg<2, 1, 1, 1, 1> AdjMid;    //  64 x 32, 128 threads
 typedef TileCfg<1, 1, 1, 1, 1> AdjSmall;  //  32 x 32, 64 threads
+typedef TileCfgB<2, 2, 2, 2, 1, true> AdjBigB;
+typedef TileCfgB<2, 1, 1, 1, 1, true> AdjMidB;
+typedef TileCfgB<1, 1, 1, 1, 1, true> AdjSmallB;
 
-template <class C>
+template <class C, class CB>
 static void launch_adj_cfg(const AdjArgs& a, hipStream_t s) {
   const long long R = (long long)a.nk * a.B;
   dim3 grid((unsigned)xcd_grid((R + C::TM - 1) / C::TM, (a.H + C::TN - 1) / C::TN));
-  if (a.mode == STEP_RELAX)
-    hipLaunchKernelGGL((adj_step_kernel<C, STEP_RELAX>), grid, dim3(C::NT), 0, s, a);
-  else if (a.mode == STEP_RESID)
-    hipLaunchKernelGGL((adj_step_kernel<C, STEP_RESID>), grid, dim3(C::NT), 0, s, a);
+  dim3 block(C::NT);
+  static_assert(C::TM == CB::TM && C::TN == CB::TN && C::NT == CB::NT, "tile shapes must agree");
+  if (a.bf16) {
+    if (a.mode == STEP_RELAX)
+      hipLaunchKernelGGL((adj_step_kernel_bf16<CB, STEP_RELAX>), grid, block, 0, s, a);
+    else if (a.mode == STEP_RESID)
+      hipLaunchKernelGGL((adj_step_kernel_bf16<CB, STEP_RESID>), grid, block, 0, s, a);
+    else
+      hipLaunchKernelGGL((adj_step_kernel_bf16<CB, STEP_RHS>), grid, block, 0, s, a);
+  } else {
+    if (a.mode == STEP_RELAX)
+      hipLaunchKernelGGL((adj_step_kernel<C, STEP_RELAX>), grid, block, 0, s, a);
+    else if (a.mode == STEP_RESID)
+      hipLaunchKernelGGL((adj_step_kernel<C, STEP_RESID>), grid, block, 0, s, a);
+    else
+      hipLaunchKernelGGL((adj_step_kernel<C, STEP_RHS>), grid, block, 0, s, a);
+  }
+}
+
+template <int CT, int MODE>
+static void launch_adj_skinny_mode(const AdjArgs& a, dim3 grid, hipStream_t s) {
+  if (a.bf16)
+    hipLaunchKernelGGL((adj_skinny_kernel<CT, MODE, bf16_t>), grid, dim3(SK_NT), 0, s, a);
   else
-    hipLaunchKernelGGL((adj_step_kernel<C, STEP_RHS>), grid, dim3(C::NT), 0, s, a);
+    hipLaunchKernelGGL((adj_skinny_kernel<CT, MODE, float>), grid, dim3(SK_NT), 0, s, a);
 }
 
 template <int CT>
 static void launch_adj_skinny(const AdjArgs& a, dim3 grid, hipStream_t s) {
   if (a.mode == STEP_RELAX)
-    hipLaunchKernelGGL((adj_skinny_kernel<CT, STEP_RELAX>), grid, dim3(SK_NT), 0, s, a);
+    launch_adj_skinny_mode<CT, STEP_RELAX>(a, grid, s);
   else if (a.mode == STEP_RESID)
-    hipLaunchKernelGGL((adj_skinny_kernel<CT, STEP_RESID>), grid, dim3(SK_NT), 0, s, a);
+    launch_adj_skinny_mode<CT, STEP_RESID>(a, grid, s);
   else
-    hipLaunchKernelGGL((adj_skinny_kernel<CT, STEP_RHS>), grid, dim3(SK_NT), 0, s, a);
+    launch_adj_skinny_mode<CT, STEP_RHS>(a, grid, s);
 }
 
 hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s) {
@@ -228,11 +327,11 @@ hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s) {
     else
       launch_adj_skinny<1>(a, grid, s);
   } else if (tiles(AdjBig::TM, AdjBig::TN) >= 512)
-    launch_adj_cfg<AdjBig>(a, s);
+    launch_adj_cfg<AdjBig, AdjBigB>(a, s);
   else if (R > 32 && tiles(AdjMid::TM, AdjMid::TN) >= 256)
-    launch_adj_cfg<AdjMid>(a, s);
+    launch_adj_cfg<AdjMid, AdjMidB>(a, s);
   else
-    launch_adj_cfg<AdjSmall>(a, s);
+    launch_adj_cfg<AdjSmall, AdjSmallB>(a, s);
   prof_end(kind, 6.0 * (double)R * a.H * a.H, 28.0 * (double)R * a.H, s);
   return hipGetLastError();
 }
@@ -240,14 +339,14 @@ hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s) {
 // ---------------------------------------------------------------------------
 // UT[cols, rows] = U[rows, cols]^T
 // ---------------------------------------------------------------------------
-__global__ void transpose_kernel(const float* __restrict__ U, float* __restrict__ UT, int rows,
-                                 int cols) {
-  __shared__ float t[32][33];
+template <class T>
+__global__ void transpose_kernel(const T* __restrict__ U, T* __restrict__ UT, int rows, int cols) {
+  __shared__ T t[32][33];
   const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
   for (int i = ty; i < 32; i += 8) {
     int r = r0 + i, c = c0 + tx;
-    t[i][tx] = (r < rows && c < cols) ? U[(long long)r * cols + c] : 0.f;
+    t[i][tx] = (r < rows && c < cols) ? U[(long long)r * cols + c] : T(0);
   }
   __syncthreads();
   for (int i = ty; i < 32; i += 8) {
@@ -256,9 +355,14 @@ __global__ void transpose_kernel(const float* __restrict__ U, float* __restrict_
   }
 }
 
-hipError_t launch_transpose(const float* U, float* UT, int rows, int cols, hipStream_t s) {
+hipError_t launch_transpose(const void* U, void* UT, int rows, int cols, int bf16, hipStream_t s) {
   dim3 grid((cols + 31) / 32, (rows + 31) / 32);
-  hipLaunchKernelGGL(transpose_kernel, grid, dim3(256), 0, s, U, UT, rows, cols);
+  if (bf16)
+    hipLaunchKernelGGL(transpose_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)U,
+                       (bf16_t*)UT, rows, cols);
+  else
+    hipLaunchKernelGGL(transpose_kernel<float>, grid, dim3(256), 0, s, (const float*)U,
+                       (float*)UT, rows, cols);
   return hipGetLastError();
 }
 
@@ -269,14 +373,15 @@ hipError_t launch_transpose(const float* U, float* UT, int rows, int cols, hipSt
 // Row k = (t-1)*B + b for step t = 1..T: kap0 and w rows are offset by one time
 // point, Hprev = h[t-1] and X = x[t-1] are not.
 // ---------------------------------------------------------------------------
-constexpr int GTK = 16;            // K-slice (rows of the sum) per iteration
+constexpr int GTK = 32;            // K-slice (rows of the sum) per iteration
 constexpr int GT = 128;            // output tile is GT x GT
-constexpr int GLD = GT + 32;       // LDS row stride in floats
+constexpr int GLD = GT + 32;       // LDS row stride in floats (keeps the two half-waves on
+                                   // different banks)
 
 struct GradArgs {
   const float* kap0;   // [(T+1),B,5H]
   const float* w;      // [(T+1),B,H]
-  const float* Bm;     // h[(T+1),B,H] or x[T,B,D]; row k as is
+  const void* Bm;      // h[(T+1),B,H] (float) or x[T,B,D] (float or bf16); row k as is
   float* part;         // [splits][3H][N]
   long long Ktot;      // T*B
   long long Kper;      // rows per split (multiple of GTK)
@@ -284,6 +389,10 @@ struct GradArgs {
   int third_off;       // 2H (k_q, dU) or 4H (k_n, dW)
 };
 
+// C[m, n] = sum_k S[k, m] Bm[k, n] over this split's rows k.  Both operands are
+// read with the contracted index k slowest, so an LDS slice is stored [k][m] and
+// a lane reads its MFMA operand as one float per k-pair.
+template <class BT>
 __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
   __shared__ __attribute__((aligned(16))) float As[GTK * GLD];
   __shared__ __attribute__((aligned(16))) float Bs[GTK * GLD];
@@ -304,58 +413,68 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  // each thread stages 2 float4 of A and 2 of B per slice: slice row = q/32, col4 = q%32
-  floatx4 ra[2], rb[2];
+  // each thread stages NCH float4 of A and of B per slice: slice row = q/32, col4 = q%32.
+  // The column part is fixed per thread; out-of-range columns and rows are clamped
+  // for the load and zeroed when the slice is written to LDS.
+  constexpr int NCH = GTK * (GT / 4) / 256;
+  const int c4 = tid & 31;
+  const int m = m0 + c4 * 4, n = n0 + c4 * 4;
+  const bool m_ok = m < M, n_ok = n < N;
+  const int mc = m_ok ? m : 0, nc = n_ok ? n : 0;
+  const int gate = mc / H, jcol = mc - gate * H;
+  const int src = gate == 2 ? a.third_off + jcol : mc;
+  floatx4 rk[NCH], rw[NCH], rb[NCH];
   auto fetch = [&](long long k0) {
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      int q = tid + s * 256;
-      int kr = q >> 5, c4 = q & 31;
-      long long k = k0 + kr;
-      int m = m0 + c4 * 4, n = n0 + c4 * 4;
-      if (k < kend && m < M) {
-        int g = m / H, j = m - g * H;
-        int src = g == 2 ? a.third_off + j : m;
-        ra[s] = ldg4(a.kap0 + (k + rowoff) * (5LL * H) + src) * ldg4(a.w + (k + rowoff) * H + j);
-      } else {
-        ra[s] = zero4();
-      }
-      rb[s] = (k < kend && n < N) ? ldg4(a.Bm + k * N + n) : zero4();
+    for (int s = 0; s < NCH; ++s) {
+      long long k = k0 + (tid >> 5) + s * 8;
+      if (k >= kend) k = kend - 1;
+      rk[s] = ldg4(a.kap0 + (k + rowoff) * (5LL * H) + src);
+      rw[s] = ldg4(a.w + (k + rowoff) * H + jcol);
+      rb[s] = ldg4w((const BT*)a.Bm + k * N + nc);
     }
   };
-  auto stash = [&]() {
+  auto stash = [&](long long k0) {
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      int q = tid + s * 256;
-      int kr = q >> 5, c4 = q & 31;
-      *reinterpret_cast<floatx4*>(&As[kr * GLD + c4 * 4]) = ra[s];
-      *reinterpret_cast<floatx4*>(&Bs[kr * GLD + c4 * 4]) = rb[s];
+    for (int s = 0; s < NCH; ++s) {
+      const int kr = (tid >> 5) + s * 8;
+      const bool k_ok = k0 + kr < kend;
+      *reinterpret_cast<floatx4*>(&As[kr * GLD + c4 * 4]) =
+          (k_ok && m_ok) ? rk[s] * rw[s] : zero4();
+      *reinterpret_cast<floatx4*>(&Bs[kr * GLD + c4 * 4]) = (k_ok && n_ok) ? rb[s] : zero4();
     }
+  };
+  auto frags = [&](int p, float (&av)[2], float (&bv)[2]) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) av[i] = As[(2 * p + lh) * GLD + wm * 64 + i * 32 + li];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) bv[j] = Bs[(2 * p + lh) * GLD + wn * 64 + j * 32 + li];
   };
 
   if (kbeg < kend) {
     fetch(kbeg);
-    stash();
+    stash(kbeg);
     __syncthreads();
     for (long long k0 = kbeg; k0 < kend; k0 += GTK) {
       const bool more = k0 + GTK < kend;
       if (more) fetch(k0 + GTK);
+      __builtin_amdgcn_sched_barrier(0);
+      float av[2][2], bv[2][2];
+      frags(0, av[0], bv[0]);
 #pragma unroll
       for (int p = 0; p < GTK / 2; ++p) {
-        float av[2], bv[2];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) av[i] = As[(2 * p + lh) * GLD + wm * 64 + i * 32 + li];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) bv[j] = Bs[(2 * p + lh) * GLD + wn * 64 + j * 32 + li];
+        if (p + 1 < GTK / 2) frags(p + 1, av[(p + 1) & 1], bv[(p + 1) & 1]);
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
           for (int j = 0; j < 2; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[p & 1][i], bv[p & 1][j],
+                                                             acc[i][j], 0, 0, 0);
       }
+      __builtin_amdgcn_sched_barrier(0);
       __syncthreads();
       if (more) {
-        stash();
+        stash(k0 + GTK);
         __syncthreads();
       }
     }
@@ -367,9 +486,9 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        int m = m0 + wm * 64 + i * 32 + 8 * (e / 4) + 4 * lh + (e & 3);
-        int n = n0 + wn * 64 + j * 32 + li;
-        if (m < M && n < N) out[(long long)m * N + n] = acc[i][j][e];
+        const int mm = m0 + wm * 64 + i * 32 + 8 * (e / 4) + 4 * lh + (e & 3);
+        const int nn = n0 + wn * 64 + j * 32 + li;
+        if (mm < M && nn < N) out[(long long)mm * N + nn] = acc[i][j][e];
       }
 }
 
@@ -433,9 +552,9 @@ size_t grad_partial_floats(int T, int B, int D, int H) {
   return (su > sw ? su : sw) + sb;
 }
 
-hipError_t launch_param_grads(const float* kap0, const float* w, const float* h, const float* x,
+hipError_t launch_param_grads(const float* kap0, const float* w, const float* h, const void* x,
                               float* dW, float* dU, float* db_i, float* db_h, float* part,
-                              int T, int B, int D, int H, hipStream_t s) {
+                              int T, int B, int D, int H, int bf16, hipStream_t s) {
   const long long Ktot = (long long)T * B;
   const int M = 3 * H;
   prof_begin(3, s);
@@ -443,7 +562,7 @@ hipError_t launch_param_grads(const float* kap0, const float* w, const float* h,
     GradArgs a;
     a.kap0 = kap0;
     a.w = w;
-    a.Bm = which == 0 ? h : x;
+    a.Bm = which == 0 ? (const void*)h : x;
     a.N = which == 0 ? H : D;
     a.third_off = which == 0 ? 2 * H : 4 * H;
     a.part = part;
@@ -454,7 +573,10 @@ hipError_t launch_param_grads(const float* kap0, const float* w, const float* h,
     long long per = (Ktot + splits - 1) / splits;
     a.Kper = (per + GTK - 1) / GTK * GTK;
     dim3 grid((M + GT - 1) / GT, (a.N + GT - 1) / GT, splits);
-    hipLaunchKernelGGL(grad_gemm_kernel, grid, dim3(256), 0, s, a);
+    if (which == 1 && bf16)
+      hipLaunchKernelGGL(grad_gemm_kernel<bf16_t>, grid, dim3(256), 0, s, a);
+    else
+      hipLaunchKernelGGL(grad_gemm_kernel<float>, grid, dim3(256), 0, s, a);
     const long long n = (long long)M * a.N;
     hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
                        part, which == 0 ? dU : dW, n, splits);

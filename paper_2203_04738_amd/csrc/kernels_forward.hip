@@ -4,6 +4,7 @@
 // right-hand side of Eq. 11, and the adjoint coefficient vectors).
 #include "common.h"
 #include "gemm_core.h"
+#include "gemm_core_bf16.h"
 #include "skinny.h"
 
 namespace mg {
@@ -66,13 +67,75 @@ __global__ __launch_bounds__(ProjCfg::NT) void projection_kernel(
     }
 }
 
-hipError_t launch_projection(const float* X, const float* W, const float* bias, float* P,
-                             long long M, int N, int K, hipStream_t s) {
-  typedef ProjCfg C;
-  dim3 grid((unsigned)xcd_grid((M + C::TM - 1) / C::TM, (N + C::TN - 1) / C::TN));
+// bf16 inputs and weights, fp32 accumulation and output
+typedef TileCfgB<2, 2, 2, 2, 1, false> ProjCfgB;
+
+__global__ __launch_bounds__(ProjCfgB::NT) void projection_kernel_bf16(
+    const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, const float* __restrict__ bias,
+    float* __restrict__ P, long long M, int N, int K) {
+  typedef ProjCfgB C;
+  __shared__ __attribute__((aligned(16))) bf16_t lds[C::LDS_ELEMS];
+  long long rt;
+  int ct;
+  if (!xcd_tile(blockIdx.x, (M + C::TM - 1) / C::TM, (N + C::TN - 1) / C::TN, rt, ct)) return;
+  const long long m0 = rt * C::TM;
+  const int n0 = ct * C::TN;
+  const bf16_t* arow[C::A_CHUNKS];
+  const bf16_t* brow[C::B_CHUNKS];
+#pragma unroll
+  for (int s = 0; s < C::A_CHUNKS; ++s) {
+    long long r = m0 + chunk_row_b<C>(s);
+    arow[s] = X + (r < M ? r : M - 1) * K;
+  }
+#pragma unroll
+  for (int s = 0; s < C::B_CHUNKS; ++s) {
+    int r = n0 + chunk_row_b<C>(s);
+    brow[s] = W + (long long)(r < N ? r : N - 1) * K;
+  }
+  Acc<C> acc;
+  acc.zero();
+  auto la = [&](int s, int k) { return ldg8h(arow[s] + k); };
+  auto lb = [&](int s, int k) { return ldg8h(brow[s] + k); };
+  auto fa = [](const bf16x8& v) { return v; };
+  if (K % C::TK == 0)
+    gemm_nt_tile_bf16<C, false>(acc, K, la, lb, fa, lds);
+  else
+    gemm_nt_tile_bf16<C, true>(acc, K, la, lb, fa, lds);
+#pragma unroll
+  for (int a = 0; a < C::BM; ++a)
+#pragma unroll
+    for (int b = 0; b < C::BN; ++b) {
+      int row, col;
+      acc_coord<C>(a, b, 0, row, col);
+      const int n = n0 + col;
+      if (n >= N) continue;
+      const float bv = bias[n];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        acc_coord<C>(a, b, e, row, col);
+        const long long m = m0 + row;
+        if (m < M) P[m * N + n] = acc.v[0][a][b][e] + bv;
+      }
+    }
+}
+
+hipError_t launch_projection(const void* X, const void* W, const float* bias, float* P,
+                             long long M, int N, int K, int bf16, hipStream_t s) {
   prof_begin(2, s);
-  hipLaunchKernelGGL(projection_kernel, grid, dim3(C::NT), 0, s, X, W, bias, P, M, N, K);
-  prof_end(2, 2.0 * (double)M * N * K, 4.0 * ((double)M * K + (double)N * K + (double)M * N), s);
+  if (bf16) {
+    typedef ProjCfgB C;
+    dim3 grid((unsigned)xcd_grid((M + C::TM - 1) / C::TM, (N + C::TN - 1) / C::TN));
+    hipLaunchKernelGGL(projection_kernel_bf16, grid, dim3(C::NT), 0, s, (const bf16_t*)X,
+                       (const bf16_t*)W, bias, P, M, N, K);
+  } else {
+    typedef ProjCfg C;
+    dim3 grid((unsigned)xcd_grid((M + C::TM - 1) / C::TM, (N + C::TN - 1) / C::TN));
+    hipLaunchKernelGGL(projection_kernel, grid, dim3(C::NT), 0, s, (const float*)X,
+                       (const float*)W, bias, P, M, N, K);
+  }
+  const double esz = bf16 ? 2.0 : 4.0;
+  prof_end(2, 2.0 * (double)M * N * K, esz * ((double)M * K + (double)N * K) + 4.0 * (double)M * N,
+           s);
   return hipGetLastError();
 }
 
@@ -206,7 +269,7 @@ __global__ __launch_bounds__(C::NT) void phi_step_kernel(PhiArgs a) {
     const int g = tr / C::TN;
     int j = n0 + tr % C::TN;
     if (j >= H) j = H - 1;
-    brow[s] = a.U + ((long long)g * H + j) * H;
+    brow[s] = (const float*)a.U + ((long long)g * H + j) * H;
   }
   Acc<C> acc;
   acc.zero();
@@ -244,10 +307,80 @@ __global__ __launch_bounds__(C::NT) void phi_step_kernel(PhiArgs a) {
   }
 }
 
+// bf16 weights: the fp32 state rows are split into hi + lo bf16 tiles (see
+// gemm_core_bf16.h); gates, update and outputs stay fp32.
+template <class C, int MODE>
+__global__ __launch_bounds__(C::NT) void phi_step_kernel_bf16(PhiArgs a) {
+  __shared__ __attribute__((aligned(16))) bf16_t lds[C::LDS_ELEMS];
+  const int H = a.H, B = a.B;
+  const long long R = (long long)a.nk * B;
+  long long rt;
+  int ct;
+  if (!xcd_tile(blockIdx.x, (R + C::TM - 1) / C::TM, (H + C::TN - 1) / C::TN, rt, ct)) return;
+  const long long m0 = rt * C::TM;
+  const int n0 = ct * C::TN;
+  const int tid = threadIdx.x;
+  const bf16_t* U = (const bf16_t*)a.U;
+
+  const float* arow[C::A_CHUNKS];
+  const bf16_t* brow[C::B_CHUNKS];
+#pragma unroll
+  for (int s = 0; s < C::A_CHUNKS; ++s) {
+    long long r = m0 + chunk_row_b<C>(s);
+    if (r >= R) r = R - 1;
+    const long long pt = r / B;
+    const int b = (int)(r - pt * B);
+    arow[s] = a.u_in + (a.in.at(pt) * B + b) * H;
+  }
+#pragma unroll
+  for (int s = 0; s < C::B_CHUNKS; ++s) {
+    const int tr = chunk_row_b<C>(s);
+    const int g = tr / C::TN;
+    int j = n0 + tr % C::TN;
+    if (j >= H) j = H - 1;
+    brow[s] = U + ((long long)g * H + j) * H;
+  }
+  Acc<C> acc;
+  acc.zero();
+  auto la = [&](int s, int k) { return F32x8{ldg4(arow[s] + k), ldg4(arow[s] + k + 4)}; };
+  auto lb = [&](int s, int k) { return ldg8h(brow[s] + k); };
+  auto fa = [](const F32x8& v) { return v; };
+  if (H % C::TK == 0)
+    gemm_nt_tile_bf16<C, false>(acc, H, la, lb, fa, lds);
+  else
+    gemm_nt_tile_bf16<C, true>(acc, H, la, lb, fa, lds);
+
+  double nrm = 0.0;
+#pragma unroll
+  for (int ba = 0; ba < C::BM; ++ba)
+#pragma unroll
+    for (int bb = 0; bb < C::BN; ++bb) {
+      int row, col;
+      acc_coord<C>(ba, bb, 0, row, col);
+      const int j = n0 + col;
+      if (j >= H) continue;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        acc_coord<C>(ba, bb, e, row, col);
+        const long long r = m0 + row;
+        if (r >= R) continue;
+        const long long pt = r / B;
+        const int b = (int)(r - pt * B);
+        phi_epilogue<MODE>(a, pt, b, j, acc.v[0][ba][bb][e], acc.v[1][ba][bb][e], acc.v[2][ba][bb][e],
+                           nrm);
+      }
+    }
+  if (MODE == STEP_RESID && a.norm) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) nrm += __shfl_down(nrm, off, 64);
+    if ((tid & 63) == 0) atomicAdd(a.norm, nrm);
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Few-row variant (coarsest-level propagation, serial scan): see skinny.h
 // ---------------------------------------------------------------------------
-template <int CT, int MODE>
+template <int CT, int MODE, class WT>
 __global__ __launch_bounds__(SK_NT) void phi_skinny_kernel(PhiArgs a) {
   constexpr int NU = 3 * CT;
   __shared__ float red[SK_NT * NU];
@@ -283,14 +416,14 @@ __global__ __launch_bounds__(SK_NT) void phi_skinny_kernel(PhiArgs a) {
     const int b = r - (int)pt * B;
     hrow = a.u_in + (a.in.at(pt) * B + b) * H;
   }
-  const float* urow[NU];
+  const WT* urow[NU];
 #pragma unroll
   for (int u = 0; u < NU; ++u) {
     const int g = u / CT, j = min(j0 + u % CT, H - 1);
-    urow[u] = a.U + ((long long)g * H + j) * H;
+    urow[u] = (const WT*)a.U + ((long long)g * H + j) * H;
   }
   float acc[NU];
-  skinny_partial<NU>(acc, H, ks, ksl, live, urow, [&](int k) { return ldg4(hrow + k); });
+  skinny_partial<NU, WT>(acc, H, ks, ksl, live, urow, [&](int k) { return ldg4(hrow + k); });
 #pragma unroll
   for (int u = 0; u < NU; ++u) red[(bl * NU + u) * ksl + ks] = acc[u];
   __syncthreads();
@@ -308,40 +441,53 @@ __global__ __launch_bounds__(SK_NT) void phi_skinny_kernel(PhiArgs a) {
 typedef TileCfg<2, 2, 2, 1, 3> PhiBig;    // 128 rows x 64 hidden columns (x3 gates), 256 threads
 typedef TileCfg<2, 1, 1, 1, 3> PhiMid;    //  64 rows x 32 hidden columns, 128 threads
 typedef TileCfg<1, 1, 1, 1, 3> PhiSmall;  //  32 rows x 32 hidden columns, 64 threads
+typedef TileCfgB<2, 2, 2, 1, 3, true> PhiBigB;
+typedef TileCfgB<2, 1, 1, 1, 3, true> PhiMidB;
+typedef TileCfgB<1, 1, 1, 1, 3, true> PhiSmallB;
 
-template <class C>
+#define MG_LAUNCH_BY_MODE(KERNEL, ...)                                                   \
+  switch (a.mode) {                                                                      \
+    case STEP_RELAX:                                                                     \
+      hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_RELAX>), grid, block, 0, s, a);       \
+      break;                                                                             \
+    case STEP_RESID:                                                                     \
+      hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_RESID>), grid, block, 0, s, a);       \
+      break;                                                                             \
+    case STEP_RHS:                                                                       \
+      hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_RHS>), grid, block, 0, s, a);         \
+      break;                                                                             \
+    default:                                                                             \
+      hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_KAPPA>), grid, block, 0, s, a);       \
+  }
+
+template <class C, class CB>
 static void launch_phi_cfg(const PhiArgs& a, hipStream_t s) {
   const long long R = (long long)a.nk * a.B;
   dim3 grid((unsigned)xcd_grid((R + C::TM - 1) / C::TM, (a.H + C::TN - 1) / C::TN));
-  switch (a.mode) {
-    case STEP_RELAX:
-      hipLaunchKernelGGL((phi_step_kernel<C, STEP_RELAX>), grid, dim3(C::NT), 0, s, a);
-      break;
-    case STEP_RESID:
-      hipLaunchKernelGGL((phi_step_kernel<C, STEP_RESID>), grid, dim3(C::NT), 0, s, a);
-      break;
-    case STEP_RHS:
-      hipLaunchKernelGGL((phi_step_kernel<C, STEP_RHS>), grid, dim3(C::NT), 0, s, a);
-      break;
-    default:
-      hipLaunchKernelGGL((phi_step_kernel<C, STEP_KAPPA>), grid, dim3(C::NT), 0, s, a);
+  dim3 block(C::NT);
+  static_assert(C::TM == CB::TM && C::TN == CB::TN && C::NT == CB::NT, "tile shapes must agree");
+  if (a.bf16) {
+    MG_LAUNCH_BY_MODE(phi_step_kernel_bf16, CB)
+  } else {
+    MG_LAUNCH_BY_MODE(phi_step_kernel, C)
   }
+}
+
+template <int CT, int MODE>
+static void launch_phi_skinny_mode(const PhiArgs& a, dim3 grid, hipStream_t s) {
+  if (a.bf16)
+    hipLaunchKernelGGL((phi_skinny_kernel<CT, MODE, bf16_t>), grid, dim3(SK_NT), 0, s, a);
+  else
+    hipLaunchKernelGGL((phi_skinny_kernel<CT, MODE, float>), grid, dim3(SK_NT), 0, s, a);
 }
 
 template <int CT>
 static void launch_phi_skinny(const PhiArgs& a, dim3 grid, hipStream_t s) {
   switch (a.mode) {
-    case STEP_RELAX:
-      hipLaunchKernelGGL((phi_skinny_kernel<CT, STEP_RELAX>), grid, dim3(SK_NT), 0, s, a);
-      break;
-    case STEP_RESID:
-      hipLaunchKernelGGL((phi_skinny_kernel<CT, STEP_RESID>), grid, dim3(SK_NT), 0, s, a);
-      break;
-    case STEP_RHS:
-      hipLaunchKernelGGL((phi_skinny_kernel<CT, STEP_RHS>), grid, dim3(SK_NT), 0, s, a);
-      break;
-    default:
-      hipLaunchKernelGGL((phi_skinny_kernel<CT, STEP_KAPPA>), grid, dim3(SK_NT), 0, s, a);
+    case STEP_RELAX: launch_phi_skinny_mode<CT, STEP_RELAX>(a, grid, s); break;
+    case STEP_RESID: launch_phi_skinny_mode<CT, STEP_RESID>(a, grid, s); break;
+    case STEP_RHS: launch_phi_skinny_mode<CT, STEP_RHS>(a, grid, s); break;
+    default: launch_phi_skinny_mode<CT, STEP_KAPPA>(a, grid, s);
   }
 }
 
@@ -361,11 +507,11 @@ hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s) {
     else
       launch_phi_skinny<1>(a, grid, s);
   } else if (tiles(PhiBig::TM, PhiBig::TN) >= 512)
-    launch_phi_cfg<PhiBig>(a, s);
+    launch_phi_cfg<PhiBig, PhiBigB>(a, s);
   else if (R > 32 && tiles(PhiMid::TM, PhiMid::TN) >= 256)
-    launch_phi_cfg<PhiMid>(a, s);
+    launch_phi_cfg<PhiMid, PhiMidB>(a, s);
   else
-    launch_phi_cfg<PhiSmall>(a, s);
+    launch_phi_cfg<PhiSmall, PhiSmallB>(a, s);
   prof_end(kind, 6.0 * (double)R * a.H * a.H, 20.0 * (double)R * a.H, s);
   return hipGetLastError();
 }

@@ -7,7 +7,7 @@
 //   interleaved float4 slices for the NU weight rows of the workgroup, partial
 //   sums meet in LDS, and thread (b, column) applies the epilogue.
 #pragma once
-#include "gemm_core.h"
+#include "gemm_core_bf16.h"
 
 namespace mg {
 
@@ -24,9 +24,9 @@ __host__ __device__ inline int sk_row_pad(int rows) {
 // Partial dot products of this thread.  getA(k) returns the float4 of the
 // thread's row at columns k..k+3; urow[u] points at weight row u (K floats).
 // rows_here <= Rp rows are live; idle threads return zeros.
-template <int NU, class GetA>
+template <int NU, class WT, class GetA>
 __device__ inline void skinny_partial(float (&acc)[NU], int K, int ks, int ksl, bool live,
-                                      const float* const (&urow)[NU], GetA getA) {
+                                      const WT* const (&urow)[NU], GetA getA) {
   // several independent slices are fetched before any is consumed, so that the
   // loop pays one memory round trip per UNR slices
   constexpr int UNR = NU >= 12 ? 1 : (NU >= 5 ? 2 : 4);
@@ -43,7 +43,7 @@ __device__ inline void skinny_partial(float (&acc)[NU], int K, int ks, int ksl, 
       if (kk < K) {
         a[i] = getA(kk);
 #pragma unroll
-        for (int u = 0; u < NU; ++u) w[i][u] = ldg4(urow[u] + kk);
+        for (int u = 0; u < NU; ++u) w[i][u] = ldg4w(urow[u] + kk);
       } else {
         a[i] = zero4();
 #pragma unroll

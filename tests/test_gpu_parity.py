@@ -184,3 +184,73 @@ def test_invalid_call_leaves_buffers_untouched(gh):
     assert e.value.code == -5
     torch.cuda.synchronize()
     assert torch.all(h == 3.0)
+
+
+# ------------------------------------------------------------------ bf16 inputs / weights
+
+TOL_BF16 = 2e-2       # the benchmark spec: bf16-input / fp32-state variant
+TIGHT_BF16 = 1e-4     # what the hi+lo split of the fp32 operand is expected to reach
+
+
+def _bf16_inputs(d):
+    from synthetic_inputs import round_to_bf16
+    d = dict(d)
+    for k in ("x", "W", "U"):
+        d[k] = round_to_bf16(d[k])      # the oracle sees exactly the stored bf16 values
+    return d
+
+
+@pytest.mark.parametrize("shape", [(13, 3, 24, 40), (6, 70, 16, 136)])
+def test_bf16_serial_scan_and_bptt(gh, shape):
+    T, B, D, H = shape
+    d = _bf16_inputs(random_small(300 + H, T, B, D, H, scale=0.3))
+    ref = orc.serial_scan(*_P(d), d["x"], d["h0"])
+    run = gh.GpuRun(d, dtype="bf16")
+    got = run.serial_scan()
+    e = gh.rel_err(got, ref)
+    assert e <= TOL_BF16 and e <= TIGHT_BF16, e
+    h = ref.astype(np.float32)
+    rb = orc.serial_bptt(*_P(d), d["x"], h, d["dL_dhT"])
+    gb = run.serial_backward(h)
+    for name, g, r in zip(("w", "dW", "dU", "db_i", "db_h"), gb, rb):
+        e = gh.rel_err(g, r)
+        assert e <= TOL_BF16 and e <= TIGHT_BF16, (name, e)
+
+
+def _check_bf16_mgrit(gh, d, cf, levels, iters):
+    _, _, rits = orc.mgrit_forward(*_P(d), d["x"], d["h0"], _zeros(d), cf, levels, iters,
+                                   keep_iterates=True)
+    run = gh.GpuRun(d, cf=cf, levels=levels, dtype="bf16")
+    gits, _ = run.forward_iterates(iters)
+    for i, (g, r) in enumerate(zip(gits, rits)):
+        e = gh.rel_err(g, r)
+        assert e <= TOL_BF16 and e <= TIGHT_BF16, (i, e)
+    h = rits[-1].astype(np.float32)
+    out = orc.mgrit_backward(*_P(d), d["x"], h, d["dL_dhT"], _zeros(d), cf, levels, iters,
+                             keep_iterates=True)
+    wits, _, grads = run.backward_iterates(h, iters)
+    for i, (g, r) in enumerate(zip(wits, out[-1])):
+        e = gh.rel_err(g, r)
+        assert e <= TOL_BF16 and e <= TIGHT_BF16, ("w", i, e)
+    for name, g, r in zip(("dW", "dU", "db_i", "db_h"), grads, out[2:6]):
+        e = gh.rel_err(g, r)
+        assert e <= TOL_BF16 and e <= TIGHT_BF16, (name, e)
+
+
+def test_bf16_mgrit_small_hierarchies(gh):
+    d = _bf16_inputs(random_small(41, 48, 3, 24, 40, scale=0.3))
+    _check_bf16_mgrit(gh, d, 4, 2, 2)
+    _check_bf16_mgrit(gh, d, 2, 3, 2)
+
+
+def test_bf16_mgrit_c4_reduced_twin(gh):
+    wl = WORKLOADS["C4"].twin()
+    d = make_inputs(wl)                 # x, W, U already bf16-representable
+    _check_bf16_mgrit(gh, d, wl.cf, wl.levels, 2)
+
+
+def test_bf16_rejects_widths_not_multiple_of_8(gh):
+    import paper_2203_04738_amd as mg
+    with pytest.raises(mg.MgritGruError) as e:
+        mg.mgrit_gru_workspace_bytes(mg.MgritGruCfg(16, 2, 12, 36, cf=4, levels=2, dtype=1))
+    assert e.value.code == -6

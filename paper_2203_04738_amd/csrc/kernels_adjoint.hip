@@ -212,7 +212,7 @@ __global__ __launch_bounds__(C::NT) void adj_step_kernel_bf16(AdjArgs a) {
 // Few-row variant (coarsest-level solve, serial BPTT): see skinny.h
 template <int CT, int MODE, class WT>
 __global__ __launch_bounds__(SK_NT) void adj_skinny_kernel(AdjArgs a) {
-  __shared__ float red[SK_NT * CT];
+  __shared__ float red[SK_MAXROWS * CT * (SK_NT / 64)];
   const int H = a.H, B = a.B, K = 3 * a.H;
   const int R = a.nk * B;
   const int r0 = blockIdx.y * SK_MAXROWS;
@@ -253,8 +253,7 @@ __global__ __launch_bounds__(SK_NT) void adj_skinny_kernel(AdjArgs a) {
     const int kk = k >= 2 * H ? k - 2 * H : (k >= H ? k - H : k);
     return ldg4(krow + k) * ldg4(wrow + kk);
   });
-#pragma unroll
-  for (int u = 0; u < CT; ++u) red[(bl * CT + u) * ksl + ks] = acc[u];
+  skinny_reduce<CT>(acc, red, bl, ks, ksl);
   __syncthreads();
 
   double nrm = 0.0;

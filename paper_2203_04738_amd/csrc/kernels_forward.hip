@@ -383,7 +383,7 @@ __global__ __launch_bounds__(C::NT) void phi_step_kernel_bf16(PhiArgs a) {
 template <int CT, int MODE, class WT>
 __global__ __launch_bounds__(SK_NT) void phi_skinny_kernel(PhiArgs a) {
   constexpr int NU = 3 * CT;
-  __shared__ float red[SK_NT * NU];
+  __shared__ float red[SK_MAXROWS * NU * (SK_NT / 64)];
   const int H = a.H, B = a.B;
   const int R = a.nk * B;
   const int r0 = blockIdx.y * SK_MAXROWS;
@@ -424,8 +424,7 @@ __global__ __launch_bounds__(SK_NT) void phi_skinny_kernel(PhiArgs a) {
   }
   float acc[NU];
   skinny_partial<NU, WT>(acc, H, ks, ksl, live, urow, [&](int k) { return ldg4(hrow + k); });
-#pragma unroll
-  for (int u = 0; u < NU; ++u) red[(bl * NU + u) * ksl + ks] = acc[u];
+  skinny_reduce<NU>(acc, red, bl, ks, ksl);
   __syncthreads();
 
   double nrm = 0.0;

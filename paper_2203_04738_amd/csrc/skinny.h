@@ -62,12 +62,34 @@ __device__ inline void skinny_partial(float (&acc)[NU], int K, int ks, int ksl, 
   }
 }
 
-// red[(b*NU + u)*ksl + ks] holds the partials; returns the full sum for (b, u).
+// Combine the partials of all k-slices of a row.  ks is the fast thread index, so
+// the slices of one row occupy min(ksl, 64) consecutive lanes of a wave: those are
+// summed with lane shuffles, and one lane per segment leaves the segment sum in
+// red[(b*NU + u)*nseg + seg], nseg = ksl / min(ksl, 64) <= SK_NT/64.
+__device__ inline int sk_nseg(int ksl) { return ksl > 64 ? ksl / 64 : 1; }
+
+template <int NU>
+__device__ inline void skinny_reduce(float (&acc)[NU], float* red, int bl, int ks, int ksl) {
+  const int width = ksl > 64 ? 64 : ksl;
+#pragma unroll
+  for (int u = 0; u < NU; ++u) {
+    float v = acc[u];
+    for (int off = width >> 1; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    acc[u] = v;
+  }
+  if ((ks & (width - 1)) == 0) {
+    const int nseg = sk_nseg(ksl);
+#pragma unroll
+    for (int u = 0; u < NU; ++u) red[(bl * NU + u) * nseg + ks / width] = acc[u];
+  }
+}
+
 template <int NU>
 __device__ inline float skinny_sum(const float* red, int b, int u, int ksl) {
-  const float* p = red + (b * NU + u) * ksl;
+  const int nseg = sk_nseg(ksl);
+  const float* p = red + (b * NU + u) * nseg;
   float s = 0.f;
-  for (int i = 0; i < ksl; ++i) s += p[i];
+  for (int i = 0; i < nseg; ++i) s += p[i];
   return s;
 }
 

@@ -51,19 +51,12 @@ __device__ inline void adj_epi_finish(const AdjArgs& a, long long pt, int b, int
   }
 }
 
-template <int MODE>
-__device__ inline void adj_epilogue(const AdjArgs& a, long long pt, int b, int j, float dot,
-                                    double& nrm) {
-  const AdjEpiIn e = adj_epi_load<MODE>(a, pt, b, j);
-  adj_epi_finish<MODE>(a, pt, b, j, dot, e, nrm);
-}
-
 struct KapW {
   floatx4 kap, w;
 };
 
 template <class C, int MODE>
-__global__ __launch_bounds__(C::NT) void adj_step_kernel(AdjArgs a) {
+__global__ __launch_bounds__(C::NT, 2) void adj_step_kernel(AdjArgs a) {
   __shared__ __attribute__((aligned(16))) float lds[C::LDS_FLOATS];
   const int H = a.H, B = a.B, K = 3 * a.H;
   const long long R = (long long)a.nk * B;
@@ -116,14 +109,28 @@ __global__ __launch_bounds__(C::NT) void adj_step_kernel(AdjArgs a) {
       acc_coord<C>(ba, bb, 0, row, col);
       const int j = n0 + col;
       if (j >= H) continue;
+      // EPI_BATCH elements at a time: all their operands are requested before the
+      // first is consumed
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        acc_coord<C>(ba, bb, e, row, col);
-        const long long r = m0 + row;
-        if (r >= R) continue;
-        const long long pt = r / B;
-        const int b = (int)(r - pt * B);
-        adj_epilogue<MODE>(a, pt, b, j, acc.v[0][ba][bb][e], nrm);
+      for (int e0 = 0; e0 < 16; e0 += EPI_BATCH) {
+        AdjEpiIn ein[EPI_BATCH];
+        int pts[EPI_BATCH], bs[EPI_BATCH];
+#pragma unroll
+        for (int i = 0; i < EPI_BATCH; ++i) {
+          acc_coord<C>(ba, bb, e0 + i, row, col);
+          long long r = m0 + row;
+          if (r >= R) r = R - 1;        // clamped rows are loaded but never stored
+          pts[i] = (int)(r / B);
+          bs[i] = (int)(r - (long long)pts[i] * B);
+          ein[i] = adj_epi_load<MODE>(a, pts[i], bs[i], j);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < EPI_BATCH; ++i) {
+          acc_coord<C>(ba, bb, e0 + i, row, col);
+          if (m0 + row >= R) continue;
+          adj_epi_finish<MODE>(a, pts[i], bs[i], j, acc.v[0][ba][bb][e0 + i], ein[i], nrm);
+        }
       }
     }
   if (MODE == STEP_RESID && a.norm) {
@@ -139,7 +146,7 @@ struct KapW8 {
 };
 
 template <class C, int MODE>
-__global__ __launch_bounds__(C::NT) void adj_step_kernel_bf16(AdjArgs a) {
+__global__ __launch_bounds__(C::NT, 2) void adj_step_kernel_bf16(AdjArgs a) {
   __shared__ __attribute__((aligned(16))) bf16_t lds[C::LDS_ELEMS];
   const int H = a.H, B = a.B, K = 3 * a.H;
   const long long R = (long long)a.nk * B;
@@ -192,14 +199,28 @@ __global__ __launch_bounds__(C::NT) void adj_step_kernel_bf16(AdjArgs a) {
       acc_coord<C>(ba, bb, 0, row, col);
       const int j = n0 + col;
       if (j >= H) continue;
+      // EPI_BATCH elements at a time: all their operands are requested before the
+      // first is consumed
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        acc_coord<C>(ba, bb, e, row, col);
-        const long long r = m0 + row;
-        if (r >= R) continue;
-        const long long pt = r / B;
-        const int b = (int)(r - pt * B);
-        adj_epilogue<MODE>(a, pt, b, j, acc.v[0][ba][bb][e], nrm);
+      for (int e0 = 0; e0 < 16; e0 += EPI_BATCH) {
+        AdjEpiIn ein[EPI_BATCH];
+        int pts[EPI_BATCH], bs[EPI_BATCH];
+#pragma unroll
+        for (int i = 0; i < EPI_BATCH; ++i) {
+          acc_coord<C>(ba, bb, e0 + i, row, col);
+          long long r = m0 + row;
+          if (r >= R) r = R - 1;        // clamped rows are loaded but never stored
+          pts[i] = (int)(r / B);
+          bs[i] = (int)(r - (long long)pts[i] * B);
+          ein[i] = adj_epi_load<MODE>(a, pts[i], bs[i], j);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < EPI_BATCH; ++i) {
+          acc_coord<C>(ba, bb, e0 + i, row, col);
+          if (m0 + row >= R) continue;
+          adj_epi_finish<MODE>(a, pts[i], bs[i], j, acc.v[0][ba][bb][e0 + i], ein[i], nrm);
+        }
       }
     }
   if (MODE == STEP_RESID && a.norm) {

@@ -160,8 +160,14 @@ __device__ inline float tanhf_(float a) {
 // loaded separately so that the few-row kernel can fetch them before its dot
 // products instead of after.
 struct PhiEpiIn {
-  float pr, pz, pn, h, bhr, bhz, bhn, gval, cur;
+  float pr, pz, pn, h, gval, cur;
 };
+struct PhiBias {          // recurrent biases of one hidden column
+  float r, z, n;
+};
+__device__ inline PhiBias phi_bias_load(const PhiArgs& a, int j) {
+  return PhiBias{a.b_h[j], a.b_h[a.H + j], a.b_h[2 * a.H + j]};
+}
 
 template <int MODE>
 __device__ inline PhiEpiIn phi_epi_load(const PhiArgs& a, long long pt, int b, int j) {
@@ -172,9 +178,6 @@ __device__ inline PhiEpiIn phi_epi_load(const PhiArgs& a, long long pt, int b, i
   e.pz = pp[H + j];
   e.pn = pp[2 * H + j];
   e.h = a.u_in[(a.in.at(pt) * B + b) * H + j];
-  e.bhr = a.b_h[j];
-  e.bhz = a.b_h[H + j];
-  e.bhn = a.b_h[2 * H + j];
   const long long oi = (a.o.at(pt) * B + b) * H + j;
   e.gval = (MODE != STEP_KAPPA && a.g) ? a.g[oi] : 0.f;
   e.cur = (MODE == STEP_RESID || MODE == STEP_RHS) ? a.u[oi] : 0.f;
@@ -186,14 +189,15 @@ __device__ inline PhiEpiIn phi_epi_load(const PhiArgs& a, long long pt, int b, i
 // contractions (U_r h)_j, (U_z h)_j, (U_n h)_j.
 template <int MODE>
 __device__ inline void phi_epi_finish(const PhiArgs& a, long long pt, int b, int j, float sr,
-                                      float sz, float sn, const PhiEpiIn& e, double& nrm) {
+                                      float sz, float sn, const PhiEpiIn& e, const PhiBias& bh,
+                                      double& nrm) {
   const int H = a.H, B = a.B;
   const float gamma = a.gamma;
   const bool implicit = a.propagator == MGRIT_PROP_IMPLICIT;
   const float h = e.h;
-  const float rg = sigmoidf_(e.pr + sr + e.bhr);
-  const float zg = sigmoidf_(e.pz + sz + e.bhz);
-  const float q = sn + e.bhn;
+  const float rg = sigmoidf_(e.pr + sr + bh.r);
+  const float zg = sigmoidf_(e.pz + sz + bh.z);
+  const float q = sn + bh.n;
   const float n = tanhf_(e.pn + rg * q);
   const float c = 1.0f - zg;
   const float d = 1.0f + gamma * c;
@@ -231,15 +235,8 @@ __device__ inline void phi_epi_finish(const PhiArgs& a, long long pt, int b, int
   }
 }
 
-template <int MODE>
-__device__ inline void phi_epilogue(const PhiArgs& a, long long pt, int b, int j, float sr,
-                                    float sz, float sn, double& nrm) {
-  const PhiEpiIn e = phi_epi_load<MODE>(a, pt, b, j);
-  phi_epi_finish<MODE>(a, pt, b, j, sr, sz, sn, e, nrm);
-}
-
 template <class C, int MODE>
-__global__ __launch_bounds__(C::NT) void phi_step_kernel(PhiArgs a) {
+__global__ __launch_bounds__(C::NT, 2) void phi_step_kernel(PhiArgs a) {
   __shared__ __attribute__((aligned(16))) float lds[C::LDS_FLOATS];
   const int H = a.H, B = a.B;
   const long long R = (long long)a.nk * B;
@@ -289,15 +286,30 @@ __global__ __launch_bounds__(C::NT) void phi_step_kernel(PhiArgs a) {
       acc_coord<C>(ba, bb, 0, row, col);
       const int j = n0 + col;
       if (j >= H) continue;
+      const PhiBias bh = phi_bias_load(a, j);
+      // EPI_BATCH elements at a time: their operands are all requested before the
+      // first is consumed, so a block pays 16/EPI_BATCH memory round trips, not sixteen
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        acc_coord<C>(ba, bb, e, row, col);
-        const long long r = m0 + row;
-        if (r >= R) continue;
-        const long long pt = r / B;
-        const int b = (int)(r - pt * B);
-        phi_epilogue<MODE>(a, pt, b, j, acc.v[0][ba][bb][e], acc.v[1][ba][bb][e], acc.v[2][ba][bb][e],
-                     nrm);
+      for (int e0 = 0; e0 < 16; e0 += EPI_BATCH) {
+        PhiEpiIn ein[EPI_BATCH];
+        int pts[EPI_BATCH], bs[EPI_BATCH];
+#pragma unroll
+        for (int i = 0; i < EPI_BATCH; ++i) {
+          acc_coord<C>(ba, bb, e0 + i, row, col);
+          long long r = m0 + row;
+          if (r >= R) r = R - 1;        // clamped rows are loaded but never stored
+          pts[i] = (int)(r / B);
+          bs[i] = (int)(r - (long long)pts[i] * B);
+          ein[i] = phi_epi_load<MODE>(a, pts[i], bs[i], j);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < EPI_BATCH; ++i) {
+          acc_coord<C>(ba, bb, e0 + i, row, col);
+          if (m0 + row >= R) continue;
+          phi_epi_finish<MODE>(a, pts[i], bs[i], j, acc.v[0][ba][bb][e0 + i],
+                               acc.v[1][ba][bb][e0 + i], acc.v[2][ba][bb][e0 + i], ein[i], bh, nrm);
+        }
       }
     }
   if (MODE == STEP_RESID && a.norm) {
@@ -310,7 +322,7 @@ __global__ __launch_bounds__(C::NT) void phi_step_kernel(PhiArgs a) {
 // bf16 weights: the fp32 state rows are split into hi + lo bf16 tiles (see
 // gemm_core_bf16.h); gates, update and outputs stay fp32.
 template <class C, int MODE>
-__global__ __launch_bounds__(C::NT) void phi_step_kernel_bf16(PhiArgs a) {
+__global__ __launch_bounds__(C::NT, 2) void phi_step_kernel_bf16(PhiArgs a) {
   __shared__ __attribute__((aligned(16))) bf16_t lds[C::LDS_ELEMS];
   const int H = a.H, B = a.B;
   const long long R = (long long)a.nk * B;
@@ -359,15 +371,30 @@ __global__ __launch_bounds__(C::NT) void phi_step_kernel_bf16(PhiArgs a) {
       acc_coord<C>(ba, bb, 0, row, col);
       const int j = n0 + col;
       if (j >= H) continue;
+      const PhiBias bh = phi_bias_load(a, j);
+      // EPI_BATCH elements at a time: their operands are all requested before the
+      // first is consumed, so a block pays 16/EPI_BATCH memory round trips, not sixteen
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        acc_coord<C>(ba, bb, e, row, col);
-        const long long r = m0 + row;
-        if (r >= R) continue;
-        const long long pt = r / B;
-        const int b = (int)(r - pt * B);
-        phi_epilogue<MODE>(a, pt, b, j, acc.v[0][ba][bb][e], acc.v[1][ba][bb][e], acc.v[2][ba][bb][e],
-                           nrm);
+      for (int e0 = 0; e0 < 16; e0 += EPI_BATCH) {
+        PhiEpiIn ein[EPI_BATCH];
+        int pts[EPI_BATCH], bs[EPI_BATCH];
+#pragma unroll
+        for (int i = 0; i < EPI_BATCH; ++i) {
+          acc_coord<C>(ba, bb, e0 + i, row, col);
+          long long r = m0 + row;
+          if (r >= R) r = R - 1;        // clamped rows are loaded but never stored
+          pts[i] = (int)(r / B);
+          bs[i] = (int)(r - (long long)pts[i] * B);
+          ein[i] = phi_epi_load<MODE>(a, pts[i], bs[i], j);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < EPI_BATCH; ++i) {
+          acc_coord<C>(ba, bb, e0 + i, row, col);
+          if (m0 + row >= R) continue;
+          phi_epi_finish<MODE>(a, pts[i], bs[i], j, acc.v[0][ba][bb][e0 + i],
+                               acc.v[1][ba][bb][e0 + i], acc.v[2][ba][bb][e0 + i], ein[i], bh, nrm);
+        }
       }
     }
   if (MODE == STEP_RESID && a.norm) {
@@ -401,12 +428,14 @@ __global__ __launch_bounds__(SK_NT) void phi_skinny_kernel(PhiArgs a) {
   long long e_pt = 0;
   int e_b = 0, e_j = 0;
   PhiEpiIn ein = {};
+  PhiBias ebh = {};
   if (epi) {
     const int r = r0 + tid / CT;
     e_pt = r / B;
     e_b = r - (int)e_pt * B;
     e_j = j0 + tid % CT;
     ein = phi_epi_load<MODE>(a, e_pt, e_b, e_j);
+    ebh = phi_bias_load(a, e_j);
   }
 
   const float* hrow = nullptr;
@@ -432,7 +461,7 @@ __global__ __launch_bounds__(SK_NT) void phi_skinny_kernel(PhiArgs a) {
     const int bl2 = tid / CT, c = tid % CT;
     phi_epi_finish<MODE>(a, e_pt, e_b, e_j, skinny_sum<NU>(red, bl2, c, ksl),
                          skinny_sum<NU>(red, bl2, CT + c, ksl),
-                         skinny_sum<NU>(red, bl2, 2 * CT + c, ksl), ein, nrm);
+                         skinny_sum<NU>(red, bl2, 2 * CT + c, ksl), ein, ebh, nrm);
   }
   if (MODE == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
 }

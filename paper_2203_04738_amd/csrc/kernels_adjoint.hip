@@ -17,14 +17,28 @@ namespace mg {
 struct AdjEpiIn {
   float kd, wv, gval, cur;
 };
+// Element offsets (column 0) of one row of a launch: input adjoint, coefficient row,
+// out/cur/g, coarse array.  Computed once per tile row and kept in LDS.
+struct AdjRow {
+  long long in, k, o, a;
+};
+__device__ inline AdjRow adj_row(const AdjArgs& a, long long r) {
+  const long long pt = r / a.B;
+  const int b = (int)(r - pt * a.B);
+  AdjRow ro;
+  ro.in = (a.in.at(pt) * a.B + b) * a.H;
+  ro.k = (a.k.at(pt) * a.B + b) * (long long)a.kw;
+  ro.o = (a.o.at(pt) * a.B + b) * a.H;
+  ro.a = (a.a.at(pt) * a.B + b) * a.H;
+  return ro;
+}
 
 template <int MODE>
-__device__ inline AdjEpiIn adj_epi_load(const AdjArgs& a, long long pt, int b, int j) {
-  const int H = a.H, B = a.B;
+__device__ inline AdjEpiIn adj_epi_load(const AdjArgs& a, const AdjRow& ro, int j) {
   AdjEpiIn e;
-  e.kd = a.kap[(a.k.at(pt) * B + b) * (long long)a.kw + 3 * H + j];
-  e.wv = a.w_in[(a.in.at(pt) * B + b) * H + j];
-  const long long oi = (a.o.at(pt) * B + b) * H + j;
+  e.kd = a.kap[ro.k + 3 * a.H + j];
+  e.wv = a.w_in[ro.in + j];
+  const long long oi = ro.o + j;
   e.gval = a.g ? a.g[oi] : 0.f;
   e.cur = (MODE == STEP_RESID || MODE == STEP_RHS) ? a.w[oi] : 0.f;
   return e;
@@ -33,16 +47,15 @@ __device__ inline AdjEpiIn adj_epi_load(const AdjArgs& a, long long pt, int b, i
 // Output of one element of the adjoint step: row (point pt, batch b), column j, given
 // the contraction  sum_g (U_g^T (k_g * w))_j.
 template <int MODE>
-__device__ inline void adj_epi_finish(const AdjArgs& a, long long pt, int b, int j, float dot,
+__device__ inline void adj_epi_finish(const AdjArgs& a, const AdjRow& ro, int j, float dot,
                                       const AdjEpiIn& e, double& nrm) {
-  const int H = a.H, B = a.B;
   const float wn = e.kd * e.wv + dot;
-  const long long oi = (a.o.at(pt) * B + b) * H + j;
+  const long long oi = ro.o + j;
   if (MODE == STEP_RELAX) {
     a.w[oi] = wn + e.gval;
   } else if (MODE == STEP_RESID) {
     const float res = e.cur - wn - e.gval;
-    const long long ai = (a.a.at(pt) * B + b) * H + j;
+    const long long ai = ro.a + j;
     a.gc[ai] = -res;
     a.wc[ai] = e.cur;
     nrm += (double)res * (double)res;
@@ -66,6 +79,13 @@ __global__ __launch_bounds__(C::NT, 2) void adj_step_kernel(AdjArgs a) {
   const long long m0 = rt * C::TM;
   const int n0 = ct * C::TN;
   const int tid = threadIdx.x;
+  __shared__ AdjRow rowtab[C::TM];
+  if (tid < C::TM) {
+    long long r = m0 + tid;
+    if (r >= R) r = R - 1;
+    rowtab[tid] = adj_row(a, r);
+  }
+  // (visible to all waves after the barriers inside the contraction)
 
   const float* krow[C::A_CHUNKS];
   const float* wrow[C::A_CHUNKS];
@@ -114,22 +134,19 @@ __global__ __launch_bounds__(C::NT, 2) void adj_step_kernel(AdjArgs a) {
 #pragma unroll
       for (int e0 = 0; e0 < 16; e0 += EPI_BATCH) {
         AdjEpiIn ein[EPI_BATCH];
-        int pts[EPI_BATCH], bs[EPI_BATCH];
+        AdjRow ros[EPI_BATCH];
 #pragma unroll
         for (int i = 0; i < EPI_BATCH; ++i) {
           acc_coord<C>(ba, bb, e0 + i, row, col);
-          long long r = m0 + row;
-          if (r >= R) r = R - 1;        // clamped rows are loaded but never stored
-          pts[i] = (int)(r / B);
-          bs[i] = (int)(r - (long long)pts[i] * B);
-          ein[i] = adj_epi_load<MODE>(a, pts[i], bs[i], j);
+          ros[i] = rowtab[row];           // rows beyond the launch hold its last row
+          ein[i] = adj_epi_load<MODE>(a, ros[i], j);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < EPI_BATCH; ++i) {
           acc_coord<C>(ba, bb, e0 + i, row, col);
           if (m0 + row >= R) continue;
-          adj_epi_finish<MODE>(a, pts[i], bs[i], j, acc.v[0][ba][bb][e0 + i], ein[i], nrm);
+          adj_epi_finish<MODE>(a, ros[i], j, acc.v[0][ba][bb][e0 + i], ein[i], nrm);
         }
       }
     }
@@ -157,6 +174,13 @@ __global__ __launch_bounds__(C::NT, 2) void adj_step_kernel_bf16(AdjArgs a) {
   const int n0 = ct * C::TN;
   const int tid = threadIdx.x;
   const bf16_t* UT = (const bf16_t*)a.UT;
+  __shared__ AdjRow rowtab[C::TM];
+  if (tid < C::TM) {
+    long long r = m0 + tid;
+    if (r >= R) r = R - 1;
+    rowtab[tid] = adj_row(a, r);
+  }
+  // (visible to all waves after the barriers inside the contraction)
 
   const float* krow[C::A_CHUNKS];
   const float* wrow[C::A_CHUNKS];
@@ -204,22 +228,19 @@ __global__ __launch_bounds__(C::NT, 2) void adj_step_kernel_bf16(AdjArgs a) {
 #pragma unroll
       for (int e0 = 0; e0 < 16; e0 += EPI_BATCH) {
         AdjEpiIn ein[EPI_BATCH];
-        int pts[EPI_BATCH], bs[EPI_BATCH];
+        AdjRow ros[EPI_BATCH];
 #pragma unroll
         for (int i = 0; i < EPI_BATCH; ++i) {
           acc_coord<C>(ba, bb, e0 + i, row, col);
-          long long r = m0 + row;
-          if (r >= R) r = R - 1;        // clamped rows are loaded but never stored
-          pts[i] = (int)(r / B);
-          bs[i] = (int)(r - (long long)pts[i] * B);
-          ein[i] = adj_epi_load<MODE>(a, pts[i], bs[i], j);
+          ros[i] = rowtab[row];           // rows beyond the launch hold its last row
+          ein[i] = adj_epi_load<MODE>(a, ros[i], j);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < EPI_BATCH; ++i) {
           acc_coord<C>(ba, bb, e0 + i, row, col);
           if (m0 + row >= R) continue;
-          adj_epi_finish<MODE>(a, pts[i], bs[i], j, acc.v[0][ba][bb][e0 + i], ein[i], nrm);
+          adj_epi_finish<MODE>(a, ros[i], j, acc.v[0][ba][bb][e0 + i], ein[i], nrm);
         }
       }
     }
@@ -246,15 +267,13 @@ __global__ __launch_bounds__(SK_NT) void adj_skinny_kernel(AdjArgs a) {
   const bool live = bl < rows_here;
 
   const bool epi = tid < rows_here * CT && j0 + tid % CT < H;
-  long long e_pt = 0;
-  int e_b = 0, e_j = 0;
+  int e_j = 0;
+  AdjRow ero = {};
   AdjEpiIn ein = {};
   if (epi) {
-    const int r = r0 + tid / CT;
-    e_pt = r / B;
-    e_b = r - (int)e_pt * B;
+    ero = adj_row(a, r0 + tid / CT);
     e_j = j0 + tid % CT;
-    ein = adj_epi_load<MODE>(a, e_pt, e_b, e_j);
+    ein = adj_epi_load<MODE>(a, ero, e_j);
   }
 
   const float* krow = nullptr;
@@ -279,7 +298,7 @@ __global__ __launch_bounds__(SK_NT) void adj_skinny_kernel(AdjArgs a) {
 
   double nrm = 0.0;
   if (epi)
-    adj_epi_finish<MODE>(a, e_pt, e_b, e_j, skinny_sum<CT>(red, tid / CT, tid % CT, ksl), ein, nrm);
+    adj_epi_finish<MODE>(a, ero, e_j, skinny_sum<CT>(red, tid / CT, tid % CT, ksl), ein, nrm);
   if (MODE == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
 }
 

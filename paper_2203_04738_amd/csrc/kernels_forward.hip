@@ -162,6 +162,23 @@ __device__ inline float tanhf_(float a) {
 struct PhiEpiIn {
   float pr, pz, pn, h, gval, cur;
 };
+// Element offsets (column 0) of one row (level point, batch element) of a launch into
+// the arrays the epilogue touches: input state, projection, out/cur/g, and the coarse
+// (or coefficient) array.  Computed once per tile row and kept in LDS: the index
+// arithmetic (a division by B and 64-bit products) is not repeated per element.
+struct PhiRow {
+  long long in, p, o, a;
+};
+__device__ inline PhiRow phi_row(const PhiArgs& a, long long r, int aux_width) {
+  const long long pt = r / a.B;
+  const int b = (int)(r - pt * a.B);
+  PhiRow ro;
+  ro.in = (a.in.at(pt) * a.B + b) * a.H;
+  ro.p = (a.p.at(pt) * a.B + b) * (3LL * a.H);
+  ro.o = (a.o.at(pt) * a.B + b) * a.H;
+  ro.a = ((aux_width == a.H ? a.a.at(pt) : a.o.at(pt)) * a.B + b) * (long long)aux_width;
+  return ro;
+}
 struct PhiBias {          // recurrent biases of one hidden column
   float r, z, n;
 };
@@ -170,15 +187,15 @@ __device__ inline PhiBias phi_bias_load(const PhiArgs& a, int j) {
 }
 
 template <int MODE>
-__device__ inline PhiEpiIn phi_epi_load(const PhiArgs& a, long long pt, int b, int j) {
-  const int H = a.H, B = a.B;
+__device__ inline PhiEpiIn phi_epi_load(const PhiArgs& a, const PhiRow& ro, int j) {
+  const int H = a.H;
   PhiEpiIn e;
-  const float* pp = a.P + (a.p.at(pt) * B + b) * (3LL * H);
+  const float* pp = a.P + ro.p;
   e.pr = pp[j];
   e.pz = pp[H + j];
   e.pn = pp[2 * H + j];
-  e.h = a.u_in[(a.in.at(pt) * B + b) * H + j];
-  const long long oi = (a.o.at(pt) * B + b) * H + j;
+  e.h = a.u_in[ro.in + j];
+  const long long oi = ro.o + j;
   e.gval = (MODE != STEP_KAPPA && a.g) ? a.g[oi] : 0.f;
   e.cur = (MODE == STEP_RESID || MODE == STEP_RHS) ? a.u[oi] : 0.f;
   return e;
@@ -188,10 +205,10 @@ __device__ inline PhiEpiIn phi_epi_load(const PhiArgs& a, long long pt, int b, i
 // element: row (point pt, batch b), hidden column j, given the three recurrent
 // contractions (U_r h)_j, (U_z h)_j, (U_n h)_j.
 template <int MODE>
-__device__ inline void phi_epi_finish(const PhiArgs& a, long long pt, int b, int j, float sr,
+__device__ inline void phi_epi_finish(const PhiArgs& a, const PhiRow& ro, int j, float sr,
                                       float sz, float sn, const PhiEpiIn& e, const PhiBias& bh,
                                       double& nrm) {
-  const int H = a.H, B = a.B;
+  const int H = a.H;
   const float gamma = a.gamma;
   const bool implicit = a.propagator == MGRIT_PROP_IMPLICIT;
   const float h = e.h;
@@ -203,12 +220,12 @@ __device__ inline void phi_epi_finish(const PhiArgs& a, long long pt, int b, int
   const float d = 1.0f + gamma * c;
   const float rd = fast_rcp(d);
   const float hn = implicit ? (h + gamma * c * n) * rd : h + gamma * c * (n - h);
-  const long long oi = (a.o.at(pt) * B + b) * H + j;
+  const long long oi = ro.o + j;
   if (MODE == STEP_RELAX) {
     a.u[oi] = hn + e.gval;
   } else if (MODE == STEP_RESID) {
     const float res = e.cur - hn - e.gval;
-    const long long ai = (a.a.at(pt) * B + b) * H + j;
+    const long long ai = ro.a + j;
     a.gc[ai] = -res;
     a.uc[ai] = e.cur;
     nrm += (double)res * (double)res;
@@ -226,7 +243,7 @@ __device__ inline void phi_epi_finish(const PhiArgs& a, long long pt, int b, int
       dz = -gamma * (n - h);
     }
     const float kn = dn * (1.0f - n * n);
-    float* kp = a.uc + (a.o.at(pt) * B + b) * (long long)a.kappa_width;
+    float* kp = a.uc + ro.a;
     kp[j] = kn * q * rg * (1.0f - rg);
     kp[H + j] = dz * zg * (1.0f - zg);
     kp[2 * H + j] = kn * rg;
@@ -246,6 +263,13 @@ __global__ __launch_bounds__(C::NT, 2) void phi_step_kernel(PhiArgs a) {
   const long long m0 = rt * C::TM;
   const int n0 = ct * C::TN;
   const int tid = threadIdx.x;
+  __shared__ PhiRow rowtab[C::TM];
+  if (tid < C::TM) {
+    long long r = m0 + tid;
+    if (r >= R) r = R - 1;
+    rowtab[tid] = phi_row(a, r, MODE == STEP_KAPPA ? a.kappa_width : H);
+  }
+  // (visible to all waves after the barriers inside the contraction)
 
   // A rows: states of the points this tile covers (row = point*B + b); rows beyond
   // the launch are clamped to its last row and never stored.
@@ -292,23 +316,20 @@ __global__ __launch_bounds__(C::NT, 2) void phi_step_kernel(PhiArgs a) {
 #pragma unroll
       for (int e0 = 0; e0 < 16; e0 += EPI_BATCH) {
         PhiEpiIn ein[EPI_BATCH];
-        int pts[EPI_BATCH], bs[EPI_BATCH];
+        PhiRow ros[EPI_BATCH];
 #pragma unroll
         for (int i = 0; i < EPI_BATCH; ++i) {
           acc_coord<C>(ba, bb, e0 + i, row, col);
-          long long r = m0 + row;
-          if (r >= R) r = R - 1;        // clamped rows are loaded but never stored
-          pts[i] = (int)(r / B);
-          bs[i] = (int)(r - (long long)pts[i] * B);
-          ein[i] = phi_epi_load<MODE>(a, pts[i], bs[i], j);
+          ros[i] = rowtab[row];           // rows beyond the launch hold its last row
+          ein[i] = phi_epi_load<MODE>(a, ros[i], j);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < EPI_BATCH; ++i) {
           acc_coord<C>(ba, bb, e0 + i, row, col);
           if (m0 + row >= R) continue;
-          phi_epi_finish<MODE>(a, pts[i], bs[i], j, acc.v[0][ba][bb][e0 + i],
-                               acc.v[1][ba][bb][e0 + i], acc.v[2][ba][bb][e0 + i], ein[i], bh, nrm);
+          phi_epi_finish<MODE>(a, ros[i], j, acc.v[0][ba][bb][e0 + i], acc.v[1][ba][bb][e0 + i],
+                               acc.v[2][ba][bb][e0 + i], ein[i], bh, nrm);
         }
       }
     }
@@ -333,6 +354,13 @@ __global__ __launch_bounds__(C::NT, 2) void phi_step_kernel_bf16(PhiArgs a) {
   const int n0 = ct * C::TN;
   const int tid = threadIdx.x;
   const bf16_t* U = (const bf16_t*)a.U;
+  __shared__ PhiRow rowtab[C::TM];
+  if (tid < C::TM) {
+    long long r = m0 + tid;
+    if (r >= R) r = R - 1;
+    rowtab[tid] = phi_row(a, r, MODE == STEP_KAPPA ? a.kappa_width : H);
+  }
+  // (visible to all waves after the barriers inside the contraction)
 
   const float* arow[C::A_CHUNKS];
   const bf16_t* brow[C::B_CHUNKS];
@@ -377,23 +405,20 @@ __global__ __launch_bounds__(C::NT, 2) void phi_step_kernel_bf16(PhiArgs a) {
 #pragma unroll
       for (int e0 = 0; e0 < 16; e0 += EPI_BATCH) {
         PhiEpiIn ein[EPI_BATCH];
-        int pts[EPI_BATCH], bs[EPI_BATCH];
+        PhiRow ros[EPI_BATCH];
 #pragma unroll
         for (int i = 0; i < EPI_BATCH; ++i) {
           acc_coord<C>(ba, bb, e0 + i, row, col);
-          long long r = m0 + row;
-          if (r >= R) r = R - 1;        // clamped rows are loaded but never stored
-          pts[i] = (int)(r / B);
-          bs[i] = (int)(r - (long long)pts[i] * B);
-          ein[i] = phi_epi_load<MODE>(a, pts[i], bs[i], j);
+          ros[i] = rowtab[row];           // rows beyond the launch hold its last row
+          ein[i] = phi_epi_load<MODE>(a, ros[i], j);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < EPI_BATCH; ++i) {
           acc_coord<C>(ba, bb, e0 + i, row, col);
           if (m0 + row >= R) continue;
-          phi_epi_finish<MODE>(a, pts[i], bs[i], j, acc.v[0][ba][bb][e0 + i],
-                               acc.v[1][ba][bb][e0 + i], acc.v[2][ba][bb][e0 + i], ein[i], bh, nrm);
+          phi_epi_finish<MODE>(a, ros[i], j, acc.v[0][ba][bb][e0 + i], acc.v[1][ba][bb][e0 + i],
+                               acc.v[2][ba][bb][e0 + i], ein[i], bh, nrm);
         }
       }
     }
@@ -425,16 +450,14 @@ __global__ __launch_bounds__(SK_NT) void phi_skinny_kernel(PhiArgs a) {
   // this thread's output element (if any): its operands are requested first so
   // that their latency overlaps the dot products
   const bool epi = tid < rows_here * CT && j0 + tid % CT < H;
-  long long e_pt = 0;
-  int e_b = 0, e_j = 0;
+  int e_j = 0;
+  PhiRow ero = {};
   PhiEpiIn ein = {};
   PhiBias ebh = {};
   if (epi) {
-    const int r = r0 + tid / CT;
-    e_pt = r / B;
-    e_b = r - (int)e_pt * B;
+    ero = phi_row(a, r0 + tid / CT, MODE == STEP_KAPPA ? a.kappa_width : H);
     e_j = j0 + tid % CT;
-    ein = phi_epi_load<MODE>(a, e_pt, e_b, e_j);
+    ein = phi_epi_load<MODE>(a, ero, e_j);
     ebh = phi_bias_load(a, e_j);
   }
 
@@ -459,7 +482,7 @@ __global__ __launch_bounds__(SK_NT) void phi_skinny_kernel(PhiArgs a) {
   double nrm = 0.0;
   if (epi) {
     const int bl2 = tid / CT, c = tid % CT;
-    phi_epi_finish<MODE>(a, e_pt, e_b, e_j, skinny_sum<NU>(red, bl2, c, ksl),
+    phi_epi_finish<MODE>(a, ero, e_j, skinny_sum<NU>(red, bl2, c, ksl),
                          skinny_sum<NU>(red, bl2, CT + c, ksl),
                          skinny_sum<NU>(red, bl2, 2 * CT + c, ksl), ein, ebh, nrm);
   }

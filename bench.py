@@ -35,7 +35,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-serial", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
-                    help="run one 256 MiB device-to-device copy first: the known-size kernel that "
+                    help="run one 1 GiB device-to-device copy first: the known-size kernel that "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     return ap.parse_args()
 
@@ -156,11 +156,17 @@ def main():
         return (time.perf_counter() - t0) / steps
 
     if args.pmc_calibration:
-        src = torch.ones(64 << 20, device=dev)          # 256 MiB read + 256 MiB written
-        dst = torch.empty_like(src)
-        dst.copy_(src)
+        # known-size kernel for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE: a 1 GiB
+        # device-to-device copy kernel whose source has been pushed out of the 256 MB
+        # memory-side cache by a 1 GiB fill in between
+        n = 256 << 20
+        src = torch.ones(n, device=dev)
+        flush = torch.zeros(n, device=dev)
+        dst = torch.empty(n, device=dev)
         torch.cuda.synchronize()
-        del src, dst
+        torch.mul(src, 1.0, out=dst)      # an elementwise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst, flush
 
     sec = timed(mgrit_step, args.steps, args.warmup)
     resf = res_f.cpu().numpy().tolist()[:fwd_iters]
@@ -186,10 +192,20 @@ def main():
                            "algorithmic_GBps": by / ms / 1e6}
     dom = kernels.get(names[0])
     peak = MI355X_PEAK["fp32_TFLOPs"] if wl.dtype == "fp32" else MI355X_PEAK["bf16_TFLOPs"]
+    # HBM traffic of the dominant kernel per launch: measured offline with rocprofv3 --pmc
+    # (FETCH_SIZE, WRITE_SIZE; scaled by a copy kernel of known size) and recorded in profiles/
+    traffic = None
+    tf = os.path.join(ROOT, "profiles", f"phi_step_{wl.name}_hbm_traffic.txt")
+    if os.path.exists(tf):
+        for line in open(tf):
+            if line.startswith("traffic_bytes_per_launch"):
+                traffic = int(line.split("=")[1].split("#")[0])
     roofline = None
     if dom:
         roofline = {"kernel": names[0], "bound": "mfma", "achieved": dom["TFLOPs"], "peak": peak,
-                    "unit": "TFLOP/s", "frac": dom["TFLOPs"] / peak, "traffic": None,
+                    "unit": "TFLOP/s", "frac": dom["TFLOPs"] / peak, "traffic": traffic,
+                    "traffic_unit": "bytes per launch at the level-0 launch shape "
+                                    "(profiles/phi_step_%s_hbm_traffic.txt)" % wl.name,
                     "avg_launch_us": dom["avg_launch_us"],
                     "launches_per_step": dom["launches_per_step"]}
 

@@ -1,0 +1,73 @@
+"""Full-size parity: the HIP path runs the benchmark's configurations at full size in the
+launch configuration bench.py times (all cycles in one call); the oracle computes a time
+window of the result.
+
+Why a window is exact: forward MGRIT is causal in time (relaxation, residual,
+restriction, the serial coarse solve and the correction at point t only use points
+<= t), so with a zero initial guess the iterate on [0, T'] of the full problem equals the
+iterate of the problem truncated to T' steps (T' a multiple of cf^(levels-1)).  The
+adjoint cycle is the same statement in reversed time: its iterate on [T-T', T] equals that
+of the problem restricted to the last T' steps.  The linearisation states handed to the
+adjoint are seeded random values (the API accepts any states), so no oracle input comes
+from the HIP path."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mgrit_gru_oracle as orc
+from synthetic_inputs import WORKLOADS, make_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gh():
+    import gpu_harness
+    return gpu_harness
+
+
+def _P(d):
+    return d["W"], d["U"], d["b_i"], d["b_h"]
+
+
+@pytest.mark.parametrize("name,window", [("C2", 1024), ("C3", 128), ("C4", 128), ("C5", 256)])
+def test_full_size_forward_window_and_serial_prefix(gh, name, window):
+    wl = WORKLOADS[name]
+    d = make_inputs(wl)
+    tol = 1e-5 if wl.dtype == "fp32" else 2e-2
+    iters = min(wl.fwd_iters, 2)
+    run = gh.GpuRun(d, cf=wl.cf, levels=wl.levels, dtype=wl.dtype)
+    its, res = run.forward_iterates(iters, per_call=iters)        # one call, as bench.py does
+    got = its[-1][:window + 1]
+    xs = d["x"][:window]
+    ref, rres = orc.mgrit_forward(*_P(d), xs, d["h0"], np.zeros((window + 1, wl.B, wl.H)),
+                                  wl.cf, wl.levels, iters)
+    assert gh.rel_err(got, ref) <= tol
+    if window == wl.T:      # the residual norm is a sum over all time points
+        for g, r in zip(res, rres):
+            assert abs(g - r) <= 1e-4 * r + 2e-6 * np.sqrt(wl.T)
+    # serial scan kernel at full size, same window (the scan is causal too)
+    sref = orc.serial_scan(*_P(d), xs, d["h0"])
+    sgot = run.serial_scan()
+    assert gh.rel_err(sgot[:window + 1], sref) <= tol
+    # converged check on what is unique at any size: the exactness front of the cycle
+    front = (iters + 1) * wl.cf - 1
+    assert gh.rel_err(its[-1][:front + 1], sgot[:front + 1]) <= 10 * tol
+
+
+@pytest.mark.parametrize("name,window", [("C3", 128), ("C4", 128), ("C5", 256)])
+def test_full_size_backward_window(gh, name, window):
+    wl = WORKLOADS[name]
+    d = make_inputs(wl)
+    tol = 1e-5 if wl.dtype == "fp32" else 2e-2
+    iters = wl.bwd_iters
+    rng = np.random.default_rng(99)
+    h = np.tanh(rng.standard_normal((wl.T + 1, wl.B, wl.H))).astype(np.float32)
+    run = gh.GpuRun(d, cf=wl.cf, levels=wl.levels, dtype=wl.dtype)
+    wits, _, grads = run.backward_iterates(h, iters, per_call=iters)
+    got = wits[-1][wl.T - window:]
+    out = orc.mgrit_backward(*_P(d), d["x"][wl.T - window:], h[wl.T - window:], d["dL_dhT"],
+                             np.zeros((window + 1, wl.B, wl.H)), wl.cf, wl.levels, iters)
+    assert gh.rel_err(got, out[0]) <= tol
+    for g in grads:
+        assert np.all(np.isfinite(g))

@@ -173,7 +173,11 @@ __device__ inline void gemm_nt_tile(Acc<C>& acc, int K, LoadA loadA, LoadB loadB
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       if (c + 1 < NC) read_frags(cur, c + 1, fa[(c + 1) & 1], fb[(c + 1) & 1]);
+      // keep the LDS reads of the next k-group ahead of this group's MFMAs (the
+      // scheduler would otherwise sink them next to their first use)
+      __builtin_amdgcn_sched_barrier(0);
       mma(fa[c & 1], fb[c & 1]);
+      __builtin_amdgcn_sched_barrier(0);
     }
     __builtin_amdgcn_sched_barrier(0);
     if (C::NBUF == 2) {

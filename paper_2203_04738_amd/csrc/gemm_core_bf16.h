@@ -168,7 +168,9 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       if (c + 1 < NC) read_frags(c + 1, fa[(c + 1) & 1], fb[(c + 1) & 1]);
+      __builtin_amdgcn_sched_barrier(0);
       mma(fa[c & 1], fb[c & 1]);
+      __builtin_amdgcn_sched_barrier(0);
     }
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();

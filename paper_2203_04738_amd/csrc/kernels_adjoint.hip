@@ -252,21 +252,28 @@ __global__ __launch_bounds__(C::NT, 2) void adj_step_kernel_bf16(AdjArgs a) {
 }
 
 // Few-row variant (coarsest-level solve, serial BPTT): see skinny.h
-template <int CT, int MODE, class WT>
-__global__ __launch_bounds__(SK_NT) void adj_skinny_kernel(AdjArgs a) {
-  __shared__ float red[SK_MAXROWS * CT * (SK_NT / 64)];
-  const int H = a.H, B = a.B, K = 3 * a.H;
-  const int R = a.nk * B;
-  const int r0 = blockIdx.y * SK_MAXROWS;
-  const int rows_here = min(SK_MAXROWS, R - r0);
-  const int Rp = sk_row_pad(rows_here);
-  const int ksl = SK_NT / Rp;
-  const int tid = threadIdx.x;
-  const int ks = tid % ksl, bl = tid / ksl;
-  const int j0 = blockIdx.x * CT;
-  const bool live = bl < rows_here;
+template <int CT>
+struct AdjSkMaxNT {
+  static constexpr int value = CT >= 8 ? 512 : SK_MAXNT;
+};
 
-  const bool epi = tid < rows_here * CT && j0 + tid % CT < H;
+template <int CT, int MODE, class WT>
+__global__ __launch_bounds__(AdjSkMaxNT<CT>::value) void adj_skinny_kernel(AdjArgs a,
+                                                                           int rows_block) {
+  constexpr int VP = sk_pow2_ceil(SK_RR * CT);
+  __shared__ float red[(SK_MAXNT / 64) * VP];
+  const int H = a.H, K = 3 * a.H;
+  const int R = a.nk * a.B;
+  const int r0 = blockIdx.y * rows_block;
+  const int rows_here = min(rows_block, R - r0);
+  const SkGeom geo = sk_geom(rows_block, K);
+  const int ksl = geo.ksl;
+  const int tid = threadIdx.x;
+  const int ks = tid & (ksl - 1), rg = tid / ksl;
+  const int j0 = blockIdx.x * CT;
+
+  const int n_out = rows_here * CT;
+  const bool epi = tid < n_out && j0 + tid % CT < H;
   int e_j = 0;
   AdjRow ero = {};
   AdjEpiIn ein = {};
@@ -276,29 +283,42 @@ __global__ __launch_bounds__(SK_NT) void adj_skinny_kernel(AdjArgs a) {
     ein = adj_epi_load<MODE>(a, ero, e_j);
   }
 
-  const float* krow = nullptr;
-  const float* wrow = nullptr;
-  if (live) {
-    const int r = r0 + bl;
-    const long long pt = r / B;
-    const int b = r - (int)pt * B;
-    krow = a.kap + (a.k.at(pt) * B + b) * (long long)a.kw;
-    wrow = a.w_in + (a.in.at(pt) * B + b) * H;
+  // rows beyond the block are clamped to its last row (their sums are never used)
+  const float* krow[SK_RR];
+  const float* wrow[SK_RR];
+#pragma unroll
+  for (int i = 0; i < SK_RR; ++i) {
+    const AdjRow ro = adj_row(a, r0 + min(rg * SK_RR + i, rows_here - 1));
+    krow[i] = a.kap + ro.k;
+    wrow[i] = a.w_in + ro.in;
   }
   const WT* urow[CT];
 #pragma unroll
   for (int u = 0; u < CT; ++u) urow[u] = (const WT*)a.UT + (long long)min(j0 + u, H - 1) * K;
-  float acc[CT];
-  skinny_partial<CT, WT>(acc, K, ks, ksl, live, urow, [&](int k) {
+  float acc[SK_RR][CT];
+  skinny_dot<CT, WT>(acc, K, ks, ksl, urow, [&](int i, int k) {
     const int kk = k >= 2 * H ? k - 2 * H : (k >= H ? k - H : k);
-    return ldg4(krow + k) * ldg4(wrow + kk);
+    return ldg4(krow[i] + k) * ldg4(wrow[i] + kk);
   });
-  skinny_reduce<CT>(acc, red, bl, ks, ksl);
+  float v[VP];
+#pragma unroll
+  for (int q = 0; q < VP; ++q) v[q] = q < SK_RR * CT ? acc[q / CT][q % CT] : 0.f;
+  skinny_reduce<VP>(v, red, rg, ks, ksl);
   __syncthreads();
 
   double nrm = 0.0;
-  if (epi)
-    adj_epi_finish<MODE>(a, ero, e_j, skinny_sum<CT>(red, tid / CT, tid % CT, ksl), ein, nrm);
+  for (int e = tid; e < n_out; e += blockDim.x) {
+    const int row = e / CT, c = e % CT;
+    const int j = j0 + c;
+    if (j >= H) continue;
+    const float dot = skinny_sum<VP>(red, row / SK_RR, (row % SK_RR) * CT + c, ksl);
+    if (e == tid && epi) {
+      adj_epi_finish<MODE>(a, ero, e_j, dot, ein, nrm);
+    } else {   // more outputs than threads (tiny K only)
+      const AdjRow ro = adj_row(a, r0 + row);
+      adj_epi_finish<MODE>(a, ro, j, dot, adj_epi_load<MODE>(a, ro, j), nrm);
+    }
+  }
   if (MODE == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
 }
 
@@ -332,12 +352,21 @@ static void launch_adj_cfg(const AdjArgs& a, hipStream_t s) {
   }
 }
 
+// Rows per workgroup of the few-row adjoint step: every workgroup streams the
+// coefficient and adjoint rows of its row block (24H bytes per row), so the block is
+// kept small and the workgroup takes more columns instead.
+constexpr int ADJ_SK_ROWS = 8;
+
+static int adj_sk_rows(long long R) { return R < ADJ_SK_ROWS ? (int)R : ADJ_SK_ROWS; }
+
 template <int CT, int MODE>
 static void launch_adj_skinny_mode(const AdjArgs& a, dim3 grid, hipStream_t s) {
+  const int rb = adj_sk_rows((long long)a.nk * a.B);
+  const dim3 block(sk_geom(rb, 3 * a.H).nt);
   if (a.bf16)
-    hipLaunchKernelGGL((adj_skinny_kernel<CT, MODE, bf16_t>), grid, dim3(SK_NT), 0, s, a);
+    hipLaunchKernelGGL((adj_skinny_kernel<CT, MODE, bf16_t>), grid, block, 0, s, a, rb);
   else
-    hipLaunchKernelGGL((adj_skinny_kernel<CT, MODE, float>), grid, dim3(SK_NT), 0, s, a);
+    hipLaunchKernelGGL((adj_skinny_kernel<CT, MODE, float>), grid, block, 0, s, a, rb);
 }
 
 template <int CT>
@@ -357,9 +386,16 @@ hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s) {
   const int kind = R <= 2 * SK_MAXROWS ? 5 : 1;
   prof_begin(kind, s);
   if (R <= 2 * SK_MAXROWS) {
-    const int ct = a.H >= 512 ? 4 : (a.H >= 256 ? 2 : 1);
-    dim3 grid((unsigned)((a.H + ct - 1) / ct), (unsigned)((R + SK_MAXROWS - 1) / SK_MAXROWS));
-    if (ct == 4)
+    // columns per workgroup: about 256 workgroups in all
+    const int rb = adj_sk_rows(R);
+    const int nrb = (int)((R + rb - 1) / rb);
+    const long long hw = (long long)a.H * nrb;
+    int ct = hw >= 2048 ? 8 : (hw >= 1024 ? 4 : (hw >= 512 ? 2 : 1));
+    if (ct == 8 && sk_geom(rb, 3 * a.H).nt > AdjSkMaxNT<8>::value) ct = 4;
+    dim3 grid((unsigned)((a.H + ct - 1) / ct), (unsigned)nrb);
+    if (ct == 8)
+      launch_adj_skinny<8>(a, grid, s);
+    else if (ct == 4)
       launch_adj_skinny<4>(a, grid, s);
     else if (ct == 2)
       launch_adj_skinny<2>(a, grid, s);

@@ -432,41 +432,53 @@ __global__ __launch_bounds__(C::NT, 2) void phi_step_kernel_bf16(PhiArgs a) {
 // ---------------------------------------------------------------------------
 // Few-row variant (coarsest-level propagation, serial scan): see skinny.h
 // ---------------------------------------------------------------------------
+// Workgroups with many columns keep RR x 3 CT sums plus their operands in registers:
+// those instantiations are limited to 512 threads.
+template <int CT>
+struct PhiSkMaxNT {
+  static constexpr int value = CT >= 4 ? 512 : SK_MAXNT;
+};
+
 template <int CT, int MODE, class WT>
-__global__ __launch_bounds__(SK_NT) void phi_skinny_kernel(PhiArgs a) {
+__global__ __launch_bounds__(PhiSkMaxNT<CT>::value) void phi_skinny_kernel(PhiArgs a,
+                                                                           int rows_block) {
   constexpr int NU = 3 * CT;
-  __shared__ float red[SK_MAXROWS * NU * (SK_NT / 64)];
-  const int H = a.H, B = a.B;
-  const int R = a.nk * B;
-  const int r0 = blockIdx.y * SK_MAXROWS;
-  const int rows_here = min(SK_MAXROWS, R - r0);
-  const int Rp = sk_row_pad(rows_here);
-  const int ksl = SK_NT / Rp;
+  constexpr int VP = sk_pow2_ceil(SK_RR * NU);
+  __shared__ float red[(SK_MAXNT / 64) * VP];
+  const int H = a.H;
+  const int R = a.nk * a.B;
+  const int r0 = blockIdx.y * rows_block;
+  const int rows_here = min(rows_block, R - r0);
+  const SkGeom geo = sk_geom(rows_block, H);
+  const int ksl = geo.ksl;
   const int tid = threadIdx.x;
-  const int ks = tid % ksl, bl = tid / ksl;
+  const int ks = tid & (ksl - 1), rg = tid / ksl;
   const int j0 = blockIdx.x * CT;
-  const bool live = bl < rows_here;
+  const int aux_w = MODE == STEP_KAPPA ? a.kappa_width : H;
 
   // this thread's output element (if any): its operands are requested first so
   // that their latency overlaps the dot products
-  const bool epi = tid < rows_here * CT && j0 + tid % CT < H;
+  const int n_out = rows_here * CT;
+  const bool epi = tid < n_out && j0 + tid % CT < H;
   int e_j = 0;
   PhiRow ero = {};
   PhiEpiIn ein = {};
   PhiBias ebh = {};
   if (epi) {
-    ero = phi_row(a, r0 + tid / CT, MODE == STEP_KAPPA ? a.kappa_width : H);
+    ero = phi_row(a, r0 + tid / CT, aux_w);
     e_j = j0 + tid % CT;
     ein = phi_epi_load<MODE>(a, ero, e_j);
     ebh = phi_bias_load(a, e_j);
   }
 
-  const float* hrow = nullptr;
-  if (live) {
-    const int r = r0 + bl;
-    const long long pt = r / B;
-    const int b = r - (int)pt * B;
-    hrow = a.u_in + (a.in.at(pt) * B + b) * H;
+  // rows beyond the block are clamped to its last row (their sums are never used)
+  const float* hrow[SK_RR];
+#pragma unroll
+  for (int i = 0; i < SK_RR; ++i) {
+    const int r = r0 + min(rg * SK_RR + i, rows_here - 1);
+    const long long pt = r / a.B;
+    const int b = r - (int)pt * a.B;
+    hrow[i] = a.u_in + (a.in.at(pt) * a.B + b) * H;
   }
   const WT* urow[NU];
 #pragma unroll
@@ -474,17 +486,30 @@ __global__ __launch_bounds__(SK_NT) void phi_skinny_kernel(PhiArgs a) {
     const int g = u / CT, j = min(j0 + u % CT, H - 1);
     urow[u] = (const WT*)a.U + ((long long)g * H + j) * H;
   }
-  float acc[NU];
-  skinny_partial<NU, WT>(acc, H, ks, ksl, live, urow, [&](int k) { return ldg4(hrow + k); });
-  skinny_reduce<NU>(acc, red, bl, ks, ksl);
+  float acc[SK_RR][NU];
+  skinny_dot<NU, WT>(acc, H, ks, ksl, urow, [&](int i, int k) { return ldg4(hrow[i] + k); });
+  float v[VP];
+#pragma unroll
+  for (int q = 0; q < VP; ++q) v[q] = q < SK_RR * NU ? acc[q / NU][q % NU] : 0.f;
+  skinny_reduce<VP>(v, red, rg, ks, ksl);
   __syncthreads();
 
   double nrm = 0.0;
-  if (epi) {
-    const int bl2 = tid / CT, c = tid % CT;
-    phi_epi_finish<MODE>(a, ero, e_j, skinny_sum<NU>(red, bl2, c, ksl),
-                         skinny_sum<NU>(red, bl2, CT + c, ksl),
-                         skinny_sum<NU>(red, bl2, 2 * CT + c, ksl), ein, ebh, nrm);
+  for (int e = tid; e < n_out; e += blockDim.x) {
+    const int row = e / CT, c = e % CT;
+    const int j = j0 + c;
+    if (j >= H) continue;
+    const int grp = row / SK_RR, base = (row % SK_RR) * NU;
+    const float sr = skinny_sum<VP>(red, grp, base + c, ksl);
+    const float sz = skinny_sum<VP>(red, grp, base + CT + c, ksl);
+    const float sn = skinny_sum<VP>(red, grp, base + 2 * CT + c, ksl);
+    if (e == tid && epi) {
+      phi_epi_finish<MODE>(a, ero, e_j, sr, sz, sn, ein, ebh, nrm);
+    } else {   // more outputs than threads (tiny K only)
+      const PhiRow ro = phi_row(a, r0 + row, aux_w);
+      phi_epi_finish<MODE>(a, ro, j, sr, sz, sn, phi_epi_load<MODE>(a, ro, j), phi_bias_load(a, j),
+                           nrm);
+    }
   }
   if (MODE == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
 }
@@ -524,12 +549,18 @@ static void launch_phi_cfg(const PhiArgs& a, hipStream_t s) {
   }
 }
 
+constexpr int PHI_SK_ROWS = 32;   // rows per workgroup of the few-row forward step
+
+static int phi_sk_rows(long long R) { return R < PHI_SK_ROWS ? (int)R : PHI_SK_ROWS; }
+
 template <int CT, int MODE>
 static void launch_phi_skinny_mode(const PhiArgs& a, dim3 grid, hipStream_t s) {
+  const int rb = phi_sk_rows((long long)a.nk * a.B);
+  const dim3 block(sk_geom(rb, a.H).nt);
   if (a.bf16)
-    hipLaunchKernelGGL((phi_skinny_kernel<CT, MODE, bf16_t>), grid, dim3(SK_NT), 0, s, a);
+    hipLaunchKernelGGL((phi_skinny_kernel<CT, MODE, bf16_t>), grid, block, 0, s, a, rb);
   else
-    hipLaunchKernelGGL((phi_skinny_kernel<CT, MODE, float>), grid, dim3(SK_NT), 0, s, a);
+    hipLaunchKernelGGL((phi_skinny_kernel<CT, MODE, float>), grid, block, 0, s, a, rb);
 }
 
 template <int CT>
@@ -549,8 +580,12 @@ hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s) {
   const int kind = R <= 2 * SK_MAXROWS ? 4 : 0;
   prof_begin(kind, s);
   if (R <= 2 * SK_MAXROWS) {
-    const int ct = a.H >= 1024 ? 4 : (a.H >= 512 ? 2 : 1);
-    dim3 grid((unsigned)((a.H + ct - 1) / ct), (unsigned)((R + SK_MAXROWS - 1) / SK_MAXROWS));
+    // columns per workgroup: about 256 workgroups in all
+    const int rb = phi_sk_rows(R);
+    const int nrb = (int)((R + rb - 1) / rb);
+    int ct = a.H * nrb >= 1024 ? 4 : (a.H * nrb >= 512 ? 2 : 1);
+    if (ct == 4 && sk_geom(rb, a.H).nt > PhiSkMaxNT<4>::value) ct = 2;
+    dim3 grid((unsigned)((a.H + ct - 1) / ct), (unsigned)nrb);
     if (ct == 4)
       launch_phi_skinny<4>(a, grid, s);
     else if (ct == 2)

@@ -64,6 +64,54 @@ __device__ inline void adj_epi_finish(const AdjArgs& a, const AdjRow& ro, int j,
   }
 }
 
+// Epilogue of one MFMA tile, batches of EPI_BATCH elements with the operands of the
+// next batch requested before the current one is finished.
+template <class C, int MODE>
+__device__ inline void adj_tile_epilogue(const AdjArgs& a, Acc<C>& acc, const AdjRow* rowtab,
+                                         long long m0, int n0, long long R, double& nrm) {
+  constexpr int NPB = 16 / EPI_BATCH;
+  constexpr int NBATCH = C::BM * C::BN * NPB;
+  const int H = a.H;
+  AdjEpiIn ein[2][EPI_BATCH];
+  AdjRow ros[2][EPI_BATCH];
+  int jcol[C::BN];
+#pragma unroll
+  for (int bb = 0; bb < C::BN; ++bb) {
+    int row, col;
+    acc_coord<C>(0, bb, 0, row, col);
+    jcol[bb] = n0 + col;
+  }
+  auto load = [&](int q, int slot) {
+    const int ba = q / (C::BN * NPB), bb = (q / NPB) % C::BN, e0 = (q % NPB) * EPI_BATCH;
+    const int j = jcol[bb] < H ? jcol[bb] : H - 1;      // clamped columns are never stored
+#pragma unroll
+    for (int i = 0; i < EPI_BATCH; ++i) {
+      int row, col;
+      acc_coord<C>(ba, bb, e0 + i, row, col);
+      ros[slot][i] = rowtab[row];
+      ein[slot][i] = adj_epi_load<MODE>(a, ros[slot][i], j);
+    }
+  };
+  load(0, 0);
+#pragma unroll
+  for (int q = 0; q < NBATCH; ++q) {
+    if (q + 1 < NBATCH) load(q + 1, (q + 1) & 1);
+    __builtin_amdgcn_sched_barrier(0);
+    const int ba = q / (C::BN * NPB), bb = (q / NPB) % C::BN, e0 = (q % NPB) * EPI_BATCH;
+    if (jcol[bb] < H) {
+#pragma unroll
+      for (int i = 0; i < EPI_BATCH; ++i) {
+        int row, col;
+        acc_coord<C>(ba, bb, e0 + i, row, col);
+        if (m0 + row < R)
+          adj_epi_finish<MODE>(a, ros[q & 1][i], jcol[bb], acc.v[0][ba][bb][e0 + i], ein[q & 1][i],
+                               nrm);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 struct KapW {
   floatx4 kap, w;
 };
@@ -121,35 +169,7 @@ __global__ __launch_bounds__(C::NT, 2) void adj_step_kernel(AdjArgs a) {
     gemm_nt_tile<C, true>(acc, K, la, lb, fa, Identity4(), lds);
 
   double nrm = 0.0;
-#pragma unroll
-  for (int ba = 0; ba < C::BM; ++ba)
-#pragma unroll
-    for (int bb = 0; bb < C::BN; ++bb) {
-      int row, col;
-      acc_coord<C>(ba, bb, 0, row, col);
-      const int j = n0 + col;
-      if (j >= H) continue;
-      // EPI_BATCH elements at a time: all their operands are requested before the
-      // first is consumed
-#pragma unroll
-      for (int e0 = 0; e0 < 16; e0 += EPI_BATCH) {
-        AdjEpiIn ein[EPI_BATCH];
-        AdjRow ros[EPI_BATCH];
-#pragma unroll
-        for (int i = 0; i < EPI_BATCH; ++i) {
-          acc_coord<C>(ba, bb, e0 + i, row, col);
-          ros[i] = rowtab[row];           // rows beyond the launch hold its last row
-          ein[i] = adj_epi_load<MODE>(a, ros[i], j);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < EPI_BATCH; ++i) {
-          acc_coord<C>(ba, bb, e0 + i, row, col);
-          if (m0 + row >= R) continue;
-          adj_epi_finish<MODE>(a, ros[i], j, acc.v[0][ba][bb][e0 + i], ein[i], nrm);
-        }
-      }
-    }
+  adj_tile_epilogue<C, MODE>(a, acc, rowtab, m0, n0, R, nrm);
   if (MODE == STEP_RESID && a.norm) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) nrm += __shfl_down(nrm, off, 64);
@@ -215,35 +235,7 @@ __global__ __launch_bounds__(C::NT, 2) void adj_step_kernel_bf16(AdjArgs a) {
     gemm_nt_tile_bf16<C, true>(acc, K, la, lb, fa, lds);
 
   double nrm = 0.0;
-#pragma unroll
-  for (int ba = 0; ba < C::BM; ++ba)
-#pragma unroll
-    for (int bb = 0; bb < C::BN; ++bb) {
-      int row, col;
-      acc_coord<C>(ba, bb, 0, row, col);
-      const int j = n0 + col;
-      if (j >= H) continue;
-      // EPI_BATCH elements at a time: all their operands are requested before the
-      // first is consumed
-#pragma unroll
-      for (int e0 = 0; e0 < 16; e0 += EPI_BATCH) {
-        AdjEpiIn ein[EPI_BATCH];
-        AdjRow ros[EPI_BATCH];
-#pragma unroll
-        for (int i = 0; i < EPI_BATCH; ++i) {
-          acc_coord<C>(ba, bb, e0 + i, row, col);
-          ros[i] = rowtab[row];           // rows beyond the launch hold its last row
-          ein[i] = adj_epi_load<MODE>(a, ros[i], j);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < EPI_BATCH; ++i) {
-          acc_coord<C>(ba, bb, e0 + i, row, col);
-          if (m0 + row >= R) continue;
-          adj_epi_finish<MODE>(a, ros[i], j, acc.v[0][ba][bb][e0 + i], ein[i], nrm);
-        }
-      }
-    }
+  adj_tile_epilogue<C, MODE>(a, acc, rowtab, m0, n0, R, nrm);
   if (MODE == STEP_RESID && a.norm) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) nrm += __shfl_down(nrm, off, 64);

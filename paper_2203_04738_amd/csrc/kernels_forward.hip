@@ -252,6 +252,58 @@ __device__ inline void phi_epi_finish(const PhiArgs& a, const PhiRow& ro, int j,
   }
 }
 
+// Epilogue of one MFMA tile: every lane walks its accumulator elements in batches of
+// EPI_BATCH; the operands of batch q+1 are requested before batch q is finished, so
+// memory latency overlaps the gate arithmetic.
+template <class C, int MODE>
+__device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const PhiRow* rowtab,
+                                         long long m0, int n0, long long R, double& nrm) {
+  constexpr int NPB = 16 / EPI_BATCH;                   // batches per 32x32 block
+  constexpr int NBATCH = C::BM * C::BN * NPB;
+  const int H = a.H;
+  PhiEpiIn ein[2][EPI_BATCH];
+  PhiRow ros[2][EPI_BATCH];
+  PhiBias bh[C::BN];
+  int jcol[C::BN];
+#pragma unroll
+  for (int bb = 0; bb < C::BN; ++bb) {
+    int row, col;
+    acc_coord<C>(0, bb, 0, row, col);
+    jcol[bb] = n0 + col;
+    bh[bb] = phi_bias_load(a, jcol[bb] < H ? jcol[bb] : H - 1);
+  }
+  auto load = [&](int q, int slot) {
+    const int ba = q / (C::BN * NPB), bb = (q / NPB) % C::BN, e0 = (q % NPB) * EPI_BATCH;
+    const int j = jcol[bb] < H ? jcol[bb] : H - 1;      // clamped columns are never stored
+#pragma unroll
+    for (int i = 0; i < EPI_BATCH; ++i) {
+      int row, col;
+      acc_coord<C>(ba, bb, e0 + i, row, col);
+      ros[slot][i] = rowtab[row];                        // rows beyond the launch hold its last row
+      ein[slot][i] = phi_epi_load<MODE>(a, ros[slot][i], j);
+    }
+  };
+  load(0, 0);
+#pragma unroll
+  for (int q = 0; q < NBATCH; ++q) {
+    if (q + 1 < NBATCH) load(q + 1, (q + 1) & 1);
+    __builtin_amdgcn_sched_barrier(0);
+    const int ba = q / (C::BN * NPB), bb = (q / NPB) % C::BN, e0 = (q % NPB) * EPI_BATCH;
+    if (jcol[bb] < H) {
+#pragma unroll
+      for (int i = 0; i < EPI_BATCH; ++i) {
+        int row, col;
+        acc_coord<C>(ba, bb, e0 + i, row, col);
+        if (m0 + row < R)
+          phi_epi_finish<MODE>(a, ros[q & 1][i], jcol[bb], acc.v[0][ba][bb][e0 + i],
+                               acc.v[1][ba][bb][e0 + i], acc.v[2][ba][bb][e0 + i], ein[q & 1][i],
+                               bh[bb], nrm);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 template <class C, int MODE>
 __global__ __launch_bounds__(C::NT, 2) void phi_step_kernel(PhiArgs a) {
   __shared__ __attribute__((aligned(16))) float lds[C::LDS_FLOATS];
@@ -302,37 +354,7 @@ __global__ __launch_bounds__(C::NT, 2) void phi_step_kernel(PhiArgs a) {
     gemm_nt_tile<C, true>(acc, H, la, lb, Identity4(), Identity4(), lds);
 
   double nrm = 0.0;
-#pragma unroll
-  for (int ba = 0; ba < C::BM; ++ba)
-#pragma unroll
-    for (int bb = 0; bb < C::BN; ++bb) {
-      int row, col;
-      acc_coord<C>(ba, bb, 0, row, col);
-      const int j = n0 + col;
-      if (j >= H) continue;
-      const PhiBias bh = phi_bias_load(a, j);
-      // EPI_BATCH elements at a time: their operands are all requested before the
-      // first is consumed, so a block pays 16/EPI_BATCH memory round trips, not sixteen
-#pragma unroll
-      for (int e0 = 0; e0 < 16; e0 += EPI_BATCH) {
-        PhiEpiIn ein[EPI_BATCH];
-        PhiRow ros[EPI_BATCH];
-#pragma unroll
-        for (int i = 0; i < EPI_BATCH; ++i) {
-          acc_coord<C>(ba, bb, e0 + i, row, col);
-          ros[i] = rowtab[row];           // rows beyond the launch hold its last row
-          ein[i] = phi_epi_load<MODE>(a, ros[i], j);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < EPI_BATCH; ++i) {
-          acc_coord<C>(ba, bb, e0 + i, row, col);
-          if (m0 + row >= R) continue;
-          phi_epi_finish<MODE>(a, ros[i], j, acc.v[0][ba][bb][e0 + i], acc.v[1][ba][bb][e0 + i],
-                               acc.v[2][ba][bb][e0 + i], ein[i], bh, nrm);
-        }
-      }
-    }
+  phi_tile_epilogue<C, MODE>(a, acc, rowtab, m0, n0, R, nrm);
   if (MODE == STEP_RESID && a.norm) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) nrm += __shfl_down(nrm, off, 64);
@@ -391,37 +413,7 @@ __global__ __launch_bounds__(C::NT, 2) void phi_step_kernel_bf16(PhiArgs a) {
     gemm_nt_tile_bf16<C, true>(acc, H, la, lb, fa, lds);
 
   double nrm = 0.0;
-#pragma unroll
-  for (int ba = 0; ba < C::BM; ++ba)
-#pragma unroll
-    for (int bb = 0; bb < C::BN; ++bb) {
-      int row, col;
-      acc_coord<C>(ba, bb, 0, row, col);
-      const int j = n0 + col;
-      if (j >= H) continue;
-      const PhiBias bh = phi_bias_load(a, j);
-      // EPI_BATCH elements at a time: their operands are all requested before the
-      // first is consumed, so a block pays 16/EPI_BATCH memory round trips, not sixteen
-#pragma unroll
-      for (int e0 = 0; e0 < 16; e0 += EPI_BATCH) {
-        PhiEpiIn ein[EPI_BATCH];
-        PhiRow ros[EPI_BATCH];
-#pragma unroll
-        for (int i = 0; i < EPI_BATCH; ++i) {
-          acc_coord<C>(ba, bb, e0 + i, row, col);
-          ros[i] = rowtab[row];           // rows beyond the launch hold its last row
-          ein[i] = phi_epi_load<MODE>(a, ros[i], j);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < EPI_BATCH; ++i) {
-          acc_coord<C>(ba, bb, e0 + i, row, col);
-          if (m0 + row >= R) continue;
-          phi_epi_finish<MODE>(a, ros[i], j, acc.v[0][ba][bb][e0 + i], acc.v[1][ba][bb][e0 + i],
-                               acc.v[2][ba][bb][e0 + i], ein[i], bh, nrm);
-        }
-      }
-    }
+  phi_tile_epilogue<C, MODE>(a, acc, rowtab, m0, n0, R, nrm);
   if (MODE == STEP_RESID && a.norm) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) nrm += __shfl_down(nrm, off, 64);

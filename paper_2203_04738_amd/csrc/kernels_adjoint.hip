@@ -315,10 +315,10 @@ __global__ __launch_bounds__(AdjSkMaxNT<CT>::value) void adj_skinny_kernel(AdjAr
 }
 
 typedef TileCfg<2, 2, 2, 2, 1> AdjBig;    // 128 x 128, 256 threads
-typedef TileCfg<2, 1, 1, 1, 1> AdjMid;    //  64 x 32, 128 threads
+typedef TileCfg<2, 2, 1, 1, 1> AdjMid;    //  64 x 64, 256 threads
 typedef TileCfg<1, 1, 1, 1, 1> AdjSmall;  //  32 x 32, 64 threads
 typedef TileCfgB<2, 2, 2, 2, 1, true> AdjBigB;
-typedef TileCfgB<2, 1, 1, 1, 1, true> AdjMidB;
+typedef TileCfgB<2, 2, 1, 1, 1, true> AdjMidB;
 typedef TileCfgB<1, 1, 1, 1, 1, true> AdjSmallB;
 
 template <class C, class CB>

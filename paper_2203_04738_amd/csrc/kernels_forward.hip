@@ -507,10 +507,10 @@ __global__ __launch_bounds__(PhiSkMaxNT<CT>::value) void phi_skinny_kernel(PhiAr
 }
 
 typedef TileCfg<2, 2, 2, 1, 3> PhiBig;    // 128 rows x 64 hidden columns (x3 gates), 256 threads
-typedef TileCfg<2, 1, 1, 1, 3> PhiMid;    //  64 rows x 32 hidden columns, 128 threads
+typedef TileCfg<2, 2, 1, 1, 3> PhiMid;    //  64 rows x 64 hidden columns, 256 threads
 typedef TileCfg<1, 1, 1, 1, 3> PhiSmall;  //  32 rows x 32 hidden columns, 64 threads
 typedef TileCfgB<2, 2, 2, 1, 3, true> PhiBigB;
-typedef TileCfgB<2, 1, 1, 1, 3, true> PhiMidB;
+typedef TileCfgB<2, 2, 1, 1, 3, true> PhiMidB;
 typedef TileCfgB<1, 1, 1, 1, 3, true> PhiSmallB;
 
 #define MG_LAUNCH_BY_MODE(KERNEL, ...)                                                   \

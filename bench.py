@@ -32,6 +32,13 @@ def parse():
     ap.add_argument("--workload", default="C3", help="C1..C5 (BASELINE.json configs in order)")
     ap.add_argument("--fwd-iters", type=int, default=None)
     ap.add_argument("--bwd-iters", type=int, default=None)
+    ap.add_argument("--fine-relax", choices=["FCF", "F"], default="FCF",
+                    help="relaxation on the fine level (Alg. 2 as printed uses FCF; the paper notes "
+                         "that F-relaxation is often used there)")
+    ap.add_argument("--until-converged", action="store_true",
+                    help="forward only: first find the number of cycles after which the level-0 "
+                         "residual, relative to the norm of the serial solution, is below 1e-8 or has "
+                         "stopped decreasing (fp32 floor), then time that many cycles")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-serial", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -40,7 +47,7 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(wl, fwd_iters, bwd_iters):
+def cpu_baseline(wl, fwd_iters, bwd_iters, fcf=True):
     """The CPU oracle as it stands, timed on the reduced twin of the workload
     (same B, D, H, cf, levels; T = 8*cf^(levels-1)); work is linear in T."""
     import numpy as np
@@ -56,10 +63,12 @@ def cpu_baseline(wl, fwd_iters, bwd_iters):
         P = (d["W"], d["U"], d["b_i"], d["b_h"])
         z = np.zeros((tw.T + 1, tw.B, tw.H))
         t0 = time.perf_counter()
-        h, _ = orc.mgrit_forward(*P, d["x"], d["h0"], z, tw.cf, tw.levels, fwd_iters)
+        h, _ = orc.mgrit_forward(*P, d["x"], d["h0"], z, tw.cf, tw.levels, fwd_iters,
+                                 fine_relax_fcf=fcf)
         if bwd_iters > 0:
             _, g = orc.cross_entropy_head(h[-1], d["W_o"], d["b_o"], d["labels"])
-            orc.mgrit_backward(*P, d["x"], h, g, z, tw.cf, tw.levels, bwd_iters)
+            orc.mgrit_backward(*P, d["x"], h, g, z, tw.cf, tw.levels, bwd_iters,
+                               fine_relax_fcf=fcf)
         return time.perf_counter() - t0
 
     unit = wl.cf ** (wl.levels - 1)
@@ -105,9 +114,43 @@ def main():
         t[k] = t[k].to(in_dt)
     dtype_code = 0 if wl.dtype == "fp32" else 1
 
+    fine_relax = 1 if args.fine_relax == "FCF" else 0
+
     def cfg(iters, flags=0, levels=wl.levels):
-        return MgritGruCfg(T, B, D, H, cf=wl.cf, levels=levels, iters=iters, fine_relax=1,
+        return MgritGruCfg(T, B, D, H, cf=wl.cf, levels=levels, iters=iters, fine_relax=fine_relax,
                            propagator=0, dtype=dtype_code, flags=flags)
+
+    convergence = None
+    if args.until_converged:
+        # R12 of the design doc: cycles are applied one call at a time; stop when the residual
+        # relative to ||h_serial|| is below 1e-8, or has not halved for two cycles in a row
+        # (the fp32 floor), or after N_1/2 cycles (two-level FCF is exact by then)
+        bwd_iters = 0
+        ws0 = torch.empty(mg.mgrit_gru_workspace_bytes(cfg(1)), dtype=torch.uint8, device=dev)
+        hs = torch.zeros(T + 1, B, H, device=dev)
+        mg.gru_serial_scan(cfg(1), t["W"], t["U"], t["b_i"], t["b_h"], t["x"], t["h0"], hs, ws0)
+        hnorm = float(torch.linalg.vector_norm(hs[1:].double()))
+        hh = torch.zeros(T + 1, B, H, device=dev)
+        r1 = torch.zeros(1, device=dev)
+        hist, stall, limit = [], 0, max(1, (T // wl.cf + 1) // 2)
+        while len(hist) < limit:
+            flags = MGRIT_REUSE_PROJECTION if hist else 0
+            mg.mgrit_gru_forward(cfg(1, flags), t["W"], t["U"], t["b_i"], t["b_h"], t["x"], t["h0"],
+                                 hh, r1, ws0)
+            hist.append(float(r1.item()) / hnorm)
+            if hist[-1] < 1e-8:
+                break
+            stall = stall + 1 if len(hist) > 1 and hist[-1] > 0.5 * hist[-2] else 0
+            if stall >= 2:
+                break
+        fwd_iters = len(hist)
+        err = float(torch.max(torch.abs(hh - hs)) / torch.max(torch.abs(hs)))
+        convergence = {"cycles": fwd_iters, "relative_residuals": hist,
+                       "max_rel_error_vs_serial_scan": err,
+                       "stopped_by": "tolerance 1e-8" if hist[-1] < 1e-8 else
+                                     ("fp32 floor (residual stopped halving)" if stall >= 2
+                                      else "cycle limit N_1/2")}
+        del ws0, hs, hh
 
     ws = torch.empty(mg.mgrit_gru_workspace_bytes(cfg(max(fwd_iters, bwd_iters, 1))),
                      dtype=torch.uint8, device=dev)
@@ -231,8 +274,10 @@ def main():
         "dtype": "f32" if wl.dtype == "fp32" else "bf16-in/f32-state",
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: T={T} B={B} D={D} H={H} cf={wl.cf} levels={wl.levels} "
-                               f"fwd_iters={fwd_iters} bwd_iters={bwd_iters} FCF implicit-GRU",
+                               f"fwd_iters={fwd_iters} bwd_iters={bwd_iters} fine-level {args.fine_relax} "
+                               f"relaxation, implicit GRU",
                    "seed": wl.seed},
+        "convergence": convergence,
         "residual_fwd": resf,
         "residual_bwd": resb,
         "roofline": roofline,
@@ -240,7 +285,7 @@ def main():
         "serial_gpu": serial,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, fwd_iters, bwd_iters)
+        out["cpu_baseline"] = cpu_baseline(wl, fwd_iters, bwd_iters, fcf=bool(fine_relax))
     print(json.dumps(out))
 
 

@@ -223,4 +223,47 @@ __device__ inline void acc_coord(int a, int b, int e, int& row, int& col) {
   col = (wn * C::BN + b) * 32 + (lane & 31);
 }
 
+// Staging of the accumulators for the epilogue.  The MFMA result layout gives a lane
+// one column and sixteen scattered rows, which would make every global access of the
+// epilogue a 4-byte one; the sums are therefore passed through LDS, one 32-row block
+// row of every wave per pass, and picked up again with a thread owning four
+// consecutive columns of a row ("item"), so that epilogue operands and outputs move
+// as 16-byte accesses covering whole row segments.
+template <class C>
+struct EpiStage {
+  static constexpr int ROWS = C::WM * 32;              // tile rows staged per pass
+  static constexpr int LD = C::TN + 8;                 // 4*LD = 32 (mod 64): conflict-free writes
+  static constexpr int C4 = C::TN / 4;                 // float4 columns of a tile row
+  static constexpr int RSTEP = C::NT / C4;             // staged rows between items of a thread
+  static constexpr int ITEMS = ROWS / RSTEP;           // items per thread and pass
+  static constexpr int FLOATS = C::NG * ROWS * LD;
+  static_assert(C::NT % C4 == 0 && ROWS % RSTEP == 0, "epilogue items must divide evenly");
+
+  // block row ba of every wave -> stage[g][row][col]
+  __device__ static inline void write(const Acc<C>& acc, int ba, float* stage) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / C::WN, wn = wave % C::WN;
+    const int li = lane & 31, lh = lane >> 5;
+#pragma unroll
+    for (int g = 0; g < C::NG; ++g)
+#pragma unroll
+      for (int bb = 0; bb < C::BN; ++bb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int row = wm * 32 + 8 * (e / 4) + 4 * lh + (e & 3);
+          const int col = (wn * C::BN + bb) * 32 + li;
+          stage[(g * ROWS + row) * LD + col] = acc.v[g][ba][bb][e];
+        }
+  }
+  __device__ static inline int col4() { return threadIdx.x % C4; }
+  __device__ static inline int staged_row(int it) { return threadIdx.x / C4 + it * RSTEP; }
+  // row of the workgroup tile behind staged row rp of pass ba
+  __device__ static inline int tile_row(int rp, int ba) {
+    return ((rp / 32) * C::BM + ba) * 32 + (rp & 31);
+  }
+  __device__ static inline floatx4 read(const float* stage, int g, int rp, int c4) {
+    return *reinterpret_cast<const floatx4*>(&stage[(g * ROWS + rp) * LD + c4 * 4]);
+  }
+};
+
 }  // namespace mg

@@ -64,51 +64,58 @@ __device__ inline void adj_epi_finish(const AdjArgs& a, const AdjRow& ro, int j,
   }
 }
 
-// Epilogue of one MFMA tile, batches of EPI_BATCH elements with the operands of the
-// next batch requested before the current one is finished.
+// Epilogue of one MFMA tile over the staged sums (see EpiStage).
+struct AdjEpiIn4 {
+  floatx4 kd, wv, gval, cur;
+};
 template <class C, int MODE>
 __device__ inline void adj_tile_epilogue(const AdjArgs& a, Acc<C>& acc, const AdjRow* rowtab,
-                                         long long m0, int n0, long long R, double& nrm) {
-  constexpr int NPB = 16 / EPI_BATCH;
-  constexpr int NBATCH = C::BM * C::BN * NPB;
+                                         float* stage, long long m0, int n0, long long R,
+                                         double& nrm) {
+  typedef EpiStage<C> E;
   const int H = a.H;
-  AdjEpiIn ein[2][EPI_BATCH];
-  AdjRow ros[2][EPI_BATCH];
-  int jcol[C::BN];
+  const int c4 = E::col4();
+  const int j = n0 + c4 * 4;
+  const bool colok = j < H;
+  const int jc = colok ? j : H - 4;                     // clamped columns are never stored
 #pragma unroll
-  for (int bb = 0; bb < C::BN; ++bb) {
-    int row, col;
-    acc_coord<C>(0, bb, 0, row, col);
-    jcol[bb] = n0 + col;
-  }
-  auto load = [&](int q, int slot) {
-    const int ba = q / (C::BN * NPB), bb = (q / NPB) % C::BN, e0 = (q % NPB) * EPI_BATCH;
-    const int j = jcol[bb] < H ? jcol[bb] : H - 1;      // clamped columns are never stored
+  for (int ba = 0; ba < C::BM; ++ba) {
+    __syncthreads();                                    // staging area no longer read
+    E::write(acc, ba, stage);
+    AdjEpiIn4 in[E::ITEMS];
+    long long oo[E::ITEMS], oa[E::ITEMS];
+    int trow[E::ITEMS];
 #pragma unroll
-    for (int i = 0; i < EPI_BATCH; ++i) {
-      int row, col;
-      acc_coord<C>(ba, bb, e0 + i, row, col);
-      ros[slot][i] = rowtab[row];
-      ein[slot][i] = adj_epi_load<MODE>(a, ros[slot][i], j);
+    for (int it = 0; it < E::ITEMS; ++it) {
+      trow[it] = E::tile_row(E::staged_row(it), ba);
+      const AdjRow ro = rowtab[trow[it]];               // rows beyond the launch hold its last row
+      oo[it] = ro.o;
+      oa[it] = ro.a;
+      in[it].kd = ldg4(a.kap + ro.k + 3 * H + jc);
+      in[it].wv = ldg4(a.w_in + ro.in + jc);
+      in[it].gval = a.g ? ldg4(a.g + ro.o + jc) : zero4();
+      in[it].cur = (MODE == STEP_RESID || MODE == STEP_RHS) ? ldg4(a.w + ro.o + jc) : zero4();
     }
-  };
-  load(0, 0);
+    __syncthreads();
 #pragma unroll
-  for (int q = 0; q < NBATCH; ++q) {
-    if (q + 1 < NBATCH) load(q + 1, (q + 1) & 1);
-    __builtin_amdgcn_sched_barrier(0);
-    const int ba = q / (C::BN * NPB), bb = (q / NPB) % C::BN, e0 = (q % NPB) * EPI_BATCH;
-    if (jcol[bb] < H) {
+    for (int it = 0; it < E::ITEMS; ++it) {
+      const floatx4 dot = E::read(stage, 0, E::staged_row(it), c4);
+      if (!colok || m0 + trow[it] >= R) continue;
+      const floatx4 wn = in[it].kd * in[it].wv + dot;
+      const long long oi = oo[it] + j;
+      if (MODE == STEP_RELAX) {
+        *reinterpret_cast<floatx4*>(a.w + oi) = wn + in[it].gval;
+      } else if (MODE == STEP_RESID) {
+        const floatx4 res = in[it].cur - wn - in[it].gval;
+        const long long ai = oa[it] + j;
+        *reinterpret_cast<floatx4*>(a.gc + ai) = -res;
+        *reinterpret_cast<floatx4*>(a.wc + ai) = in[it].cur;
 #pragma unroll
-      for (int i = 0; i < EPI_BATCH; ++i) {
-        int row, col;
-        acc_coord<C>(ba, bb, e0 + i, row, col);
-        if (m0 + row < R)
-          adj_epi_finish<MODE>(a, ros[q & 1][i], jcol[bb], acc.v[0][ba][bb][e0 + i], ein[q & 1][i],
-                               nrm);
+        for (int i = 0; i < 4; ++i) nrm += (double)res[i] * (double)res[i];
+      } else {  // STEP_RHS
+        *reinterpret_cast<floatx4*>(a.g + oi) = (in[it].cur - wn) + in[it].gval;
       }
     }
-    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
@@ -118,7 +125,9 @@ struct KapW {
 
 template <class C, int MODE>
 __global__ __launch_bounds__(C::NT, 2) void adj_step_kernel(AdjArgs a) {
-  __shared__ __attribute__((aligned(16))) float lds[C::LDS_FLOATS];
+  constexpr int LDSF =
+      C::LDS_FLOATS > EpiStage<C>::FLOATS ? C::LDS_FLOATS : EpiStage<C>::FLOATS;
+  __shared__ __attribute__((aligned(16))) float lds[LDSF];
   const int H = a.H, B = a.B, K = 3 * a.H;
   const long long R = (long long)a.nk * B;
   long long rt;
@@ -169,7 +178,7 @@ __global__ __launch_bounds__(C::NT, 2) void adj_step_kernel(AdjArgs a) {
     gemm_nt_tile<C, true>(acc, K, la, lb, fa, Identity4(), lds);
 
   double nrm = 0.0;
-  adj_tile_epilogue<C, MODE>(a, acc, rowtab, m0, n0, R, nrm);
+  adj_tile_epilogue<C, MODE>(a, acc, rowtab, lds, m0, n0, R, nrm);
   if (MODE == STEP_RESID && a.norm) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) nrm += __shfl_down(nrm, off, 64);
@@ -184,7 +193,10 @@ struct KapW8 {
 
 template <class C, int MODE>
 __global__ __launch_bounds__(C::NT, 2) void adj_step_kernel_bf16(AdjArgs a) {
-  __shared__ __attribute__((aligned(16))) bf16_t lds[C::LDS_ELEMS];
+  constexpr int LDSF = C::LDS_ELEMS / 2 + 1 > EpiStage<C>::FLOATS ? C::LDS_ELEMS / 2 + 1
+                                                                  : EpiStage<C>::FLOATS;
+  __shared__ __attribute__((aligned(16))) float ldsf[LDSF];
+  bf16_t* lds = reinterpret_cast<bf16_t*>(ldsf);
   const int H = a.H, B = a.B, K = 3 * a.H;
   const long long R = (long long)a.nk * B;
   long long rt;
@@ -235,7 +247,7 @@ __global__ __launch_bounds__(C::NT, 2) void adj_step_kernel_bf16(AdjArgs a) {
     gemm_nt_tile_bf16<C, true>(acc, K, la, lb, fa, lds);
 
   double nrm = 0.0;
-  adj_tile_epilogue<C, MODE>(a, acc, rowtab, m0, n0, R, nrm);
+  adj_tile_epilogue<C, MODE>(a, acc, rowtab, ldsf, m0, n0, R, nrm);
   if (MODE == STEP_RESID && a.norm) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) nrm += __shfl_down(nrm, off, 64);

@@ -201,16 +201,16 @@ __device__ inline PhiEpiIn phi_epi_load(const PhiArgs& a, const PhiRow& ro, int 
   return e;
 }
 
-// Gates of Eq. 1, the update of Eq. 16 / Eq. 3 and the mode-specific output for one
-// element: row (point pt, batch b), hidden column j, given the three recurrent
-// contractions (U_r h)_j, (U_z h)_j, (U_n h)_j.
+// Gates of Eq. 1, the update of Eq. 16 / Eq. 3 and the mode-specific outputs of one
+// element, given the three recurrent contractions (U_r h)_j, (U_z h)_j, (U_n h)_j.
+//   RELAX: v0 = new state (+ g)          RESID: v0 = -r (coarse right-hand side), v1 = cur
+//   RHS:   v0 = cur - step + g           KAPPA: v0..v4 = k_r, k_z, k_q, k_d, k_n
+struct PhiOut {
+  float v0, v1, v2, v3, v4;
+};
 template <int MODE>
-__device__ inline void phi_epi_finish(const PhiArgs& a, const PhiRow& ro, int j, float sr,
-                                      float sz, float sn, const PhiEpiIn& e, const PhiBias& bh,
-                                      double& nrm) {
-  const int H = a.H;
-  const float gamma = a.gamma;
-  const bool implicit = a.propagator == MGRIT_PROP_IMPLICIT;
+__device__ inline PhiOut phi_elem(float gamma, bool implicit, float sr, float sz, float sn,
+                                  const PhiEpiIn& e, const PhiBias& bh) {
   const float h = e.h;
   const float rg = sigmoidf_(e.pr + sr + bh.r);
   const float zg = sigmoidf_(e.pz + sz + bh.z);
@@ -220,17 +220,14 @@ __device__ inline void phi_epi_finish(const PhiArgs& a, const PhiRow& ro, int j,
   const float d = 1.0f + gamma * c;
   const float rd = fast_rcp(d);
   const float hn = implicit ? (h + gamma * c * n) * rd : h + gamma * c * (n - h);
-  const long long oi = ro.o + j;
+  PhiOut o{0.f, 0.f, 0.f, 0.f, 0.f};
   if (MODE == STEP_RELAX) {
-    a.u[oi] = hn + e.gval;
+    o.v0 = hn + e.gval;
   } else if (MODE == STEP_RESID) {
-    const float res = e.cur - hn - e.gval;
-    const long long ai = ro.a + j;
-    a.gc[ai] = -res;
-    a.uc[ai] = e.cur;
-    nrm += (double)res * (double)res;
+    o.v0 = -(e.cur - hn - e.gval);
+    o.v1 = e.cur;
   } else if (MODE == STEP_RHS) {
-    a.g[oi] = (e.cur - hn) + e.gval;
+    o.v0 = (e.cur - hn) + e.gval;
   } else {  // STEP_KAPPA: coefficients of the transposed Jacobian of this step
     float kd, dn, dz;
     if (implicit) {
@@ -243,70 +240,133 @@ __device__ inline void phi_epi_finish(const PhiArgs& a, const PhiRow& ro, int j,
       dz = -gamma * (n - h);
     }
     const float kn = dn * (1.0f - n * n);
+    o.v0 = kn * q * rg * (1.0f - rg);
+    o.v1 = dz * zg * (1.0f - zg);
+    o.v2 = kn * rg;
+    o.v3 = kd;
+    o.v4 = kn;
+  }
+  return o;
+}
+
+// Scalar form used by the few-row kernel: computes and stores one element of row ro.
+template <int MODE>
+__device__ inline void phi_epi_finish(const PhiArgs& a, const PhiRow& ro, int j, float sr,
+                                      float sz, float sn, const PhiEpiIn& e, const PhiBias& bh,
+                                      double& nrm) {
+  const int H = a.H;
+  const PhiOut o =
+      phi_elem<MODE>(a.gamma, a.propagator == MGRIT_PROP_IMPLICIT, sr, sz, sn, e, bh);
+  const long long oi = ro.o + j;
+  if (MODE == STEP_RELAX) {
+    a.u[oi] = o.v0;
+  } else if (MODE == STEP_RESID) {
+    const long long ai = ro.a + j;
+    a.gc[ai] = o.v0;
+    a.uc[ai] = o.v1;
+    nrm += (double)o.v0 * (double)o.v0;
+  } else if (MODE == STEP_RHS) {
+    a.g[oi] = o.v0;
+  } else {
     float* kp = a.uc + ro.a;
-    kp[j] = kn * q * rg * (1.0f - rg);
-    kp[H + j] = dz * zg * (1.0f - zg);
-    kp[2 * H + j] = kn * rg;
-    kp[3 * H + j] = kd;
-    if (a.kappa_width >= 5 * H) kp[4 * H + j] = kn;
+    kp[j] = o.v0;
+    kp[H + j] = o.v1;
+    kp[2 * H + j] = o.v2;
+    kp[3 * H + j] = o.v3;
+    if (a.kappa_width >= 5 * H) kp[4 * H + j] = o.v4;
   }
 }
 
-// Epilogue of one MFMA tile: every lane walks its accumulator elements in batches of
-// EPI_BATCH; the operands of batch q+1 are requested before batch q is finished, so
-// memory latency overlaps the gate arithmetic.
+// Epilogue of one MFMA tile over the staged sums (see EpiStage): per pass a thread
+// requests the operands of its items, the sums go through LDS, and each item is
+// finished and stored as float4.
+struct PhiEpiIn4 {
+  floatx4 pr, pz, pn, h, gval, cur;
+};
+
 template <class C, int MODE>
 __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const PhiRow* rowtab,
-                                         long long m0, int n0, long long R, double& nrm) {
-  constexpr int NPB = 16 / EPI_BATCH;                   // batches per 32x32 block
-  constexpr int NBATCH = C::BM * C::BN * NPB;
+                                         float* stage, long long m0, int n0, long long R,
+                                         double& nrm) {
+  typedef EpiStage<C> E;
   const int H = a.H;
-  PhiEpiIn ein[2][EPI_BATCH];
-  PhiRow ros[2][EPI_BATCH];
-  PhiBias bh[C::BN];
-  int jcol[C::BN];
+  const int c4 = E::col4();
+  const int j = n0 + c4 * 4;
+  const bool colok = j < H;
+  const int jc = colok ? j : H - 4;                     // clamped columns are never stored
+  PhiBias bh[4];
 #pragma unroll
-  for (int bb = 0; bb < C::BN; ++bb) {
-    int row, col;
-    acc_coord<C>(0, bb, 0, row, col);
-    jcol[bb] = n0 + col;
-    bh[bb] = phi_bias_load(a, jcol[bb] < H ? jcol[bb] : H - 1);
-  }
-  auto load = [&](int q, int slot) {
-    const int ba = q / (C::BN * NPB), bb = (q / NPB) % C::BN, e0 = (q % NPB) * EPI_BATCH;
-    const int j = jcol[bb] < H ? jcol[bb] : H - 1;      // clamped columns are never stored
+  for (int i = 0; i < 4; ++i) bh[i] = phi_bias_load(a, jc + i);
+  const float gamma = a.gamma;
+  const bool implicit = a.propagator == MGRIT_PROP_IMPLICIT;
+
 #pragma unroll
-    for (int i = 0; i < EPI_BATCH; ++i) {
-      int row, col;
-      acc_coord<C>(ba, bb, e0 + i, row, col);
-      ros[slot][i] = rowtab[row];                        // rows beyond the launch hold its last row
-      ein[slot][i] = phi_epi_load<MODE>(a, ros[slot][i], j);
+  for (int ba = 0; ba < C::BM; ++ba) {
+    __syncthreads();                                    // staging area no longer read
+    E::write(acc, ba, stage);
+    // operands that do not depend on the sums: requested before the barrier
+    PhiEpiIn4 in[E::ITEMS];
+    long long oo[E::ITEMS], oa[E::ITEMS];
+    int trow[E::ITEMS];
+#pragma unroll
+    for (int it = 0; it < E::ITEMS; ++it) {
+      trow[it] = E::tile_row(E::staged_row(it), ba);
+      const PhiRow ro = rowtab[trow[it]];               // rows beyond the launch hold its last row
+      oo[it] = ro.o;
+      oa[it] = ro.a;
+      const float* pp = a.P + ro.p + jc;
+      in[it].pr = ldg4(pp);
+      in[it].pz = ldg4(pp + H);
+      in[it].pn = ldg4(pp + 2 * H);
+      in[it].h = ldg4(a.u_in + ro.in + jc);
+      if (MODE != STEP_KAPPA && a.g) in[it].gval = ldg4(a.g + ro.o + jc);
+      else in[it].gval = zero4();
+      if (MODE == STEP_RESID || MODE == STEP_RHS) in[it].cur = ldg4(a.u + ro.o + jc);
+      else in[it].cur = zero4();
     }
-  };
-  load(0, 0);
+    __syncthreads();
 #pragma unroll
-  for (int q = 0; q < NBATCH; ++q) {
-    if (q + 1 < NBATCH) load(q + 1, (q + 1) & 1);
-    __builtin_amdgcn_sched_barrier(0);
-    const int ba = q / (C::BN * NPB), bb = (q / NPB) % C::BN, e0 = (q % NPB) * EPI_BATCH;
-    if (jcol[bb] < H) {
+    for (int it = 0; it < E::ITEMS; ++it) {
+      const int rp = E::staged_row(it);
+      const floatx4 sr = E::read(stage, 0, rp, c4);
+      const floatx4 sz = E::read(stage, 1, rp, c4);
+      const floatx4 sn = E::read(stage, 2, rp, c4);
+      floatx4 o0, o1, o2, o3, o4;
 #pragma unroll
-      for (int i = 0; i < EPI_BATCH; ++i) {
-        int row, col;
-        acc_coord<C>(ba, bb, e0 + i, row, col);
-        if (m0 + row < R)
-          phi_epi_finish<MODE>(a, ros[q & 1][i], jcol[bb], acc.v[0][ba][bb][e0 + i],
-                               acc.v[1][ba][bb][e0 + i], acc.v[2][ba][bb][e0 + i], ein[q & 1][i],
-                               bh[bb], nrm);
+      for (int i = 0; i < 4; ++i) {
+        const PhiEpiIn e1{in[it].pr[i], in[it].pz[i], in[it].pn[i], in[it].h[i], in[it].gval[i],
+                          in[it].cur[i]};
+        const PhiOut o = phi_elem<MODE>(gamma, implicit, sr[i], sz[i], sn[i], e1, bh[i]);
+        o0[i] = o.v0; o1[i] = o.v1; o2[i] = o.v2; o3[i] = o.v3; o4[i] = o.v4;
+      }
+      if (!colok || m0 + trow[it] >= R) continue;
+      const long long oi = oo[it] + j;
+      if (MODE == STEP_RELAX) {
+        *reinterpret_cast<floatx4*>(a.u + oi) = o0;
+      } else if (MODE == STEP_RESID) {
+        const long long ai = oa[it] + j;
+        *reinterpret_cast<floatx4*>(a.gc + ai) = o0;
+        *reinterpret_cast<floatx4*>(a.uc + ai) = o1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) nrm += (double)o0[i] * (double)o0[i];
+      } else if (MODE == STEP_RHS) {
+        *reinterpret_cast<floatx4*>(a.g + oi) = o0;
+      } else {
+        float* kp = a.uc + oa[it] + j;
+        *reinterpret_cast<floatx4*>(kp) = o0;
+        *reinterpret_cast<floatx4*>(kp + H) = o1;
+        *reinterpret_cast<floatx4*>(kp + 2 * H) = o2;
+        *reinterpret_cast<floatx4*>(kp + 3 * H) = o3;
+        if (a.kappa_width >= 5 * H) *reinterpret_cast<floatx4*>(kp + 4 * H) = o4;
       }
     }
-    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
 template <class C, int MODE>
 __global__ __launch_bounds__(C::NT, 2) void phi_step_kernel(PhiArgs a) {
-  __shared__ __attribute__((aligned(16))) float lds[C::LDS_FLOATS];
+  constexpr int LDSF = C::LDS_FLOATS > EpiStage<C>::FLOATS ? C::LDS_FLOATS : EpiStage<C>::FLOATS;
+  __shared__ __attribute__((aligned(16))) float lds[LDSF];
   const int H = a.H, B = a.B;
   const long long R = (long long)a.nk * B;
   long long rt;
@@ -354,7 +414,7 @@ __global__ __launch_bounds__(C::NT, 2) void phi_step_kernel(PhiArgs a) {
     gemm_nt_tile<C, true>(acc, H, la, lb, Identity4(), Identity4(), lds);
 
   double nrm = 0.0;
-  phi_tile_epilogue<C, MODE>(a, acc, rowtab, m0, n0, R, nrm);
+  phi_tile_epilogue<C, MODE>(a, acc, rowtab, lds, m0, n0, R, nrm);
   if (MODE == STEP_RESID && a.norm) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) nrm += __shfl_down(nrm, off, 64);
@@ -366,7 +426,10 @@ __global__ __launch_bounds__(C::NT, 2) void phi_step_kernel(PhiArgs a) {
 // gemm_core_bf16.h); gates, update and outputs stay fp32.
 template <class C, int MODE>
 __global__ __launch_bounds__(C::NT, 2) void phi_step_kernel_bf16(PhiArgs a) {
-  __shared__ __attribute__((aligned(16))) bf16_t lds[C::LDS_ELEMS];
+  constexpr int LDSF =
+      C::LDS_ELEMS / 2 + 1 > EpiStage<C>::FLOATS ? C::LDS_ELEMS / 2 + 1 : EpiStage<C>::FLOATS;
+  __shared__ __attribute__((aligned(16))) float ldsf[LDSF];
+  bf16_t* lds = reinterpret_cast<bf16_t*>(ldsf);
   const int H = a.H, B = a.B;
   const long long R = (long long)a.nk * B;
   long long rt;
@@ -413,7 +476,7 @@ __global__ __launch_bounds__(C::NT, 2) void phi_step_kernel_bf16(PhiArgs a) {
     gemm_nt_tile_bf16<C, true>(acc, H, la, lb, fa, lds);
 
   double nrm = 0.0;
-  phi_tile_epilogue<C, MODE>(a, acc, rowtab, m0, n0, R, nrm);
+  phi_tile_epilogue<C, MODE>(a, acc, rowtab, ldsf, m0, n0, R, nrm);
   if (MODE == STEP_RESID && a.norm) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) nrm += __shfl_down(nrm, off, 64);

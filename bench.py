@@ -233,6 +233,8 @@ def main():
             kernels[nm] = {"launches_per_step": n / args.steps, "ms_per_step": ms / args.steps,
                            "avg_launch_us": 1e3 * ms / n, "TFLOPs": fl / ms / 1e9,
                            "algorithmic_GBps": by / ms / 1e6}
+    # whole step against the matrix-core peak: flops of all library kernels / step time
+    step_flops = sum(v["TFLOPs"] * v["ms_per_step"] * 1e9 for v in kernels.values())
     dom = kernels.get(names[0])
     peak = MI355X_PEAK["fp32_TFLOPs"] if wl.dtype == "fp32" else MI355X_PEAK["bf16_TFLOPs"]
     # HBM traffic of the dominant kernel per launch: measured offline with rocprofv3 --pmc
@@ -259,6 +261,19 @@ def main():
         serial = {"value": T * B / ssec, "unit": "time-steps*batch/s", "ms_per_step": 1e3 * ssec,
                   "what": "gru_serial_scan + gru_serial_scan_backward on the same GPU",
                   "mgrit_speedup": ssec / sec}
+        # the same comparison without the GEMMs both paths share (input projection and
+        # weight gradients), from the per-kernel event times of one profiled step each
+        mg.mgrit_gru_profile_enable(True)
+        serial_step()
+        torch.cuda.synchronize()
+        mg.mgrit_gru_profile_enable(False)
+        s_shared = sum(mg.mgrit_gru_profile_read(k)[1] for k in (2, 3))
+        m_shared = sum(kernels[names[k]]["ms_per_step"] for k in (2, 3) if names[k] in kernels)
+        m_rec, s_rec = 1e3 * sec - m_shared, 1e3 * ssec - s_shared
+        serial["without_shared_gemms"] = {
+            "mgrit_ms_per_step": m_rec, "serial_ms_per_step": s_rec,
+            "mgrit_value": T * B / (1e-3 * m_rec), "serial_value": T * B / (1e-3 * s_rec),
+            "mgrit_speedup": s_rec / m_rec}
 
     out = {
         "metric": "GRU time-steps x batch / sec, MGRIT fwd+bwd (1 GPU)",
@@ -282,6 +297,8 @@ def main():
         "residual_bwd": resb,
         "roofline": roofline,
         "kernels": kernels,
+        "whole_step": {"TFLOPs": step_flops / sec / 1e12,
+                       "frac_of_mfma_peak": step_flops / sec / 1e12 / peak},
         "serial_gpu": serial,
     }
     if not args.no_cpu_baseline:

@@ -462,22 +462,38 @@ struct GradArgs {
   const float* w;      // [(T+1),B,H]
   const void* Bm;      // h[(T+1),B,H] (float) or x[T,B,D] (float or bf16); row k as is
   float* part;         // [splits][3H][N]
+  float* bpart;        // [splits][ntiles][3H] column sums of S (bias gradients)
   long long Ktot;      // T*B
   long long Kper;      // rows per split (multiple of GTK)
   int B, H, N;         // N = H (dU) or D (dW)
   int third_off;       // 2H (k_q, dU) or 4H (k_n, dW)
+  int mtiles, ntiles;  // output tiles along 3H and N
+  int splits;          // row splits (a multiple of 8, or fewer than 8)
 };
 
 // C[m, n] = sum_k S[k, m] Bm[k, n] over this split's rows k.  Both operands are
 // read with the contracted index k slowest, so an LDS slice is stored [k][m] and
 // a lane reads its MFMA operand as one float per k-pair.
+// 1-D grid: workgroups go round-robin over the 8 XCDs, so split z is given to XCD
+// z % 8 and all output tiles of a split run on that XCD: its rows of S and Bm are
+// fetched into one L2 only.
 template <class BT>
 __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
   __shared__ __attribute__((aligned(16))) float As[GTK * GLD];
   __shared__ __attribute__((aligned(16))) float Bs[GTK * GLD];
   const int H = a.H, N = a.N, M = 3 * a.H;
-  const int m0 = blockIdx.x * GT, n0 = blockIdx.y * GT;
-  const long long kbeg = (long long)blockIdx.z * a.Kper;
+  const int tiles = a.mtiles * a.ntiles;
+  int tile, z;
+  if (a.splits % NXCD == 0) {
+    const int j = blockIdx.x / NXCD;
+    tile = j % tiles;
+    z = (j / tiles) * NXCD + blockIdx.x % NXCD;
+  } else {
+    tile = blockIdx.x % tiles;
+    z = blockIdx.x / tiles;
+  }
+  const int m0 = (tile % a.mtiles) * GT, n0 = (tile / a.mtiles) * GT;
+  const long long kbeg = (long long)z * a.Kper;
   long long kend = kbeg + a.Kper;
   if (kend > a.Ktot) kend = a.Ktot;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -530,6 +546,11 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
     for (int j = 0; j < 2; ++j) bv[j] = Bs[(2 * p + lh) * GLD + wn * 64 + j * 32 + li];
   };
 
+  // Bias gradients are the column sums of S: the staged slices already hold S, so
+  // thread t < GT adds up column t over the slice rows r = nt (mod ntiles); the
+  // workgroups of the ntiles column tiles share the rows of a slice between them.
+  const int nt = tile / a.mtiles;
+  float colsum = 0.f;
   if (kbeg < kend) {
     fetch(kbeg);
     stash(kbeg);
@@ -538,17 +559,22 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
       const bool more = k0 + GTK < kend;
       if (more) fetch(k0 + GTK);
       __builtin_amdgcn_sched_barrier(0);
+      if (tid < GT)
+        for (int r = nt; r < GTK; r += a.ntiles) colsum += As[r * GLD + tid];
       float av[2][2], bv[2][2];
       frags(0, av[0], bv[0]);
 #pragma unroll
       for (int p = 0; p < GTK / 2; ++p) {
         if (p + 1 < GTK / 2) frags(p + 1, av[(p + 1) & 1], bv[(p + 1) & 1]);
+        // keep the LDS reads of the next k-pair ahead of this pair's MFMAs
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
           for (int j = 0; j < 2; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[p & 1][i], bv[p & 1][j],
                                                              acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
       __builtin_amdgcn_sched_barrier(0);
       __syncthreads();
@@ -558,7 +584,9 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
       }
     }
   }
-  float* out = a.part + (long long)blockIdx.z * M * N;
+  if (tid < GT && m0 + tid < M)
+    a.bpart[((long long)z * a.ntiles + nt) * M + m0 + tid] = colsum;
+  float* out = a.part + (long long)z * M * N;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -580,54 +608,58 @@ __global__ void reduce_partials_kernel(const float* __restrict__ part, float* __
   out[i] = s;
 }
 
-// Column sums over rows k of the 4H virtual columns (k_r w, k_z w, k_q w, k_n w).
-constexpr int BIAS_SPLITS = 128;
-__global__ void bias_partial_kernel(const float* __restrict__ kap0, const float* __restrict__ w,
-                                    float* __restrict__ part, long long Ktot, int B, int H) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;   // virtual column
-  if (c >= 4 * H) return;
-  const int g = c / H, j = c - g * H;
-  const int src = g == 3 ? 4 * H + j : c;
-  const long long per = (Ktot + BIAS_SPLITS - 1) / BIAS_SPLITS;
-  long long kb = (long long)blockIdx.y * per, ke = kb + per;
-  if (ke > Ktot) ke = Ktot;
-  float s = 0.f;
-  for (long long k = kb; k < ke; ++k)
-    s += kap0[(k + B) * (5LL * H) + src] * w[(k + B) * H + j];
-  part[(long long)blockIdx.y * 4 * H + c] = s;
-}
-
-__global__ void bias_reduce_kernel(const float* __restrict__ part, float* __restrict__ db_i,
-                                   float* __restrict__ db_h, int H) {
+// Bias gradients from the column sums the two gradient GEMMs leave behind:
+// pu[nu][3H] (columns k_r w, k_z w, k_q w) and pw[nw][3H] (k_r w, k_z w, k_n w).
+__global__ void bias_reduce_kernel(const float* __restrict__ pu, int nu,
+                                   const float* __restrict__ pw, int nw,
+                                   float* __restrict__ db_i, float* __restrict__ db_h, int H) {
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= 4 * H) return;
-  float s = 0.f;
-  for (int z = 0; z < BIAS_SPLITS; ++z) s += part[(long long)z * 4 * H + c];
+  if (c >= 3 * H) return;
+  float su = 0.f;
+  for (int z = 0; z < nu; ++z) su += pu[(long long)z * 3 * H + c];
+  db_h[c] = su;
   if (c < 2 * H) {
-    db_h[c] = s;
-    db_i[c] = s;
-  } else if (c < 3 * H) {
-    db_h[c] = s;            // k_q w
+    db_i[c] = su;
   } else {
-    db_i[c - H] = s;        // k_n w -> third block of db_i
+    float sw = 0.f;
+    for (int z = 0; z < nw; ++z) sw += pw[(long long)z * 3 * H + c];
+    db_i[c] = sw;
   }
 }
 
+// Row splits of a gradient GEMM.  Enough workgroups for at least two per slot (512
+// slots: 256 CUs x 2 resident workgroups); from 8 splits on, a multiple of 8 (whole
+// splits per XCD) chosen so that the grid is close to a whole number of rounds over the
+// slots: a partly filled last round costs as much time as a full one.
 static int grad_splits(long long Ktot, int M, int N) {
-  long long tiles = (long long)((M + GT - 1) / GT) * ((N + GT - 1) / GT);
-  long long want = (1024 + tiles - 1) / tiles;
+  const long long tiles = (long long)((M + GT - 1) / GT) * ((N + GT - 1) / GT);
+  const long long slots = 512;
   long long maxs = (Ktot + 4 * GTK - 1) / (4 * GTK);   // at least 4 slices per split
+  if (maxs > 256) maxs = 256;
+  if (maxs < 1) maxs = 1;
+  long long want = (2 * slots + tiles - 1) / tiles;
   if (want > maxs) want = maxs;
-  if (want < 1) want = 1;
-  if (want > 256) want = 256;
-  return (int)want;
+  if (want < NXCD) return (int)want;
+  long long best = want / NXCD * NXCD;
+  double best_eff = 0.0;
+  for (long long sp = (want + NXCD - 1) / NXCD * NXCD; sp <= maxs && sp <= 4 * want; sp += NXCD) {
+    const double rounds = (double)(tiles * sp) / (double)slots;
+    const double eff = rounds / (double)(long long)(rounds + 0.999999);
+    if (eff > best_eff + 0.02) {
+      best_eff = eff;
+      best = sp;
+    }
+    if (eff >= 0.97) break;
+  }
+  return (int)best;
 }
 
 size_t grad_partial_floats(int T, int B, int D, int H) {
   const long long Ktot = (long long)T * B;
   size_t su = (size_t)grad_splits(Ktot, 3 * H, H) * 3 * H * H;
   size_t sw = (size_t)grad_splits(Ktot, 3 * H, D) * 3 * H * D;
-  size_t sb = (size_t)BIAS_SPLITS * 4 * H;
+  size_t sb = (size_t)(grad_splits(Ktot, 3 * H, H) * ((H + GT - 1) / GT) +
+                       grad_splits(Ktot, 3 * H, D) * ((D + GT - 1) / GT)) * 3 * H;
   return (su > sw ? su : sw) + sb;
 }
 
@@ -637,6 +669,11 @@ hipError_t launch_param_grads(const float* kap0, const float* w, const float* h,
   const long long Ktot = (long long)T * B;
   const int M = 3 * H;
   prof_begin(3, s);
+  const size_t su = (size_t)grad_splits(Ktot, M, H) * M * H;
+  const size_t sw = (size_t)grad_splits(Ktot, M, D) * M * D;
+  float* bpart[2];
+  int nbpart[2];
+  bpart[0] = part + (su > sw ? su : sw);
   for (int which = 0; which < 2; ++which) {
     GradArgs a;
     a.kap0 = kap0;
@@ -651,7 +688,13 @@ hipError_t launch_param_grads(const float* kap0, const float* w, const float* h,
     const int splits = grad_splits(Ktot, M, a.N);
     long long per = (Ktot + splits - 1) / splits;
     a.Kper = (per + GTK - 1) / GTK * GTK;
-    dim3 grid((M + GT - 1) / GT, (a.N + GT - 1) / GT, splits);
+    a.mtiles = (M + GT - 1) / GT;
+    a.ntiles = (a.N + GT - 1) / GT;
+    a.splits = splits;
+    a.bpart = bpart[which];
+    nbpart[which] = splits * a.ntiles;
+    if (which == 0) bpart[1] = bpart[0] + (size_t)nbpart[0] * M;
+    dim3 grid((unsigned)((long long)a.mtiles * a.ntiles * splits));
     if (which == 1 && bf16)
       hipLaunchKernelGGL(grad_gemm_kernel<bf16_t>, grid, dim3(256), 0, s, a);
     else
@@ -660,12 +703,8 @@ hipError_t launch_param_grads(const float* kap0, const float* w, const float* h,
     hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
                        part, which == 0 ? dU : dW, n, splits);
   }
-  size_t su = (size_t)grad_splits(Ktot, M, H) * M * H, sw = (size_t)grad_splits(Ktot, M, D) * M * D;
-  float* bpart = part + (su > sw ? su : sw);
-  hipLaunchKernelGGL(bias_partial_kernel, dim3((4 * H + 255) / 256, BIAS_SPLITS), dim3(256), 0, s,
-                     kap0, w, bpart, Ktot, B, H);
-  hipLaunchKernelGGL(bias_reduce_kernel, dim3((4 * H + 255) / 256), dim3(256), 0, s, bpart, db_i,
-                     db_h, H);
+  hipLaunchKernelGGL(bias_reduce_kernel, dim3((3 * H + 255) / 256), dim3(256), 0, s, bpart[0],
+                     nbpart[0], bpart[1], nbpart[1], db_i, db_h, H);
   prof_end(3, 2.0 * (double)Ktot * M * (H + D),
            4.0 * (double)Ktot * (5.0 * H + H + H + D), s);
   return hipGetLastError();

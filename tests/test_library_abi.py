@@ -89,3 +89,14 @@ def test_strerror_names_codes():
     assert "divide" in mg.mgrit_gru_strerror(-3)
     with pytest.raises(mg.MgritGruError):
         mg.mgrit_gru_workspace_bytes(MgritGruCfg(60, 2, 16, 32, cf=4, levels=3))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # one GPU only: the bench exits with a message instead of starting ranks
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "--gpus 1" in r.stderr

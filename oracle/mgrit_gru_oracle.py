@@ -180,6 +180,40 @@ def serial_bptt(W, U, b_i, b_h, x, h, dL_dhT, propagator=IMPLICIT):
     return (w,) + parameter_gradients(W, U, b_i, b_h, x, h, w, propagator)
 
 
+def input_gradients(W, U, b_i, b_h, x, h, w, propagator=IMPLICIT):
+    """dL/dx_t = (dPhi_1/dx)^T(x_t, h_{t-1}) w_t for t = 1..T (row t-1 of the
+    result), the input-side counterpart of Alg. 3's gradient line: x_t enters the
+    step only through W x_t inside the three gates (Eq. 1), so
+    dL/dx_t = W_r^T(k_r w_t) + W_z^T(k_z w_t) + W_n^T(k_n w_t)."""
+    W, U, b_i, b_h, x, h, w = map(_f64, (W, U, b_i, b_h, x, h, w))
+    P = input_projection(W, b_i, x)
+    T = x.shape[0]
+    dx = np.empty_like(x)
+    for t in range(1, T + 1):
+        k_d, k_r, k_z, k_q, k_n = phi_adjoint_coeffs(1.0, P[t - 1], h[t - 1], U, b_h, propagator)
+        s_x = np.concatenate([k_r * w[t], k_z * w[t], k_n * w[t]], axis=-1)   # [B,3H]
+        dx[t - 1] = s_x @ W
+    return dx
+
+
+def serial_bptt_steps(W, U, b_i, b_h, x, h, dL_dh, propagator=IMPLICIT):
+    """Back-propagation through time for a loss that depends on every state:
+    dL_dh[(T+1),B,H] holds the direct derivative of the loss with respect to h_t
+    in row t.  w_T = dL_dh[T];  w_{t-1} = (dPhi_1/dh)^T(x_t, h_{t-1}) w_t + dL_dh[t-1]
+    (the adjoint recurrence of Appendix A.2 with a source term).  Returns
+    (w, dW, dU, db_i, db_h, dx)."""
+    W, U, b_i, b_h, x, h, dL_dh = map(_f64, (W, U, b_i, b_h, x, h, dL_dh))
+    P = input_projection(W, b_i, x)
+    T = x.shape[0]
+    w = np.empty_like(h)
+    w[T] = dL_dh[T]
+    for t in range(T, 0, -1):
+        co = phi_adjoint_coeffs(1.0, P[t - 1], h[t - 1], U, b_h, propagator)
+        w[t - 1] = phi_transpose(co, w[t], U) + dL_dh[t - 1]
+    return ((w,) + parameter_gradients(W, U, b_i, b_h, x, h, w, propagator)
+            + (input_gradients(W, U, b_i, b_h, x, h, w, propagator),))
+
+
 # --------------------------------------------------------------------------
 # MGRIT: relaxation (Alg. 1, Eq. 8), V-cycle (Alg. 2, Remark 2, Eq. 11)
 # --------------------------------------------------------------------------
@@ -287,7 +321,8 @@ def mgrit_forward(W, U, b_i, b_h, x, h0, h_init, cf, levels, iters,
 
 
 def mgrit_backward(W, U, b_i, b_h, x, h, dL_dhT, w_init, cf, levels, iters,
-                   fine_relax_fcf=True, propagator=IMPLICIT, keep_iterates=False):
+                   fine_relax_fcf=True, propagator=IMPLICIT, keep_iterates=False,
+                   dL_dh=None):
     """Alg. 3 backward block: `iters` applications of MGBackProp to the adjoint
     iterate w_init[(T+1),B,H] (row T is overwritten with dL/dh_T), then the
     parameter gradients from the final w (Alg. 3 gradient line).
@@ -297,7 +332,15 @@ def mgrit_backward(W, U, b_i, b_h, x, h, dL_dhT, w_init, cf, levels, iters,
     m = N_l - k the level-l step m-1 -> m is the transposed Jacobian of the
     forward level step k = N_l - m + 1, i.e. of Phi_{cf^l}(x_{k cf^l}, .)
     linearised at h_{(k-1) cf^l}, where h is the given forward iterate.
-    Returns (w, resnorms, dW, dU, db_i, db_h)."""
+    Returns (w, resnorms, dW, dU, db_i, db_h).
+
+    With dL_dh[(T+1),B,H] given (a loss on every state; dL_dhT is then ignored)
+    the adjoint recurrence carries the source term dL_dh[t] at point t: it is
+    the right-hand side of the level-0 equation, which the cycle restricts like
+    any other (Eq. 11); the result gains a last element dx = input_gradients."""
+    if dL_dh is not None:
+        dL_dh = _f64(dL_dh)
+        dL_dhT = dL_dh[-1]
     W, U, b_i, b_h, x, h, dL_dhT = map(_f64, (W, U, b_i, b_h, x, h, dL_dhT))
     T = x.shape[0]
     _check_hierarchy(T, cf, levels)
@@ -313,6 +356,8 @@ def mgrit_backward(W, U, b_i, b_h, x, h, dL_dhT, w_init, cf, levels, iters,
     w[T] = dL_dhT
     wr = w[::-1].copy()                           # reversed time: wr[m] = w[T-m]
     g0 = np.zeros_like(wr)
+    if dL_dh is not None:
+        g0[1:] = dL_dh[::-1][1:]                  # source at reversed point m is dL_dh[T-m]
     resnorms, iterates = [], []
     for _ in range(iters):
         wr = v_cycle(step, cf, levels, 0, wr, g0, fine_relax_fcf, resnorms)
@@ -320,9 +365,50 @@ def mgrit_backward(W, U, b_i, b_h, x, h, dL_dhT, w_init, cf, levels, iters,
             iterates.append(wr[::-1].copy())
     w = wr[::-1].copy()
     grads = parameter_gradients(W, U, b_i, b_h, x, h, w, propagator)
+    if dL_dh is not None:
+        grads = grads + (input_gradients(W, U, b_i, b_h, x, h, w, propagator),)
     if keep_iterates:
         return (w, resnorms) + grads + (iterates,)
     return (w, resnorms) + grads
+
+
+# --------------------------------------------------------------------------
+# Stacked layers
+# --------------------------------------------------------------------------
+# The experiments use two GRU layers (Tables of Sec. 4) without saying how layers
+# enter the time integration.  Reading taken here: the usual stacked network, layer
+# j+1 reading the state sequence of layer j as its input sequence
+# (x^{j+1}_t = h^j_t), each layer solved by its own MGRIT solve, layers in order.
+
+def stacked_forward(params, x, h0s, solve):
+    """params: list of (W, U, b_i, b_h); h0s: list of h_0 per layer; solve(layer,
+    W, U, b_i, b_h, x, h0) -> h[(T+1),B,H].  Returns the list of state arrays."""
+    hs = []
+    inp = _f64(x)
+    for j, (W, U, b_i, b_h) in enumerate(params):
+        h = solve(j, W, U, b_i, b_h, inp, h0s[j])
+        hs.append(h)
+        inp = h[1:]
+    return hs
+
+
+def stacked_backward(params, x, hs, dL_dh_top, solve_adjoint):
+    """Reverse pass through the stack: the top layer's source term is the loss
+    derivative dL_dh_top[(T+1),B,H]; layer j receives dL/dx^{j+1}_t as the source
+    at its point t.  solve_adjoint(layer, W, U, b_i, b_h, x, h, dL_dh) ->
+    (w, dW, dU, db_i, db_h, dx).  Returns the per-layer results, bottom layer first."""
+    out = [None] * len(params)
+    src = _f64(dL_dh_top)
+    for j in range(len(params) - 1, -1, -1):
+        W, U, b_i, b_h = params[j]
+        inp = _f64(x) if j == 0 else hs[j - 1][1:]
+        res = solve_adjoint(j, W, U, b_i, b_h, inp, hs[j], src)
+        out[j] = res
+        dx = res[5]
+        src = np.zeros_like(hs[j - 1]) if j > 0 else None
+        if j > 0:
+            src[1:] = dx                           # x^{j}_t = h^{j-1}_t for t = 1..T
+    return out
 
 
 # --------------------------------------------------------------------------

@@ -376,3 +376,122 @@ def test_cross_entropy_head_gradient_matches_autograd():
     lt.backward()
     assert abs(loss - lt.item()) < 1e-12
     assert np.allclose(g, ht.grad.numpy(), atol=1e-13)
+
+
+# ---------------------------------------------------------------- loss on every state, dL/dx, layers
+
+def _two_layer(seed, T, B, D, H):
+    """Seeded two-layer parameter set: layer 1 reads D features, layer 2 reads H."""
+    d1 = random_small(seed, T, B, D, H)
+    d2 = random_small(seed + 1, T, B, H, H)
+    params = [_params(d1), _params(d2)]
+    rng = np.random.default_rng(seed + 2)
+    c = 0.3 * rng.standard_normal((T + 1, B, H))        # loss L = sum_t <c_t, h^top_t>
+    c[0] = 0.0
+    return d1, d2, params, c
+
+
+def test_two_layer_classic_stack_is_the_library_gru_with_a_loss_on_every_step():
+    """torch.nn.GRU(num_layers=2) is the stacked network in which layer 2 reads the
+    states of layer 1.  With a loss on every top-layer state its autograd fixes the
+    source term of the adjoint recurrence, the input gradient dL/dx (which carries
+    the loss into layer 1) and both layers' parameter gradients."""
+    T, B, D, H = 9, 3, 5, 4
+    d1, d2, params, c = _two_layer(41, T, B, D, H)
+    gru = torch.nn.GRU(D, H, num_layers=2, bias=True, batch_first=False).double()
+    with torch.no_grad():
+        for j, (W, U, b_i, b_h) in enumerate(params):
+            getattr(gru, f"weight_ih_l{j}").copy_(torch.from_numpy(W).double())
+            getattr(gru, f"weight_hh_l{j}").copy_(torch.from_numpy(U).double())
+            getattr(gru, f"bias_ih_l{j}").copy_(torch.from_numpy(b_i).double())
+            getattr(gru, f"bias_hh_l{j}").copy_(torch.from_numpy(b_h).double())
+    x = torch.from_numpy(d1["x"]).double().requires_grad_(True)
+    h0 = torch.stack([torch.from_numpy(d1["h0"]), torch.from_numpy(d2["h0"])]).double()
+    h0.requires_grad_(True)
+    out, _ = gru(x, h0)
+    (out * torch.from_numpy(c[1:])).sum().backward()
+
+    h0s = [d1["h0"], d2["h0"]]
+    hs = orc.stacked_forward(
+        params, d1["x"], h0s,
+        lambda j, W, U, bi, bh, xin, h0_: orc.serial_scan(W, U, bi, bh, xin, h0_, orc.CLASSIC))
+    assert np.allclose(hs[1][1:], out.detach().numpy(), atol=1e-13)
+    res = orc.stacked_backward(
+        params, d1["x"], hs, c,
+        lambda j, W, U, bi, bh, xin, h, src: orc.serial_bptt_steps(W, U, bi, bh, xin, h, src,
+                                                                   orc.CLASSIC))
+    assert np.allclose(res[0][5], x.grad.numpy(), atol=1e-12)            # dL/dx of layer 1
+    for j in range(2):
+        w, dW, dU, db_i, db_h, dx = res[j]
+        assert np.allclose(w[0], h0.grad[j].numpy(), atol=1e-12)
+        assert np.allclose(dW, getattr(gru, f"weight_ih_l{j}").grad.numpy(), atol=1e-12)
+        assert np.allclose(dU, getattr(gru, f"weight_hh_l{j}").grad.numpy(), atol=1e-12)
+        assert np.allclose(db_i, getattr(gru, f"bias_ih_l{j}").grad.numpy(), atol=1e-12)
+        assert np.allclose(db_h, getattr(gru, f"bias_hh_l{j}").grad.numpy(), atol=1e-12)
+
+
+@pytest.mark.parametrize("prop", [orc.IMPLICIT, orc.CLASSIC])
+def test_step_loss_gradients_match_central_finite_differences(prop):
+    """Loss on every state, Implicit and Classic step: w_0, dL/dx and the parameter
+    gradients equal central finite differences of the serial propagation."""
+    T, B, D, H = 10, 2, 3, 4
+    d = {k: v.astype(np.float64) for k, v in random_small(17, T, B, D, H).items()}
+    rng = np.random.default_rng(5)
+    c = 0.4 * rng.standard_normal((T + 1, B, H))
+
+    def loss(**over):
+        p = dict(d)
+        p.update(over)
+        h = orc.serial_scan(p["W"], p["U"], p["b_i"], p["b_h"], p["x"], p["h0"], prop)
+        return float(np.sum(h * c))
+
+    h = orc.serial_scan(*_params(d), d["x"], d["h0"], prop)
+    w, dW, dU, db_i, db_h, dx = orc.serial_bptt_steps(*_params(d), d["x"], h, c, prop)
+    got = {"W": dW, "U": dU, "b_i": db_i, "b_h": db_h, "h0": w[0], "x": dx}
+    eps = 1e-6
+    for name, grad in got.items():
+        fd = np.zeros_like(grad)
+        it = np.nditer(grad, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            ap, am = d[name].copy(), d[name].copy()
+            ap[idx] += eps
+            am[idx] -= eps
+            fd[idx] = (loss(**{name: ap}) - loss(**{name: am})) / (2 * eps)
+        assert _rel(grad, fd) < 1e-7, name
+
+
+def test_terminal_loss_is_the_special_case_of_the_step_loss():
+    T, B, D, H = 8, 2, 3, 4
+    d = random_small(19, T, B, D, H)
+    h = orc.serial_scan(*_params(d), d["x"], d["h0"])
+    src = np.zeros((T + 1, B, H))
+    src[T] = d["dL_dhT"]
+    a = orc.serial_bptt(*_params(d), d["x"], h, d["dL_dhT"])
+    b = orc.serial_bptt_steps(*_params(d), d["x"], h, src)
+    for u, v in zip(a, b[:5]):
+        assert np.array_equal(u, v)
+
+
+@pytest.mark.parametrize("levels,fcf", [(2, True), (2, False), (3, True)])
+def test_adjoint_mgrit_with_source_term_converges_to_step_bptt(levels, fcf):
+    """The source term is the right-hand side of the level-0 adjoint equation; the
+    cycle restricts it like any right-hand side (Eq. 11).  The exactness front of
+    the reversed-time cycle is unchanged and the converged result is the serial
+    adjoint with source, pinned by finite differences and the library GRU above."""
+    cf = 2
+    T = 8 * cf ** (levels - 1)
+    d = random_small(37, T, 2, 3, 4)
+    rng = np.random.default_rng(9)
+    src = 0.3 * rng.standard_normal((T + 1, 2, 4))
+    h = orc.serial_scan(*_params(d), d["x"], d["h0"])
+    ref = orc.serial_bptt_steps(*_params(d), d["x"], h, src)
+    out = orc.mgrit_backward(*_params(d), d["x"], h, None, np.zeros_like(h), cf, levels, T // cf,
+                             fine_relax_fcf=fcf, keep_iterates=True, dL_dh=src)
+    its = out[-1]
+    for i, w in enumerate(its, start=1):
+        front = max(T - ((i + 1) * cf - 1), 0) if fcf else max(T - (i * cf - 1), 0)
+        assert np.allclose(w[front:], ref[0][front:], rtol=0, atol=1e-12), i
+    w, res, gW, gU, gbi, gbh, gx = out[:7]
+    for a, b in zip((w, gW, gU, gbi, gbh, gx), ref):
+        assert np.allclose(a, b, atol=1e-11)

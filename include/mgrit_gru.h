@@ -145,6 +145,34 @@ MGRIT_API int mgrit_gru_backward(const mgrit_gru_cfg* cfg, const void* W, const 
                        float* dW, float* dU, float* db_i, float* db_h,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* The two back-propagations above for a loss that depends on every state, and
+ * with the gradient with respect to the inputs: what a stack of GRU layers
+ * (Sec. 4: two layers in every experiment) needs, layer j+1 reading the states
+ * of layer j as its input sequence and handing dL/dx back as layer j's loss term.
+ *   dL_dh[(T+1),B,H] in (device, 16-byte aligned): row t holds the direct
+ *     derivative of the loss with respect to h_t (row 0: h_0).  The adjoint
+ *     recurrence of Appendix A.2 gains it as a source term,
+ *         w_T = dL_dh[T],   w_{t-1} = (dPhi_1/dh)^T(x_t,h_{t-1}) w_t + dL_dh[t-1],
+ *     which is the right-hand side of the level-0 equation of the cycle; coarse
+ *     levels receive it through the restriction of Eq. 11 like any residual.
+ *     A loss on h_T alone is the array that is zero except for row T.
+ *   dx[T,B,D] out (device, float, may be NULL): row t-1 receives
+ *     dL/dx_t = (dPhi_1/dx)^T(x_t,h_{t-1}) w_t, formed from the final w like the
+ *     parameter gradients (Alg. 3, gradient line).
+ * All other arguments, and the error behaviour, are those of
+ * gru_serial_scan_backward / mgrit_gru_backward. */
+MGRIT_API int gru_serial_scan_backward_steps(const mgrit_gru_cfg* cfg, const void* W,
+                             const void* U, const float* b_i, const float* b_h, const void* x,
+                             const float* h, const float* dL_dh, float* w_out,
+                             float* dW, float* dU, float* db_i, float* db_h, float* dx,
+                             void* workspace, size_t workspace_bytes, void* stream);
+MGRIT_API int mgrit_gru_backward_steps(const mgrit_gru_cfg* cfg, const void* W, const void* U,
+                       const float* b_i, const float* b_h, const void* x,
+                       const float* h, const float* dL_dh, float* w_inout,
+                       float* resnorm_out,
+                       float* dW, float* dU, float* db_i, float* db_h, float* dx,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
 /* Name of an error code (host string with static storage). */
 MGRIT_API const char* mgrit_gru_strerror(int code);
 
@@ -157,7 +185,8 @@ MGRIT_API const char* mgrit_gru_strerror(int code);
  * host-side and created on demand; nothing here touches device memory.
  *   kind: 0 = forward step (Phi) on MFMA tiles, 1 = adjoint step (Phi^T) on MFMA tiles,
  *         2 = projection GEMM, 3 = weight-gradient GEMMs, 4 / 5 = forward / adjoint step
- *         in the few-row form used by the serial scan and the coarsest-level solve.
+ *         in the few-row form used by the serial scan and the coarsest-level solve,
+ *         6 = input-gradient GEMM.
  * All out-pointers are host pointers. */
 MGRIT_API int mgrit_gru_profile_enable(int on);
 MGRIT_API int mgrit_gru_profile_read(int kind, int64_t* launches, double* ms,

@@ -4,9 +4,11 @@ from .binding import (  # noqa: F401
     MgritGruError,
     gru_serial_scan,
     gru_serial_scan_backward,
+    gru_serial_scan_backward_steps,
     lib,
     lib_path,
     mgrit_gru_backward,
+    mgrit_gru_backward_steps,
     mgrit_gru_forward,
     mgrit_gru_profile_enable,
     mgrit_gru_profile_read,

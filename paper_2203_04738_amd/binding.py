@@ -63,6 +63,10 @@ def lib() -> ctypes.CDLL:
                                            vp, sz, vp]
     L.mgrit_gru_backward.argtypes = [cfgp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, fp, fp, fp,
                                      vp, sz, vp]
+    L.gru_serial_scan_backward_steps.argtypes = [cfgp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, fp,
+                                                 fp, fp, vp, sz, vp]
+    L.mgrit_gru_backward_steps.argtypes = [cfgp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, fp, fp,
+                                           fp, fp, vp, sz, vp]
     L.mgrit_gru_strerror.argtypes = [ctypes.c_int]
     L.mgrit_gru_strerror.restype = ctypes.c_char_p
     L.mgrit_gru_profile_enable.argtypes = [ctypes.c_int]
@@ -71,7 +75,9 @@ def lib() -> ctypes.CDLL:
                                          ctypes.POINTER(ctypes.c_double),
                                          ctypes.POINTER(ctypes.c_double)]
     for name in ("mgrit_gru_workspace_bytes", "gru_serial_scan", "mgrit_gru_forward",
-                 "gru_serial_scan_backward", "mgrit_gru_backward", "mgrit_gru_profile_enable",
+                 "gru_serial_scan_backward", "mgrit_gru_backward",
+                 "gru_serial_scan_backward_steps", "mgrit_gru_backward_steps",
+                 "mgrit_gru_profile_enable",
                  "mgrit_gru_profile_read"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
@@ -163,6 +169,33 @@ def mgrit_gru_backward(cfg, W, U, b_i, b_h, x, h, dL_dhT, w_inout, resnorm_out, 
         _ptr(dW, "dW", f32), _ptr(dU, "dU", f32), _ptr(db_i, "db_i", f32), _ptr(db_h, "db_h", f32),
         _ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()),
         "mgrit_gru_backward")
+
+
+def gru_serial_scan_backward_steps(cfg, W, U, b_i, b_h, x, h, dL_dh, w_out, dW, dU, db_i, db_h,
+                                   dx, workspace) -> None:
+    import torch
+    f32, dt = torch.float32, _in_dtype(cfg)
+    _check(lib().gru_serial_scan_backward_steps(
+        ctypes.byref(cfg), _ptr(W, "W", dt), _ptr(U, "U", dt), _ptr(b_i, "b_i", f32),
+        _ptr(b_h, "b_h", f32), _ptr(x, "x", dt), _ptr(h, "h", f32), _ptr(dL_dh, "dL_dh", f32),
+        _ptr(w_out, "w_out", f32), _ptr(dW, "dW", f32), _ptr(dU, "dU", f32),
+        _ptr(db_i, "db_i", f32), _ptr(db_h, "db_h", f32), _ptr(dx, "dx", f32),
+        _ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()),
+        "gru_serial_scan_backward_steps")
+
+
+def mgrit_gru_backward_steps(cfg, W, U, b_i, b_h, x, h, dL_dh, w_inout, resnorm_out, dW, dU,
+                             db_i, db_h, dx, workspace) -> None:
+    import torch
+    f32, dt = torch.float32, _in_dtype(cfg)
+    _check(lib().mgrit_gru_backward_steps(
+        ctypes.byref(cfg), _ptr(W, "W", dt), _ptr(U, "U", dt), _ptr(b_i, "b_i", f32),
+        _ptr(b_h, "b_h", f32), _ptr(x, "x", dt), _ptr(h, "h", f32), _ptr(dL_dh, "dL_dh", f32),
+        _ptr(w_inout, "w_inout", f32), _ptr(resnorm_out, "resnorm_out", f32),
+        _ptr(dW, "dW", f32), _ptr(dU, "dU", f32), _ptr(db_i, "db_i", f32), _ptr(db_h, "db_h", f32),
+        _ptr(dx, "dx", f32),
+        _ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()),
+        "mgrit_gru_backward_steps")
 
 
 def mgrit_gru_profile_enable(on: bool) -> None:

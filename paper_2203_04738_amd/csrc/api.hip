@@ -57,7 +57,7 @@ struct Layout {
   size_t tmp;                     // cf == 1 only: Jacobi scratch for the C-sweep
   size_t norm;
   size_t kap[MAX_LEVELS];
-  size_t UT, part;
+  size_t UT, WT, part;
   size_t total;
 };
 
@@ -117,6 +117,8 @@ static int make_layout(const mgrit_gru_cfg* c, Layout* lay) {
   }
   lay->UT = off;
   off = align_up(off + (size_t)3 * c->H * c->H * sizeof(float));
+  lay->WT = off;
+  off = align_up(off + (size_t)3 * c->H * c->D * sizeof(float));
   lay->part = off;
   off = align_up(off + grad_partial_floats(c->T, c->B, c->D, c->H) * sizeof(float));
   lay->total = off;
@@ -412,11 +414,17 @@ static int vcycle_bwd(const BwdCtx& x, int l, bool f_points_current = false) {
 
 static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, const void* U,
                          const float* b_i, const float* b_h, const void* x, const float* h,
-                         const float* dL_dhT, float* w, float* resnorm, float* dW, float* dU,
-                         float* db_i, float* db_h, void* ws, size_t ws_bytes, void* stream) {
+                         const float* dL_dhT, const float* dL_dh, float* w, float* resnorm,
+                         float* dW, float* dU, float* db_i, float* db_h, float* dx, void* ws,
+                         size_t ws_bytes, void* stream) {
   int rc = check_cfg(cin, !serial);
   if (rc) return rc;
+  // a loss on every state: dL_dh[(T+1),B,H] is the source term of the adjoint
+  // recurrence, i.e. the right-hand side of the level-0 equation; its last row is
+  // the terminal condition
+  if (dL_dh) dL_dhT = dL_dh + (size_t)cin->T * cin->B * cin->H;
   if (!W || !U || !b_i || !b_h || !x || !h || !dL_dhT || !w || !ws) return MGRIT_E_NULL;
+  if (misaligned(dL_dh) || misaligned(dx)) return MGRIT_E_ALIGN;
   const int ngrad = (dW != nullptr) + (dU != nullptr) + (db_i != nullptr) + (db_h != nullptr);
   if (ngrad != 0 && ngrad != 4) return MGRIT_E_NULL;
   if (serial && ngrad != 4) return MGRIT_E_NULL;
@@ -449,7 +457,7 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
   ctx.s = s;
   ctx.tmp = (float*)(base + lay.tmp);
   ctx.wl[0] = w;
-  ctx.gl[0] = nullptr;
+  ctx.gl[0] = const_cast<float*>(dL_dh);   // level 0 only reads its right-hand side
   for (int l = 0; l < lay.L; ++l) {
     ctx.kap[l] = (const float*)(base + lay.kap[l]);
     if (l > 0) {
@@ -490,6 +498,10 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
   if (ngrad == 4)
     CHECK_HIP(launch_param_grads(ctx.kap[0], w, h, x, dW, dU, db_i, db_h,
                                  (float*)(base + lay.part), c.T, c.B, c.D, c.H, bf16, s));
+  if (dx) {
+    CHECK_HIP(launch_transpose(W, base + lay.WT, 3 * c.H, c.D, bf16, s));
+    CHECK_HIP(launch_input_grads(ctx.kap[0], w, base + lay.WT, dx, c.T, c.B, c.D, c.H, bf16, s));
+  }
   return MGRIT_OK;
 }
 
@@ -530,16 +542,36 @@ int gru_serial_scan_backward(const mgrit_gru_cfg* cfg, const void* W, const void
                              const float* b_i, const float* b_h, const void* x, const float* h,
                              const float* dL_dhT, float* w_out, float* dW, float* dU, float* db_i,
                              float* db_h, void* workspace, size_t workspace_bytes, void* stream) {
-  return backward_impl(cfg, true, W, U, b_i, b_h, x, h, dL_dhT, w_out, nullptr, dW, dU, db_i,
-                       db_h, workspace, workspace_bytes, stream);
+  return backward_impl(cfg, true, W, U, b_i, b_h, x, h, dL_dhT, nullptr, w_out, nullptr, dW, dU,
+                       db_i, db_h, nullptr, workspace, workspace_bytes, stream);
+}
+
+int gru_serial_scan_backward_steps(const mgrit_gru_cfg* cfg, const void* W, const void* U,
+                                   const float* b_i, const float* b_h, const void* x,
+                                   const float* h, const float* dL_dh, float* w_out, float* dW,
+                                   float* dU, float* db_i, float* db_h, float* dx,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+  if (!dL_dh) return MGRIT_E_NULL;
+  return backward_impl(cfg, true, W, U, b_i, b_h, x, h, nullptr, dL_dh, w_out, nullptr, dW, dU,
+                       db_i, db_h, dx, workspace, workspace_bytes, stream);
+}
+
+int mgrit_gru_backward_steps(const mgrit_gru_cfg* cfg, const void* W, const void* U,
+                             const float* b_i, const float* b_h, const void* x, const float* h,
+                             const float* dL_dh, float* w_inout, float* resnorm_out, float* dW,
+                             float* dU, float* db_i, float* db_h, float* dx, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  if (!dL_dh) return MGRIT_E_NULL;
+  return backward_impl(cfg, false, W, U, b_i, b_h, x, h, nullptr, dL_dh, w_inout, resnorm_out, dW,
+                       dU, db_i, db_h, dx, workspace, workspace_bytes, stream);
 }
 
 int mgrit_gru_backward(const mgrit_gru_cfg* cfg, const void* W, const void* U, const float* b_i,
                        const float* b_h, const void* x, const float* h, const float* dL_dhT,
                        float* w_inout, float* resnorm_out, float* dW, float* dU, float* db_i,
                        float* db_h, void* workspace, size_t workspace_bytes, void* stream) {
-  return backward_impl(cfg, false, W, U, b_i, b_h, x, h, dL_dhT, w_inout, resnorm_out, dW, dU,
-                       db_i, db_h, workspace, workspace_bytes, stream);
+  return backward_impl(cfg, false, W, U, b_i, b_h, x, h, dL_dhT, nullptr, w_inout, resnorm_out,
+                       dW, dU, db_i, db_h, nullptr, workspace, workspace_bytes, stream);
 }
 
 const char* mgrit_gru_strerror(int code) {

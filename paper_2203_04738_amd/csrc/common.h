@@ -80,6 +80,11 @@ hipError_t launch_param_grads(const float* kap0, const float* w, const float* h,
                               float* dW, float* dU, float* db_i, float* db_h, float* part,
                               int T, int B, int D, int H, int bf16, hipStream_t s);
 
+// Input gradients dx[T,B,D] from the level-0 coefficients, the adjoint w and the
+// transposed input weights WT[D,3H] (float, or bf16 with bf16 = 1).
+hipError_t launch_input_grads(const float* kap0, const float* w, const void* WT, float* dx, int T,
+                              int B, int D, int H, int bf16, hipStream_t s);
+
 hipError_t launch_fill_f64(double* p, long long n, double v, hipStream_t s);
 // dst[(d.off + i*d.str), :, :] = src[(s.off + i*s.str), :, :] for i < nk; blocks of `block` floats
 hipError_t launch_copy_points(float* dst, const float* src, Idx d, Idx s, int nk, long long block,

@@ -255,6 +255,143 @@ __global__ __launch_bounds__(C::NT, 2) void adj_step_kernel_bf16(AdjArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// Input gradients: dx[R, D] = S_x[R, 3H] . WT[D, 3H]^T,  S_x = (k_r w, k_z w, k_n w)
+// of step t in row (t-1)*B + b  (input-side counterpart of Alg. 3's gradient line)
+// ---------------------------------------------------------------------------
+typedef TileCfg<2, 2, 2, 2, 1> DxCfg;            // 128 x 128 tile
+typedef TileCfgB<2, 2, 2, 2, 1, true> DxCfgB;
+
+// Stores one accumulator tile of a plain GEMM: out[m, n], leading dimension N.
+template <class C>
+__device__ inline void store_tile(const Acc<C>& acc, float* out, long long m0, int n0,
+                                  long long M, int N) {
+#pragma unroll
+  for (int a = 0; a < C::BM; ++a)
+#pragma unroll
+    for (int b = 0; b < C::BN; ++b) {
+      int row, col;
+      acc_coord<C>(a, b, 0, row, col);
+      const int n = n0 + col;
+      if (n >= N) continue;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        acc_coord<C>(a, b, e, row, col);
+        const long long m = m0 + row;
+        if (m < M) out[m * N + n] = acc.v[0][a][b][e];
+      }
+    }
+}
+
+__global__ __launch_bounds__(DxCfg::NT) void input_grad_kernel(
+    const float* __restrict__ kap0, const float* __restrict__ w, const float* __restrict__ WT,
+    float* __restrict__ dx, long long R, int B, int H, int D) {
+  typedef DxCfg C;
+  __shared__ __attribute__((aligned(16))) float lds[C::LDS_FLOATS];
+  const int K = 3 * H;
+  long long rt;
+  int ct;
+  if (!xcd_tile(blockIdx.x, (R + C::TM - 1) / C::TM, (D + C::TN - 1) / C::TN, rt, ct)) return;
+  const long long m0 = rt * C::TM;
+  const int n0 = ct * C::TN;
+  // coefficient and adjoint rows are one time point ahead of the dx row
+  const float* krow[C::A_CHUNKS];
+  const float* wrow[C::A_CHUNKS];
+  const float* brow[C::B_CHUNKS];
+#pragma unroll
+  for (int s = 0; s < C::A_CHUNKS; ++s) {
+    long long r = m0 + chunk_row<C>(s);
+    if (r >= R) r = R - 1;     // clamped rows are never stored
+    krow[s] = kap0 + (r + B) * (5LL * H);
+    wrow[s] = w + (r + B) * H;
+  }
+#pragma unroll
+  for (int s = 0; s < C::B_CHUNKS; ++s) {
+    int n = n0 + chunk_row<C>(s);
+    if (n >= D) n = D - 1;
+    brow[s] = WT + (long long)n * K;
+  }
+  Acc<C> acc;
+  acc.zero();
+  auto la = [&](int s, int k) {
+    // third gate: k_n is the fifth coefficient block
+    const int kk = k >= 2 * H ? k - 2 * H : (k >= H ? k - H : k);
+    const int ks = k >= 2 * H ? k + 2 * H : k;
+    return KapW{ldg4(krow[s] + ks), ldg4(wrow[s] + kk)};
+  };
+  auto lb = [&](int s, int k) { return ldg4(brow[s] + k); };
+  auto fa = [](const KapW& r) { return r.kap * r.w; };
+  if (K % C::TK == 0)
+    gemm_nt_tile<C, false>(acc, K, la, lb, fa, Identity4(), lds);
+  else
+    gemm_nt_tile<C, true>(acc, K, la, lb, fa, Identity4(), lds);
+  store_tile<C>(acc, dx, m0, n0, R, D);
+}
+
+__global__ __launch_bounds__(DxCfgB::NT) void input_grad_kernel_bf16(
+    const float* __restrict__ kap0, const float* __restrict__ w, const bf16_t* __restrict__ WT,
+    float* __restrict__ dx, long long R, int B, int H, int D) {
+  typedef DxCfgB C;
+  __shared__ __attribute__((aligned(16))) bf16_t lds[C::LDS_ELEMS];
+  const int K = 3 * H;
+  long long rt;
+  int ct;
+  if (!xcd_tile(blockIdx.x, (R + C::TM - 1) / C::TM, (D + C::TN - 1) / C::TN, rt, ct)) return;
+  const long long m0 = rt * C::TM;
+  const int n0 = ct * C::TN;
+  const float* krow[C::A_CHUNKS];
+  const float* wrow[C::A_CHUNKS];
+  const bf16_t* brow[C::B_CHUNKS];
+#pragma unroll
+  for (int s = 0; s < C::A_CHUNKS; ++s) {
+    long long r = m0 + chunk_row_b<C>(s);
+    if (r >= R) r = R - 1;
+    krow[s] = kap0 + (r + B) * (5LL * H);
+    wrow[s] = w + (r + B) * H;
+  }
+#pragma unroll
+  for (int s = 0; s < C::B_CHUNKS; ++s) {
+    int n = n0 + chunk_row_b<C>(s);
+    if (n >= D) n = D - 1;
+    brow[s] = WT + (long long)n * K;
+  }
+  Acc<C> acc;
+  acc.zero();
+  auto la = [&](int s, int k) {
+    const int kk = k >= 2 * H ? k - 2 * H : (k >= H ? k - H : k);
+    const int ks = k >= 2 * H ? k + 2 * H : k;
+    return KapW8{ldg4(krow[s] + ks), ldg4(krow[s] + ks + 4), ldg4(wrow[s] + kk),
+                 ldg4(wrow[s] + kk + 4)};
+  };
+  auto lb = [&](int s, int k) { return ldg8h(brow[s] + k); };
+  auto fa = [](const KapW8& r) { return F32x8{r.k0 * r.w0, r.k1 * r.w1}; };
+  if (K % C::TK == 0)
+    gemm_nt_tile_bf16<C, false>(acc, K, la, lb, fa, lds);
+  else
+    gemm_nt_tile_bf16<C, true>(acc, K, la, lb, fa, lds);
+  store_tile<C>(acc, dx, m0, n0, R, D);
+}
+
+hipError_t launch_input_grads(const float* kap0, const float* w, const void* WT, float* dx, int T,
+                              int B, int D, int H, int bf16, hipStream_t s) {
+  const long long R = (long long)T * B;
+  prof_begin(6, s);
+  if (bf16) {
+    typedef DxCfgB C;
+    dim3 grid((unsigned)xcd_grid((R + C::TM - 1) / C::TM, (D + C::TN - 1) / C::TN));
+    hipLaunchKernelGGL(input_grad_kernel_bf16, grid, dim3(C::NT), 0, s, kap0, w,
+                       (const bf16_t*)WT, dx, R, B, H, D);
+  } else {
+    typedef DxCfg C;
+    dim3 grid((unsigned)xcd_grid((R + C::TM - 1) / C::TM, (D + C::TN - 1) / C::TN));
+    hipLaunchKernelGGL(input_grad_kernel, grid, dim3(C::NT), 0, s, kap0, w, (const float*)WT, dx,
+                       R, B, H, D);
+  }
+  prof_end(6, 2.0 * (double)R * 3 * H * D,
+           4.0 * (double)R * (4.0 * H + D) + (bf16 ? 2.0 : 4.0) * 3.0 * H * D, s);
+  return hipGetLastError();
+}
+
 // Few-row variant (coarsest-level solve, serial BPTT): see skinny.h
 template <int CT>
 struct AdjSkMaxNT {

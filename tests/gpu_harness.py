@@ -99,6 +99,39 @@ class GpuRun:
             done += n
         return its, norms, grads
 
+    # ---- loss on every state, input gradients
+    def _dev(self, a):
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV)
+
+    def serial_backward_steps(self, h, dL_dh, want_dx=True):
+        hd, sd = self._dev(h), self._dev(dL_dh)
+        w = torch.full((self.T + 1, self.B, self.H), float("nan"), device=DEV)
+        g = self._grads()
+        dx = torch.full((self.T, self.B, self.D), float("nan"), device=DEV) if want_dx else None
+        mg.gru_serial_scan_backward_steps(self.cfg(), *self._p(), hd, sd, w, *g, dx, self.ws)
+        torch.cuda.synchronize()
+        return ((w.cpu().numpy(),) + tuple(a.cpu().numpy() for a in g)
+                + ((dx.cpu().numpy(),) if want_dx else ()))
+
+    def backward_steps_iterates(self, h, dL_dh, iters, per_call=1, want_dx=True):
+        hd, sd = self._dev(h), self._dev(dL_dh)
+        w = torch.zeros(self.T + 1, self.B, self.H, device=DEV)
+        its, norms, grads = [], [], None
+        done = 0
+        while done < iters:
+            n = min(per_call, iters - done)
+            res = torch.full((n,), float("nan"), device=DEV)
+            g = self._grads()
+            dx = (torch.full((self.T, self.B, self.D), float("nan"), device=DEV)
+                  if want_dx else None)
+            mg.mgrit_gru_backward_steps(self.cfg(n), *self._p(), hd, sd, w, res, *g, dx, self.ws)
+            torch.cuda.synchronize()
+            its.append(w.cpu().numpy().copy())
+            norms += res.cpu().numpy().tolist()
+            grads = tuple(a.cpu().numpy() for a in g) + ((dx.cpu().numpy(),) if want_dx else ())
+            done += n
+        return its, norms, grads
+
 
 def rel_err(got, ref):
     """max |got - ref| / max |ref| over a tensor (states cross zero, so element-wise

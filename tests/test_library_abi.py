@@ -84,6 +84,25 @@ def test_entry_points_reject_null_and_small_workspace_without_a_gpu():
                                 None, p, 1 << 30, None) == -1
 
 
+def test_step_loss_entry_points_validate_their_arguments_without_a_gpu():
+    L = mg.lib()
+    cfg = MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, iters=1)
+    p = 4096
+    # the loss array is required
+    assert L.mgrit_gru_backward_steps(ctypes.byref(cfg), p, p, p, p, p, p, None, p, None, p, p,
+                                      p, p, p, p, 1 << 30, None) == -1
+    assert L.gru_serial_scan_backward_steps(ctypes.byref(cfg), p, p, p, p, p, p, None, p, p, p,
+                                            p, p, p, p, 1 << 30, None) == -1
+    # misaligned loss array or dx
+    assert L.mgrit_gru_backward_steps(ctypes.byref(cfg), p, p, p, p, p, p, p + 4, p, None, p, p,
+                                      p, p, p, p, 1 << 30, None) == -6
+    assert L.mgrit_gru_backward_steps(ctypes.byref(cfg), p, p, p, p, p, p, p, p, None, p, p,
+                                      p, p, p + 8, p, 1 << 30, None) == -6
+    # too-small workspace: refused before any launch
+    assert L.mgrit_gru_backward_steps(ctypes.byref(cfg), p, p, p, p, p, p, p, p, None, p, p,
+                                      p, p, p, p, 16, None) == -5
+
+
 def test_strerror_names_codes():
     assert mg.mgrit_gru_strerror(0) == "ok"
     assert "divide" in mg.mgrit_gru_strerror(-3)

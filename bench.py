@@ -29,7 +29,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C3", help="C1..C5 (BASELINE.json configs in order)")
+    ap.add_argument("--workload", default="C3",
+                    help="C1..C5 (BASELINE.json configs in order); P1: the paper's HMDB51 shape")
     ap.add_argument("--fwd-iters", type=int, default=None)
     ap.add_argument("--bwd-iters", type=int, default=None)
     ap.add_argument("--fine-relax", choices=["FCF", "F"], default="FCF",
@@ -39,6 +40,9 @@ def parse():
                     help="forward only: first find the number of cycles after which the level-0 "
                          "residual, relative to the norm of the serial solution, is below 1e-8 or has "
                          "stopped decreasing (fp32 floor), then time that many cycles")
+    ap.add_argument("--layers", type=int, default=1,
+                    help="2: a stack of two GRU layers (layer 2 reads the states of layer 1; "
+                         "fp32 workloads only), each solved by its own MGRIT solve")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-serial", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -88,12 +92,198 @@ def cpu_baseline(wl, fwd_iters, bwd_iters, fcf=True):
                       f"bwd cycles, numpy float64, {dt:.1f} s"}
 
 
+def stack_cpu_baseline(wl, layers, fwd_iters, bwd_iters, fcf=True):
+    """The oracle's stacked solve on the reduced twin (T = 8*cf^(levels-1))."""
+    import numpy as np
+    from oracle import mgrit_gru_oracle as orc
+    from synthetic_inputs import layer_workload, make_inputs
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    tw = wl.twin(min(8, wl.T // wl.cf ** (wl.levels - 1)))
+    ds = [make_inputs(layer_workload(tw, j)) for j in range(layers)]
+    params = [(d["W"], d["U"], d["b_i"], d["b_h"]) for d in ds]
+    z = np.zeros((tw.T + 1, tw.B, tw.H))
+    t0 = time.perf_counter()
+    hs = orc.stacked_forward(
+        params, ds[0]["x"], [d["h0"] for d in ds],
+        lambda j, W, U, bi, bh, x, h0: orc.mgrit_forward(W, U, bi, bh, x, h0, z, tw.cf, tw.levels,
+                                                         fwd_iters, fine_relax_fcf=fcf)[0])
+    top = ds[-1]
+    _, g = orc.cross_entropy_head(hs[-1][-1], top["W_o"], top["b_o"], top["labels"])
+    src = np.zeros_like(z)
+    src[-1] = g
+
+    def bwd(j, W, U, bi, bh, x, h, s):
+        out = orc.mgrit_backward(W, U, bi, bh, x, h, None, z, tw.cf, tw.levels, bwd_iters,
+                                 fine_relax_fcf=fcf, dL_dh=s)
+        return (out[0],) + tuple(out[2:7])
+
+    orc.stacked_backward(params, ds[0]["x"], hs, src, bwd)
+    dt = time.perf_counter() - t0
+    return {"value": tw.T * tw.B / dt, "unit": "time-steps*batch/s", "cores": int(cores),
+            "kind": "oracle",
+            "sample": f"reduced-T twin of {wl.name}, {layers} layers: T={tw.T} (of {wl.T}), "
+                      f"B={tw.B}, D={tw.D}, H={tw.H}, cf={tw.cf}, levels={tw.levels}, {fwd_iters} fwd + "
+                      f"{bwd_iters} bwd cycles per layer, numpy float64, {dt:.1f} s"}
+
+
+def stack_main(args):
+    """--layers L: one training step of a stack of L GRU layers.  Forward: the layers
+    in order, each by MGRIT, layer j+1 reading the states of layer j.  Backward: the
+    loss head on the top layer's h_T, then the layers in reverse order, each layer's
+    input gradient being the source term of the layer below."""
+    import numpy as np
+    import torch
+
+    import paper_2203_04738_amd as mg
+    from paper_2203_04738_amd.binding import MGRIT_REUSE_PROJECTION, MgritGruCfg
+    from synthetic_inputs import WORKLOADS, layer_workload, make_inputs
+
+    wl = WORKLOADS[args.workload]
+    if wl.dtype != "fp32":
+        print("bench.py: --layers needs an fp32 workload (upper layers read fp32 states)",
+              file=sys.stderr)
+        sys.exit(2)
+    L = args.layers
+    fwd_iters = wl.fwd_iters if args.fwd_iters is None else args.fwd_iters
+    bwd_iters = max(1, wl.bwd_iters if args.bwd_iters is None else args.bwd_iters)
+    fine_relax = 1 if args.fine_relax == "FCF" else 0
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    T, B, H = wl.T, wl.B, wl.H
+    lay = []
+    for j in range(L):
+        wj = layer_workload(wl, j)
+        d = make_inputs(wj)
+        t = {k: torch.from_numpy(v).to(dev) for k, v in d.items() if k != "x" or j == 0}
+        cfgj = (lambda wj: lambda iters, flags=0: MgritGruCfg(
+            T, B, wj.D, H, cf=wl.cf, levels=wl.levels, iters=iters, fine_relax=fine_relax,
+            propagator=0, dtype=0, flags=flags))(wj)
+        lay.append({
+            "t": t, "cfg": cfgj, "D": wj.D,
+            "ws": torch.empty(mg.mgrit_gru_workspace_bytes(cfgj(max(fwd_iters, bwd_iters))),
+                              dtype=torch.uint8, device=dev),
+            "h": torch.zeros(T + 1, B, H, device=dev), "w": torch.zeros(T + 1, B, H, device=dev),
+            "src": torch.zeros(T + 1, B, H, device=dev),
+            "g": (torch.empty(3 * H, wj.D, device=dev), torch.empty(3 * H, H, device=dev),
+                  torch.empty(3 * H, device=dev), torch.empty(3 * H, device=dev)),
+        })
+    top = lay[-1]["t"]
+    x0 = lay[0]["t"]["x"]
+
+    def inp(j):
+        return x0 if j == 0 else lay[j - 1]["h"][1:]
+
+    def P(j):
+        t = lay[j]["t"]
+        return t["W"], t["U"], t["b_i"], t["b_h"], inp(j)
+
+    def head():
+        logits = lay[-1]["h"][T] @ top["W_o"].T + top["b_o"]
+        p = torch.softmax(logits, dim=1)
+        p[torch.arange(B, device=dev), top["labels"]] -= 1.0
+        lay[-1]["src"][T] = (p / B) @ top["W_o"]
+
+    def dx_of(j):
+        # the input gradient of layer j lands in rows 1..T of the source term of layer j-1
+        return lay[j - 1]["src"][1:] if j > 0 else None
+
+    def mgrit_step():
+        for j in range(L):
+            lay[j]["h"].zero_()
+            mg.mgrit_gru_forward(lay[j]["cfg"](fwd_iters), *P(j), lay[j]["t"]["h0"], lay[j]["h"],
+                                 None, lay[j]["ws"])
+        head()
+        for j in range(L - 1, -1, -1):
+            lay[j]["w"].zero_()
+            mg.mgrit_gru_backward_steps(lay[j]["cfg"](bwd_iters, MGRIT_REUSE_PROJECTION), *P(j),
+                                        lay[j]["h"], lay[j]["src"], lay[j]["w"], None,
+                                        *lay[j]["g"], dx_of(j), lay[j]["ws"])
+
+    def serial_step():
+        for j in range(L):
+            mg.gru_serial_scan(lay[j]["cfg"](1), *P(j), lay[j]["t"]["h0"], lay[j]["h"],
+                               lay[j]["ws"])
+        head()
+        for j in range(L - 1, -1, -1):
+            mg.gru_serial_scan_backward_steps(lay[j]["cfg"](1, MGRIT_REUSE_PROJECTION), *P(j),
+                                              lay[j]["h"], lay[j]["src"], lay[j]["w"],
+                                              *lay[j]["g"], dx_of(j), lay[j]["ws"])
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    sec = timed(mgrit_step, args.steps, args.warmup)
+    mg.mgrit_gru_profile_enable(True)
+    for _ in range(args.steps):
+        mgrit_step()
+    torch.cuda.synchronize()
+    mg.mgrit_gru_profile_enable(False)
+    names = {0: "phi_step (fused forward level step, MFMA tiles)",
+             1: "adj_step (fused adjoint level step, MFMA tiles)",
+             2: "projection GEMM", 3: "weight-gradient GEMMs + bias sums",
+             4: "phi_skinny (few-row forward step, coarsest level)",
+             5: "adj_skinny (few-row adjoint step, coarsest level)",
+             6: "input-gradient GEMM"}
+    kernels = {}
+    for kind, nm in names.items():
+        n, ms, fl, by = mg.mgrit_gru_profile_read(kind)
+        if n:
+            kernels[nm] = {"launches_per_step": n / args.steps, "ms_per_step": ms / args.steps,
+                           "avg_launch_us": 1e3 * ms / n, "TFLOPs": fl / ms / 1e9,
+                           "algorithmic_GBps": by / ms / 1e6}
+    peak = MI355X_PEAK["fp32_TFLOPs"]
+    step_flops = sum(v["TFLOPs"] * v["ms_per_step"] * 1e9 for v in kernels.values())
+    dom = kernels.get(names[0])
+    roofline = None
+    if dom:
+        roofline = {"kernel": names[0], "bound": "mfma", "achieved": dom["TFLOPs"], "peak": peak,
+                    "unit": "TFLOP/s", "frac": dom["TFLOPs"] / peak, "traffic": None,
+                    "avg_launch_us": dom["avg_launch_us"],
+                    "launches_per_step": dom["launches_per_step"]}
+    serial = None
+    if not args.no_serial:
+        ssec = timed(serial_step, max(1, min(args.steps, 3)), 1)
+        serial = {"value": T * B / ssec, "unit": "time-steps*batch/s", "ms_per_step": 1e3 * ssec,
+                  "what": "gru_serial_scan + gru_serial_scan_backward_steps per layer on the same GPU",
+                  "mgrit_speedup": ssec / sec}
+    out = {
+        "metric": f"GRU time-steps x batch / sec, {L}-layer MGRIT fwd+bwd (1 GPU)",
+        "value": T * B / sec, "unit": "time-steps*batch/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": 1e3 * sec, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name} x {L} layers: T={T} B={B} D={wl.D} H={H} cf={wl.cf} "
+                               f"levels={wl.levels} fwd_iters={fwd_iters} bwd_iters={bwd_iters} per layer, "
+                               f"fine-level {args.fine_relax} relaxation, implicit GRU",
+                   "seed": wl.seed},
+        "roofline": roofline, "kernels": kernels,
+        "whole_step": {"TFLOPs": step_flops / sec / 1e12,
+                       "frac_of_mfma_peak": step_flops / sec / 1e12 / peak},
+        "serial_gpu": serial,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = stack_cpu_baseline(wl, L, fwd_iters, bwd_iters, fcf=bool(fine_relax))
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.layers > 1:
+        return stack_main(args)
     import numpy as np
     import torch
 

@@ -35,10 +35,15 @@ struct Identity4 {
 
 constexpr int LDS_PAD = 4;    // floats; keeps rows 16-byte aligned and spreads banks
 
-template <int WM_, int WN_, int BM_, int BN_, int NG_, int TK_ = 32, int NBUF_ = 1>
+// KS > 1: K-split inside the workgroup for launches with few rows.  KS groups of
+// WM*WN waves all compute the same output tile, group ks contracting the k-groups
+// [ks*NC/KS, (ks+1)*NC/KS) of every staged slice (TK is KS times longer, the loads
+// stay coalesced); the partial sums are added in the epilogue staging.
+template <int WM_, int WN_, int BM_, int BN_, int NG_, int TK_ = 32, int NBUF_ = 1, int KS_ = 1>
 struct TileCfg {
   static constexpr int WM = WM_, WN = WN_, BM = BM_, BN = BN_, NG = NG_, TK = TK_, NBUF = NBUF_;
-  static constexpr int NWAVES = WM * WN;
+  static constexpr int KS = KS_;
+  static constexpr int NWAVES = WM * WN * KS;
   static constexpr int NT = NWAVES * 64;
   static constexpr int TM = WM * BM * 32;
   static constexpr int TN = WN * BN * 32;       // per gate group
@@ -50,7 +55,7 @@ struct TileCfg {
   static constexpr int BUF_FLOATS = (TM + BROWS) * LD;
   static constexpr int LDS_FLOATS = NBUF * BUF_FLOATS;
   static_assert((TM * CPR) % NT == 0 && (BROWS * CPR) % NT == 0, "tile rows must divide evenly");
-  static_assert(TK % 8 == 0, "TK must be a multiple of 8");
+  static_assert(TK % (8 * KS) == 0, "TK must be a multiple of 8 per K-split group");
 };
 
 // Accumulators of one wave: acc[g][bm][bn] is a 32x32 block.
@@ -86,12 +91,13 @@ __device__ inline void gemm_nt_tile(Acc<C>& acc, int K, LoadA loadA, LoadB loadB
                                     FinB finB, float* lds) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = (tid >> 6) % (C::WM * C::WN);
+  const int ks = (tid >> 6) / (C::WM * C::WN);      // K-split group of this wave
   const int wm = wave / C::WN;
   const int wn = wave % C::WN;
   const int li = lane & 31;
   const int lh = lane >> 5;
-  constexpr int NC = C::TK / 8;          // k-groups of eight per slice
+  constexpr int NC = C::TK / 8 / C::KS;  // k-groups of eight per slice and K-split group
   constexpr int NB = C::NG * C::BN;      // B fragments per k-group
 
   decltype(loadA(0, 0)) ra[C::A_CHUNKS];
@@ -129,9 +135,9 @@ __device__ inline void gemm_nt_tile(Acc<C>& acc, int K, LoadA loadA, LoadB loadB
       *reinterpret_cast<floatx4*>(&Bs[(q / C::CPR) * C::LD + (q % C::CPR) * 4]) = v;
     }
   };
-  // fragment addresses of this lane inside a buffer (k-group 0)
-  const int a_off = ((wm * C::BM) * 32 + li) * C::LD + lh * 4;
-  const int b_off = C::TM * C::LD + ((wn * C::BN) * 32 + li) * C::LD + lh * 4;
+  // fragment addresses of this lane inside a buffer (first k-group of its K-split group)
+  const int a_off = ((wm * C::BM) * 32 + li) * C::LD + lh * 4 + ks * NC * 8;
+  const int b_off = C::TM * C::LD + ((wn * C::BN) * 32 + li) * C::LD + lh * 4 + ks * NC * 8;
   auto read_frags = [&](const float* buf, int c, floatx4 (&fa)[C::BM], floatx4 (&fb)[NB]) {
 #pragma unroll
     for (int a = 0; a < C::BM; ++a)
@@ -217,7 +223,7 @@ __device__ inline bool xcd_tile(long long bid, long long nrow, int ncol, long lo
 template <class C>
 __device__ inline void acc_coord(int a, int b, int e, int& row, int& col) {
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
+  const int wave = (threadIdx.x >> 6) % (C::WM * C::WN);
   const int wm = wave / C::WN, wn = wave % C::WN;
   row = (wm * C::BM + a) * 32 + 8 * (e / 4) + 4 * (lane >> 5) + (e & 3);
   col = (wn * C::BN + b) * 32 + (lane & 31);
@@ -234,14 +240,19 @@ struct EpiStage {
   static constexpr int ROWS = C::WM * 32;              // tile rows staged per pass
   static constexpr int LD = C::TN + 8;                 // 4*LD = 32 (mod 64): conflict-free writes
   static constexpr int C4 = C::TN / 4;                 // float4 columns of a tile row
+  static constexpr int NITEM = ROWS * C4;              // items of a pass
+  static constexpr int ITEMS = (NITEM + C::NT - 1) / C::NT;   // items per thread and pass
   static constexpr int RSTEP = C::NT / C4;             // staged rows between items of a thread
-  static constexpr int ITEMS = ROWS / RSTEP;           // items per thread and pass
-  static constexpr int FLOATS = C::NG * ROWS * LD;
-  static_assert(C::NT % C4 == 0 && ROWS % RSTEP == 0, "epilogue items must divide evenly");
+  static constexpr int SLAB = C::NG * ROWS * LD;       // floats of one K-split group
+  static constexpr int FLOATS = C::KS * SLAB;
+  static_assert(C::NT % C4 == 0, "threads must cover whole staged rows");
+  static_assert(NITEM % C::NT == 0 || C::NT % NITEM == 0, "epilogue items must divide evenly");
 
-  // block row ba of every wave -> stage[g][row][col]
+  // block row ba of every wave -> stage[ks][g][row][col]
   __device__ static inline void write(const Acc<C>& acc, int ba, float* stage) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = (threadIdx.x >> 6) % (C::WM * C::WN);
+    const int ks = (threadIdx.x >> 6) / (C::WM * C::WN);
     const int wm = wave / C::WN, wn = wave % C::WN;
     const int li = lane & 31, lh = lane >> 5;
 #pragma unroll
@@ -252,17 +263,27 @@ struct EpiStage {
         for (int e = 0; e < 16; ++e) {
           const int row = wm * 32 + 8 * (e / 4) + 4 * lh + (e & 3);
           const int col = (wn * C::BN + bb) * 32 + li;
-          stage[(g * ROWS + row) * LD + col] = acc.v[g][ba][bb][e];
+          stage[ks * SLAB + (g * ROWS + row) * LD + col] = acc.v[g][ba][bb][e];
         }
   }
+  // threads beyond the items of a pass (workgroups wider than the staged block) idle
+  __device__ static inline bool active() { return C::NT <= NITEM || (int)threadIdx.x < NITEM; }
   __device__ static inline int col4() { return threadIdx.x % C4; }
-  __device__ static inline int staged_row(int it) { return threadIdx.x / C4 + it * RSTEP; }
+  __device__ static inline int staged_row(int it) {
+    const int rp = threadIdx.x / C4 + it * RSTEP;
+    return rp < ROWS ? rp : ROWS - 1;
+  }
   // row of the workgroup tile behind staged row rp of pass ba
   __device__ static inline int tile_row(int rp, int ba) {
     return ((rp / 32) * C::BM + ba) * 32 + (rp & 31);
   }
+  // sum over the K-split groups of gate g at (rp, c4)
   __device__ static inline floatx4 read(const float* stage, int g, int rp, int c4) {
-    return *reinterpret_cast<const floatx4*>(&stage[(g * ROWS + rp) * LD + c4 * 4]);
+    floatx4 v = *reinterpret_cast<const floatx4*>(&stage[(g * ROWS + rp) * LD + c4 * 4]);
+#pragma unroll
+    for (int k = 1; k < C::KS; ++k)
+      v += *reinterpret_cast<const floatx4*>(&stage[k * SLAB + (g * ROWS + rp) * LD + c4 * 4]);
+    return v;
   }
 };
 

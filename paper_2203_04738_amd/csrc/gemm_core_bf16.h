@@ -40,13 +40,14 @@ __device__ inline void split_bf16(const F32x8& v, bf16x8& hi, bf16x8& lo) {
   }
 }
 
-template <int WM_, int WN_, int BM_, int BN_, int NG_, bool SPLIT_A_>
+template <int WM_, int WN_, int BM_, int BN_, int NG_, bool SPLIT_A_, int KS_ = 1>
 struct TileCfgB {
   static constexpr int WM = WM_, WN = WN_, BM = BM_, BN = BN_, NG = NG_;
   static constexpr bool SPLIT_A = SPLIT_A_;
-  static constexpr int TK = 64;                 // bf16 elements per K-slice
+  static constexpr int KS = KS_;                // K-split groups of waves (see TileCfg)
+  static constexpr int TK = 64 * KS;            // bf16 elements per K-slice
   static constexpr int NA = SPLIT_A ? 2 : 1;    // A tiles in LDS
-  static constexpr int NWAVES = WM * WN;
+  static constexpr int NWAVES = WM * WN * KS;
   static constexpr int NT = NWAVES * 64;
   static constexpr int TM = WM * BM * 32;
   static constexpr int TN = WN * BN * 32;
@@ -72,12 +73,13 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
                                          bf16_t* lds) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = (tid >> 6) % (C::WM * C::WN);
+  const int ks = (tid >> 6) / (C::WM * C::WN);      // K-split group of this wave
   const int wm = wave / C::WN;
   const int wn = wave % C::WN;
   const int li = lane & 31;
   const int lh = lane >> 5;
-  constexpr int NC = C::TK / 16;
+  constexpr int NC = C::TK / 16 / C::KS;            // k-groups of sixteen per slice and group
   constexpr int NB = C::NG * C::BN;
   constexpr int NFA = C::NA * C::BM;
 
@@ -125,8 +127,8 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
       *reinterpret_cast<bf16x8*>(&Bs[(q / C::CPR) * C::LD + (q % C::CPR) * 8]) = dead ? z : rb[s];
     }
   };
-  const int a_off = ((wm * C::BM) * 32 + li) * C::LD + lh * 8;
-  const int b_off = ((wn * C::BN) * 32 + li) * C::LD + lh * 8;
+  const int a_off = ((wm * C::BM) * 32 + li) * C::LD + lh * 8 + ks * NC * 16;
+  const int b_off = ((wn * C::BN) * 32 + li) * C::LD + lh * 8 + ks * NC * 16;
   auto read_frags = [&](int c, bf16x8 (&fa)[NFA], bf16x8 (&fb)[NB]) {
 #pragma unroll
     for (int t = 0; t < C::NA; ++t)

@@ -76,7 +76,7 @@ __device__ inline void adj_tile_epilogue(const AdjArgs& a, Acc<C>& acc, const Ad
   const int H = a.H;
   const int c4 = E::col4();
   const int j = n0 + c4 * 4;
-  const bool colok = j < H;
+  const bool colok = E::active() && j < H;
   const int jc = colok ? j : H - 4;                     // clamped columns are never stored
 #pragma unroll
   for (int ba = 0; ba < C::BM; ++ba) {
@@ -465,10 +465,10 @@ __global__ __launch_bounds__(AdjSkMaxNT<CT>::value) void adj_skinny_kernel(AdjAr
 
 typedef TileCfg<2, 2, 2, 2, 1> AdjBig;    // 128 x 128, 256 threads
 typedef TileCfg<2, 2, 1, 1, 1> AdjMid;    //  64 x 64, 256 threads
-typedef TileCfg<1, 1, 1, 1, 1> AdjSmall;  //  32 x 32, 64 threads
+typedef TileCfg<1, 1, 1, 1, 1, 128, 1, 4> AdjSmall;  //  32 x 32, 4 waves splitting K
 typedef TileCfgB<2, 2, 2, 2, 1, true> AdjBigB;
 typedef TileCfgB<2, 2, 1, 1, 1, true> AdjMidB;
-typedef TileCfgB<1, 1, 1, 1, 1, true> AdjSmallB;
+typedef TileCfgB<1, 1, 1, 1, 1, true, 4> AdjSmallB;
 
 template <class C, class CB>
 static void launch_adj_cfg(const AdjArgs& a, hipStream_t s) {
@@ -542,7 +542,7 @@ hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s) {
       launch_adj_skinny<2>(a, grid, s);
     else
       launch_adj_skinny<1>(a, grid, s);
-  } else if (tiles(AdjBig::TM, AdjBig::TN) >= 512)
+  } else if (tiles(AdjBig::TM, AdjBig::TN) >= 384)
     launch_adj_cfg<AdjBig, AdjBigB>(a, s);
   else if (R > 32 && tiles(AdjMid::TM, AdjMid::TN) >= 256)
     launch_adj_cfg<AdjMid, AdjMidB>(a, s);

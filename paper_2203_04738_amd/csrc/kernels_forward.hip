@@ -292,7 +292,7 @@ __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Ph
   const int H = a.H;
   const int c4 = E::col4();
   const int j = n0 + c4 * 4;
-  const bool colok = j < H;
+  const bool colok = E::active() && j < H;
   const int jc = colok ? j : H - 4;                     // clamped columns are never stored
   PhiBias bh[4];
 #pragma unroll
@@ -571,10 +571,11 @@ __global__ __launch_bounds__(PhiSkMaxNT<CT>::value) void phi_skinny_kernel(PhiAr
 
 typedef TileCfg<2, 2, 2, 1, 3> PhiBig;    // 128 rows x 64 hidden columns (x3 gates), 256 threads
 typedef TileCfg<2, 2, 1, 1, 3> PhiMid;    //  64 rows x 64 hidden columns, 256 threads
-typedef TileCfg<1, 1, 1, 1, 3> PhiSmall;  //  32 rows x 32 hidden columns, 64 threads
+// few rows:  32 rows x 32 hidden columns, 4 waves splitting K (slices of 128)
+typedef TileCfg<1, 1, 1, 1, 3, 128, 1, 4> PhiSmall;
 typedef TileCfgB<2, 2, 2, 1, 3, true> PhiBigB;
 typedef TileCfgB<2, 2, 1, 1, 3, true> PhiMidB;
-typedef TileCfgB<1, 1, 1, 1, 3, true> PhiSmallB;
+typedef TileCfgB<1, 1, 1, 1, 3, true, 4> PhiSmallB;
 
 #define MG_LAUNCH_BY_MODE(KERNEL, ...)                                                   \
   switch (a.mode) {                                                                      \
@@ -647,7 +648,7 @@ hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s) {
       launch_phi_skinny<2>(a, grid, s);
     else
       launch_phi_skinny<1>(a, grid, s);
-  } else if (tiles(PhiBig::TM, PhiBig::TN) >= 512)
+  } else if (tiles(PhiBig::TM, PhiBig::TN) >= 384)
     launch_phi_cfg<PhiBig, PhiBigB>(a, s);
   else if (R > 32 && tiles(PhiMid::TM, PhiMid::TN) >= 256)
     launch_phi_cfg<PhiMid, PhiMidB>(a, s);

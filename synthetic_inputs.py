@@ -56,7 +56,21 @@ WORKLOADS: Dict[str, Workload] = {
     "C4": Workload("C4", T=4096, B=8, D=2048, H=1024, cf=8, levels=3, fwd_iters=2, bwd_iters=1,
                    dtype="bf16", x_dist="relu_normal"),
     "C5": Workload("C5", T=16384, B=4, D=1024, H=1024, cf=4, levels=4, fwd_iters=2, bwd_iters=2),
+    # Shape of the paper's HMDB51 experiment (Sec. 4: 128 time steps, batch 100, 1000
+    # features, hidden size 1000, cf = 4, 3 levels, 2 forward / 1 backward iterations);
+    # used with two stacked layers.  Not one of the benchmark's configurations.
+    "P1": Workload("P1", T=128, B=100, D=1000, H=1000, cf=4, levels=3, fwd_iters=2, bwd_iters=1,
+                   x_dist="relu_normal"),
 }
+
+
+def layer_workload(wl: Workload, layer: int) -> Workload:
+    """Workload whose draw gives the parameters of layer `layer` (0-based) of a stack
+    built on `wl`: layers above the first read H features (the states of the layer
+    below) and use their own seed; the x of their draw is not used."""
+    if layer == 0:
+        return wl
+    return replace(wl, name=f"{wl.name}-layer{layer + 1}", D=wl.H, seed=wl.seed + 1000 * layer)
 
 
 def round_to_bf16(a: np.ndarray) -> np.ndarray:

@@ -43,6 +43,10 @@ def parse():
     ap.add_argument("--layers", type=int, default=1,
                     help="2: a stack of two GRU layers (layer 2 reads the states of layer 1; "
                          "fp32 workloads only), each solved by its own MGRIT solve")
+    ap.add_argument("--study", choices=["convergence"], default=None,
+                    help="convergence: residual per cycle, forward and backward, for the paper's "
+                         "hierarchies at T = 128 (cf 2 / 4 / 8 with 6 / 3 / 2 levels) and for the "
+                         "Classic coarse propagator; prints one JSON line, times nothing")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-serial", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -276,12 +280,60 @@ def stack_main(args):
     print(json.dumps(out))
 
 
+def study_convergence(args):
+    """Residual history of MGRIT on the paper-shaped workload P1 (one layer): the study
+    behind the paper's choice of cf = 4 and of 2 forward / 1 backward iterations
+    (Sec. 4.2, residual figure), on synthetic stand-in data, and the Implicit against the
+    Classic coarse propagator (Sec. 3.3)."""
+    import torch
+
+    import paper_2203_04738_amd as mg
+    from paper_2203_04738_amd.binding import MgritGruCfg
+    from synthetic_inputs import WORKLOADS, make_inputs
+
+    wl = WORKLOADS["P1"]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    d = make_inputs(wl)
+    t = {k: torch.from_numpy(v).to(dev) for k, v in d.items()}
+    T, B, D, H = wl.T, wl.B, wl.D, wl.H
+    P = (t["W"], t["U"], t["b_i"], t["b_h"], t["x"])
+    cycles = 8
+    rows = []
+    for cf, levels, prop in ((2, 6, 0), (4, 3, 0), (8, 2, 0), (2, 6, 1), (4, 3, 1), (8, 2, 1)):
+        cfg = MgritGruCfg(T, B, D, H, cf=cf, levels=levels, iters=cycles, fine_relax=1,
+                          propagator=prop, dtype=0)
+        ws = torch.empty(mg.mgrit_gru_workspace_bytes(cfg), dtype=torch.uint8, device=dev)
+        hs = torch.zeros(T + 1, B, H, device=dev)
+        mg.gru_serial_scan(cfg, *P, t["h0"], hs, ws)
+        h = torch.zeros(T + 1, B, H, device=dev)
+        rf = torch.zeros(cycles, device=dev)
+        mg.mgrit_gru_forward(cfg, *P, t["h0"], h, rf, ws)
+        err = float(torch.max(torch.abs(h - hs)) / torch.max(torch.abs(hs)))
+        # adjoint around the serial states, terminal loss gradient from the seeded draw
+        w = torch.zeros(T + 1, B, H, device=dev)
+        rb = torch.zeros(cycles, device=dev)
+        mg.mgrit_gru_backward(cfg, *P, hs, t["dL_dhT"], w, rb, None, None, None, None, ws)
+        torch.cuda.synchronize()
+        rows.append({"cf": cf, "levels": levels,
+                     "propagator": "implicit" if prop == 0 else "classic",
+                     "forward_residuals": rf.cpu().tolist(), "backward_residuals": rb.cpu().tolist(),
+                     "forward_max_rel_error_after_%d_cycles" % cycles: err})
+        del ws
+    print(json.dumps({"study": "convergence",
+                      "workload": f"P1: T={T} B={B} D={D} H={H}, one layer, FCF relaxation, fp32, "
+                                  f"synthetic stand-in for the HMDB51 features",
+                      "cycles": cycles, "rows": rows}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.study == "convergence":
+        return study_convergence(args)
     if args.layers > 1:
         return stack_main(args)
     import numpy as np

@@ -169,6 +169,15 @@ def test_mgrit_backward_reduced_twins(gh, name):
     _check_backward(gh, d, wl.cf, wl.levels, 2)
 
 
+@pytest.mark.parametrize("cf,levels", [(2, 6), (4, 3), (8, 2)])
+def test_the_papers_hierarchies_at_128_steps(gh, cf, levels):
+    """Sec. 4.2: 128 time steps with cf = 2, 4, 8 give 6, 3, 2 levels (coarsest level
+    of 4, 8, 16 steps); the deepest hierarchy the experiments use."""
+    d = random_small(60 + cf, 128, 3, 12, 36, scale=0.3)
+    gits, _ = _check_forward(gh, d, cf, levels, 3)
+    _check_backward(gh, d, cf, levels, 2, h=gits[-1].astype(np.float64))
+
+
 # ------------------------------------------------------------------ API behaviour on the device
 
 def test_invalid_call_leaves_buffers_untouched(gh):

@@ -43,10 +43,13 @@ def parse():
     ap.add_argument("--layers", type=int, default=1,
                     help="2: a stack of two GRU layers (layer 2 reads the states of layer 1; "
                          "fp32 workloads only), each solved by its own MGRIT solve")
-    ap.add_argument("--study", choices=["convergence"], default=None,
+    ap.add_argument("--study", choices=["convergence", "training"], default=None,
                     help="convergence: residual per cycle, forward and backward, for the paper's "
                          "hierarchies at T = 128 (cf 2 / 4 / 8 with 6 / 3 / 2 levels) and for the "
-                         "Classic coarse propagator; prints one JSON line, times nothing")
+                         "Classic coarse propagator.  training: the training loop of Alg. 3 with Adam "
+                         "on a synthetic classification task, MGRIT (2 forward / 1 backward cycles) "
+                         "against serial propagation from the same start.  One JSON line each")
+    ap.add_argument("--train-steps", type=int, default=300)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-serial", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -326,6 +329,145 @@ def study_convergence(args):
                       "cycles": cycles, "rows": rows}))
 
 
+def study_training(args):
+    """Alg. 3 as a training loop: a two-layer Implicit GRU with a linear head, trained
+    with Adam (lr 1e-3, Sec. 3.4) on a synthetic sequence-classification task of the
+    UCI-HAR shape (128 steps, 9 features padded to 12, hidden 100, 6 classes, batch 100;
+    cf = 4, 3 levels, 2 forward / 1 backward cycles).  The label of a sequence is a fixed
+    function of the sequence (argmax of an exponentially weighted linear read-out), so no
+    dataset is needed.  Two runs from the same initial weights on the same batches: one
+    with serial propagation (exact states and gradients), one with MGRIT; then the
+    MGRIT-trained model is evaluated with serial and with MGRIT inference (Remark 3)."""
+    import numpy as np
+    import torch
+
+    import paper_2203_04738_amd as mg
+    from paper_2203_04738_amd.binding import MGRIT_REUSE_PROJECTION, MgritGruCfg
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    T, B, D, H, C, L = 128, 100, 12, 100, 6, 2
+    cf, levels = 4, 3
+    fwd_iters = 2 if args.fwd_iters is None else args.fwd_iters
+    bwd_iters = 1 if args.bwd_iters is None else max(1, args.bwd_iters)
+    rng = np.random.default_rng(0)
+    readout = rng.standard_normal((C, 9)).astype(np.float32)
+    decay = (0.97 ** np.arange(T - 1, -1, -1)).astype(np.float32)        # weight of step t
+
+    def batch(seed):
+        r = np.random.default_rng(1000 + seed)
+        x = np.zeros((T, B, D), dtype=np.float32)
+        x[:, :, :9] = r.standard_normal((T, B, 9))
+        score = np.einsum("t,tbd,cd->bc", decay, x[:, :, :9], readout)
+        return torch.from_numpy(x).to(dev), torch.from_numpy(np.argmax(score, axis=1)).to(dev)
+
+    def init_params():
+        r = np.random.default_rng(7)
+        ps = []
+        for j in range(L):
+            Dj = D if j == 0 else H
+            bw, bu = np.sqrt(6.0 / (Dj + H)), np.sqrt(6.0 / (2 * H))
+            ps.append([torch.from_numpy(r.uniform(-bw, bw, (3 * H, Dj)).astype(np.float32)).to(dev),
+                       torch.from_numpy(r.uniform(-bu, bu, (3 * H, H)).astype(np.float32)).to(dev),
+                       torch.zeros(3 * H, device=dev), torch.zeros(3 * H, device=dev)])
+        bo = np.sqrt(6.0 / (H + C))
+        head = [torch.from_numpy(r.uniform(-bo, bo, (C, H)).astype(np.float32)).to(dev),
+                torch.zeros(C, device=dev)]
+        return ps, head
+
+    def cfg(Dj, iters, flags=0):
+        return MgritGruCfg(T, B, Dj, H, cf=cf, levels=levels, iters=iters, fine_relax=1,
+                           propagator=0, dtype=0, flags=flags)
+
+    dims = [D] + [H] * (L - 1)
+    wss = [torch.empty(mg.mgrit_gru_workspace_bytes(cfg(Dj, max(fwd_iters, bwd_iters))),
+                       dtype=torch.uint8, device=dev) for Dj in dims]
+    hs = [torch.zeros(T + 1, B, H, device=dev) for _ in range(L)]
+    ws_ = [torch.zeros(T + 1, B, H, device=dev) for _ in range(L)]
+    srcs = [torch.zeros(T + 1, B, H, device=dev) for _ in range(L)]
+    h0 = torch.zeros(B, H, device=dev)
+
+    def forward(ps, x, parallel):
+        for j in range(L):
+            xin = x if j == 0 else hs[j - 1][1:]
+            if parallel:
+                hs[j].zero_()
+                mg.mgrit_gru_forward(cfg(dims[j], fwd_iters), *ps[j], xin, h0, hs[j], None, wss[j])
+            else:
+                mg.gru_serial_scan(cfg(dims[j], 1), *ps[j], xin, h0, hs[j], wss[j])
+        return hs[-1][T]
+
+    def backward(ps, x, g_top, grads, parallel):
+        srcs[-1].zero_()
+        srcs[-1][T] = g_top
+        for j in range(L - 1, -1, -1):
+            xin = x if j == 0 else hs[j - 1][1:]
+            dx = srcs[j - 1][1:] if j > 0 else None
+            if j > 0:
+                srcs[j - 1][0].zero_()
+            if parallel:
+                ws_[j].zero_()
+                mg.mgrit_gru_backward_steps(cfg(dims[j], bwd_iters, MGRIT_REUSE_PROJECTION), *ps[j],
+                                            xin, hs[j], srcs[j], ws_[j], None, *grads[j], dx, wss[j])
+            else:
+                mg.gru_serial_scan_backward_steps(cfg(dims[j], 1, MGRIT_REUSE_PROJECTION), *ps[j],
+                                                  xin, hs[j], srcs[j], ws_[j], *grads[j], dx, wss[j])
+
+    def accuracy(ps, head, parallel, seeds):
+        hit = 0
+        for sd in seeds:
+            x, y = batch(sd)
+            hT = forward(ps, x, parallel)
+            hit += int((torch.argmax(hT @ head[0].T + head[1], dim=1) == y).sum())
+        return hit / (len(seeds) * B)
+
+    def train(parallel):
+        ps, head = init_params()
+        flat = [p for lp in ps for p in lp] + head
+        grads = [[torch.zeros_like(p) for p in lp] for lp in ps]
+        opt = torch.optim.Adam(flat, lr=1e-3)
+        losses = []
+        for step in range(args.train_steps):
+            x, y = batch(step)
+            hT = forward(ps, x, parallel).clone().requires_grad_(True)
+            Wo, bo = head[0].requires_grad_(True), head[1].requires_grad_(True)
+            loss = torch.nn.functional.cross_entropy(hT @ Wo.T + bo, y)
+            gh, gW, gb = torch.autograd.grad(loss, (hT, Wo, bo))
+            head[0].requires_grad_(False)
+            head[1].requires_grad_(False)
+            backward(ps, x, gh, grads, parallel)
+            for lp, lg in zip(ps, grads):
+                for p_, g_ in zip(lp, lg):
+                    p_.grad = g_
+            head[0].grad, head[1].grad = gW, gb
+            opt.step()
+            losses.append(float(loss.detach()))
+        return ps, head, losses
+
+    test_seeds = list(range(100000, 100010))
+    out = {"study": "training",
+           "task": f"synthetic sequence classification, T={T} B={B} features 9 (padded to {D}) H={H} "
+                   f"classes={C} layers={L}; cf={cf} levels={levels} {fwd_iters} fwd / {bwd_iters} bwd "
+                   f"cycles; Adam lr 1e-3, {args.train_steps} steps, fresh seeded batch every step",
+           "runs": {}}
+    for name, parallel in (("serial", False), ("mgrit", True)):
+        t0 = time.perf_counter()
+        ps, head, losses = train(parallel)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        k = max(1, args.train_steps // 10)
+        run = {"loss_first_%d" % k: float(np.mean(losses[:k])),
+               "loss_last_%d" % k: float(np.mean(losses[-k:])),
+               "loss_every_%d" % k: [float(np.mean(losses[i:i + k]))
+                                     for i in range(0, args.train_steps, k)],
+               "test_accuracy_serial_inference": accuracy(ps, head, False, test_seeds),
+               "seconds": dt}
+        if parallel:
+            run["test_accuracy_mgrit_inference"] = accuracy(ps, head, True, test_seeds)
+        out["runs"][name] = run
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -334,6 +476,8 @@ def main():
         sys.exit(2)
     if args.study == "convergence":
         return study_convergence(args)
+    if args.study == "training":
+        return study_training(args)
     if args.layers > 1:
         return stack_main(args)
     import numpy as np

@@ -25,6 +25,11 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 __device__ inline floatx4 ldg4(const float* p) { return *reinterpret_cast<const floatx4*>(p); }
+// streamed operand (read once per launch): loaded with the non-temporal hint so that
+// it does not displace the weights and state rows the tiles share in L2
+__device__ inline floatx4 ldg4_stream(const float* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(p));
+}
 __device__ inline floatx4 zero4() {
   floatx4 z = {0.f, 0.f, 0.f, 0.f};
   return z;

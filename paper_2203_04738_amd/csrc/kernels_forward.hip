@@ -315,9 +315,9 @@ __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Ph
       oo[it] = ro.o;
       oa[it] = ro.a;
       const float* pp = a.P + ro.p + jc;
-      in[it].pr = ldg4(pp);
-      in[it].pz = ldg4(pp + H);
-      in[it].pn = ldg4(pp + 2 * H);
+      in[it].pr = ldg4_stream(pp);
+      in[it].pz = ldg4_stream(pp + H);
+      in[it].pn = ldg4_stream(pp + 2 * H);
       in[it].h = ldg4(a.u_in + ro.in + jc);
       if (MODE != STEP_KAPPA && a.g) in[it].gval = ldg4(a.g + ro.o + jc);
       else in[it].gval = zero4();

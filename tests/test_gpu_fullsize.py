@@ -71,3 +71,50 @@ def test_full_size_backward_window(gh, name, window):
     assert gh.rel_err(got, out[0]) <= tol
     for g in grads:
         assert np.all(np.isfinite(g))
+
+
+@pytest.mark.parametrize("name", ["C3", "C4", "C5"])
+def test_full_size_gradients_and_input_gradients_on_a_sparse_adjoint(gh, name):
+    """Gradient GEMMs, bias sums and the input-gradient GEMM at full size, element by
+    element.  With zero cycles the entry point forms the gradients from the adjoint it is
+    given; that adjoint (seeded) is non-zero on 96 time steps spread over the whole
+    sequence, first and last step included, and zero elsewhere, so the sums of Alg. 3's
+    gradient line reduce to those steps and the oracle evaluates them on the gathered
+    steps (a step's contribution depends on x_t, h_{t-1}, w_t only)."""
+    import paper_2203_04738_amd as mg
+    wl = WORKLOADS[name]
+    d = make_inputs(wl)
+    tol = 1e-5 if wl.dtype == "fp32" else 2e-2
+    T, B, D, H = wl.T, wl.B, wl.D, wl.H
+    rng = np.random.default_rng(123)
+    steps = np.unique(np.concatenate([[1, T], rng.integers(1, T + 1, size=94)]))
+    h = np.tanh(rng.standard_normal((T + 1, B, H))).astype(np.float32)
+    w = np.zeros((T + 1, B, H), dtype=np.float32)
+    w[steps] = rng.standard_normal((len(steps), B, H)).astype(np.float32)
+
+    run = gh.GpuRun(d, cf=wl.cf, levels=wl.levels, dtype=wl.dtype)
+    dev = gh.DEV
+    hd, wd = run._dev(h), run._dev(w)
+    src = torch.zeros(T + 1, B, H, device=dev)
+    src[T] = wd[T]                                   # row T of the adjoint is set from the loss term
+    g = run._grads()
+    dx = torch.full((T, B, D), float("nan"), device=dev)
+    mg.mgrit_gru_backward_steps(run.cfg(0), *run._p(), hd, src, wd, None, *g, dx, run.ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(wd.cpu().numpy(), w)       # zero cycles leave the adjoint as given
+
+    # gathered sub-problem: pseudo-step i uses x_{t_i}, h_{t_i - 1}, w_{t_i}
+    n = len(steps)
+    xs = d["x"][steps - 1]
+    hs = np.concatenate([h[steps - 1], np.zeros((1, B, H), dtype=np.float32)])
+    ws_ = np.concatenate([np.zeros((1, B, H), dtype=np.float32), w[steps]])
+    ref = orc.parameter_gradients(*_P(d), xs, hs, ws_)
+    for nm, got, r in zip(("dW", "dU", "db_i", "db_h"), g, ref):
+        assert gh.rel_err(got.cpu().numpy(), r) <= tol, nm
+    rdx = orc.input_gradients(*_P(d), xs, hs, ws_)
+    gdx = dx.cpu().numpy()
+    assert gh.rel_err(gdx[steps - 1], rdx) <= tol
+    mask = np.ones(T, dtype=bool)
+    mask[steps - 1] = False
+    assert not np.any(gdx[mask])                     # steps with a zero adjoint contribute nothing
+    assert n >= 90

@@ -736,6 +736,206 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
       }
 }
 
+// The same contraction for the bf16-input variant on the bf16 MFMA
+// (v_mfma_f32_32x32x16_bf16).  The instruction wants eight consecutive k per lane,
+// the operands have k as the slow index, so the transposition happens in registers on
+// the way to LDS: a thread loads an 8 (k) x 4 (m) block of kappa and w, forms the
+// products and writes, for each of its four m, the eight k as one 16-byte row segment
+// of a [m][k] tile - after which fragments are read exactly as in the NT kernels.
+// fp32 operands (S = kappa*w, and h for dU) go to LDS as hi + lo bf16 tiles:
+//   dW: S_hi x + S_lo x (x is bf16 already);  dU: S_hi h_hi + S_lo h_hi + S_hi h_lo.
+// Bias gradients: column sums of the fp32 products, accumulated by the staging threads.
+constexpr int HB_TK = 64;                 // k rows per slice
+constexpr int HB_LD = HB_TK + 8;          // LDS row stride in bf16 elements
+template <bool B_BF16>
+__global__ __launch_bounds__(256, 2) void grad_gemm_bf16_kernel(GradArgs a) {
+  constexpr int NBT = B_BF16 ? 1 : 2;     // B tiles in LDS (hi, lo)
+  __shared__ __attribute__((aligned(16))) bf16_t As[2][GT * HB_LD];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[NBT][GT * HB_LD];
+  const int H = a.H, N = a.N, M = 3 * a.H;
+  const int tiles = a.mtiles * a.ntiles;
+  int tile, z;
+  if (a.splits % NXCD == 0) {
+    const int j = blockIdx.x / NXCD;
+    tile = j % tiles;
+    z = (j / tiles) * NXCD + blockIdx.x % NXCD;
+  } else {
+    tile = blockIdx.x % tiles;
+    z = blockIdx.x / tiles;
+  }
+  const int nt = tile / a.mtiles;
+  const int m0 = (tile % a.mtiles) * GT, n0 = nt * GT;
+  const long long kbeg = (long long)z * a.Kper;
+  long long kend = kbeg + a.Kper;
+  if (kend > a.Ktot) kend = a.Ktot;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1, li = lane & 31, lh = lane >> 5;
+  const long long rowoff = a.B;           // kap0 / w rows are one time point ahead
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // staging block of this thread: A: columns m4*4..+3, rows k8*8..+7 of the slice
+  const int m4 = tid & 31, k8 = tid >> 5;
+  const int m = m0 + m4 * 4;
+  const bool m_ok = m < M;
+  const int mc = m_ok ? m : 0;
+  const int gate = mc / H, jcol = mc - gate * H;
+  const int src = gate == 2 ? a.third_off + jcol : mc;
+  // B (bf16): columns n8*8..+7, rows kb*8..+7, threads 0..127;  B (fp32): as A
+  const int n8 = tid & 15, kb = B_BF16 ? (tid >> 4) : k8;
+  const bool b_thread = !B_BF16 || tid < 128;
+  const int n = n0 + (B_BF16 ? n8 * 8 : m4 * 4);
+  const bool n_ok = n < N;
+  const int nc = n_ok ? n : 0;
+
+  floatx4 rk[8], rw[8];
+  floatx4 rbf[B_BF16 ? 1 : 8];
+  bf16x8 rbh[B_BF16 ? 8 : 1];
+  float colsum[4] = {0.f, 0.f, 0.f, 0.f};
+  auto fetch = [&](long long k0) {
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      long long k = k0 + k8 * 8 + r;
+      if (k >= kend) k = kend - 1;
+      rk[r] = ldg4(a.kap0 + (k + rowoff) * (5LL * H) + src);
+      rw[r] = ldg4(a.w + (k + rowoff) * H + jcol);
+    }
+    if (b_thread) {
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        long long k = k0 + kb * 8 + r;
+        if (k >= kend) k = kend - 1;
+        if constexpr (B_BF16)
+          rbh[r] = ldg8h((const bf16_t*)a.Bm + k * N + nc);
+        else
+          rbf[r] = ldg4((const float*)a.Bm + k * N + nc);
+      }
+    }
+  };
+  auto stash = [&](long long k0) {
+    floatx4 p[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const bool k_ok = k0 + k8 * 8 + r < kend;
+      p[r] = (k_ok && m_ok) ? rk[r] * rw[r] : zero4();
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      F32x8 v;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        v.lo4[r] = p[r][e];
+        v.hi4[r] = p[4 + r][e];
+        colsum[e] += p[r][e] + p[4 + r][e];
+      }
+      bf16x8 hi, lo;
+      split_bf16(v, hi, lo);
+      *reinterpret_cast<bf16x8*>(&As[0][(m4 * 4 + e) * HB_LD + k8 * 8]) = hi;
+      *reinterpret_cast<bf16x8*>(&As[1][(m4 * 4 + e) * HB_LD + k8 * 8]) = lo;
+    }
+    if (b_thread) {
+      if constexpr (B_BF16) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          bf16x8 o;
+#pragma unroll
+          for (int r = 0; r < 8; ++r) {
+            const bool k_ok = k0 + kb * 8 + r < kend;
+            o[r] = (k_ok && n_ok) ? rbh[r][e] : (__bf16)0.f;
+          }
+          *reinterpret_cast<bf16x8*>(&Bs[0][(n8 * 8 + e) * HB_LD + kb * 8]) = o;
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          F32x8 v;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            v.lo4[r] = (k0 + kb * 8 + r < kend && n_ok) ? rbf[r][e] : 0.f;
+            v.hi4[r] = (k0 + kb * 8 + 4 + r < kend && n_ok) ? rbf[4 + r][e] : 0.f;
+          }
+          bf16x8 hi, lo;
+          split_bf16(v, hi, lo);
+          *reinterpret_cast<bf16x8*>(&Bs[0][(m4 * 4 + e) * HB_LD + kb * 8]) = hi;
+          *reinterpret_cast<bf16x8*>(&Bs[NBT - 1][(m4 * 4 + e) * HB_LD + kb * 8]) = lo;
+        }
+      }
+    }
+  };
+
+  if (kbeg < kend) {
+    fetch(kbeg);
+    stash(kbeg);
+    __syncthreads();
+    for (long long k0 = kbeg; k0 < kend; k0 += HB_TK) {
+      const bool more = k0 + HB_TK < kend;
+      if (more) fetch(k0 + HB_TK);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int c = 0; c < HB_TK / 16; ++c) {
+        bf16x8 fa[2][2], fb[NBT][2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+            fa[t][i] = *reinterpret_cast<const bf16x8*>(
+                &As[t][(wm * 64 + i * 32 + li) * HB_LD + c * 16 + lh * 8]);
+#pragma unroll
+        for (int t = 0; t < NBT; ++t)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            fb[t][j] = *reinterpret_cast<const bf16x8*>(
+                &Bs[t][(wn * 64 + j * 32 + li) * HB_LD + c * 16 + lh * 8]);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][i], fb[0][j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[0][j], acc[i][j], 0, 0, 0);
+            if constexpr (!B_BF16)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][i], fb[NBT - 1][j], acc[i][j], 0, 0, 0);
+          }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      __syncthreads();
+      if (more) {
+        stash(k0 + HB_TK);
+        __syncthreads();
+      }
+    }
+  }
+  // column sums: the eight row groups of a column meet in LDS (the A tiles are free now)
+  float* red = reinterpret_cast<float*>(&As[0][0]);      // [8][GT] floats = 4 KB
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < 4; ++e) red[k8 * GT + m4 * 4 + e] = colsum[e];
+  __syncthreads();
+  if (tid < GT && m0 + tid < M) {
+    float sum = 0.f;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) sum += red[q * GT + tid];
+    // every column tile holds the same sums: the first one reports them
+    a.bpart[((long long)z * a.ntiles + nt) * M + m0 + tid] = nt == 0 ? sum : 0.f;
+  }
+  float* out = a.part + (long long)z * M * N;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int mm = m0 + wm * 64 + i * 32 + 8 * (e / 4) + 4 * lh + (e & 3);
+        const int nn = n0 + wn * 64 + j * 32 + li;
+        if (mm < M && nn < N) out[(long long)mm * N + nn] = acc[i][j][e];
+      }
+}
+
 __global__ void reduce_partials_kernel(const float* __restrict__ part, float* __restrict__ out,
                                        long long n, int splits) {
   long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -824,7 +1024,8 @@ hipError_t launch_param_grads(const float* kap0, const float* w, const float* h,
     a.H = H;
     const int splits = grad_splits(Ktot, M, a.N);
     long long per = (Ktot + splits - 1) / splits;
-    a.Kper = (per + GTK - 1) / GTK * GTK;
+    const int slice = bf16 ? HB_TK : GTK;
+    a.Kper = (per + slice - 1) / slice * slice;
     a.mtiles = (M + GT - 1) / GT;
     a.ntiles = (a.N + GT - 1) / GT;
     a.splits = splits;
@@ -832,8 +1033,10 @@ hipError_t launch_param_grads(const float* kap0, const float* w, const float* h,
     nbpart[which] = splits * a.ntiles;
     if (which == 0) bpart[1] = bpart[0] + (size_t)nbpart[0] * M;
     dim3 grid((unsigned)((long long)a.mtiles * a.ntiles * splits));
-    if (which == 1 && bf16)
-      hipLaunchKernelGGL(grad_gemm_kernel<bf16_t>, grid, dim3(256), 0, s, a);
+    if (bf16 && which == 1)
+      hipLaunchKernelGGL(grad_gemm_bf16_kernel<true>, grid, dim3(256), 0, s, a);
+    else if (bf16)
+      hipLaunchKernelGGL(grad_gemm_bf16_kernel<false>, grid, dim3(256), 0, s, a);
     else
       hipLaunchKernelGGL(grad_gemm_kernel<float>, grid, dim3(256), 0, s, a);
     const long long n = (long long)M * a.N;

@@ -146,7 +146,8 @@ def stack_main(args):
     import torch
 
     import paper_2203_04738_amd as mg
-    from paper_2203_04738_amd.binding import MGRIT_REUSE_PROJECTION, MgritGruCfg
+    from paper_2203_04738_amd.binding import (MGRIT_KEEP_COEFFS, MGRIT_REUSE_COEFFS,
+                                              MGRIT_REUSE_PROJECTION, MgritGruCfg)
     from synthetic_inputs import WORKLOADS, layer_workload, make_inputs
 
     wl = WORKLOADS[args.workload]
@@ -201,22 +202,24 @@ def stack_main(args):
     def mgrit_step():
         for j in range(L):
             lay[j]["h"].zero_()
-            mg.mgrit_gru_forward(lay[j]["cfg"](fwd_iters), *P(j), lay[j]["t"]["h0"], lay[j]["h"],
-                                 None, lay[j]["ws"])
+            mg.mgrit_gru_forward(lay[j]["cfg"](fwd_iters, MGRIT_KEEP_COEFFS), *P(j),
+                                 lay[j]["t"]["h0"], lay[j]["h"], None, lay[j]["ws"])
         head()
         for j in range(L - 1, -1, -1):
             lay[j]["w"].zero_()
-            mg.mgrit_gru_backward_steps(lay[j]["cfg"](bwd_iters, MGRIT_REUSE_PROJECTION), *P(j),
+            mg.mgrit_gru_backward_steps(lay[j]["cfg"](bwd_iters, MGRIT_REUSE_PROJECTION |
+                                                      MGRIT_REUSE_COEFFS), *P(j),
                                         lay[j]["h"], lay[j]["src"], lay[j]["w"], None,
                                         *lay[j]["g"], dx_of(j), lay[j]["ws"])
 
     def serial_step():
         for j in range(L):
-            mg.gru_serial_scan(lay[j]["cfg"](1), *P(j), lay[j]["t"]["h0"], lay[j]["h"],
-                               lay[j]["ws"])
+            mg.gru_serial_scan(lay[j]["cfg"](1, MGRIT_KEEP_COEFFS), *P(j), lay[j]["t"]["h0"],
+                               lay[j]["h"], lay[j]["ws"])
         head()
         for j in range(L - 1, -1, -1):
-            mg.gru_serial_scan_backward_steps(lay[j]["cfg"](1, MGRIT_REUSE_PROJECTION), *P(j),
+            mg.gru_serial_scan_backward_steps(lay[j]["cfg"](1, MGRIT_REUSE_PROJECTION |
+                                                            MGRIT_REUSE_COEFFS), *P(j),
                                               lay[j]["h"], lay[j]["src"], lay[j]["w"],
                                               *lay[j]["g"], dx_of(j), lay[j]["ws"])
 
@@ -342,7 +345,8 @@ def study_training(args):
     import torch
 
     import paper_2203_04738_amd as mg
-    from paper_2203_04738_amd.binding import MGRIT_REUSE_PROJECTION, MgritGruCfg
+    from paper_2203_04738_amd.binding import (MGRIT_KEEP_COEFFS, MGRIT_REUSE_COEFFS,
+                                              MGRIT_REUSE_PROJECTION, MgritGruCfg)
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -484,7 +488,8 @@ def main():
     import torch
 
     import paper_2203_04738_amd as mg
-    from paper_2203_04738_amd.binding import MGRIT_REUSE_PROJECTION, MgritGruCfg
+    from paper_2203_04738_amd.binding import (MGRIT_KEEP_COEFFS, MGRIT_REUSE_COEFFS,
+                                              MGRIT_REUSE_PROJECTION, MgritGruCfg)
     from synthetic_inputs import WORKLOADS, make_inputs
 
     wl = WORKLOADS[args.workload]
@@ -560,19 +565,22 @@ def main():
 
     def mgrit_step():
         h.zero_()
-        mg.mgrit_gru_forward(cfg(fwd_iters), *Wp, t["h0"], h, res_f, ws)
+        # the forward solve leaves the projection and the adjoint coefficients of the steps of
+        # its closing relaxation in the workspace; the backward solve reuses both
+        mg.mgrit_gru_forward(cfg(fwd_iters, MGRIT_KEEP_COEFFS if bwd_iters > 0 else 0), *Wp,
+                             t["h0"], h, res_f, ws)
         if bwd_iters > 0:
             g = loss_head()
             w.zero_()
-            mg.mgrit_gru_backward(cfg(bwd_iters, MGRIT_REUSE_PROJECTION), *Wp, h, g, w, res_b,
-                                  dW, dU, dbi, dbh, ws)
+            mg.mgrit_gru_backward(cfg(bwd_iters, MGRIT_REUSE_PROJECTION | MGRIT_REUSE_COEFFS), *Wp,
+                                  h, g, w, res_b, dW, dU, dbi, dbh, ws)
 
     def serial_step():
-        mg.gru_serial_scan(cfg(1), *Wp, t["h0"], h, ws)
+        mg.gru_serial_scan(cfg(1, MGRIT_KEEP_COEFFS if bwd_iters > 0 else 0), *Wp, t["h0"], h, ws)
         if bwd_iters > 0:
             g = loss_head()
-            mg.gru_serial_scan_backward(cfg(1, MGRIT_REUSE_PROJECTION), *Wp, h, g, w, dW, dU, dbi,
-                                        dbh, ws)
+            mg.gru_serial_scan_backward(cfg(1, MGRIT_REUSE_PROJECTION | MGRIT_REUSE_COEFFS), *Wp,
+                                        h, g, w, dW, dU, dbi, dbh, ws)
 
     def timed(fn, steps, warmup):
         for _ in range(warmup):

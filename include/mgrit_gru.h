@@ -72,7 +72,19 @@ enum {
    * there by an earlier call with the same sizes and dtype): skip recomputing
    * it.  The paper likewise computes per-step input features once and reuses
    * them on coarse grids and in back-propagation (Appendix A.3.2). */
-  MGRIT_REUSE_PROJECTION = 1
+  MGRIT_REUSE_PROJECTION = 1,
+  /* Forward calls (mgrit_gru_forward with iters >= 1, gru_serial_scan): while the
+   * closing F-relaxation of the last cycle (Alg. 2 line 6; every step of the
+   * serial scan) writes the final states, also leave in the workspace the
+   * coefficient vectors of the transposed Jacobian of each step it takes
+   * (Appendix A.2), which the adjoint solve would otherwise recompute. */
+  MGRIT_KEEP_COEFFS = 2,
+  /* Backward calls: the workspace holds what a forward call with
+   * MGRIT_KEEP_COEFFS left there, for the same sizes, hierarchy, dtype,
+   * propagator and workspace pointer, and the states h passed in are the ones
+   * that call returned: only the steps it did not cover (those into the coarse
+   * points) are linearised again. */
+  MGRIT_REUSE_COEFFS = 4
 };
 
 typedef struct {
@@ -84,7 +96,7 @@ typedef struct {
                            (Eq. 8); coarser levels always use FCF */
   int32_t propagator;   /* MGRIT_PROP_* */
   int32_t dtype;        /* MGRIT_F32 / MGRIT_BF16 */
-  int32_t flags;        /* MGRIT_REUSE_PROJECTION or 0 */
+  int32_t flags;        /* 0 or an OR of the flags above */
 } mgrit_gru_cfg;
 
 /* Bytes of device workspace one call needs (host-only computation).  The same

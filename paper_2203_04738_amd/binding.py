@@ -36,6 +36,8 @@ class MgritGruCfg(ctypes.Structure):
 
 
 MGRIT_REUSE_PROJECTION = 1
+MGRIT_KEEP_COEFFS = 2
+MGRIT_REUSE_COEFFS = 4
 _lib = None
 
 

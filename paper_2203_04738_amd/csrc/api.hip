@@ -71,7 +71,8 @@ static int check_cfg(const mgrit_gru_cfg* c, bool need_hierarchy) {
   if (c->propagator != MGRIT_PROP_IMPLICIT && c->propagator != MGRIT_PROP_CLASSIC)
     return MGRIT_E_ENUM;
   if (c->dtype != MGRIT_F32 && c->dtype != MGRIT_BF16) return MGRIT_E_ENUM;
-  if (c->flags & ~MGRIT_REUSE_PROJECTION) return MGRIT_E_ENUM;
+  if (c->flags & ~(MGRIT_REUSE_PROJECTION | MGRIT_KEEP_COEFFS | MGRIT_REUSE_COEFFS))
+    return MGRIT_E_ENUM;
   if (need_hierarchy) {
     if (c->cf < 1 || c->levels < 1 || c->levels > MAX_LEVELS) return MGRIT_E_SIZE;
     if (c->fine_relax != 0 && c->fine_relax != 1) return MGRIT_E_ENUM;
@@ -109,8 +110,6 @@ static int make_layout(const mgrit_gru_cfg* c, Layout* lay) {
   }
   lay->tmp = off;
   if (c->cf == 1 && L > 1) off = align_up(off + (size_t)(c->T + 1) * BH);
-  lay->norm = off;
-  off = align_up(off + (size_t)(c->iters > 0 ? c->iters : 1) * sizeof(double));
   for (int l = 0; l < L; ++l) {
     lay->kap[l] = off;
     off = align_up(off + (size_t)(lay->N[l] + 1) * BH * (l == 0 ? 5 : 4));
@@ -121,6 +120,11 @@ static int make_layout(const mgrit_gru_cfg* c, Layout* lay) {
   off = align_up(off + (size_t)3 * c->H * c->D * sizeof(float));
   lay->part = off;
   off = align_up(off + grad_partial_floats(c->T, c->B, c->D, c->H) * sizeof(float));
+  // last, because its size depends on iters: everything before it sits at the same
+  // offset in every call with the same sizes and hierarchy (projection and coefficient
+  // arrays can be reused across calls)
+  lay->norm = off;
+  off = align_up(off + (size_t)(c->iters > 0 ? c->iters : 1) * sizeof(double));
   lay->total = off;
   return MGRIT_OK;
 }
@@ -144,6 +148,7 @@ struct FwdCtx {
   float* gl[MAX_LEVELS];
   float* tmp;
   double* norm;     // accumulator of the current cycle (may be null)
+  float* emit_kap;  // level-0 coefficient array the closing relaxation also fills (or null)
   hipStream_t s;
 };
 
@@ -168,7 +173,8 @@ static PhiArgs phi_base(const FwdCtx& x, int l) {
 // advances every interval from point i*cf+j-1 to i*cf+j.  All intervals move in one
 // launch, so the C-sweep reads only values written by earlier launches (Jacobi in
 // the coarse points).
-static int relax_fwd(const FwdCtx& x, int l, bool include_c, bool f_points_current = false) {
+static int relax_fwd(const FwdCtx& x, int l, bool include_c, bool f_points_current = false,
+                     bool emit = false) {
   const long long cf = x.c->cf, S = x.lay->S[l];
   const int nint = (int)(x.lay->N[l] / cf);
   // f_points_current: the F-points already equal the propagation of their coarse
@@ -178,6 +184,13 @@ static int relax_fwd(const FwdCtx& x, int l, bool include_c, bool f_points_curre
   for (long long j = f_points_current ? cf : 1; j < cf + (include_c ? 1 : 0); ++j) {
     PhiArgs a = phi_base(x, l);
     a.mode = STEP_RELAX;
+    if (emit && x.emit_kap && l == 0) {
+      // this sweep's values are final: the step from point o-1 to o is the one the
+      // adjoint linearises, so its coefficient vectors are written along the way
+      a.mode = STEP_RELAX_KAPPA;
+      a.uc = x.emit_kap;
+      a.kappa_width = 5 * x.c->H;
+    }
     a.nk = nint;
     a.in = Idx{j - 1, cf};
     a.o = Idx{j, cf};
@@ -191,7 +204,7 @@ static int relax_fwd(const FwdCtx& x, int l, bool include_c, bool f_points_curre
   return MGRIT_OK;
 }
 
-static int vcycle_fwd(const FwdCtx& x, int l, bool f_points_current = false) {
+static int vcycle_fwd(const FwdCtx& x, int l, bool f_points_current = false, bool last = false) {
   const long long cf = x.c->cf, S = x.lay->S[l], N = x.lay->N[l];
   const int L = x.lay->L;
   if (l == L - 1) {
@@ -199,6 +212,11 @@ static int vcycle_fwd(const FwdCtx& x, int l, bool f_points_current = false) {
     for (long long k = 1; k <= N; ++k) {
       PhiArgs a = phi_base(x, l);
       a.mode = STEP_RELAX;
+      if (l == 0 && x.emit_kap) {        // one level: the serial scan itself
+        a.mode = STEP_RELAX_KAPPA;
+        a.uc = x.emit_kap;
+        a.kappa_width = 5 * x.c->H;
+      }
       a.nk = 1;
       a.in = Idx{k - 1, 0};
       a.o = Idx{k, 0};
@@ -246,7 +264,7 @@ static int vcycle_fwd(const FwdCtx& x, int l, bool f_points_current = false) {
   CHECK_HIP(launch_copy_points(x.ul[l], x.ul[l + 1], Idx{cf, cf}, Idx{1, 1}, Nc,
                                (long long)x.c->B * x.c->H, x.s));
   // line 6
-  return relax_fwd(x, l, false);
+  return relax_fwd(x, l, false, false, last && l == 0);
 }
 
 static int run_projection(const mgrit_gru_cfg* c, const void* W, const float* b_i, const void* x,
@@ -294,6 +312,10 @@ static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, co
     ctx.gl[l] = (float*)(base + lay.g[l]);
   }
   double* norm = (double*)(base + lay.norm);
+  // MGRIT_KEEP_COEFFS: the closing F-relaxation of the last cycle (the serial scan, with
+  // one level) also leaves the adjoint coefficient vectors of the steps it takes
+  ctx.emit_kap = (c.flags & MGRIT_KEEP_COEFFS) ? (float*)(base + lay.kap[0]) : nullptr;
+  if (ctx.emit_kap && c.iters < 1) return MGRIT_E_SIZE;
 
   if ((rc = run_projection(&c, W, b_i, x, (float*)(base + lay.P), s))) return rc;
   const long long BH = (long long)c.B * c.H;
@@ -302,7 +324,7 @@ static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, co
   if (resnorm && c.iters > 0) CHECK_HIP(launch_fill_f64(norm, c.iters, 0.0, s));
   for (int it = 0; it < c.iters; ++it) {
     ctx.norm = resnorm ? norm + it : nullptr;
-    if ((rc = vcycle_fwd(ctx, 0, it > 0))) return rc;
+    if ((rc = vcycle_fwd(ctx, 0, it > 0, it == c.iters - 1))) return rc;
   }
   if (resnorm && !serial) CHECK_HIP(launch_sqrt_to_float(norm, resnorm, c.iters, s));
   return MGRIT_OK;
@@ -484,6 +506,18 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
     a.in = Idx{0, lay.S[l]};
     a.p = Idx{lay.S[l] - 1, lay.S[l]};
     a.o = Idx{1, 1};
+    if (l == 0 && (c.flags & MGRIT_REUSE_COEFFS)) {
+      // the forward call left the coefficients of every step that ends in an F-point (all
+      // steps, with one level): only the steps into the coarse points i*cf remain
+      if (lay.L == 1) {
+        a.nk = 0;
+      } else {
+        a.nk = (int)(lay.N[0] / c.cf);
+        a.in = Idx{c.cf - 1, c.cf};
+        a.p = Idx{c.cf - 1, c.cf};
+        a.o = Idx{c.cf, c.cf};
+      }
+    }
     CHECK_HIP(launch_phi_step(a, s));
     // the terminal condition w_T = dL/dh_T is the fixed end point of every level
     CHECK_HIP(launch_copy_points(ctx.wl[l], dL_dhT, Idx{lay.N[l], 0}, Idx{0, 0}, 1, BH, s));

@@ -206,7 +206,7 @@ __device__ inline PhiEpiIn phi_epi_load(const PhiArgs& a, const PhiRow& ro, int 
 //   RELAX: v0 = new state (+ g)          RESID: v0 = -r (coarse right-hand side), v1 = cur
 //   RHS:   v0 = cur - step + g           KAPPA: v0..v4 = k_r, k_z, k_q, k_d, k_n
 struct PhiOut {
-  float v0, v1, v2, v3, v4;
+  float v0, v1, v2, v3, v4, v5;       // v5: new state (+ g) of STEP_RELAX_KAPPA
 };
 template <int MODE>
 __device__ inline PhiOut phi_elem(float gamma, bool implicit, float sr, float sz, float sn,
@@ -220,7 +220,8 @@ __device__ inline PhiOut phi_elem(float gamma, bool implicit, float sr, float sz
   const float d = 1.0f + gamma * c;
   const float rd = fast_rcp(d);
   const float hn = implicit ? (h + gamma * c * n) * rd : h + gamma * c * (n - h);
-  PhiOut o{0.f, 0.f, 0.f, 0.f, 0.f};
+  PhiOut o{0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (MODE == STEP_RELAX_KAPPA) o.v5 = hn + e.gval;
   if (MODE == STEP_RELAX) {
     o.v0 = hn + e.gval;
   } else if (MODE == STEP_RESID) {
@@ -268,6 +269,7 @@ __device__ inline void phi_epi_finish(const PhiArgs& a, const PhiRow& ro, int j,
   } else if (MODE == STEP_RHS) {
     a.g[oi] = o.v0;
   } else {
+    if (MODE == STEP_RELAX_KAPPA) a.u[oi] = o.v5;
     float* kp = a.uc + ro.a;
     kp[j] = o.v0;
     kp[H + j] = o.v1;
@@ -331,13 +333,13 @@ __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Ph
       const floatx4 sr = E::read(stage, 0, rp, c4);
       const floatx4 sz = E::read(stage, 1, rp, c4);
       const floatx4 sn = E::read(stage, 2, rp, c4);
-      floatx4 o0, o1, o2, o3, o4;
+      floatx4 o0, o1, o2, o3, o4, o5;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const PhiEpiIn e1{in[it].pr[i], in[it].pz[i], in[it].pn[i], in[it].h[i], in[it].gval[i],
                           in[it].cur[i]};
         const PhiOut o = phi_elem<MODE>(gamma, implicit, sr[i], sz[i], sn[i], e1, bh[i]);
-        o0[i] = o.v0; o1[i] = o.v1; o2[i] = o.v2; o3[i] = o.v3; o4[i] = o.v4;
+        o0[i] = o.v0; o1[i] = o.v1; o2[i] = o.v2; o3[i] = o.v3; o4[i] = o.v4; o5[i] = o.v5;
       }
       if (!colok || m0 + trow[it] >= R) continue;
       const long long oi = oo[it] + j;
@@ -352,6 +354,7 @@ __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Ph
       } else if (MODE == STEP_RHS) {
         *reinterpret_cast<floatx4*>(a.g + oi) = o0;
       } else {
+        if (MODE == STEP_RELAX_KAPPA) *reinterpret_cast<floatx4*>(a.u + oi) = o5;
         float* kp = a.uc + oa[it] + j;
         *reinterpret_cast<floatx4*>(kp) = o0;
         *reinterpret_cast<floatx4*>(kp + H) = o1;
@@ -379,7 +382,7 @@ __global__ __launch_bounds__(C::NT, 2) void phi_step_kernel(PhiArgs a) {
   if (tid < C::TM) {
     long long r = m0 + tid;
     if (r >= R) r = R - 1;
-    rowtab[tid] = phi_row(a, r, MODE == STEP_KAPPA ? a.kappa_width : H);
+    rowtab[tid] = phi_row(a, r, (MODE == STEP_KAPPA || MODE == STEP_RELAX_KAPPA) ? a.kappa_width : H);
   }
   // (visible to all waves after the barriers inside the contraction)
 
@@ -443,7 +446,7 @@ __global__ __launch_bounds__(C::NT, 2) void phi_step_kernel_bf16(PhiArgs a) {
   if (tid < C::TM) {
     long long r = m0 + tid;
     if (r >= R) r = R - 1;
-    rowtab[tid] = phi_row(a, r, MODE == STEP_KAPPA ? a.kappa_width : H);
+    rowtab[tid] = phi_row(a, r, (MODE == STEP_KAPPA || MODE == STEP_RELAX_KAPPA) ? a.kappa_width : H);
   }
   // (visible to all waves after the barriers inside the contraction)
 
@@ -509,7 +512,7 @@ __global__ __launch_bounds__(PhiSkMaxNT<CT>::value) void phi_skinny_kernel(PhiAr
   const int tid = threadIdx.x;
   const int ks = tid & (ksl - 1), rg = tid / ksl;
   const int j0 = blockIdx.x * CT;
-  const int aux_w = MODE == STEP_KAPPA ? a.kappa_width : H;
+  const int aux_w = (MODE == STEP_KAPPA || MODE == STEP_RELAX_KAPPA) ? a.kappa_width : H;
 
   // this thread's output element (if any): its operands are requested first so
   // that their latency overlaps the dot products
@@ -588,6 +591,9 @@ typedef TileCfgB<1, 1, 1, 1, 3, true, 4> PhiSmallB;
     case STEP_RHS:                                                                       \
       hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_RHS>), grid, block, 0, s, a);         \
       break;                                                                             \
+    case STEP_RELAX_KAPPA:                                                               \
+      hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_RELAX_KAPPA>), grid, block, 0, s, a); \
+      break;                                                                             \
     default:                                                                             \
       hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_KAPPA>), grid, block, 0, s, a);       \
   }
@@ -625,6 +631,7 @@ static void launch_phi_skinny(const PhiArgs& a, dim3 grid, hipStream_t s) {
     case STEP_RELAX: launch_phi_skinny_mode<CT, STEP_RELAX>(a, grid, s); break;
     case STEP_RESID: launch_phi_skinny_mode<CT, STEP_RESID>(a, grid, s); break;
     case STEP_RHS: launch_phi_skinny_mode<CT, STEP_RHS>(a, grid, s); break;
+    case STEP_RELAX_KAPPA: launch_phi_skinny_mode<CT, STEP_RELAX_KAPPA>(a, grid, s); break;
     default: launch_phi_skinny_mode<CT, STEP_KAPPA>(a, grid, s);
   }
 }

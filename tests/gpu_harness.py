@@ -6,7 +6,8 @@ import numpy as np
 import torch
 
 import paper_2203_04738_amd as mg
-from paper_2203_04738_amd.binding import MGRIT_REUSE_PROJECTION, MgritGruCfg
+from paper_2203_04738_amd.binding import (MGRIT_KEEP_COEFFS, MGRIT_REUSE_COEFFS,
+                                          MGRIT_REUSE_PROJECTION, MgritGruCfg)
 
 DEV = "cuda:0"
 
@@ -131,6 +132,24 @@ class GpuRun:
             grads = tuple(a.cpu().numpy() for a in g) + ((dx.cpu().numpy(),) if want_dx else ())
             done += n
         return its, norms, grads
+
+
+    # ---- forward call that keeps the adjoint coefficients, backward call that reuses them
+    def forward_then_backward_reusing_coeffs(self, fwd_iters, bwd_iters, serial=False):
+        h = torch.zeros(self.T + 1, self.B, self.H, device=DEV)
+        w = torch.zeros(self.T + 1, self.B, self.H, device=DEV)
+        g = self._grads()
+        if serial:
+            mg.gru_serial_scan(self.cfg(1, MGRIT_KEEP_COEFFS), *self._p(), self.t["h0"], h, self.ws)
+            mg.gru_serial_scan_backward(self.cfg(1, MGRIT_REUSE_PROJECTION | MGRIT_REUSE_COEFFS),
+                                        *self._p(), h, self.t["dL_dhT"], w, *g, self.ws)
+        else:
+            mg.mgrit_gru_forward(self.cfg(fwd_iters, MGRIT_KEEP_COEFFS), *self._p(), self.t["h0"],
+                                 h, None, self.ws)
+            mg.mgrit_gru_backward(self.cfg(bwd_iters, MGRIT_REUSE_PROJECTION | MGRIT_REUSE_COEFFS),
+                                  *self._p(), h, self.t["dL_dhT"], w, None, *g, self.ws)
+        torch.cuda.synchronize()
+        return (h.cpu().numpy(), w.cpu().numpy()) + tuple(a.cpu().numpy() for a in g)
 
 
 def rel_err(got, ref):

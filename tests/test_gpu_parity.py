@@ -178,6 +178,38 @@ def test_the_papers_hierarchies_at_128_steps(gh, cf, levels):
     _check_backward(gh, d, cf, levels, 2, h=gits[-1].astype(np.float64))
 
 
+@pytest.mark.parametrize("cf,levels,fcf,shape", [(4, 2, True, (48, 3, 20, 36)), (4, 3, False, (64, 3, 20, 36)),
+                                                 (1, 2, True, (12, 2, 8, 8)), (2, 3, True, (384, 40, 72, 100))])
+def test_coefficients_kept_by_the_forward_call_and_reused_by_the_backward_call(gh, cf, levels, fcf, shape):
+    """MGRIT_KEEP_COEFFS / MGRIT_REUSE_COEFFS: same results as the oracle, which linearises
+    every step at the states the forward solve returned."""
+    T, B, D, H = shape
+    d = random_small(80 + cf, T, B, D, H, scale=0.3)
+    run = gh.GpuRun(d, cf=cf, levels=levels, fine_relax=int(fcf))
+    got = run.forward_then_backward_reusing_coeffs(2, 2)
+    rh, _ = orc.mgrit_forward(*_P(d), d["x"], d["h0"], _zeros(d), cf, levels, 2, fine_relax_fcf=fcf)
+    assert gh.rel_err(got[0], rh) <= TOL
+    ref = orc.mgrit_backward(*_P(d), d["x"], got[0], d["dL_dhT"], _zeros(d), cf, levels, 2,
+                             fine_relax_fcf=fcf)
+    for name, g, r in zip(("w", "dW", "dU", "db_i", "db_h"), got[1:], (ref[0],) + ref[2:6]):
+        assert gh.rel_err(g, r) <= TOL, name
+    # and the plain calls on the same states give the same adjoint
+    its, _, _ = run.backward_iterates(got[0], 2, per_call=2)
+    assert gh.rel_err(got[1], its[-1]) <= 1e-6
+
+
+@pytest.mark.parametrize("shape", [(13, 3, 20, 36), (9, 70, 12, 132)])
+def test_serial_scan_keeps_coefficients_for_serial_bptt(gh, shape):
+    T, B, D, H = shape
+    d = random_small(90 + H, T, B, D, H, scale=0.3)
+    got = gh.GpuRun(d).forward_then_backward_reusing_coeffs(1, 1, serial=True)
+    rh = orc.serial_scan(*_P(d), d["x"], d["h0"])
+    assert gh.rel_err(got[0], rh) <= TOL
+    ref = orc.serial_bptt(*_P(d), d["x"], got[0], d["dL_dhT"])
+    for name, g, r in zip(("w", "dW", "dU", "db_i", "db_h"), got[1:], ref):
+        assert gh.rel_err(g, r) <= TOL, name
+
+
 # ------------------------------------------------------------------ API behaviour on the device
 
 def test_invalid_call_leaves_buffers_untouched(gh):

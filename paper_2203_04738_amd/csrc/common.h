@@ -60,9 +60,6 @@ struct AdjArgs {
   int bf16;
 };
 
-// elements of a 32x32 accumulator block whose epilogue operands are fetched together
-constexpr int EPI_BATCH = 4;
-
 hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s);
 hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s);
 

@@ -23,7 +23,7 @@ struct AdjRow {
   long long in, k, o, a;
 };
 __device__ inline AdjRow adj_row(const AdjArgs& a, long long r) {
-  const long long pt = r / a.B;
+  const long long pt = (unsigned)r / (unsigned)a.B;   // rows < 2^31: 32-bit division
   const int b = (int)(r - pt * a.B);
   AdjRow ro;
   ro.in = (a.in.at(pt) * a.B + b) * a.H;
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(C::NT, 2) void adj_step_kernel(AdjArgs a) {
   for (int s = 0; s < C::A_CHUNKS; ++s) {
     long long r = m0 + chunk_row<C>(s);
     if (r >= R) r = R - 1;     // clamped rows are never stored
-    const long long pt = r / B;
+    const long long pt = (unsigned)r / (unsigned)B;   // rows < 2^31: 32-bit division
     const int b = (int)(r - pt * B);
     krow[s] = a.kap + (a.k.at(pt) * B + b) * (long long)a.kw;
     wrow[s] = a.w_in + (a.in.at(pt) * B + b) * H;
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(C::NT, 2) void adj_step_kernel_bf16(AdjArgs a) {
   for (int s = 0; s < C::A_CHUNKS; ++s) {
     long long r = m0 + chunk_row_b<C>(s);
     if (r >= R) r = R - 1;
-    const long long pt = r / B;
+    const long long pt = (unsigned)r / (unsigned)B;   // rows < 2^31: 32-bit division
     const int b = (int)(r - pt * B);
     krow[s] = a.kap + (a.k.at(pt) * B + b) * (long long)a.kw;
     wrow[s] = a.w_in + (a.in.at(pt) * B + b) * H;

@@ -170,7 +170,7 @@ struct PhiRow {
   long long in, p, o, a;
 };
 __device__ inline PhiRow phi_row(const PhiArgs& a, long long r, int aux_width) {
-  const long long pt = r / a.B;
+  const long long pt = (unsigned)r / (unsigned)a.B;   // rows < 2^31: 32-bit division
   const int b = (int)(r - pt * a.B);
   PhiRow ro;
   ro.in = (a.in.at(pt) * a.B + b) * a.H;
@@ -394,7 +394,7 @@ __global__ __launch_bounds__(C::NT, 2) void phi_step_kernel(PhiArgs a) {
   for (int s = 0; s < C::A_CHUNKS; ++s) {
     long long r = m0 + chunk_row<C>(s);
     if (r >= R) r = R - 1;
-    const long long pt = r / B;
+    const long long pt = (unsigned)r / (unsigned)B;   // rows < 2^31: 32-bit division
     const int b = (int)(r - pt * B);
     arow[s] = a.u_in + (a.in.at(pt) * B + b) * H;
   }
@@ -456,7 +456,7 @@ __global__ __launch_bounds__(C::NT, 2) void phi_step_kernel_bf16(PhiArgs a) {
   for (int s = 0; s < C::A_CHUNKS; ++s) {
     long long r = m0 + chunk_row_b<C>(s);
     if (r >= R) r = R - 1;
-    const long long pt = r / B;
+    const long long pt = (unsigned)r / (unsigned)B;   // rows < 2^31: 32-bit division
     const int b = (int)(r - pt * B);
     arow[s] = a.u_in + (a.in.at(pt) * B + b) * H;
   }
@@ -534,7 +534,7 @@ __global__ __launch_bounds__(PhiSkMaxNT<CT>::value) void phi_skinny_kernel(PhiAr
 #pragma unroll
   for (int i = 0; i < SK_RR; ++i) {
     const int r = r0 + min(rg * SK_RR + i, rows_here - 1);
-    const long long pt = r / a.B;
+    const long long pt = (unsigned)r / (unsigned)a.B;   // rows < 2^31: 32-bit division
     const int b = r - (int)pt * a.B;
     hrow[i] = a.u_in + (a.in.at(pt) * a.B + b) * H;
   }

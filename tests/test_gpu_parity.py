@@ -295,3 +295,34 @@ def test_bf16_rejects_widths_not_multiple_of_8(gh):
     with pytest.raises(mg.MgritGruError) as e:
         mg.mgrit_gru_workspace_bytes(mg.MgritGruCfg(16, 2, 12, 36, cf=4, levels=2, dtype=1))
     assert e.value.code == -6
+
+
+# ------------------------------------------------------------------ the big tile configuration, ragged
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_big_tiles_with_ragged_rows_columns_and_k(gh, dtype):
+    """8 intervals x 1240 batch rows = 9920 rows per launch with H = 520: forward and adjoint
+    launches take the 128-row tile configurations of the full-size workloads, with a partly
+    filled last row tile (9920 = 77.5 x 128), a last column tile of 8 columns (520 = 8 x 64 + 8
+    = 4 x 128 + 8) and K tails (520 = 16 x 32 + 8, 1560 = 48 x 32 + 24).  Batch elements evolve
+    independently, so the oracle follows a sample of them through the full problem."""
+    T, B, D, H, cf, levels = 32, 1240, 8, 520, 4, 2
+    d = dict(random_small(55, T, B, D, H, scale=0.06))   # weights ~ 1.4/sqrt(H): a well-conditioned step
+    tol, tight = (TOL, TOL) if dtype == "fp32" else (TOL_BF16, TIGHT_BF16)
+    if dtype == "bf16":
+        d = _bf16_inputs(d)
+    run = gh.GpuRun(d, cf=cf, levels=levels, dtype=dtype)
+    gits, _ = run.forward_iterates(2, per_call=2)
+    sample = np.array([0, 1, 127, 128, 619, 1111, 1238, 1239])
+    ds = {k: (v[:, sample] if k == "x" else (v[sample] if k in ("h0", "dL_dhT") else v))
+          for k, v in d.items()}
+    rh, _ = orc.mgrit_forward(*_P(ds), ds["x"], ds["h0"], np.zeros((T + 1, len(sample), H)), cf,
+                              levels, 2)
+    e = gh.rel_err(gits[-1][:, sample], rh)
+    assert e <= tol and e <= tight, e
+    h = gits[-1]                                   # the adjoint is linearised at the states given
+    wits, _, _ = run.backward_iterates(h, 1)
+    out = orc.mgrit_backward(*_P(ds), ds["x"], h[:, sample], ds["dL_dhT"],
+                             np.zeros((T + 1, len(sample), H)), cf, levels, 1)
+    e = gh.rel_err(wits[-1][:, sample], out[0])
+    assert e <= tol and e <= tight, e

@@ -48,6 +48,7 @@ template <int WM_, int WN_, int BM_, int BN_, int NG_, int TK_ = 32, int NBUF_ =
 struct TileCfg {
   static constexpr int WM = WM_, WN = WN_, BM = BM_, BN = BN_, NG = NG_, TK = TK_, NBUF = NBUF_;
   static constexpr int KS = KS_;
+  static constexpr int MINWG = 2;               // resident workgroups per CU planned for
   static constexpr int NWAVES = WM * WN * KS;
   static constexpr int NT = NWAVES * 64;
   static constexpr int TM = WM * BM * 32;

@@ -40,10 +40,17 @@ __device__ inline void split_bf16(const F32x8& v, bf16x8& hi, bf16x8& lo) {
   }
 }
 
-template <int WM_, int WN_, int BM_, int BN_, int NG_, bool SPLIT_A_, int KS_ = 1>
+// DEPTH: K-slices whose global loads are in flight at once (each in its own set of
+// registers).  The MFMAs of a bf16 slice take a quarter of the time of an fp32 one, less
+// than the latency of the loads for the next slice; with DEPTH = 3 a slice's loads have
+// three slice times to arrive.  MINWG: resident workgroups per CU the register budget
+// is planned for.
+template <int WM_, int WN_, int BM_, int BN_, int NG_, bool SPLIT_A_, int KS_ = 1, int DEPTH_ = 1,
+          int MINWG_ = 2>
 struct TileCfgB {
   static constexpr int WM = WM_, WN = WN_, BM = BM_, BN = BN_, NG = NG_;
   static constexpr bool SPLIT_A = SPLIT_A_;
+  static constexpr int DEPTH = DEPTH_, MINWG = MINWG_;
   static constexpr int KS = KS_;                // K-split groups of waves (see TileCfg)
   static constexpr int TK = 64 * KS;            // bf16 elements per K-slice
   static constexpr int NA = SPLIT_A ? 2 : 1;    // A tiles in LDS
@@ -83,26 +90,29 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
   constexpr int NB = C::NG * C::BN;
   constexpr int NFA = C::NA * C::BM;
 
-  decltype(loadA(0, 0)) ra[C::A_CHUNKS];
-  bf16x8 rb[C::B_CHUNKS];
+  constexpr int DP = C::DEPTH;
+  // register set d holds the raw loads of the slices kt = d (mod DP); every index into
+  // these arrays is a constant once the loops below are unrolled
+  decltype(loadA(0, 0)) ra[DP][C::A_CHUNKS];
+  bf16x8 rb[DP][C::B_CHUNKS];
 
-  auto fetch = [&](int k0) {
+  auto fetch = [&](int d, int k0) {
 #pragma unroll
     for (int s = 0; s < C::A_CHUNKS; ++s) {
       int k = k0 + ((tid + s * C::NT) % C::CPR) * 8;
       if (KTAIL && k >= K) k = K - 8;
-      ra[s] = loadA(s, k);
+      ra[d][s] = loadA(s, k);
     }
 #pragma unroll
     for (int s = 0; s < C::B_CHUNKS; ++s) {
       int k = k0 + ((tid + s * C::NT) % C::CPR) * 8;
       if (KTAIL && k >= K) k = K - 8;
-      rb[s] = loadB(s, k);
+      rb[d][s] = loadB(s, k);
     }
   };
   bf16_t* As = lds;                               // hi (or only) A tile, then lo tile
   bf16_t* Bs = lds + C::NA * C::TM * C::LD;
-  auto stash = [&](int k0) {
+  auto stash = [&](int d, int k0) {
     bf16x8 z;
 #pragma unroll
     for (int i = 0; i < 8; ++i) z[i] = (__bf16)0.f;
@@ -113,18 +123,19 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
       const bool dead = KTAIL && k0 + (q % C::CPR) * 8 >= K;
       if constexpr (C::SPLIT_A) {
         bf16x8 hi, lo;
-        split_bf16(finA(ra[s]), hi, lo);
+        split_bf16(finA(ra[d][s]), hi, lo);
         *reinterpret_cast<bf16x8*>(&As[off]) = dead ? z : hi;
         *reinterpret_cast<bf16x8*>(&As[C::TM * C::LD + off]) = dead ? z : lo;
       } else {
-        *reinterpret_cast<bf16x8*>(&As[off]) = dead ? z : finA(ra[s]);
+        *reinterpret_cast<bf16x8*>(&As[off]) = dead ? z : finA(ra[d][s]);
       }
     }
 #pragma unroll
     for (int s = 0; s < C::B_CHUNKS; ++s) {
       const int q = tid + s * C::NT;
       const bool dead = KTAIL && k0 + (q % C::CPR) * 8 >= K;
-      *reinterpret_cast<bf16x8*>(&Bs[(q / C::CPR) * C::LD + (q % C::CPR) * 8]) = dead ? z : rb[s];
+      *reinterpret_cast<bf16x8*>(&Bs[(q / C::CPR) * C::LD + (q % C::CPR) * 8]) =
+          dead ? z : rb[d][s];
     }
   };
   const int a_off = ((wm * C::BM) * 32 + li) * C::LD + lh * 8 + ks * NC * 16;
@@ -157,28 +168,36 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
   };
 
   const int nkt = (K + C::TK - 1) / C::TK;
-  fetch(0);
-  stash(0);
-  __syncthreads();
-  for (int kt = 0; kt < nkt; ++kt) {
-    const bool more = kt + 1 < nkt;
-    if (more) fetch((kt + 1) * C::TK);
-    __builtin_amdgcn_sched_barrier(0);
-    bf16x8 fa[2][NFA];
-    bf16x8 fb[2][NB];
-    read_frags(0, fa[0], fb[0]);
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      if (c + 1 < NC) read_frags(c + 1, fa[(c + 1) & 1], fb[(c + 1) & 1]);
-      __builtin_amdgcn_sched_barrier(0);
-      mma(fa[c & 1], fb[c & 1]);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    __syncthreads();
-    if (more) {
-      stash((kt + 1) * C::TK);
-      __syncthreads();
+  for (int d = 0; d < DP; ++d)
+    if (d < nkt) fetch(d, d * C::TK);
+  stash(0, 0);
+  __syncthreads();
+  for (int kt0 = 0; kt0 < nkt; kt0 += DP) {
+#pragma unroll
+    for (int d = 0; d < DP; ++d) {
+      const int kt = kt0 + d;
+      if (kt < nkt) {
+        // slice kt sits in LDS, so its register set is free for slice kt + DP
+        if (kt + DP < nkt) fetch(d, (kt + DP) * C::TK);
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 fa[2][NFA];
+        bf16x8 fb[2][NB];
+        read_frags(0, fa[0], fb[0]);
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+          if (c + 1 < NC) read_frags(c + 1, fa[(c + 1) & 1], fb[(c + 1) & 1]);
+          __builtin_amdgcn_sched_barrier(0);
+          mma(fa[c & 1], fb[c & 1]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        if (kt + 1 < nkt) {
+          stash((d + 1) % DP, (kt + 1) * C::TK);
+          __syncthreads();
+        }
+      }
     }
   }
 }

@@ -124,7 +124,7 @@ struct KapW {
 };
 
 template <class C, int MODE>
-__global__ __launch_bounds__(C::NT, 2) void adj_step_kernel(AdjArgs a) {
+__global__ __launch_bounds__(C::NT, C::MINWG) void adj_step_kernel(AdjArgs a) {
   constexpr int LDSF =
       C::LDS_FLOATS > EpiStage<C>::FLOATS ? C::LDS_FLOATS : EpiStage<C>::FLOATS;
   __shared__ __attribute__((aligned(16))) float lds[LDSF];
@@ -192,7 +192,7 @@ struct KapW8 {
 };
 
 template <class C, int MODE>
-__global__ __launch_bounds__(C::NT, 2) void adj_step_kernel_bf16(AdjArgs a) {
+__global__ __launch_bounds__(C::NT, C::MINWG) void adj_step_kernel_bf16(AdjArgs a) {
   constexpr int LDSF = C::LDS_ELEMS / 2 + 1 > EpiStage<C>::FLOATS ? C::LDS_ELEMS / 2 + 1
                                                                   : EpiStage<C>::FLOATS;
   __shared__ __attribute__((aligned(16))) float ldsf[LDSF];
@@ -466,7 +466,9 @@ __global__ __launch_bounds__(AdjSkMaxNT<CT>::value) void adj_skinny_kernel(AdjAr
 typedef TileCfg<2, 2, 2, 2, 1> AdjBig;    // 128 x 128, 256 threads
 typedef TileCfg<2, 2, 1, 1, 1> AdjMid;    //  64 x 64, 256 threads
 typedef TileCfg<1, 1, 1, 1, 1, 128, 1, 4> AdjSmall;  //  32 x 32, 4 waves splitting K
-typedef TileCfgB<2, 2, 2, 2, 1, true> AdjBigB;
+// bf16: 8 waves of 32 x 64 each, one workgroup per CU, three K-slices in flight (the MFMAs
+// of a slice take less time than its loads need to arrive)
+typedef TileCfgB<4, 2, 1, 2, 1, true, 1, 3, 1> AdjBigB;
 typedef TileCfgB<2, 2, 1, 1, 1, true> AdjMidB;
 typedef TileCfgB<1, 1, 1, 1, 1, true, 4> AdjSmallB;
 
@@ -474,8 +476,8 @@ template <class C, class CB>
 static void launch_adj_cfg(const AdjArgs& a, hipStream_t s) {
   const long long R = (long long)a.nk * a.B;
   dim3 grid((unsigned)xcd_grid((R + C::TM - 1) / C::TM, (a.H + C::TN - 1) / C::TN));
-  dim3 block(C::NT);
-  static_assert(C::TM == CB::TM && C::TN == CB::TN && C::NT == CB::NT, "tile shapes must agree");
+  dim3 block(a.bf16 ? CB::NT : C::NT);
+  static_assert(C::TM == CB::TM && C::TN == CB::TN, "tile shapes must agree");
   if (a.bf16) {
     if (a.mode == STEP_RELAX)
       hipLaunchKernelGGL((adj_step_kernel_bf16<CB, STEP_RELAX>), grid, block, 0, s, a);
@@ -542,7 +544,7 @@ hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s) {
       launch_adj_skinny<2>(a, grid, s);
     else
       launch_adj_skinny<1>(a, grid, s);
-  } else if (tiles(AdjBig::TM, AdjBig::TN) >= 384)
+  } else if (tiles(AdjBig::TM, AdjBig::TN) >= (a.bf16 ? 256 : 384))
     launch_adj_cfg<AdjBig, AdjBigB>(a, s);
   else if (R > 32 && tiles(AdjMid::TM, AdjMid::TN) >= 256)
     launch_adj_cfg<AdjMid, AdjMidB>(a, s);

@@ -367,7 +367,7 @@ __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Ph
 }
 
 template <class C, int MODE>
-__global__ __launch_bounds__(C::NT, 2) void phi_step_kernel(PhiArgs a) {
+__global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel(PhiArgs a) {
   constexpr int LDSF = C::LDS_FLOATS > EpiStage<C>::FLOATS ? C::LDS_FLOATS : EpiStage<C>::FLOATS;
   __shared__ __attribute__((aligned(16))) float lds[LDSF];
   const int H = a.H, B = a.B;
@@ -428,7 +428,7 @@ __global__ __launch_bounds__(C::NT, 2) void phi_step_kernel(PhiArgs a) {
 // bf16 weights: the fp32 state rows are split into hi + lo bf16 tiles (see
 // gemm_core_bf16.h); gates, update and outputs stay fp32.
 template <class C, int MODE>
-__global__ __launch_bounds__(C::NT, 2) void phi_step_kernel_bf16(PhiArgs a) {
+__global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel_bf16(PhiArgs a) {
   constexpr int LDSF =
       C::LDS_ELEMS / 2 + 1 > EpiStage<C>::FLOATS ? C::LDS_ELEMS / 2 + 1 : EpiStage<C>::FLOATS;
   __shared__ __attribute__((aligned(16))) float ldsf[LDSF];
@@ -602,8 +602,8 @@ template <class C, class CB>
 static void launch_phi_cfg(const PhiArgs& a, hipStream_t s) {
   const long long R = (long long)a.nk * a.B;
   dim3 grid((unsigned)xcd_grid((R + C::TM - 1) / C::TM, (a.H + C::TN - 1) / C::TN));
-  dim3 block(C::NT);
-  static_assert(C::TM == CB::TM && C::TN == CB::TN && C::NT == CB::NT, "tile shapes must agree");
+  dim3 block(a.bf16 ? CB::NT : C::NT);
+  static_assert(C::TM == CB::TM && C::TN == CB::TN, "tile shapes must agree");
   if (a.bf16) {
     MG_LAUNCH_BY_MODE(phi_step_kernel_bf16, CB)
   } else {

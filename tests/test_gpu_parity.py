@@ -33,7 +33,8 @@ def _zeros(d):
 # ------------------------------------------------------------------ serial scan
 
 @pytest.mark.parametrize("prop", [orc.IMPLICIT, orc.CLASSIC])
-@pytest.mark.parametrize("shape", [(13, 3, 20, 36), (5, 1, 4, 4), (9, 70, 12, 132)])
+@pytest.mark.parametrize("shape", [(13, 3, 20, 36), (5, 1, 4, 4), (9, 70, 12, 132), (6, 70, 4, 4),
+                                   (6, 130, 8, 12)])
 def test_serial_scan_ragged_shapes(gh, prop, shape):
     T, B, D, H = shape
     d = random_small(100 + H, T, B, D, H, scale=0.3)
@@ -136,7 +137,7 @@ def _check_backward(gh, d, cf, levels, iters, fcf=True, prop=orc.IMPLICIT, h=Non
 
 
 @pytest.mark.parametrize("prop", [orc.IMPLICIT, orc.CLASSIC])
-@pytest.mark.parametrize("shape", [(13, 3, 20, 36), (9, 70, 12, 132)])
+@pytest.mark.parametrize("shape", [(13, 3, 20, 36), (9, 70, 12, 132), (6, 70, 4, 4), (6, 130, 8, 12)])
 def test_serial_bptt_and_gradients(gh, prop, shape):
     T, B, D, H = shape
     d = random_small(200 + H, T, B, D, H, scale=0.3)
@@ -241,7 +242,7 @@ def _bf16_inputs(d):
     return d
 
 
-@pytest.mark.parametrize("shape", [(13, 3, 24, 40), (6, 70, 16, 136)])
+@pytest.mark.parametrize("shape", [(13, 3, 24, 40), (6, 70, 16, 136), (6, 70, 8, 8)])
 def test_bf16_serial_scan_and_bptt(gh, shape):
     T, B, D, H = shape
     d = _bf16_inputs(random_small(300 + H, T, B, D, H, scale=0.3))

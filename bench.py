@@ -30,7 +30,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C3",
-                    help="C1..C5 (BASELINE.json configs in order); P1: the paper's HMDB51 shape")
+                    help="C1..C5 (the benchmark configurations in order); P1: the paper's HMDB51 shape")
     ap.add_argument("--fwd-iters", type=int, default=None)
     ap.add_argument("--bwd-iters", type=int, default=None)
     ap.add_argument("--fine-relax", choices=["FCF", "F"], default="FCF",
@@ -513,7 +513,7 @@ def main():
 
     convergence = None
     if args.until_converged:
-        # R12 of the design doc: cycles are applied one call at a time; stop when the residual
+        # cycles are applied one call at a time; stop when the residual
         # relative to ||h_serial|| is below 1e-8, or has not halved for two cycles in a row
         # (the fp32 floor), or after N_1/2 cycles (two-level FCF is exact by then)
         bwd_iters = 0

@@ -47,7 +47,7 @@ class Workload:
         return replace(self, name=self.name + "-twin", T=T)
 
 
-# The five configurations of the benchmark spec, in order (C1..C5).
+# The five benchmark configurations, in order (C1..C5).
 WORKLOADS: Dict[str, Workload] = {
     "C1": Workload("C1", T=64, B=2, D=16, H=32, cf=4, levels=2, fwd_iters=3, bwd_iters=3,
                    x_dist="normal0.1", w_dist="normal0.1"),
@@ -58,7 +58,7 @@ WORKLOADS: Dict[str, Workload] = {
     "C5": Workload("C5", T=16384, B=4, D=1024, H=1024, cf=4, levels=4, fwd_iters=2, bwd_iters=2),
     # Shape of the paper's HMDB51 experiment (Sec. 4: 128 time steps, batch 100, 1000
     # features, hidden size 1000, cf = 4, 3 levels, 2 forward / 1 backward iterations);
-    # used with two stacked layers.  Not one of the benchmark's configurations.
+    # used with two stacked layers.  Not one of the five benchmark configurations.
     "P1": Workload("P1", T=128, B=100, D=1000, H=1000, cf=4, levels=3, fwd_iters=2, bwd_iters=1,
                    x_dist="relu_normal"),
 }

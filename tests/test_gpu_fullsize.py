@@ -1,4 +1,4 @@
-"""Full-size parity: the HIP path runs the benchmark's configurations at full size in the
+"""Full-size parity: the HIP path runs the benchmark configurations C2..C5 at full size in the
 launch configuration bench.py times (all cycles in one call); the oracle computes a time
 window of the result.
 

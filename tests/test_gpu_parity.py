@@ -1,7 +1,7 @@
 """Parity of the HIP path with the CPU oracle, element by element, through the C ABI.
 
 Tolerance (fp32 path): max|gpu - oracle| / max|oracle| <= 1e-5 per tensor, the
-bar the benchmark spec states.  The oracle computes in float64 on the
+bar stated for this path.  The oracle computes in float64 on the
 same float32 inputs."""
 import numpy as np
 import pytest
@@ -230,7 +230,7 @@ def test_invalid_call_leaves_buffers_untouched(gh):
 
 # ------------------------------------------------------------------ bf16 inputs / weights
 
-TOL_BF16 = 2e-2       # the benchmark spec: bf16-input / fp32-state variant
+TOL_BF16 = 2e-2       # stated bar of the bf16-input / fp32-state variant
 TIGHT_BF16 = 1e-4     # what the hi+lo split of the fp32 operand is expected to reach
 
 

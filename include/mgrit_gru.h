@@ -203,6 +203,13 @@ MGRIT_API const char* mgrit_gru_strerror(int code);
 MGRIT_API int mgrit_gru_profile_enable(int on);
 MGRIT_API int mgrit_gru_profile_read(int kind, int64_t* launches, double* ms,
                            double* flops, double* bytes);
+/* The same for one launch shape of a step kernel class (kind 0, 1, 4, 5): only the
+ * launches that advance `rows` rows (level points x batch) in epilogue mode `mode`
+ * (0 = relaxation update, 1 = residual + restriction, 2 = coarse right-hand side,
+ * 3 = coefficients, 4 = relaxation update that keeps the coefficients); a negative
+ * value matches any.  Records that do not match stay for later reads. */
+MGRIT_API int mgrit_gru_profile_read_shape(int kind, int64_t rows, int mode,
+                           int64_t* launches, double* ms, double* flops, double* bytes);
 
 #ifdef __cplusplus
 }

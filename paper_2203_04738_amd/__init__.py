@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     mgrit_gru_forward,
     mgrit_gru_profile_enable,
     mgrit_gru_profile_read,
+    mgrit_gru_profile_read_shape,
     mgrit_gru_strerror,
     mgrit_gru_workspace_bytes,
 )

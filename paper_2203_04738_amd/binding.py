@@ -76,10 +76,15 @@ def lib() -> ctypes.CDLL:
                                          ctypes.POINTER(ctypes.c_double),
                                          ctypes.POINTER(ctypes.c_double),
                                          ctypes.POINTER(ctypes.c_double)]
+    L.mgrit_gru_profile_read_shape.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int,
+                                               ctypes.POINTER(ctypes.c_int64),
+                                               ctypes.POINTER(ctypes.c_double),
+                                               ctypes.POINTER(ctypes.c_double),
+                                               ctypes.POINTER(ctypes.c_double)]
     for name in ("mgrit_gru_workspace_bytes", "gru_serial_scan", "mgrit_gru_forward",
                  "gru_serial_scan_backward", "mgrit_gru_backward",
                  "gru_serial_scan_backward_steps", "mgrit_gru_backward_steps",
-                 "mgrit_gru_profile_enable",
+                 "mgrit_gru_profile_enable", "mgrit_gru_profile_read_shape",
                  "mgrit_gru_profile_read"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
@@ -202,6 +207,17 @@ def mgrit_gru_backward_steps(cfg, W, U, b_i, b_h, x, h, dL_dh, w_inout, resnorm_
 
 def mgrit_gru_profile_enable(on: bool) -> None:
     _check(lib().mgrit_gru_profile_enable(1 if on else 0), "mgrit_gru_profile_enable")
+
+
+def mgrit_gru_profile_read_shape(kind: int, rows: int = -1, mode: int = -1):
+    """(launches, total_ms, flops, bytes) of the launches of a step kernel class that advance
+    `rows` rows in epilogue mode `mode` (negative: any); clears what it returns."""
+    n = ctypes.c_int64(0)
+    ms, fl, by = ctypes.c_double(0), ctypes.c_double(0), ctypes.c_double(0)
+    _check(lib().mgrit_gru_profile_read_shape(kind, rows, mode, ctypes.byref(n), ctypes.byref(ms),
+                                              ctypes.byref(fl), ctypes.byref(by)),
+           "mgrit_gru_profile_read_shape")
+    return int(n.value), float(ms.value), float(fl.value), float(by.value)
 
 
 def mgrit_gru_profile_read(kind: int):

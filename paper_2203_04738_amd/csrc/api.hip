@@ -17,7 +17,8 @@ constexpr int MAX_LEVELS = 24;
 // profiling brackets
 // ---------------------------------------------------------------------------
 struct ProfRec {
-  int kind;
+  int kind, mode;
+  long long rows;
   hipEvent_t e0, e1;
   double flops, bytes;
 };
@@ -25,11 +26,13 @@ static bool g_prof = false;
 static std::mutex g_prof_mu;
 static std::vector<ProfRec> g_recs;
 
-void prof_begin(int kind, hipStream_t s) {
+void prof_begin(int kind, hipStream_t s, long long rows, int mode) {
   if (!g_prof) return;
   std::lock_guard<std::mutex> lk(g_prof_mu);
   ProfRec r;
   r.kind = kind;
+  r.rows = rows;
+  r.mode = mode;
   r.flops = r.bytes = 0;
   if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) return;
   (void)hipEventRecord(r.e0, s);
@@ -630,13 +633,18 @@ int mgrit_gru_profile_enable(int on) {
 }
 
 int mgrit_gru_profile_read(int kind, int64_t* launches, double* ms, double* flops, double* bytes) {
+  return mgrit_gru_profile_read_shape(kind, -1, -1, launches, ms, flops, bytes);
+}
+
+int mgrit_gru_profile_read_shape(int kind, int64_t rows, int mode, int64_t* launches, double* ms,
+                                 double* flops, double* bytes) {
   if (!launches || !ms || !flops || !bytes) return MGRIT_E_NULL;
   std::lock_guard<std::mutex> lk(g_prof_mu);
   *launches = 0;
   *ms = *flops = *bytes = 0.0;
   std::vector<ProfRec> keep;
   for (auto& r : g_recs) {
-    if (r.kind != kind) {
+    if (r.kind != kind || (rows >= 0 && r.rows != rows) || (mode >= 0 && r.mode != mode)) {
       keep.push_back(r);
       continue;
     }

@@ -91,7 +91,8 @@ hipError_t launch_copy_points(float* dst, const float* src, Idx d, Idx s, int nk
 hipError_t launch_sqrt_to_float(const double* acc, float* out, int n, hipStream_t s);
 
 // profiling brackets (see mgrit_gru_profile_enable)
-void prof_begin(int kind, hipStream_t s);
+// rows / mode describe the launch shape of a step kernel (0 / -1 where they do not apply)
+void prof_begin(int kind, hipStream_t s, long long rows = 0, int mode = -1);
 void prof_end(int kind, double flops, double bytes, hipStream_t s);
 
 }  // namespace mg

@@ -641,7 +641,7 @@ hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s) {
   const long long R = (long long)a.nk * a.B;
   auto tiles = [&](int tm, int tn) { return ((R + tm - 1) / tm) * ((a.H + tn - 1) / tn); };
   const int kind = R <= 2 * SK_MAXROWS ? 4 : 0;
-  prof_begin(kind, s);
+  prof_begin(kind, s, R, a.mode);
   if (R <= 2 * SK_MAXROWS) {
     // columns per workgroup: about 256 workgroups in all
     const int rb = phi_sk_rows(R);

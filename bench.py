@@ -619,7 +619,8 @@ def main():
              1: "adj_step (fused adjoint level step, MFMA tiles)",
              2: "projection GEMM", 3: "weight-gradient GEMMs + bias sums",
              4: "phi_skinny (few-row forward step, coarsest level)",
-             5: "adj_skinny (few-row adjoint step, coarsest level)"}
+             5: "adj_skinny (few-row adjoint step, coarsest level)",
+             7: "copy_points (coarse-grid correction, end conditions; HBM-bound)"}
     # dominant launch shape: the level-0 relaxation sub-step (all intervals x batch rows, epilogue
     # mode 0), read first; its launches are put back into the class total below
     dom_rows = (T // wl.cf) * B if wl.levels > 1 else B
@@ -633,6 +634,11 @@ def main():
             kernels[nm] = {"launches_per_step": n / args.steps, "ms_per_step": ms / args.steps,
                            "avg_launch_us": 1e3 * ms / n, "TFLOPs": fl / ms / 1e9,
                            "algorithmic_GBps": by / ms / 1e6}
+            if kind in (0, 1, 2, 3):
+                kernels[nm]["frac_of_mfma_peak"] = fl / ms / 1e9 / (
+                    MI355X_PEAK["fp32_TFLOPs"] if wl.dtype == "fp32" else MI355X_PEAK["bf16_TFLOPs"])
+            if kind == 7:
+                kernels[nm]["frac_of_hbm_peak"] = by / ms / 1e6 / MI355X_PEAK["hbm_GBps"]
     # whole step against the matrix-core peak: flops of all library kernels / step time
     step_flops = sum(v["TFLOPs"] * v["ms_per_step"] * 1e9 for v in kernels.values())
     dom = None

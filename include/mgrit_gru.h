@@ -198,7 +198,8 @@ MGRIT_API const char* mgrit_gru_strerror(int code);
  *   kind: 0 = forward step (Phi) on MFMA tiles, 1 = adjoint step (Phi^T) on MFMA tiles,
  *         2 = projection GEMM, 3 = weight-gradient GEMMs, 4 / 5 = forward / adjoint step
  *         in the few-row form used by the serial scan and the coarsest-level solve,
- *         6 = input-gradient GEMM.
+ *         6 = input-gradient GEMM, 7 = point copies (coarse-grid correction, terminal and
+ *         initial conditions).
  * All out-pointers are host pointers. */
 MGRIT_API int mgrit_gru_profile_enable(int on);
 MGRIT_API int mgrit_gru_profile_read(int kind, int64_t* launches, double* ms,

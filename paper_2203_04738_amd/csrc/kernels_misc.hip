@@ -33,8 +33,10 @@ hipError_t launch_copy_points(float* dst, const float* src, Idx d, Idx s, int nk
   if (nk <= 0) return hipSuccess;
   const long long block4 = block / 4;
   const long long n = (long long)nk * block4;
+  prof_begin(7, st, nk);
   hipLaunchKernelGGL(copy_points_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, dst,
                      src, d, s, nk, block4);
+  prof_end(7, 0.0, 8.0 * (double)nk * (double)block, st);   // one read and one write per float
   return hipGetLastError();
 }
 

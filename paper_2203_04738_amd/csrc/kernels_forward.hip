@@ -601,12 +601,13 @@ typedef TileCfgB<1, 1, 1, 1, 3, true, 4> PhiSmallB;
 template <class C, class CB>
 static void launch_phi_cfg(const PhiArgs& a, hipStream_t s) {
   const long long R = (long long)a.nk * a.B;
-  dim3 grid((unsigned)xcd_grid((R + C::TM - 1) / C::TM, (a.H + C::TN - 1) / C::TN));
-  dim3 block(a.bf16 ? CB::NT : C::NT);
-  static_assert(C::TM == CB::TM && C::TN == CB::TN, "tile shapes must agree");
   if (a.bf16) {
+    dim3 grid((unsigned)xcd_grid((R + CB::TM - 1) / CB::TM, (a.H + CB::TN - 1) / CB::TN));
+    dim3 block(CB::NT);
     MG_LAUNCH_BY_MODE(phi_step_kernel_bf16, CB)
   } else {
+    dim3 grid((unsigned)xcd_grid((R + C::TM - 1) / C::TM, (a.H + C::TN - 1) / C::TN));
+    dim3 block(C::NT);
     MG_LAUNCH_BY_MODE(phi_step_kernel, C)
   }
 }

@@ -427,3 +427,53 @@ def cross_entropy_head(h_T, W_o, b_o, labels):
     loss = -np.mean(np.log(p[np.arange(B), labels]))
     p[np.arange(B), labels] -= 1.0
     return loss, (p / B) @ W_o
+
+
+# --------------------------------------------------------------------------
+# The library's entry points, by name, on host arrays
+# --------------------------------------------------------------------------
+# Same argument order and the same configuration fields as the C ABI of the HIP
+# library (T, B, D, H are taken from the arrays; cf, levels, iters, fine_relax,
+# propagator from cfg, a mapping or an object with those attributes), so that a
+# test can call either side with one argument list.  Outputs are returned
+# (float64) instead of written through pointers; there is no workspace.
+
+def _cfg(cfg, name, default=None):
+    if isinstance(cfg, dict):
+        return cfg.get(name, default)
+    return getattr(cfg, name, default)
+
+
+def oracle_gru_serial_scan(cfg, W, U, b_i, b_h, x, h0):
+    return serial_scan(W, U, b_i, b_h, x, h0, _cfg(cfg, "propagator", IMPLICIT))
+
+
+def oracle_mgrit_gru_forward(cfg, W, U, b_i, b_h, x, h0, h_init):
+    """Returns (h, resnorms[iters])."""
+    return mgrit_forward(W, U, b_i, b_h, x, h0, h_init, _cfg(cfg, "cf"), _cfg(cfg, "levels"),
+                         _cfg(cfg, "iters"), bool(_cfg(cfg, "fine_relax", 1)),
+                         _cfg(cfg, "propagator", IMPLICIT))
+
+
+def oracle_gru_serial_scan_backward(cfg, W, U, b_i, b_h, x, h, dL_dhT):
+    """Returns (w, dW, dU, db_i, db_h)."""
+    return serial_bptt(W, U, b_i, b_h, x, h, dL_dhT, _cfg(cfg, "propagator", IMPLICIT))
+
+
+def oracle_mgrit_gru_backward(cfg, W, U, b_i, b_h, x, h, dL_dhT, w_init):
+    """Returns (w, resnorms[iters], dW, dU, db_i, db_h)."""
+    return mgrit_backward(W, U, b_i, b_h, x, h, dL_dhT, w_init, _cfg(cfg, "cf"),
+                          _cfg(cfg, "levels"), _cfg(cfg, "iters"),
+                          bool(_cfg(cfg, "fine_relax", 1)), _cfg(cfg, "propagator", IMPLICIT))
+
+
+def oracle_gru_serial_scan_backward_steps(cfg, W, U, b_i, b_h, x, h, dL_dh):
+    """Returns (w, dW, dU, db_i, db_h, dx)."""
+    return serial_bptt_steps(W, U, b_i, b_h, x, h, dL_dh, _cfg(cfg, "propagator", IMPLICIT))
+
+
+def oracle_mgrit_gru_backward_steps(cfg, W, U, b_i, b_h, x, h, dL_dh, w_init):
+    """Returns (w, resnorms[iters], dW, dU, db_i, db_h, dx)."""
+    return mgrit_backward(W, U, b_i, b_h, x, h, None, w_init, _cfg(cfg, "cf"), _cfg(cfg, "levels"),
+                          _cfg(cfg, "iters"), bool(_cfg(cfg, "fine_relax", 1)),
+                          _cfg(cfg, "propagator", IMPLICIT), dL_dh=dL_dh)

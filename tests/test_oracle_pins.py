@@ -495,3 +495,29 @@ def test_adjoint_mgrit_with_source_term_converges_to_step_bptt(levels, fcf):
     w, res, gW, gU, gbi, gbh, gx = out[:7]
     for a, b in zip((w, gW, gU, gbi, gbh, gx), ref):
         assert np.allclose(a, b, atol=1e-11)
+
+
+def test_entry_points_by_library_name_are_the_plain_functions():
+    """The oracle_* wrappers take the library's argument order and configuration fields."""
+    T, B, D, H = 16, 2, 3, 4
+    d = random_small(23, T, B, D, H)
+    cfg = {"cf": 4, "levels": 2, "iters": 2, "fine_relax": 1, "propagator": orc.IMPLICIT}
+    z = np.zeros((T + 1, B, H))
+    h, res = orc.oracle_mgrit_gru_forward(cfg, *_params(d), d["x"], d["h0"], z)
+    h2, res2 = orc.mgrit_forward(*_params(d), d["x"], d["h0"], z, 4, 2, 2)
+    assert np.array_equal(h, h2) and res == res2
+    assert np.array_equal(orc.oracle_gru_serial_scan(cfg, *_params(d), d["x"], d["h0"]),
+                          orc.serial_scan(*_params(d), d["x"], d["h0"]))
+    a = orc.oracle_mgrit_gru_backward(cfg, *_params(d), d["x"], h, d["dL_dhT"], z)
+    b = orc.mgrit_backward(*_params(d), d["x"], h, d["dL_dhT"], z, 4, 2, 2)
+    assert all(np.array_equal(u, v) for u, v in zip(a, b))
+    a = orc.oracle_gru_serial_scan_backward(cfg, *_params(d), d["x"], h, d["dL_dhT"])
+    b = orc.serial_bptt(*_params(d), d["x"], h, d["dL_dhT"])
+    assert all(np.array_equal(u, v) for u, v in zip(a, b))
+    src = np.zeros((T + 1, B, H))
+    src[T] = d["dL_dhT"]
+    a = orc.oracle_mgrit_gru_backward_steps(cfg, *_params(d), d["x"], h, src, z)
+    t = orc.oracle_mgrit_gru_backward(cfg, *_params(d), d["x"], h, d["dL_dhT"], z)
+    assert len(a) == 7 and all(np.array_equal(u, v) for u, v in zip(a[:6], t))
+    s6 = orc.oracle_gru_serial_scan_backward_steps(cfg, *_params(d), d["x"], h, src)
+    assert len(s6) == 6 and all(np.array_equal(u, v) for u, v in zip(s6[:5], b))

@@ -521,3 +521,46 @@ def test_entry_points_by_library_name_are_the_plain_functions():
     assert len(a) == 7 and all(np.array_equal(u, v) for u, v in zip(a[:6], t))
     s6 = orc.oracle_gru_serial_scan_backward_steps(cfg, *_params(d), d["x"], h, src)
     assert len(s6) == 6 and all(np.array_equal(u, v) for u, v in zip(s6[:5], b))
+
+
+@pytest.mark.parametrize("gamma_steps", [(1.0, 6), (4.0, 3)])
+def test_implicit_step_and_its_adjoint_against_autograd(gamma_steps):
+    """Eq. 16 written out once more as a few float64 tensor operations, differentiated by
+    autograd instead of by hand: pins the hand-derived transposed Jacobian of the Implicit
+    step (also for a coarse-level step size) and the Implicit serial BPTT."""
+    gamma, T = gamma_steps
+    B, D, H = 2, 3, 4
+    d = random_small(29, T, B, D, H)
+    W, U, b_i, b_h = (torch.from_numpy(a).double().requires_grad_(True) for a in _params(d))
+    x = torch.from_numpy(d["x"]).double().requires_grad_(True)
+    h0 = torch.from_numpy(d["h0"]).double().requires_grad_(True)
+
+    def step(xt, h):
+        gi, gh = xt @ W.T + b_i, h @ U.T + b_h
+        r = torch.sigmoid(gi[:, :H] + gh[:, :H])
+        z = torch.sigmoid(gi[:, H:2 * H] + gh[:, H:2 * H])
+        n = torch.tanh(gi[:, 2 * H:] + r * gh[:, 2 * H:])
+        return (h + gamma * (1 - z) * n) / (1 + gamma * (1 - z))
+
+    h, hs = h0, [h0]
+    for t in range(T):
+        h = step(x[t], h)
+        hs.append(h)
+    g = torch.from_numpy(d["dL_dhT"]).double()
+    (h * g).sum().backward()
+
+    ref = orc.serial_scan(*_params(d), d["x"], d["h0"], orc.IMPLICIT, gamma=gamma)
+    assert np.allclose(ref, torch.stack(hs).detach().numpy(), atol=1e-13)
+    # adjoint of the scan from the oracle's step pieces
+    P = orc.input_projection(d["W"], d["b_i"], d["x"])
+    w = d["dL_dhT"].astype(np.float64)
+    for t in range(T, 0, -1):
+        co = orc.phi_adjoint_coeffs(gamma, P[t - 1], ref[t - 1], d["U"].astype(np.float64),
+                                    d["b_h"].astype(np.float64), orc.IMPLICIT)
+        w = orc.phi_transpose(co, w, d["U"].astype(np.float64))
+    assert np.allclose(w, h0.grad.numpy(), atol=1e-12)
+    if gamma == 1.0:
+        out = orc.serial_bptt_steps(*_params(d), d["x"], ref,
+                                    np.concatenate([np.zeros((T, B, H)), d["dL_dhT"][None]]))
+        for a, b in zip(out[1:], (W.grad, U.grad, b_i.grad, b_h.grad, x.grad)):
+            assert np.allclose(a, b.numpy(), atol=1e-12)

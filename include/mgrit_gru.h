@@ -77,7 +77,9 @@ enum {
    * closing F-relaxation of the last cycle (Alg. 2 line 6; every step of the
    * serial scan) writes the final states, also leave in the workspace the
    * coefficient vectors of the transposed Jacobian of each step it takes
-   * (Appendix A.2), which the adjoint solve would otherwise recompute. */
+   * (Appendix A.2), which the adjoint solve would otherwise recompute.  (A
+   * serial scan over 64 or fewer batch rows leaves none: there one pass over
+   * all steps in the backward call is cheaper; the backward call knows.) */
   MGRIT_KEEP_COEFFS = 2,
   /* Backward calls: the workspace holds what a forward call with
    * MGRIT_KEEP_COEFFS left there, for the same sizes, hierarchy, dtype,

@@ -176,6 +176,12 @@ static PhiArgs phi_base(const FwdCtx& x, int l) {
 // advances every interval from point i*cf+j-1 to i*cf+j.  All intervals move in one
 // launch, so the C-sweep reads only values written by earlier launches (Jacobi in
 // the coarse points).
+// One level (the serial scan): whether the scan writes the adjoint coefficients along
+// the way when asked to keep them.  With few rows per step the scan runs in the few-row
+// kernels, where the five extra vectors per step cost more than one pass over all steps
+// in the tile kernel afterwards; forward and backward calls decide by the same rule.
+static bool serial_scan_keeps_coeffs(const mgrit_gru_cfg& c) { return c.B > 64; }
+
 static int relax_fwd(const FwdCtx& x, int l, bool include_c, bool f_points_current = false,
                      bool emit = false) {
   const long long cf = x.c->cf, S = x.lay->S[l];
@@ -319,6 +325,7 @@ static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, co
   // one level) also leaves the adjoint coefficient vectors of the steps it takes
   ctx.emit_kap = (c.flags & MGRIT_KEEP_COEFFS) ? (float*)(base + lay.kap[0]) : nullptr;
   if (ctx.emit_kap && c.iters < 1) return MGRIT_E_SIZE;
+  if (lay.L == 1 && !serial_scan_keeps_coeffs(c)) ctx.emit_kap = nullptr;
 
   if ((rc = run_projection(&c, W, b_i, x, (float*)(base + lay.P), s))) return rc;
   const long long BH = (long long)c.B * c.H;
@@ -513,7 +520,7 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
       // the forward call left the coefficients of every step that ends in an F-point (all
       // steps, with one level): only the steps into the coarse points i*cf remain
       if (lay.L == 1) {
-        a.nk = 0;
+        if (serial_scan_keeps_coeffs(c)) a.nk = 0;   // else: the scan left none, full pass
       } else {
         a.nk = (int)(lay.N[0] / c.cf);
         a.in = Idx{c.cf - 1, c.cf};

@@ -529,16 +529,13 @@ hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s) {
   const int kind = R <= 2 * SK_MAXROWS ? 5 : 1;
   prof_begin(kind, s, R, a.mode);
   if (R <= 2 * SK_MAXROWS) {
-    // columns per workgroup: about 256 workgroups in all
+    // up to four columns per workgroup (eight measured 1.8 us slower per step at 32 rows x 512)
     const int rb = adj_sk_rows(R);
     const int nrb = (int)((R + rb - 1) / rb);
     const long long hw = (long long)a.H * nrb;
-    int ct = hw >= 2048 ? 8 : (hw >= 1024 ? 4 : (hw >= 512 ? 2 : 1));
-    if (ct == 8 && sk_geom(rb, 3 * a.H).nt > AdjSkMaxNT<8>::value) ct = 4;
+    const int ct = hw >= 1024 ? 4 : (hw >= 512 ? 2 : 1);
     dim3 grid((unsigned)((a.H + ct - 1) / ct), (unsigned)nrb);
-    if (ct == 8)
-      launch_adj_skinny<8>(a, grid, s);
-    else if (ct == 4)
+    if (ct == 4)
       launch_adj_skinny<4>(a, grid, s);
     else if (ct == 2)
       launch_adj_skinny<2>(a, grid, s);

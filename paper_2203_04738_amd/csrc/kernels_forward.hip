@@ -644,15 +644,13 @@ hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s) {
   const int kind = R <= 2 * SK_MAXROWS ? 4 : 0;
   prof_begin(kind, s, R, a.mode);
   if (R <= 2 * SK_MAXROWS) {
-    // columns per workgroup: about 256 workgroups in all
+    // two hidden columns (six weight rows) per workgroup measured best from H = 512 up
+    // (6.2 us per step at 32 rows x 512, 5.5 at 4 rows x 1024; four columns: +0.5 us)
     const int rb = phi_sk_rows(R);
     const int nrb = (int)((R + rb - 1) / rb);
-    int ct = a.H * nrb >= 1024 ? 4 : (a.H * nrb >= 512 ? 2 : 1);
-    if (ct == 4 && sk_geom(rb, a.H).nt > PhiSkMaxNT<4>::value) ct = 2;
+    const int ct = a.H * nrb >= 512 ? 2 : 1;
     dim3 grid((unsigned)((a.H + ct - 1) / ct), (unsigned)nrb);
-    if (ct == 4)
-      launch_phi_skinny<4>(a, grid, s);
-    else if (ct == 2)
+    if (ct == 2)
       launch_phi_skinny<2>(a, grid, s);
     else
       launch_phi_skinny<1>(a, grid, s);

@@ -656,7 +656,7 @@ hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s) {
       launch_phi_skinny<1>(a, grid, s);
   } else if (tiles(PhiBig::TM, PhiBig::TN) >= 384)
     launch_phi_cfg<PhiBig, PhiBigB>(a, s);
-  else if (R > 32 && tiles(PhiMid::TM, PhiMid::TN) >= 256)
+  else if (R > 32 && tiles(PhiMid::TM, PhiMid::TN) >= 128)
     launch_phi_cfg<PhiMid, PhiMidB>(a, s);
   else
     launch_phi_cfg<PhiSmall, PhiSmallB>(a, s);

@@ -185,10 +185,19 @@ __device__ inline void gemm_nt_tile(Acc<C>& acc, int K, LoadA loadA, LoadB loadB
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       if (c + 1 < NC) read_frags(cur, c + 1, fa[(c + 1) & 1], fb[(c + 1) & 1]);
-      // keep the LDS reads of the next k-group ahead of this group's MFMAs (the
-      // scheduler would otherwise sink them next to their first use)
-      __builtin_amdgcn_sched_barrier(0);
       mma(fa[c & 1], fb[c & 1]);
+      if (c + 1 < NC) {
+        // issue order inside this k-group: one LDS read of the next group's fragments,
+        // then a share of this group's MFMAs, and so on (left to itself the scheduler
+        // sinks the reads next to their first use)
+        constexpr int NR = C::BM + NB;
+        constexpr int MPR = (4 * C::BM * NB) / NR;
+#pragma unroll
+        for (int i = 0; i < NR; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // one DS read
+          __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);   // MPR MFMAs
+        }
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
     __builtin_amdgcn_sched_barrier(0);

@@ -187,8 +187,18 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
           if (c + 1 < NC) read_frags(c + 1, fa[(c + 1) & 1], fb[(c + 1) & 1]);
-          __builtin_amdgcn_sched_barrier(0);
           mma(fa[c & 1], fb[c & 1]);
+          if (c + 1 < NC) {
+            // one LDS read of the next k-group, then a share of this group's MFMAs, in turn
+            constexpr int NR = NFA + NB;
+            constexpr int NM = C::NA * C::BM * NB;
+            constexpr int MPR = NM / NR > 0 ? NM / NR : 1;
+#pragma unroll
+            for (int i = 0; i < NR; ++i) {
+              __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+              __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);
+            }
+          }
           __builtin_amdgcn_sched_barrier(0);
         }
         __builtin_amdgcn_sched_barrier(0);

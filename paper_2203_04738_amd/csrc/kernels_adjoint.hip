@@ -702,14 +702,20 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
 #pragma unroll
       for (int p = 0; p < GTK / 2; ++p) {
         if (p + 1 < GTK / 2) frags(p + 1, av[(p + 1) & 1], bv[(p + 1) & 1]);
-        // keep the LDS reads of the next k-pair ahead of this pair's MFMAs
-        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
           for (int j = 0; j < 2; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[p & 1][i], bv[p & 1][j],
                                                              acc[i][j], 0, 0, 0);
+        if (p + 1 < GTK / 2) {
+          // one LDS read of the next k-pair, one MFMA of this pair, four times
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          }
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
       __builtin_amdgcn_sched_barrier(0);

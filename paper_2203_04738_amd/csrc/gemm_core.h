@@ -181,6 +181,9 @@ __device__ inline void gemm_nt_tile(Acc<C>& acc, int K, LoadA loadA, LoadB loadB
     __builtin_amdgcn_sched_barrier(0);
     floatx4 fa[2][C::BM];
     floatx4 fb[2][NB];
+    // waves that are feeding the MFMA pipe go first at instruction issue: waves of the
+    // other resident workgroup that are staging or in their epilogue fill the gaps
+    __builtin_amdgcn_s_setprio(2);
     read_frags(cur, 0, fa[0], fb[0]);
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
@@ -201,6 +204,7 @@ __device__ inline void gemm_nt_tile(Acc<C>& acc, int K, LoadA loadA, LoadB loadB
       __builtin_amdgcn_sched_barrier(0);
     }
     __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_setprio(0);
     if (C::NBUF == 2) {
       if (more) stash(nxt, (kt + 1) * C::TK);
       __syncthreads();

@@ -183,6 +183,7 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
         __builtin_amdgcn_sched_barrier(0);
         bf16x8 fa[2][NFA];
         bf16x8 fb[2][NB];
+        __builtin_amdgcn_s_setprio(2);        // see gemm_core.h
         read_frags(0, fa[0], fb[0]);
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
@@ -202,6 +203,7 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
           __builtin_amdgcn_sched_barrier(0);
         }
         __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_setprio(0);
         __syncthreads();
         if (kt + 1 < nkt) {
           stash((d + 1) % DP, (kt + 1) * C::TK);

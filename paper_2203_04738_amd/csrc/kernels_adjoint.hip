@@ -698,6 +698,7 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
       if (tid < GT)
         for (int r = nt; r < GTK; r += a.ntiles) colsum += As[r * GLD + tid];
       float av[2][2], bv[2][2];
+      __builtin_amdgcn_s_setprio(2);      // MFMA phase first at issue (see gemm_core.h)
       frags(0, av[0], bv[0]);
 #pragma unroll
       for (int p = 0; p < GTK / 2; ++p) {
@@ -719,6 +720,7 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
         __builtin_amdgcn_sched_barrier(0);
       }
       __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_setprio(0);
       __syncthreads();
       if (more) {
         stash(k0 + GTK);

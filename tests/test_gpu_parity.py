@@ -355,3 +355,58 @@ def test_launch_counts_of_two_fcf_cycles(gh):
     assert mg.mgrit_gru_profile_read(2)[0] == 1                          # one projection
     for kind in (4, 7):
         mg.mgrit_gru_profile_read(kind)                                  # drain
+
+
+# ------------------------------------------------------------------ capture in a HIP graph
+
+def test_forward_and_backward_calls_replay_from_a_hip_graph(gh):
+    """The library only enqueues kernels on the caller's stream (no allocation, no memset node,
+    no synchronisation), so a training step can be captured once and replayed.  Every replay,
+    with unrelated eager work and synchronisations in between, must give the bits of the eager
+    run (the residual norms to rounding: their accumulators are cleared by a kernel)."""
+    import paper_2203_04738_amd as mg
+    from paper_2203_04738_amd.binding import (MGRIT_KEEP_COEFFS, MGRIT_REUSE_COEFFS,
+                                              MGRIT_REUSE_PROJECTION)
+    T, B, D, H = 64, 70, 12, 36
+    d = random_small(12, T, B, D, H, scale=0.2)
+    run = gh.GpuRun(d, cf=4, levels=3)
+    dev = gh.DEV
+    h = torch.zeros(T + 1, B, H, device=dev)
+    w = torch.zeros(T + 1, B, H, device=dev)
+    rf = torch.zeros(2, device=dev)
+    rb = torch.zeros(1, device=dev)
+    g = run._grads()
+
+    def step():
+        h.zero_()
+        mg.mgrit_gru_forward(run.cfg(2, MGRIT_KEEP_COEFFS), *run._p(), run.t["h0"], h, rf, run.ws)
+        w.zero_()
+        mg.mgrit_gru_backward(run.cfg(1, MGRIT_REUSE_PROJECTION | MGRIT_REUSE_COEFFS), *run._p(),
+                              h, run.t["dL_dhT"], w, rb, *g, run.ws)
+
+    step()
+    torch.cuda.synchronize()
+    ref = [a.clone() for a in (h, w, rf, rb) + tuple(g)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                    # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+    for i in range(3):
+        for a in (h, w, rf, rb) + tuple(g):
+            a.fill_(float(i + 2))                 # stale values a replay must overwrite
+        junk = torch.randn(256, 256, device=dev) @ torch.randn(256, 256, device=dev)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, (a, r) in enumerate(zip((h, w, rf, rb) + tuple(g), ref)):
+            if k in (2, 3):       # residual norms: sums of atomics, the order of terms is free
+                assert torch.allclose(a, r, rtol=1e-6, atol=0), i
+            else:
+                assert torch.equal(a, r), i
+        del junk

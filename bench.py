@@ -689,7 +689,7 @@ def main():
             "mgrit_speedup": s_rec / m_rec}
 
     out = {
-        "metric": "GRU time-steps x batch / sec, MGRIT fwd+bwd (1 GPU)",
+        "metric": "GRU time-steps×batch/sec, MGRIT fwd+bwd vs serial scan (1 GPU); % roofline",
         "value": T * B / sec,
         "unit": "time-steps*batch/s",
         "n_gpus": 1,

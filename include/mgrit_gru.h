@@ -64,7 +64,7 @@ enum {
 
 enum { MGRIT_PROP_IMPLICIT = 0,   /* Eq. 16, the paper's propagator on all levels */
        MGRIT_PROP_CLASSIC = 1 };  /* Eq. 3 (explicit Euler; Classic GRU when step = 1) */
-enum { MGRIT_F32 = 0, MGRIT_BF16 = 1 };
+enum { MGRIT_F32 = 0, MGRIT_BF16 = 1, MGRIT_F32_BF16X3 = 2 };
 
 /* flags */
 enum {
@@ -97,7 +97,7 @@ typedef struct {
   int32_t fine_relax;   /* level-0 relaxation in Alg. 2 line 1: 0 = F, 1 = FCF
                            (Eq. 8); coarser levels always use FCF */
   int32_t propagator;   /* MGRIT_PROP_* */
-  int32_t dtype;        /* MGRIT_F32 / MGRIT_BF16 */
+  int32_t dtype;        /* MGRIT_F32 / MGRIT_BF16 / MGRIT_F32_BF16X3 */
   int32_t flags;        /* 0 or an OR of the flags above */
 } mgrit_gru_cfg;
 

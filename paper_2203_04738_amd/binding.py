@@ -116,7 +116,7 @@ def _stream() -> int:
 
 def _in_dtype(cfg: MgritGruCfg):
     import torch
-    return torch.float32 if cfg.dtype == 0 else torch.bfloat16
+    return torch.bfloat16 if cfg.dtype == 1 else torch.float32
 
 
 def _check(rc: int, where: str) -> None:

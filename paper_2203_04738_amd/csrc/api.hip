@@ -61,6 +61,8 @@ struct Layout {
   size_t norm;
   size_t kap[MAX_LEVELS];
   size_t UT, WT, part;
+  size_t U3, UT3, W3;             // MGRIT_F32_BF16X3: three-term bf16 copies of U, U^T and
+                                  // W (or W^T, once the projection is done)
   size_t total;
 };
 
@@ -73,7 +75,8 @@ static int check_cfg(const mgrit_gru_cfg* c, bool need_hierarchy) {
   if (c->iters < 0) return MGRIT_E_SIZE;
   if (c->propagator != MGRIT_PROP_IMPLICIT && c->propagator != MGRIT_PROP_CLASSIC)
     return MGRIT_E_ENUM;
-  if (c->dtype != MGRIT_F32 && c->dtype != MGRIT_BF16) return MGRIT_E_ENUM;
+  if (c->dtype != MGRIT_F32 && c->dtype != MGRIT_BF16 && c->dtype != MGRIT_F32_BF16X3)
+    return MGRIT_E_ENUM;
   if (c->flags & ~(MGRIT_REUSE_PROJECTION | MGRIT_KEEP_COEFFS | MGRIT_REUSE_COEFFS))
     return MGRIT_E_ENUM;
   if (need_hierarchy) {
@@ -86,7 +89,7 @@ static int check_cfg(const mgrit_gru_cfg* c, bool need_hierarchy) {
     }
     if (c->T % s != 0) return MGRIT_E_HIERARCHY;
   }
-  const int mult = c->dtype == MGRIT_BF16 ? 8 : 4;
+  const int mult = c->dtype == MGRIT_F32 ? 4 : 8;
   if (c->H % mult != 0 || c->D % mult != 0) return MGRIT_E_ALIGN;
   return MGRIT_OK;
 }
@@ -123,6 +126,14 @@ static int make_layout(const mgrit_gru_cfg* c, Layout* lay) {
   off = align_up(off + (size_t)3 * c->H * c->D * sizeof(float));
   lay->part = off;
   off = align_up(off + grad_partial_floats(c->T, c->B, c->D, c->H) * sizeof(float));
+  if (c->dtype == MGRIT_F32_BF16X3) {
+    lay->U3 = off;
+    off = align_up(off + (size_t)3 * 3 * c->H * c->H * 2);
+    lay->UT3 = off;
+    off = align_up(off + (size_t)3 * 3 * c->H * c->H * 2);
+    lay->W3 = off;
+    off = align_up(off + (size_t)3 * 3 * c->H * c->D * 2);
+  }
   // last, because its size depends on iters: everything before it sits at the same
   // offset in every call with the same sizes and hierarchy (projection and coefficient
   // arrays can be reused across calls)
@@ -145,7 +156,7 @@ static bool misaligned(const void* p) { return ((uintptr_t)p & 15) != 0; }
 struct FwdCtx {
   const mgrit_gru_cfg* c;
   const Layout* lay;
-  const void* U;
+  const void *U, *U3;
   const float *b_h, *P;
   float* ul[MAX_LEVELS];
   float* gl[MAX_LEVELS];
@@ -159,6 +170,7 @@ static PhiArgs phi_base(const FwdCtx& x, int l) {
   PhiArgs a;
   std::memset(&a, 0, sizeof(a));
   a.U = x.U;
+  a.U3 = x.U3;
   a.b_h = x.b_h;
   a.P = x.P;
   a.u_in = x.ul[l];
@@ -168,7 +180,7 @@ static PhiArgs phi_base(const FwdCtx& x, int l) {
   a.H = x.c->H;
   a.gamma = (float)x.lay->S[l];
   a.propagator = x.c->propagator;
-  a.bf16 = x.c->dtype == MGRIT_BF16;
+  a.bf16 = x.c->dtype;      // the enum values are the kernels' operand forms
   return a;
 }
 
@@ -276,11 +288,15 @@ static int vcycle_fwd(const FwdCtx& x, int l, bool f_points_current = false, boo
   return relax_fwd(x, l, false, false, last && l == 0);
 }
 
-static int run_projection(const mgrit_gru_cfg* c, const void* W, const float* b_i, const void* x,
-                          float* P, hipStream_t s) {
+static int run_projection(const mgrit_gru_cfg* c, const Layout& lay, char* base, const void* W,
+                          const float* b_i, const void* x, hipStream_t s) {
   if (c->flags & MGRIT_REUSE_PROJECTION) return MGRIT_OK;
-  CHECK_HIP(launch_projection(x, W, b_i, P, (long long)c->T * c->B, 3 * c->H, c->D,
-                              c->dtype == MGRIT_BF16, s));
+  if (c->dtype == MGRIT_F32_BF16X3) {
+    CHECK_HIP(launch_split3((const float*)W, base + lay.W3, 3LL * c->H * c->D, s));
+    W = base + lay.W3;
+  }
+  CHECK_HIP(launch_projection(x, W, b_i, (float*)(base + lay.P), (long long)c->T * c->B, 3 * c->H,
+                              c->D, c->dtype, s));
   return MGRIT_OK;
 }
 
@@ -310,6 +326,11 @@ static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, co
   ctx.c = &c;
   ctx.lay = &lay;
   ctx.U = U;
+  ctx.U3 = nullptr;
+  if (c.dtype == MGRIT_F32_BF16X3) {
+    ctx.U3 = base + lay.U3;
+    CHECK_HIP(launch_split3((const float*)U, base + lay.U3, 3LL * c.H * c.H, s));
+  }
   ctx.b_h = b_h;
   ctx.P = (const float*)(base + lay.P);
   ctx.s = s;
@@ -327,7 +348,7 @@ static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, co
   if (ctx.emit_kap && c.iters < 1) return MGRIT_E_SIZE;
   if (lay.L == 1 && !serial_scan_keeps_coeffs(c)) ctx.emit_kap = nullptr;
 
-  if ((rc = run_projection(&c, W, b_i, x, (float*)(base + lay.P), s))) return rc;
+  if ((rc = run_projection(&c, lay, base, W, b_i, x, s))) return rc;
   const long long BH = (long long)c.B * c.H;
   for (int l = 0; l < lay.L; ++l)   // point 0 of every level is the initial condition
     CHECK_HIP(launch_copy_points(ctx.ul[l], h0, Idx{0, 0}, Idx{0, 0}, 1, BH, s));
@@ -346,7 +367,7 @@ static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, co
 struct BwdCtx {
   const mgrit_gru_cfg* c;
   const Layout* lay;
-  const void* UT;
+  const void *UT, *UT3;
   const float* kap[MAX_LEVELS];
   float* wl[MAX_LEVELS];
   float* gl[MAX_LEVELS];
@@ -359,6 +380,7 @@ static AdjArgs adj_base(const BwdCtx& x, int l) {
   AdjArgs a;
   std::memset(&a, 0, sizeof(a));
   a.UT = x.UT;
+  a.UT3 = x.UT3;
   a.kap = x.kap[l];
   a.kw = (l == 0 ? 5 : 4) * x.c->H;
   a.w_in = x.wl[l];
@@ -366,7 +388,7 @@ static AdjArgs adj_base(const BwdCtx& x, int l) {
   a.g = x.gl[l];
   a.B = x.c->B;
   a.H = x.c->H;
-  a.bf16 = x.c->dtype == MGRIT_BF16;
+  a.bf16 = x.c->dtype;
   return a;
 }
 
@@ -478,14 +500,19 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
   const float* P = (const float*)(base + lay.P);
   const long long BH = (long long)c.B * c.H;
 
-  if ((rc = run_projection(&c, W, b_i, x, (float*)(base + lay.P), s))) return rc;
+  if ((rc = run_projection(&c, lay, base, W, b_i, x, s))) return rc;
   const int bf16 = c.dtype == MGRIT_BF16;
   CHECK_HIP(launch_transpose(U, base + lay.UT, 3 * c.H, c.H, bf16, s));
+  if (c.dtype == MGRIT_F32_BF16X3) {
+    CHECK_HIP(launch_split3((const float*)U, base + lay.U3, 3LL * c.H * c.H, s));
+    CHECK_HIP(launch_split3((const float*)(base + lay.UT), base + lay.UT3, 3LL * c.H * c.H, s));
+  }
 
   BwdCtx ctx;
   ctx.c = &c;
   ctx.lay = &lay;
   ctx.UT = base + lay.UT;
+  ctx.UT3 = base + lay.UT3;
   ctx.s = s;
   ctx.tmp = (float*)(base + lay.tmp);
   ctx.wl[0] = w;
@@ -501,7 +528,8 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
     PhiArgs a;
     std::memset(&a, 0, sizeof(a));
     a.U = U;
-    a.bf16 = bf16;
+    a.U3 = base + lay.U3;
+    a.bf16 = c.dtype;
     a.b_h = b_h;
     a.P = P;
     a.u_in = h;
@@ -541,10 +569,15 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
   if (resnorm && !serial) CHECK_HIP(launch_sqrt_to_float(norm, resnorm, c.iters, s));
   if (ngrad == 4)
     CHECK_HIP(launch_param_grads(ctx.kap[0], w, h, x, dW, dU, db_i, db_h,
-                                 (float*)(base + lay.part), c.T, c.B, c.D, c.H, bf16, s));
+                                 (float*)(base + lay.part), c.T, c.B, c.D, c.H, c.dtype, s));
   if (dx) {
     CHECK_HIP(launch_transpose(W, base + lay.WT, 3 * c.H, c.D, bf16, s));
-    CHECK_HIP(launch_input_grads(ctx.kap[0], w, base + lay.WT, dx, c.T, c.B, c.D, c.H, bf16, s));
+    const void* WT = base + lay.WT;
+    if (c.dtype == MGRIT_F32_BF16X3) {
+      CHECK_HIP(launch_split3((const float*)WT, base + lay.W3, 3LL * c.H * c.D, s));
+      WT = base + lay.W3;
+    }
+    CHECK_HIP(launch_input_grads(ctx.kap[0], w, WT, dx, c.T, c.B, c.D, c.H, c.dtype, s));
   }
   return MGRIT_OK;
 }

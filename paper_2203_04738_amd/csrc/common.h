@@ -27,6 +27,7 @@ enum StepMode {
 // One launch of the fused forward step  Phi_gamma(x, h) over nk level points.
 struct PhiArgs {
   const void* U;       // [3H,H], float or bf16 (see bf16)
+  const void* U3;      // bf16 == 2: the three bf16 terms of U, [3][3H,H]
   const float* b_h;    // [3H]
   const float* P;      // [T,B,3H] input projection
   const float* u_in;   // state array the step reads from
@@ -42,11 +43,13 @@ struct PhiArgs {
   int propagator;
   int mode;
   int bf16;            // 1: U is bf16 and the contraction runs on the bf16 MFMA path
+                       // 2: U is float; the tile kernels contract three-term bf16 operands
 };
 
 // One launch of the fused adjoint step  w_out = (dPhi/dh)^T w_in  over nk points.
 struct AdjArgs {
   const void* UT;      // [H,3H] transposed recurrent weights, float or bf16
+  const void* UT3;     // bf16 == 2: the three bf16 terms of UT, [3][H,3H]
   const float* kap;    // coefficient array of this level, [*,B,kw]: k_r,k_z,k_q,k_d(,k_n)
   const float* w_in;   // adjoint array the step reads from
   float* w;            // level adjoint array (out / cur)
@@ -57,14 +60,15 @@ struct AdjArgs {
   Idx in, k, o, a;     // point indices: input adjoint, coefficient row, out/cur/g, coarse
   int nk, B, H, kw;
   int mode;
-  int bf16;
+  int bf16;            // operand form, as in PhiArgs
 };
 
 hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s);
 hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s);
 
 // P[M,N] = X[M,K] W[N,K]^T + bias[N]
-// X, W: float (bf16 = 0) or bf16 (bf16 = 1)
+// X, W: float (bf16 = 0) or bf16 (bf16 = 1); bf16 = 2: X float, W the three bf16 terms
+// [3][N,K] of the float weights
 hipError_t launch_projection(const void* X, const void* W, const float* bias, float* P,
                              long long M, int N, int K, int bf16, hipStream_t s);
 // UT[H,3H] = U[3H,H]^T; elements are 4 bytes (bf16 = 0) or 2 bytes
@@ -80,9 +84,14 @@ hipError_t launch_param_grads(const float* kap0, const float* w, const float* h,
                               int T, int B, int D, int H, int bf16, hipStream_t s);
 
 // Input gradients dx[T,B,D] from the level-0 coefficients, the adjoint w and the
-// transposed input weights WT[D,3H] (float, or bf16 with bf16 = 1).
+// transposed input weights WT[D,3H] (float, or bf16 with bf16 = 1, or its three bf16 terms
+// [3][D,3H] with bf16 = 2).
 hipError_t launch_input_grads(const float* kap0, const float* w, const void* WT, float* dx, int T,
                               int B, int D, int H, int bf16, hipStream_t s);
+
+// dst[t][i] (t = 0..2, bf16) = t-th term of src[i]: src = dst[0] + dst[1] + dst[2] exactly
+// unless a term underflows; n a multiple of 4
+hipError_t launch_split3(const float* src, void* dst, long long n, hipStream_t s);
 
 hipError_t launch_fill_f64(double* p, long long n, double v, hipStream_t s);
 // dst[(d.off + i*d.str), :, :] = src[(s.off + i*s.str), :, :] for i < nk; blocks of `block` floats

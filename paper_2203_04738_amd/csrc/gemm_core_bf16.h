@@ -9,6 +9,13 @@
 // fp32 state in the product, so the only rounding the method sees beyond fp32 is
 // the one already present in the stored bf16 weights.
 //
+// With NP = 3 both operands are fp32 VALUES carried as three bf16 terms each
+// (a = a0 + a1 + a2 exactly: 3 x 8 mantissa bits); the contraction keeps the six
+// products a_t * b_u with t + u <= 2 and drops the three of relative size 2^-24 and
+// below, so the fp32 accumulators receive what an fp32 product would have given them,
+// at the rate of the bf16 matrix pipe.  A is split on its way to LDS, B arrives already
+// split (three arrays, prepared once per call).
+//
 // A lane supplies eight consecutive k of its row (one ds_read_b128) per MFMA, the
 // two half-waves taking k-offsets 0..7 and 8..15 of each group of sixteen; A and B
 // use the same assignment, so the contraction is independent of how the
@@ -26,6 +33,25 @@ struct F32x8 {
 };
 
 __device__ inline bf16x8 ldg8h(const bf16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
+
+struct Bf16x8x3 {
+  bf16x8 p[3];                     // the three terms of eight consecutive values
+};
+__device__ inline const bf16x8& operand_term(const bf16x8& v, int) { return v; }
+__device__ inline const bf16x8& operand_term(const Bf16x8x3& v, int u) { return v.p[u]; }
+
+__device__ inline void split_bf16_3(const F32x8& v, bf16x8& t0, bf16x8& t1, bf16x8& t2) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const float a = i < 4 ? v.lo4[i] : v.hi4[i - 4];
+    const __bf16 h = (__bf16)a;
+    const float r1 = a - (float)h;           // exact
+    const __bf16 m = (__bf16)r1;
+    t0[i] = h;
+    t1[i] = m;
+    t2[i] = (__bf16)(r1 - (float)m);         // the difference is exact
+  }
+}
 
 __device__ inline void split_bf16(const F32x8& v, bf16x8& hi, bf16x8& lo) {
 #pragma unroll
@@ -45,25 +71,32 @@ __device__ inline void split_bf16(const F32x8& v, bf16x8& hi, bf16x8& lo) {
 // than the latency of the loads for the next slice; with DEPTH = 3 a slice's loads have
 // three slice times to arrive.  MINWG: resident workgroups per CU the register budget
 // is planned for.
+// NP: 1 = operands as stored (A optionally in two terms), 3 = three terms per operand.
+// TKB: elements per K-slice and K-split group.
 template <int WM_, int WN_, int BM_, int BN_, int NG_, bool SPLIT_A_, int KS_ = 1, int DEPTH_ = 1,
-          int MINWG_ = 2>
+          int MINWG_ = 2, int NP_ = 1, int TKB_ = 64>
 struct TileCfgB {
   static constexpr int WM = WM_, WN = WN_, BM = BM_, BN = BN_, NG = NG_;
   static constexpr bool SPLIT_A = SPLIT_A_;
   static constexpr int DEPTH = DEPTH_, MINWG = MINWG_;
   static constexpr int KS = KS_;                // K-split groups of waves (see TileCfg)
-  static constexpr int TK = 64 * KS;            // bf16 elements per K-slice
-  static constexpr int NA = SPLIT_A ? 2 : 1;    // A tiles in LDS
+  static constexpr int NP = NP_;
+  static constexpr int TK = TKB_ * KS;          // bf16 elements per K-slice
+  static constexpr int NA = NP == 3 ? 3 : SPLIT_A ? 2 : 1;   // A tiles in LDS
+  static constexpr int NBP = NP == 3 ? 3 : 1;                // B tiles in LDS
+  static constexpr int NTERM = NA > NBP ? NA : NBP;          // products kept: t + u < NTERM
+  static constexpr int FSETS = NP == 3 ? 1 : 2;              // fragment register sets
   static constexpr int NWAVES = WM * WN * KS;
   static constexpr int NT = NWAVES * 64;
   static constexpr int TM = WM * BM * 32;
   static constexpr int TN = WN * BN * 32;
   static constexpr int BROWS = NG * TN;
-  static constexpr int LD = TK + 8;             // LDS row stride in elements (144 bytes)
+  static constexpr int LD = TK + 8;             // LDS row stride in elements (odd multiple of 16 bytes)
   static constexpr int CPR = TK / 8;            // 16-byte chunks per tile row
   static constexpr int A_CHUNKS = (TM * CPR) / NT;
   static constexpr int B_CHUNKS = (BROWS * CPR) / NT;
-  static constexpr int LDS_ELEMS = (NA * TM + BROWS) * LD;
+  static constexpr int LDS_ELEMS = (NA * TM + NBP * BROWS) * LD;
+  static_assert(SPLIT_A || NP == 1, "three-term operands are fp32 in memory");
   static_assert((TM * CPR) % NT == 0 && (BROWS * CPR) % NT == 0, "tile rows must divide evenly");
 };
 
@@ -74,7 +107,7 @@ __device__ inline int chunk_row_b(int s) { return (threadIdx.x + s * C::NT) / C:
 //   loadA(s, k): raw global load(s) for columns k..k+7 of the tile row of chunk s;
 //   finA(raw): -> bf16x8 (SPLIT_A false) or F32x8 (SPLIT_A true), applied when the
 //              slice is written to LDS;
-//   loadB(s, k): -> bf16x8.
+//   loadB(s, k): -> bf16x8, or Bf16x8x3 (NP = 3).
 template <class C, bool KTAIL, class LoadA, class LoadB, class FinA>
 __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB loadB, FinA finA,
                                          bf16_t* lds) {
@@ -89,12 +122,13 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
   constexpr int NC = C::TK / 16 / C::KS;            // k-groups of sixteen per slice and group
   constexpr int NB = C::NG * C::BN;
   constexpr int NFA = C::NA * C::BM;
+  constexpr int NFB = C::NBP * NB;
 
   constexpr int DP = C::DEPTH;
   // register set d holds the raw loads of the slices kt = d (mod DP); every index into
   // these arrays is a constant once the loops below are unrolled
   decltype(loadA(0, 0)) ra[DP][C::A_CHUNKS];
-  bf16x8 rb[DP][C::B_CHUNKS];
+  decltype(loadB(0, 0)) rb[DP][C::B_CHUNKS];
 
   auto fetch = [&](int d, int k0) {
 #pragma unroll
@@ -121,7 +155,13 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
       const int q = tid + s * C::NT;
       const int off = (q / C::CPR) * C::LD + (q % C::CPR) * 8;
       const bool dead = KTAIL && k0 + (q % C::CPR) * 8 >= K;
-      if constexpr (C::SPLIT_A) {
+      if constexpr (C::NA == 3) {
+        bf16x8 t0, t1, t2;
+        split_bf16_3(finA(ra[d][s]), t0, t1, t2);
+        *reinterpret_cast<bf16x8*>(&As[off]) = dead ? z : t0;
+        *reinterpret_cast<bf16x8*>(&As[C::TM * C::LD + off]) = dead ? z : t1;
+        *reinterpret_cast<bf16x8*>(&As[2 * C::TM * C::LD + off]) = dead ? z : t2;
+      } else if constexpr (C::SPLIT_A) {
         bf16x8 hi, lo;
         split_bf16(finA(ra[d][s]), hi, lo);
         *reinterpret_cast<bf16x8*>(&As[off]) = dead ? z : hi;
@@ -134,13 +174,16 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
     for (int s = 0; s < C::B_CHUNKS; ++s) {
       const int q = tid + s * C::NT;
       const bool dead = KTAIL && k0 + (q % C::CPR) * 8 >= K;
-      *reinterpret_cast<bf16x8*>(&Bs[(q / C::CPR) * C::LD + (q % C::CPR) * 8]) =
-          dead ? z : rb[d][s];
+#pragma unroll
+      for (int u = 0; u < C::NBP; ++u)
+        *reinterpret_cast<bf16x8*>(
+            &Bs[(u * C::BROWS + q / C::CPR) * C::LD + (q % C::CPR) * 8]) =
+            dead ? z : operand_term(rb[d][s], u);
     }
   };
   const int a_off = ((wm * C::BM) * 32 + li) * C::LD + lh * 8 + ks * NC * 16;
   const int b_off = ((wn * C::BN) * 32 + li) * C::LD + lh * 8 + ks * NC * 16;
-  auto read_frags = [&](int c, bf16x8 (&fa)[NFA], bf16x8 (&fb)[NB]) {
+  auto read_frags = [&](int c, bf16x8 (&fa)[NFA], bf16x8 (&fb)[NFB]) {
 #pragma unroll
     for (int t = 0; t < C::NA; ++t)
 #pragma unroll
@@ -148,23 +191,29 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
         fa[t * C::BM + a] = *reinterpret_cast<const bf16x8*>(
             &As[t * C::TM * C::LD + a_off + a * 32 * C::LD + c * 16]);
 #pragma unroll
-    for (int g = 0; g < C::NG; ++g)
-#pragma unroll
-      for (int b = 0; b < C::BN; ++b)
-        fb[g * C::BN + b] = *reinterpret_cast<const bf16x8*>(
-            &Bs[b_off + (g * C::TN + b * 32) * C::LD + c * 16]);
-  };
-  auto mma = [&](const bf16x8 (&fa)[NFA], const bf16x8 (&fb)[NB]) {
-#pragma unroll
-    for (int t = 0; t < C::NA; ++t)
+    for (int u = 0; u < C::NBP; ++u)
 #pragma unroll
       for (int g = 0; g < C::NG; ++g)
 #pragma unroll
         for (int b = 0; b < C::BN; ++b)
+          fb[u * NB + g * C::BN + b] = *reinterpret_cast<const bf16x8*>(
+              &Bs[u * C::BROWS * C::LD + b_off + (g * C::TN + b * 32) * C::LD + c * 16]);
+  };
+  auto mma = [&](const bf16x8 (&fa)[NFA], const bf16x8 (&fb)[NFB]) {
 #pragma unroll
-          for (int a = 0; a < C::BM; ++a)
-            acc.v[g][a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                fa[t * C::BM + a], fb[g * C::BN + b], acc.v[g][a][b], 0, 0, 0);
+    for (int t = 0; t < C::NA; ++t)
+#pragma unroll
+      for (int u = 0; u < C::NBP; ++u) {
+        if (t + u >= C::NTERM) continue;
+#pragma unroll
+        for (int g = 0; g < C::NG; ++g)
+#pragma unroll
+          for (int b = 0; b < C::BN; ++b)
+#pragma unroll
+            for (int a = 0; a < C::BM; ++a)
+              acc.v[g][a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                  fa[t * C::BM + a], fb[u * NB + g * C::BN + b], acc.v[g][a][b], 0, 0, 0);
+      }
   };
 
   const int nkt = (K + C::TK - 1) / C::TK;
@@ -181,9 +230,18 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
         // slice kt sits in LDS, so its register set is free for slice kt + DP
         if (kt + DP < nkt) fetch(d, (kt + DP) * C::TK);
         __builtin_amdgcn_sched_barrier(0);
-        bf16x8 fa[2][NFA];
-        bf16x8 fb[2][NB];
+        bf16x8 fa[C::FSETS][NFA];
+        bf16x8 fb[C::FSETS][NFB];
         __builtin_amdgcn_s_setprio(2);        // see gemm_core.h
+        if constexpr (C::FSETS == 1) {
+          // six MFMAs per operand pair: the reads of a k-group are a small share of its
+          // issue time, one fragment set is enough
+#pragma unroll
+          for (int c = 0; c < NC; ++c) {
+            read_frags(c, fa[0], fb[0]);
+            mma(fa[0], fb[0]);
+          }
+        } else {
         read_frags(0, fa[0], fb[0]);
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
@@ -192,7 +250,7 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
           if (c + 1 < NC) {
             // one LDS read of the next k-group, then a share of this group's MFMAs, in turn
             constexpr int NR = NFA + NB;
-            constexpr int NM = C::NA * C::BM * NB;
+            constexpr int NM = C::NA * C::BM * NB;   // (FSETS == 2: one B term)
             constexpr int MPR = NM / NR > 0 ? NM / NR : 1;
 #pragma unroll
             for (int i = 0; i < NR; ++i) {
@@ -201,6 +259,7 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
             }
           }
           __builtin_amdgcn_sched_barrier(0);
+        }
         }
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_setprio(0);

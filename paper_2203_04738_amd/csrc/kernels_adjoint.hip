@@ -205,7 +205,7 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void adj_step_kernel_bf16(AdjArgs 
   const long long m0 = rt * C::TM;
   const int n0 = ct * C::TN;
   const int tid = threadIdx.x;
-  const bf16_t* UT = (const bf16_t*)a.UT;
+  const bf16_t* UT = (const bf16_t*)(C::NP == 3 ? a.UT3 : a.UT);
   __shared__ AdjRow rowtab[C::TM];
   if (tid < C::TM) {
     long long r = m0 + tid;
@@ -239,12 +239,24 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void adj_step_kernel_bf16(AdjArgs 
     return KapW8{ldg4(krow[s] + k), ldg4(krow[s] + k + 4), ldg4(wrow[s] + kk),
                  ldg4(wrow[s] + kk + 4)};
   };
-  auto lb = [&](int s, int k) { return ldg8h(brow[s] + k); };
   auto fa = [](const KapW8& r) { return F32x8{r.k0 * r.w0, r.k1 * r.w1}; };
-  if (K % C::TK == 0)
-    gemm_nt_tile_bf16<C, false>(acc, K, la, lb, fa, lds);
-  else
-    gemm_nt_tile_bf16<C, true>(acc, K, la, lb, fa, lds);
+  if constexpr (C::NP == 3) {
+    const long long term = (long long)H * K;
+    auto lb = [&](int s, int k) {
+      return Bf16x8x3{{ldg8h(brow[s] + k), ldg8h(brow[s] + term + k),
+                       ldg8h(brow[s] + 2 * term + k)}};
+    };
+    if (K % C::TK == 0)
+      gemm_nt_tile_bf16<C, false>(acc, K, la, lb, fa, lds);
+    else
+      gemm_nt_tile_bf16<C, true>(acc, K, la, lb, fa, lds);
+  } else {
+    auto lb = [&](int s, int k) { return ldg8h(brow[s] + k); };
+    if (K % C::TK == 0)
+      gemm_nt_tile_bf16<C, false>(acc, K, la, lb, fa, lds);
+    else
+      gemm_nt_tile_bf16<C, true>(acc, K, la, lb, fa, lds);
+  }
 
   double nrm = 0.0;
   adj_tile_epilogue<C, MODE>(a, acc, rowtab, ldsf, m0, n0, R, nrm);
@@ -261,6 +273,7 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void adj_step_kernel_bf16(AdjArgs 
 // ---------------------------------------------------------------------------
 typedef TileCfg<2, 2, 2, 2, 1> DxCfg;            // 128 x 128 tile
 typedef TileCfgB<2, 2, 2, 2, 1, true> DxCfgB;
+typedef TileCfgB<2, 2, 2, 2, 1, true, 1, 1, 2, 3, 32> DxCfgS;
 
 // Stores one accumulator tile of a plain GEMM: out[m, n], leading dimension N.
 template <class C>
@@ -328,10 +341,10 @@ __global__ __launch_bounds__(DxCfg::NT) void input_grad_kernel(
   store_tile<C>(acc, dx, m0, n0, R, D);
 }
 
-__global__ __launch_bounds__(DxCfgB::NT) void input_grad_kernel_bf16(
+template <class C>
+__global__ __launch_bounds__(C::NT) void input_grad_kernel_bf16(
     const float* __restrict__ kap0, const float* __restrict__ w, const bf16_t* __restrict__ WT,
     float* __restrict__ dx, long long R, int B, int H, int D) {
-  typedef DxCfgB C;
   __shared__ __attribute__((aligned(16))) bf16_t lds[C::LDS_ELEMS];
   const int K = 3 * H;
   long long rt;
@@ -363,12 +376,24 @@ __global__ __launch_bounds__(DxCfgB::NT) void input_grad_kernel_bf16(
     return KapW8{ldg4(krow[s] + ks), ldg4(krow[s] + ks + 4), ldg4(wrow[s] + kk),
                  ldg4(wrow[s] + kk + 4)};
   };
-  auto lb = [&](int s, int k) { return ldg8h(brow[s] + k); };
   auto fa = [](const KapW8& r) { return F32x8{r.k0 * r.w0, r.k1 * r.w1}; };
-  if (K % C::TK == 0)
-    gemm_nt_tile_bf16<C, false>(acc, K, la, lb, fa, lds);
-  else
-    gemm_nt_tile_bf16<C, true>(acc, K, la, lb, fa, lds);
+  if constexpr (C::NP == 3) {
+    const long long term = (long long)D * K;
+    auto lb = [&](int s, int k) {
+      return Bf16x8x3{{ldg8h(brow[s] + k), ldg8h(brow[s] + term + k),
+                       ldg8h(brow[s] + 2 * term + k)}};
+    };
+    if (K % C::TK == 0)
+      gemm_nt_tile_bf16<C, false>(acc, K, la, lb, fa, lds);
+    else
+      gemm_nt_tile_bf16<C, true>(acc, K, la, lb, fa, lds);
+  } else {
+    auto lb = [&](int s, int k) { return ldg8h(brow[s] + k); };
+    if (K % C::TK == 0)
+      gemm_nt_tile_bf16<C, false>(acc, K, la, lb, fa, lds);
+    else
+      gemm_nt_tile_bf16<C, true>(acc, K, la, lb, fa, lds);
+  }
   store_tile<C>(acc, dx, m0, n0, R, D);
 }
 
@@ -376,10 +401,15 @@ hipError_t launch_input_grads(const float* kap0, const float* w, const void* WT,
                               int B, int D, int H, int bf16, hipStream_t s) {
   const long long R = (long long)T * B;
   prof_begin(6, s);
-  if (bf16) {
+  if (bf16 == 2) {
+    typedef DxCfgS C;
+    dim3 grid((unsigned)xcd_grid((R + C::TM - 1) / C::TM, (D + C::TN - 1) / C::TN));
+    hipLaunchKernelGGL(input_grad_kernel_bf16<C>, grid, dim3(C::NT), 0, s, kap0, w,
+                       (const bf16_t*)WT, dx, R, B, H, D);
+  } else if (bf16) {
     typedef DxCfgB C;
     dim3 grid((unsigned)xcd_grid((R + C::TM - 1) / C::TM, (D + C::TN - 1) / C::TN));
-    hipLaunchKernelGGL(input_grad_kernel_bf16, grid, dim3(C::NT), 0, s, kap0, w,
+    hipLaunchKernelGGL(input_grad_kernel_bf16<C>, grid, dim3(C::NT), 0, s, kap0, w,
                        (const bf16_t*)WT, dx, R, B, H, D);
   } else {
     typedef DxCfg C;
@@ -388,7 +418,7 @@ hipError_t launch_input_grads(const float* kap0, const float* w, const void* WT,
                        R, B, H, D);
   }
   prof_end(6, 2.0 * (double)R * 3 * H * D,
-           4.0 * (double)R * (4.0 * H + D) + (bf16 ? 2.0 : 4.0) * 3.0 * H * D, s);
+           4.0 * (double)R * (4.0 * H + D) + (bf16 == 1 ? 2.0 : 4.0) * 3.0 * H * D, s);
   return hipGetLastError();
 }
 
@@ -471,14 +501,26 @@ typedef TileCfg<1, 1, 1, 1, 1, 128, 1, 4> AdjSmall;  //  32 x 32, 4 waves splitt
 typedef TileCfgB<4, 2, 1, 2, 1, true, 1, 3, 1> AdjBigB;
 typedef TileCfgB<2, 2, 1, 1, 1, true> AdjMidB;
 typedef TileCfgB<1, 1, 1, 1, 1, true, 4> AdjSmallB;
+// three-term operands (K-slices of 32)
+typedef TileCfgB<2, 2, 2, 2, 1, true, 1, 1, 2, 3, 32> AdjBigS;
+typedef TileCfgB<2, 2, 1, 1, 1, true, 1, 1, 2, 3, 32> AdjMidS;
+typedef TileCfgB<1, 1, 1, 1, 1, true, 4, 1, 2, 3, 32> AdjSmallS;
 
-template <class C, class CB>
+template <class C, class CB, class CS>
 static void launch_adj_cfg(const AdjArgs& a, hipStream_t s) {
   const long long R = (long long)a.nk * a.B;
   dim3 grid((unsigned)xcd_grid((R + C::TM - 1) / C::TM, (a.H + C::TN - 1) / C::TN));
-  dim3 block(a.bf16 ? CB::NT : C::NT);
+  dim3 block(a.bf16 == 2 ? CS::NT : a.bf16 ? CB::NT : C::NT);
   static_assert(C::TM == CB::TM && C::TN == CB::TN, "tile shapes must agree");
-  if (a.bf16) {
+  static_assert(C::TM == CS::TM && C::TN == CS::TN, "tile shapes must agree");
+  if (a.bf16 == 2) {
+    if (a.mode == STEP_RELAX)
+      hipLaunchKernelGGL((adj_step_kernel_bf16<CS, STEP_RELAX>), grid, block, 0, s, a);
+    else if (a.mode == STEP_RESID)
+      hipLaunchKernelGGL((adj_step_kernel_bf16<CS, STEP_RESID>), grid, block, 0, s, a);
+    else
+      hipLaunchKernelGGL((adj_step_kernel_bf16<CS, STEP_RHS>), grid, block, 0, s, a);
+  } else if (a.bf16) {
     if (a.mode == STEP_RELAX)
       hipLaunchKernelGGL((adj_step_kernel_bf16<CB, STEP_RELAX>), grid, block, 0, s, a);
     else if (a.mode == STEP_RESID)
@@ -506,7 +548,7 @@ template <int CT, int MODE>
 static void launch_adj_skinny_mode(const AdjArgs& a, dim3 grid, hipStream_t s) {
   const int rb = adj_sk_rows((long long)a.nk * a.B);
   const dim3 block(sk_geom(rb, 3 * a.H).nt);
-  if (a.bf16)
+  if (a.bf16 == 1)
     hipLaunchKernelGGL((adj_skinny_kernel<CT, MODE, bf16_t>), grid, block, 0, s, a, rb);
   else
     hipLaunchKernelGGL((adj_skinny_kernel<CT, MODE, float>), grid, block, 0, s, a, rb);
@@ -541,12 +583,12 @@ hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s) {
       launch_adj_skinny<2>(a, grid, s);
     else
       launch_adj_skinny<1>(a, grid, s);
-  } else if (tiles(AdjBig::TM, AdjBig::TN) >= (a.bf16 ? 256 : 384))
-    launch_adj_cfg<AdjBig, AdjBigB>(a, s);
+  } else if (tiles(AdjBig::TM, AdjBig::TN) >= (a.bf16 == 1 ? 256 : 384))
+    launch_adj_cfg<AdjBig, AdjBigB, AdjBigS>(a, s);
   else if (R > 32 && tiles(AdjMid::TM, AdjMid::TN) >= 256)
-    launch_adj_cfg<AdjMid, AdjMidB>(a, s);
+    launch_adj_cfg<AdjMid, AdjMidB, AdjMidS>(a, s);
   else
-    launch_adj_cfg<AdjSmall, AdjSmallB>(a, s);
+    launch_adj_cfg<AdjSmall, AdjSmallB, AdjSmallS>(a, s);
   prof_end(kind, 6.0 * (double)R * a.H * a.H, 28.0 * (double)R * a.H, s);
   return hipGetLastError();
 }
@@ -943,6 +985,164 @@ __global__ __launch_bounds__(256, 2) void grad_gemm_bf16_kernel(GradArgs a) {
       }
 }
 
+// The same partial products for fp32 operands carried as three bf16 terms each (see
+// gemm_core_bf16.h): S and the second operand (h or x) are split on their way to LDS and six
+// of the nine term products are kept.  K-slices of 32 rows; waves 0-1 stage S (the product
+// kappa * w, transposed in registers as above), waves 2-3 stage the second operand.
+constexpr int HS_TK = 32;
+constexpr int HS_LD = HS_TK + 8;
+__global__ __launch_bounds__(256, 2) void grad_gemm_x3_kernel(GradArgs a) {
+  __shared__ __attribute__((aligned(16))) bf16_t As[3][GT * HS_LD];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[3][GT * HS_LD];
+  const int H = a.H, N = a.N, M = 3 * a.H;
+  const int tiles = a.mtiles * a.ntiles;
+  int tile, z;
+  if (a.splits % NXCD == 0) {
+    const int j = blockIdx.x / NXCD;
+    tile = j % tiles;
+    z = (j / tiles) * NXCD + blockIdx.x % NXCD;
+  } else {
+    tile = blockIdx.x % tiles;
+    z = blockIdx.x / tiles;
+  }
+  const int nt = tile / a.mtiles;
+  const int m0 = (tile % a.mtiles) * GT, n0 = nt * GT;
+  const long long kbeg = (long long)z * a.Kper;
+  long long kend = kbeg + a.Kper;
+  if (kend > a.Ktot) kend = a.Ktot;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1, li = lane & 31, lh = lane >> 5;
+  const long long rowoff = a.B;           // kap0 / w rows are one time point ahead
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // staging block of a thread: columns c4*4..+3 of its operand, rows k8*8..+7 of the slice
+  const bool is_a = tid < 128;             // uniform per wave
+  const int c4 = tid & 31, k8 = (tid >> 5) & 3;
+  const int col = (is_a ? m0 : n0) + c4 * 4;
+  const bool c_ok = col < (is_a ? M : N);
+  const int cc = c_ok ? col : 0;
+  const int gate = cc / H, jcol = cc - gate * H;            // (A threads)
+  const int src = gate == 2 ? a.third_off + jcol : cc;
+  bf16_t* dst = (is_a ? &As[0][0] : &Bs[0][0]) + (c4 * 4) * HS_LD + k8 * 8;
+
+  // first operand row k of this thread: a coefficient row (A) or a row of h / x (B)
+  const float* base0 = is_a ? a.kap0 + rowoff * (5LL * H) + src : (const float*)a.Bm + cc;
+  const long long stride0 = is_a ? 5LL * H : (long long)N;
+  floatx4 r0[8], r1[8];
+  float colsum[4] = {0.f, 0.f, 0.f, 0.f};
+  auto fetch = [&](long long k0) {
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      long long k = k0 + k8 * 8 + r;
+      if (k >= kend) k = kend - 1;
+      r0[r] = ldg4(base0 + k * stride0);
+      floatx4 t = zero4();
+      if (is_a) t = ldg4(a.w + (k + rowoff) * H + jcol);
+      r1[r] = t;
+    }
+  };
+  auto stash = [&](long long k0) {
+    floatx4 p[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const bool ok = c_ok && k0 + k8 * 8 + r < kend;
+      p[r] = ok ? (is_a ? r0[r] * r1[r] : r0[r]) : zero4();
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      F32x8 v;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        v.lo4[r] = p[r][e];
+        v.hi4[r] = p[4 + r][e];
+        colsum[e] += p[r][e] + p[4 + r][e];
+      }
+      bf16x8 t0, t1, t2;
+      split_bf16_3(v, t0, t1, t2);
+      *reinterpret_cast<bf16x8*>(dst + e * HS_LD) = t0;
+      *reinterpret_cast<bf16x8*>(dst + GT * HS_LD + e * HS_LD) = t1;
+      *reinterpret_cast<bf16x8*>(dst + 2 * GT * HS_LD + e * HS_LD) = t2;
+    }
+  };
+
+  if (kbeg < kend) {
+    fetch(kbeg);
+    stash(kbeg);
+    __syncthreads();
+    for (long long k0 = kbeg; k0 < kend; k0 += HS_TK) {
+      const bool more = k0 + HS_TK < kend;
+      if (more) fetch(k0 + HS_TK);
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+      for (int c = 0; c < HS_TK / 16; ++c) {
+        bf16x8 fa[3][2], fb[3][2];
+#pragma unroll
+        for (int t = 0; t < 3; ++t)
+#pragma unroll
+          for (int i = 0; i < 2; ++i) {
+            fa[t][i] = *reinterpret_cast<const bf16x8*>(
+                &As[t][(wm * 64 + i * 32 + li) * HS_LD + c * 16 + lh * 8]);
+            fb[t][i] = *reinterpret_cast<const bf16x8*>(
+                &Bs[t][(wn * 64 + i * 32 + li) * HS_LD + c * 16 + lh * 8]);
+          }
+#pragma unroll
+        for (int t = 0; t < 3; ++t)
+#pragma unroll
+          for (int u = 0; u < 3; ++u) {
+            if (t + u > 2) continue;
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+              for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[t][i], fb[u][j], acc[i][j],
+                                                                    0, 0, 0);
+          }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_setprio(0);
+      __syncthreads();
+      if (more) {
+        stash(k0 + HS_TK);
+        __syncthreads();
+      }
+    }
+  }
+  // column sums of S: the four row groups of a column meet in LDS (the A tiles are free now)
+  float* red = reinterpret_cast<float*>(&As[0][0]);      // [4][GT] floats
+  __syncthreads();
+  if (is_a) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) red[k8 * GT + c4 * 4 + e] = colsum[e];
+  }
+  __syncthreads();
+  if (tid < GT && m0 + tid < M) {
+    float sum = 0.f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) sum += red[q * GT + tid];
+    // every column tile holds the same sums: the first one reports them
+    a.bpart[((long long)z * a.ntiles + nt) * M + m0 + tid] = nt == 0 ? sum : 0.f;
+  }
+  float* out = a.part + (long long)z * M * N;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int mm = m0 + wm * 64 + i * 32 + 8 * (e / 4) + 4 * lh + (e & 3);
+        const int nn = n0 + wn * 64 + j * 32 + li;
+        if (mm < M && nn < N) out[(long long)mm * N + nn] = acc[i][j][e];
+      }
+}
+
 __global__ void reduce_partials_kernel(const float* __restrict__ part, float* __restrict__ out,
                                        long long n, int splits) {
   long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -1031,7 +1231,7 @@ hipError_t launch_param_grads(const float* kap0, const float* w, const float* h,
     a.H = H;
     const int splits = grad_splits(Ktot, M, a.N);
     long long per = (Ktot + splits - 1) / splits;
-    const int slice = bf16 ? HB_TK : GTK;
+    const int slice = bf16 == 1 ? HB_TK : GTK;      // (both multiples of the 32 of bf16 = 2)
     a.Kper = (per + slice - 1) / slice * slice;
     a.mtiles = (M + GT - 1) / GT;
     a.ntiles = (a.N + GT - 1) / GT;
@@ -1040,7 +1240,9 @@ hipError_t launch_param_grads(const float* kap0, const float* w, const float* h,
     nbpart[which] = splits * a.ntiles;
     if (which == 0) bpart[1] = bpart[0] + (size_t)nbpart[0] * M;
     dim3 grid((unsigned)((long long)a.mtiles * a.ntiles * splits));
-    if (bf16 && which == 1)
+    if (bf16 == 2)
+      hipLaunchKernelGGL(grad_gemm_x3_kernel, grid, dim3(256), 0, s, a);
+    else if (bf16 && which == 1)
       hipLaunchKernelGGL(grad_gemm_bf16_kernel<true>, grid, dim3(256), 0, s, a);
     else if (bf16)
       hipLaunchKernelGGL(grad_gemm_bf16_kernel<false>, grid, dim3(256), 0, s, a);

@@ -2,6 +2,8 @@
 // Phi_gamma(x, h) (Eq. 1 gates + Eq. 16 / Eq. 3 update) with the MGRIT epilogues
 // (relaxation update of Alg. 1, residual + restriction of Alg. 2 lines 2-3, the
 // right-hand side of Eq. 11, and the adjoint coefficient vectors).
+#include <type_traits>
+
 #include "common.h"
 #include "gemm_core.h"
 #include "gemm_core_bf16.h"
@@ -67,20 +69,24 @@ __global__ __launch_bounds__(ProjCfg::NT) void projection_kernel(
     }
 }
 
-// bf16 inputs and weights, fp32 accumulation and output
+// bf16 inputs and weights (ProjCfgB), or fp32 inputs with the weights given as their three
+// bf16 terms W3[3][N,K] (ProjCfgS); fp32 accumulation and output
 typedef TileCfgB<2, 2, 2, 2, 1, false> ProjCfgB;
+typedef TileCfgB<2, 2, 2, 2, 1, true, 1, 1, 2, 3, 32> ProjCfgS;
 
-__global__ __launch_bounds__(ProjCfgB::NT) void projection_kernel_bf16(
-    const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, const float* __restrict__ bias,
+template <class C>
+__global__ __launch_bounds__(C::NT) void projection_kernel_bf16(
+    const void* __restrict__ Xv, const bf16_t* __restrict__ W, const float* __restrict__ bias,
     float* __restrict__ P, long long M, int N, int K) {
-  typedef ProjCfgB C;
+  typedef typename std::conditional<C::SPLIT_A, float, bf16_t>::type AT;
+  const AT* X = (const AT*)Xv;
   __shared__ __attribute__((aligned(16))) bf16_t lds[C::LDS_ELEMS];
   long long rt;
   int ct;
   if (!xcd_tile(blockIdx.x, (M + C::TM - 1) / C::TM, (N + C::TN - 1) / C::TN, rt, ct)) return;
   const long long m0 = rt * C::TM;
   const int n0 = ct * C::TN;
-  const bf16_t* arow[C::A_CHUNKS];
+  const AT* arow[C::A_CHUNKS];
   const bf16_t* brow[C::B_CHUNKS];
 #pragma unroll
   for (int s = 0; s < C::A_CHUNKS; ++s) {
@@ -94,13 +100,27 @@ __global__ __launch_bounds__(ProjCfgB::NT) void projection_kernel_bf16(
   }
   Acc<C> acc;
   acc.zero();
-  auto la = [&](int s, int k) { return ldg8h(arow[s] + k); };
-  auto lb = [&](int s, int k) { return ldg8h(brow[s] + k); };
-  auto fa = [](const bf16x8& v) { return v; };
-  if (K % C::TK == 0)
-    gemm_nt_tile_bf16<C, false>(acc, K, la, lb, fa, lds);
-  else
-    gemm_nt_tile_bf16<C, true>(acc, K, la, lb, fa, lds);
+  if constexpr (C::NP == 3) {
+    const long long term = (long long)N * K;
+    auto la = [&](int s, int k) { return F32x8{ldg4(arow[s] + k), ldg4(arow[s] + k + 4)}; };
+    auto lb = [&](int s, int k) {
+      return Bf16x8x3{{ldg8h(brow[s] + k), ldg8h(brow[s] + term + k),
+                       ldg8h(brow[s] + 2 * term + k)}};
+    };
+    auto fa = [](const F32x8& v) { return v; };
+    if (K % C::TK == 0)
+      gemm_nt_tile_bf16<C, false>(acc, K, la, lb, fa, lds);
+    else
+      gemm_nt_tile_bf16<C, true>(acc, K, la, lb, fa, lds);
+  } else {
+    auto la = [&](int s, int k) { return ldg8h(arow[s] + k); };
+    auto lb = [&](int s, int k) { return ldg8h(brow[s] + k); };
+    auto fa = [](const bf16x8& v) { return v; };
+    if (K % C::TK == 0)
+      gemm_nt_tile_bf16<C, false>(acc, K, la, lb, fa, lds);
+    else
+      gemm_nt_tile_bf16<C, true>(acc, K, la, lb, fa, lds);
+  }
 #pragma unroll
   for (int a = 0; a < C::BM; ++a)
 #pragma unroll
@@ -122,18 +142,23 @@ __global__ __launch_bounds__(ProjCfgB::NT) void projection_kernel_bf16(
 hipError_t launch_projection(const void* X, const void* W, const float* bias, float* P,
                              long long M, int N, int K, int bf16, hipStream_t s) {
   prof_begin(2, s);
-  if (bf16) {
+  if (bf16 == 2) {
+    typedef ProjCfgS C;
+    dim3 grid((unsigned)xcd_grid((M + C::TM - 1) / C::TM, (N + C::TN - 1) / C::TN));
+    hipLaunchKernelGGL(projection_kernel_bf16<C>, grid, dim3(C::NT), 0, s, X, (const bf16_t*)W,
+                       bias, P, M, N, K);
+  } else if (bf16) {
     typedef ProjCfgB C;
     dim3 grid((unsigned)xcd_grid((M + C::TM - 1) / C::TM, (N + C::TN - 1) / C::TN));
-    hipLaunchKernelGGL(projection_kernel_bf16, grid, dim3(C::NT), 0, s, (const bf16_t*)X,
-                       (const bf16_t*)W, bias, P, M, N, K);
+    hipLaunchKernelGGL(projection_kernel_bf16<C>, grid, dim3(C::NT), 0, s, X, (const bf16_t*)W,
+                       bias, P, M, N, K);
   } else {
     typedef ProjCfg C;
     dim3 grid((unsigned)xcd_grid((M + C::TM - 1) / C::TM, (N + C::TN - 1) / C::TN));
     hipLaunchKernelGGL(projection_kernel, grid, dim3(C::NT), 0, s, (const float*)X,
                        (const float*)W, bias, P, M, N, K);
   }
-  const double esz = bf16 ? 2.0 : 4.0;
+  const double esz = bf16 == 1 ? 2.0 : 4.0;
   prof_end(2, 2.0 * (double)M * N * K, esz * ((double)M * K + (double)N * K) + 4.0 * (double)M * N,
            s);
   return hipGetLastError();
@@ -426,7 +451,8 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel(PhiArgs a) {
 }
 
 // bf16 weights: the fp32 state rows are split into hi + lo bf16 tiles (see
-// gemm_core_bf16.h); gates, update and outputs stay fp32.
+// gemm_core_bf16.h); gates, update and outputs stay fp32.  With a three-term
+// configuration the weights are fp32 values held as three bf16 arrays.
 template <class C, int MODE>
 __global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel_bf16(PhiArgs a) {
   constexpr int LDSF =
@@ -441,7 +467,7 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel_bf16(PhiArgs 
   const long long m0 = rt * C::TM;
   const int n0 = ct * C::TN;
   const int tid = threadIdx.x;
-  const bf16_t* U = (const bf16_t*)a.U;
+  const bf16_t* U = (const bf16_t*)(C::NP == 3 ? a.U3 : a.U);
   __shared__ PhiRow rowtab[C::TM];
   if (tid < C::TM) {
     long long r = m0 + tid;
@@ -471,12 +497,24 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel_bf16(PhiArgs 
   Acc<C> acc;
   acc.zero();
   auto la = [&](int s, int k) { return F32x8{ldg4(arow[s] + k), ldg4(arow[s] + k + 4)}; };
-  auto lb = [&](int s, int k) { return ldg8h(brow[s] + k); };
   auto fa = [](const F32x8& v) { return v; };
-  if (H % C::TK == 0)
-    gemm_nt_tile_bf16<C, false>(acc, H, la, lb, fa, lds);
-  else
-    gemm_nt_tile_bf16<C, true>(acc, H, la, lb, fa, lds);
+  if constexpr (C::NP == 3) {
+    const long long term = 3LL * H * H;
+    auto lb = [&](int s, int k) {
+      return Bf16x8x3{{ldg8h(brow[s] + k), ldg8h(brow[s] + term + k),
+                       ldg8h(brow[s] + 2 * term + k)}};
+    };
+    if (H % C::TK == 0)
+      gemm_nt_tile_bf16<C, false>(acc, H, la, lb, fa, lds);
+    else
+      gemm_nt_tile_bf16<C, true>(acc, H, la, lb, fa, lds);
+  } else {
+    auto lb = [&](int s, int k) { return ldg8h(brow[s] + k); };
+    if (H % C::TK == 0)
+      gemm_nt_tile_bf16<C, false>(acc, H, la, lb, fa, lds);
+    else
+      gemm_nt_tile_bf16<C, true>(acc, H, la, lb, fa, lds);
+  }
 
   double nrm = 0.0;
   phi_tile_epilogue<C, MODE>(a, acc, rowtab, ldsf, m0, n0, R, nrm);
@@ -579,6 +617,10 @@ typedef TileCfg<1, 1, 1, 1, 3, 128, 1, 4> PhiSmall;
 typedef TileCfgB<2, 2, 2, 1, 3, true> PhiBigB;
 typedef TileCfgB<2, 2, 1, 1, 3, true> PhiMidB;
 typedef TileCfgB<1, 1, 1, 1, 3, true, 4> PhiSmallB;
+// three-term operands: K-slices of 32 keep two workgroups' tiles in a CU's LDS
+typedef TileCfgB<2, 2, 2, 1, 3, true, 1, 1, 2, 3, 32> PhiBigS;
+typedef TileCfgB<2, 2, 1, 1, 3, true, 1, 1, 2, 3, 32> PhiMidS;
+typedef TileCfgB<1, 1, 1, 1, 3, true, 4, 1, 2, 3, 32> PhiSmallS;
 
 #define MG_LAUNCH_BY_MODE(KERNEL, ...)                                                   \
   switch (a.mode) {                                                                      \
@@ -598,10 +640,14 @@ typedef TileCfgB<1, 1, 1, 1, 3, true, 4> PhiSmallB;
       hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_KAPPA>), grid, block, 0, s, a);       \
   }
 
-template <class C, class CB>
+template <class C, class CB, class CS>
 static void launch_phi_cfg(const PhiArgs& a, hipStream_t s) {
   const long long R = (long long)a.nk * a.B;
-  if (a.bf16) {
+  if (a.bf16 == 2) {
+    dim3 grid((unsigned)xcd_grid((R + CS::TM - 1) / CS::TM, (a.H + CS::TN - 1) / CS::TN));
+    dim3 block(CS::NT);
+    MG_LAUNCH_BY_MODE(phi_step_kernel_bf16, CS)
+  } else if (a.bf16) {
     dim3 grid((unsigned)xcd_grid((R + CB::TM - 1) / CB::TM, (a.H + CB::TN - 1) / CB::TN));
     dim3 block(CB::NT);
     MG_LAUNCH_BY_MODE(phi_step_kernel_bf16, CB)
@@ -620,7 +666,7 @@ template <int CT, int MODE>
 static void launch_phi_skinny_mode(const PhiArgs& a, dim3 grid, hipStream_t s) {
   const int rb = phi_sk_rows((long long)a.nk * a.B);
   const dim3 block(sk_geom(rb, a.H).nt);
-  if (a.bf16)
+  if (a.bf16 == 1)
     hipLaunchKernelGGL((phi_skinny_kernel<CT, MODE, bf16_t>), grid, block, 0, s, a, rb);
   else
     hipLaunchKernelGGL((phi_skinny_kernel<CT, MODE, float>), grid, block, 0, s, a, rb);
@@ -655,11 +701,11 @@ hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s) {
     else
       launch_phi_skinny<1>(a, grid, s);
   } else if (tiles(PhiBig::TM, PhiBig::TN) >= 384)
-    launch_phi_cfg<PhiBig, PhiBigB>(a, s);
+    launch_phi_cfg<PhiBig, PhiBigB, PhiBigS>(a, s);
   else if (R > 32 && tiles(PhiMid::TM, PhiMid::TN) >= 128)
-    launch_phi_cfg<PhiMid, PhiMidB>(a, s);
+    launch_phi_cfg<PhiMid, PhiMidB, PhiMidS>(a, s);
   else
-    launch_phi_cfg<PhiSmall, PhiSmallB>(a, s);
+    launch_phi_cfg<PhiSmall, PhiSmallB, PhiSmallS>(a, s);
   prof_end(kind, 6.0 * (double)R * a.H * a.H, 20.0 * (double)R * a.H, s);
   return hipGetLastError();
 }

@@ -40,6 +40,36 @@ hipError_t launch_copy_points(float* dst, const float* src, Idx d, Idx s, int nk
   return hipGetLastError();
 }
 
+// Three-term bf16 form of an fp32 array (weights of the MGRIT_F32_BF16X3 path).
+__global__ void split3_kernel(const float* __restrict__ src, unsigned short* __restrict__ dst,
+                              long long n4) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n4) return;
+  const floatx4 v = reinterpret_cast<const floatx4*>(src)[i];
+  ushort4 t[3];
+  unsigned short* tp = reinterpret_cast<unsigned short*>(t);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const __bf16 h = (__bf16)v[e];
+    const float r1 = v[e] - (float)h;
+    const __bf16 m = (__bf16)r1;
+    const __bf16 l = (__bf16)(r1 - (float)m);
+    tp[e] = __builtin_bit_cast(unsigned short, h);
+    tp[4 + e] = __builtin_bit_cast(unsigned short, m);
+    tp[8 + e] = __builtin_bit_cast(unsigned short, l);
+  }
+#pragma unroll
+  for (int k = 0; k < 3; ++k) reinterpret_cast<ushort4*>(dst + k * n4 * 4)[i] = t[k];
+}
+
+hipError_t launch_split3(const float* src, void* dst, long long n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  const long long n4 = n / 4;
+  hipLaunchKernelGGL(split3_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, src,
+                     (unsigned short*)dst, n4);
+  return hipGetLastError();
+}
+
 __global__ void sqrt_to_float_kernel(const double* acc, float* out, int n) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) out[i] = (float)sqrt(acc[i]);

@@ -31,7 +31,7 @@ class GpuRun:
         H = d["U"].shape[1]
         self.T, self.B, self.D, self.H = T, B, D, H
         self.kw = dict(cf=cf, levels=levels, fine_relax=fine_relax, propagator=propagator,
-                       dtype=0 if dtype == "fp32" else 1)
+                       dtype={"fp32": 0, "bf16": 1, "fp32x3": 2}[dtype])
         cfg = self.cfg(iters=64)
         self.ws = torch.empty(mg.mgrit_gru_workspace_bytes(cfg), dtype=torch.uint8, device=DEV)
 

@@ -30,13 +30,20 @@ def _P(d):
     return d["W"], d["U"], d["b_i"], d["b_h"]
 
 
-@pytest.mark.parametrize("name,window", [("C2", 1024), ("C3", 128), ("C4", 128), ("C5", 256)])
-def test_full_size_forward_window_and_serial_prefix(gh, name, window):
+def _dtype(wl, form):
+    """Operand form of the run: the workload's own, or fp32 values contracted as three bf16
+    terms ("fp32x3": same inputs and the same bar as fp32)."""
+    return form or wl.dtype
+
+
+@pytest.mark.parametrize("name,window,form", [("C2", 1024, None), ("C3", 128, None), ("C4", 128, None),
+                                              ("C5", 256, None), ("C3", 128, "fp32x3")])
+def test_full_size_forward_window_and_serial_prefix(gh, name, window, form):
     wl = WORKLOADS[name]
     d = make_inputs(wl)
     tol = 1e-5 if wl.dtype == "fp32" else 2e-2
     iters = min(wl.fwd_iters, 2)
-    run = gh.GpuRun(d, cf=wl.cf, levels=wl.levels, dtype=wl.dtype)
+    run = gh.GpuRun(d, cf=wl.cf, levels=wl.levels, dtype=_dtype(wl, form))
     its, res = run.forward_iterates(iters, per_call=iters)        # one call, as bench.py does
     got = its[-1][:window + 1]
     xs = d["x"][:window]
@@ -55,15 +62,16 @@ def test_full_size_forward_window_and_serial_prefix(gh, name, window):
     assert gh.rel_err(its[-1][:front + 1], sgot[:front + 1]) <= 10 * tol
 
 
-@pytest.mark.parametrize("name,window", [("C3", 128), ("C4", 128), ("C5", 256)])
-def test_full_size_backward_window(gh, name, window):
+@pytest.mark.parametrize("name,window,form", [("C3", 128, None), ("C4", 128, None), ("C5", 256, None),
+                                              ("C3", 128, "fp32x3")])
+def test_full_size_backward_window(gh, name, window, form):
     wl = WORKLOADS[name]
     d = make_inputs(wl)
     tol = 1e-5 if wl.dtype == "fp32" else 2e-2
     iters = wl.bwd_iters
     rng = np.random.default_rng(99)
     h = np.tanh(rng.standard_normal((wl.T + 1, wl.B, wl.H))).astype(np.float32)
-    run = gh.GpuRun(d, cf=wl.cf, levels=wl.levels, dtype=wl.dtype)
+    run = gh.GpuRun(d, cf=wl.cf, levels=wl.levels, dtype=_dtype(wl, form))
     wits, _, grads = run.backward_iterates(h, iters, per_call=iters)
     got = wits[-1][wl.T - window:]
     out = orc.mgrit_backward(*_P(d), d["x"][wl.T - window:], h[wl.T - window:], d["dL_dhT"],
@@ -73,8 +81,8 @@ def test_full_size_backward_window(gh, name, window):
         assert np.all(np.isfinite(g))
 
 
-@pytest.mark.parametrize("name", ["C3", "C4", "C5"])
-def test_full_size_gradients_and_input_gradients_on_a_sparse_adjoint(gh, name):
+@pytest.mark.parametrize("name,form", [("C3", None), ("C4", None), ("C5", None), ("C3", "fp32x3")])
+def test_full_size_gradients_and_input_gradients_on_a_sparse_adjoint(gh, name, form):
     """Gradient GEMMs, bias sums and the input-gradient GEMM at full size, element by
     element.  With zero cycles the entry point forms the gradients from the adjoint it is
     given; that adjoint (seeded) is non-zero on 96 time steps spread over the whole
@@ -92,7 +100,7 @@ def test_full_size_gradients_and_input_gradients_on_a_sparse_adjoint(gh, name):
     w = np.zeros((T + 1, B, H), dtype=np.float32)
     w[steps] = rng.standard_normal((len(steps), B, H)).astype(np.float32)
 
-    run = gh.GpuRun(d, cf=wl.cf, levels=wl.levels, dtype=wl.dtype)
+    run = gh.GpuRun(d, cf=wl.cf, levels=wl.levels, dtype=_dtype(wl, form))
     dev = gh.DEV
     hd, wd = run._dev(h), run._dev(w)
     src = torch.zeros(T + 1, B, H, device=dev)

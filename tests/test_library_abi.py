@@ -59,6 +59,11 @@ def test_workspace_size_and_validation_codes():
     assert _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, flags=8))[0] == -4
     assert _ws(MgritGruCfg(64, 2, 16, 30, cf=4, levels=2))[0] == -6
     assert _ws(MgritGruCfg(64, 2, 9, 32, cf=4, levels=2))[0] == -6
+    # fp32 values as three bf16 terms: widths in multiples of 8, a larger workspace (term arrays)
+    assert _ws(MgritGruCfg(64, 2, 16, 36, cf=4, levels=2, dtype=2))[0] == -6
+    rc2, n2 = _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, iters=3, dtype=2))
+    assert rc2 == 0 and n2 >= n + 18 * 32 * (2 * 32 + 16)
+    assert _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, dtype=3))[0] == -4
     assert mg.lib().mgrit_gru_workspace_bytes(None, None) == -1
 
 

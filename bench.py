@@ -50,6 +50,10 @@ def parse():
                          "on a synthetic classification task, MGRIT (2 forward / 1 backward cycles) "
                          "against serial propagation from the same start.  One JSON line each")
     ap.add_argument("--train-steps", type=int, default=300)
+    ap.add_argument("--operands", choices=["stored", "bf16x3"], default="stored",
+                    help="stored: the workload's own form (fp32 or bf16 MFMA).  bf16x3 (fp32 "
+                         "workloads): the tile kernels contract the fp32 operands as three bf16 "
+                         "terms each on the bf16 matrix pipe (same inputs, same parity bar)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-serial", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -281,6 +285,10 @@ def stack_main(args):
                        "frac_of_mfma_peak": step_flops / sec / 1e12 / peak},
         "serial_gpu": serial,
     }
+    if other_form:
+        other_form["mgrit_speedup_vs_serial"] = (serial["ms_per_step"] / other_form["ms_per_step"]
+                                                 if serial else None)
+        out["bf16x3_operands"] = other_form
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = stack_cpu_baseline(wl, L, fwd_iters, bwd_iters, fcf=bool(fine_relax))
     print(json.dumps(out))
@@ -504,12 +512,18 @@ def main():
     for k in ("x", "W", "U"):
         t[k] = t[k].to(in_dt)
     dtype_code = 0 if wl.dtype == "fp32" else 1
+    x3 = args.operands == "bf16x3"
+    if x3:
+        if wl.dtype != "fp32":
+            print("bench.py: --operands bf16x3 applies to fp32 workloads", file=sys.stderr)
+            sys.exit(2)
+        dtype_code = 2
 
     fine_relax = 1 if args.fine_relax == "FCF" else 0
 
-    def cfg(iters, flags=0, levels=wl.levels):
+    def cfg(iters, flags=0, levels=wl.levels, dtype=None):
         return MgritGruCfg(T, B, D, H, cf=wl.cf, levels=levels, iters=iters, fine_relax=fine_relax,
-                           propagator=0, dtype=dtype_code, flags=flags)
+                           propagator=0, dtype=dtype_code if dtype is None else dtype, flags=flags)
 
     convergence = None
     if args.until_converged:
@@ -543,8 +557,9 @@ def main():
                                       else "cycle limit N_1/2")}
         del ws0, hs, hh
 
-    ws = torch.empty(mg.mgrit_gru_workspace_bytes(cfg(max(fwd_iters, bwd_iters, 1))),
-                     dtype=torch.uint8, device=dev)
+    other = 2 if (wl.dtype == "fp32" and not x3) else None   # the form timed beside the main one
+    ws = torch.empty(max(mg.mgrit_gru_workspace_bytes(cfg(max(fwd_iters, bwd_iters, 1), dtype=dt))
+                         for dt in (None, other)), dtype=torch.uint8, device=dev)
     h = torch.zeros(T + 1, B, H, device=dev)
     w = torch.zeros(T + 1, B, H, device=dev)
     dW = torch.empty(3 * H, D, device=dev)
@@ -563,17 +578,17 @@ def main():
         p[torch.arange(B, device=dev), labels] -= 1.0
         return (p / B) @ W_o
 
-    def mgrit_step():
+    def mgrit_step(dtype=None):
         h.zero_()
         # the forward solve leaves the projection and the adjoint coefficients of the steps of
         # its closing relaxation in the workspace; the backward solve reuses both
-        mg.mgrit_gru_forward(cfg(fwd_iters, MGRIT_KEEP_COEFFS if bwd_iters > 0 else 0), *Wp,
-                             t["h0"], h, res_f, ws)
+        mg.mgrit_gru_forward(cfg(fwd_iters, MGRIT_KEEP_COEFFS if bwd_iters > 0 else 0, dtype=dtype),
+                             *Wp, t["h0"], h, res_f, ws)
         if bwd_iters > 0:
             g = loss_head()
             w.zero_()
-            mg.mgrit_gru_backward(cfg(bwd_iters, MGRIT_REUSE_PROJECTION | MGRIT_REUSE_COEFFS), *Wp,
-                                  h, g, w, res_b, dW, dU, dbi, dbh, ws)
+            mg.mgrit_gru_backward(cfg(bwd_iters, MGRIT_REUSE_PROJECTION | MGRIT_REUSE_COEFFS,
+                                      dtype=dtype), *Wp, h, g, w, res_b, dW, dU, dbi, dbh, ws)
 
     def serial_step():
         mg.gru_serial_scan(cfg(1, MGRIT_KEEP_COEFFS if bwd_iters > 0 else 0), *Wp, t["h0"], h, ws)
@@ -636,7 +651,10 @@ def main():
                            "algorithmic_GBps": by / ms / 1e6}
             if kind in (0, 1, 2, 3):
                 kernels[nm]["frac_of_mfma_peak"] = fl / ms / 1e9 / (
-                    MI355X_PEAK["fp32_TFLOPs"] if wl.dtype == "fp32" else MI355X_PEAK["bf16_TFLOPs"])
+                    MI355X_PEAK["fp32_TFLOPs"] if dtype_code == 0 else MI355X_PEAK["bf16_TFLOPs"])
+                if x3:   # six bf16 MFMA products per algorithmic multiply-add
+                    kernels[nm]["issued_TFLOPs"] = 6.0 * fl / ms / 1e9
+                    kernels[nm]["issued_frac_of_mfma_peak"] = 6.0 * kernels[nm]["frac_of_mfma_peak"]
             if kind == 7:
                 kernels[nm]["frac_of_hbm_peak"] = by / ms / 1e6 / MI355X_PEAK["hbm_GBps"]
     # whole step against the matrix-core peak: flops of all library kernels / step time
@@ -645,12 +663,12 @@ def main():
     if dn:
         dom = {"launches_per_step": dn / args.steps, "avg_launch_us": 1e3 * dms / dn,
                "TFLOPs": dfl / dms / 1e9, "flops_per_launch": dfl / dn, "bytes_per_launch": dby / dn}
-    peak = MI355X_PEAK["fp32_TFLOPs"] if wl.dtype == "fp32" else MI355X_PEAK["bf16_TFLOPs"]
+    peak = MI355X_PEAK["fp32_TFLOPs"] if dtype_code == 0 else MI355X_PEAK["bf16_TFLOPs"]
     # HBM traffic of the dominant kernel per launch: measured offline with rocprofv3 --pmc
     # (FETCH_SIZE, WRITE_SIZE; scaled by a copy kernel of known size) and recorded in profiles/
     traffic = None
     tf = os.path.join(ROOT, "profiles", f"phi_step_{wl.name}_hbm_traffic.txt")
-    if os.path.exists(tf):
+    if os.path.exists(tf) and not x3:
         for line in open(tf):
             if line.startswith("traffic_bytes_per_launch"):
                 traffic = int(line.split("=")[1].split("#")[0])
@@ -666,6 +684,34 @@ def main():
                     "avg_launch_us": dom["avg_launch_us"],
                     "launches_per_step": dom["launches_per_step"],
                     "all_launch_shapes_TFLOPs": kernels[names[0]]["TFLOPs"]}
+        if x3:
+            # the pipe runs six bf16 products per algorithmic multiply-add: frac prices the
+            # algorithmic flops against the bf16 peak, issued_frac the MFMA work actually done
+            roofline["issued_TFLOPs"] = 6.0 * dom["TFLOPs"]
+            roofline["issued_frac"] = 6.0 * dom["TFLOPs"] / peak
+            roofline["frac_of_fp32_mfma_peak"] = dom["TFLOPs"] / MI355X_PEAK["fp32_TFLOPs"]
+
+    # fp32 workloads: the same step with the operands contracted as three bf16 terms
+    other_form = None
+    if other is not None:
+        osec = timed(lambda: mgrit_step(other), args.steps, 1)
+        mg.mgrit_gru_profile_enable(True)
+        mgrit_step(other)
+        torch.cuda.synchronize()
+        mg.mgrit_gru_profile_enable(False)
+        on, oms, ofl, _ = mg.mgrit_gru_profile_read_shape(0, dom_rows, 0)
+        for kind in names:
+            mg.mgrit_gru_profile_read(kind)
+        other_form = {"what": "same step, same inputs, dtype MGRIT_F32_BF16X3: fp32 operands of the "
+                              "tile kernels contracted as three bf16 terms each (six bf16 MFMA "
+                              "products per multiply-add, fp32 accumulation; same 1e-5 parity bar)",
+                      "ms_per_step": 1e3 * osec, "value": T * B / osec,
+                      "speedup_over_fp32_mfma": sec / osec}
+        if on:
+            other_form["phi_step_level0_avg_launch_us"] = 1e3 * oms / on
+            other_form["phi_step_level0_TFLOPs"] = ofl / oms / 1e9
+            other_form["phi_step_level0_frac_of_fp32_mfma_peak"] = (
+                ofl / oms / 1e9 / MI355X_PEAK["fp32_TFLOPs"])
 
     serial = None
     if not args.no_serial:
@@ -699,12 +745,13 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32" if wl.dtype == "fp32" else "bf16-in/f32-state",
+        "dtype": ("f32 as 3 bf16 terms (bf16 MFMA, f32 accumulate)" if x3 else
+                  "f32" if wl.dtype == "fp32" else "bf16-in/f32-state"),
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: T={T} B={B} D={D} H={H} cf={wl.cf} levels={wl.levels} "
                                f"fwd_iters={fwd_iters} bwd_iters={bwd_iters} fine-level {args.fine_relax} "
                                f"relaxation, implicit GRU",
-                   "seed": wl.seed},
+                   "operands": args.operands, "seed": wl.seed},
         "convergence": convergence,
         "residual_fwd": resf,
         "residual_bwd": resb,
@@ -714,6 +761,10 @@ def main():
                        "frac_of_mfma_peak": step_flops / sec / 1e12 / peak},
         "serial_gpu": serial,
     }
+    if other_form:
+        other_form["mgrit_speedup_vs_serial"] = (serial["ms_per_step"] / other_form["ms_per_step"]
+                                                 if serial else None)
+        out["bf16x3_operands"] = other_form
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, fwd_iters, bwd_iters, fcf=bool(fine_relax))
     print(json.dumps(out))

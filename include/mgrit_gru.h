@@ -17,9 +17,15 @@
  *   order r, z, n:  W[3H,D] = (W_ir;W_iz;W_in), U[3H,H] = (W_hr;W_hz;W_hn),
  *   b_i[3H] = (b_ir;b_iz;b_in), b_h[3H] = (b_hr;b_hz;b_hn).  b_hn sits inside
  *   r*(W_hn h + b_hn), so the two bias sets cannot be merged.
- * - dtype 0: x, W, U are float.  dtype 1: x, W, U are bf16 (uint16 bit
- *   patterns); biases, states, projections, accumulation and every output
- *   stay float.
+ * - dtype MGRIT_F32: x, W, U are float.  MGRIT_BF16: x, W, U are bf16 (uint16
+ *   bit patterns); biases, states, projections, accumulation and every output
+ *   stay float.  MGRIT_F32_BF16X3: arguments exactly as for MGRIT_F32 and
+ *   results to the same accuracy; the tile kernels carry each fp32 operand of
+ *   a contraction as the sum of three bf16 terms (3 x 8 mantissa bits, the
+ *   exponent range of fp32) and keep six of the nine term products, accumulated
+ *   in fp32 on the bf16 matrix pipe, which is faster than the fp32 one.  The
+ *   weights' term arrays live in the workspace (it is larger for this dtype)
+ *   and are rebuilt by every call; H and D must be multiples of 8.
  * - Level l of the hierarchy has N_l = T / cf^l steps and step size cf^l
  *   (Sec. 3.3); `levels` counts the fine level (three levels over 128 steps
  *   with cf = 4 are grids of 128, 32 and 8 steps).  cf^(levels-1) must divide T.
@@ -56,8 +62,8 @@ enum {
   MGRIT_E_HIERARCHY = -3,   /* cf^(levels-1) does not divide T */
   MGRIT_E_ENUM = -4,        /* unknown propagator / dtype / fine_relax / flags */
   MGRIT_E_WORKSPACE = -5,   /* workspace smaller than mgrit_gru_workspace_bytes */
-  MGRIT_E_ALIGN = -6,       /* H or D not a multiple of 4 (float dtype) / 8 (bf16), or
-                               a pointer not 16-byte aligned */
+  MGRIT_E_ALIGN = -6,       /* H or D not a multiple of 4 (MGRIT_F32) / 8 (other dtypes),
+                               or a pointer not 16-byte aligned */
   MGRIT_E_LAUNCH = -7,      /* the HIP runtime refused a launch */
   MGRIT_E_UNSUPPORTED = -8  /* a valid request this build has no kernel for */
 };

@@ -35,6 +35,7 @@ class MgritGruCfg(ctypes.Structure):
         super().__init__(T, B, D, H, cf, levels, iters, fine_relax, propagator, dtype, flags)
 
 
+MGRIT_F32, MGRIT_BF16, MGRIT_F32_BF16X3 = 0, 1, 2   # cfg.dtype
 MGRIT_REUSE_PROJECTION = 1
 MGRIT_KEEP_COEFFS = 2
 MGRIT_REUSE_COEFFS = 4

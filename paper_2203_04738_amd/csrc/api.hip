@@ -659,7 +659,7 @@ const char* mgrit_gru_strerror(int code) {
     case MGRIT_E_HIERARCHY: return "cf^(levels-1) does not divide T";
     case MGRIT_E_ENUM: return "unknown enum or flag value";
     case MGRIT_E_WORKSPACE: return "workspace too small";
-    case MGRIT_E_ALIGN: return "width not a multiple of 4 (8 for bf16) or pointer not 16-byte aligned";
+    case MGRIT_E_ALIGN: return "width not a multiple of 4 (8 unless dtype is MGRIT_F32) or pointer not 16-byte aligned";
     case MGRIT_E_LAUNCH: return "HIP launch failed";
     case MGRIT_E_UNSUPPORTED: return "unsupported configuration";
     default: return "unknown error";

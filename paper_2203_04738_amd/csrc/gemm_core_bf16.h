@@ -21,6 +21,8 @@
 // use the same assignment, so the contraction is independent of how the
 // instruction numbers k inside a lane.
 #pragma once
+#include <type_traits>
+
 #include "gemm_core.h"
 
 namespace mg {
@@ -85,7 +87,6 @@ struct TileCfgB {
   static constexpr int NA = NP == 3 ? 3 : SPLIT_A ? 2 : 1;   // A tiles in LDS
   static constexpr int NBP = NP == 3 ? 3 : 1;                // B tiles in LDS
   static constexpr int NTERM = NA > NBP ? NA : NBP;          // products kept: t + u < NTERM
-  static constexpr int FSETS = NP == 3 ? 1 : 2;              // fragment register sets
   static constexpr int NWAVES = WM * WN * KS;
   static constexpr int NT = NWAVES * 64;
   static constexpr int TM = WM * BM * 32;
@@ -230,17 +231,102 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
         // slice kt sits in LDS, so its register set is free for slice kt + DP
         if (kt + DP < nkt) fetch(d, (kt + DP) * C::TK);
         __builtin_amdgcn_sched_barrier(0);
-        bf16x8 fa[C::FSETS][NFA];
-        bf16x8 fb[C::FSETS][NFB];
+        bf16x8 fa[2][NFA];
+        bf16x8 fb[2][NFB];
         __builtin_amdgcn_s_setprio(2);        // see gemm_core.h
-        if constexpr (C::FSETS == 1) {
-          // six MFMAs per operand pair: the reads of a k-group are a small share of its
-          // issue time, one fragment set is enough
+        if constexpr (C::NP == 3) {
+          // Three-term operands: the products of a k-group are issued in three units, one
+          // per B term u (A terms 0..2-u against it: 18, 12 and 6 MFMAs for a 2 x 3 block
+          // tile), and every fragment is requested one unit before its first use, a read
+          // in front of each of the unit's first MFMAs.  B terms alternate between two
+          // register sets; of the A terms only term 0 (used by every unit) needs two.
+          bf16x8 a0[2][C::BM], a1[C::BM], a2[C::BM], bt[2][NB];
+          auto rdA = [&](int c, int t, bf16x8 (&f)[C::BM]) {
 #pragma unroll
-          for (int c = 0; c < NC; ++c) {
-            read_frags(c, fa[0], fb[0]);
-            mma(fa[0], fb[0]);
-          }
+            for (int a = 0; a < C::BM; ++a)
+              f[a] = *reinterpret_cast<const bf16x8*>(
+                  &As[t * C::TM * C::LD + a_off + a * 32 * C::LD + c * 16]);
+          };
+          auto rdB = [&](int c, int u, bf16x8 (&f)[NB]) {
+#pragma unroll
+            for (int g = 0; g < C::NG; ++g)
+#pragma unroll
+              for (int b = 0; b < C::BN; ++b)
+                f[g * C::BN + b] = *reinterpret_cast<const bf16x8*>(
+                    &Bs[u * C::BROWS * C::LD + b_off + (g * C::TN + b * 32) * C::LD + c * 16]);
+          };
+          auto mm = [&](const bf16x8 (&f)[C::BM], const bf16x8 (&h)[NB]) {
+#pragma unroll
+            for (int g = 0; g < C::NG; ++g)
+#pragma unroll
+              for (int b = 0; b < C::BN; ++b)
+#pragma unroll
+                for (int a = 0; a < C::BM; ++a)
+                  acc.v[g][a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                      f[a], h[g * C::BN + b], acc.v[g][a][b], 0, 0, 0);
+          };
+          constexpr int UM = C::BM * NB;            // MFMAs of one (A term, B term) pair
+          rdA(0, 0, a0[0]);
+          rdB(0, 0, bt[0]);
+          rdA(0, 2, a2);
+          rdA(0, 1, a1);
+          auto group = [&](auto more_tag, int c) {
+            constexpr bool more = decltype(more_tag)::value;   // a k-group follows in this slice
+            const int s0 = (3 * c) & 1;            // register set of B term 0 of this group
+            // unit 0
+            rdB(c, 1, bt[s0 ^ 1]);
+            mm(a0[c & 1], bt[s0]);
+            mm(a2, bt[s0]);
+            mm(a1, bt[s0]);
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+              __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+              __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 3 * UM - NB, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            // unit 1
+            rdB(c, 2, bt[s0]);
+            if constexpr (more) {
+              rdA(c + 1, 2, a2);
+              rdA(c + 1, 0, a0[(c + 1) & 1]);
+            }
+            mm(a0[c & 1], bt[s0 ^ 1]);
+            mm(a1, bt[s0 ^ 1]);
+            {
+              constexpr int nr = NB + (more ? 2 * C::BM : 0);
+              constexpr int np = nr < 2 * UM ? nr : 2 * UM;
+#pragma unroll
+              for (int i = 0; i < np; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+              }
+              if constexpr (nr > np) __builtin_amdgcn_sched_group_barrier(0x100, nr - np, 0);
+              if constexpr (2 * UM > np) __builtin_amdgcn_sched_group_barrier(0x008, 2 * UM - np, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // unit 2
+            if constexpr (more) {
+              rdB(c + 1, 0, bt[s0 ^ 1]);
+              rdA(c + 1, 1, a1);
+            }
+            mm(a0[c & 1], bt[s0]);
+            if constexpr (more) {
+              constexpr int nr = NB + C::BM;
+              constexpr int np = nr < UM ? nr : UM;
+#pragma unroll
+              for (int i = 0; i < np; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+              }
+              if constexpr (nr > np) __builtin_amdgcn_sched_group_barrier(0x100, nr - np, 0);
+              if constexpr (UM > np) __builtin_amdgcn_sched_group_barrier(0x008, UM - np, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          };
+#pragma unroll
+          for (int c = 0; c + 1 < NC; ++c) group(std::true_type(), c);
+          group(std::false_type(), NC - 1);
         } else {
         read_frags(0, fa[0], fb[0]);
 #pragma unroll
@@ -250,7 +336,7 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
           if (c + 1 < NC) {
             // one LDS read of the next k-group, then a share of this group's MFMAs, in turn
             constexpr int NR = NFA + NB;
-            constexpr int NM = C::NA * C::BM * NB;   // (FSETS == 2: one B term)
+            constexpr int NM = C::NA * C::BM * NB;
             constexpr int MPR = NM / NR > 0 ? NM / NR : 1;
 #pragma unroll
             for (int i = 0; i < NR; ++i) {

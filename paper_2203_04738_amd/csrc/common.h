@@ -27,7 +27,6 @@ enum StepMode {
 // One launch of the fused forward step  Phi_gamma(x, h) over nk level points.
 struct PhiArgs {
   const void* U;       // [3H,H], float or bf16 (see bf16)
-  const void* U3;      // bf16 == 2: the three bf16 terms of U, [3][3H,H]
   const float* b_h;    // [3H]
   const float* P;      // [T,B,3H] input projection
   const float* u_in;   // state array the step reads from
@@ -44,12 +43,12 @@ struct PhiArgs {
   int mode;
   int bf16;            // 1: U is bf16 and the contraction runs on the bf16 MFMA path
                        // 2: U is float; the tile kernels contract three-term bf16 operands
+  const void* U3;      // bf16 == 2: the three bf16 terms of U, [3][3H,H]
 };
 
 // One launch of the fused adjoint step  w_out = (dPhi/dh)^T w_in  over nk points.
 struct AdjArgs {
   const void* UT;      // [H,3H] transposed recurrent weights, float or bf16
-  const void* UT3;     // bf16 == 2: the three bf16 terms of UT, [3][H,3H]
   const float* kap;    // coefficient array of this level, [*,B,kw]: k_r,k_z,k_q,k_d(,k_n)
   const float* w_in;   // adjoint array the step reads from
   float* w;            // level adjoint array (out / cur)
@@ -61,6 +60,7 @@ struct AdjArgs {
   int nk, B, H, kw;
   int mode;
   int bf16;            // operand form, as in PhiArgs
+  const void* UT3;     // bf16 == 2: the three bf16 terms of UT, [3][H,3H]
 };
 
 hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s);

@@ -285,10 +285,6 @@ def stack_main(args):
                        "frac_of_mfma_peak": step_flops / sec / 1e12 / peak},
         "serial_gpu": serial,
     }
-    if other_form:
-        other_form["mgrit_speedup_vs_serial"] = (serial["ms_per_step"] / other_form["ms_per_step"]
-                                                 if serial else None)
-        out["bf16x3_operands"] = other_form
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = stack_cpu_baseline(wl, L, fwd_iters, bwd_iters, fcf=bool(fine_relax))
     print(json.dumps(out))

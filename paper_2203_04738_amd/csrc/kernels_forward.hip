@@ -591,7 +591,7 @@ __global__ __launch_bounds__(PhiSkMaxNT<CT>::value) void phi_skinny_kernel(PhiAr
   __syncthreads();
 
   double nrm = 0.0;
-  for (int e = tid; e < n_out; e += blockDim.x) {
+  for (int e = tid; e < n_out; e += geo.nt) {
     const int row = e / CT, c = e % CT;
     const int j = j0 + c;
     if (j >= H) continue;

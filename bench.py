@@ -160,6 +160,8 @@ def stack_main(args):
               file=sys.stderr)
         sys.exit(2)
     L = args.layers
+    x3 = args.operands == "bf16x3"
+    dtype_code = 2 if x3 else 0
     fwd_iters = wl.fwd_iters if args.fwd_iters is None else args.fwd_iters
     bwd_iters = max(1, wl.bwd_iters if args.bwd_iters is None else args.bwd_iters)
     fine_relax = 1 if args.fine_relax == "FCF" else 0
@@ -173,7 +175,7 @@ def stack_main(args):
         t = {k: torch.from_numpy(v).to(dev) for k, v in d.items() if k != "x" or j == 0}
         cfgj = (lambda wj: lambda iters, flags=0: MgritGruCfg(
             T, B, wj.D, H, cf=wl.cf, levels=wl.levels, iters=iters, fine_relax=fine_relax,
-            propagator=0, dtype=0, flags=flags))(wj)
+            propagator=0, dtype=dtype_code, flags=flags))(wj)
         lay.append({
             "t": t, "cfg": cfgj, "D": wj.D,
             "ws": torch.empty(mg.mgrit_gru_workspace_bytes(cfgj(max(fwd_iters, bwd_iters))),
@@ -256,7 +258,7 @@ def stack_main(args):
             kernels[nm] = {"launches_per_step": n / args.steps, "ms_per_step": ms / args.steps,
                            "avg_launch_us": 1e3 * ms / n, "TFLOPs": fl / ms / 1e9,
                            "algorithmic_GBps": by / ms / 1e6}
-    peak = MI355X_PEAK["fp32_TFLOPs"]
+    peak = MI355X_PEAK["bf16_TFLOPs"] if x3 else MI355X_PEAK["fp32_TFLOPs"]
     step_flops = sum(v["TFLOPs"] * v["ms_per_step"] * 1e9 for v in kernels.values())
     dom = kernels.get(names[0])
     roofline = None
@@ -275,11 +277,13 @@ def stack_main(args):
         "metric": f"GRU time-steps x batch / sec, {L}-layer MGRIT fwd+bwd (1 GPU)",
         "value": T * B / sec, "unit": "time-steps*batch/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": 1e3 * sec, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 as 3 bf16 terms (bf16 MFMA, f32 accumulate)" if x3 else "f32",
+        "data": "synthetic",
         "config": {"workload": f"{wl.name} x {L} layers: T={T} B={B} D={wl.D} H={H} cf={wl.cf} "
                                f"levels={wl.levels} fwd_iters={fwd_iters} bwd_iters={bwd_iters} per layer, "
                                f"fine-level {args.fine_relax} relaxation, implicit GRU",
-                   "seed": wl.seed},
+                   "operands": args.operands, "seed": wl.seed},
         "roofline": roofline, "kernels": kernels,
         "whole_step": {"TFLOPs": step_flops / sec / 1e12,
                        "frac_of_mfma_peak": step_flops / sec / 1e12 / peak},

@@ -843,6 +843,13 @@ __global__ __launch_bounds__(256, 2) void grad_gemm_bf16_kernel(GradArgs a) {
   const bool n_ok = n < N;
   const int nc = n_ok ? n : 0;
 
+  // LDS chunk positions.  A thread's rows are four (fp32 operands) or eight (bf16 second
+  // operand) apart, 64 or 128 bytes modulo the 256 the banks span, so the 16-byte chunk it
+  // writes is exchanged with another chunk of the row, chosen by the column block (bits 4-5,
+  // or 4-6, of the row; the readers apply the same exchange): sixteen neighbouring lanes
+  // then cover all banks once.
+  const int ka = (k8 ^ ((m4 >> 2) & 3)) * 8;              // k8 == kb for fp32 operands
+  const int kbs = (kb ^ ((n8 >> 1) & 7)) * 8;
   floatx4 rk[8], rw[8];
   floatx4 rbf[B_BF16 ? 1 : 8];
   bf16x8 rbh[B_BF16 ? 8 : 1];
@@ -885,8 +892,8 @@ __global__ __launch_bounds__(256, 2) void grad_gemm_bf16_kernel(GradArgs a) {
       }
       bf16x8 hi, lo;
       split_bf16(v, hi, lo);
-      *reinterpret_cast<bf16x8*>(&As[0][(m4 * 4 + e) * HB_LD + k8 * 8]) = hi;
-      *reinterpret_cast<bf16x8*>(&As[1][(m4 * 4 + e) * HB_LD + k8 * 8]) = lo;
+      *reinterpret_cast<bf16x8*>(&As[0][(m4 * 4 + e) * HB_LD + ka]) = hi;
+      *reinterpret_cast<bf16x8*>(&As[1][(m4 * 4 + e) * HB_LD + ka]) = lo;
     }
     if (b_thread) {
       if constexpr (B_BF16) {
@@ -898,7 +905,7 @@ __global__ __launch_bounds__(256, 2) void grad_gemm_bf16_kernel(GradArgs a) {
             const bool k_ok = k0 + kb * 8 + r < kend;
             o[r] = (k_ok && n_ok) ? rbh[r][e] : (__bf16)0.f;
           }
-          *reinterpret_cast<bf16x8*>(&Bs[0][(n8 * 8 + e) * HB_LD + kb * 8]) = o;
+          *reinterpret_cast<bf16x8*>(&Bs[0][(n8 * 8 + e) * HB_LD + kbs]) = o;
         }
       } else {
 #pragma unroll
@@ -911,8 +918,8 @@ __global__ __launch_bounds__(256, 2) void grad_gemm_bf16_kernel(GradArgs a) {
           }
           bf16x8 hi, lo;
           split_bf16(v, hi, lo);
-          *reinterpret_cast<bf16x8*>(&Bs[0][(m4 * 4 + e) * HB_LD + kb * 8]) = hi;
-          *reinterpret_cast<bf16x8*>(&Bs[NBT - 1][(m4 * 4 + e) * HB_LD + kb * 8]) = lo;
+          *reinterpret_cast<bf16x8*>(&Bs[0][(m4 * 4 + e) * HB_LD + ka]) = hi;
+          *reinterpret_cast<bf16x8*>(&Bs[NBT - 1][(m4 * 4 + e) * HB_LD + ka]) = lo;
         }
       }
     }
@@ -934,13 +941,15 @@ __global__ __launch_bounds__(256, 2) void grad_gemm_bf16_kernel(GradArgs a) {
 #pragma unroll
           for (int i = 0; i < 2; ++i)
             fa[t][i] = *reinterpret_cast<const bf16x8*>(
-                &As[t][(wm * 64 + i * 32 + li) * HB_LD + c * 16 + lh * 8]);
+                &As[t][(wm * 64 + i * 32 + li) * HB_LD + ((2 * c + lh) ^ ((2 * i + (li >> 4)) & 3)) * 8]);
 #pragma unroll
         for (int t = 0; t < NBT; ++t)
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
+          for (int j = 0; j < 2; ++j) {
+            const int sw = B_BF16 ? (4 * wn + 2 * j + (li >> 4)) & 7 : (2 * j + (li >> 4)) & 3;
             fb[t][j] = *reinterpret_cast<const bf16x8*>(
-                &Bs[t][(wn * 64 + j * 32 + li) * HB_LD + c * 16 + lh * 8]);
+                &Bs[t][(wn * 64 + j * 32 + li) * HB_LD + ((2 * c + lh) ^ sw) * 8]);
+          }
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -1030,7 +1039,11 @@ __global__ __launch_bounds__(256, 2) void grad_gemm_x3_kernel(GradArgs a) {
   const int cc = c_ok ? col : 0;
   const int gate = cc / H, jcol = cc - gate * H;            // (A threads)
   const int src = gate == 2 ? a.third_off + jcol : cc;
-  bf16_t* dst = (is_a ? &As[0][0] : &Bs[0][0]) + (c4 * 4) * HS_LD + k8 * 8;
+  // Rows four apart are 320 bytes apart, i.e. 64 modulo the 256 bytes the banks span: the
+  // 16-byte chunk a thread writes is therefore exchanged with another chunk of its rows,
+  // chosen by bits 2-3 of the column block (the readers undo it with bits 4-5 of the row),
+  // so that sixteen neighbouring lanes cover all banks once.
+  bf16_t* dst = (is_a ? &As[0][0] : &Bs[0][0]) + (c4 * 4) * HS_LD + (k8 ^ ((c4 >> 2) & 3)) * 8;
 
   // first operand row k of this thread: a coefficient row (A) or a row of h / x (B)
   const float* base0 = is_a ? a.kap0 + rowoff * (5LL * H) + src : (const float*)a.Bm + cc;
@@ -1088,10 +1101,11 @@ __global__ __launch_bounds__(256, 2) void grad_gemm_x3_kernel(GradArgs a) {
         for (int t = 0; t < 3; ++t)
 #pragma unroll
           for (int i = 0; i < 2; ++i) {
+            const int ch = ((2 * c + lh) ^ ((2 * i + (li >> 4)) & 3)) * 8;
             fa[t][i] = *reinterpret_cast<const bf16x8*>(
-                &As[t][(wm * 64 + i * 32 + li) * HS_LD + c * 16 + lh * 8]);
+                &As[t][(wm * 64 + i * 32 + li) * HS_LD + ch]);
             fb[t][i] = *reinterpret_cast<const bf16x8*>(
-                &Bs[t][(wn * 64 + i * 32 + li) * HS_LD + c * 16 + lh * 8]);
+                &Bs[t][(wn * 64 + i * 32 + li) * HS_LD + ch]);
           }
 #pragma unroll
         for (int t = 0; t < 3; ++t)

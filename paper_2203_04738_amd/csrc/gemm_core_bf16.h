@@ -92,7 +92,12 @@ struct TileCfgB {
   static constexpr int TM = WM * BM * 32;
   static constexpr int TN = WN * BN * 32;
   static constexpr int BROWS = NG * TN;
-  static constexpr int LD = TK + 8;             // LDS row stride in elements (odd multiple of 16 bytes)
+  // LDS rows: padded by 16 bytes (an odd multiple of 16 bytes per row), or, for the three-term
+  // tiles with 64-byte rows, unpadded with the four 16-byte chunks of a row exchanged by
+  // bits 2-3 of the row number, so that sixteen neighbouring lanes cover all banks once both
+  // when a slice is written (four rows x four chunks) and when it is read (sixteen rows).
+  static constexpr bool SWZ = NP_ == 3 && KS_ == 1 && TKB_ == 32;
+  static constexpr int LD = SWZ ? TK : TK + 8;  // LDS row stride in elements
   static constexpr int CPR = TK / 8;            // 16-byte chunks per tile row
   static constexpr int A_CHUNKS = (TM * CPR) / NT;
   static constexpr int B_CHUNKS = (BROWS * CPR) / NT;
@@ -103,6 +108,11 @@ struct TileCfgB {
 
 template <class C>
 __device__ inline int chunk_row_b(int s) { return (threadIdx.x + s * C::NT) / C::CPR; }
+// position of 16-byte chunk `chunk` inside LDS row `row`
+template <class C>
+__device__ inline int swz_chunk(int row, int chunk) {
+  return C::SWZ ? chunk ^ ((row >> 2) & 3) : chunk;
+}
 
 // One pass over K (elements; a multiple of 8).
 //   loadA(s, k): raw global load(s) for columns k..k+7 of the tile row of chunk s;
@@ -154,7 +164,7 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
 #pragma unroll
     for (int s = 0; s < C::A_CHUNKS; ++s) {
       const int q = tid + s * C::NT;
-      const int off = (q / C::CPR) * C::LD + (q % C::CPR) * 8;
+      const int off = (q / C::CPR) * C::LD + swz_chunk<C>(q / C::CPR, q % C::CPR) * 8;
       const bool dead = KTAIL && k0 + (q % C::CPR) * 8 >= K;
       if constexpr (C::NA == 3) {
         bf16x8 t0, t1, t2;
@@ -178,7 +188,7 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
 #pragma unroll
       for (int u = 0; u < C::NBP; ++u)
         *reinterpret_cast<bf16x8*>(
-            &Bs[(u * C::BROWS + q / C::CPR) * C::LD + (q % C::CPR) * 8]) =
+            &Bs[(u * C::BROWS + q / C::CPR) * C::LD + swz_chunk<C>(q / C::CPR, q % C::CPR) * 8]) =
             dead ? z : operand_term(rb[d][s], u);
     }
   };
@@ -241,11 +251,16 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
           // in front of each of the unit's first MFMAs.  B terms alternate between two
           // register sets; of the A terms only term 0 (used by every unit) needs two.
           bf16x8 a0[2][C::BM], a1[C::BM], a2[C::BM], bt[2][NB];
+          // element offset of this lane's chunk of k-group c inside its rows (all rows a
+          // lane reads are 32 apart: one exchange pattern, bits 2-3 of li)
+          const int a_row = ((wm * C::BM) * 32 + li) * C::LD;
+          const int b_row = ((wn * C::BN) * 32 + li) * C::LD;
+          auto kpos = [&](int c) { return swz_chunk<C>(li, ks * NC * 2 + 2 * c + lh) * 8; };
           auto rdA = [&](int c, int t, bf16x8 (&f)[C::BM]) {
 #pragma unroll
             for (int a = 0; a < C::BM; ++a)
               f[a] = *reinterpret_cast<const bf16x8*>(
-                  &As[t * C::TM * C::LD + a_off + a * 32 * C::LD + c * 16]);
+                  &As[t * C::TM * C::LD + a_row + a * 32 * C::LD + kpos(c)]);
           };
           auto rdB = [&](int c, int u, bf16x8 (&f)[NB]) {
 #pragma unroll
@@ -253,7 +268,7 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
 #pragma unroll
               for (int b = 0; b < C::BN; ++b)
                 f[g * C::BN + b] = *reinterpret_cast<const bf16x8*>(
-                    &Bs[u * C::BROWS * C::LD + b_off + (g * C::TN + b * 32) * C::LD + c * 16]);
+                    &Bs[u * C::BROWS * C::LD + b_row + (g * C::TN + b * 32) * C::LD + kpos(c)]);
           };
           auto mm = [&](const bf16x8 (&f)[C::BM], const bf16x8 (&h)[NB]) {
 #pragma unroll

@@ -273,7 +273,7 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void adj_step_kernel_bf16(AdjArgs 
 // ---------------------------------------------------------------------------
 typedef TileCfg<2, 2, 2, 2, 1> DxCfg;            // 128 x 128 tile
 typedef TileCfgB<2, 2, 2, 2, 1, true> DxCfgB;
-typedef TileCfgB<2, 2, 2, 2, 1, true, 1, 1, 2, 3, 32> DxCfgS;
+typedef TileCfgB<4, 2, 1, 2, 1, true, 1, 1, 2, 3, 32> DxCfgS;     // 8 waves of 32 x 64
 
 // Stores one accumulator tile of a plain GEMM: out[m, n], leading dimension N.
 template <class C>
@@ -342,7 +342,7 @@ __global__ __launch_bounds__(DxCfg::NT) void input_grad_kernel(
 }
 
 template <class C>
-__global__ __launch_bounds__(C::NT) void input_grad_kernel_bf16(
+__global__ __launch_bounds__(C::NT, C::NT > 256 ? 2 : 1) void input_grad_kernel_bf16(
     const float* __restrict__ kap0, const float* __restrict__ w, const bf16_t* __restrict__ WT,
     float* __restrict__ dx, long long R, int B, int H, int D) {
   __shared__ __attribute__((aligned(16))) bf16_t lds[C::LDS_ELEMS];
@@ -503,6 +503,10 @@ typedef TileCfgB<2, 2, 1, 1, 1, true> AdjMidB;
 typedef TileCfgB<1, 1, 1, 1, 1, true, 4> AdjSmallB;
 // three-term operands (K-slices of 32)
 typedef TileCfgB<2, 2, 2, 2, 1, true, 1, 1, 2, 3, 32> AdjBigS;
+// the same tile with 8 waves of 32 x 64 each: half the accumulators per wave, so that two
+// workgroups (16 waves, 128 registers per lane) share a CU and keep twice the loads in
+// flight; the relaxation mode fits that register budget, the others use the 4-wave form
+typedef TileCfgB<4, 2, 1, 2, 1, true, 1, 1, 2, 3, 32> AdjBigS8;
 typedef TileCfgB<2, 2, 1, 1, 1, true, 1, 1, 2, 3, 32> AdjMidS;
 typedef TileCfgB<1, 1, 1, 1, 1, true, 4, 1, 2, 3, 32> AdjSmallS;
 
@@ -513,8 +517,12 @@ static void launch_adj_cfg(const AdjArgs& a, hipStream_t s) {
   dim3 block(a.bf16 == 2 ? CS::NT : a.bf16 ? CB::NT : C::NT);
   static_assert(C::TM == CB::TM && C::TN == CB::TN, "tile shapes must agree");
   static_assert(C::TM == CS::TM && C::TN == CS::TN, "tile shapes must agree");
+  static_assert(AdjBigS8::TM == AdjBigS::TM && AdjBigS8::TN == AdjBigS::TN, "tile shapes must agree");
   if (a.bf16 == 2) {
-    if (a.mode == STEP_RELAX)
+    if (a.mode == STEP_RELAX && std::is_same<CS, AdjBigS>::value)
+      hipLaunchKernelGGL((adj_step_kernel_bf16<AdjBigS8, STEP_RELAX>), grid, dim3(AdjBigS8::NT), 0,
+                         s, a);
+    else if (a.mode == STEP_RELAX)
       hipLaunchKernelGGL((adj_step_kernel_bf16<CS, STEP_RELAX>), grid, block, 0, s, a);
     else if (a.mode == STEP_RESID)
       hipLaunchKernelGGL((adj_step_kernel_bf16<CS, STEP_RESID>), grid, block, 0, s, a);

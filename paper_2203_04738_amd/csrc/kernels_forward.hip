@@ -72,10 +72,10 @@ __global__ __launch_bounds__(ProjCfg::NT) void projection_kernel(
 // bf16 inputs and weights (ProjCfgB), or fp32 inputs with the weights given as their three
 // bf16 terms W3[3][N,K] (ProjCfgS); fp32 accumulation and output
 typedef TileCfgB<2, 2, 2, 2, 1, false> ProjCfgB;
-typedef TileCfgB<2, 2, 2, 2, 1, true, 1, 1, 2, 3, 32> ProjCfgS;
+typedef TileCfgB<4, 2, 1, 2, 1, true, 1, 1, 2, 3, 32> ProjCfgS;   // 8 waves of 32 x 64
 
 template <class C>
-__global__ __launch_bounds__(C::NT) void projection_kernel_bf16(
+__global__ __launch_bounds__(C::NT, C::NT > 256 ? 2 : 1) void projection_kernel_bf16(
     const void* __restrict__ Xv, const bf16_t* __restrict__ W, const float* __restrict__ bias,
     float* __restrict__ P, long long M, int N, int K) {
   typedef typename std::conditional<C::SPLIT_A, float, bf16_t>::type AT;

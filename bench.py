@@ -497,7 +497,8 @@ def main():
 
     import paper_2203_04738_amd as mg
     from paper_2203_04738_amd.binding import (MGRIT_KEEP_COEFFS, MGRIT_REUSE_COEFFS,
-                                              MGRIT_REUSE_PROJECTION, MgritGruCfg)
+                                              MGRIT_REUSE_PROJECTION, MGRIT_ZERO_ADJOINT_GUESS,
+                                              MgritGruCfg)
     from synthetic_inputs import WORKLOADS, make_inputs
 
     wl = WORKLOADS[args.workload]
@@ -587,8 +588,10 @@ def main():
         if bwd_iters > 0:
             g = loss_head()
             w.zero_()
-            mg.mgrit_gru_backward(cfg(bwd_iters, MGRIT_REUSE_PROJECTION | MGRIT_REUSE_COEFFS,
-                                      dtype=dtype), *Wp, h, g, w, res_b, dW, dU, dbi, dbh, ws)
+            # w is the zero initial guess of Alg. 3: the first cycle may skip what is still zero
+            mg.mgrit_gru_backward(cfg(bwd_iters, MGRIT_REUSE_PROJECTION | MGRIT_REUSE_COEFFS |
+                                      MGRIT_ZERO_ADJOINT_GUESS, dtype=dtype),
+                                  *Wp, h, g, w, res_b, dW, dU, dbi, dbh, ws)
 
     def serial_step():
         mg.gru_serial_scan(cfg(1, MGRIT_KEEP_COEFFS if bwd_iters > 0 else 0), *Wp, t["h0"], h, ws)

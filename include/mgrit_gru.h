@@ -92,7 +92,18 @@ enum {
    * propagator and workspace pointer, and the states h passed in are the ones
    * that call returned: only the steps it did not cover (those into the coarse
    * points) are linearised again. */
-  MGRIT_REUSE_COEFFS = 4
+  MGRIT_REUSE_COEFFS = 4,
+  /* mgrit_gru_backward: rows 0..T-1 of w_inout are zero on entry (the initial
+   * guess of Alg. 3).  The adjoint recurrence is linear and homogeneous, so in
+   * the first cycle everything below the last intervals is still zero when the
+   * relaxation, residual and right-hand-side passes reach it; with this flag
+   * those passes skip the rows whose result is known to be zero (the zeros are
+   * written where a coarse level needs them).  The iterate returned is the same
+   * up to rounding (a pass over fewer rows may run in another kernel form, which
+   * adds in another order).  Ignored by mgrit_gru_backward_steps (a loss term on every
+   * state makes the adjoint non-zero everywhere) and by the serial entry
+   * points. */
+  MGRIT_ZERO_ADJOINT_GUESS = 8
 };
 
 typedef struct {

@@ -39,6 +39,7 @@ MGRIT_F32, MGRIT_BF16, MGRIT_F32_BF16X3 = 0, 1, 2   # cfg.dtype
 MGRIT_REUSE_PROJECTION = 1
 MGRIT_KEEP_COEFFS = 2
 MGRIT_REUSE_COEFFS = 4
+MGRIT_ZERO_ADJOINT_GUESS = 8
 _lib = None
 
 

@@ -77,7 +77,8 @@ static int check_cfg(const mgrit_gru_cfg* c, bool need_hierarchy) {
     return MGRIT_E_ENUM;
   if (c->dtype != MGRIT_F32 && c->dtype != MGRIT_BF16 && c->dtype != MGRIT_F32_BF16X3)
     return MGRIT_E_ENUM;
-  if (c->flags & ~(MGRIT_REUSE_PROJECTION | MGRIT_KEEP_COEFFS | MGRIT_REUSE_COEFFS))
+  if (c->flags & ~(MGRIT_REUSE_PROJECTION | MGRIT_KEEP_COEFFS | MGRIT_REUSE_COEFFS |
+                   MGRIT_ZERO_ADJOINT_GUESS))
     return MGRIT_E_ENUM;
   if (need_hierarchy) {
     if (c->cf < 1 || c->levels < 1 || c->levels > MAX_LEVELS) return MGRIT_E_SIZE;
@@ -395,26 +396,42 @@ static AdjArgs adj_base(const BwdCtx& x, int l) {
 // Relaxation of the reversed recurrence: interval i hangs below coarse point
 // (i+1)*cf; sub-step j moves from point (i+1)cf-j+1 to (i+1)cf-j with the
 // coefficients of level step (i+1)cf-j+1.
-static int relax_bwd(const BwdCtx& x, int l, bool include_c, bool f_points_current = false) {
+//
+// lo (a multiple of cf, or null): on entry the adjoint and the right-hand side of the
+// level are known to be zero at every point below *lo.  The recurrence is linear and
+// homogeneous, so an interval whose upper coarse point lies below *lo stays zero and is
+// left out of the launches; on return *lo is the bound that holds after the sweep (one
+// interval lower).
+static int relax_bwd(const BwdCtx& x, int l, bool include_c, bool f_points_current = false,
+                     long long* lo = nullptr) {
   const long long cf = x.c->cf;
   const int nint = (int)(x.lay->N[l] / cf);
+  long long i0 = 0;                        // first interval that can hold non-zero values
+  if (lo) {
+    i0 = *lo / cf - 1;
+    if (i0 < 0) i0 = 0;
+    *lo = i0 * cf;
+  }
   for (long long j = f_points_current ? cf : 1; j < cf + (include_c ? 1 : 0); ++j) {
     AdjArgs a = adj_base(x, l);
     a.mode = STEP_RELAX;
-    a.nk = nint;
-    a.in = Idx{cf - j + 1, cf};
+    a.nk = nint - (int)i0;
+    a.in = Idx{cf - j + 1 + i0 * cf, cf};
     a.k = a.in;
-    a.o = Idx{cf - j, cf};
+    a.o = Idx{cf - j + i0 * cf, cf};
     const bool overlap = (cf == 1);
     if (overlap) a.w = x.tmp;
     CHECK_HIP(launch_adj_step(a, x.s));
     if (overlap)
-      CHECK_HIP(launch_copy_points(x.wl[l], x.tmp, a.o, a.o, nint, (long long)a.B * a.H, x.s));
+      CHECK_HIP(launch_copy_points(x.wl[l], x.tmp, a.o, a.o, a.nk, (long long)a.B * a.H, x.s));
   }
   return MGRIT_OK;
 }
 
-static int vcycle_bwd(const BwdCtx& x, int l, bool f_points_current = false) {
+// lo_in: bound below which adjoint and right-hand side of this level are zero on entry (see
+// relax_bwd; 0 = nothing known).
+static int vcycle_bwd(const BwdCtx& x, int l, bool f_points_current = false,
+                      long long lo_in = 0) {
   const long long cf = x.c->cf, N = x.lay->N[l];
   const int L = x.lay->L;
   if (l == L - 1) {
@@ -431,21 +448,33 @@ static int vcycle_bwd(const BwdCtx& x, int l, bool f_points_current = false) {
   }
   int rc;
   const bool cur = l == 0 && f_points_current;
+  long long lo = lo_in;
+  long long* plo = lo > 0 && cf > 1 ? &lo : nullptr;
+  if (!plo) lo = 0;
   if (l == 0 && x.c->fine_relax == 0) {
-    if ((rc = relax_bwd(x, l, false, cur))) return rc;
+    if ((rc = relax_bwd(x, l, false, cur, plo))) return rc;
   } else {
-    if ((rc = relax_bwd(x, l, true, cur))) return rc;
-    if ((rc = relax_bwd(x, l, false))) return rc;
+    if ((rc = relax_bwd(x, l, true, cur, plo))) return rc;
+    if ((rc = relax_bwd(x, l, false, false, plo))) return rc;
   }
   const int Nc = (int)(N / cf);
-  {  // residual at coarse points i*cf, i = 0..Nc-1, and restriction
+  // coarse points below lo have a zero adjoint, a zero successor and a zero right-hand
+  // side: their residual and their restricted value are zero and are written as such
+  const long long iR = lo / cf;            // first coarse point with a non-zero residual
+  const long long jR = iR > 0 ? iR - 1 : 0;  // first one with a non-zero coarse right-hand side
+  if (iR > 0) {
+    const long long BH = (long long)x.c->B * x.c->H;
+    CHECK_HIP(launch_zero_f32(x.wl[l + 1], iR * BH, x.s));
+    CHECK_HIP(launch_zero_f32(x.gl[l + 1], iR * BH, x.s));
+  }
+  {  // residual at coarse points i*cf, i = iR..Nc-1, and restriction
     AdjArgs a = adj_base(x, l);
     a.mode = STEP_RESID;
-    a.nk = Nc;
-    a.in = Idx{1, cf};
-    a.k = Idx{1, cf};
-    a.o = Idx{0, cf};
-    a.a = Idx{0, 1};
+    a.nk = Nc - (int)iR;
+    a.in = Idx{1 + iR * cf, cf};
+    a.k = a.in;
+    a.o = Idx{iR * cf, cf};
+    a.a = Idx{iR, 1};
     a.wc = x.wl[l + 1];
     a.gc = x.gl[l + 1];
     a.norm = l == 0 ? x.norm : nullptr;
@@ -454,13 +483,14 @@ static int vcycle_bwd(const BwdCtx& x, int l, bool f_points_current = false) {
   {  // coarse right-hand side
     AdjArgs a = adj_base(x, l + 1);
     a.mode = STEP_RHS;
-    a.nk = Nc;
-    a.in = Idx{1, 1};
-    a.k = Idx{1, 1};
-    a.o = Idx{0, 1};
+    a.nk = Nc - (int)jR;
+    a.in = Idx{1 + jR, 1};
+    a.k = a.in;
+    a.o = Idx{jR, 1};
     CHECK_HIP(launch_adj_step(a, x.s));
   }
-  if ((rc = vcycle_bwd(x, l + 1))) return rc;
+  // on the coarse level the adjoint is zero below iR and the right-hand side below jR
+  if ((rc = vcycle_bwd(x, l + 1, false, jR / cf * cf))) return rc;
   CHECK_HIP(launch_copy_points(x.wl[l], x.wl[l + 1], Idx{0, cf}, Idx{0, 1}, Nc,
                                (long long)x.c->B * x.c->H, x.s));
   return relax_bwd(x, l, false);
@@ -564,7 +594,10 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
   if (resnorm && c.iters > 0) CHECK_HIP(launch_fill_f64(norm, c.iters, 0.0, s));
   for (int it = 0; it < c.iters; ++it) {
     ctx.norm = resnorm ? norm + it : nullptr;
-    if ((rc = vcycle_bwd(ctx, 0, it > 0))) return rc;
+    // the caller's zero initial guess with a terminal loss term: everything below point T
+    // is zero when the first cycle starts
+    const bool zero_guess = it == 0 && (c.flags & MGRIT_ZERO_ADJOINT_GUESS) && !dL_dh && !serial;
+    if ((rc = vcycle_bwd(ctx, 0, it > 0, zero_guess ? lay.N[0] : 0))) return rc;
   }
   if (resnorm && !serial) CHECK_HIP(launch_sqrt_to_float(norm, resnorm, c.iters, s));
   if (ngrad == 4)

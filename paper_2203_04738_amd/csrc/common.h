@@ -94,6 +94,8 @@ hipError_t launch_input_grads(const float* kap0, const float* w, const void* WT,
 hipError_t launch_split3(const float* src, void* dst, long long n, hipStream_t s);
 
 hipError_t launch_fill_f64(double* p, long long n, double v, hipStream_t s);
+// p[0..n) = 0; n a multiple of 4, p 16-byte aligned
+hipError_t launch_zero_f32(float* p, long long n, hipStream_t s);
 // dst[(d.off + i*d.str), :, :] = src[(s.off + i*s.str), :, :] for i < nk; blocks of `block` floats
 hipError_t launch_copy_points(float* dst, const float* src, Idx d, Idx s, int nk, long long block,
                               hipStream_t st);

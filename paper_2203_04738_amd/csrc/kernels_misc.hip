@@ -17,6 +17,19 @@ hipError_t launch_fill_f64(double* p, long long n, double v, hipStream_t s) {
   return hipGetLastError();
 }
 
+__global__ void zero_f32_kernel(floatx4* p, long long n4) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n4) p[i] = zero4();
+}
+
+hipError_t launch_zero_f32(float* p, long long n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  const long long n4 = n / 4;
+  hipLaunchKernelGGL(zero_f32_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s,
+                     reinterpret_cast<floatx4*>(p), n4);
+  return hipGetLastError();
+}
+
 // One float4 per thread; `block` (floats per point) is a multiple of 4.
 __global__ void copy_points_kernel(float* __restrict__ dst, const float* __restrict__ src, Idx d,
                                    Idx s, int nk, long long block4) {

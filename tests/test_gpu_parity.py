@@ -329,6 +329,44 @@ def test_big_tiles_with_ragged_rows_columns_and_k(gh, dtype):
     assert e <= tol and e <= tight, e
 
 
+# ------------------------------------------------------------------ zero initial guess of the adjoint
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16", "fp32x3"])
+@pytest.mark.parametrize("cf,levels,fcf,T,B", [(4, 3, True, 128, 3), (4, 2, False, 32, 70), (2, 4, True, 64, 40),
+                                               (8, 2, True, 64, 3), (4, 4, True, 256, 2), (3, 3, True, 27, 5),
+                                               (1, 2, True, 12, 3), (4, 3, True, 16, 3)])
+def test_zero_adjoint_guess_flag(gh, dtype, cf, levels, fcf, T, B):
+    """MGRIT_ZERO_ADJOINT_GUESS lets the first adjoint cycle leave out the rows whose result is
+    known to be zero.  What is left out is exactly zero in the full computation; the launches
+    that remain cover fewer rows and may take another kernel form (other summation order), so
+    the iterates agree with those of the call without the flag to rounding, and meet the
+    oracle's bar on their own.  Hierarchies down to one interval per level, F and FCF, one
+    and several cycles per call."""
+    from paper_2203_04738_amd.binding import MGRIT_ZERO_ADJOINT_GUESS
+    D, H = 16, 40
+    d = random_small(800 + cf + levels, T, B, D, H, scale=0.3)
+    tol, close = (TOL, 2e-6)
+    if dtype == "bf16":
+        d = _bf16_inputs(d)
+        tol = TIGHT_BF16
+    h = orc.serial_scan(*_P(d), d["x"], d["h0"]).astype(np.float32)
+    out = orc.mgrit_backward(*_P(d), d["x"], h, d["dL_dhT"], _zeros(d), cf, levels, 3,
+                             fine_relax_fcf=fcf, keep_iterates=True)
+    run = gh.GpuRun(d, cf=cf, levels=levels, fine_relax=int(fcf), dtype=dtype)
+    for per_call in (1, 3):
+        a_its, a_res, a_gr = run.backward_iterates(h, 3, per_call=per_call)
+        b_its, b_res, b_gr = run.backward_iterates(h, 3, per_call=per_call,
+                                                   first_call_flags=MGRIT_ZERO_ADJOINT_GUESS)
+        for u, v in zip(a_its + list(a_gr), b_its + list(b_gr)):
+            assert gh.rel_err(v, u) <= close
+        assert np.allclose(a_res, b_res, rtol=1e-5, atol=0)
+        refs = out[-1] if per_call == 1 else out[-1][-1:]
+        for g, r in zip(b_its, refs):
+            assert gh.rel_err(g, r) <= tol
+        for name, g, r in zip(("dW", "dU", "db_i", "db_h"), b_gr, out[2:6]):
+            assert gh.rel_err(g, r) <= tol, name
+
+
 # ------------------------------------------------------------------ launch structure of a cycle
 
 def test_launch_counts_of_two_fcf_cycles(gh):

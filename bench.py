@@ -151,7 +151,8 @@ def stack_main(args):
 
     import paper_2203_04738_amd as mg
     from paper_2203_04738_amd.binding import (MGRIT_KEEP_COEFFS, MGRIT_REUSE_COEFFS,
-                                              MGRIT_REUSE_PROJECTION, MgritGruCfg)
+                                              MGRIT_REUSE_PROJECTION, MGRIT_ZERO_ADJOINT_GUESS,
+                                              MgritGruCfg)
     from synthetic_inputs import WORKLOADS, layer_workload, make_inputs
 
     wl = WORKLOADS[args.workload]
@@ -213,8 +214,11 @@ def stack_main(args):
         head()
         for j in range(L - 1, -1, -1):
             lay[j]["w"].zero_()
+            # the top layer's source term is zero below row T and its adjoint starts from zero:
+            # its first cycle may skip what is still zero
+            top_flag = MGRIT_ZERO_ADJOINT_GUESS if j == L - 1 else 0
             mg.mgrit_gru_backward_steps(lay[j]["cfg"](bwd_iters, MGRIT_REUSE_PROJECTION |
-                                                      MGRIT_REUSE_COEFFS), *P(j),
+                                                      MGRIT_REUSE_COEFFS | top_flag), *P(j),
                                         lay[j]["h"], lay[j]["src"], lay[j]["w"], None,
                                         *lay[j]["g"], dx_of(j), lay[j]["ws"])
 

@@ -100,9 +100,11 @@ enum {
    * those passes skip the rows whose result is known to be zero (the zeros are
    * written where a coarse level needs them).  The iterate returned is the same
    * up to rounding (a pass over fewer rows may run in another kernel form, which
-   * adds in another order).  Ignored by mgrit_gru_backward_steps (a loss term on every
-   * state makes the adjoint non-zero everywhere) and by the serial entry
-   * points. */
+   * adds in another order).  With mgrit_gru_backward_steps the flag declares in
+   * addition that rows 0..T-1 of dL_dh are zero (the top layer of a stack whose
+   * loss reads h_T only, called through this entry point for its dx); with a
+   * loss term on earlier states it must not be set.  Ignored by the serial
+   * entry points. */
   MGRIT_ZERO_ADJOINT_GUESS = 8
 };
 

@@ -596,7 +596,8 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
     ctx.norm = resnorm ? norm + it : nullptr;
     // the caller's zero initial guess with a terminal loss term: everything below point T
     // is zero when the first cycle starts
-    const bool zero_guess = it == 0 && (c.flags & MGRIT_ZERO_ADJOINT_GUESS) && !dL_dh && !serial;
+    // (with a loss term on every state the flag also declares rows 0..T-1 of that term zero)
+    const bool zero_guess = it == 0 && (c.flags & MGRIT_ZERO_ADJOINT_GUESS) && !serial;
     if ((rc = vcycle_bwd(ctx, 0, it > 0, zero_guess ? lay.N[0] : 0))) return rc;
   }
   if (resnorm && !serial) CHECK_HIP(launch_sqrt_to_float(norm, resnorm, c.iters, s));

@@ -117,7 +117,7 @@ class GpuRun:
         return ((w.cpu().numpy(),) + tuple(a.cpu().numpy() for a in g)
                 + ((dx.cpu().numpy(),) if want_dx else ()))
 
-    def backward_steps_iterates(self, h, dL_dh, iters, per_call=1, want_dx=True):
+    def backward_steps_iterates(self, h, dL_dh, iters, per_call=1, want_dx=True, first_call_flags=0):
         hd, sd = self._dev(h), self._dev(dL_dh)
         w = torch.zeros(self.T + 1, self.B, self.H, device=DEV)
         its, norms, grads = [], [], None
@@ -128,7 +128,8 @@ class GpuRun:
             g = self._grads()
             dx = (torch.full((self.T, self.B, self.D), float("nan"), device=DEV)
                   if want_dx else None)
-            mg.mgrit_gru_backward_steps(self.cfg(n), *self._p(), hd, sd, w, res, *g, dx, self.ws)
+            mg.mgrit_gru_backward_steps(self.cfg(n, first_call_flags if done == 0 else 0), *self._p(),
+                                        hd, sd, w, res, *g, dx, self.ws)
             torch.cuda.synchronize()
             its.append(w.cpu().numpy().copy())
             norms += res.cpu().numpy().tolist()

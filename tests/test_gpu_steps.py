@@ -62,6 +62,28 @@ def test_source_that_is_zero_except_at_T_reproduces_the_terminal_entry_point(gh)
         assert np.array_equal(u, v)
 
 
+def test_zero_guess_flag_with_a_source_that_is_zero_below_T(gh):
+    """The top layer of a stack whose loss reads h_T only: its source term is zero except in
+    row T, it goes through the step-loss entry point for its dx, and may declare the zero
+    guess.  Same bar against the oracle, and agreement to rounding with the undeclared call."""
+    from paper_2203_04738_amd.binding import MGRIT_ZERO_ADJOINT_GUESS
+    T, B, D, H, cf, levels = 64, 5, 24, 40, 4, 3
+    d = random_small(78, T, B, D, H, scale=0.3)
+    src = np.zeros((T + 1, B, H), dtype=np.float32)
+    src[T] = d["dL_dhT"]
+    h = orc.serial_scan(*_P(d), d["x"], d["h0"]).astype(np.float32)
+    out = orc.mgrit_backward(*_P(d), d["x"], h, None, np.zeros((T + 1, B, H)), cf, levels, 2,
+                             dL_dh=src)
+    run = gh.GpuRun(d, cf=cf, levels=levels)
+    ia, _, ga = run.backward_steps_iterates(h, src, 2, per_call=2)
+    ib, _, gb = run.backward_steps_iterates(h, src, 2, per_call=2,
+                                            first_call_flags=MGRIT_ZERO_ADJOINT_GUESS)
+    for u, v in zip(ia + list(ga), ib + list(gb)):
+        assert gh.rel_err(v, u) <= 2e-6
+    for name, g, r in zip(NAMES, [ib[-1]] + list(gb), (out[0],) + tuple(out[2:7])):
+        assert gh.rel_err(g, r) <= TOL, name
+
+
 def _check_mgrit_steps(gh, d, src, cf, levels, iters, fcf=True, prop=orc.IMPLICIT, per_call=1):
     T, B = d["x"].shape[:2]
     H = d["U"].shape[1]

@@ -583,7 +583,7 @@ def main():
         p[torch.arange(B, device=dev), labels] -= 1.0
         return (p / B) @ W_o
 
-    def mgrit_step(dtype=None):
+    def mgrit_step(dtype=None, declare_zero_guess=True):
         h.zero_()
         # the forward solve leaves the projection and the adjoint coefficients of the steps of
         # its closing relaxation in the workspace; the backward solve reuses both
@@ -593,8 +593,9 @@ def main():
             g = loss_head()
             w.zero_()
             # w is the zero initial guess of Alg. 3: the first cycle may skip what is still zero
-            mg.mgrit_gru_backward(cfg(bwd_iters, MGRIT_REUSE_PROJECTION | MGRIT_REUSE_COEFFS |
-                                      MGRIT_ZERO_ADJOINT_GUESS, dtype=dtype),
+            zg = MGRIT_ZERO_ADJOINT_GUESS if declare_zero_guess else 0
+            mg.mgrit_gru_backward(cfg(bwd_iters, MGRIT_REUSE_PROJECTION | MGRIT_REUSE_COEFFS | zg,
+                                      dtype=dtype),
                                   *Wp, h, g, w, res_b, dW, dU, dbi, dbh, ws)
 
     def serial_step():
@@ -698,6 +699,15 @@ def main():
             roofline["issued_frac"] = 6.0 * dom["TFLOPs"] / peak
             roofline["frac_of_fp32_mfma_peak"] = dom["TFLOPs"] / MI355X_PEAK["fp32_TFLOPs"]
 
+    # the same step without declaring the adjoint's zero initial guess: every pass of its first
+    # cycle then runs over all rows, those that only produce zeros included
+    undeclared = None
+    if bwd_iters > 0:
+        usec = timed(lambda: mgrit_step(declare_zero_guess=False), args.steps, 1)
+        undeclared = {"what": "same step without MGRIT_ZERO_ADJOINT_GUESS (the adjoint's first cycle also "
+                              "runs the rows whose result is exactly zero)",
+                      "ms_per_step": 1e3 * usec, "value": T * B / usec}
+
     # fp32 workloads: the same step with the operands contracted as three bf16 terms
     other_form = None
     if other is not None:
@@ -757,7 +767,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: T={T} B={B} D={D} H={H} cf={wl.cf} levels={wl.levels} "
                                f"fwd_iters={fwd_iters} bwd_iters={bwd_iters} fine-level {args.fine_relax} "
-                               f"relaxation, implicit GRU",
+                               f"relaxation, implicit GRU, zero initial guesses (the adjoint's declared)",
                    "operands": args.operands, "seed": wl.seed},
         "convergence": convergence,
         "residual_fwd": resf,
@@ -768,6 +778,8 @@ def main():
                        "frac_of_mfma_peak": step_flops / sec / 1e12 / peak},
         "serial_gpu": serial,
     }
+    if undeclared:
+        out["without_zero_guess_flag"] = undeclared
     if other_form:
         other_form["mgrit_speedup_vs_serial"] = (serial["ms_per_step"] / other_form["ms_per_step"]
                                                  if serial else None)

@@ -502,7 +502,7 @@ def main():
     import paper_2203_04738_amd as mg
     from paper_2203_04738_amd.binding import (MGRIT_KEEP_COEFFS, MGRIT_REUSE_COEFFS,
                                               MGRIT_REUSE_PROJECTION, MGRIT_ZERO_ADJOINT_GUESS,
-                                              MgritGruCfg)
+                                              MGRIT_ZERO_STATE_GUESS, MgritGruCfg)
     from synthetic_inputs import WORKLOADS, make_inputs
 
     wl = WORKLOADS[args.workload]
@@ -587,8 +587,9 @@ def main():
         h.zero_()
         # the forward solve leaves the projection and the adjoint coefficients of the steps of
         # its closing relaxation in the workspace; the backward solve reuses both
-        mg.mgrit_gru_forward(cfg(fwd_iters, MGRIT_KEEP_COEFFS if bwd_iters > 0 else 0, dtype=dtype),
-                             *Wp, t["h0"], h, res_f, ws)
+        zs = MGRIT_ZERO_STATE_GUESS if declare_zero_guess else 0      # h was just zero-filled
+        mg.mgrit_gru_forward(cfg(fwd_iters, (MGRIT_KEEP_COEFFS if bwd_iters > 0 else 0) | zs,
+                                 dtype=dtype), *Wp, t["h0"], h, res_f, ws)
         if bwd_iters > 0:
             g = loss_head()
             w.zero_()
@@ -699,13 +700,13 @@ def main():
             roofline["issued_frac"] = 6.0 * dom["TFLOPs"] / peak
             roofline["frac_of_fp32_mfma_peak"] = dom["TFLOPs"] / MI355X_PEAK["fp32_TFLOPs"]
 
-    # the same step without declaring the adjoint's zero initial guess: every pass of its first
-    # cycle then runs over all rows, those that only produce zeros included
+    # the same step without declaring the zero initial guesses: every pass of the first cycles
+    # then runs over all rows, those that only produce (or only read) zeros included
     undeclared = None
     if bwd_iters > 0:
         usec = timed(lambda: mgrit_step(declare_zero_guess=False), args.steps, 1)
-        undeclared = {"what": "same step without MGRIT_ZERO_ADJOINT_GUESS (the adjoint's first cycle also "
-                              "runs the rows whose result is exactly zero)",
+        undeclared = {"what": "same step without MGRIT_ZERO_STATE_GUESS / MGRIT_ZERO_ADJOINT_GUESS (the first "
+                              "cycles also run the contractions whose result is exactly zero)",
                       "ms_per_step": 1e3 * usec, "value": T * B / usec}
 
     # fp32 workloads: the same step with the operands contracted as three bf16 terms

@@ -105,7 +105,14 @@ enum {
    * loss reads h_T only, called through this entry point for its dx); with a
    * loss term on earlier states it must not be set.  Ignored by the serial
    * entry points. */
-  MGRIT_ZERO_ADJOINT_GUESS = 8
+  MGRIT_ZERO_ADJOINT_GUESS = 8,
+  /* mgrit_gru_forward: rows 1..T of h_inout are zero on entry (the initial guess
+   * of Alg. 3).  The first sub-step of the first relaxation then starts from
+   * zero states everywhere but in the first interval, and its recurrent
+   * contraction U h is skipped where h is zero (the sums are exactly zero
+   * either way: the iterate is the same, bit for bit).  Ignored by the serial
+   * scan. */
+  MGRIT_ZERO_STATE_GUESS = 16
 };
 
 typedef struct {

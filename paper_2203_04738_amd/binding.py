@@ -40,6 +40,7 @@ MGRIT_REUSE_PROJECTION = 1
 MGRIT_KEEP_COEFFS = 2
 MGRIT_REUSE_COEFFS = 4
 MGRIT_ZERO_ADJOINT_GUESS = 8
+MGRIT_ZERO_STATE_GUESS = 16
 _lib = None
 
 

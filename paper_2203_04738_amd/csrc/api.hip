@@ -78,7 +78,7 @@ static int check_cfg(const mgrit_gru_cfg* c, bool need_hierarchy) {
   if (c->dtype != MGRIT_F32 && c->dtype != MGRIT_BF16 && c->dtype != MGRIT_F32_BF16X3)
     return MGRIT_E_ENUM;
   if (c->flags & ~(MGRIT_REUSE_PROJECTION | MGRIT_KEEP_COEFFS | MGRIT_REUSE_COEFFS |
-                   MGRIT_ZERO_ADJOINT_GUESS))
+                   MGRIT_ZERO_ADJOINT_GUESS | MGRIT_ZERO_STATE_GUESS))
     return MGRIT_E_ENUM;
   if (need_hierarchy) {
     if (c->cf < 1 || c->levels < 1 || c->levels > MAX_LEVELS) return MGRIT_E_SIZE;
@@ -195,8 +195,10 @@ static PhiArgs phi_base(const FwdCtx& x, int l) {
 // in the tile kernel afterwards; forward and backward calls decide by the same rule.
 static bool serial_scan_keeps_coeffs(const mgrit_gru_cfg& c) { return c.B > 64; }
 
+// zero_c: the coarse points 1.. of the level hold zero states (the caller's initial guess):
+// the first sub-step reads nothing else outside the first interval.
 static int relax_fwd(const FwdCtx& x, int l, bool include_c, bool f_points_current = false,
-                     bool emit = false) {
+                     bool emit = false, bool zero_c = false) {
   const long long cf = x.c->cf, S = x.lay->S[l];
   const int nint = (int)(x.lay->N[l] / cf);
   // f_points_current: the F-points already equal the propagation of their coarse
@@ -217,6 +219,7 @@ static int relax_fwd(const FwdCtx& x, int l, bool include_c, bool f_points_curre
     a.in = Idx{j - 1, cf};
     a.o = Idx{j, cf};
     a.p = Idx{j * S - 1, cf * S};
+    if (zero_c && j == 1 && cf > 1) a.zero_from = x.c->B;   // rows of the intervals 1..
     const bool overlap = (cf == 1);   // reads and writes would share points
     if (overlap) a.u = x.tmp;
     CHECK_HIP(launch_phi_step(a, x.s));
@@ -226,7 +229,8 @@ static int relax_fwd(const FwdCtx& x, int l, bool include_c, bool f_points_curre
   return MGRIT_OK;
 }
 
-static int vcycle_fwd(const FwdCtx& x, int l, bool f_points_current = false, bool last = false) {
+static int vcycle_fwd(const FwdCtx& x, int l, bool f_points_current = false, bool last = false,
+                      bool zero_guess = false) {
   const long long cf = x.c->cf, S = x.lay->S[l], N = x.lay->N[l];
   const int L = x.lay->L;
   if (l == L - 1) {
@@ -250,10 +254,11 @@ static int vcycle_fwd(const FwdCtx& x, int l, bool f_points_current = false, boo
   int rc;
   // Alg. 2 line 1
   const bool cur = l == 0 && f_points_current;
+  const bool zc = l == 0 && zero_guess && !cur;
   if (l == 0 && x.c->fine_relax == 0) {
-    if ((rc = relax_fwd(x, l, false, cur))) return rc;
+    if ((rc = relax_fwd(x, l, false, cur, false, zc))) return rc;
   } else {
-    if ((rc = relax_fwd(x, l, true, cur))) return rc;
+    if ((rc = relax_fwd(x, l, true, cur, false, zc))) return rc;
     if ((rc = relax_fwd(x, l, false))) return rc;
   }
   const int Nc = (int)(N / cf);
@@ -356,7 +361,8 @@ static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, co
   if (resnorm && c.iters > 0) CHECK_HIP(launch_fill_f64(norm, c.iters, 0.0, s));
   for (int it = 0; it < c.iters; ++it) {
     ctx.norm = resnorm ? norm + it : nullptr;
-    if ((rc = vcycle_fwd(ctx, 0, it > 0, it == c.iters - 1))) return rc;
+    const bool zero_guess = it == 0 && (c.flags & MGRIT_ZERO_STATE_GUESS) && !serial;
+    if ((rc = vcycle_fwd(ctx, 0, it > 0, it == c.iters - 1, zero_guess))) return rc;
   }
   if (resnorm && !serial) CHECK_HIP(launch_sqrt_to_float(norm, resnorm, c.iters, s));
   return MGRIT_OK;

@@ -44,6 +44,8 @@ struct PhiArgs {
   int bf16;            // 1: U is bf16 and the contraction runs on the bf16 MFMA path
                        // 2: U is float; the tile kernels contract three-term bf16 operands
   const void* U3;      // bf16 == 2: the three bf16 terms of U, [3][3H,H]
+  int zero_from;       // > 0: the input states of rows >= zero_from are all zero (tile kernels
+                       // skip the contraction of tiles that start there; 0: nothing known)
 };
 
 // One launch of the fused adjoint step  w_out = (dPhi/dh)^T w_in  over nk points.

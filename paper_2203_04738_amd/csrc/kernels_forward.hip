@@ -436,7 +436,10 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel(PhiArgs a) {
   acc.zero();
   auto la = [&](int s, int k) { return ldg4(arow[s] + k); };
   auto lb = [&](int s, int k) { return ldg4(brow[s] + k); };
-  if (H % C::TK == 0)
+  // a tile whose input states are known to be zero keeps its zero sums (uniform per workgroup)
+  const bool zero_in = a.zero_from > 0 && m0 >= a.zero_from;
+  if (zero_in) {
+  } else if (H % C::TK == 0)
     gemm_nt_tile<C, false>(acc, H, la, lb, Identity4(), Identity4(), lds);
   else
     gemm_nt_tile<C, true>(acc, H, la, lb, Identity4(), Identity4(), lds);
@@ -498,7 +501,9 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel_bf16(PhiArgs 
   acc.zero();
   auto la = [&](int s, int k) { return F32x8{ldg4(arow[s] + k), ldg4(arow[s] + k + 4)}; };
   auto fa = [](const F32x8& v) { return v; };
-  if constexpr (C::NP == 3) {
+  const bool zero_in = a.zero_from > 0 && m0 >= a.zero_from;   // see phi_step_kernel
+  if (zero_in) {
+  } else if constexpr (C::NP == 3) {
     const long long term = 3LL * H * H;
     auto lb = [&](int s, int k) {
       return Bf16x8x3{{ldg8h(brow[s] + k), ldg8h(brow[s] + term + k),

@@ -8,7 +8,7 @@ import torch
 import paper_2203_04738_amd as mg
 from paper_2203_04738_amd.binding import (MGRIT_KEEP_COEFFS, MGRIT_REUSE_COEFFS,
                                           MGRIT_REUSE_PROJECTION, MGRIT_ZERO_ADJOINT_GUESS,
-                                          MgritGruCfg)
+                                          MGRIT_ZERO_STATE_GUESS, MgritGruCfg)
 
 DEV = "cuda:0"
 
@@ -49,7 +49,7 @@ class GpuRun:
         torch.cuda.synchronize()
         return h.cpu().numpy()
 
-    def forward_iterates(self, iters, h_init=None, per_call=1):
+    def forward_iterates(self, iters, h_init=None, per_call=1, first_call_flags=0):
         """Calls mgrit_gru_forward repeatedly with `per_call` cycles each and returns
         the iterate after every call plus all residual norms."""
         h = torch.zeros(self.T + 1, self.B, self.H, device=DEV)
@@ -60,7 +60,7 @@ class GpuRun:
         while done < iters:
             n = min(per_call, iters - done)
             res = torch.full((n,), float("nan"), device=DEV)
-            flags = MGRIT_REUSE_PROJECTION if done > 0 else 0
+            flags = MGRIT_REUSE_PROJECTION if done > 0 else first_call_flags
             mg.mgrit_gru_forward(self.cfg(n, flags), *self._p(), self.t["h0"], h, res, self.ws)
             torch.cuda.synchronize()
             its.append(h.cpu().numpy().copy())
@@ -148,8 +148,8 @@ class GpuRun:
             mg.gru_serial_scan_backward(self.cfg(1, MGRIT_REUSE_PROJECTION | MGRIT_REUSE_COEFFS),
                                         *self._p(), h, self.t["dL_dhT"], w, *g, self.ws)
         else:
-            mg.mgrit_gru_forward(self.cfg(fwd_iters, MGRIT_KEEP_COEFFS), *self._p(), self.t["h0"],
-                                 h, None, self.ws)
+            mg.mgrit_gru_forward(self.cfg(fwd_iters, MGRIT_KEEP_COEFFS | MGRIT_ZERO_STATE_GUESS),
+                                 *self._p(), self.t["h0"], h, None, self.ws)
             # the call sequence of bench.py: projection and coefficients reused, zero guess declared
             mg.mgrit_gru_backward(self.cfg(bwd_iters, MGRIT_REUSE_PROJECTION | MGRIT_REUSE_COEFFS |
                                            MGRIT_ZERO_ADJOINT_GUESS),

@@ -44,7 +44,9 @@ def test_full_size_forward_window_and_serial_prefix(gh, name, window, form):
     tol = 1e-5 if wl.dtype == "fp32" else 2e-2
     iters = min(wl.fwd_iters, 2)
     run = gh.GpuRun(d, cf=wl.cf, levels=wl.levels, dtype=_dtype(wl, form))
-    its, res = run.forward_iterates(iters, per_call=iters)        # one call, as bench.py does
+    from paper_2203_04738_amd.binding import MGRIT_ZERO_STATE_GUESS
+    its, res = run.forward_iterates(iters, per_call=iters,        # one call, as bench.py does,
+                                    first_call_flags=MGRIT_ZERO_STATE_GUESS)   # zero guess declared
     got = its[-1][:window + 1]
     xs = d["x"][:window]
     ref, rres = orc.mgrit_forward(*_P(d), xs, d["h0"], np.zeros((window + 1, wl.B, wl.H)),

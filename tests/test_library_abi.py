@@ -57,7 +57,8 @@ def test_workspace_size_and_validation_codes():
     assert _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, dtype=7))[0] == -4
     assert _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, fine_relax=2))[0] == -4
     assert _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, flags=8))[0] == 0
-    assert _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, flags=16))[0] == -4
+    assert _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, flags=16))[0] == 0
+    assert _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, flags=32))[0] == -4
     assert _ws(MgritGruCfg(64, 2, 16, 30, cf=4, levels=2))[0] == -6
     assert _ws(MgritGruCfg(64, 2, 9, 32, cf=4, levels=2))[0] == -6
     # fp32 values as three bf16 terms: widths in multiples of 8, a larger workspace (term arrays)

@@ -152,7 +152,7 @@ def stack_main(args):
     import paper_2203_04738_amd as mg
     from paper_2203_04738_amd.binding import (MGRIT_KEEP_COEFFS, MGRIT_REUSE_COEFFS,
                                               MGRIT_REUSE_PROJECTION, MGRIT_ZERO_ADJOINT_GUESS,
-                                              MgritGruCfg)
+                                              MGRIT_ZERO_STATE_GUESS, MgritGruCfg)
     from synthetic_inputs import WORKLOADS, layer_workload, make_inputs
 
     wl = WORKLOADS[args.workload]
@@ -209,7 +209,8 @@ def stack_main(args):
     def mgrit_step():
         for j in range(L):
             lay[j]["h"].zero_()
-            mg.mgrit_gru_forward(lay[j]["cfg"](fwd_iters, MGRIT_KEEP_COEFFS), *P(j),
+            mg.mgrit_gru_forward(lay[j]["cfg"](fwd_iters, MGRIT_KEEP_COEFFS | MGRIT_ZERO_STATE_GUESS),
+                                 *P(j),
                                  lay[j]["t"]["h0"], lay[j]["h"], None, lay[j]["ws"])
         head()
         for j in range(L - 1, -1, -1):

@@ -392,7 +392,9 @@ __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Ph
   }
 }
 
-template <class C, int MODE>
+// ZS: the launch knows that the input states of the rows from a.zero_from on are zero (its
+// own instantiation, so that kernel traces list these launches apart).
+template <class C, int MODE, bool ZS = false>
 __global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel(PhiArgs a) {
   constexpr int LDSF = C::LDS_FLOATS > EpiStage<C>::FLOATS ? C::LDS_FLOATS : EpiStage<C>::FLOATS;
   __shared__ __attribute__((aligned(16))) float lds[LDSF];
@@ -438,7 +440,7 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel(PhiArgs a) {
   auto la = [&](int s, int k) { return ldg4(arow[s] + k); };
   auto lb = [&](int s, int k) { return ldg4(brow[s] + k); };
   // a tile whose input states are known to be zero keeps its zero sums (uniform per workgroup)
-  const bool zero_in = a.zero_from > 0 && m0 >= a.zero_from;
+  const bool zero_in = ZS && m0 >= a.zero_from;
   if (zero_in) {
   } else if (H % C::TK == 0)
     gemm_nt_tile<C, false>(acc, H, la, lb, Identity4(), Identity4(), lds);
@@ -457,7 +459,7 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel(PhiArgs a) {
 // bf16 weights: the fp32 state rows are split into hi + lo bf16 tiles (see
 // gemm_core_bf16.h); gates, update and outputs stay fp32.  With a three-term
 // configuration the weights are fp32 values held as three bf16 arrays.
-template <class C, int MODE>
+template <class C, int MODE, bool ZS = false>
 __global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel_bf16(PhiArgs a) {
   constexpr int LDSF =
       C::LDS_ELEMS / 2 + 1 > EpiStage<C>::FLOATS ? C::LDS_ELEMS / 2 + 1 : EpiStage<C>::FLOATS;
@@ -502,7 +504,7 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel_bf16(PhiArgs 
   acc.zero();
   auto la = [&](int s, int k) { return F32x8{ldg4(arow[s] + k), ldg4(arow[s] + k + 4)}; };
   auto fa = [](const F32x8& v) { return v; };
-  const bool zero_in = a.zero_from > 0 && m0 >= a.zero_from;   // see phi_step_kernel
+  const bool zero_in = ZS && m0 >= a.zero_from;                // see phi_step_kernel
   if (zero_in) {
   } else if constexpr (C::NP == 3) {
     const long long term = 3LL * H * H;
@@ -631,7 +633,10 @@ typedef TileCfgB<1, 1, 1, 1, 3, true, 4, 1, 2, 3, 32> PhiSmallS;
 #define MG_LAUNCH_BY_MODE(KERNEL, ...)                                                   \
   switch (a.mode) {                                                                      \
     case STEP_RELAX:                                                                     \
-      hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_RELAX>), grid, block, 0, s, a);       \
+      if (a.zero_from > 0)                                                               \
+        hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_RELAX, true>), grid, block, 0, s, a); \
+      else                                                                               \
+        hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_RELAX>), grid, block, 0, s, a);     \
       break;                                                                             \
     case STEP_RESID:                                                                     \
       hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_RESID>), grid, block, 0, s, a);       \

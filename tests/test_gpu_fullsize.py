@@ -37,7 +37,8 @@ def _dtype(wl, form):
 
 
 @pytest.mark.parametrize("name,window,form", [("C2", 1024, None), ("C3", 128, None), ("C4", 128, None),
-                                              ("C5", 256, None), ("C3", 128, "fp32x3")])
+                                              ("C5", 256, None), ("C3", 128, "fp32x3"),
+                                              ("C5", 256, "fp32x3")])
 def test_full_size_forward_window_and_serial_prefix(gh, name, window, form):
     wl = WORKLOADS[name]
     d = make_inputs(wl)
@@ -65,7 +66,7 @@ def test_full_size_forward_window_and_serial_prefix(gh, name, window, form):
 
 
 @pytest.mark.parametrize("name,window,form", [("C3", 128, None), ("C4", 128, None), ("C5", 256, None),
-                                              ("C3", 128, "fp32x3")])
+                                              ("C3", 128, "fp32x3"), ("C5", 256, "fp32x3")])
 def test_full_size_backward_window(gh, name, window, form):
     wl = WORKLOADS[name]
     d = make_inputs(wl)
@@ -86,7 +87,8 @@ def test_full_size_backward_window(gh, name, window, form):
         assert np.all(np.isfinite(g))
 
 
-@pytest.mark.parametrize("name,form", [("C3", None), ("C4", None), ("C5", None), ("C3", "fp32x3")])
+@pytest.mark.parametrize("name,form", [("C3", None), ("C4", None), ("C5", None), ("C3", "fp32x3"),
+                                       ("C5", "fp32x3")])
 def test_full_size_gradients_and_input_gradients_on_a_sparse_adjoint(gh, name, form):
     """Gradient GEMMs, bias sums and the input-gradient GEMM at full size, element by
     element.  With zero cycles the entry point forms the gradients from the adjoint it is

@@ -32,10 +32,11 @@ def _zeros(d):
 
 
 @pytest.mark.parametrize("prop", [orc.IMPLICIT, orc.CLASSIC])
-@pytest.mark.parametrize("shape", [(6, 70, 16, 136), (9, 130, 8, 24), (5, 300, 40, 72)])
+@pytest.mark.parametrize("shape", [(6, 70, 16, 136), (9, 130, 8, 24), (5, 300, 40, 72), (6, 70, 8, 8)])
 def test_serial_scan_and_bptt(gh, prop, shape):
     """Few tiles per launch: the K-split tile configuration, ragged rows, columns and K
-    (136 = 4 x 32 + 8, 3 x 24 = 72 = 2 x 32 + 8)."""
+    (136 = 4 x 32 + 8, 3 x 24 = 72 = 2 x 32 + 8), down to the smallest widths the form takes
+    (H = D = 8: a quarter of one K-slice)."""
     T, B, D, H = shape
     d = random_small(900 + H, T, B, D, H, scale=0.3)
     ref = orc.serial_scan(*_P(d), d["x"], d["h0"], prop)

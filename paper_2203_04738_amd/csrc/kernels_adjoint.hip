@@ -705,6 +705,9 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
   const int gate = mc / H, jcol = mc - gate * H;
   const int src = gate == 2 ? a.third_off + jcol : mc;
   floatx4 rk[NCH], rw[NCH], rb[NCH];
+  // Bias gradients are the column sums of S: every thread adds up the products it stages
+  // (its four columns, its rows of every slice); the eight row groups meet in LDS at the end.
+  floatx4 colsum = zero4();
   auto fetch = [&](long long k0) {
 #pragma unroll
     for (int s = 0; s < NCH; ++s) {
@@ -720,8 +723,9 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
     for (int s = 0; s < NCH; ++s) {
       const int kr = (tid >> 5) + s * 8;
       const bool k_ok = k0 + kr < kend;
-      *reinterpret_cast<floatx4*>(&As[kr * GLD + c4 * 4]) =
-          (k_ok && m_ok) ? rk[s] * rw[s] : zero4();
+      const floatx4 p = (k_ok && m_ok) ? rk[s] * rw[s] : zero4();
+      colsum += p;
+      *reinterpret_cast<floatx4*>(&As[kr * GLD + c4 * 4]) = p;
       *reinterpret_cast<floatx4*>(&Bs[kr * GLD + c4 * 4]) = (k_ok && n_ok) ? rb[s] : zero4();
     }
   };
@@ -732,11 +736,7 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
     for (int j = 0; j < 2; ++j) bv[j] = Bs[(2 * p + lh) * GLD + wn * 64 + j * 32 + li];
   };
 
-  // Bias gradients are the column sums of S: the staged slices already hold S, so
-  // thread t < GT adds up column t over the slice rows r = nt (mod ntiles); the
-  // workgroups of the ntiles column tiles share the rows of a slice between them.
   const int nt = tile / a.mtiles;
-  float colsum = 0.f;
   if (kbeg < kend) {
     fetch(kbeg);
     stash(kbeg);
@@ -745,8 +745,6 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
       const bool more = k0 + GTK < kend;
       if (more) fetch(k0 + GTK);
       __builtin_amdgcn_sched_barrier(0);
-      if (tid < GT)
-        for (int r = nt; r < GTK; r += a.ntiles) colsum += As[r * GLD + tid];
       float av[2][2], bv[2][2];
       __builtin_amdgcn_s_setprio(2);      // MFMA phase first at issue (see gemm_core.h)
       frags(0, av[0], bv[0]);
@@ -778,8 +776,20 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
       }
     }
   }
-  if (tid < GT && m0 + tid < M)
-    a.bpart[((long long)z * a.ntiles + nt) * M + m0 + tid] = colsum;
+  {
+    float* red = As;                       // [8][GT] floats (the slices are no longer read)
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < 4; ++e) red[(tid >> 5) * GT + c4 * 4 + e] = colsum[e];
+    __syncthreads();
+    if (tid < GT && m0 + tid < M) {
+      float sum = 0.f;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) sum += red[q * GT + tid];
+      // every column tile holds the same sums: the first one reports them
+      a.bpart[((long long)z * a.ntiles + nt) * M + m0 + tid] = nt == 0 ? sum : 0.f;
+    }
+  }
   float* out = a.part + (long long)z * M * N;
 #pragma unroll
   for (int i = 0; i < 2; ++i)

@@ -648,7 +648,7 @@ struct GradArgs {
   const float* w;      // [(T+1),B,H]
   const void* Bm;      // h[(T+1),B,H] (float) or x[T,B,D] (float or bf16); row k as is
   float* part;         // [splits][3H][N]
-  float* bpart;        // [splits][ntiles][3H] column sums of S (bias gradients)
+  float* bpart;        // [splits][3H] column sums of S (bias gradients), written by the first column tile
   long long Ktot;      // T*B
   long long Kper;      // rows per split (multiple of GTK)
   int B, H, N;         // N = H (dU) or D (dW)
@@ -787,7 +787,7 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
 #pragma unroll
       for (int q = 0; q < 8; ++q) sum += red[q * GT + tid];
       // every column tile holds the same sums: the first one reports them
-      a.bpart[((long long)z * a.ntiles + nt) * M + m0 + tid] = nt == 0 ? sum : 0.f;
+      if (nt == 0) a.bpart[(long long)z * M + m0 + tid] = sum;
     }
   }
   float* out = a.part + (long long)z * M * N;
@@ -997,7 +997,7 @@ __global__ __launch_bounds__(256, 2) void grad_gemm_bf16_kernel(GradArgs a) {
 #pragma unroll
     for (int q = 0; q < 8; ++q) sum += red[q * GT + tid];
     // every column tile holds the same sums: the first one reports them
-    a.bpart[((long long)z * a.ntiles + nt) * M + m0 + tid] = nt == 0 ? sum : 0.f;
+    if (nt == 0) a.bpart[(long long)z * M + m0 + tid] = sum;
   }
   float* out = a.part + (long long)z * M * N;
 #pragma unroll
@@ -1160,7 +1160,7 @@ __global__ __launch_bounds__(256, 2) void grad_gemm_x3_kernel(GradArgs a) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) sum += red[q * GT + tid];
     // every column tile holds the same sums: the first one reports them
-    a.bpart[((long long)z * a.ntiles + nt) * M + m0 + tid] = nt == 0 ? sum : 0.f;
+    if (nt == 0) a.bpart[(long long)z * M + m0 + tid] = sum;
   }
   float* out = a.part + (long long)z * M * N;
 #pragma unroll
@@ -1184,22 +1184,34 @@ __global__ void reduce_partials_kernel(const float* __restrict__ part, float* __
   out[i] = s;
 }
 
-// Bias gradients from the column sums the two gradient GEMMs leave behind:
-// pu[nu][3H] (columns k_r w, k_z w, k_q w) and pw[nw][3H] (k_r w, k_z w, k_n w).
-__global__ void bias_reduce_kernel(const float* __restrict__ pu, int nu,
-                                   const float* __restrict__ pw, int nw,
-                                   float* __restrict__ db_i, float* __restrict__ db_h, int H) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= 3 * H) return;
-  float su = 0.f;
-  for (int z = 0; z < nu; ++z) su += pu[(long long)z * 3 * H + c];
-  db_h[c] = su;
-  if (c < 2 * H) {
-    db_i[c] = su;
-  } else {
-    float sw = 0.f;
-    for (int z = 0; z < nw; ++z) sw += pw[(long long)z * 3 * H + c];
-    db_i[c] = sw;
+// Bias gradients from the column sums the two gradient GEMMs leave behind, one row per
+// row split: pu[nu][3H] (columns k_r w, k_z w, k_q w) and pw[nw][3H] (k_r w, k_z w, k_n w).
+// A workgroup covers 32 columns; its eight thread rows share the splits and meet in LDS.
+__global__ void __launch_bounds__(256)
+bias_reduce_kernel(const float* __restrict__ pu, int nu, const float* __restrict__ pw, int nw,
+                   float* __restrict__ db_i, float* __restrict__ db_h, int H) {
+  __shared__ float red[2][8][32];
+  const int lane = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  const int c = blockIdx.x * 32 + lane;
+  float su = 0.f, sw = 0.f;
+  if (c < 3 * H) {
+    for (int z = grp; z < nu; z += 8) su += pu[(long long)z * 3 * H + c];
+    if (c >= 2 * H)
+      for (int z = grp; z < nw; z += 8) sw += pw[(long long)z * 3 * H + c];
+  }
+  red[0][grp][lane] = su;
+  red[1][grp][lane] = sw;
+  __syncthreads();
+  if (grp == 0 && c < 3 * H) {
+    su = 0.f;
+    sw = 0.f;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      su += red[0][q][lane];
+      sw += red[1][q][lane];
+    }
+    db_h[c] = su;
+    db_i[c] = c < 2 * H ? su : sw;
   }
 }
 
@@ -1234,8 +1246,7 @@ size_t grad_partial_floats(int T, int B, int D, int H) {
   const long long Ktot = (long long)T * B;
   size_t su = (size_t)grad_splits(Ktot, 3 * H, H) * 3 * H * H;
   size_t sw = (size_t)grad_splits(Ktot, 3 * H, D) * 3 * H * D;
-  size_t sb = (size_t)(grad_splits(Ktot, 3 * H, H) * ((H + GT - 1) / GT) +
-                       grad_splits(Ktot, 3 * H, D) * ((D + GT - 1) / GT)) * 3 * H;
+  size_t sb = (size_t)(grad_splits(Ktot, 3 * H, H) + grad_splits(Ktot, 3 * H, D)) * 3 * H;
   return (su > sw ? su : sw) + sb;
 }
 
@@ -1269,7 +1280,7 @@ hipError_t launch_param_grads(const float* kap0, const float* w, const float* h,
     a.ntiles = (a.N + GT - 1) / GT;
     a.splits = splits;
     a.bpart = bpart[which];
-    nbpart[which] = splits * a.ntiles;
+    nbpart[which] = splits;
     if (which == 0) bpart[1] = bpart[0] + (size_t)nbpart[0] * M;
     dim3 grid((unsigned)((long long)a.mtiles * a.ntiles * splits));
     if (bf16 == 2)
@@ -1284,7 +1295,7 @@ hipError_t launch_param_grads(const float* kap0, const float* w, const float* h,
     hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
                        part, which == 0 ? dU : dW, n, splits);
   }
-  hipLaunchKernelGGL(bias_reduce_kernel, dim3((3 * H + 255) / 256), dim3(256), 0, s, bpart[0],
+  hipLaunchKernelGGL(bias_reduce_kernel, dim3((3 * H + 31) / 32), dim3(256), 0, s, bpart[0],
                      nbpart[0], bpart[1], nbpart[1], db_i, db_h, H);
   prof_end(3, 2.0 * (double)Ktot * M * (H + D),
            4.0 * (double)Ktot * (5.0 * H + H + H + D), s);

@@ -126,7 +126,7 @@ static int make_layout(const mgrit_gru_cfg* c, Layout* lay) {
   lay->WT = off;
   off = align_up(off + (size_t)3 * c->H * c->D * sizeof(float));
   lay->part = off;
-  off = align_up(off + grad_partial_floats(c->T, c->B, c->D, c->H) * sizeof(float));
+  off = align_up(off + grad_partial_floats(c->T, c->B, c->D, c->H, c->dtype) * sizeof(float));
   if (c->dtype == MGRIT_F32_BF16X3) {
     lay->U3 = off;
     off = align_up(off + (size_t)3 * 3 * c->H * c->H * 2);

@@ -79,7 +79,7 @@ hipError_t launch_transpose(const void* U, void* UT, int rows, int cols, int bf1
 // Weight gradients (Alg. 3 gradient line) from the level-0 coefficients kap0[(T+1),B,5H]
 // (row t = step t), the adjoint w[(T+1),B,H], the states h[(T+1),B,H] and x[T,B,D].
 // part: scratch of grad_partial_floats(...) floats.
-size_t grad_partial_floats(int T, int B, int D, int H);
+size_t grad_partial_floats(int T, int B, int D, int H, int bf16);
 // x: float (bf16 = 0) or bf16 (bf16 = 1)
 hipError_t launch_param_grads(const float* kap0, const float* w, const float* h, const void* x,
                               float* dW, float* dU, float* db_i, float* db_h, float* part,

@@ -640,8 +640,9 @@ hipError_t launch_transpose(const void* U, void* UT, int rows, int cols, int bf1
 // ---------------------------------------------------------------------------
 constexpr int GTK = 32;            // K-slice (rows of the sum) per iteration
 constexpr int GT = 128;            // output tile is GT x GT
-constexpr int GLD = GT + 32;       // LDS row stride in floats (keeps the two half-waves on
-                                   // different banks)
+constexpr int GLD = GT;            // LDS row stride in floats; odd rows swap their 32-column
+                                   // halves pairwise (column ^ 32), which keeps the two
+                                   // half-waves of an operand read on different banks
 
 struct GradArgs {
   const float* kap0;   // [(T+1),B,5H]
@@ -664,9 +665,9 @@ struct GradArgs {
 // z % 8 and all output tiles of a split run on that XCD: its rows of S and Bm are
 // fetched into one L2 only.
 template <class BT>
-__global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
-  __shared__ __attribute__((aligned(16))) float As[GTK * GLD];
-  __shared__ __attribute__((aligned(16))) float Bs[GTK * GLD];
+__global__ __launch_bounds__(256, 3) void grad_gemm_kernel(GradArgs a) {
+  __shared__ __attribute__((aligned(16))) float As[1][GTK * GLD];
+  __shared__ __attribute__((aligned(16))) float Bs[1][GTK * GLD];
   const int H = a.H, N = a.N, M = 3 * a.H;
   const int tiles = a.mtiles * a.ntiles;
   int tile, z;
@@ -718,39 +719,43 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
       rb[s] = ldg4w((const BT*)a.Bm + k * N + nc);
     }
   };
-  auto stash = [&](long long k0) {
+  const int wcol = (c4 * 4) ^ (((tid >> 5) & 1) << 5);     // slice rows kr and tid >> 5: same parity
+  auto stash = [&](long long k0, int buf) {
 #pragma unroll
     for (int s = 0; s < NCH; ++s) {
       const int kr = (tid >> 5) + s * 8;
       const bool k_ok = k0 + kr < kend;
       const floatx4 p = (k_ok && m_ok) ? rk[s] * rw[s] : zero4();
       colsum += p;
-      *reinterpret_cast<floatx4*>(&As[kr * GLD + c4 * 4]) = p;
-      *reinterpret_cast<floatx4*>(&Bs[kr * GLD + c4 * 4]) = (k_ok && n_ok) ? rb[s] : zero4();
+      *reinterpret_cast<floatx4*>(&As[buf][kr * GLD + wcol]) = p;
+      *reinterpret_cast<floatx4*>(&Bs[buf][kr * GLD + wcol]) = (k_ok && n_ok) ? rb[s] : zero4();
     }
   };
-  auto frags = [&](int p, float (&av)[2], float (&bv)[2]) {
+  auto frags = [&](int buf, int p, float (&av)[2], float (&bv)[2]) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) av[i] = As[(2 * p + lh) * GLD + wm * 64 + i * 32 + li];
+    for (int i = 0; i < 2; ++i)
+      av[i] = As[buf][(2 * p + lh) * GLD + wm * 64 + ((i ^ lh) << 5) + li];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) bv[j] = Bs[(2 * p + lh) * GLD + wn * 64 + j * 32 + li];
+    for (int j = 0; j < 2; ++j)
+      bv[j] = Bs[buf][(2 * p + lh) * GLD + wn * 64 + ((j ^ lh) << 5) + li];
   };
 
   const int nt = tile / a.mtiles;
   if (kbeg < kend) {
     fetch(kbeg);
-    stash(kbeg);
+    stash(kbeg, 0);
     __syncthreads();
+    constexpr int buf = 0;
     for (long long k0 = kbeg; k0 < kend; k0 += GTK) {
       const bool more = k0 + GTK < kend;
       if (more) fetch(k0 + GTK);
       __builtin_amdgcn_sched_barrier(0);
       float av[2][2], bv[2][2];
       __builtin_amdgcn_s_setprio(2);      // MFMA phase first at issue (see gemm_core.h)
-      frags(0, av[0], bv[0]);
+      frags(buf, 0, av[0], bv[0]);
 #pragma unroll
       for (int p = 0; p < GTK / 2; ++p) {
-        if (p + 1 < GTK / 2) frags(p + 1, av[(p + 1) & 1], bv[(p + 1) & 1]);
+        if (p + 1 < GTK / 2) frags(buf, p + 1, av[(p + 1) & 1], bv[(p + 1) & 1]);
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -771,13 +776,13 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
       __builtin_amdgcn_s_setprio(0);
       __syncthreads();
       if (more) {
-        stash(k0 + GTK);
+        stash(k0 + GTK, buf);
         __syncthreads();
       }
     }
   }
   {
-    float* red = As;                       // [8][GT] floats (the slices are no longer read)
+    float* red = As[0];                    // [8][GT] floats (the slices are no longer read)
     __syncthreads();
 #pragma unroll
     for (int e = 0; e < 4; ++e) red[(tid >> 5) * GT + c4 * 4 + e] = colsum[e];
@@ -1215,24 +1220,28 @@ bias_reduce_kernel(const float* __restrict__ pu, int nu, const float* __restrict
   }
 }
 
-// Row splits of a gradient GEMM.  Enough workgroups for at least two per slot (512
-// slots: 256 CUs x 2 resident workgroups); from 8 splits on, a multiple of 8 (whole
-// splits per XCD) chosen so that the grid is close to a whole number of rounds over the
-// slots: a partly filled last round costs as much time as a full one.
-static int grad_splits(long long Ktot, int M, int N) {
+// Row splits of a gradient GEMM.  Enough workgroups for at least two per slot (256 CUs x
+// the kernel's resident workgroups: three for the fp32 kernel, two for the others); a
+// multiple of 8 (whole splits per XCD) unless fewer than 8 fill the slots as well, chosen
+// so that the grid is close to a whole number of rounds over the slots: a partly filled
+// last round costs as much time as a full one.
+static int grad_splits(long long Ktot, int M, int N, int bf16) {
   const long long tiles = (long long)((M + GT - 1) / GT) * ((N + GT - 1) / GT);
-  const long long slots = 512;
+  const long long slots = bf16 == 0 ? 768 : 512;
   long long maxs = (Ktot + 4 * GTK - 1) / (4 * GTK);   // at least 4 slices per split
   if (maxs > 256) maxs = 256;
   if (maxs < 1) maxs = 1;
   long long want = (2 * slots + tiles - 1) / tiles;
   if (want > maxs) want = maxs;
-  if (want < NXCD) return (int)want;
-  long long best = want / NXCD * NXCD;
-  double best_eff = 0.0;
-  for (long long sp = (want + NXCD - 1) / NXCD * NXCD; sp <= maxs && sp <= 4 * want; sp += NXCD) {
+  auto efficiency = [&](long long sp) {
     const double rounds = (double)(tiles * sp) / (double)slots;
-    const double eff = rounds / (double)(long long)(rounds + 0.999999);
+    return rounds / (double)(long long)(rounds + 0.999999);
+  };
+  long long best = want < NXCD ? want : want / NXCD * NXCD;
+  double best_eff = want < NXCD ? efficiency(want) : 0.0;
+  if (best_eff >= 0.97) return (int)best;
+  for (long long sp = (want + NXCD - 1) / NXCD * NXCD; sp <= maxs && sp <= 4 * want; sp += NXCD) {
+    const double eff = efficiency(sp);
     if (eff > best_eff + 0.02) {
       best_eff = eff;
       best = sp;
@@ -1242,12 +1251,12 @@ static int grad_splits(long long Ktot, int M, int N) {
   return (int)best;
 }
 
-size_t grad_partial_floats(int T, int B, int D, int H) {
+size_t grad_partial_floats(int T, int B, int D, int H, int bf16) {
   const long long Ktot = (long long)T * B;
-  size_t su = (size_t)grad_splits(Ktot, 3 * H, H) * 3 * H * H;
-  size_t sw = (size_t)grad_splits(Ktot, 3 * H, D) * 3 * H * D;
-  size_t sb = (size_t)(grad_splits(Ktot, 3 * H, H) + grad_splits(Ktot, 3 * H, D)) * 3 * H;
-  return (su > sw ? su : sw) + sb;
+  const size_t zu = (size_t)grad_splits(Ktot, 3 * H, H, bf16);
+  const size_t zw = (size_t)grad_splits(Ktot, 3 * H, D, bf16);
+  const size_t su = zu * 3 * H * H, sw = zw * 3 * H * D;
+  return (su > sw ? su : sw) + (zu + zw) * 3 * H;
 }
 
 hipError_t launch_param_grads(const float* kap0, const float* w, const float* h, const void* x,
@@ -1256,8 +1265,8 @@ hipError_t launch_param_grads(const float* kap0, const float* w, const float* h,
   const long long Ktot = (long long)T * B;
   const int M = 3 * H;
   prof_begin(3, s);
-  const size_t su = (size_t)grad_splits(Ktot, M, H) * M * H;
-  const size_t sw = (size_t)grad_splits(Ktot, M, D) * M * D;
+  const size_t su = (size_t)grad_splits(Ktot, M, H, bf16) * M * H;
+  const size_t sw = (size_t)grad_splits(Ktot, M, D, bf16) * M * D;
   float* bpart[2];
   int nbpart[2];
   bpart[0] = part + (su > sw ? su : sw);
@@ -1272,7 +1281,7 @@ hipError_t launch_param_grads(const float* kap0, const float* w, const float* h,
     a.Ktot = Ktot;
     a.B = B;
     a.H = H;
-    const int splits = grad_splits(Ktot, M, a.N);
+    const int splits = grad_splits(Ktot, M, a.N, bf16);
     long long per = (Ktot + splits - 1) / splits;
     const int slice = bf16 == 1 ? HB_TK : GTK;      // (both multiples of the 32 of bf16 = 2)
     a.Kper = (per + slice - 1) / slice * slice;

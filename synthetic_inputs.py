@@ -156,3 +156,22 @@ def random_small(seed: int, T: int, B: int, D: int, H: int, scale: float = 0.5,
         "dL_dhT": rng.standard_normal((B, H)),
     }
     return {k: np.ascontiguousarray(v, dtype=np.float32) for k, v in d.items()}
+
+
+def random_ode(seed: int, T: int, B: int, D: int, H: int, scale: Optional[float] = None,
+               h0_random: bool = True) -> Dict[str, np.ndarray]:
+    """Inputs of the demonstration ODE (appendix, Eq. 17): data d[T,B,D] ~ N(0,1),
+    randomly selected time-independent weights A[H,H], Bw[H,D] and bias b[H]
+    (N(0,1) scaled by `scale`, default 1/sqrt(fan-in)), initial state h0[B,H].
+    Draw order: d, A, Bw, b, h0."""
+    rng = np.random.default_rng(seed)
+    sa = scale if scale is not None else 1.0 / np.sqrt(H)
+    sb = scale if scale is not None else 1.0 / np.sqrt(D)
+    out = {
+        "d": rng.standard_normal((T, B, D)),
+        "A": sa * rng.standard_normal((H, H)),
+        "Bw": sb * rng.standard_normal((H, D)),
+        "b": 0.5 * rng.standard_normal(H),
+        "h0": (rng.standard_normal((B, H)) if h0_random else np.zeros((B, H))),
+    }
+    return {k: np.ascontiguousarray(v, dtype=np.float32) for k, v in out.items()}

@@ -213,6 +213,30 @@ MGRIT_API int mgrit_gru_backward_steps(const mgrit_gru_cfg* cfg, const void* W, 
                        float* dW, float* dU, float* db_i, float* db_h, float* dx,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* A second propagator behind the same forward cycle: the demonstration ODE of the
+ * appendix "Why does MGRIT work?" (Eq. 17),
+ *     dh/dt = -h/2 + sigmoid(A h + B d(t) + b),
+ * forward propagation only, as in the paper.  The appendix does not print the
+ * discretisation; here a step is forward Euler over one data sample,
+ *     Phi_dt(h_{t-1}; d_t) = h_{t-1} + dt (-h_{t-1}/2 + sigmoid(A h_{t-1} + B d_t + b)),
+ * and level l of the hierarchy uses the step size cf^l dt with the data of its own
+ * points (the rule of Sec. 3.3).
+ *   cfg: T, B, D, H, cf, levels, iters, fine_relax as for the GRU entry points;
+ *     dtype must be MGRIT_F32 and flags 0 (MGRIT_E_UNSUPPORTED otherwise);
+ *     propagator is not read.  dt: level-0 step size, finite and > 0.
+ *   A[H,H], Bw[H,D], b[H], d[T,B,D] (row t-1 holds d_t), h0[B,H]: device, float.
+ *   h_out / h_inout[(T+1),B,H], resnorm_out[iters]: as for gru_serial_scan and
+ *     mgrit_gru_forward.
+ *   workspace: mgrit_gru_workspace_bytes(cfg) bytes serve these calls too. */
+MGRIT_API int ode_serial_scan(const mgrit_gru_cfg* cfg, float dt, const float* A,
+                    const float* Bw, const float* b, const float* d,
+                    const float* h0, float* h_out,
+                    void* workspace, size_t workspace_bytes, void* stream);
+MGRIT_API int mgrit_ode_forward(const mgrit_gru_cfg* cfg, float dt, const float* A,
+                      const float* Bw, const float* b, const float* d,
+                      const float* h0, float* h_inout, float* resnorm_out,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
 /* Name of an error code (host string with static storage). */
 MGRIT_API const char* mgrit_gru_strerror(int code);
 

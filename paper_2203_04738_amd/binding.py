@@ -72,6 +72,9 @@ def lib() -> ctypes.CDLL:
                                                  fp, fp, vp, sz, vp]
     L.mgrit_gru_backward_steps.argtypes = [cfgp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, fp, fp,
                                            fp, fp, vp, sz, vp]
+    cf = ctypes.c_float
+    L.ode_serial_scan.argtypes = [cfgp, cf, fp, fp, fp, fp, fp, fp, vp, sz, vp]
+    L.mgrit_ode_forward.argtypes = [cfgp, cf, fp, fp, fp, fp, fp, fp, fp, vp, sz, vp]
     L.mgrit_gru_strerror.argtypes = [ctypes.c_int]
     L.mgrit_gru_strerror.restype = ctypes.c_char_p
     L.mgrit_gru_profile_enable.argtypes = [ctypes.c_int]
@@ -87,7 +90,7 @@ def lib() -> ctypes.CDLL:
     for name in ("mgrit_gru_workspace_bytes", "gru_serial_scan", "mgrit_gru_forward",
                  "gru_serial_scan_backward", "mgrit_gru_backward",
                  "gru_serial_scan_backward_steps", "mgrit_gru_backward_steps",
-                 "mgrit_gru_profile_enable", "mgrit_gru_profile_read_shape",
+                 "ode_serial_scan", "mgrit_ode_forward", "mgrit_gru_profile_enable", "mgrit_gru_profile_read_shape",
                  "mgrit_gru_profile_read"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
@@ -206,6 +209,27 @@ def mgrit_gru_backward_steps(cfg, W, U, b_i, b_h, x, h, dL_dh, w_inout, resnorm_
         _ptr(dx, "dx", f32),
         _ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()),
         "mgrit_gru_backward_steps")
+
+
+def ode_serial_scan(cfg, dt, A, Bw, b, d, h0, h_out, workspace) -> None:
+    import torch
+    f32 = torch.float32
+    _check(lib().ode_serial_scan(
+        ctypes.byref(cfg), float(dt), _ptr(A, "A", f32), _ptr(Bw, "Bw", f32), _ptr(b, "b", f32),
+        _ptr(d, "d", f32), _ptr(h0, "h0", f32), _ptr(h_out, "h_out", f32),
+        _ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()),
+        "ode_serial_scan")
+
+
+def mgrit_ode_forward(cfg, dt, A, Bw, b, d, h0, h_inout, resnorm_out, workspace) -> None:
+    import torch
+    f32 = torch.float32
+    _check(lib().mgrit_ode_forward(
+        ctypes.byref(cfg), float(dt), _ptr(A, "A", f32), _ptr(Bw, "Bw", f32), _ptr(b, "b", f32),
+        _ptr(d, "d", f32), _ptr(h0, "h0", f32), _ptr(h_inout, "h_inout", f32),
+        _ptr(resnorm_out, "resnorm_out", f32),
+        _ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()),
+        "mgrit_ode_forward")
 
 
 def mgrit_gru_profile_enable(on: bool) -> None:

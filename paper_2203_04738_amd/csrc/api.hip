@@ -164,6 +164,7 @@ struct FwdCtx {
   float* tmp;
   double* norm;     // accumulator of the current cycle (may be null)
   float* emit_kap;  // level-0 coefficient array the closing relaxation also fills (or null)
+  float dt;         // step size of level 0 (1 for the GRU propagators, Sec. 3.3)
   hipStream_t s;
 };
 
@@ -179,7 +180,7 @@ static PhiArgs phi_base(const FwdCtx& x, int l) {
   a.g = x.gl[l];
   a.B = x.c->B;
   a.H = x.c->H;
-  a.gamma = (float)x.lay->S[l];
+  a.gamma = (float)x.lay->S[l] * x.dt;
   a.propagator = x.c->propagator;
   a.bf16 = x.c->dtype;      // the enum values are the kernels' operand forms
   return a;
@@ -301,21 +302,33 @@ static int run_projection(const mgrit_gru_cfg* c, const Layout& lay, char* base,
     CHECK_HIP(launch_split3((const float*)W, base + lay.W3, 3LL * c->H * c->D, s));
     W = base + lay.W3;
   }
-  CHECK_HIP(launch_projection(x, W, b_i, (float*)(base + lay.P), (long long)c->T * c->B, 3 * c->H,
+  const int width = c->propagator == PROP_ODE_DEMO ? c->H : 3 * c->H;
+  CHECK_HIP(launch_projection(x, W, b_i, (float*)(base + lay.P), (long long)c->T * c->B, width,
                               c->D, c->dtype, s));
   return MGRIT_OK;
 }
 
+// ode_dt != 0: the demonstration ODE (W = Bw[H,D], U = A[H,H], b_i = b, b_h unused) with
+// level-0 step size ode_dt; the propagator field of the caller's cfg is not read.
 static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, const void* U,
                         const float* b_i, const float* b_h, const void* x, const float* h0,
-                        float* h, float* resnorm, void* ws, size_t ws_bytes, void* stream) {
-  int rc = check_cfg(cin, !serial);
+                        float* h, float* resnorm, void* ws, size_t ws_bytes, void* stream,
+                        float ode_dt = 0.f) {
+  if (!cin) return MGRIT_E_NULL;
+  mgrit_gru_cfg c = *cin;
+  const bool ode = ode_dt != 0.f;
+  if (ode) {
+    if (!(ode_dt > 0.f) || !(ode_dt < 1e30f)) return MGRIT_E_SIZE;
+    c.propagator = MGRIT_PROP_IMPLICIT;     // (any valid value for the checks below)
+  }
+  int rc = check_cfg(&c, !serial);
   if (rc) return rc;
+  if (ode && (c.dtype != MGRIT_F32 || c.flags != 0)) return MGRIT_E_UNSUPPORTED;
   if (!W || !U || !b_i || !b_h || !x || !h0 || !h || !ws) return MGRIT_E_NULL;
   if (misaligned(W) || misaligned(U) || misaligned(x) || misaligned(h0) || misaligned(h) ||
       misaligned(ws))
     return MGRIT_E_ALIGN;
-  mgrit_gru_cfg c = *cin;
+  if (ode) c.propagator = PROP_ODE_DEMO;
   if (serial) {
     c.levels = 1;
     c.cf = 1;
@@ -339,6 +352,7 @@ static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, co
   }
   ctx.b_h = b_h;
   ctx.P = (const float*)(base + lay.P);
+  ctx.dt = ode ? ode_dt : 1.f;
   ctx.s = s;
   ctx.tmp = (float*)(base + lay.tmp);
   ctx.ul[0] = h;
@@ -653,6 +667,23 @@ int mgrit_gru_forward(const mgrit_gru_cfg* cfg, const void* W, const void* U, co
                       float* resnorm_out, void* workspace, size_t workspace_bytes, void* stream) {
   return forward_impl(cfg, false, W, U, b_i, b_h, x, h0, h_inout, resnorm_out, workspace,
                       workspace_bytes, stream);
+}
+
+int ode_serial_scan(const mgrit_gru_cfg* cfg, float dt, const float* A, const float* Bw,
+                    const float* b, const float* d, const float* h0, float* h_out,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+  if (!(dt > 0.f)) return MGRIT_E_SIZE;
+  return forward_impl(cfg, true, Bw, A, b, b, d, h0, h_out, nullptr, workspace, workspace_bytes,
+                      stream, dt);
+}
+
+int mgrit_ode_forward(const mgrit_gru_cfg* cfg, float dt, const float* A, const float* Bw,
+                      const float* b, const float* d, const float* h0, float* h_inout,
+                      float* resnorm_out, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+  if (!(dt > 0.f)) return MGRIT_E_SIZE;
+  return forward_impl(cfg, false, Bw, A, b, b, d, h0, h_inout, resnorm_out, workspace,
+                      workspace_bytes, stream, dt);
 }
 
 int gru_serial_scan_backward(const mgrit_gru_cfg* cfg, const void* W, const void* U,

@@ -65,7 +65,15 @@ struct AdjArgs {
   const void* UT3;     // bf16 == 2: the three bf16 terms of UT, [3][H,3H]
 };
 
+// Internal propagator code (beside the public MGRIT_PROP_* values): the forward-Euler
+// step of the appendix's demonstration ODE (Eq. 17).  PhiArgs then reads U = A[H,H],
+// P rows of width H (B d + b), gamma = step size of the level; b_h is unused.
+constexpr int PROP_ODE_DEMO = 100;
+
+// (dispatches to launch_ode_step for PROP_ODE_DEMO)
 hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s);
+// modes STEP_RELAX, STEP_RESID, STEP_RHS; fp32 operands
+hipError_t launch_ode_step(const PhiArgs& a, hipStream_t s);
 hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s);
 
 // P[M,N] = X[M,K] W[N,K]^T + bias[N]

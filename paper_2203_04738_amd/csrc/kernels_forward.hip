@@ -6,6 +6,7 @@
 #include <type_traits>
 
 #include "common.h"
+#include "gates.h"
 #include "gemm_core.h"
 #include "gemm_core_bf16.h"
 #include "skinny.h"
@@ -168,20 +169,6 @@ hipError_t launch_projection(const void* X, const void* W, const float* bias, fl
 // ---------------------------------------------------------------------------
 // Fused level step
 // ---------------------------------------------------------------------------
-// Gate nonlinearities on the hardware exp2 / reciprocal units (each within 1 ulp):
-// absolute error of sigmoid and tanh about 1e-7, far inside the fp32 parity bar,
-// at a fraction of the instruction count of the library routines.
-__device__ inline float fast_rcp(float a) { return __builtin_amdgcn_rcpf(a); }
-__device__ inline float sigmoidf_(float a) {
-  return fast_rcp(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896341f * a));
-}
-__device__ inline float tanhf_(float a) {
-  // tanh(a) = sign(a) (1 - e)/(1 + e), e = exp(-2|a|) in (0, 1]
-  const float e = __builtin_amdgcn_exp2f(-2.88539008177792681f * fabsf(a));
-  const float t = (1.0f - e) * fast_rcp(1.0f + e);
-  return copysignf(t, a);
-}
-
 // Operands of one output element that do not depend on the contraction: they are
 // loaded separately so that the few-row kernel can fetch them before its dot
 // products instead of after.
@@ -696,6 +683,7 @@ static void launch_phi_skinny(const PhiArgs& a, dim3 grid, hipStream_t s) {
 
 hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s) {
   if (a.nk <= 0) return hipSuccess;
+  if (a.propagator == PROP_ODE_DEMO) return launch_ode_step(a, s);
   const long long R = (long long)a.nk * a.B;
   auto tiles = [&](int tm, int tn) { return ((R + tm - 1) / tm) * ((a.H + tn - 1) / tn); };
   const int kind = R <= 2 * SK_MAXROWS ? 4 : 0;

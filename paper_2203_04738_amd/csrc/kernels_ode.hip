@@ -1,0 +1,187 @@
+// Forward-Euler level step of the demonstration ODE of the paper's appendix
+// ("Why does MGRIT work?", Eq. 17),
+//   dh/dt = -h/2 + sigmoid(A h + B d(t) + b),
+//   Phi_dt(h; d) = h + dt * (-h/2 + sigmoid(A h + P)),   P = B d + b  (precomputed),
+// as a second propagator behind the forward MGRIT drivers: the same launch
+// description (PhiArgs: U = A[H,H], P rows of width H, gamma = dt of the level, b_h
+// unused) and the same epilogue modes as the GRU step, forward propagation only.
+#include "common.h"
+#include "gates.h"
+#include "gemm_core.h"
+
+namespace mg {
+
+// Element offsets (column 0) of one row (level point, batch element) of a launch:
+// input state, projection row, out/cur/g, coarse array.
+struct OdeRow {
+  long long in, p, o, a;
+};
+__device__ inline OdeRow ode_row(const PhiArgs& a, long long r) {
+  const long long pt = (unsigned)r / (unsigned)a.B;   // rows < 2^31: 32-bit division
+  const int b = (int)(r - pt * a.B);
+  OdeRow ro;
+  ro.in = (a.in.at(pt) * a.B + b) * a.H;
+  ro.p = (a.p.at(pt) * a.B + b) * a.H;
+  ro.o = (a.o.at(pt) * a.B + b) * a.H;
+  ro.a = (a.a.at(pt) * a.B + b) * a.H;
+  return ro;
+}
+
+struct OdeEpiIn4 {
+  floatx4 p, h, gval, cur;
+};
+
+// Epilogue of one MFMA tile over the staged sums (A h): the Euler update and the
+// mode's outputs, moved as float4 (see EpiStage).
+template <class C, int MODE>
+__device__ inline void ode_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const OdeRow* rowtab,
+                                         float* stage, long long m0, int n0, long long R,
+                                         double& nrm) {
+  typedef EpiStage<C> E;
+  const int H = a.H;
+  const int c4 = E::col4();
+  const int j = n0 + c4 * 4;
+  const bool colok = E::active() && j < H;
+  const int jc = colok ? j : H - 4;                     // clamped columns are never stored
+  const float dt = a.gamma;
+#pragma unroll
+  for (int ba = 0; ba < C::BM; ++ba) {
+    __syncthreads();                                    // staging area no longer read
+    E::write(acc, ba, stage);
+    OdeEpiIn4 in[E::ITEMS];
+    long long oo[E::ITEMS], oa[E::ITEMS];
+    int trow[E::ITEMS];
+#pragma unroll
+    for (int it = 0; it < E::ITEMS; ++it) {
+      trow[it] = E::tile_row(E::staged_row(it), ba);
+      const OdeRow ro = rowtab[trow[it]];               // rows beyond the launch hold its last row
+      oo[it] = ro.o;
+      oa[it] = ro.a;
+      in[it].p = ldg4(a.P + ro.p + jc);
+      in[it].h = ldg4(a.u_in + ro.in + jc);
+      in[it].gval = a.g ? ldg4(a.g + ro.o + jc) : zero4();
+      in[it].cur = (MODE == STEP_RESID || MODE == STEP_RHS) ? ldg4(a.u + ro.o + jc) : zero4();
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < E::ITEMS; ++it) {
+      const floatx4 dot = E::read(stage, 0, E::staged_row(it), c4);
+      if (!colok || m0 + trow[it] >= R) continue;
+      floatx4 hn;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float h = in[it].h[i];
+        hn[i] = h + dt * (sigmoidf_(dot[i] + in[it].p[i]) - 0.5f * h);
+      }
+      const long long oi = oo[it] + j;
+      if (MODE == STEP_RELAX) {
+        *reinterpret_cast<floatx4*>(a.u + oi) = hn + in[it].gval;
+      } else if (MODE == STEP_RESID) {
+        const floatx4 res = in[it].cur - hn - in[it].gval;
+        const long long ai = oa[it] + j;
+        *reinterpret_cast<floatx4*>(a.gc + ai) = -res;
+        *reinterpret_cast<floatx4*>(a.uc + ai) = in[it].cur;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) nrm += (double)res[i] * (double)res[i];
+      } else {  // STEP_RHS
+        *reinterpret_cast<floatx4*>(a.g + oi) = (in[it].cur - hn) + in[it].gval;
+      }
+    }
+  }
+}
+
+// out[R,H] rows = (level point, batch element); the contraction is h[R,H] . A[H,H]^T on
+// the fp32 MFMA tile core, one workgroup per (row tile, column tile).
+template <class C, int MODE>
+__global__ __launch_bounds__(C::NT, C::MINWG) void ode_step_kernel(PhiArgs a) {
+  constexpr int LDSF =
+      C::LDS_FLOATS > EpiStage<C>::FLOATS ? C::LDS_FLOATS : EpiStage<C>::FLOATS;
+  __shared__ __attribute__((aligned(16))) float lds[LDSF];
+  const int H = a.H, B = a.B;
+  const long long R = (long long)a.nk * B;
+  long long rt;
+  int ct;
+  if (!xcd_tile(blockIdx.x, (R + C::TM - 1) / C::TM, (H + C::TN - 1) / C::TN, rt, ct)) return;
+  const long long m0 = rt * C::TM;
+  const int n0 = ct * C::TN;
+  const int tid = threadIdx.x;
+  __shared__ OdeRow rowtab[C::TM];
+  if (tid < C::TM) {
+    long long r = m0 + tid;
+    if (r >= R) r = R - 1;
+    rowtab[tid] = ode_row(a, r);
+  }
+  // (visible to all waves after the barriers inside the contraction)
+
+  const float* arow[C::A_CHUNKS];
+  const float* brow[C::B_CHUNKS];
+#pragma unroll
+  for (int s = 0; s < C::A_CHUNKS; ++s) {
+    long long r = m0 + chunk_row<C>(s);
+    if (r >= R) r = R - 1;     // clamped rows are never stored
+    const long long pt = (unsigned)r / (unsigned)B;
+    const int b = (int)(r - pt * B);
+    arow[s] = a.u_in + (a.in.at(pt) * B + b) * H;
+  }
+#pragma unroll
+  for (int s = 0; s < C::B_CHUNKS; ++s) {
+    int j = n0 + chunk_row<C>(s);
+    if (j >= H) j = H - 1;
+    brow[s] = (const float*)a.U + (long long)j * H;
+  }
+  Acc<C> acc;
+  acc.zero();
+  auto la = [&](int s, int k) { return ldg4(arow[s] + k); };
+  auto lb = [&](int s, int k) { return ldg4(brow[s] + k); };
+  if (H % C::TK == 0)
+    gemm_nt_tile<C, false>(acc, H, la, lb, Identity4(), Identity4(), lds);
+  else
+    gemm_nt_tile<C, true>(acc, H, la, lb, Identity4(), Identity4(), lds);
+
+  double nrm = 0.0;
+  ode_tile_epilogue<C, MODE>(a, acc, rowtab, lds, m0, n0, R, nrm);
+  if (MODE == STEP_RESID && a.norm) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) nrm += __shfl_down(nrm, off, 64);
+    if ((tid & 63) == 0) atomicAdd(a.norm, nrm);
+  }
+}
+
+typedef TileCfg<2, 2, 2, 2, 1> OdeBig;                  // 128 x 128, 256 threads
+typedef TileCfg<2, 2, 1, 1, 1> OdeMid;                  //  64 x 64, 256 threads
+typedef TileCfg<1, 1, 1, 1, 1, 128, 1, 4> OdeSmall;     //  32 x 32, 4 waves splitting K
+
+template <class C>
+static void launch_ode_cfg(const PhiArgs& a, hipStream_t s) {
+  const long long R = (long long)a.nk * a.B;
+  dim3 grid((unsigned)xcd_grid((R + C::TM - 1) / C::TM, (a.H + C::TN - 1) / C::TN));
+  dim3 block(C::NT);
+  if (a.mode == STEP_RELAX)
+    hipLaunchKernelGGL((ode_step_kernel<C, STEP_RELAX>), grid, block, 0, s, a);
+  else if (a.mode == STEP_RESID)
+    hipLaunchKernelGGL((ode_step_kernel<C, STEP_RESID>), grid, block, 0, s, a);
+  else
+    hipLaunchKernelGGL((ode_step_kernel<C, STEP_RHS>), grid, block, 0, s, a);
+}
+
+// Tile shape by the number of workgroups it gives: 128 x 128 tiles when they alone fill
+// the chip, 64 x 64 below that, and for a few rows (the coarsest level's serial
+// propagation) 32 x 32 tiles whose four waves split K.
+hipError_t launch_ode_step(const PhiArgs& a, hipStream_t s) {
+  if (a.nk <= 0) return hipSuccess;
+  if (a.mode != STEP_RELAX && a.mode != STEP_RESID && a.mode != STEP_RHS)
+    return hipErrorInvalidValue;
+  const long long R = (long long)a.nk * a.B;
+  auto tiles = [&](int tm, int tn) { return ((R + tm - 1) / tm) * ((a.H + tn - 1) / tn); };
+  prof_begin(6, s, R, a.mode);
+  if (tiles(OdeBig::TM, OdeBig::TN) >= 384)
+    launch_ode_cfg<OdeBig>(a, s);
+  else if (R > 32 && tiles(OdeMid::TM, OdeMid::TN) >= 256)
+    launch_ode_cfg<OdeMid>(a, s);
+  else
+    launch_ode_cfg<OdeSmall>(a, s);
+  prof_end(6, 2.0 * (double)R * a.H * a.H, 16.0 * (double)R * a.H, s);
+  return hipGetLastError();
+}
+
+}  // namespace mg

@@ -110,6 +110,33 @@ def test_step_loss_entry_points_validate_their_arguments_without_a_gpu():
                                       p, p, p, p, 16, None) == -5
 
 
+def test_ode_entry_points_validate_their_arguments_without_a_gpu():
+    L = mg.lib()
+    cfg = MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, iters=1)
+    p = 4096
+    dt = ctypes.c_float(0.25)
+    assert L.mgrit_ode_forward(ctypes.byref(cfg), dt, None, None, None, None, None, None, None,
+                               None, 0, None) == -1
+    assert L.ode_serial_scan(ctypes.byref(cfg), dt, p, p, p, p, p, p, p, 16, None) == -5
+    assert L.mgrit_ode_forward(ctypes.byref(cfg), dt, p, p, p, p, p, p, None, p, 16, None) == -5
+    # step size must be positive and finite
+    for bad in (0.0, -1.0, float("nan"), float("inf")):
+        assert L.mgrit_ode_forward(ctypes.byref(cfg), ctypes.c_float(bad), p, p, p, p, p, p, None,
+                                   p, 1 << 30, None) == -2
+    # fp32 operands and no flags only
+    for kw in ({"dtype": mg.MGRIT_BF16}, {"dtype": mg.MGRIT_F32_BF16X3},
+               {"flags": mg.MGRIT_ZERO_STATE_GUESS}):
+        c2 = MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, iters=1, **kw)
+        assert L.mgrit_ode_forward(ctypes.byref(c2), dt, p, p, p, p, p, p, None, p, 1 << 30,
+                                   None) == -8
+    # the propagator field is not read; the hierarchy is checked
+    c3 = MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, iters=1, propagator=77)
+    assert L.mgrit_ode_forward(ctypes.byref(c3), dt, p, p, p, p, p, p, None, p, 16, None) == -5
+    c4 = MgritGruCfg(60, 2, 16, 32, cf=8, levels=2, iters=1)
+    assert L.mgrit_ode_forward(ctypes.byref(c4), dt, p, p, p, p, p, p, None, p, 1 << 30,
+                               None) == -3
+
+
 def test_strerror_names_codes():
     assert mg.mgrit_gru_strerror(0) == "ok"
     assert "divide" in mg.mgrit_gru_strerror(-3)

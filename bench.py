@@ -43,12 +43,14 @@ def parse():
     ap.add_argument("--layers", type=int, default=1,
                     help="2: a stack of two GRU layers (layer 2 reads the states of layer 1; "
                          "fp32 workloads only), each solved by its own MGRIT solve")
-    ap.add_argument("--study", choices=["convergence", "training"], default=None,
+    ap.add_argument("--study", choices=["convergence", "training", "ode"], default=None,
                     help="convergence: residual per cycle, forward and backward, for the paper's "
                          "hierarchies at T = 128 (cf 2 / 4 / 8 with 6 / 3 / 2 levels) and for the "
                          "Classic coarse propagator.  training: the training loop of Alg. 3 with Adam "
                          "on a synthetic classification task, MGRIT (2 forward / 1 backward cycles) "
-                         "against serial propagation from the same start.  One JSON line each")
+                         "against serial propagation from the same start.  ode: the appendix's "
+                         "demonstration ODE (Eq. 17) as the propagator of the forward cycle, at the "
+                         "sizes of --workload, against its serial propagation.  One JSON line each")
     ap.add_argument("--train-steps", type=int, default=300)
     ap.add_argument("--operands", choices=["stored", "bf16x3"], default="stored",
                     help="stored: the workload's own form (fp32 or bf16 MFMA).  bf16x3 (fp32 "
@@ -345,6 +347,143 @@ def study_convergence(args):
                       "cycles": cycles, "rows": rows}))
 
 
+def study_ode(args):
+    """Forward MGRIT with the demonstration ODE of the appendix (Eq. 17; forward Euler,
+    step size dt on level 0) as propagator, at the sizes and hierarchy of --workload,
+    against serial propagation on the same GPU.  A step is one forward solve (projection
+    included) over one batch of synthetic data."""
+    import numpy as np
+    import torch
+
+    import paper_2203_04738_amd as mg
+    from paper_2203_04738_amd.binding import MgritGruCfg
+    from synthetic_inputs import WORKLOADS, random_ode
+
+    wl = WORKLOADS[args.workload]
+    if wl.dtype != "fp32":
+        print("bench.py: --study ode runs fp32 workloads", file=sys.stderr)
+        sys.exit(2)
+    T, B, D, H = wl.T, wl.B, wl.D, wl.H
+    iters = wl.fwd_iters if args.fwd_iters is None else args.fwd_iters
+    fine_relax = 1 if args.fine_relax == "FCF" else 0
+    # forward Euler must stay stable on the coarsest level (step size cf^(levels-1) dt;
+    # the decay term alone needs it below 4): the coarsest step is at most 1
+    dt = min(1.0 / 16, 1.0 / wl.cf ** (wl.levels - 1))
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    p = random_ode(0, T, B, D, H, h0_random=False)
+    t = {k: torch.from_numpy(v).to(dev) for k, v in p.items()}
+    P = (t["A"], t["Bw"], t["b"], t["d"], t["h0"])
+
+    def cfg(n, levels=wl.levels):
+        return MgritGruCfg(T, B, D, H, cf=wl.cf, levels=levels, iters=n, fine_relax=fine_relax)
+
+    ws = torch.empty(mg.mgrit_gru_workspace_bytes(cfg(max(iters, 1))), dtype=torch.uint8,
+                     device=dev)
+    h = torch.zeros(T + 1, B, H, device=dev)
+    hs = torch.zeros(T + 1, B, H, device=dev)
+    res = torch.zeros(max(iters, 1), device=dev)
+
+    def mgrit_step():
+        h[1:].zero_()
+        mg.mgrit_ode_forward(cfg(iters), dt, *P, h, res, ws)
+
+    def serial_step():
+        mg.ode_serial_scan(cfg(1), dt, *P, hs, ws)
+
+    def timed(fn, warmup, steps):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    sec = timed(mgrit_step, args.warmup, args.steps)
+    residuals = res.cpu().tolist()
+    ssec = None if args.no_serial else timed(serial_step, 1, max(2, args.steps // 3))
+    err = None
+    if ssec is not None:
+        err = float(torch.max(torch.abs(h - hs)) / torch.max(torch.abs(hs)))
+
+    # event-timed pass: the level-0 relaxation launches of the ODE step kernel
+    rows0 = (T // wl.cf) * B
+    mg.mgrit_gru_profile_enable(True)
+    for _ in range(args.steps):
+        mgrit_step()
+    torch.cuda.synchronize()
+    mg.mgrit_gru_profile_enable(False)
+    n0, ms0, fl0, _ = mg.mgrit_gru_profile_read_shape(6, rows0, 0)
+    nall, msall, flall, _ = mg.mgrit_gru_profile_read(6)
+    npj, mspj, flpj, _ = mg.mgrit_gru_profile_read(2)
+    roof = None
+    if n0:
+        ach = fl0 / ms0 / 1e9
+        roof = {"kernel": f"ode_step (fused forward-Euler level step, MFMA tiles), level-0 "
+                          f"relaxation launches ({rows0} rows x H={H})",
+                "bound": "mfma", "achieved": ach, "peak": MI355X_PEAK["fp32_TFLOPs"],
+                "unit": "TFLOP/s", "frac": ach / MI355X_PEAK["fp32_TFLOPs"], "traffic": None,
+                "algorithmic_flops_per_launch": fl0 / n0, "avg_launch_us": 1e3 * ms0 / n0,
+                "launches_per_step": n0 / args.steps}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import demo_ode_oracle as ode
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([q.get("num_threads", 1) for q in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        unit = wl.cf ** (wl.levels - 1)
+
+        def run(Tt):
+            q = random_ode(0, Tt, B, D, H, h0_random=False)
+            t0 = time.perf_counter()
+            ode.ode_mgrit_forward(q["A"], q["Bw"], q["b"], q["d"], q["h0"],
+                                  np.zeros((Tt + 1, B, H)), dt, wl.cf, wl.levels, iters,
+                                  fine_relax_fcf=bool(fine_relax))
+            return time.perf_counter() - t0
+
+        n, n_max = min(16, T // unit), T // unit
+        Tt = n * unit
+        el = run(Tt)
+        if el < 8.0 and n < n_max:     # enlarge the sample towards ~15 s of CPU work
+            n = int(min(n_max, max(n + 1, n * 15.0 / max(el, 1e-3))))
+            Tt = n * unit
+            el = run(Tt)
+        cpu = {"value": Tt * B / el, "unit": "time-steps*batch/s", "cores": int(cores),
+               "kind": "oracle",
+               "sample": f"T={Tt} (of {T}), B={B}, D={D}, H={H}, cf={wl.cf}, levels={wl.levels}, "
+                         f"{iters} cycles, numpy float64, {el:.1f} s"}
+
+    out = {"study": "ode",
+           "metric": "time-steps*batch/sec, MGRIT forward propagation of the demonstration ODE vs "
+                     "serial propagation (1 GPU); % roofline",
+           "value": T * B / sec, "unit": "time-steps*batch/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": 1e3 * sec, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"demonstration ODE (Eq. 17), forward Euler dt={dt}, sizes of "
+                                  f"{wl.name}: T={T} B={B} D={D} H={H} cf={wl.cf} "
+                                  f"levels={wl.levels} cycles={iters} fine-level "
+                                  f"{args.fine_relax} relaxation, zero initial guess", "seed": 0},
+           "residual_fwd": residuals,
+           "max_rel_difference_from_serial_propagation": err,
+           "roofline": roof,
+           "ode_step_all_launches": ({"launches_per_step": nall / args.steps,
+                                      "ms_per_step": msall / args.steps,
+                                      "TFLOPs": flall / msall / 1e9} if nall else None),
+           "projection": ({"ms_per_step": mspj / args.steps, "TFLOPs": flpj / mspj / 1e9}
+                          if npj else None),
+           "serial_gpu": (None if ssec is None else
+                          {"value": T * B / ssec, "unit": "time-steps*batch/s",
+                           "ms_per_step": 1e3 * ssec, "what": "ode_serial_scan on the same GPU",
+                           "mgrit_speedup": ssec / sec}),
+           "cpu_baseline": cpu}
+    print(json.dumps(out))
+
+
 def study_training(args):
     """Alg. 3 as a training loop: a two-layer Implicit GRU with a linear head, trained
     with Adam (lr 1e-3, Sec. 3.4) on a synthetic sequence-classification task of the
@@ -495,6 +634,8 @@ def main():
         return study_convergence(args)
     if args.study == "training":
         return study_training(args)
+    if args.study == "ode":
+        return study_ode(args)
     if args.layers > 1:
         return stack_main(args)
     import numpy as np

@@ -8,6 +8,7 @@
 #include "common.h"
 #include "gates.h"
 #include "gemm_core.h"
+#include "skinny.h"
 
 namespace mg {
 
@@ -147,6 +148,115 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void ode_step_kernel(PhiArgs a) {
   }
 }
 
+// Few rows (the coarsest level's serial propagation, a serial scan over a small batch):
+// the vector-FMA form of skinny.h.  A workgroup owns a block of rows x CT columns of A h;
+// its threads split K, the partial sums meet through the lane butterfly and LDS, and
+// thread (row, column) applies the update.  Epilogue operands are requested before the
+// dot products.
+struct OdeEpiIn {
+  float p, h, gval, cur;
+};
+template <int MODE>
+__device__ inline OdeEpiIn ode_epi_load(const PhiArgs& a, const OdeRow& ro, int j) {
+  OdeEpiIn e;
+  e.p = a.P[ro.p + j];
+  e.h = a.u_in[ro.in + j];
+  e.gval = a.g ? a.g[ro.o + j] : 0.f;
+  e.cur = (MODE == STEP_RESID || MODE == STEP_RHS) ? a.u[ro.o + j] : 0.f;
+  return e;
+}
+template <int MODE>
+__device__ inline void ode_epi_finish(const PhiArgs& a, const OdeRow& ro, int j, float dot,
+                                      const OdeEpiIn& e, double& nrm) {
+  const float hn = e.h + a.gamma * (sigmoidf_(dot + e.p) - 0.5f * e.h);
+  const long long oi = ro.o + j;
+  if (MODE == STEP_RELAX) {
+    a.u[oi] = hn + e.gval;
+  } else if (MODE == STEP_RESID) {
+    const float res = e.cur - hn - e.gval;
+    const long long ai = ro.a + j;
+    a.gc[ai] = -res;
+    a.uc[ai] = e.cur;
+    nrm += (double)res * (double)res;
+  } else {  // STEP_RHS
+    a.g[oi] = (e.cur - hn) + e.gval;
+  }
+}
+
+constexpr int ODE_SK_ROWS = 32;   // rows per workgroup of the few-row step
+
+template <int CT, int MODE>
+__global__ __launch_bounds__(SK_MAXNT) void ode_skinny_kernel(PhiArgs a, int rows_block) {
+  constexpr int VP = sk_pow2_ceil(SK_RR * CT);
+  __shared__ float red[(SK_MAXNT / 64) * VP];
+  const int H = a.H;
+  const int R = a.nk * a.B;
+  const int r0 = blockIdx.y * rows_block;
+  const int rows_here = min(rows_block, R - r0);
+  const SkGeom geo = sk_geom(rows_block, H);
+  const int ksl = geo.ksl;
+  const int tid = threadIdx.x;
+  const int ks = tid & (ksl - 1), rg = tid / ksl;
+  const int j0 = blockIdx.x * CT;
+
+  const int n_out = rows_here * CT;
+  const bool epi = tid < n_out && j0 + tid % CT < H;
+  int e_j = 0;
+  OdeRow ero = {};
+  OdeEpiIn ein = {};
+  if (epi) {
+    ero = ode_row(a, r0 + tid / CT);
+    e_j = j0 + tid % CT;
+    ein = ode_epi_load<MODE>(a, ero, e_j);
+  }
+
+  // rows beyond the block are clamped to its last row (their sums are never used)
+  const float* hrow[SK_RR];
+#pragma unroll
+  for (int i = 0; i < SK_RR; ++i) {
+    const int r = r0 + min(rg * SK_RR + i, rows_here - 1);
+    const long long pt = (unsigned)r / (unsigned)a.B;
+    const int b = r - (int)pt * a.B;
+    hrow[i] = a.u_in + (a.in.at(pt) * a.B + b) * H;
+  }
+  const float* wrow[CT];
+#pragma unroll
+  for (int u = 0; u < CT; ++u) wrow[u] = (const float*)a.U + (long long)min(j0 + u, H - 1) * H;
+  float acc[SK_RR][CT];
+  skinny_dot<CT, float>(acc, H, ks, ksl, wrow, [&](int i, int k) { return ldg4(hrow[i] + k); });
+  float v[VP];
+#pragma unroll
+  for (int q = 0; q < VP; ++q) v[q] = q < SK_RR * CT ? acc[q / CT][q % CT] : 0.f;
+  skinny_reduce<VP>(v, red, rg, ks, ksl);
+  __syncthreads();
+
+  double nrm = 0.0;
+  for (int e = tid; e < n_out; e += geo.nt) {
+    const int row = e / CT, c = e % CT;
+    const int j = j0 + c;
+    if (j >= H) continue;
+    const float dot = skinny_sum<VP>(red, row / SK_RR, (row % SK_RR) * CT + c, ksl);
+    if (e == tid && epi) {
+      ode_epi_finish<MODE>(a, ero, e_j, dot, ein, nrm);
+    } else {   // more outputs than threads (tiny K only)
+      const OdeRow ro = ode_row(a, r0 + row);
+      ode_epi_finish<MODE>(a, ro, j, dot, ode_epi_load<MODE>(a, ro, j), nrm);
+    }
+  }
+  if (MODE == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
+}
+
+template <int CT>
+static void launch_ode_skinny(const PhiArgs& a, dim3 grid, int rb, hipStream_t s) {
+  const dim3 block(sk_geom(rb, a.H).nt);
+  if (a.mode == STEP_RELAX)
+    hipLaunchKernelGGL((ode_skinny_kernel<CT, STEP_RELAX>), grid, block, 0, s, a, rb);
+  else if (a.mode == STEP_RESID)
+    hipLaunchKernelGGL((ode_skinny_kernel<CT, STEP_RESID>), grid, block, 0, s, a, rb);
+  else
+    hipLaunchKernelGGL((ode_skinny_kernel<CT, STEP_RHS>), grid, block, 0, s, a, rb);
+}
+
 typedef TileCfg<2, 2, 2, 2, 1> OdeBig;                  // 128 x 128, 256 threads
 typedef TileCfg<2, 2, 1, 1, 1> OdeMid;                  //  64 x 64, 256 threads
 typedef TileCfg<1, 1, 1, 1, 1, 128, 1, 4> OdeSmall;     //  32 x 32, 4 waves splitting K
@@ -164,9 +274,9 @@ static void launch_ode_cfg(const PhiArgs& a, hipStream_t s) {
     hipLaunchKernelGGL((ode_step_kernel<C, STEP_RHS>), grid, block, 0, s, a);
 }
 
-// Tile shape by the number of workgroups it gives: 128 x 128 tiles when they alone fill
-// the chip, 64 x 64 below that, and for a few rows (the coarsest level's serial
-// propagation) 32 x 32 tiles whose four waves split K.
+// Up to 64 rows: the few-row kernel.  Above: tile shape by the number of workgroups it
+// gives, 128 x 128 tiles when they alone fill the chip, 64 x 64 below that, else 32 x 32
+// tiles whose four waves split K.
 hipError_t launch_ode_step(const PhiArgs& a, hipStream_t s) {
   if (a.nk <= 0) return hipSuccess;
   if (a.mode != STEP_RELAX && a.mode != STEP_RESID && a.mode != STEP_RHS)
@@ -174,7 +284,20 @@ hipError_t launch_ode_step(const PhiArgs& a, hipStream_t s) {
   const long long R = (long long)a.nk * a.B;
   auto tiles = [&](int tm, int tn) { return ((R + tm - 1) / tm) * ((a.H + tn - 1) / tn); };
   prof_begin(6, s, R, a.mode);
-  if (tiles(OdeBig::TM, OdeBig::TN) >= 384)
+  if (R <= 2 * SK_MAXROWS) {
+    // as many workgroups as the GRU's few-row step has at the same width: H / 2 there
+    // (two columns of three gates), H / 4 or H / 2 here
+    const int rb = R < ODE_SK_ROWS ? (int)R : ODE_SK_ROWS;
+    const int nrb = (int)((R + rb - 1) / rb);
+    const int ct = a.H * nrb >= 1024 ? 4 : (a.H * nrb >= 256 ? 2 : 1);
+    dim3 grid((unsigned)((a.H + ct - 1) / ct), (unsigned)nrb);
+    if (ct == 4)
+      launch_ode_skinny<4>(a, grid, rb, s);
+    else if (ct == 2)
+      launch_ode_skinny<2>(a, grid, rb, s);
+    else
+      launch_ode_skinny<1>(a, grid, rb, s);
+  } else if (tiles(OdeBig::TM, OdeBig::TN) >= 384)
     launch_ode_cfg<OdeBig>(a, s);
   else if (R > 32 && tiles(OdeMid::TM, OdeMid::TN) >= 256)
     launch_ode_cfg<OdeMid>(a, s);

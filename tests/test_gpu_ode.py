@@ -135,3 +135,27 @@ def test_mgrit_converges_to_the_serial_propagation_and_keeps_it():
     assert norms[3] < 1e-3 * norms[0]
     its2, norms2 = run.iterates(1, h_init=ser)
     assert _rel(its2[0], ser) <= 1e-6 and norms2[0] <= 2e-6 * np.sqrt(T * B * H)
+
+
+def test_full_size_solve_matches_the_oracle():
+    """The sizes of the headline configuration (T = 2048, B = 32, D = 1024, H = 512,
+    cf = 4, three levels, two cycles: the launch shapes bench.py --study ode times).  The
+    oracle runs this solve in a few seconds, so both iterates, the residual norms and the
+    serial propagation are compared element by element."""
+    T, B, D, H, cf, levels, dt = 2048, 32, 1024, 512, 4, 3, 1.0 / 16
+    p = random_ode(0, T, B, D, H, h0_random=False)
+    run = OdeRun(p, dt, cf=cf, levels=levels)
+    its, norms = run.iterates(2)
+    ser = run.serial()
+    _, want_norms, want = ode.ode_mgrit_forward(*_oracle_args(p), np.zeros((T + 1, B, H)), dt, cf,
+                                                levels, 2, keep_iterates=True)
+    for k in range(2):
+        assert _rel(its[k], want[k]) <= TOL, k
+        assert abs(norms[k] - want_norms[k]) <= 1e-4 * want_norms[k] + 2e-6 * np.sqrt(T * B * H)
+    assert _rel(ser, ode.ode_serial_scan(*_oracle_args(p), dt)) <= TOL
+    # one call with both cycles, as the bench issues it
+    h = torch.zeros(T + 1, B, H, device=DEV)
+    res = torch.zeros(2, device=DEV)
+    mg.mgrit_ode_forward(run.cfg(2), dt, *run._p(), h, res, run.ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(h.cpu().numpy(), its[1])

@@ -172,10 +172,35 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void adj_step_kernel(AdjArgs a) {
   };
   auto lb = [&](int s, int k) { return ldg4(brow[s] + k); };
   auto fa = [](const KapW& r) { return r.kap * r.w; };
-  if (K % C::TK == 0)
+  if (K % C::TK == 0 && C::KS == 1 && C::BM * C::BN >= 4) {
+    // Whole slices per gate (H is a multiple of the slice width): the sum over k may run
+    // in any slice order, so slice i takes gate i % 3 and the columns of slice i / 3 of
+    // that gate.  The three slices that multiply the same columns of w then follow each
+    // other, and w is loaded for the first of them only.
+    floatx4 wkeep[C::A_CHUNKS];
+    auto col = [&](int k, int& kk) {
+      const int i = k / C::TK;
+      const int g = i % 3;
+      kk = (i / 3) * C::TK + (k - i * C::TK);
+      return g;
+    };
+    auto lag = [&](int s, int k) {
+      int kk;
+      const int g = col(k, kk);
+      if (g == 0) wkeep[s] = ldg4(wrow[s] + kk);
+      return KapW{ldg4(krow[s] + g * H + kk), wkeep[s]};
+    };
+    auto lbg = [&](int s, int k) {
+      int kk;
+      const int g = col(k, kk);
+      return ldg4(brow[s] + g * H + kk);
+    };
+    gemm_nt_tile<C, false>(acc, K, lag, lbg, fa, Identity4(), lds);
+  } else if (K % C::TK == 0) {
     gemm_nt_tile<C, false>(acc, K, la, lb, fa, Identity4(), lds);
-  else
+  } else {
     gemm_nt_tile<C, true>(acc, K, la, lb, fa, Identity4(), lds);
+  }
 
   double nrm = 0.0;
   adj_tile_epilogue<C, MODE>(a, acc, rowtab, lds, m0, n0, R, nrm);

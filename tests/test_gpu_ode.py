@@ -91,6 +91,8 @@ MGRIT_CASES = [
     (64, 40, 16, 136, 4, 3, 1, 0.0625),    # tile kernels on the fine level, few-row below
     (256, 24, 32, 256, 8, 2, 1, 0.0625),   # 128 x 128 tiles
     (16, 2, 8, 16, 1, 2, 1, 0.25),         # cf = 1: every point is a coarse point
+    (4, 1, 4, 4, 4, 2, 1, 0.25),           # a single interval, one coarse step
+    (8, 1, 4, 8, 2, 4, 0, 0.5),            # coarsest level of one step, F-relaxation
 ]
 
 
@@ -108,6 +110,17 @@ def test_every_iterate_and_residual_matches_the_oracle(T, B, D, H, cf, levels, f
         assert _rel(its[k], want[k]) <= TOL, k
         floor = 2e-6 * np.sqrt(T * B * H)
         assert abs(norms[k] - want_norms[k]) <= 1e-4 * want_norms[k] + floor, k
+
+
+def test_zero_cycles_only_write_the_initial_condition():
+    T, B, D, H = 8, 2, 4, 8
+    p = random_ode(61, T, B, D, H)
+    run = OdeRun(p, 0.25, cf=2, levels=2)
+    h = torch.full((T + 1, B, H), 7.0, device=DEV)
+    mg.mgrit_ode_forward(run.cfg(0), 0.25, *run._p(), h, None, run.ws)
+    torch.cuda.synchronize()
+    h = h.cpu().numpy()
+    assert np.array_equal(h[0], p["h0"]) and np.all(h[1:] == 7.0)
 
 
 def test_several_cycles_in_one_call_equal_one_cycle_per_call():

@@ -18,9 +18,10 @@ the discretisation):
   its own points (injection), the rule Sec. 3.3 gives for the GRU;
 * dt is an argument; the demonstration's parameter "alpha" is not defined in the
   text and is not modelled.
-"parity unpinned" against the printed residual history (random weights, integrator
-not stated); pinned by closed forms, the exact solution of the ODE in the limit
-dt -> 0, and MGRIT's exactness properties in tests/test_oracle_pins_ode.py.
+Against the printed residual history only the rate per cycle can be compared
+(random weights, integrator not stated): values "parity unpinned" there.  Pinned by
+closed forms, the exact solution of the ODE in the limit dt -> 0, and MGRIT's
+exactness properties in tests/test_oracle_pins_ode.py.
 
 Layout as for the GRU oracle: d[T,B,D] row t-1 holds d_t; h[(T+1),B,H] row t holds
 h_t, row 0 the initial condition.

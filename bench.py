@@ -415,8 +415,8 @@ def study_ode(args):
         mgrit_step()
     torch.cuda.synchronize()
     mg.mgrit_gru_profile_enable(False)
-    n0, ms0, fl0, _ = mg.mgrit_gru_profile_read_shape(6, rows0, 0)
-    nall, msall, flall, _ = mg.mgrit_gru_profile_read(6)
+    n0, ms0, fl0, _ = mg.mgrit_gru_profile_read_shape(8, rows0, 0)
+    nall, msall, flall, _ = mg.mgrit_gru_profile_read(8)
     npj, mspj, flpj, _ = mg.mgrit_gru_profile_read(2)
     roof = None
     if n0:

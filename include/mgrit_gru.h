@@ -251,12 +251,12 @@ MGRIT_API const char* mgrit_gru_strerror(int code);
  *         2 = projection GEMM, 3 = weight-gradient GEMMs, 4 / 5 = forward / adjoint step
  *         in the few-row form used by the serial scan and the coarsest-level solve,
  *         6 = input-gradient GEMM, 7 = point copies (coarse-grid correction, terminal and
- *         initial conditions).
+ *         initial conditions), 8 = step of the demonstration ODE (tile and few-row forms).
  * All out-pointers are host pointers. */
 MGRIT_API int mgrit_gru_profile_enable(int on);
 MGRIT_API int mgrit_gru_profile_read(int kind, int64_t* launches, double* ms,
                            double* flops, double* bytes);
-/* The same for one launch shape of a step kernel class (kind 0, 1, 4, 5): only the
+/* The same for one launch shape of a step kernel class (kind 0, 1, 4, 5, 8): only the
  * launches that advance `rows` rows (level points x batch) in epilogue mode `mode`
  * (0 = relaxation update, 1 = residual + restriction, 2 = coarse right-hand side,
  * 3 = coefficients, 4 = relaxation update that keeps the coefficients; + 16 for a

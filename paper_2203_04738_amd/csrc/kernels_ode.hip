@@ -283,7 +283,7 @@ hipError_t launch_ode_step(const PhiArgs& a, hipStream_t s) {
     return hipErrorInvalidValue;
   const long long R = (long long)a.nk * a.B;
   auto tiles = [&](int tm, int tn) { return ((R + tm - 1) / tm) * ((a.H + tn - 1) / tn); };
-  prof_begin(6, s, R, a.mode);
+  prof_begin(8, s, R, a.mode);
   if (R <= 2 * SK_MAXROWS) {
     // as many workgroups as the GRU's few-row step has at the same width: H / 2 there
     // (two columns of three gates), H / 4 or H / 2 here
@@ -303,7 +303,7 @@ hipError_t launch_ode_step(const PhiArgs& a, hipStream_t s) {
     launch_ode_cfg<OdeMid>(a, s);
   else
     launch_ode_cfg<OdeSmall>(a, s);
-  prof_end(6, 2.0 * (double)R * a.H * a.H, 16.0 * (double)R * a.H, s);
+  prof_end(8, 2.0 * (double)R * a.H * a.H, 16.0 * (double)R * a.H, s);
   return hipGetLastError();
 }
 

@@ -259,7 +259,8 @@ MGRIT_API int mgrit_gru_profile_read(int kind, int64_t* launches, double* ms,
 /* The same for one launch shape of a step kernel class (kind 0, 1, 4, 5, 8): only the
  * launches that advance `rows` rows (level points x batch) in epilogue mode `mode`
  * (0 = relaxation update, 1 = residual + restriction, 2 = coarse right-hand side,
- * 3 = coefficients, 4 = relaxation update that keeps the coefficients; + 16 for a
+ * 3 = coefficients, 4 = relaxation update that keeps the coefficients, 5 = relaxation
+ * update from the coarse points that also evaluates the coarse level's step; + 16 for a
  * forward launch that skips the contraction of zero-input tiles, whose flops count
  * the rows it contracts only); a negative value matches any.  Records that do not
  * match stay for later reads. */

@@ -198,10 +198,16 @@ static bool serial_scan_keeps_coeffs(const mgrit_gru_cfg& c) { return c.B > 64; 
 
 // zero_c: the coarse points 1.. of the level hold zero states (the caller's initial guess):
 // the first sub-step reads nothing else outside the first interval.
+// rhs_fused (may be null; F-sweeps of a level that has a coarser one): the sweep's first
+// sub-step starts from the coarse points, the states the coarse level's operator is applied to
+// in Eq. 11, and the contraction U h does not depend on the step size: that launch also
+// evaluates the coarse step and leaves  R u' - Phi_c(R u')  in the coarse right-hand side
+// array (mode STEP_RELAX_RHS).  *rhs_fused tells the caller whether such a launch ran.
 static int relax_fwd(const FwdCtx& x, int l, bool include_c, bool f_points_current = false,
-                     bool emit = false, bool zero_c = false) {
+                     bool emit = false, bool zero_c = false, bool* rhs_fused = nullptr) {
   const long long cf = x.c->cf, S = x.lay->S[l];
   const int nint = (int)(x.lay->N[l] / cf);
+  if (rhs_fused) *rhs_fused = false;
   // f_points_current: the F-points already equal the propagation of their coarse
   // points (they were written by the closing F-relaxation of the previous cycle of
   // this call and nothing changed since), so recomputing them would reproduce the
@@ -221,6 +227,17 @@ static int relax_fwd(const FwdCtx& x, int l, bool include_c, bool f_points_curre
     a.o = Idx{j, cf};
     a.p = Idx{j * S - 1, cf * S};
     if (zero_c && j == 1 && cf > 1) a.zero_from = x.c->B;   // rows of the intervals 1..
+    if (rhs_fused && j == 1 && cf > 1 && !include_c && a.mode == STEP_RELAX) {
+      // interval i: coarse step from coarse point i to i + 1 (level point (i + 1) cf)
+      a.mode = STEP_RELAX_RHS;
+      a.gc = x.gl[l + 1];
+      a.a = Idx{1, 1};
+      a.gamma2 = (float)x.lay->S[l + 1] * x.dt;
+      const long long width = x.c->propagator == PROP_ODE_DEMO ? x.c->H : 3LL * x.c->H;
+      a.dp2 = (cf * S - 1 - a.p.off) * x.c->B * width;       // P row (i + 1) cf S - 1
+      a.do2 = (cf - a.o.off) * x.c->B * (long long)x.c->H;   // level point (i + 1) cf
+      *rhs_fused = true;
+    }
     const bool overlap = (cf == 1);   // reads and writes would share points
     if (overlap) a.u = x.tmp;
     CHECK_HIP(launch_phi_step(a, x.s));
@@ -256,11 +273,12 @@ static int vcycle_fwd(const FwdCtx& x, int l, bool f_points_current = false, boo
   // Alg. 2 line 1
   const bool cur = l == 0 && f_points_current;
   const bool zc = l == 0 && zero_guess && !cur;
+  bool rhs_fused = false;
   if (l == 0 && x.c->fine_relax == 0) {
-    if ((rc = relax_fwd(x, l, false, cur, false, zc))) return rc;
+    if ((rc = relax_fwd(x, l, false, cur, false, zc, &rhs_fused))) return rc;
   } else {
     if ((rc = relax_fwd(x, l, true, cur, false, zc))) return rc;
-    if ((rc = relax_fwd(x, l, false))) return rc;
+    if ((rc = relax_fwd(x, l, false, false, false, false, &rhs_fused))) return rc;
   }
   const int Nc = (int)(N / cf);
   const long long Sc = x.lay->S[l + 1];
@@ -275,9 +293,10 @@ static int vcycle_fwd(const FwdCtx& x, int l, bool f_points_current = false, boo
     a.uc = x.ul[l + 1];
     a.gc = x.gl[l + 1];
     a.norm = l == 0 ? x.norm : nullptr;
+    a.resid_adds = rhs_fused ? 1 : 0;     // completes g_c = (R u' - Phi_c(R u')) - R r
     CHECK_HIP(launch_phi_step(a, x.s));
   }
-  {  // line 4, right-hand side of Eq. 11: g_c = A_c(R u') - R r
+  if (!rhs_fused) {  // line 4, right-hand side of Eq. 11: g_c = A_c(R u') - R r
     PhiArgs a = phi_base(x, l + 1);
     a.mode = STEP_RHS;
     a.nk = Nc;

@@ -20,8 +20,13 @@ enum StepMode {
                     //                                                 (Alg. 2 lines 2-3)
   STEP_RHS = 2,     // g[o] = cur[o] - step(in) + g[o]                 (Eq. 11 right-hand side)
   STEP_KAPPA = 3,   // forward only: adjoint coefficient vectors of the step
-  STEP_RELAX_KAPPA = 4  // forward only: STEP_RELAX that also leaves the coefficient vectors of
+  STEP_RELAX_KAPPA = 4, // forward only: STEP_RELAX that also leaves the coefficient vectors of
                         // the step it takes (row = output point) in uc
+  STEP_RELAX_RHS = 5    // forward only: STEP_RELAX from the coarse points of a level (first
+                        // sub-step of an F-sweep) that also evaluates the coarse level's step
+                        // from the same inputs -- the contraction U h does not depend on the
+                        // step size -- and leaves  gc[a] = cur2 - step2(in)  (the first half
+                        // of the Eq. 11 right-hand side; STEP_RESID with resid_adds adds -r)
 };
 
 // One launch of the fused forward step  Phi_gamma(x, h) over nk level points.
@@ -46,6 +51,14 @@ struct PhiArgs {
   const void* U3;      // bf16 == 2: the three bf16 terms of U, [3][3H,H]
   int zero_from;       // > 0: the input states of rows >= zero_from are all zero (tile kernels
                        // skip the contraction of tiles that start there; 0: nothing known)
+  // STEP_RELAX_RHS: the second (coarse-level) evaluation of a row.  Its projection row and its
+  // current coarse value sit at fixed element offsets from the row's own projection row
+  // (index p) and output element (index o): both index pairs have the same stride.
+  long long dp2;       // elements from the row's P row to the coarse step's P row
+  long long do2;       // elements from the row's output row in u to the coarse point's row in u
+  float gamma2;        // step size of the coarse level
+  int resid_adds;      // STEP_RESID: gc[a] = gc[a] - r instead of -r (gc was prepared by
+                       // STEP_RELAX_RHS)
 };
 
 // One launch of the fused adjoint step  w_out = (dPhi/dh)^T w_in  over nk points.

@@ -174,6 +174,8 @@ hipError_t launch_projection(const void* X, const void* W, const float* bias, fl
 // products instead of after.
 struct PhiEpiIn {
   float pr, pz, pn, h, gval, cur;
+  float pr2, pz2, pn2, cur2;     // STEP_RELAX_RHS: projection and current value of the coarse step
+  float prep;                    // STEP_RESID with resid_adds: the prepared half of the right-hand side
 };
 // Element offsets (column 0) of one row (level point, batch element) of a launch into
 // the arrays the epilogue touches: input state, projection, out/cur/g, and the coarse
@@ -211,6 +213,15 @@ __device__ inline PhiEpiIn phi_epi_load(const PhiArgs& a, const PhiRow& ro, int 
   const long long oi = ro.o + j;
   e.gval = (MODE != STEP_KAPPA && a.g) ? a.g[oi] : 0.f;
   e.cur = (MODE == STEP_RESID || MODE == STEP_RHS) ? a.u[oi] : 0.f;
+  e.pr2 = e.pz2 = e.pn2 = e.cur2 = e.prep = 0.f;
+  if (MODE == STEP_RELAX_RHS) {
+    const float* p2 = pp + a.dp2;
+    e.pr2 = p2[j];
+    e.pz2 = p2[H + j];
+    e.pn2 = p2[2 * H + j];
+    e.cur2 = a.u[oi + a.do2];
+  }
+  if (MODE == STEP_RESID && a.resid_adds) e.prep = a.gc[ro.a + j];
   return e;
 }
 
@@ -223,7 +234,7 @@ struct PhiOut {
 };
 template <int MODE>
 __device__ inline PhiOut phi_elem(float gamma, bool implicit, float sr, float sz, float sn,
-                                  const PhiEpiIn& e, const PhiBias& bh) {
+                                  const PhiEpiIn& e, const PhiBias& bh, float gamma2 = 0.f) {
   const float h = e.h;
   const float rg = sigmoidf_(e.pr + sr + bh.r);
   const float zg = sigmoidf_(e.pz + sz + bh.z);
@@ -237,6 +248,16 @@ __device__ inline PhiOut phi_elem(float gamma, bool implicit, float sr, float sz
   if (MODE == STEP_RELAX_KAPPA) o.v5 = hn + e.gval;
   if (MODE == STEP_RELAX) {
     o.v0 = hn + e.gval;
+  } else if (MODE == STEP_RELAX_RHS) {
+    o.v0 = hn + e.gval;
+    // the coarse level's step from the same state: same sums, its own projection and step size
+    const float rg2 = sigmoidf_(e.pr2 + sr + bh.r);
+    const float zg2 = sigmoidf_(e.pz2 + sz + bh.z);
+    const float n2 = tanhf_(e.pn2 + rg2 * q);
+    const float c2 = 1.0f - zg2;
+    const float hn2 = implicit ? (h + gamma2 * c2 * n2) * fast_rcp(1.0f + gamma2 * c2)
+                               : h + gamma2 * c2 * (n2 - h);
+    o.v1 = e.cur2 - hn2;
   } else if (MODE == STEP_RESID) {
     o.v0 = -(e.cur - hn - e.gval);
     o.v1 = e.cur;
@@ -270,13 +291,16 @@ __device__ inline void phi_epi_finish(const PhiArgs& a, const PhiRow& ro, int j,
                                       double& nrm) {
   const int H = a.H;
   const PhiOut o =
-      phi_elem<MODE>(a.gamma, a.propagator == MGRIT_PROP_IMPLICIT, sr, sz, sn, e, bh);
+      phi_elem<MODE>(a.gamma, a.propagator == MGRIT_PROP_IMPLICIT, sr, sz, sn, e, bh, a.gamma2);
   const long long oi = ro.o + j;
   if (MODE == STEP_RELAX) {
     a.u[oi] = o.v0;
+  } else if (MODE == STEP_RELAX_RHS) {
+    a.u[oi] = o.v0;
+    a.gc[ro.a + j] = o.v1;
   } else if (MODE == STEP_RESID) {
     const long long ai = ro.a + j;
-    a.gc[ai] = o.v0;
+    a.gc[ai] = a.resid_adds ? e.prep + o.v0 : o.v0;
     a.uc[ai] = o.v1;
     nrm += (double)o.v0 * (double)o.v0;
   } else if (MODE == STEP_RHS) {
@@ -297,6 +321,9 @@ __device__ inline void phi_epi_finish(const PhiArgs& a, const PhiRow& ro, int j,
 // finished and stored as float4.
 struct PhiEpiIn4 {
   floatx4 pr, pz, pn, h, gval, cur;
+};
+struct PhiEpiExtra4 {     // STEP_RELAX_RHS (pr2..cur2) and STEP_RESID with resid_adds (prep)
+  floatx4 pr2, pz2, pn2, cur2, prep;
 };
 
 template <class C, int MODE>
@@ -321,6 +348,8 @@ __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Ph
     E::write(acc, ba, stage);
     // operands that do not depend on the sums: requested before the barrier
     PhiEpiIn4 in[E::ITEMS];
+    constexpr bool EXTRA = MODE == STEP_RELAX_RHS || MODE == STEP_RESID;
+    PhiEpiExtra4 ex[EXTRA ? E::ITEMS : 1];
     long long oo[E::ITEMS], oa[E::ITEMS];
     int trow[E::ITEMS];
 #pragma unroll
@@ -338,6 +367,13 @@ __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Ph
       else in[it].gval = zero4();
       if (MODE == STEP_RESID || MODE == STEP_RHS) in[it].cur = ldg4(a.u + ro.o + jc);
       else in[it].cur = zero4();
+      if (MODE == STEP_RELAX_RHS) {
+        ex[it].pr2 = ldg4_stream(pp + a.dp2);
+        ex[it].pz2 = ldg4_stream(pp + a.dp2 + H);
+        ex[it].pn2 = ldg4_stream(pp + a.dp2 + 2 * H);
+        ex[it].cur2 = ldg4(a.u + ro.o + a.do2 + jc);
+      }
+      if (MODE == STEP_RESID) ex[it].prep = a.resid_adds ? ldg4(a.gc + ro.a + jc) : zero4();
     }
     __syncthreads();
 #pragma unroll
@@ -349,18 +385,28 @@ __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Ph
       floatx4 o0, o1, o2, o3, o4, o5;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const PhiEpiIn e1{in[it].pr[i], in[it].pz[i], in[it].pn[i], in[it].h[i], in[it].gval[i],
-                          in[it].cur[i]};
-        const PhiOut o = phi_elem<MODE>(gamma, implicit, sr[i], sz[i], sn[i], e1, bh[i]);
+        PhiEpiIn e1{in[it].pr[i], in[it].pz[i], in[it].pn[i], in[it].h[i], in[it].gval[i],
+                    in[it].cur[i], 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (MODE == STEP_RELAX_RHS) {
+          e1.pr2 = ex[it].pr2[i];
+          e1.pz2 = ex[it].pz2[i];
+          e1.pn2 = ex[it].pn2[i];
+          e1.cur2 = ex[it].cur2[i];
+        }
+        const PhiOut o = phi_elem<MODE>(gamma, implicit, sr[i], sz[i], sn[i], e1, bh[i], a.gamma2);
         o0[i] = o.v0; o1[i] = o.v1; o2[i] = o.v2; o3[i] = o.v3; o4[i] = o.v4; o5[i] = o.v5;
       }
       if (!colok || m0 + trow[it] >= R) continue;
       const long long oi = oo[it] + j;
       if (MODE == STEP_RELAX) {
         *reinterpret_cast<floatx4*>(a.u + oi) = o0;
+      } else if (MODE == STEP_RELAX_RHS) {
+        *reinterpret_cast<floatx4*>(a.u + oi) = o0;
+        *reinterpret_cast<floatx4*>(a.gc + oa[it] + j) = o1;
       } else if (MODE == STEP_RESID) {
         const long long ai = oa[it] + j;
-        *reinterpret_cast<floatx4*>(a.gc + ai) = o0;
+        // (adding the zero of a launch without a prepared half changes no value)
+        *reinterpret_cast<floatx4*>(a.gc + ai) = ex[it].prep + o0;
         *reinterpret_cast<floatx4*>(a.uc + ai) = o1;
 #pragma unroll
         for (int i = 0; i < 4; ++i) nrm += (double)o0[i] * (double)o0[i];
@@ -634,6 +680,12 @@ typedef TileCfgB<1, 1, 1, 1, 3, true, 4, 1, 2, 3, 32> PhiSmallS;
     case STEP_RELAX_KAPPA:                                                               \
       hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_RELAX_KAPPA>), grid, block, 0, s, a); \
       break;                                                                             \
+    case STEP_RELAX_RHS:                                                                 \
+      if (a.zero_from > 0)                                                               \
+        hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_RELAX_RHS, true>), grid, block, 0, s, a); \
+      else                                                                               \
+        hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_RELAX_RHS>), grid, block, 0, s, a); \
+      break;                                                                             \
     default:                                                                             \
       hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_KAPPA>), grid, block, 0, s, a);       \
   }
@@ -677,6 +729,7 @@ static void launch_phi_skinny(const PhiArgs& a, dim3 grid, hipStream_t s) {
     case STEP_RESID: launch_phi_skinny_mode<CT, STEP_RESID>(a, grid, s); break;
     case STEP_RHS: launch_phi_skinny_mode<CT, STEP_RHS>(a, grid, s); break;
     case STEP_RELAX_KAPPA: launch_phi_skinny_mode<CT, STEP_RELAX_KAPPA>(a, grid, s); break;
+    case STEP_RELAX_RHS: launch_phi_skinny_mode<CT, STEP_RELAX_RHS>(a, grid, s); break;
     default: launch_phi_skinny_mode<CT, STEP_KAPPA>(a, grid, s);
   }
 }

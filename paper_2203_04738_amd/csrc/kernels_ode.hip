@@ -31,6 +31,9 @@ __device__ inline OdeRow ode_row(const PhiArgs& a, long long r) {
 struct OdeEpiIn4 {
   floatx4 p, h, gval, cur;
 };
+struct OdeEpiExtra4 {     // STEP_RELAX_RHS (p2, cur2) and STEP_RESID with resid_adds (prep)
+  floatx4 p2, cur2, prep;
+};
 
 // Epilogue of one MFMA tile over the staged sums (A h): the Euler update and the
 // mode's outputs, moved as float4 (see EpiStage).
@@ -50,6 +53,8 @@ __device__ inline void ode_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Od
     __syncthreads();                                    // staging area no longer read
     E::write(acc, ba, stage);
     OdeEpiIn4 in[E::ITEMS];
+    constexpr bool EXTRA = MODE == STEP_RELAX_RHS || MODE == STEP_RESID;
+    OdeEpiExtra4 ex[EXTRA ? E::ITEMS : 1];
     long long oo[E::ITEMS], oa[E::ITEMS];
     int trow[E::ITEMS];
 #pragma unroll
@@ -62,6 +67,11 @@ __device__ inline void ode_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Od
       in[it].h = ldg4(a.u_in + ro.in + jc);
       in[it].gval = a.g ? ldg4(a.g + ro.o + jc) : zero4();
       in[it].cur = (MODE == STEP_RESID || MODE == STEP_RHS) ? ldg4(a.u + ro.o + jc) : zero4();
+      if (MODE == STEP_RELAX_RHS) {
+        ex[it].p2 = ldg4(a.P + ro.p + a.dp2 + jc);
+        ex[it].cur2 = ldg4(a.u + ro.o + a.do2 + jc);
+      }
+      if (MODE == STEP_RESID) ex[it].prep = a.resid_adds ? ldg4(a.gc + ro.a + jc) : zero4();
     }
     __syncthreads();
 #pragma unroll
@@ -77,10 +87,20 @@ __device__ inline void ode_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Od
       const long long oi = oo[it] + j;
       if (MODE == STEP_RELAX) {
         *reinterpret_cast<floatx4*>(a.u + oi) = hn + in[it].gval;
+      } else if (MODE == STEP_RELAX_RHS) {
+        *reinterpret_cast<floatx4*>(a.u + oi) = hn + in[it].gval;
+        // the coarse level's step from the same state: same sums, its own data and step size
+        floatx4 hn2;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float h = in[it].h[i];
+          hn2[i] = h + a.gamma2 * (sigmoidf_(dot[i] + ex[it].p2[i]) - 0.5f * h);
+        }
+        *reinterpret_cast<floatx4*>(a.gc + oa[it] + j) = ex[it].cur2 - hn2;
       } else if (MODE == STEP_RESID) {
         const floatx4 res = in[it].cur - hn - in[it].gval;
         const long long ai = oa[it] + j;
-        *reinterpret_cast<floatx4*>(a.gc + ai) = -res;
+        *reinterpret_cast<floatx4*>(a.gc + ai) = ex[it].prep + (-res);
         *reinterpret_cast<floatx4*>(a.uc + ai) = in[it].cur;
 #pragma unroll
         for (int i = 0; i < 4; ++i) nrm += (double)res[i] * (double)res[i];
@@ -155,6 +175,7 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void ode_step_kernel(PhiArgs a) {
 // dot products.
 struct OdeEpiIn {
   float p, h, gval, cur;
+  float p2, cur2, prep;     // STEP_RELAX_RHS / STEP_RESID with resid_adds (see OdeEpiExtra4)
 };
 template <int MODE>
 __device__ inline OdeEpiIn ode_epi_load(const PhiArgs& a, const OdeRow& ro, int j) {
@@ -163,6 +184,12 @@ __device__ inline OdeEpiIn ode_epi_load(const PhiArgs& a, const OdeRow& ro, int 
   e.h = a.u_in[ro.in + j];
   e.gval = a.g ? a.g[ro.o + j] : 0.f;
   e.cur = (MODE == STEP_RESID || MODE == STEP_RHS) ? a.u[ro.o + j] : 0.f;
+  e.p2 = e.cur2 = e.prep = 0.f;
+  if (MODE == STEP_RELAX_RHS) {
+    e.p2 = a.P[ro.p + a.dp2 + j];
+    e.cur2 = a.u[ro.o + a.do2 + j];
+  }
+  if (MODE == STEP_RESID && a.resid_adds) e.prep = a.gc[ro.a + j];
   return e;
 }
 template <int MODE>
@@ -172,10 +199,14 @@ __device__ inline void ode_epi_finish(const PhiArgs& a, const OdeRow& ro, int j,
   const long long oi = ro.o + j;
   if (MODE == STEP_RELAX) {
     a.u[oi] = hn + e.gval;
+  } else if (MODE == STEP_RELAX_RHS) {
+    a.u[oi] = hn + e.gval;
+    const float hn2 = e.h + a.gamma2 * (sigmoidf_(dot + e.p2) - 0.5f * e.h);
+    a.gc[ro.a + j] = e.cur2 - hn2;
   } else if (MODE == STEP_RESID) {
     const float res = e.cur - hn - e.gval;
     const long long ai = ro.a + j;
-    a.gc[ai] = -res;
+    a.gc[ai] = a.resid_adds ? e.prep + (-res) : -res;
     a.uc[ai] = e.cur;
     nrm += (double)res * (double)res;
   } else {  // STEP_RHS
@@ -251,6 +282,8 @@ static void launch_ode_skinny(const PhiArgs& a, dim3 grid, int rb, hipStream_t s
   const dim3 block(sk_geom(rb, a.H).nt);
   if (a.mode == STEP_RELAX)
     hipLaunchKernelGGL((ode_skinny_kernel<CT, STEP_RELAX>), grid, block, 0, s, a, rb);
+  else if (a.mode == STEP_RELAX_RHS)
+    hipLaunchKernelGGL((ode_skinny_kernel<CT, STEP_RELAX_RHS>), grid, block, 0, s, a, rb);
   else if (a.mode == STEP_RESID)
     hipLaunchKernelGGL((ode_skinny_kernel<CT, STEP_RESID>), grid, block, 0, s, a, rb);
   else
@@ -268,6 +301,8 @@ static void launch_ode_cfg(const PhiArgs& a, hipStream_t s) {
   dim3 block(C::NT);
   if (a.mode == STEP_RELAX)
     hipLaunchKernelGGL((ode_step_kernel<C, STEP_RELAX>), grid, block, 0, s, a);
+  else if (a.mode == STEP_RELAX_RHS)
+    hipLaunchKernelGGL((ode_step_kernel<C, STEP_RELAX_RHS>), grid, block, 0, s, a);
   else if (a.mode == STEP_RESID)
     hipLaunchKernelGGL((ode_step_kernel<C, STEP_RESID>), grid, block, 0, s, a);
   else
@@ -279,7 +314,8 @@ static void launch_ode_cfg(const PhiArgs& a, hipStream_t s) {
 // tiles whose four waves split K.
 hipError_t launch_ode_step(const PhiArgs& a, hipStream_t s) {
   if (a.nk <= 0) return hipSuccess;
-  if (a.mode != STEP_RELAX && a.mode != STEP_RESID && a.mode != STEP_RHS)
+  if (a.mode != STEP_RELAX && a.mode != STEP_RESID && a.mode != STEP_RHS &&
+      a.mode != STEP_RELAX_RHS)
     return hipErrorInvalidValue;
   const long long R = (long long)a.nk * a.B;
   auto tiles = [&](int tm, int tn) { return ((R + tm - 1) / tm) * ((a.H + tn - 1) / tn); };

@@ -395,8 +395,10 @@ def test_launch_counts_of_two_fcf_cycles(gh):
     """What one call enqueues, read back through the event-timing interface: with cf = 4, two
     levels, FCF relaxation and two cycles, level 0 takes 3 + 1 + 3 relaxation sub-steps, one
     residual launch and 3 closing sub-steps in the first cycle; the second cycle skips the
-    opening F-sweep (its values are current): 1 + 3, one residual, 3.  The coarse level gets one
-    right-hand-side launch and N_1 serial steps per cycle."""
+    opening F-sweep (its values are current): 1 + 3, one residual, 3.  The first sub-step of
+    the F-sweep that follows the C-sweep also evaluates the coarse operator on the coarse
+    points it starts from (mode 5), so no separate right-hand-side launch is left; the coarse
+    level gets N_1 serial steps per cycle."""
     import paper_2203_04738_amd as mg
     T, B, D, H = 64, 70, 8, 16
     d = random_small(3, T, B, D, H, scale=0.2)
@@ -407,9 +409,10 @@ def test_launch_counts_of_two_fcf_cycles(gh):
         run.forward_iterates(2, per_call=2)
     finally:
         mg.mgrit_gru_profile_enable(False)
-    assert mg.mgrit_gru_profile_read_shape(0, rows0, 0)[0] == (3 + 1 + 3 + 3) + (1 + 3 + 3)
+    assert mg.mgrit_gru_profile_read_shape(0, rows0, 0)[0] == (3 + 1 + 2 + 3) + (1 + 2 + 3)
+    assert mg.mgrit_gru_profile_read_shape(0, rows0, 5)[0] == 2          # sub-step + coarse operator
     assert mg.mgrit_gru_profile_read_shape(0, rows0, 1)[0] == 2          # residual + restriction
-    assert mg.mgrit_gru_profile_read_shape(0, rows0, 2)[0] == 2          # coarse right-hand side
+    assert mg.mgrit_gru_profile_read_shape(0, rows0, 2)[0] == 0          # no separate right-hand side
     assert mg.mgrit_gru_profile_read_shape(0, rows1, 0)[0] == 2 * (T // 4)   # coarsest serial steps
     assert mg.mgrit_gru_profile_read(0)[0] == 0                          # nothing else of this class
     assert mg.mgrit_gru_profile_read(2)[0] == 1                          # one projection

@@ -164,6 +164,7 @@ struct FwdCtx {
   float* tmp;
   double* norm;     // accumulator of the current cycle (may be null)
   float* emit_kap;  // level-0 coefficient array the closing relaxation also fills (or null)
+  float* emit_kap1; // level-1 coefficient array filled along with it (null with one level)
   float dt;         // step size of level 0 (1 for the GRU propagators, Sec. 3.3)
   hipStream_t s;
 };
@@ -226,6 +227,17 @@ static int relax_fwd(const FwdCtx& x, int l, bool include_c, bool f_points_curre
     a.in = Idx{j - 1, cf};
     a.o = Idx{j, cf};
     a.p = Idx{j * S - 1, cf * S};
+    if (a.mode == STEP_RELAX_KAPPA && j == 1 && cf > 1 && x.emit_kap1) {
+      // the first sub-step starts from the coarse points, whose values are final: they are the
+      // states the steps of level 1 are linearised at, and the contraction U h is the same for
+      // both step sizes, so this launch also leaves the coefficient vectors of level 1
+      // (step from level-1 point i to i + 1, row i + 1)
+      a.mode = STEP_RELAX_KAPPA2;
+      a.gc = x.emit_kap1;
+      a.a = Idx{1, 1};
+      a.gamma2 = (float)x.lay->S[l + 1] * x.dt;
+      a.dp2 = (cf * S - 1 - a.p.off) * x.c->B * 3LL * x.c->H;   // P row (i + 1) cf S - 1
+    }
     if (zero_c && j == 1 && cf > 1) a.zero_from = x.c->B;   // rows of the intervals 1..
     if (rhs_fused && j == 1 && cf > 1 && !include_c && a.mode == STEP_RELAX) {
       // interval i: coarse step from coarse point i to i + 1 (level point (i + 1) cf)
@@ -386,6 +398,7 @@ static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, co
   ctx.emit_kap = (c.flags & MGRIT_KEEP_COEFFS) ? (float*)(base + lay.kap[0]) : nullptr;
   if (ctx.emit_kap && c.iters < 1) return MGRIT_E_SIZE;
   if (lay.L == 1 && !serial_scan_keeps_coeffs(c)) ctx.emit_kap = nullptr;
+  ctx.emit_kap1 = (ctx.emit_kap && lay.L > 1) ? (float*)(base + lay.kap[1]) : nullptr;
 
   if ((rc = run_projection(&c, lay, base, W, b_i, x, s))) return rc;
   const long long BH = (long long)c.B * c.H;
@@ -625,6 +638,9 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
         a.o = Idx{c.cf, c.cf};
       }
     }
+    // ... and, from the coarse points its first sub-step starts at, the coefficients of every
+    // step of level 1
+    if (l == 1 && (c.flags & MGRIT_REUSE_COEFFS) && c.cf > 1) a.nk = 0;
     CHECK_HIP(launch_phi_step(a, s));
     // the terminal condition w_T = dL/dh_T is the fixed end point of every level
     CHECK_HIP(launch_copy_points(ctx.wl[l], dL_dhT, Idx{lay.N[l], 0}, Idx{0, 0}, 1, BH, s));

@@ -27,6 +27,10 @@ enum StepMode {
                         // from the same inputs -- the contraction U h does not depend on the
                         // step size -- and leaves  gc[a] = cur2 - step2(in)  (the first half
                         // of the Eq. 11 right-hand side; STEP_RESID with resid_adds adds -r)
+  ,
+  STEP_RELAX_KAPPA2 = 6 // forward only: STEP_RELAX_KAPPA from the coarse points of level 0 that
+                        // also leaves the coefficient vectors of the coarse level's step from
+                        // the same states (k_r, k_z, k_q, k_d; row = coarse output point) in gc
 };
 
 // One launch of the fused forward step  Phi_gamma(x, h) over nk level points.

@@ -194,6 +194,13 @@ __device__ inline PhiRow phi_row(const PhiArgs& a, long long r, int aux_width) {
   ro.a = ((aux_width == a.H ? a.a.at(pt) : a.o.at(pt)) * a.B + b) * (long long)aux_width;
   return ro;
 }
+// STEP_RELAX_KAPPA2: element offset of the row's coarse output point (index a) in the coarse
+// level's coefficient array (4H wide).
+__device__ inline long long phi_row_coarse_kappa(const PhiArgs& a, long long r) {
+  const long long pt = (unsigned)r / (unsigned)a.B;
+  const int b = (int)(r - pt * a.B);
+  return (a.a.at(pt) * a.B + b) * (4LL * a.H);
+}
 struct PhiBias {          // recurrent biases of one hidden column
   float r, z, n;
 };
@@ -214,12 +221,12 @@ __device__ inline PhiEpiIn phi_epi_load(const PhiArgs& a, const PhiRow& ro, int 
   e.gval = (MODE != STEP_KAPPA && a.g) ? a.g[oi] : 0.f;
   e.cur = (MODE == STEP_RESID || MODE == STEP_RHS) ? a.u[oi] : 0.f;
   e.pr2 = e.pz2 = e.pn2 = e.cur2 = e.prep = 0.f;
-  if (MODE == STEP_RELAX_RHS) {
+  if (MODE == STEP_RELAX_RHS || MODE == STEP_RELAX_KAPPA2) {
     const float* p2 = pp + a.dp2;
     e.pr2 = p2[j];
     e.pz2 = p2[H + j];
     e.pn2 = p2[2 * H + j];
-    e.cur2 = a.u[oi + a.do2];
+    if (MODE == STEP_RELAX_RHS) e.cur2 = a.u[oi + a.do2];
   }
   if (MODE == STEP_RESID && a.resid_adds) e.prep = a.gc[ro.a + j];
   return e;
@@ -231,7 +238,27 @@ __device__ inline PhiEpiIn phi_epi_load(const PhiArgs& a, const PhiRow& ro, int 
 //   RHS:   v0 = cur - step + g           KAPPA: v0..v4 = k_r, k_z, k_q, k_d, k_n
 struct PhiOut {
   float v0, v1, v2, v3, v4, v5;       // v5: new state (+ g) of STEP_RELAX_KAPPA
+  float c0, c1, c2, c3;               // STEP_RELAX_KAPPA2: k_r, k_z, k_q, k_d of the coarse step
 };
+// Coefficient vectors of the transposed Jacobian of one step (Appendix A.2), from its gates.
+struct PhiKappa {
+  float kr, kz, kq, kd, kn;
+};
+__device__ inline PhiKappa phi_kappa(float gamma, bool implicit, float h, float rg, float zg,
+                                     float q, float n, float c, float rd, float hn) {
+  float kd, dn, dz;
+  if (implicit) {
+    kd = rd;
+    dn = gamma * c * rd;
+    dz = -gamma * (n - hn) * rd;
+  } else {
+    kd = 1.0f - gamma * c;
+    dn = gamma * c;
+    dz = -gamma * (n - h);
+  }
+  const float kn = dn * (1.0f - n * n);
+  return PhiKappa{kn * q * rg * (1.0f - rg), dz * zg * (1.0f - zg), kn * rg, kd, kn};
+}
 template <int MODE>
 __device__ inline PhiOut phi_elem(float gamma, bool implicit, float sr, float sz, float sn,
                                   const PhiEpiIn& e, const PhiBias& bh, float gamma2 = 0.f) {
@@ -244,8 +271,8 @@ __device__ inline PhiOut phi_elem(float gamma, bool implicit, float sr, float sz
   const float d = 1.0f + gamma * c;
   const float rd = fast_rcp(d);
   const float hn = implicit ? (h + gamma * c * n) * rd : h + gamma * c * (n - h);
-  PhiOut o{0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  if (MODE == STEP_RELAX_KAPPA) o.v5 = hn + e.gval;
+  PhiOut o{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (MODE == STEP_RELAX_KAPPA || MODE == STEP_RELAX_KAPPA2) o.v5 = hn + e.gval;
   if (MODE == STEP_RELAX) {
     o.v0 = hn + e.gval;
   } else if (MODE == STEP_RELAX_RHS) {
@@ -263,23 +290,27 @@ __device__ inline PhiOut phi_elem(float gamma, bool implicit, float sr, float sz
     o.v1 = e.cur;
   } else if (MODE == STEP_RHS) {
     o.v0 = (e.cur - hn) + e.gval;
-  } else {  // STEP_KAPPA: coefficients of the transposed Jacobian of this step
-    float kd, dn, dz;
-    if (implicit) {
-      kd = rd;
-      dn = gamma * c * rd;
-      dz = -gamma * (n - hn) * rd;
-    } else {
-      kd = 1.0f - gamma * c;
-      dn = gamma * c;
-      dz = -gamma * (n - h);
+  } else {  // STEP_KAPPA (and the relaxation modes that keep them): coefficients of this step
+    const PhiKappa k = phi_kappa(gamma, implicit, h, rg, zg, q, n, c, rd, hn);
+    o.v0 = k.kr;
+    o.v1 = k.kz;
+    o.v2 = k.kq;
+    o.v3 = k.kd;
+    o.v4 = k.kn;
+    if (MODE == STEP_RELAX_KAPPA2) {
+      // the coarse level's step from the same state: same sums, its own projection and step size
+      const float rg2 = sigmoidf_(e.pr2 + sr + bh.r);
+      const float zg2 = sigmoidf_(e.pz2 + sz + bh.z);
+      const float n2 = tanhf_(e.pn2 + rg2 * q);
+      const float c2 = 1.0f - zg2;
+      const float rd2 = fast_rcp(1.0f + gamma2 * c2);
+      const float hn2 = implicit ? (h + gamma2 * c2 * n2) * rd2 : h + gamma2 * c2 * (n2 - h);
+      const PhiKappa k2 = phi_kappa(gamma2, implicit, h, rg2, zg2, q, n2, c2, rd2, hn2);
+      o.c0 = k2.kr;
+      o.c1 = k2.kz;
+      o.c2 = k2.kq;
+      o.c3 = k2.kd;
     }
-    const float kn = dn * (1.0f - n * n);
-    o.v0 = kn * q * rg * (1.0f - rg);
-    o.v1 = dz * zg * (1.0f - zg);
-    o.v2 = kn * rg;
-    o.v3 = kd;
-    o.v4 = kn;
   }
   return o;
 }
@@ -288,7 +319,7 @@ __device__ inline PhiOut phi_elem(float gamma, bool implicit, float sr, float sz
 template <int MODE>
 __device__ inline void phi_epi_finish(const PhiArgs& a, const PhiRow& ro, int j, float sr,
                                       float sz, float sn, const PhiEpiIn& e, const PhiBias& bh,
-                                      double& nrm) {
+                                      double& nrm, long long coarse_kappa_row = 0) {
   const int H = a.H;
   const PhiOut o =
       phi_elem<MODE>(a.gamma, a.propagator == MGRIT_PROP_IMPLICIT, sr, sz, sn, e, bh, a.gamma2);
@@ -306,13 +337,20 @@ __device__ inline void phi_epi_finish(const PhiArgs& a, const PhiRow& ro, int j,
   } else if (MODE == STEP_RHS) {
     a.g[oi] = o.v0;
   } else {
-    if (MODE == STEP_RELAX_KAPPA) a.u[oi] = o.v5;
+    if (MODE == STEP_RELAX_KAPPA || MODE == STEP_RELAX_KAPPA2) a.u[oi] = o.v5;
     float* kp = a.uc + ro.a;
     kp[j] = o.v0;
     kp[H + j] = o.v1;
     kp[2 * H + j] = o.v2;
     kp[3 * H + j] = o.v3;
     if (a.kappa_width >= 5 * H) kp[4 * H + j] = o.v4;
+    if (MODE == STEP_RELAX_KAPPA2) {
+      float* kc = a.gc + coarse_kappa_row;
+      kc[j] = o.c0;
+      kc[H + j] = o.c1;
+      kc[2 * H + j] = o.c2;
+      kc[3 * H + j] = o.c3;
+    }
   }
 }
 
@@ -329,7 +367,7 @@ struct PhiEpiExtra4 {     // STEP_RELAX_RHS (pr2..cur2) and STEP_RESID with resi
 template <class C, int MODE>
 __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const PhiRow* rowtab,
                                          float* stage, long long m0, int n0, long long R,
-                                         double& nrm) {
+                                         double& nrm, const long long* rowtab2 = nullptr) {
   typedef EpiStage<C> E;
   const int H = a.H;
   const int c4 = E::col4();
@@ -348,9 +386,11 @@ __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Ph
     E::write(acc, ba, stage);
     // operands that do not depend on the sums: requested before the barrier
     PhiEpiIn4 in[E::ITEMS];
-    constexpr bool EXTRA = MODE == STEP_RELAX_RHS || MODE == STEP_RESID;
+    constexpr bool EXTRA =
+        MODE == STEP_RELAX_RHS || MODE == STEP_RESID || MODE == STEP_RELAX_KAPPA2;
     PhiEpiExtra4 ex[EXTRA ? E::ITEMS : 1];
     long long oo[E::ITEMS], oa[E::ITEMS];
+    long long oa2[MODE == STEP_RELAX_KAPPA2 ? E::ITEMS : 1];
     int trow[E::ITEMS];
 #pragma unroll
     for (int it = 0; it < E::ITEMS; ++it) {
@@ -367,11 +407,12 @@ __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Ph
       else in[it].gval = zero4();
       if (MODE == STEP_RESID || MODE == STEP_RHS) in[it].cur = ldg4(a.u + ro.o + jc);
       else in[it].cur = zero4();
-      if (MODE == STEP_RELAX_RHS) {
+      if (MODE == STEP_RELAX_RHS || MODE == STEP_RELAX_KAPPA2) {
         ex[it].pr2 = ldg4_stream(pp + a.dp2);
         ex[it].pz2 = ldg4_stream(pp + a.dp2 + H);
         ex[it].pn2 = ldg4_stream(pp + a.dp2 + 2 * H);
-        ex[it].cur2 = ldg4(a.u + ro.o + a.do2 + jc);
+        if (MODE == STEP_RELAX_RHS) ex[it].cur2 = ldg4(a.u + ro.o + a.do2 + jc);
+        if (MODE == STEP_RELAX_KAPPA2) oa2[it] = rowtab2[trow[it]];
       }
       if (MODE == STEP_RESID) ex[it].prep = a.resid_adds ? ldg4(a.gc + ro.a + jc) : zero4();
     }
@@ -383,18 +424,20 @@ __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Ph
       const floatx4 sz = E::read(stage, 1, rp, c4);
       const floatx4 sn = E::read(stage, 2, rp, c4);
       floatx4 o0, o1, o2, o3, o4, o5;
+      floatx4 q0, q1, q2, q3;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         PhiEpiIn e1{in[it].pr[i], in[it].pz[i], in[it].pn[i], in[it].h[i], in[it].gval[i],
                     in[it].cur[i], 0.f, 0.f, 0.f, 0.f, 0.f};
-        if (MODE == STEP_RELAX_RHS) {
+        if (MODE == STEP_RELAX_RHS || MODE == STEP_RELAX_KAPPA2) {
           e1.pr2 = ex[it].pr2[i];
           e1.pz2 = ex[it].pz2[i];
           e1.pn2 = ex[it].pn2[i];
-          e1.cur2 = ex[it].cur2[i];
+          if (MODE == STEP_RELAX_RHS) e1.cur2 = ex[it].cur2[i];
         }
         const PhiOut o = phi_elem<MODE>(gamma, implicit, sr[i], sz[i], sn[i], e1, bh[i], a.gamma2);
         o0[i] = o.v0; o1[i] = o.v1; o2[i] = o.v2; o3[i] = o.v3; o4[i] = o.v4; o5[i] = o.v5;
+        q0[i] = o.c0; q1[i] = o.c1; q2[i] = o.c2; q3[i] = o.c3;
       }
       if (!colok || m0 + trow[it] >= R) continue;
       const long long oi = oo[it] + j;
@@ -413,13 +456,21 @@ __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Ph
       } else if (MODE == STEP_RHS) {
         *reinterpret_cast<floatx4*>(a.g + oi) = o0;
       } else {
-        if (MODE == STEP_RELAX_KAPPA) *reinterpret_cast<floatx4*>(a.u + oi) = o5;
+        if (MODE == STEP_RELAX_KAPPA || MODE == STEP_RELAX_KAPPA2)
+          *reinterpret_cast<floatx4*>(a.u + oi) = o5;
         float* kp = a.uc + oa[it] + j;
         *reinterpret_cast<floatx4*>(kp) = o0;
         *reinterpret_cast<floatx4*>(kp + H) = o1;
         *reinterpret_cast<floatx4*>(kp + 2 * H) = o2;
         *reinterpret_cast<floatx4*>(kp + 3 * H) = o3;
         if (a.kappa_width >= 5 * H) *reinterpret_cast<floatx4*>(kp + 4 * H) = o4;
+        if (MODE == STEP_RELAX_KAPPA2) {
+          float* kc = a.gc + oa2[it] + j;
+          *reinterpret_cast<floatx4*>(kc) = q0;
+          *reinterpret_cast<floatx4*>(kc + H) = q1;
+          *reinterpret_cast<floatx4*>(kc + 2 * H) = q2;
+          *reinterpret_cast<floatx4*>(kc + 3 * H) = q3;
+        }
       }
     }
   }
@@ -440,10 +491,14 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel(PhiArgs a) {
   const int n0 = ct * C::TN;
   const int tid = threadIdx.x;
   __shared__ PhiRow rowtab[C::TM];
+  __shared__ long long rowtab2[MODE == STEP_RELAX_KAPPA2 ? C::TM : 1];
   if (tid < C::TM) {
     long long r = m0 + tid;
     if (r >= R) r = R - 1;
-    rowtab[tid] = phi_row(a, r, (MODE == STEP_KAPPA || MODE == STEP_RELAX_KAPPA) ? a.kappa_width : H);
+    rowtab[tid] = phi_row(a, r,
+                          (MODE == STEP_KAPPA || MODE == STEP_RELAX_KAPPA ||
+                           MODE == STEP_RELAX_KAPPA2) ? a.kappa_width : H);
+    if (MODE == STEP_RELAX_KAPPA2) rowtab2[tid] = phi_row_coarse_kappa(a, r);
   }
   // (visible to all waves after the barriers inside the contraction)
 
@@ -481,7 +536,7 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel(PhiArgs a) {
     gemm_nt_tile<C, true>(acc, H, la, lb, Identity4(), Identity4(), lds);
 
   double nrm = 0.0;
-  phi_tile_epilogue<C, MODE>(a, acc, rowtab, lds, m0, n0, R, nrm);
+  phi_tile_epilogue<C, MODE>(a, acc, rowtab, lds, m0, n0, R, nrm, rowtab2);
   if (MODE == STEP_RESID && a.norm) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) nrm += __shfl_down(nrm, off, 64);
@@ -508,10 +563,14 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel_bf16(PhiArgs 
   const int tid = threadIdx.x;
   const bf16_t* U = (const bf16_t*)(C::NP == 3 ? a.U3 : a.U);
   __shared__ PhiRow rowtab[C::TM];
+  __shared__ long long rowtab2[MODE == STEP_RELAX_KAPPA2 ? C::TM : 1];
   if (tid < C::TM) {
     long long r = m0 + tid;
     if (r >= R) r = R - 1;
-    rowtab[tid] = phi_row(a, r, (MODE == STEP_KAPPA || MODE == STEP_RELAX_KAPPA) ? a.kappa_width : H);
+    rowtab[tid] = phi_row(a, r,
+                          (MODE == STEP_KAPPA || MODE == STEP_RELAX_KAPPA ||
+                           MODE == STEP_RELAX_KAPPA2) ? a.kappa_width : H);
+    if (MODE == STEP_RELAX_KAPPA2) rowtab2[tid] = phi_row_coarse_kappa(a, r);
   }
   // (visible to all waves after the barriers inside the contraction)
 
@@ -558,7 +617,7 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel_bf16(PhiArgs 
   }
 
   double nrm = 0.0;
-  phi_tile_epilogue<C, MODE>(a, acc, rowtab, ldsf, m0, n0, R, nrm);
+  phi_tile_epilogue<C, MODE>(a, acc, rowtab, ldsf, m0, n0, R, nrm, rowtab2);
   if (MODE == STEP_RESID && a.norm) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) nrm += __shfl_down(nrm, off, 64);
@@ -591,7 +650,9 @@ __global__ __launch_bounds__(PhiSkMaxNT<CT>::value) void phi_skinny_kernel(PhiAr
   const int tid = threadIdx.x;
   const int ks = tid & (ksl - 1), rg = tid / ksl;
   const int j0 = blockIdx.x * CT;
-  const int aux_w = (MODE == STEP_KAPPA || MODE == STEP_RELAX_KAPPA) ? a.kappa_width : H;
+  const int aux_w =
+      (MODE == STEP_KAPPA || MODE == STEP_RELAX_KAPPA || MODE == STEP_RELAX_KAPPA2) ? a.kappa_width
+                                                                                    : H;
 
   // this thread's output element (if any): its operands are requested first so
   // that their latency overlaps the dot products
@@ -641,11 +702,13 @@ __global__ __launch_bounds__(PhiSkMaxNT<CT>::value) void phi_skinny_kernel(PhiAr
     const float sz = skinny_sum<VP>(red, grp, base + CT + c, ksl);
     const float sn = skinny_sum<VP>(red, grp, base + 2 * CT + c, ksl);
     if (e == tid && epi) {
-      phi_epi_finish<MODE>(a, ero, e_j, sr, sz, sn, ein, ebh, nrm);
+      phi_epi_finish<MODE>(a, ero, e_j, sr, sz, sn, ein, ebh, nrm,
+                           MODE == STEP_RELAX_KAPPA2 ? phi_row_coarse_kappa(a, r0 + row) : 0);
     } else {   // more outputs than threads (tiny K only)
       const PhiRow ro = phi_row(a, r0 + row, aux_w);
       phi_epi_finish<MODE>(a, ro, j, sr, sz, sn, phi_epi_load<MODE>(a, ro, j), phi_bias_load(a, j),
-                           nrm);
+                           nrm,
+                           MODE == STEP_RELAX_KAPPA2 ? phi_row_coarse_kappa(a, r0 + row) : 0);
     }
   }
   if (MODE == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
@@ -679,6 +742,9 @@ typedef TileCfgB<1, 1, 1, 1, 3, true, 4, 1, 2, 3, 32> PhiSmallS;
       break;                                                                             \
     case STEP_RELAX_KAPPA:                                                               \
       hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_RELAX_KAPPA>), grid, block, 0, s, a); \
+      break;                                                                             \
+    case STEP_RELAX_KAPPA2:                                                              \
+      hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_RELAX_KAPPA2>), grid, block, 0, s, a); \
       break;                                                                             \
     case STEP_RELAX_RHS:                                                                 \
       if (a.zero_from > 0)                                                               \
@@ -730,6 +796,7 @@ static void launch_phi_skinny(const PhiArgs& a, dim3 grid, hipStream_t s) {
     case STEP_RHS: launch_phi_skinny_mode<CT, STEP_RHS>(a, grid, s); break;
     case STEP_RELAX_KAPPA: launch_phi_skinny_mode<CT, STEP_RELAX_KAPPA>(a, grid, s); break;
     case STEP_RELAX_RHS: launch_phi_skinny_mode<CT, STEP_RELAX_RHS>(a, grid, s); break;
+    case STEP_RELAX_KAPPA2: launch_phi_skinny_mode<CT, STEP_RELAX_KAPPA2>(a, grid, s); break;
     default: launch_phi_skinny_mode<CT, STEP_KAPPA>(a, grid, s);
   }
 }

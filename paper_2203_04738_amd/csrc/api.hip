@@ -204,8 +204,10 @@ static bool serial_scan_keeps_coeffs(const mgrit_gru_cfg& c) { return c.B > 64; 
 // in Eq. 11, and the contraction U h does not depend on the step size: that launch also
 // evaluates the coarse step and leaves  R u' - Phi_c(R u')  in the coarse right-hand side
 // array (mode STEP_RELAX_RHS).  *rhs_fused tells the caller whether such a launch ran.
+// first_done: the first sub-step of the sweep is in place already (see vcycle_fwd).
 static int relax_fwd(const FwdCtx& x, int l, bool include_c, bool f_points_current = false,
-                     bool emit = false, bool zero_c = false, bool* rhs_fused = nullptr) {
+                     bool emit = false, bool zero_c = false, bool* rhs_fused = nullptr,
+                     bool first_done = false) {
   const long long cf = x.c->cf, S = x.lay->S[l];
   const int nint = (int)(x.lay->N[l] / cf);
   if (rhs_fused) *rhs_fused = false;
@@ -213,7 +215,8 @@ static int relax_fwd(const FwdCtx& x, int l, bool include_c, bool f_points_curre
   // points (they were written by the closing F-relaxation of the previous cycle of
   // this call and nothing changed since), so recomputing them would reproduce the
   // same bits; only the C-sweep remains.
-  for (long long j = f_points_current ? cf : 1; j < cf + (include_c ? 1 : 0); ++j) {
+  for (long long j = f_points_current ? cf : (first_done ? 2 : 1); j < cf + (include_c ? 1 : 0);
+       ++j) {
     PhiArgs a = phi_base(x, l);
     a.mode = STEP_RELAX;
     if (emit && x.emit_kap && l == 0) {
@@ -259,8 +262,10 @@ static int relax_fwd(const FwdCtx& x, int l, bool include_c, bool f_points_curre
   return MGRIT_OK;
 }
 
+// first_f_done (coarse levels): the iterate is the restricted one and the parent's residual
+// launch has written the values of the first relaxation sub-step, R u' - R r, already.
 static int vcycle_fwd(const FwdCtx& x, int l, bool f_points_current = false, bool last = false,
-                      bool zero_guess = false) {
+                      bool zero_guess = false, bool first_f_done = false) {
   const long long cf = x.c->cf, S = x.lay->S[l], N = x.lay->N[l];
   const int L = x.lay->L;
   if (l == L - 1) {
@@ -289,11 +294,12 @@ static int vcycle_fwd(const FwdCtx& x, int l, bool f_points_current = false, boo
   if (l == 0 && x.c->fine_relax == 0) {
     if ((rc = relax_fwd(x, l, false, cur, false, zc, &rhs_fused))) return rc;
   } else {
-    if ((rc = relax_fwd(x, l, true, cur, false, zc))) return rc;
+    if ((rc = relax_fwd(x, l, true, cur, false, zc, nullptr, first_f_done))) return rc;
     if ((rc = relax_fwd(x, l, false, false, false, false, &rhs_fused))) return rc;
   }
   const int Nc = (int)(N / cf);
   const long long Sc = x.lay->S[l + 1];
+  bool child_first_done = false;
   {  // lines 2-3: residual at the coarse points, restricted state
     PhiArgs a = phi_base(x, l);
     a.mode = STEP_RESID;
@@ -306,6 +312,15 @@ static int vcycle_fwd(const FwdCtx& x, int l, bool f_points_current = false, boo
     a.gc = x.gl[l + 1];
     a.norm = l == 0 ? x.norm : nullptr;
     a.resid_adds = rhs_fused ? 1 : 0;     // completes g_c = (R u' - Phi_c(R u')) - R r
+    // A coarse level that relaxes starts with an F-sweep from the restricted iterate; its first
+    // sub-step gives Phi_c(R u')_k + g_k = (R u')_k - (R r)_k at the points k = 1 (mod cf): this
+    // launch writes them.  (Only with the fused right-hand side: a separate right-hand-side
+    // launch reads the restricted iterate from the coarse array.)
+    child_first_done = rhs_fused && cf > 1 && l + 1 < L - 1;
+    if (child_first_done) {
+      a.ff_cf = (int)cf;
+      a.ff_rem = 1;
+    }
     CHECK_HIP(launch_phi_step(a, x.s));
   }
   if (!rhs_fused) {  // line 4, right-hand side of Eq. 11: g_c = A_c(R u') - R r
@@ -317,7 +332,7 @@ static int vcycle_fwd(const FwdCtx& x, int l, bool f_points_current = false, boo
     a.p = Idx{Sc - 1, Sc};
     CHECK_HIP(launch_phi_step(a, x.s));
   }
-  if ((rc = vcycle_fwd(x, l + 1))) return rc;
+  if ((rc = vcycle_fwd(x, l + 1, false, false, false, child_first_done))) return rc;
   // line 5 at the coarse points: u'_{cf j} + (v_j - u'_{cf j}) = v_j.  F-points
   // would receive the same correction but are overwritten by line 6.
   CHECK_HIP(launch_copy_points(x.ul[l], x.ul[l + 1], Idx{cf, cf}, Idx{1, 1}, Nc,

@@ -63,6 +63,12 @@ struct PhiArgs {
   float gamma2;        // step size of the coarse level
   int resid_adds;      // STEP_RESID: gc[a] = gc[a] - r instead of -r (gc was prepared by
                        // STEP_RELAX_RHS)
+  // STEP_RESID, ff_cf > 0: at coarse points whose index is ff_rem modulo ff_cf the coarse
+  // array receives cur - r instead of cur.  Those are the points the coarse level's first
+  // relaxation sub-step writes, and from the restricted iterate that sub-step gives
+  // Phi_c(R u')_k + g_k = (R u')_k - (R r)_k by the definition of g (Eq. 11): no evaluation
+  // of Phi is needed for it.
+  int ff_cf, ff_rem;
 };
 
 // One launch of the fused adjoint step  w_out = (dPhi/dh)^T w_in  over nk points.

@@ -192,6 +192,8 @@ __device__ inline PhiRow phi_row(const PhiArgs& a, long long r, int aux_width) {
   ro.p = (a.p.at(pt) * a.B + b) * (3LL * a.H);
   ro.o = (a.o.at(pt) * a.B + b) * a.H;
   ro.a = ((aux_width == a.H ? a.a.at(pt) : a.o.at(pt)) * a.B + b) * (long long)aux_width;
+  // (row offsets are multiples of four elements: bit 0 marks the coarse points of ff_cf / ff_rem)
+  if (a.ff_cf > 0 && a.a.at(pt) % a.ff_cf == a.ff_rem) ro.a |= 1;
   return ro;
 }
 // STEP_RELAX_KAPPA2: element offset of the row's coarse output point (index a) in the coarse
@@ -228,7 +230,7 @@ __device__ inline PhiEpiIn phi_epi_load(const PhiArgs& a, const PhiRow& ro, int 
     e.pn2 = p2[2 * H + j];
     if (MODE == STEP_RELAX_RHS) e.cur2 = a.u[oi + a.do2];
   }
-  if (MODE == STEP_RESID && a.resid_adds) e.prep = a.gc[ro.a + j];
+  if (MODE == STEP_RESID && a.resid_adds) e.prep = a.gc[(ro.a & ~1LL) + j];
   return e;
 }
 
@@ -330,9 +332,9 @@ __device__ inline void phi_epi_finish(const PhiArgs& a, const PhiRow& ro, int j,
     a.u[oi] = o.v0;
     a.gc[ro.a + j] = o.v1;
   } else if (MODE == STEP_RESID) {
-    const long long ai = ro.a + j;
+    const long long ai = (ro.a & ~1LL) + j;
     a.gc[ai] = a.resid_adds ? e.prep + o.v0 : o.v0;
-    a.uc[ai] = o.v1;
+    a.uc[ai] = (ro.a & 1) ? o.v1 + o.v0 : o.v1;        // cur - r at the marked points
     nrm += (double)o.v0 * (double)o.v0;
   } else if (MODE == STEP_RHS) {
     a.g[oi] = o.v0;
@@ -414,7 +416,8 @@ __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Ph
         if (MODE == STEP_RELAX_RHS) ex[it].cur2 = ldg4(a.u + ro.o + a.do2 + jc);
         if (MODE == STEP_RELAX_KAPPA2) oa2[it] = rowtab2[trow[it]];
       }
-      if (MODE == STEP_RESID) ex[it].prep = a.resid_adds ? ldg4(a.gc + ro.a + jc) : zero4();
+      if (MODE == STEP_RESID)
+        ex[it].prep = a.resid_adds ? ldg4(a.gc + (ro.a & ~1LL) + jc) : zero4();
     }
     __syncthreads();
 #pragma unroll
@@ -447,10 +450,10 @@ __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Ph
         *reinterpret_cast<floatx4*>(a.u + oi) = o0;
         *reinterpret_cast<floatx4*>(a.gc + oa[it] + j) = o1;
       } else if (MODE == STEP_RESID) {
-        const long long ai = oa[it] + j;
+        const long long ai = (oa[it] & ~1LL) + j;
         // (adding the zero of a launch without a prepared half changes no value)
         *reinterpret_cast<floatx4*>(a.gc + ai) = ex[it].prep + o0;
-        *reinterpret_cast<floatx4*>(a.uc + ai) = o1;
+        *reinterpret_cast<floatx4*>(a.uc + ai) = (oa[it] & 1) ? o1 + o0 : o1;   // cur - r if marked
 #pragma unroll
         for (int i = 0; i < 4; ++i) nrm += (double)o0[i] * (double)o0[i];
       } else if (MODE == STEP_RHS) {

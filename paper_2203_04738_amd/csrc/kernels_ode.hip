@@ -25,6 +25,8 @@ __device__ inline OdeRow ode_row(const PhiArgs& a, long long r) {
   ro.p = (a.p.at(pt) * a.B + b) * a.H;
   ro.o = (a.o.at(pt) * a.B + b) * a.H;
   ro.a = (a.a.at(pt) * a.B + b) * a.H;
+  // (row offsets are multiples of four elements: bit 0 marks the coarse points of ff_cf / ff_rem)
+  if (a.ff_cf > 0 && a.a.at(pt) % a.ff_cf == a.ff_rem) ro.a |= 1;
   return ro;
 }
 
@@ -71,7 +73,8 @@ __device__ inline void ode_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Od
         ex[it].p2 = ldg4(a.P + ro.p + a.dp2 + jc);
         ex[it].cur2 = ldg4(a.u + ro.o + a.do2 + jc);
       }
-      if (MODE == STEP_RESID) ex[it].prep = a.resid_adds ? ldg4(a.gc + ro.a + jc) : zero4();
+      if (MODE == STEP_RESID)
+        ex[it].prep = a.resid_adds ? ldg4(a.gc + (ro.a & ~1LL) + jc) : zero4();
     }
     __syncthreads();
 #pragma unroll
@@ -99,9 +102,10 @@ __device__ inline void ode_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Od
         *reinterpret_cast<floatx4*>(a.gc + oa[it] + j) = ex[it].cur2 - hn2;
       } else if (MODE == STEP_RESID) {
         const floatx4 res = in[it].cur - hn - in[it].gval;
-        const long long ai = oa[it] + j;
+        const long long ai = (oa[it] & ~1LL) + j;
         *reinterpret_cast<floatx4*>(a.gc + ai) = ex[it].prep + (-res);
-        *reinterpret_cast<floatx4*>(a.uc + ai) = in[it].cur;
+        // cur - r at the marked points
+        *reinterpret_cast<floatx4*>(a.uc + ai) = (oa[it] & 1) ? in[it].cur - res : in[it].cur;
 #pragma unroll
         for (int i = 0; i < 4; ++i) nrm += (double)res[i] * (double)res[i];
       } else {  // STEP_RHS
@@ -189,7 +193,7 @@ __device__ inline OdeEpiIn ode_epi_load(const PhiArgs& a, const OdeRow& ro, int 
     e.p2 = a.P[ro.p + a.dp2 + j];
     e.cur2 = a.u[ro.o + a.do2 + j];
   }
-  if (MODE == STEP_RESID && a.resid_adds) e.prep = a.gc[ro.a + j];
+  if (MODE == STEP_RESID && a.resid_adds) e.prep = a.gc[(ro.a & ~1LL) + j];
   return e;
 }
 template <int MODE>
@@ -205,9 +209,9 @@ __device__ inline void ode_epi_finish(const PhiArgs& a, const OdeRow& ro, int j,
     a.gc[ro.a + j] = e.cur2 - hn2;
   } else if (MODE == STEP_RESID) {
     const float res = e.cur - hn - e.gval;
-    const long long ai = ro.a + j;
+    const long long ai = (ro.a & ~1LL) + j;
     a.gc[ai] = a.resid_adds ? e.prep + (-res) : -res;
-    a.uc[ai] = e.cur;
+    a.uc[ai] = (ro.a & 1) ? e.cur - res : e.cur;       // cur - r at the marked points
     nrm += (double)res * (double)res;
   } else {  // STEP_RHS
     a.g[oi] = (e.cur - hn) + e.gval;

@@ -469,8 +469,9 @@ static AdjArgs adj_base(const BwdCtx& x, int l) {
 // homogeneous, so an interval whose upper coarse point lies below *lo stays zero and is
 // left out of the launches; on return *lo is the bound that holds after the sweep (one
 // interval lower).
+// first_done: the first sub-step of the sweep is in place already (see vcycle_bwd).
 static int relax_bwd(const BwdCtx& x, int l, bool include_c, bool f_points_current = false,
-                     long long* lo = nullptr) {
+                     long long* lo = nullptr, bool first_done = false) {
   const long long cf = x.c->cf;
   const int nint = (int)(x.lay->N[l] / cf);
   long long i0 = 0;                        // first interval that can hold non-zero values
@@ -479,7 +480,8 @@ static int relax_bwd(const BwdCtx& x, int l, bool include_c, bool f_points_curre
     if (i0 < 0) i0 = 0;
     *lo = i0 * cf;
   }
-  for (long long j = f_points_current ? cf : 1; j < cf + (include_c ? 1 : 0); ++j) {
+  for (long long j = f_points_current ? cf : (first_done ? 2 : 1); j < cf + (include_c ? 1 : 0);
+       ++j) {
     AdjArgs a = adj_base(x, l);
     a.mode = STEP_RELAX;
     a.nk = nint - (int)i0;
@@ -497,8 +499,10 @@ static int relax_bwd(const BwdCtx& x, int l, bool include_c, bool f_points_curre
 
 // lo_in: bound below which adjoint and right-hand side of this level are zero on entry (see
 // relax_bwd; 0 = nothing known).
+// first_f_done (coarse levels): the iterate is the restricted one and the parent's residual
+// launch has written the values of the first relaxation sub-step, R w' - R r, already.
 static int vcycle_bwd(const BwdCtx& x, int l, bool f_points_current = false,
-                      long long lo_in = 0) {
+                      long long lo_in = 0, bool first_f_done = false) {
   const long long cf = x.c->cf, N = x.lay->N[l];
   const int L = x.lay->L;
   if (l == L - 1) {
@@ -521,7 +525,7 @@ static int vcycle_bwd(const BwdCtx& x, int l, bool f_points_current = false,
   if (l == 0 && x.c->fine_relax == 0) {
     if ((rc = relax_bwd(x, l, false, cur, plo))) return rc;
   } else {
-    if ((rc = relax_bwd(x, l, true, cur, plo))) return rc;
+    if ((rc = relax_bwd(x, l, true, cur, plo, first_f_done))) return rc;
     if ((rc = relax_bwd(x, l, false, false, plo))) return rc;
   }
   const int Nc = (int)(N / cf);
@@ -529,6 +533,10 @@ static int vcycle_bwd(const BwdCtx& x, int l, bool f_points_current = false,
   // side: their residual and their restricted value are zero and are written as such
   const long long iR = lo / cf;            // first coarse point with a non-zero residual
   const long long jR = iR > 0 ? iR - 1 : 0;  // first one with a non-zero coarse right-hand side
+  // A coarse level that relaxes starts with an F-sweep from the restricted iterate; its first
+  // sub-step gives (Phi_c^T R w')_k + g_k = (R w')_k - (R r)_k at the points k = cf - 1 (mod cf):
+  // the residual launch writes them (not in a cycle that skips zero intervals).
+  const bool child_first_done = cf > 1 && l + 1 < L - 1 && iR == 0;
   if (iR > 0) {
     const long long BH = (long long)x.c->B * x.c->H;
     CHECK_HIP(launch_zero_f32(x.wl[l + 1], iR * BH, x.s));
@@ -545,6 +553,10 @@ static int vcycle_bwd(const BwdCtx& x, int l, bool f_points_current = false,
     a.wc = x.wl[l + 1];
     a.gc = x.gl[l + 1];
     a.norm = l == 0 ? x.norm : nullptr;
+    if (child_first_done) {
+      a.ff_cf = (int)cf;
+      a.ff_rem = (int)cf - 1;
+    }
     CHECK_HIP(launch_adj_step(a, x.s));
   }
   {  // coarse right-hand side
@@ -554,10 +566,22 @@ static int vcycle_bwd(const BwdCtx& x, int l, bool f_points_current = false,
     a.in = Idx{1 + jR, 1};
     a.k = a.in;
     a.o = Idx{jR, 1};
+    if (child_first_done) {
+      // the coarse array holds first-sub-step values at some points: the restricted iterate
+      // is read from this level's coarse points instead
+      a.w_in = x.wl[l];
+      a.w = x.wl[l];
+      a.in = Idx{(1 + jR) * cf, cf};
+      a.o = Idx{jR * cf, cf};
+      a.a = Idx{jR, 1};
+      a.gc = x.gl[l + 1];
+      a.g = nullptr;
+      a.rhs_coarse_g = 1;
+    }
     CHECK_HIP(launch_adj_step(a, x.s));
   }
   // on the coarse level the adjoint is zero below iR and the right-hand side below jR
-  if ((rc = vcycle_bwd(x, l + 1, false, jR / cf * cf))) return rc;
+  if ((rc = vcycle_bwd(x, l + 1, false, jR / cf * cf, child_first_done))) return rc;
   CHECK_HIP(launch_copy_points(x.wl[l], x.wl[l + 1], Idx{0, cf}, Idx{0, 1}, Nc,
                                (long long)x.c->B * x.c->H, x.s));
   return relax_bwd(x, l, false);

@@ -86,6 +86,10 @@ struct AdjArgs {
   int mode;
   int bf16;            // operand form, as in PhiArgs
   const void* UT3;     // bf16 == 2: the three bf16 terms of UT, [3][H,3H]
+  int ff_cf, ff_rem;   // STEP_RESID: as in PhiArgs (the coarse array receives cur - r at the
+                       // coarse points of index ff_rem modulo ff_cf)
+  int rhs_coarse_g;    // STEP_RHS: the right-hand side is read and written in gc at index a
+                       // (w_in / w then address another level's array through in / o); g unused
 };
 
 // Internal propagator code (beside the public MGRIT_PROP_* values): the forward-Euler

@@ -497,10 +497,16 @@ static int relax_bwd(const BwdCtx& x, int l, bool include_c, bool f_points_curre
   return MGRIT_OK;
 }
 
-// lo_in: bound below which adjoint and right-hand side of this level are zero on entry (see
-// relax_bwd; 0 = nothing known).
-// first_f_done (coarse levels): the iterate is the restricted one and the parent's residual
-// launch has written the values of the first relaxation sub-step, R w' - R r, already.
+// The adjoint recurrence is linear, so the coarse equation of Eq. 11 can be written for the
+// error: with v = R w' + e its right-hand side A_c(R w') - R r turns into -R r and its initial
+// guess R w' into zero; every relaxation and coarse solve then produces e where the scheme for
+// v produces v - R w', and the correction adds e at the coarse points.  The iterates are those
+// of Eq. 11 (up to rounding) without the launch that applies A_c to R w'.
+//
+// lo_in: bound below which the iterate and the right-hand side of this level are zero on entry
+// (see relax_bwd; 0 = nothing known).
+// first_f_done (coarse levels): the parent's residual launch has written the values of the
+// first relaxation sub-step from the zero guess, -R r, already.
 static int vcycle_bwd(const BwdCtx& x, int l, bool f_points_current = false,
                       long long lo_in = 0, bool first_f_done = false) {
   const long long cf = x.c->cf, N = x.lay->N[l];
@@ -529,20 +535,19 @@ static int vcycle_bwd(const BwdCtx& x, int l, bool f_points_current = false,
     if ((rc = relax_bwd(x, l, false, false, plo))) return rc;
   }
   const int Nc = (int)(N / cf);
-  // coarse points below lo have a zero adjoint, a zero successor and a zero right-hand
-  // side: their residual and their restricted value are zero and are written as such
+  // coarse points below lo have a zero iterate, a zero successor and a zero right-hand
+  // side: their residual is zero and is written as such
   const long long iR = lo / cf;            // first coarse point with a non-zero residual
-  const long long jR = iR > 0 ? iR - 1 : 0;  // first one with a non-zero coarse right-hand side
-  // A coarse level that relaxes starts with an F-sweep from the restricted iterate; its first
-  // sub-step gives (Phi_c^T R w')_k + g_k = (R w')_k - (R r)_k at the points k = cf - 1 (mod cf):
-  // the residual launch writes them (not in a cycle that skips zero intervals).
+  // A coarse level that relaxes starts with an F-sweep from its zero guess; the first sub-step
+  // gives g_k = -(R r)_k at the points k = cf - 1 (mod cf): the residual launch writes them
+  // (not in a cycle that skips zero intervals).
   const bool child_first_done = cf > 1 && l + 1 < L - 1 && iR == 0;
+  const long long BH = (long long)x.c->B * x.c->H;
   if (iR > 0) {
-    const long long BH = (long long)x.c->B * x.c->H;
     CHECK_HIP(launch_zero_f32(x.wl[l + 1], iR * BH, x.s));
     CHECK_HIP(launch_zero_f32(x.gl[l + 1], iR * BH, x.s));
   }
-  {  // residual at coarse points i*cf, i = iR..Nc-1, and restriction
+  {  // residual at coarse points i*cf, i = iR..Nc-1; coarse right-hand side -R r, zero guess
     AdjArgs a = adj_base(x, l);
     a.mode = STEP_RESID;
     a.nk = Nc - (int)iR;
@@ -559,31 +564,10 @@ static int vcycle_bwd(const BwdCtx& x, int l, bool f_points_current = false,
     }
     CHECK_HIP(launch_adj_step(a, x.s));
   }
-  {  // coarse right-hand side
-    AdjArgs a = adj_base(x, l + 1);
-    a.mode = STEP_RHS;
-    a.nk = Nc - (int)jR;
-    a.in = Idx{1 + jR, 1};
-    a.k = a.in;
-    a.o = Idx{jR, 1};
-    if (child_first_done) {
-      // the coarse array holds first-sub-step values at some points: the restricted iterate
-      // is read from this level's coarse points instead
-      a.w_in = x.wl[l];
-      a.w = x.wl[l];
-      a.in = Idx{(1 + jR) * cf, cf};
-      a.o = Idx{jR * cf, cf};
-      a.a = Idx{jR, 1};
-      a.gc = x.gl[l + 1];
-      a.g = nullptr;
-      a.rhs_coarse_g = 1;
-    }
-    CHECK_HIP(launch_adj_step(a, x.s));
-  }
-  // on the coarse level the adjoint is zero below iR and the right-hand side below jR
-  if ((rc = vcycle_bwd(x, l + 1, false, jR / cf * cf, child_first_done))) return rc;
-  CHECK_HIP(launch_copy_points(x.wl[l], x.wl[l + 1], Idx{0, cf}, Idx{0, 1}, Nc,
-                               (long long)x.c->B * x.c->H, x.s));
+  // on the coarse level iterate and right-hand side are zero below iR
+  if ((rc = vcycle_bwd(x, l + 1, false, iR / cf * cf, child_first_done))) return rc;
+  // correction at the coarse points: w'_{cf i} + e_i (the coarse solve carries e below iR too)
+  CHECK_HIP(launch_add_points(x.wl[l], x.wl[l + 1], Idx{0, cf}, Idx{0, 1}, Nc, BH, x.s));
   return relax_bwd(x, l, false);
 }
 
@@ -681,8 +665,12 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
     // step of level 1
     if (l == 1 && (c.flags & MGRIT_REUSE_COEFFS) && c.cf > 1) a.nk = 0;
     CHECK_HIP(launch_phi_step(a, s));
-    // the terminal condition w_T = dL/dh_T is the fixed end point of every level
-    CHECK_HIP(launch_copy_points(ctx.wl[l], dL_dhT, Idx{lay.N[l], 0}, Idx{0, 0}, 1, BH, s));
+    // the terminal condition w_T = dL/dh_T is the fixed end point of level 0; the coarse levels
+    // solve for errors, whose end point is zero
+    if (l == 0)
+      CHECK_HIP(launch_copy_points(ctx.wl[l], dL_dhT, Idx{lay.N[l], 0}, Idx{0, 0}, 1, BH, s));
+    else
+      CHECK_HIP(launch_zero_f32(ctx.wl[l] + lay.N[l] * BH, BH, s));
   }
   double* norm = (double*)(base + lay.norm);
   if (resnorm && c.iters > 0) CHECK_HIP(launch_fill_f64(norm, c.iters, 0.0, s));

@@ -18,6 +18,7 @@ enum StepMode {
   STEP_RELAX = 0,   // out[o] = step(in) + g[o]                       (Alg. 1 update; coarsest solve)
   STEP_RESID = 1,   // r = cur[o] - step(in) - g[o];  gc[a] = -r; uc[a] = cur[o]; norm += r^2
                     //                                                 (Alg. 2 lines 2-3)
+                    // adjoint: wc[a] = 0 instead (error equation of a linear problem)
   STEP_RHS = 2,     // g[o] = cur[o] - step(in) + g[o]                 (Eq. 11 right-hand side)
   STEP_KAPPA = 3,   // forward only: adjoint coefficient vectors of the step
   STEP_RELAX_KAPPA = 4, // forward only: STEP_RELAX that also leaves the coefficient vectors of
@@ -86,10 +87,10 @@ struct AdjArgs {
   int mode;
   int bf16;            // operand form, as in PhiArgs
   const void* UT3;     // bf16 == 2: the three bf16 terms of UT, [3][H,3H]
-  int ff_cf, ff_rem;   // STEP_RESID: as in PhiArgs (the coarse array receives cur - r at the
-                       // coarse points of index ff_rem modulo ff_cf)
-  int rhs_coarse_g;    // STEP_RHS: the right-hand side is read and written in gc at index a
-                       // (w_in / w then address another level's array through in / o); g unused
+  int ff_cf, ff_rem;   // STEP_RESID: the coarse array wc receives the zero initial guess of the
+                       // coarse error equation, except at the coarse points of index ff_rem
+                       // modulo ff_cf (ff_cf > 0), which receive -r: the value the coarse level's
+                       // first relaxation sub-step gives from that guess
 };
 
 // Internal propagator code (beside the public MGRIT_PROP_* values): the forward-Euler
@@ -135,6 +136,9 @@ hipError_t launch_fill_f64(double* p, long long n, double v, hipStream_t s);
 hipError_t launch_zero_f32(float* p, long long n, hipStream_t s);
 // dst[(d.off + i*d.str), :, :] = src[(s.off + i*s.str), :, :] for i < nk; blocks of `block` floats
 hipError_t launch_copy_points(float* dst, const float* src, Idx d, Idx s, int nk, long long block,
+                              hipStream_t st);
+// dst[d.at(i)] += src[s.at(i)] for i < nk (blocks of `block` floats)
+hipError_t launch_add_points(float* dst, const float* src, Idx d, Idx s, int nk, long long block,
                               hipStream_t st);
 hipError_t launch_sqrt_to_float(const double* acc, float* out, int n, hipStream_t s);
 

@@ -42,7 +42,6 @@ __device__ inline AdjEpiIn adj_epi_load(const AdjArgs& a, const AdjRow& ro, int 
   e.wv = a.w_in[ro.in + j];
   const long long oi = ro.o + j;
   e.gval = a.g ? a.g[oi] : 0.f;
-  if (MODE == STEP_RHS && a.rhs_coarse_g) e.gval = a.gc[ro.a + j];
   e.cur = (MODE == STEP_RESID || MODE == STEP_RHS) ? a.w[oi] : 0.f;
   return e;
 }
@@ -60,12 +59,10 @@ __device__ inline void adj_epi_finish(const AdjArgs& a, const AdjRow& ro, int j,
     const float res = e.cur - wn - e.gval;
     const long long ai = (ro.a & ~1LL) + j;
     a.gc[ai] = -res;
-    a.wc[ai] = (ro.a & 1) ? e.cur - res : e.cur;       // cur - r at the marked points
+    a.wc[ai] = (ro.a & 1) ? -res : 0.f;                // zero guess; -r at the marked points
     nrm += (double)res * (double)res;
   } else {  // STEP_RHS
-    const float gn = (e.cur - wn) + e.gval;
-    if (a.rhs_coarse_g) a.gc[ro.a + j] = gn;
-    else a.g[oi] = gn;
+    a.g[oi] = (e.cur - wn) + e.gval;
   }
 }
 
@@ -99,7 +96,6 @@ __device__ inline void adj_tile_epilogue(const AdjArgs& a, Acc<C>& acc, const Ad
       in[it].kd = ldg4(a.kap + ro.k + 3 * H + jc);
       in[it].wv = ldg4(a.w_in + ro.in + jc);
       in[it].gval = a.g ? ldg4(a.g + ro.o + jc) : zero4();
-      if (MODE == STEP_RHS && a.rhs_coarse_g) in[it].gval = ldg4(a.gc + ro.a + jc);
       in[it].cur = (MODE == STEP_RESID || MODE == STEP_RHS) ? ldg4(a.w + ro.o + jc) : zero4();
     }
     __syncthreads();
@@ -115,14 +111,12 @@ __device__ inline void adj_tile_epilogue(const AdjArgs& a, Acc<C>& acc, const Ad
         const floatx4 res = in[it].cur - wn - in[it].gval;
         const long long ai = (oa[it] & ~1LL) + j;
         *reinterpret_cast<floatx4*>(a.gc + ai) = -res;
-        // cur - r at the marked points
-        *reinterpret_cast<floatx4*>(a.wc + ai) = (oa[it] & 1) ? in[it].cur - res : in[it].cur;
+        // zero guess of the coarse error equation; -r at the marked points
+        *reinterpret_cast<floatx4*>(a.wc + ai) = (oa[it] & 1) ? -res : zero4();
 #pragma unroll
         for (int i = 0; i < 4; ++i) nrm += (double)res[i] * (double)res[i];
       } else {  // STEP_RHS
-        const floatx4 gn = (in[it].cur - wn) + in[it].gval;
-        if (a.rhs_coarse_g) *reinterpret_cast<floatx4*>(a.gc + oa[it] + j) = gn;
-        else *reinterpret_cast<floatx4*>(a.g + oi) = gn;
+        *reinterpret_cast<floatx4*>(a.g + oi) = (in[it].cur - wn) + in[it].gval;
       }
     }
   }

@@ -53,6 +53,28 @@ hipError_t launch_copy_points(float* dst, const float* src, Idx d, Idx s, int nk
   return hipGetLastError();
 }
 
+__global__ void add_points_kernel(float* __restrict__ dst, const float* __restrict__ src, Idx d,
+                                  Idx s, int nk, long long block4) {
+  long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (long long)nk * block4) return;
+  long long pt = i / block4, e = i - pt * block4;
+  const floatx4* sp = reinterpret_cast<const floatx4*>(src) + s.at(pt) * block4 + e;
+  floatx4* dp = reinterpret_cast<floatx4*>(dst) + d.at(pt) * block4 + e;
+  *dp = *dp + *sp;
+}
+
+hipError_t launch_add_points(float* dst, const float* src, Idx d, Idx s, int nk, long long block,
+                             hipStream_t st) {
+  if (nk <= 0) return hipSuccess;
+  const long long block4 = block / 4;
+  const long long n = (long long)nk * block4;
+  prof_begin(7, st, nk);
+  hipLaunchKernelGGL(add_points_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, dst,
+                     src, d, s, nk, block4);
+  prof_end(7, 0.0, 12.0 * (double)nk * (double)block, st);   // two reads and one write per float
+  return hipGetLastError();
+}
+
 // Three-term bf16 form of an fp32 array (weights of the MGRIT_F32_BF16X3 path).
 __global__ void split3_kernel(const float* __restrict__ src, unsigned short* __restrict__ dst,
                               long long n4) {

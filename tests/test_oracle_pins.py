@@ -564,3 +564,69 @@ def test_implicit_step_and_its_adjoint_against_autograd(gamma_steps):
                                     np.concatenate([np.zeros((T, B, H)), d["dL_dhT"][None]]))
         for a, b in zip(out[1:], (W.grad, U.grad, b_i.grad, b_h.grad, x.grad)):
             assert np.allclose(a, b.numpy(), atol=1e-12)
+
+
+# ---------------------------------------------------------------- error form of the adjoint cycle
+
+def _error_form_cycle(step, cf, levels, l, u, g, fcf, resnorms):
+    """One cycle with the coarse equation written for the error (zero coarse guess, right-hand
+    side -R r, additive correction): what a linear level equation allows instead of Eq. 11."""
+    N = u.shape[0] - 1
+    if l == levels - 1:
+        out = u.copy()
+        for k in range(1, N + 1):
+            out[k] = step(l, np.array([k]), out[k - 1:k])[0] + g[k]
+        return out
+    if l == 0 and not fcf:
+        up = orc.relax(step, l, cf, u, g, False)
+    else:
+        up = orc.relax(step, l, cf, orc.relax(step, l, cf, u, g, True), g, False)
+    Nc = N // cf
+    cpts = cf * np.arange(1, Nc + 1)
+    r = up[cpts] - step(l, cpts, up[cpts - 1]) - g[cpts]
+    if l == 0:
+        resnorms.append(float(np.sqrt(np.sum(r * r))))
+    gc = np.zeros((Nc + 1,) + u.shape[1:])
+    gc[1:] = -r
+    e = _error_form_cycle(step, cf, levels, l + 1, np.zeros_like(gc), gc, fcf, resnorms)
+    upp = up.copy()
+    upp[cf * np.arange(0, Nc + 1)] += e
+    return orc.relax(step, l, cf, upp, g, False)
+
+
+@pytest.mark.parametrize("T,cf,levels,fcf,every_state", [(64, 4, 3, True, False),
+                                                         (32, 2, 4, True, True),
+                                                         (64, 4, 2, False, False)])
+def test_adjoint_cycle_in_error_form_gives_the_iterates_of_eq_11(T, cf, levels, fcf, every_state):
+    """The adjoint recurrence is linear, so the full-approximation coarse equation of Eq. 11
+    (unknown v, right-hand side A_c(R w') - R r, guess R w') and the error equation (unknown
+    e = v - R w', right-hand side -R r, zero guess) produce the same iterates.  The HIP path
+    runs the adjoint cycle in the second form; this pins that form to the oracle's cycle."""
+    B, D, H = 3, 5, 6
+    d = random_small(5, T, B, D, H)
+    W, U, b_i, b_h = (np.asarray(a, np.float64) for a in _params(d))
+    x = np.asarray(d["x"], np.float64)
+    h = orc.serial_scan(W, U, b_i, b_h, x, d["h0"])
+    dL = np.random.default_rng(1).standard_normal((T + 1, B, H)) if every_state else None
+    out = orc.mgrit_backward(W, U, b_i, b_h, x, h, d["dL_dhT"], np.zeros((T + 1, B, H)), cf,
+                             levels, 3, fine_relax_fcf=fcf, keep_iterates=True, dL_dh=dL)
+    want, want_res = out[-1], out[1]
+    P = orc.input_projection(W, b_i, x)
+
+    def step(l, ms, v):
+        s = cf ** l
+        k = T // s - ms + 1
+        co = orc.phi_adjoint_coeffs(float(s), P[k * s - 1], h[(k - 1) * s], U, b_h, orc.IMPLICIT)
+        return orc.phi_transpose(co, v, U)
+
+    w = np.zeros((T + 1, B, H))
+    w[T] = dL[-1] if every_state else d["dL_dhT"]
+    wr = w[::-1].copy()
+    g0 = np.zeros_like(wr)
+    if every_state:
+        g0[1:] = dL[::-1][1:]
+    res = []
+    for it in range(3):
+        wr = _error_form_cycle(step, cf, levels, 0, wr, g0, fcf, res)
+        assert _rel(wr[::-1], want[it]) < 1e-13
+        assert abs(res[it] - want_res[it]) <= 1e-12 * want_res[it]

@@ -174,7 +174,9 @@ MGRIT_API int gru_serial_scan_backward(const mgrit_gru_cfg* cfg, const void* W, 
  * cycle run on the adjoint recurrence in reversed time (Appendix A.1 last
  * paragraph, A.2 last paragraph; Alg. 3 backward block), each level step being
  * the transposed Jacobian of that level's forward step linearised at the given
- * forward iterate h; then the parameter gradients from the final w.
+ * forward iterate h; then the parameter gradients from the final w.  (The
+ * adjoint recurrence is linear: the coarse equations of the cycle are solved
+ * for the error, which gives the iterates of the Eq. 11 form up to rounding.)
  *   w_inout[(T+1),B,H]: initial guess in (Alg. 3 uses zeros), iterate out; row T
  *     is overwritten with dL_dhT.
  *   resnorm_out[iters] (device, may be NULL): as in mgrit_gru_forward, for the

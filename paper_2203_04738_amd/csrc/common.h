@@ -19,7 +19,7 @@ enum StepMode {
   STEP_RESID = 1,   // r = cur[o] - step(in) - g[o];  gc[a] = -r; uc[a] = cur[o]; norm += r^2
                     //                                                 (Alg. 2 lines 2-3)
                     // adjoint: wc[a] = 0 instead (error equation of a linear problem)
-  STEP_RHS = 2,     // g[o] = cur[o] - step(in) + g[o]                 (Eq. 11 right-hand side)
+  STEP_RHS = 2,     // forward only: g[o] = cur[o] - step(in) + g[o]   (Eq. 11 right-hand side)
   STEP_KAPPA = 3,   // forward only: adjoint coefficient vectors of the step
   STEP_RELAX_KAPPA = 4, // forward only: STEP_RELAX that also leaves the coefficient vectors of
                         // the step it takes (row = output point) in uc

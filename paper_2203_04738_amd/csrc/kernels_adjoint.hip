@@ -42,7 +42,7 @@ __device__ inline AdjEpiIn adj_epi_load(const AdjArgs& a, const AdjRow& ro, int 
   e.wv = a.w_in[ro.in + j];
   const long long oi = ro.o + j;
   e.gval = a.g ? a.g[oi] : 0.f;
-  e.cur = (MODE == STEP_RESID || MODE == STEP_RHS) ? a.w[oi] : 0.f;
+  e.cur = MODE == STEP_RESID ? a.w[oi] : 0.f;
   return e;
 }
 
@@ -55,14 +55,12 @@ __device__ inline void adj_epi_finish(const AdjArgs& a, const AdjRow& ro, int j,
   const long long oi = ro.o + j;
   if (MODE == STEP_RELAX) {
     a.w[oi] = wn + e.gval;
-  } else if (MODE == STEP_RESID) {
+  } else {  // STEP_RESID
     const float res = e.cur - wn - e.gval;
     const long long ai = (ro.a & ~1LL) + j;
     a.gc[ai] = -res;
     a.wc[ai] = (ro.a & 1) ? -res : 0.f;                // zero guess; -r at the marked points
     nrm += (double)res * (double)res;
-  } else {  // STEP_RHS
-    a.g[oi] = (e.cur - wn) + e.gval;
   }
 }
 
@@ -96,7 +94,7 @@ __device__ inline void adj_tile_epilogue(const AdjArgs& a, Acc<C>& acc, const Ad
       in[it].kd = ldg4(a.kap + ro.k + 3 * H + jc);
       in[it].wv = ldg4(a.w_in + ro.in + jc);
       in[it].gval = a.g ? ldg4(a.g + ro.o + jc) : zero4();
-      in[it].cur = (MODE == STEP_RESID || MODE == STEP_RHS) ? ldg4(a.w + ro.o + jc) : zero4();
+      in[it].cur = MODE == STEP_RESID ? ldg4(a.w + ro.o + jc) : zero4();
     }
     __syncthreads();
 #pragma unroll
@@ -107,7 +105,7 @@ __device__ inline void adj_tile_epilogue(const AdjArgs& a, Acc<C>& acc, const Ad
       const long long oi = oo[it] + j;
       if (MODE == STEP_RELAX) {
         *reinterpret_cast<floatx4*>(a.w + oi) = wn + in[it].gval;
-      } else if (MODE == STEP_RESID) {
+      } else {  // STEP_RESID
         const floatx4 res = in[it].cur - wn - in[it].gval;
         const long long ai = (oa[it] & ~1LL) + j;
         *reinterpret_cast<floatx4*>(a.gc + ai) = -res;
@@ -115,8 +113,6 @@ __device__ inline void adj_tile_epilogue(const AdjArgs& a, Acc<C>& acc, const Ad
         *reinterpret_cast<floatx4*>(a.wc + ai) = (oa[it] & 1) ? -res : zero4();
 #pragma unroll
         for (int i = 0; i < 4; ++i) nrm += (double)res[i] * (double)res[i];
-      } else {  // STEP_RHS
-        *reinterpret_cast<floatx4*>(a.g + oi) = (in[it].cur - wn) + in[it].gval;
       }
     }
   }
@@ -552,24 +548,18 @@ static void launch_adj_cfg(const AdjArgs& a, hipStream_t s) {
                          s, a);
     else if (a.mode == STEP_RELAX)
       hipLaunchKernelGGL((adj_step_kernel_bf16<CS, STEP_RELAX>), grid, block, 0, s, a);
-    else if (a.mode == STEP_RESID)
-      hipLaunchKernelGGL((adj_step_kernel_bf16<CS, STEP_RESID>), grid, block, 0, s, a);
     else
-      hipLaunchKernelGGL((adj_step_kernel_bf16<CS, STEP_RHS>), grid, block, 0, s, a);
+      hipLaunchKernelGGL((adj_step_kernel_bf16<CS, STEP_RESID>), grid, block, 0, s, a);
   } else if (a.bf16) {
     if (a.mode == STEP_RELAX)
       hipLaunchKernelGGL((adj_step_kernel_bf16<CB, STEP_RELAX>), grid, block, 0, s, a);
-    else if (a.mode == STEP_RESID)
-      hipLaunchKernelGGL((adj_step_kernel_bf16<CB, STEP_RESID>), grid, block, 0, s, a);
     else
-      hipLaunchKernelGGL((adj_step_kernel_bf16<CB, STEP_RHS>), grid, block, 0, s, a);
+      hipLaunchKernelGGL((adj_step_kernel_bf16<CB, STEP_RESID>), grid, block, 0, s, a);
   } else {
     if (a.mode == STEP_RELAX)
       hipLaunchKernelGGL((adj_step_kernel<C, STEP_RELAX>), grid, block, 0, s, a);
-    else if (a.mode == STEP_RESID)
-      hipLaunchKernelGGL((adj_step_kernel<C, STEP_RESID>), grid, block, 0, s, a);
     else
-      hipLaunchKernelGGL((adj_step_kernel<C, STEP_RHS>), grid, block, 0, s, a);
+      hipLaunchKernelGGL((adj_step_kernel<C, STEP_RESID>), grid, block, 0, s, a);
   }
 }
 
@@ -594,14 +584,15 @@ template <int CT>
 static void launch_adj_skinny(const AdjArgs& a, dim3 grid, hipStream_t s) {
   if (a.mode == STEP_RELAX)
     launch_adj_skinny_mode<CT, STEP_RELAX>(a, grid, s);
-  else if (a.mode == STEP_RESID)
-    launch_adj_skinny_mode<CT, STEP_RESID>(a, grid, s);
   else
-    launch_adj_skinny_mode<CT, STEP_RHS>(a, grid, s);
+    launch_adj_skinny_mode<CT, STEP_RESID>(a, grid, s);
 }
 
+// modes STEP_RELAX and STEP_RESID (the adjoint cycle solves its coarse equations for the
+// error and needs no right-hand-side launch)
 hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s) {
   if (a.nk <= 0) return hipSuccess;
+  if (a.mode != STEP_RELAX && a.mode != STEP_RESID) return hipErrorInvalidValue;
   const long long R = (long long)a.nk * a.B;
   auto tiles = [&](int tm, int tn) { return ((R + tm - 1) / tm) * ((a.H + tn - 1) / tn); };
   const int kind = R <= 2 * SK_MAXROWS ? 5 : 1;

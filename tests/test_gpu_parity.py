@@ -420,6 +420,38 @@ def test_launch_counts_of_two_fcf_cycles(gh):
         mg.mgrit_gru_profile_read(kind)                                  # drain
 
 
+def test_launch_counts_of_two_adjoint_cycles(gh):
+    """The adjoint cycle solves its coarse equations for the error (the recurrence is linear):
+    per cycle level 0 takes its relaxation sub-steps and one residual launch, and nothing
+    applies the coarse operator to the restricted iterate.  With three levels the middle
+    level's opening F-sweep starts at its second sub-step: the first one, -R r from the zero
+    guess, is written by level 0's residual launch."""
+    import paper_2203_04738_amd as mg
+    T, B, D, H = 64, 70, 8, 16
+    d = random_small(3, T, B, D, H, scale=0.2)
+    h = orc.serial_scan(*_P(d), d["x"], d["h0"])
+    for levels, rows1_relax in ((2, None), (3, (2 + 1 + 3 + 3))):
+        run = gh.GpuRun(d, cf=4, levels=levels)
+        rows0, rows1 = (T // 4) * B, (T // 16) * B
+        mg.mgrit_gru_profile_enable(True)
+        try:
+            its, _, _ = run.backward_iterates(h, 2, per_call=2)
+        finally:
+            mg.mgrit_gru_profile_enable(False)
+        assert mg.mgrit_gru_profile_read_shape(1, rows0, 0)[0] == (3 + 1 + 3 + 3) + (1 + 3 + 3)
+        assert mg.mgrit_gru_profile_read_shape(1, rows0, 1)[0] == 2      # residual + restriction
+        assert mg.mgrit_gru_profile_read_shape(1, rows0, 2)[0] == 0      # no right-hand-side launch
+        if rows1_relax is not None:
+            # level 1, per cycle: (first sub-step given) 2 + 1 + 3, closing 3; one residual
+            assert mg.mgrit_gru_profile_read_shape(1, rows1, 0)[0] == 2 * rows1_relax
+            assert mg.mgrit_gru_profile_read_shape(1, rows1, 1)[0] == 2
+        for kind in (0, 1, 2, 3, 4, 5, 7):
+            mg.mgrit_gru_profile_read(kind)                              # drain
+        want = orc.mgrit_backward(*_P(d), d["x"], h, d["dL_dhT"], np.zeros((T + 1, B, H)), 4,
+                                  levels, 2)[0]
+        assert gh.rel_err(its[-1], want) <= 1e-5
+
+
 # ------------------------------------------------------------------ capture in a HIP graph
 
 def test_forward_and_backward_calls_replay_from_a_hip_graph(gh):

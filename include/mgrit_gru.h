@@ -86,7 +86,9 @@ enum {
    * (Appendix A.2), which the adjoint solve would otherwise recompute; with
    * more than one level its first sub-step, which starts from the coarse points,
    * leaves the vectors of every step of level 1 as well (same states, same
-   * recurrent contraction, the coarse step size and inputs).  (A
+   * recurrent contraction, the coarse step size and inputs), and so do the
+   * closing relaxations of the coarse levels for the level below them, except
+   * for the coarsest level.  (A
    * serial scan over 64 or fewer batch rows leaves none: there one pass over
    * all steps in the backward call is cheaper; the backward call knows.) */
   MGRIT_KEEP_COEFFS = 2,
@@ -94,7 +96,8 @@ enum {
    * MGRIT_KEEP_COEFFS left there, for the same sizes, hierarchy, dtype,
    * propagator and workspace pointer, and the states h passed in are the ones
    * that call returned: only the steps it did not cover (those of level 0
-   * into the coarse points, and levels 2 and up) are linearised again. */
+   * into the coarse points, and the coarsest level beyond level 1) are
+   * linearised again. */
   MGRIT_REUSE_COEFFS = 4,
   /* mgrit_gru_backward: rows 0..T-1 of w_inout are zero on entry (the initial
    * guess of Alg. 3).  The adjoint recurrence is linear and homogeneous, so in
@@ -266,7 +269,8 @@ MGRIT_API int mgrit_gru_profile_read(int kind, int64_t* launches, double* ms,
  * (0 = relaxation update, 1 = residual + restriction, 2 = coarse right-hand side,
  * 3 = coefficients, 4 = relaxation update that keeps the coefficients, 5 = relaxation
  * update from the coarse points that also evaluates the coarse level's step, 6 = mode 4
- * that also leaves the coefficients of level 1; + 16 for a
+ * that also leaves the coefficients of level 1, 7 = mode 0 that leaves the coefficients
+ * of the next level; + 16 for a
  * forward launch that skips the contraction of zero-input tiles, whose flops count
  * the rows it contracts only); a negative value matches any.  Records that do not
  * match stay for later reads. */

@@ -164,7 +164,8 @@ struct FwdCtx {
   float* tmp;
   double* norm;     // accumulator of the current cycle (may be null)
   float* emit_kap;  // level-0 coefficient array the closing relaxation also fills (or null)
-  float* emit_kap1; // level-1 coefficient array filled along with it (null with one level)
+  float* emit_kapl[MAX_LEVELS];  // [l]: coefficient array of level l >= 1 that the closing
+                                 // relaxation of level l - 1 fills along with it (or null)
   float dt;         // step size of level 0 (1 for the GRU propagators, Sec. 3.3)
   hipStream_t s;
 };
@@ -196,6 +197,12 @@ static PhiArgs phi_base(const FwdCtx& x, int l) {
 // kernels, where the five extra vectors per step cost more than one pass over all steps
 // in the tile kernel afterwards; forward and backward calls decide by the same rule.
 static bool serial_scan_keeps_coeffs(const mgrit_gru_cfg& c) { return c.B > 64; }
+
+// Levels >= 1 whose coefficient vectors the forward call leaves (with MGRIT_KEEP_COEFFS and
+// cf > 1) from the closing relaxation of the level above: level 1 always; deeper levels unless
+// they are the coarsest one, whose few-row adjoint steps run faster on coefficients that the
+// backward call has just written (0.4 us per step at 32 rows x 512) than the pass costs.
+static bool forward_leaves_coeffs(int l, int L) { return l >= 1 && l < L && (l == 1 || l < L - 1); }
 
 // zero_c: the coarse points 1.. of the level hold zero states (the caller's initial guess):
 // the first sub-step reads nothing else outside the first interval.
@@ -230,13 +237,13 @@ static int relax_fwd(const FwdCtx& x, int l, bool include_c, bool f_points_curre
     a.in = Idx{j - 1, cf};
     a.o = Idx{j, cf};
     a.p = Idx{j * S - 1, cf * S};
-    if (a.mode == STEP_RELAX_KAPPA && j == 1 && cf > 1 && x.emit_kap1) {
+    if (emit && j == 1 && cf > 1 && x.emit_kapl[l + 1]) {
       // the first sub-step starts from the coarse points, whose values are final: they are the
-      // states the steps of level 1 are linearised at, and the contraction U h is the same for
-      // both step sizes, so this launch also leaves the coefficient vectors of level 1
-      // (step from level-1 point i to i + 1, row i + 1)
-      a.mode = STEP_RELAX_KAPPA2;
-      a.gc = x.emit_kap1;
+      // states the steps of level l + 1 are linearised at, and the contraction U h is the same
+      // for both step sizes, so this launch also leaves the coefficient vectors of level l + 1
+      // (step from its point i to i + 1, row i + 1)
+      a.mode = l == 0 ? STEP_RELAX_KAPPA2 : STEP_RELAX_CK;
+      a.gc = x.emit_kapl[l + 1];
       a.a = Idx{1, 1};
       a.gamma2 = (float)x.lay->S[l + 1] * x.dt;
       a.dp2 = (cf * S - 1 - a.p.off) * x.c->B * 3LL * x.c->H;   // P row (i + 1) cf S - 1
@@ -332,13 +339,13 @@ static int vcycle_fwd(const FwdCtx& x, int l, bool f_points_current = false, boo
     a.p = Idx{Sc - 1, Sc};
     CHECK_HIP(launch_phi_step(a, x.s));
   }
-  if ((rc = vcycle_fwd(x, l + 1, false, false, false, child_first_done))) return rc;
+  if ((rc = vcycle_fwd(x, l + 1, false, last, false, child_first_done))) return rc;
   // line 5 at the coarse points: u'_{cf j} + (v_j - u'_{cf j}) = v_j.  F-points
   // would receive the same correction but are overwritten by line 6.
   CHECK_HIP(launch_copy_points(x.ul[l], x.ul[l + 1], Idx{cf, cf}, Idx{1, 1}, Nc,
                                (long long)x.c->B * x.c->H, x.s));
   // line 6
-  return relax_fwd(x, l, false, false, last && l == 0);
+  return relax_fwd(x, l, false, false, last);
 }
 
 static int run_projection(const mgrit_gru_cfg* c, const Layout& lay, char* base, const void* W,
@@ -413,7 +420,9 @@ static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, co
   ctx.emit_kap = (c.flags & MGRIT_KEEP_COEFFS) ? (float*)(base + lay.kap[0]) : nullptr;
   if (ctx.emit_kap && c.iters < 1) return MGRIT_E_SIZE;
   if (lay.L == 1 && !serial_scan_keeps_coeffs(c)) ctx.emit_kap = nullptr;
-  ctx.emit_kap1 = (ctx.emit_kap && lay.L > 1) ? (float*)(base + lay.kap[1]) : nullptr;
+  for (int l = 0; l < MAX_LEVELS; ++l)
+    ctx.emit_kapl[l] = (ctx.emit_kap && forward_leaves_coeffs(l, lay.L))
+                           ? (float*)(base + lay.kap[l]) : nullptr;
 
   if ((rc = run_projection(&c, lay, base, W, b_i, x, s))) return rc;
   const long long BH = (long long)c.B * c.H;
@@ -661,9 +670,9 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
         a.o = Idx{c.cf, c.cf};
       }
     }
-    // ... and, from the coarse points its first sub-step starts at, the coefficients of every
-    // step of level 1
-    if (l == 1 && (c.flags & MGRIT_REUSE_COEFFS) && c.cf > 1) a.nk = 0;
+    // ... and, from the coarse points the first sub-step of every level's closing relaxation
+    // starts at, the coefficients of every step of the next level
+    if ((c.flags & MGRIT_REUSE_COEFFS) && c.cf > 1 && forward_leaves_coeffs(l, lay.L)) a.nk = 0;
     CHECK_HIP(launch_phi_step(a, s));
     // the terminal condition w_T = dL/dh_T is the fixed end point of level 0; the coarse levels
     // solve for errors, whose end point is zero

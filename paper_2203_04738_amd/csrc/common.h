@@ -32,6 +32,9 @@ enum StepMode {
   STEP_RELAX_KAPPA2 = 6 // forward only: STEP_RELAX_KAPPA from the coarse points of level 0 that
                         // also leaves the coefficient vectors of the coarse level's step from
                         // the same states (k_r, k_z, k_q, k_d; row = coarse output point) in gc
+  ,
+  STEP_RELAX_CK = 7     // forward only: STEP_RELAX from the coarse points of a level >= 1 that
+                        // leaves the coarser level's coefficient vectors like STEP_RELAX_KAPPA2
 };
 
 // One launch of the fused forward step  Phi_gamma(x, h) over nk level points.

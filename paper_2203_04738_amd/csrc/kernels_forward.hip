@@ -223,7 +223,7 @@ __device__ inline PhiEpiIn phi_epi_load(const PhiArgs& a, const PhiRow& ro, int 
   e.gval = (MODE != STEP_KAPPA && a.g) ? a.g[oi] : 0.f;
   e.cur = (MODE == STEP_RESID || MODE == STEP_RHS) ? a.u[oi] : 0.f;
   e.pr2 = e.pz2 = e.pn2 = e.cur2 = e.prep = 0.f;
-  if (MODE == STEP_RELAX_RHS || MODE == STEP_RELAX_KAPPA2) {
+  if (MODE == STEP_RELAX_RHS || MODE == STEP_RELAX_KAPPA2 || MODE == STEP_RELAX_CK) {
     const float* p2 = pp + a.dp2;
     e.pr2 = p2[j];
     e.pz2 = p2[H + j];
@@ -287,6 +287,20 @@ __device__ inline PhiOut phi_elem(float gamma, bool implicit, float sr, float sz
     const float hn2 = implicit ? (h + gamma2 * c2 * n2) * fast_rcp(1.0f + gamma2 * c2)
                                : h + gamma2 * c2 * (n2 - h);
     o.v1 = e.cur2 - hn2;
+  } else if (MODE == STEP_RELAX_CK) {
+    o.v0 = hn + e.gval;
+    // coefficient vectors of the coarser level's step from the same state
+    const float rg2 = sigmoidf_(e.pr2 + sr + bh.r);
+    const float zg2 = sigmoidf_(e.pz2 + sz + bh.z);
+    const float n2 = tanhf_(e.pn2 + rg2 * q);
+    const float c2 = 1.0f - zg2;
+    const float rd2 = fast_rcp(1.0f + gamma2 * c2);
+    const float hn2 = implicit ? (h + gamma2 * c2 * n2) * rd2 : h + gamma2 * c2 * (n2 - h);
+    const PhiKappa k2 = phi_kappa(gamma2, implicit, h, rg2, zg2, q, n2, c2, rd2, hn2);
+    o.c0 = k2.kr;
+    o.c1 = k2.kz;
+    o.c2 = k2.kq;
+    o.c3 = k2.kd;
   } else if (MODE == STEP_RESID) {
     o.v0 = -(e.cur - hn - e.gval);
     o.v1 = e.cur;
@@ -331,6 +345,13 @@ __device__ inline void phi_epi_finish(const PhiArgs& a, const PhiRow& ro, int j,
   } else if (MODE == STEP_RELAX_RHS) {
     a.u[oi] = o.v0;
     a.gc[ro.a + j] = o.v1;
+  } else if (MODE == STEP_RELAX_CK) {
+    a.u[oi] = o.v0;
+    float* kc = a.gc + coarse_kappa_row;
+    kc[j] = o.c0;
+    kc[H + j] = o.c1;
+    kc[2 * H + j] = o.c2;
+    kc[3 * H + j] = o.c3;
   } else if (MODE == STEP_RESID) {
     const long long ai = (ro.a & ~1LL) + j;
     a.gc[ai] = a.resid_adds ? e.prep + o.v0 : o.v0;
@@ -388,11 +409,11 @@ __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Ph
     E::write(acc, ba, stage);
     // operands that do not depend on the sums: requested before the barrier
     PhiEpiIn4 in[E::ITEMS];
-    constexpr bool EXTRA =
-        MODE == STEP_RELAX_RHS || MODE == STEP_RESID || MODE == STEP_RELAX_KAPPA2;
+    constexpr bool CK = MODE == STEP_RELAX_KAPPA2 || MODE == STEP_RELAX_CK;
+    constexpr bool EXTRA = MODE == STEP_RELAX_RHS || MODE == STEP_RESID || CK;
     PhiEpiExtra4 ex[EXTRA ? E::ITEMS : 1];
     long long oo[E::ITEMS], oa[E::ITEMS];
-    long long oa2[MODE == STEP_RELAX_KAPPA2 ? E::ITEMS : 1];
+    long long oa2[CK ? E::ITEMS : 1];
     int trow[E::ITEMS];
 #pragma unroll
     for (int it = 0; it < E::ITEMS; ++it) {
@@ -409,12 +430,12 @@ __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Ph
       else in[it].gval = zero4();
       if (MODE == STEP_RESID || MODE == STEP_RHS) in[it].cur = ldg4(a.u + ro.o + jc);
       else in[it].cur = zero4();
-      if (MODE == STEP_RELAX_RHS || MODE == STEP_RELAX_KAPPA2) {
+      if (MODE == STEP_RELAX_RHS || CK) {
         ex[it].pr2 = ldg4_stream(pp + a.dp2);
         ex[it].pz2 = ldg4_stream(pp + a.dp2 + H);
         ex[it].pn2 = ldg4_stream(pp + a.dp2 + 2 * H);
         if (MODE == STEP_RELAX_RHS) ex[it].cur2 = ldg4(a.u + ro.o + a.do2 + jc);
-        if (MODE == STEP_RELAX_KAPPA2) oa2[it] = rowtab2[trow[it]];
+        if (CK) oa2[it] = rowtab2[trow[it]];
       }
       if (MODE == STEP_RESID)
         ex[it].prep = a.resid_adds ? ldg4(a.gc + (ro.a & ~1LL) + jc) : zero4();
@@ -432,7 +453,7 @@ __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Ph
       for (int i = 0; i < 4; ++i) {
         PhiEpiIn e1{in[it].pr[i], in[it].pz[i], in[it].pn[i], in[it].h[i], in[it].gval[i],
                     in[it].cur[i], 0.f, 0.f, 0.f, 0.f, 0.f};
-        if (MODE == STEP_RELAX_RHS || MODE == STEP_RELAX_KAPPA2) {
+        if (MODE == STEP_RELAX_RHS || CK) {
           e1.pr2 = ex[it].pr2[i];
           e1.pz2 = ex[it].pz2[i];
           e1.pn2 = ex[it].pn2[i];
@@ -449,6 +470,13 @@ __device__ inline void phi_tile_epilogue(const PhiArgs& a, Acc<C>& acc, const Ph
       } else if (MODE == STEP_RELAX_RHS) {
         *reinterpret_cast<floatx4*>(a.u + oi) = o0;
         *reinterpret_cast<floatx4*>(a.gc + oa[it] + j) = o1;
+      } else if (MODE == STEP_RELAX_CK) {
+        *reinterpret_cast<floatx4*>(a.u + oi) = o0;
+        float* kc = a.gc + oa2[it] + j;
+        *reinterpret_cast<floatx4*>(kc) = q0;
+        *reinterpret_cast<floatx4*>(kc + H) = q1;
+        *reinterpret_cast<floatx4*>(kc + 2 * H) = q2;
+        *reinterpret_cast<floatx4*>(kc + 3 * H) = q3;
       } else if (MODE == STEP_RESID) {
         const long long ai = (oa[it] & ~1LL) + j;
         // (adding the zero of a launch without a prepared half changes no value)
@@ -494,14 +522,15 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel(PhiArgs a) {
   const int n0 = ct * C::TN;
   const int tid = threadIdx.x;
   __shared__ PhiRow rowtab[C::TM];
-  __shared__ long long rowtab2[MODE == STEP_RELAX_KAPPA2 ? C::TM : 1];
+  __shared__ long long rowtab2[(MODE == STEP_RELAX_KAPPA2 || MODE == STEP_RELAX_CK) ? C::TM : 1];
   if (tid < C::TM) {
     long long r = m0 + tid;
     if (r >= R) r = R - 1;
     rowtab[tid] = phi_row(a, r,
                           (MODE == STEP_KAPPA || MODE == STEP_RELAX_KAPPA ||
                            MODE == STEP_RELAX_KAPPA2) ? a.kappa_width : H);
-    if (MODE == STEP_RELAX_KAPPA2) rowtab2[tid] = phi_row_coarse_kappa(a, r);
+    if (MODE == STEP_RELAX_KAPPA2 || MODE == STEP_RELAX_CK)
+      rowtab2[tid] = phi_row_coarse_kappa(a, r);
   }
   // (visible to all waves after the barriers inside the contraction)
 
@@ -566,14 +595,15 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel_bf16(PhiArgs 
   const int tid = threadIdx.x;
   const bf16_t* U = (const bf16_t*)(C::NP == 3 ? a.U3 : a.U);
   __shared__ PhiRow rowtab[C::TM];
-  __shared__ long long rowtab2[MODE == STEP_RELAX_KAPPA2 ? C::TM : 1];
+  __shared__ long long rowtab2[(MODE == STEP_RELAX_KAPPA2 || MODE == STEP_RELAX_CK) ? C::TM : 1];
   if (tid < C::TM) {
     long long r = m0 + tid;
     if (r >= R) r = R - 1;
     rowtab[tid] = phi_row(a, r,
                           (MODE == STEP_KAPPA || MODE == STEP_RELAX_KAPPA ||
                            MODE == STEP_RELAX_KAPPA2) ? a.kappa_width : H);
-    if (MODE == STEP_RELAX_KAPPA2) rowtab2[tid] = phi_row_coarse_kappa(a, r);
+    if (MODE == STEP_RELAX_KAPPA2 || MODE == STEP_RELAX_CK)
+      rowtab2[tid] = phi_row_coarse_kappa(a, r);
   }
   // (visible to all waves after the barriers inside the contraction)
 
@@ -706,12 +736,14 @@ __global__ __launch_bounds__(PhiSkMaxNT<CT>::value) void phi_skinny_kernel(PhiAr
     const float sn = skinny_sum<VP>(red, grp, base + 2 * CT + c, ksl);
     if (e == tid && epi) {
       phi_epi_finish<MODE>(a, ero, e_j, sr, sz, sn, ein, ebh, nrm,
-                           MODE == STEP_RELAX_KAPPA2 ? phi_row_coarse_kappa(a, r0 + row) : 0);
+                           (MODE == STEP_RELAX_KAPPA2 || MODE == STEP_RELAX_CK)
+                               ? phi_row_coarse_kappa(a, r0 + row) : 0);
     } else {   // more outputs than threads (tiny K only)
       const PhiRow ro = phi_row(a, r0 + row, aux_w);
       phi_epi_finish<MODE>(a, ro, j, sr, sz, sn, phi_epi_load<MODE>(a, ro, j), phi_bias_load(a, j),
                            nrm,
-                           MODE == STEP_RELAX_KAPPA2 ? phi_row_coarse_kappa(a, r0 + row) : 0);
+                           (MODE == STEP_RELAX_KAPPA2 || MODE == STEP_RELAX_CK)
+                               ? phi_row_coarse_kappa(a, r0 + row) : 0);
     }
   }
   if (MODE == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
@@ -745,6 +777,9 @@ typedef TileCfgB<1, 1, 1, 1, 3, true, 4, 1, 2, 3, 32> PhiSmallS;
       break;                                                                             \
     case STEP_RELAX_KAPPA:                                                               \
       hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_RELAX_KAPPA>), grid, block, 0, s, a); \
+      break;                                                                             \
+    case STEP_RELAX_CK:                                                                  \
+      hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_RELAX_CK>), grid, block, 0, s, a);    \
       break;                                                                             \
     case STEP_RELAX_KAPPA2:                                                              \
       hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_RELAX_KAPPA2>), grid, block, 0, s, a); \
@@ -800,6 +835,7 @@ static void launch_phi_skinny(const PhiArgs& a, dim3 grid, hipStream_t s) {
     case STEP_RELAX_KAPPA: launch_phi_skinny_mode<CT, STEP_RELAX_KAPPA>(a, grid, s); break;
     case STEP_RELAX_RHS: launch_phi_skinny_mode<CT, STEP_RELAX_RHS>(a, grid, s); break;
     case STEP_RELAX_KAPPA2: launch_phi_skinny_mode<CT, STEP_RELAX_KAPPA2>(a, grid, s); break;
+    case STEP_RELAX_CK: launch_phi_skinny_mode<CT, STEP_RELAX_CK>(a, grid, s); break;
     default: launch_phi_skinny_mode<CT, STEP_KAPPA>(a, grid, s);
   }
 }

@@ -180,7 +180,12 @@ def test_the_papers_hierarchies_at_128_steps(gh, cf, levels):
 
 
 @pytest.mark.parametrize("cf,levels,fcf,shape", [(4, 2, True, (48, 3, 20, 36)), (4, 3, False, (64, 3, 20, 36)),
-                                                 (1, 2, True, (12, 2, 8, 8)), (2, 3, True, (384, 40, 72, 100))])
+                                                 (1, 2, True, (12, 2, 8, 8)), (2, 3, True, (384, 40, 72, 100)),
+                                                 # four and five levels: the closing relaxations of
+                                                 # levels 1.. leave the next level's vectors too
+                                                 (2, 4, True, (64, 3, 12, 20)),
+                                                 (2, 5, True, (128, 40, 16, 72)),
+                                                 (4, 4, False, (256, 20, 8, 40))])
 def test_coefficients_kept_by_the_forward_call_and_reused_by_the_backward_call(gh, cf, levels, fcf, shape):
     """MGRIT_KEEP_COEFFS / MGRIT_REUSE_COEFFS: same results as the oracle, which linearises
     every step at the states the forward solve returned."""

@@ -303,6 +303,25 @@ def test_bf16_rejects_widths_not_multiple_of_8(gh):
     assert e.value.code == -6
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "fp32x3"])
+def test_kept_coefficients_on_four_levels_in_the_other_operand_forms(gh, dtype):
+    """The forward call's closing relaxations leave the coefficient vectors of levels 1 and 2
+    (four levels: the second through the mode that levels >= 1 use); same bar as the plain
+    calls of the operand form."""
+    T, B, D, H, cf, levels = 128, 40, 16, 72, 2, 4
+    d = dict(random_small(91, T, B, D, H, scale=0.3))
+    tol = TOL_BF16 if dtype == "bf16" else TOL
+    if dtype == "bf16":
+        d = _bf16_inputs(d)
+    run = gh.GpuRun(d, cf=cf, levels=levels, dtype=dtype)
+    got = run.forward_then_backward_reusing_coeffs(2, 2)
+    rh, _ = orc.mgrit_forward(*_P(d), d["x"], d["h0"], _zeros(d), cf, levels, 2)
+    assert gh.rel_err(got[0], rh) <= tol
+    ref = orc.mgrit_backward(*_P(d), d["x"], got[0], d["dL_dhT"], _zeros(d), cf, levels, 2)
+    for name, g, r in zip(("w", "dW", "dU", "db_i", "db_h"), got[1:], (ref[0],) + ref[2:6]):
+        assert gh.rel_err(g, r) <= tol, name
+
+
 # ------------------------------------------------------------------ the big tile configuration, ragged
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16", "fp32x3"])

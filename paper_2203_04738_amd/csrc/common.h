@@ -15,26 +15,31 @@ struct Idx {
 };
 
 enum StepMode {
-  STEP_RELAX = 0,   // out[o] = step(in) + g[o]                       (Alg. 1 update; coarsest solve)
-  STEP_RESID = 1,   // r = cur[o] - step(in) - g[o];  gc[a] = -r; uc[a] = cur[o]; norm += r^2
-                    //                                                 (Alg. 2 lines 2-3)
-                    // adjoint: wc[a] = 0 instead (error equation of a linear problem)
-  STEP_RHS = 2,     // forward only: g[o] = cur[o] - step(in) + g[o]   (Eq. 11 right-hand side)
-  STEP_KAPPA = 3,   // forward only: adjoint coefficient vectors of the step
-  STEP_RELAX_KAPPA = 4, // forward only: STEP_RELAX that also leaves the coefficient vectors of
-                        // the step it takes (row = output point) in uc
-  STEP_RELAX_RHS = 5    // forward only: STEP_RELAX from the coarse points of a level (first
-                        // sub-step of an F-sweep) that also evaluates the coarse level's step
-                        // from the same inputs -- the contraction U h does not depend on the
-                        // step size -- and leaves  gc[a] = cur2 - step2(in)  (the first half
-                        // of the Eq. 11 right-hand side; STEP_RESID with resid_adds adds -r)
-  ,
-  STEP_RELAX_KAPPA2 = 6 // forward only: STEP_RELAX_KAPPA from the coarse points of level 0 that
-                        // also leaves the coefficient vectors of the coarse level's step from
-                        // the same states (k_r, k_z, k_q, k_d; row = coarse output point) in gc
-  ,
-  STEP_RELAX_CK = 7     // forward only: STEP_RELAX from the coarse points of a level >= 1 that
-                        // leaves the coarser level's coefficient vectors like STEP_RELAX_KAPPA2
+  // out[o] = step(in) + g[o]   (Alg. 1 update; coarsest solve)
+  STEP_RELAX = 0,
+  // r = cur[o] - step(in) - g[o];  gc[a] = -r;  norm += r^2   (Alg. 2 lines 2-3)
+  // forward: uc[a] = cur[o], the restricted iterate; adjoint: wc[a] = 0, the zero guess of the
+  // error equation of a linear problem (see ff_cf for the exception in both)
+  STEP_RESID = 1,
+  // forward only: g[o] = cur[o] - step(in) + g[o]   (Eq. 11 right-hand side)
+  STEP_RHS = 2,
+  // forward only: adjoint coefficient vectors of the step
+  STEP_KAPPA = 3,
+  // forward only: STEP_RELAX that also leaves the coefficient vectors of the step it takes
+  // (row = output point) in uc
+  STEP_RELAX_KAPPA = 4,
+  // forward only: STEP_RELAX from the coarse points of a level (first sub-step of an F-sweep)
+  // that also evaluates the coarse level's step from the same inputs -- the contraction U h
+  // does not depend on the step size -- and leaves  gc[a] = cur2 - step2(in), the first half
+  // of the Eq. 11 right-hand side (STEP_RESID with resid_adds adds -r)
+  STEP_RELAX_RHS = 5,
+  // forward only: STEP_RELAX_KAPPA from the coarse points of level 0 that also leaves the
+  // coefficient vectors of the coarse level's step from the same states (k_r, k_z, k_q, k_d;
+  // row = coarse output point) in gc
+  STEP_RELAX_KAPPA2 = 6,
+  // forward only: STEP_RELAX from the coarse points of a level >= 1 that leaves the coarser
+  // level's coefficient vectors like STEP_RELAX_KAPPA2
+  STEP_RELAX_CK = 7
 };
 
 // One launch of the fused forward step  Phi_gamma(x, h) over nk level points.

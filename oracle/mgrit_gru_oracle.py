@@ -22,9 +22,13 @@ Conventions
 
 Every function cites the passage it follows.  Pins that tie this file to the
 paper and to mathematics (closed forms, a library GRU, finite differences,
-exactness fronts) are in tests/test_oracle_pins.py.  Per-iterate values of
-MGRIT at 2-3 iterations have no published reference: "parity unpinned" beyond
-those structural pins.
+exactness fronts, the per-level decay factors of a zero-weight problem, and the
+cycle of Alg. 2 carried out by dense linear algebra on affine forward problems
+and on the linear adjoint problem with autograd Jacobians) are in
+tests/test_oracle_pins.py.  Per-iterate values of the NONLINEAR forward cycle
+(U != 0) at 2-3 iterations have no published reference: they are pinned through
+the same cycle code on the affine and adjoint problems and by the structural
+pins, not value by value.
 """
 from __future__ import annotations
 

@@ -630,3 +630,242 @@ def test_adjoint_cycle_in_error_form_gives_the_iterates_of_eq_11(T, cf, levels, 
         wr = _error_form_cycle(step, cf, levels, 0, wr, g0, fcf, res)
         assert _rel(wr[::-1], want[it]) < 1e-13
         assert abs(res[it] - want_res[it]) <= 1e-12 * want_res[it]
+
+
+# ---------------------------------------------------------------- level step size, coarse inputs, coarse relaxation
+# The exactness fronts, the fixed point and finite termination above hold for ANY coarse
+# propagator, so they cannot see the step size of a coarse level (Sec. 3.3: cf^l), which inputs
+# a coarse level reads (Sec. 3.1: the restriction of x is injection) or how a coarse level
+# relaxes (Alg. 2 line 1 applied recursively, Remark 2).  The pins below do, without using the
+# oracle's step or relaxation code: a closed form for a problem whose steps are scalings, and the
+# cycle of Alg. 2 carried out by dense linear algebra on problems whose level operators are
+# explicit matrices.
+
+def _decay_ratio_check(v, cf, levels, factor):
+    """v[(T+1),...]: iterate after ONE cycle from a zero guess on a problem whose level-l step is
+    the scaling u_k = factor(l) * u_{k-1}.  The right-hand side of every coarse equation (Eq. 11)
+    is non-zero at its first two points only (the relaxation of Alg. 2 line 1 moves the zero
+    guess's non-zero region by at most two intervals), so from point 3 of every level on the
+    coarsest solve and the closing F-relaxations (Alg. 2 line 6) are pure scalings by that
+    level's factor, and their values reach the fine iterate by injection."""
+    T = v.shape[0] - 1
+    checked = 0
+    for l in range(levels):
+        s = cf ** l
+        for k in range(3, T // s + 1):
+            if l < levels - 1 and k % cf == 0:
+                continue                 # a coarse point of level l: written by a coarser level
+            num, den = v[k * s], v[(k - 1) * s]
+            assert np.all(np.abs(den) > 0)
+            assert np.allclose(num / den, factor(l), rtol=1e-12, atol=0), (l, k)
+            checked += 1
+    assert checked > levels
+
+
+@pytest.mark.parametrize("cf,levels", [(3, 2), (3, 3), (4, 3), (3, 4)])
+@pytest.mark.parametrize("prop", [orc.IMPLICIT, orc.CLASSIC])
+def test_level_step_size_is_cf_to_the_level_forward_and_adjoint(cf, levels, prop):
+    """Sec. 3.3: the step size of level l is cf^l.  With all weights and biases zero the gates
+    are r = z = 1/2, n = 0 whatever the input and the state, so the step with size gamma is the
+    scaling by 1/(1 + gamma/2) (Eq. 16) or by 1 - gamma/2 (Eq. 3), and so is its transposed
+    Jacobian.  One cycle from the zero guess of Alg. 3 then shows, level by level, which gamma
+    each level used: forward, and for the adjoint in reversed time."""
+    T, B, D, H = 6 * cf ** (levels - 1), 2, 3, 4
+    rng = np.random.default_rng(7)
+    W, U = np.zeros((3 * H, D)), np.zeros((3 * H, H))
+    z3 = np.zeros(3 * H)
+    x = rng.standard_normal((T, B, D))
+    h0 = 1.0 + rng.random((B, H))
+
+    def factor(l):
+        g = float(cf) ** l
+        return 1.0 / (1.0 + g / 2.0) if prop == orc.IMPLICIT else 1.0 - g / 2.0
+
+    h, _ = orc.mgrit_forward(W, U, z3, z3, x, h0, np.zeros((T + 1, B, H)), cf, levels, 1,
+                             propagator=prop)
+    _decay_ratio_check(h, cf, levels, factor)
+    wT = 1.0 + rng.random((B, H))
+    out = orc.mgrit_backward(W, U, z3, z3, x, h, wT, np.zeros((T + 1, B, H)), cf, levels, 1,
+                             propagator=prop)
+    _decay_ratio_check(out[0][::-1], cf, levels, factor)
+
+
+def _level_matrix(M):
+    """Dense matrix of a level operator  (A u)_k = u_k - M_k u_{k-1}, k = 1..N, (A u)_0 = u_0
+    (Eq. 4 / Eq. 7 for a linear step), from the step matrices M[k-1] (each m x m)."""
+    N, m = len(M), M[0].shape[0]
+    A = np.eye((N + 1) * m)
+    for k in range(1, N + 1):
+        A[k * m:(k + 1) * m, (k - 1) * m:k * m] = -M[k - 1]
+    return A
+
+
+def _dense_cycle(As, l, u, b, cf, fcf_fine, m, resnorms=None):
+    """Alg. 2 (recursive, Remark 2) on the linear level equations A_l u = b by dense solves.
+    F-relaxation solves the F-point rows exactly for the F-point unknowns, C-relaxation the
+    C-point rows for the C-point unknowns; the coarse equation is Eq. 11 as written,
+    A_c v = A_c (R u') - R r  with  r = A u' - b; the coarsest level is solved directly."""
+    A = As[l]
+    N = u.shape[0] // m - 1
+    if l == len(As) - 1:
+        return np.linalg.solve(A, b)
+
+    def rows(points):
+        return (np.asarray(points)[:, None] * m + np.arange(m)[None, :]).ravel()
+
+    C = rows(range(0, N + 1, cf))
+    F = rows([k for k in range(N + 1) if k % cf])
+
+    def f_relax(v):
+        v = v.copy()
+        v[F] = np.linalg.solve(A[np.ix_(F, F)], b[F] - A[np.ix_(F, C)] @ v[C])
+        return v
+
+    def c_relax(v):
+        v = v.copy()
+        v[C] = np.linalg.solve(A[np.ix_(C, C)], b[C] - A[np.ix_(C, F)] @ v[F])
+        return v
+
+    up = f_relax(u)                                    # line 1 (Eq. 8: F, then C, then F)
+    if l > 0 or fcf_fine:
+        up = f_relax(c_relax(up))
+    r = (A @ up - b)[C]                                # line 2
+    if l == 0 and resnorms is not None:
+        resnorms.append(float(np.linalg.norm(r)))
+    Ru = up[C]                                         # line 3
+    bc = As[l + 1] @ Ru - r                            # line 4 (Eq. 11)
+    v = _dense_cycle(As, l + 1, Ru.copy(), bc, cf, fcf_fine, m)
+    upp = up.copy()
+    upp[C] = up[C] + (v - Ru)                          # line 5 at the coarse points
+    return f_relax(upp)                                # line 6 (overwrites every F-point)
+
+
+def _library_affine_coefficients(d, H):
+    """U = 0: the Classic GRU step (Eq. 1) is affine in the state, h' = z h + (1-z) n with z, n
+    functions of x alone.  Read both off a library GRU cell: slope z = cell(x,1) - cell(x,0),
+    intercept (1-z) n = cell(x,0).  Returns (c, cn) = (1-z, (1-z) n), each [T,B,H]."""
+    D = d["W"].shape[1]
+    cell = torch.nn.GRUCell(D, H).double()
+    with torch.no_grad():
+        cell.weight_ih.copy_(torch.from_numpy(d["W"]).double())
+        cell.weight_hh.zero_()
+        cell.bias_ih.copy_(torch.from_numpy(d["b_i"]).double())
+        cell.bias_hh.copy_(torch.from_numpy(d["b_h"]).double())
+        x = torch.from_numpy(d["x"]).double()
+        T, B = x.shape[:2]
+        at0 = cell(x.reshape(T * B, D), torch.zeros(T * B, H, dtype=torch.float64))
+        at1 = cell(x.reshape(T * B, D), torch.ones(T * B, H, dtype=torch.float64))
+    z = (at1 - at0).reshape(T, B, H).numpy()
+    return 1.0 - z, at0.reshape(T, B, H).numpy()
+
+
+@pytest.mark.parametrize("T,cf,levels,fcf", [(36, 3, 3, True), (32, 2, 4, True), (48, 4, 3, False),
+                                              (54, 3, 4, True)])
+@pytest.mark.parametrize("prop", [orc.IMPLICIT, orc.CLASSIC])
+def test_forward_cycle_on_an_affine_problem_equals_dense_linear_algebra(T, cf, levels, fcf, prop):
+    """With U = 0 every level step is affine in the state with coefficients from x alone:
+    Phi_gamma(x_t, h) = a h + beta with a = 1/(1 + gamma c), beta = gamma c n / (1 + gamma c)
+    (Eq. 16) or a = 1 - gamma c, beta = gamma c n (Eq. 3), c and c n taken from a library GRU
+    cell.  Level l uses gamma = cf^l (Sec. 3.3) and the inputs of its own points, x_{k cf^l}
+    (Sec. 3.1), and every coarse level relaxes with FCF (Alg. 2 line 1, applied recursively).
+    The cycle by dense solves must give the oracle's iterates and residual norms."""
+    B, D, H = 2, 3, 3
+    d = random_small(51, T, B, D, H, scale=0.7)
+    d["U"][:] = 0.0
+    c, cn = _library_affine_coefficients(d, H)
+    m = B * H
+    As, betas = [], []
+    for l in range(levels):
+        g = float(cf ** l)
+        idx = np.arange(1, T // cf ** l + 1) * cf ** l - 1          # x_{k cf^l} is row k cf^l - 1
+        cl, cnl = c[idx].reshape(-1, m), cn[idx].reshape(-1, m)
+        if prop == orc.IMPLICIT:
+            a, beta = 1.0 / (1.0 + g * cl), g * cnl / (1.0 + g * cl)
+        else:
+            a, beta = 1.0 - g * cl, g * cnl
+        As.append(_level_matrix([np.diag(ak) for ak in a]))
+        betas.append(beta)
+    h0 = d["h0"].astype(np.float64)
+    b0 = np.concatenate([h0.ravel(), betas[0].ravel()])
+    u = np.zeros((T + 1) * m)
+    u[:m] = h0.ravel()
+    _, res, its = orc.mgrit_forward(*_params(d), d["x"], d["h0"], np.zeros((T + 1, B, H)), cf,
+                                    levels, 3, fine_relax_fcf=fcf, propagator=prop,
+                                    keep_iterates=True)
+    norms = []
+    for it in range(3):
+        u = _dense_cycle(As, 0, u, b0, cf, fcf, m, norms)
+        want = its[it].reshape(-1)
+        assert np.max(np.abs(u - want)) <= 1e-12 * max(1.0, np.max(np.abs(want))), it
+        assert abs(norms[it] - res[it]) <= 1e-11 * max(res), it
+    # the serial scan is the solution of the level-0 system
+    hs = orc.serial_scan(*_params(d), d["x"], d["h0"], prop)
+    assert np.allclose(np.linalg.solve(As[0], b0), hs.reshape(-1), rtol=1e-10, atol=1e-12)
+
+
+@pytest.mark.parametrize("T,cf,levels,fcf,every_state", [(36, 3, 3, True, False),
+                                                         (32, 2, 4, True, True),
+                                                         (32, 4, 3, False, False)])
+@pytest.mark.parametrize("prop", [orc.IMPLICIT, orc.CLASSIC])
+def test_adjoint_cycle_equals_dense_linear_algebra_on_autograd_jacobians(T, cf, levels, fcf,
+                                                                         every_state, prop):
+    """The adjoint recurrence is linear: level step k -> k-1 is the transposed Jacobian of
+    Phi_{cf^l}(x_{k cf^l}, .) at the given forward iterate's state h_{(k-1) cf^l} (Appendix A.2;
+    Alg. 3 hands h to MGBackProp).  The Jacobians come from autograd -- of a library GRU cell for
+    the explicit step (Eq. 3 is h + gamma (cell(x, h) - h)), of Eq. 16 written as tensor
+    operations for the implicit one -- the level operators are assembled as dense matrices in
+    reversed time and the cycle of Alg. 2 is carried out by dense solves.  Sees the adjoint's
+    step size per level, its linearisation points, its inputs and its coarse relaxation."""
+    B, D, H = 1, 3, 4
+    d = random_small(61, T, B, D, H, scale=0.4)
+    W, U, b_i, b_h = (torch.from_numpy(a).double() for a in _params(d))
+    cell = torch.nn.GRUCell(D, H).double()
+    with torch.no_grad():
+        cell.weight_ih.copy_(W)
+        cell.weight_hh.copy_(U)
+        cell.bias_ih.copy_(b_i)
+        cell.bias_hh.copy_(b_h)
+    # linearisation states: any given iterate; take a partly converged one
+    h, _ = orc.mgrit_forward(*_params(d), d["x"], d["h0"], np.zeros((T + 1, B, H)), cf, levels, 1,
+                             propagator=prop)
+
+    def phi_t(gamma, xt, hv):
+        if prop == orc.CLASSIC:
+            return hv + gamma * (cell(xt[None], hv[None])[0] - hv)
+        gi, gh = W @ xt + b_i, U @ hv + b_h
+        r = torch.sigmoid(gi[:H] + gh[:H])
+        z = torch.sigmoid(gi[H:2 * H] + gh[H:2 * H])
+        n = torch.tanh(gi[2 * H:] + r * gh[2 * H:])
+        return (hv + gamma * (1 - z) * n) / (1 + gamma * (1 - z))
+
+    xs = torch.from_numpy(d["x"]).double()
+    As = []
+    for l in range(levels):
+        s = cf ** l
+        N = T // s
+        M = []
+        for mrev in range(1, N + 1):            # reversed point mrev is forward level point N - mrev
+            k = N - mrev + 1                    # forward level step k: from point k-1 to k
+            J = torch.autograd.functional.jacobian(
+                lambda hv: phi_t(float(s), xs[k * s - 1, 0], hv), torch.from_numpy(h[(k - 1) * s, 0]))
+            M.append(J.numpy().T)
+        As.append(_level_matrix(M))
+    rng = np.random.default_rng(3)
+    src = 0.5 * rng.standard_normal((T + 1, B, H)) if every_state else None
+    wT = src[T] if every_state else d["dL_dhT"].astype(np.float64)
+    out = orc.mgrit_backward(*_params(d), d["x"], h, wT, np.zeros((T + 1, B, H)), cf, levels, 3,
+                             fine_relax_fcf=fcf, propagator=prop, keep_iterates=True, dL_dh=src)
+    its = out[-1]
+    m = H
+    b0 = np.zeros((T + 1) * m)
+    b0[:m] = wT.ravel()
+    if every_state:
+        b0[m:] = src[::-1][1:].ravel()          # source at reversed point mrev is dL_dh[T - mrev]
+    u = np.zeros((T + 1) * m)
+    u[:m] = wT.ravel()
+    norms = []
+    for it in range(3):
+        u = _dense_cycle(As, 0, u, b0, cf, fcf, m, norms)
+        want = its[it][::-1].reshape(-1)
+        assert np.max(np.abs(u - want)) <= 1e-11 * max(1.0, np.max(np.abs(want))), it
+        assert abs(norms[it] - out[1][it]) <= 1e-10 * max(out[1]), it

@@ -30,14 +30,24 @@
  *   (Sec. 3.3); `levels` counts the fine level (three levels over 128 steps
  *   with cf = 4 are grids of 128, 32 and 8 steps).  cf^(levels-1) must divide T.
  * - Ownership: the caller owns every buffer including the workspace.  The
- *   library never allocates or frees device memory and never synchronises the
- *   device; all work is enqueued on `stream` (a hipStream_t passed as void*;
- *   NULL is the default stream).  Outputs are overwritten, never accumulated.
+ *   library never allocates or frees device memory, and the compute entry
+ *   points never synchronise the device: all their work is enqueued on
+ *   `stream` (a hipStream_t passed as void*; NULL is the default stream).  The
+ *   only calls that wait are mgrit_gru_profile_read / _read_shape, which
+ *   synchronise on the timing events they report.  Outputs are overwritten,
+ *   never accumulated.
  * - Errors: every entry point returns 0 on success or a negative MGRIT_E_*
- *   code.  Arguments are validated on the host before anything is launched, so
- *   a failing call leaves all buffers untouched.  No exception crosses the ABI.
- *   mgrit_gru_strerror() names a code.
+ *   code.  Arguments are validated on the host before anything is launched:
+ *   with every code except MGRIT_E_LAUNCH a failing call has launched nothing
+ *   and all buffers are untouched.  MGRIT_E_LAUNCH is returned from the middle
+ *   of the work when the HIP runtime refuses a launch; outputs and workspace are
+ *   then undefined.  (An error state left on the calling thread by earlier,
+ *   unrelated HIP work is cleared at entry and not reported.)  No exception
+ *   crosses the ABI.  mgrit_gru_strerror() names a code.
  * - Calls that share a workspace must be ordered on one stream.
+ * - resnorm_out values are sums of squares accumulated with floating-point
+ *   atomics in double precision: reproducible to about 1e-15 relative, not
+ *   bit for bit; every other output is bitwise reproducible.
  */
 #ifndef MGRIT_GRU_H
 #define MGRIT_GRU_H
@@ -65,7 +75,13 @@ enum {
   MGRIT_E_ALIGN = -6,       /* H or D not a multiple of 4 (MGRIT_F32) / 8 (other dtypes),
                                or a pointer not 16-byte aligned */
   MGRIT_E_LAUNCH = -7,      /* the HIP runtime refused a launch */
-  MGRIT_E_UNSUPPORTED = -8  /* a valid request this build has no kernel for */
+  MGRIT_E_UNSUPPORTED = -8, /* a valid request this build has no kernel for */
+  MGRIT_E_STATE = -9        /* MGRIT_REUSE_PROJECTION / MGRIT_REUSE_COEFFS, but the library's
+                               host-side record of this workspace pointer says the projection
+                               / coefficient vectors of another problem (other sizes, hierarchy,
+                               dtype, propagator, x / W / b_i / h arrays), or none, were left
+                               there.  The record cannot see memory overwritten by others or
+                               arrays changed in place: that part stays the caller's promise */
 };
 
 enum { MGRIT_PROP_IMPLICIT = 0,   /* Eq. 16, the paper's propagator on all levels */
@@ -97,7 +113,10 @@ enum {
    * propagator and workspace pointer, and the states h passed in are the ones
    * that call returned: only the steps it did not cover (those of level 0
    * into the coarse points, and the coarsest level beyond level 1) are
-   * linearised again. */
+   * linearised again.  A backward call leaves the vectors of every step, so a
+   * further backward call on the same problem may reuse them too.  Checked
+   * against the host-side record of the workspace (MGRIT_E_STATE), like
+   * MGRIT_REUSE_PROJECTION. */
   MGRIT_REUSE_COEFFS = 4,
   /* mgrit_gru_backward: rows 0..T-1 of w_inout are zero on entry (the initial
    * guess of Alg. 3).  The adjoint recurrence is linear and homogeneous, so in
@@ -253,8 +272,10 @@ MGRIT_API const char* mgrit_gru_strerror(int code);
  * bracketed by HIP events on the launch stream.  mgrit_gru_profile_read
  * synchronises those events and returns, per kernel class, the number of
  * launches, their summed duration in milliseconds and their summed
- * algorithmic flops and bytes; it then clears the record.  Event objects are
- * host-side and created on demand; nothing here touches device memory.
+ * algorithmic flops and bytes; it then clears what it returned.  Event objects are
+ * host-side and created on demand; nothing here touches device memory.  Switching
+ * profiling on starts an empty record; the record holds at most 2^18 launches
+ * (later ones run unbracketed until a read makes room).
  *   kind: 0 = forward step (Phi) on MFMA tiles, 1 = adjoint step (Phi^T) on MFMA tiles,
  *         2 = projection GEMM, 3 = weight-gradient GEMMs, 4 / 5 = forward / adjoint step
  *         in the few-row form used by the serial scan and the coarsest-level solve,

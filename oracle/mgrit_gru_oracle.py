@@ -46,6 +46,13 @@ def sigmoid(a):
     return 1.0 / (1.0 + np.exp(-a))
 
 
+def _rows_times(a, M):
+    """a[..., K] @ M[K, N] with all leading axes of `a` taken together as the rows of ONE matrix
+    product (numpy would otherwise run one small product per leading index)."""
+    a = np.asarray(a)
+    return (a.reshape(-1, a.shape[-1]) @ M).reshape(a.shape[:-1] + (M.shape[1],))
+
+
 # --------------------------------------------------------------------------
 # Cell: Eq. 1 gates, Eq. 3 / Eq. 16 propagators
 # --------------------------------------------------------------------------
@@ -55,7 +62,7 @@ def input_projection(W, b_i, x):
     pre-activations).  Computed once and reused on every level and in the
     adjoint, as the paper reuses its precomputed per-step features
     (Appendix A.3.2)."""
-    return _f64(x) @ _f64(W).T + _f64(b_i)
+    return _rows_times(_f64(x), _f64(W).T) + _f64(b_i)
 
 
 def gates(P, h, U, b_h):
@@ -63,7 +70,7 @@ def gates(P, h, U, b_h):
     the OLD state h = h_{t-1} (Sec. 3.3, text after Eq. 15).  Also returns
     q = W_hn h + b_hn, needed by the adjoint."""
     H = h.shape[-1]
-    a = h @ U.T + b_h
+    a = _rows_times(h, U.T) + b_h
     r = sigmoid(P[..., :H] + a[..., :H])
     z = sigmoid(P[..., H:2 * H] + a[..., H:2 * H])
     q = a[..., 2 * H:]
@@ -122,7 +129,8 @@ def phi_transpose(coeffs, w, U):
     """(dPhi/dh)^T w = k_d*w + U_r^T(k_r*w) + U_z^T(k_z*w) + U_n^T(k_q*w)."""
     k_d, k_r, k_z, k_q, _ = coeffs
     H = w.shape[-1]
-    return (k_d * w + (k_r * w) @ U[:H] + (k_z * w) @ U[H:2 * H] + (k_q * w) @ U[2 * H:])
+    return (k_d * w + _rows_times(k_r * w, U[:H]) + _rows_times(k_z * w, U[H:2 * H])
+            + _rows_times(k_q * w, U[2 * H:]))
 
 
 # --------------------------------------------------------------------------
@@ -326,7 +334,7 @@ def mgrit_forward(W, U, b_i, b_h, x, h0, h_init, cf, levels, iters,
 
 def mgrit_backward(W, U, b_i, b_h, x, h, dL_dhT, w_init, cf, levels, iters,
                    fine_relax_fcf=True, propagator=IMPLICIT, keep_iterates=False,
-                   dL_dh=None):
+                   dL_dh=None, with_gradients=True):
     """Alg. 3 backward block: `iters` applications of MGBackProp to the adjoint
     iterate w_init[(T+1),B,H] (row T is overwritten with dL/dh_T), then the
     parameter gradients from the final w (Alg. 3 gradient line).
@@ -341,7 +349,10 @@ def mgrit_backward(W, U, b_i, b_h, x, h, dL_dhT, w_init, cf, levels, iters,
     With dL_dh[(T+1),B,H] given (a loss on every state; dL_dhT is then ignored)
     the adjoint recurrence carries the source term dL_dh[t] at point t: it is
     the right-hand side of the level-0 equation, which the cycle restricts like
-    any other (Eq. 11); the result gains a last element dx = input_gradients."""
+    any other (Eq. 11); the result gains a last element dx = input_gradients.
+
+    with_gradients=False stops after the cycles and returns (w, resnorms[, iterates]): for
+    callers that compare the adjoint iterate only (the gradient line is a loop over all T)."""
     if dL_dh is not None:
         dL_dh = _f64(dL_dh)
         dL_dhT = dL_dh[-1]
@@ -368,6 +379,8 @@ def mgrit_backward(W, U, b_i, b_h, x, h, dL_dhT, w_init, cf, levels, iters,
         if keep_iterates:
             iterates.append(wr[::-1].copy())
     w = wr[::-1].copy()
+    if not with_gradients:
+        return (w, resnorms, iterates) if keep_iterates else (w, resnorms)
     grads = parameter_gradients(W, U, b_i, b_h, x, h, w, propagator)
     if dL_dh is not None:
         grads = grads + (input_gradients(W, U, b_i, b_h, x, h, w, propagator),)

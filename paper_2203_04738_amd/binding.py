@@ -41,6 +41,7 @@ MGRIT_KEEP_COEFFS = 2
 MGRIT_REUSE_COEFFS = 4
 MGRIT_ZERO_ADJOINT_GUESS = 8
 MGRIT_ZERO_STATE_GUESS = 16
+MGRIT_E_STATE = -9
 _lib = None
 
 
@@ -101,18 +102,45 @@ def mgrit_gru_strerror(code: int) -> str:
     return lib().mgrit_gru_strerror(int(code)).decode()
 
 
-def _ptr(t, name: str, dtype=None) -> Optional[int]:
-    """Device pointer of a contiguous CUDA tensor (None passes NULL)."""
-    if t is None:
-        return None
+class _Arg:
+    """One tensor argument and what cfg implies about it."""
+
+    def __init__(self, t, name, dtype=None, shape=None, min_numel=None):
+        self.t, self.name, self.dtype, self.shape, self.min_numel = t, name, dtype, shape, min_numel
+
+
+def _marshal(args):
+    """Device pointers of contiguous CUDA tensors (None passes NULL; plain values pass through).
+    The C ABI takes plain pointers and cannot know buffer sizes, so the size of every tensor is
+    compared with what cfg implies here: `shape` must match exactly, `min_numel` is a lower
+    bound.  All sizes are checked first (ValueError), then dtype, layout and device
+    (TypeError / ValueError); nothing is launched unless every argument passes."""
     import torch
-    if not isinstance(t, torch.Tensor) or not t.is_cuda:
-        raise TypeError(f"{name}: expected a CUDA tensor")
-    if not t.is_contiguous():
-        raise ValueError(f"{name}: tensor must be contiguous")
-    if dtype is not None and t.dtype != dtype:
-        raise TypeError(f"{name}: expected dtype {dtype}, got {t.dtype}")
-    return t.data_ptr()
+    for a in args:
+        if not isinstance(a, _Arg) or a.t is None:
+            continue
+        if not isinstance(a.t, torch.Tensor):
+            raise TypeError(f"{a.name}: expected a CUDA tensor")
+        if a.shape is not None and tuple(a.t.shape) != tuple(a.shape):
+            raise ValueError(f"{a.name}: expected shape {tuple(a.shape)}, got {tuple(a.t.shape)}")
+        if a.min_numel is not None and a.t.numel() < a.min_numel:
+            raise ValueError(f"{a.name}: expected at least {a.min_numel} elements, "
+                             f"got {a.t.numel()}")
+    out = []
+    for a in args:
+        if not isinstance(a, _Arg):
+            out.append(a)
+        elif a.t is None:
+            out.append(None)
+        else:
+            if a.dtype is not None and a.t.dtype != a.dtype:
+                raise TypeError(f"{a.name}: expected dtype {a.dtype}, got {a.t.dtype}")
+            if not a.t.is_contiguous():
+                raise ValueError(f"{a.name}: tensor must be contiguous")
+            if not a.t.is_cuda:
+                raise TypeError(f"{a.name}: expected a CUDA tensor")
+            out.append(a.t.data_ptr())
+    return out
 
 
 def _stream() -> int:
@@ -120,14 +148,15 @@ def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
-def _in_dtype(cfg: MgritGruCfg):
-    import torch
-    return torch.bfloat16 if cfg.dtype == 1 else torch.float32
-
-
 def _check(rc: int, where: str) -> None:
     if rc != 0:
         raise MgritGruError(rc, where)
+
+
+def _call(name: str, cfg, *args) -> None:
+    """Checks and marshals the arguments, then calls entry point `name` on the current stream."""
+    ptrs = _marshal(args)
+    _check(getattr(lib(), name)(ctypes.byref(cfg), *ptrs, _stream()), name)
 
 
 def mgrit_gru_workspace_bytes(cfg: MgritGruCfg) -> int:
@@ -137,99 +166,103 @@ def mgrit_gru_workspace_bytes(cfg: MgritGruCfg) -> int:
     return int(n.value)
 
 
-def gru_serial_scan(cfg, W, U, b_i, b_h, x, h0, h_out, workspace) -> None:
+def _f32():
     import torch
-    f32, dt = torch.float32, _in_dtype(cfg)
-    _check(lib().gru_serial_scan(
-        ctypes.byref(cfg), _ptr(W, "W", dt), _ptr(U, "U", dt), _ptr(b_i, "b_i", f32),
-        _ptr(b_h, "b_h", f32), _ptr(x, "x", dt), _ptr(h0, "h0", f32), _ptr(h_out, "h_out", f32),
-        _ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()),
-        "gru_serial_scan")
+    return torch.float32
+
+
+def _params(cfg, W, U, b_i, b_h, x):
+    """The five arguments every GRU entry point starts with."""
+    import torch
+    f32 = torch.float32
+    dt = torch.bfloat16 if cfg.dtype == MGRIT_BF16 else f32
+    T, B, D, H = cfg.T, cfg.B, cfg.D, cfg.H
+    return (_Arg(W, "W", dt, (3 * H, D)), _Arg(U, "U", dt, (3 * H, H)),
+            _Arg(b_i, "b_i", f32, (3 * H,)), _Arg(b_h, "b_h", f32, (3 * H,)),
+            _Arg(x, "x", dt, (T, B, D)))
+
+
+def _grads(cfg, dW, dU, db_i, db_h):
+    f32, D, H = _f32(), cfg.D, cfg.H
+    return (_Arg(dW, "dW", f32, (3 * H, D)), _Arg(dU, "dU", f32, (3 * H, H)),
+            _Arg(db_i, "db_i", f32, (3 * H,)), _Arg(db_h, "db_h", f32, (3 * H,)))
+
+
+def _workspace(workspace):
+    """Workspace pointer and its size in bytes (the library compares the size with cfg)."""
+    n = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    return _Arg(workspace, "workspace"), ctypes.c_size_t(n)
+
+
+def _state(cfg, t, name):
+    return _Arg(t, name, _f32(), (cfg.T + 1, cfg.B, cfg.H))
+
+
+def _row(cfg, t, name):
+    return _Arg(t, name, _f32(), (cfg.B, cfg.H))
+
+
+def _res(cfg, t):
+    return _Arg(t, "resnorm_out", _f32(), min_numel=cfg.iters)
+
+
+def _dx(cfg, t):
+    return _Arg(t, "dx", _f32(), (cfg.T, cfg.B, cfg.D))
+
+
+def gru_serial_scan(cfg, W, U, b_i, b_h, x, h0, h_out, workspace) -> None:
+    _call("gru_serial_scan", cfg, *_params(cfg, W, U, b_i, b_h, x), _row(cfg, h0, "h0"),
+          _state(cfg, h_out, "h_out"), *_workspace(workspace))
 
 
 def mgrit_gru_forward(cfg, W, U, b_i, b_h, x, h0, h_inout, resnorm_out, workspace) -> None:
-    import torch
-    f32, dt = torch.float32, _in_dtype(cfg)
-    _check(lib().mgrit_gru_forward(
-        ctypes.byref(cfg), _ptr(W, "W", dt), _ptr(U, "U", dt), _ptr(b_i, "b_i", f32),
-        _ptr(b_h, "b_h", f32), _ptr(x, "x", dt), _ptr(h0, "h0", f32),
-        _ptr(h_inout, "h_inout", f32), _ptr(resnorm_out, "resnorm_out", f32),
-        _ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()),
-        "mgrit_gru_forward")
+    _call("mgrit_gru_forward", cfg, *_params(cfg, W, U, b_i, b_h, x), _row(cfg, h0, "h0"),
+          _state(cfg, h_inout, "h_inout"), _res(cfg, resnorm_out), *_workspace(workspace))
 
 
 def gru_serial_scan_backward(cfg, W, U, b_i, b_h, x, h, dL_dhT, w_out, dW, dU, db_i, db_h,
                              workspace) -> None:
-    import torch
-    f32, dt = torch.float32, _in_dtype(cfg)
-    _check(lib().gru_serial_scan_backward(
-        ctypes.byref(cfg), _ptr(W, "W", dt), _ptr(U, "U", dt), _ptr(b_i, "b_i", f32),
-        _ptr(b_h, "b_h", f32), _ptr(x, "x", dt), _ptr(h, "h", f32), _ptr(dL_dhT, "dL_dhT", f32),
-        _ptr(w_out, "w_out", f32), _ptr(dW, "dW", f32), _ptr(dU, "dU", f32),
-        _ptr(db_i, "db_i", f32), _ptr(db_h, "db_h", f32),
-        _ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()),
-        "gru_serial_scan_backward")
+    _call("gru_serial_scan_backward", cfg, *_params(cfg, W, U, b_i, b_h, x), _state(cfg, h, "h"),
+          _row(cfg, dL_dhT, "dL_dhT"), _state(cfg, w_out, "w_out"),
+          *_grads(cfg, dW, dU, db_i, db_h), *_workspace(workspace))
 
 
 def mgrit_gru_backward(cfg, W, U, b_i, b_h, x, h, dL_dhT, w_inout, resnorm_out, dW, dU, db_i,
                        db_h, workspace) -> None:
-    import torch
-    f32, dt = torch.float32, _in_dtype(cfg)
-    _check(lib().mgrit_gru_backward(
-        ctypes.byref(cfg), _ptr(W, "W", dt), _ptr(U, "U", dt), _ptr(b_i, "b_i", f32),
-        _ptr(b_h, "b_h", f32), _ptr(x, "x", dt), _ptr(h, "h", f32), _ptr(dL_dhT, "dL_dhT", f32),
-        _ptr(w_inout, "w_inout", f32), _ptr(resnorm_out, "resnorm_out", f32),
-        _ptr(dW, "dW", f32), _ptr(dU, "dU", f32), _ptr(db_i, "db_i", f32), _ptr(db_h, "db_h", f32),
-        _ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()),
-        "mgrit_gru_backward")
+    _call("mgrit_gru_backward", cfg, *_params(cfg, W, U, b_i, b_h, x), _state(cfg, h, "h"),
+          _row(cfg, dL_dhT, "dL_dhT"), _state(cfg, w_inout, "w_inout"), _res(cfg, resnorm_out),
+          *_grads(cfg, dW, dU, db_i, db_h), *_workspace(workspace))
 
 
 def gru_serial_scan_backward_steps(cfg, W, U, b_i, b_h, x, h, dL_dh, w_out, dW, dU, db_i, db_h,
                                    dx, workspace) -> None:
-    import torch
-    f32, dt = torch.float32, _in_dtype(cfg)
-    _check(lib().gru_serial_scan_backward_steps(
-        ctypes.byref(cfg), _ptr(W, "W", dt), _ptr(U, "U", dt), _ptr(b_i, "b_i", f32),
-        _ptr(b_h, "b_h", f32), _ptr(x, "x", dt), _ptr(h, "h", f32), _ptr(dL_dh, "dL_dh", f32),
-        _ptr(w_out, "w_out", f32), _ptr(dW, "dW", f32), _ptr(dU, "dU", f32),
-        _ptr(db_i, "db_i", f32), _ptr(db_h, "db_h", f32), _ptr(dx, "dx", f32),
-        _ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()),
-        "gru_serial_scan_backward_steps")
+    _call("gru_serial_scan_backward_steps", cfg, *_params(cfg, W, U, b_i, b_h, x),
+          _state(cfg, h, "h"), _state(cfg, dL_dh, "dL_dh"), _state(cfg, w_out, "w_out"),
+          *_grads(cfg, dW, dU, db_i, db_h), _dx(cfg, dx), *_workspace(workspace))
 
 
 def mgrit_gru_backward_steps(cfg, W, U, b_i, b_h, x, h, dL_dh, w_inout, resnorm_out, dW, dU,
                              db_i, db_h, dx, workspace) -> None:
-    import torch
-    f32, dt = torch.float32, _in_dtype(cfg)
-    _check(lib().mgrit_gru_backward_steps(
-        ctypes.byref(cfg), _ptr(W, "W", dt), _ptr(U, "U", dt), _ptr(b_i, "b_i", f32),
-        _ptr(b_h, "b_h", f32), _ptr(x, "x", dt), _ptr(h, "h", f32), _ptr(dL_dh, "dL_dh", f32),
-        _ptr(w_inout, "w_inout", f32), _ptr(resnorm_out, "resnorm_out", f32),
-        _ptr(dW, "dW", f32), _ptr(dU, "dU", f32), _ptr(db_i, "db_i", f32), _ptr(db_h, "db_h", f32),
-        _ptr(dx, "dx", f32),
-        _ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()),
-        "mgrit_gru_backward_steps")
+    _call("mgrit_gru_backward_steps", cfg, *_params(cfg, W, U, b_i, b_h, x), _state(cfg, h, "h"),
+          _state(cfg, dL_dh, "dL_dh"), _state(cfg, w_inout, "w_inout"), _res(cfg, resnorm_out),
+          *_grads(cfg, dW, dU, db_i, db_h), _dx(cfg, dx), *_workspace(workspace))
+
+
+def _ode_params(cfg, dt, A, Bw, b, d):
+    f32 = _f32()
+    T, B, D, H = cfg.T, cfg.B, cfg.D, cfg.H
+    return (ctypes.c_float(float(dt)), _Arg(A, "A", f32, (H, H)), _Arg(Bw, "Bw", f32, (H, D)),
+            _Arg(b, "b", f32, (H,)), _Arg(d, "d", f32, (T, B, D)))
 
 
 def ode_serial_scan(cfg, dt, A, Bw, b, d, h0, h_out, workspace) -> None:
-    import torch
-    f32 = torch.float32
-    _check(lib().ode_serial_scan(
-        ctypes.byref(cfg), float(dt), _ptr(A, "A", f32), _ptr(Bw, "Bw", f32), _ptr(b, "b", f32),
-        _ptr(d, "d", f32), _ptr(h0, "h0", f32), _ptr(h_out, "h_out", f32),
-        _ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()),
-        "ode_serial_scan")
+    _call("ode_serial_scan", cfg, *_ode_params(cfg, dt, A, Bw, b, d), _row(cfg, h0, "h0"),
+          _state(cfg, h_out, "h_out"), *_workspace(workspace))
 
 
 def mgrit_ode_forward(cfg, dt, A, Bw, b, d, h0, h_inout, resnorm_out, workspace) -> None:
-    import torch
-    f32 = torch.float32
-    _check(lib().mgrit_ode_forward(
-        ctypes.byref(cfg), float(dt), _ptr(A, "A", f32), _ptr(Bw, "Bw", f32), _ptr(b, "b", f32),
-        _ptr(d, "d", f32), _ptr(h0, "h0", f32), _ptr(h_inout, "h_inout", f32),
-        _ptr(resnorm_out, "resnorm_out", f32),
-        _ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream()),
-        "mgrit_ode_forward")
+    _call("mgrit_ode_forward", cfg, *_ode_params(cfg, dt, A, Bw, b, d), _row(cfg, h0, "h0"),
+          _state(cfg, h_inout, "h_inout"), _res(cfg, resnorm_out), *_workspace(workspace))
 
 
 def mgrit_gru_profile_enable(on: bool) -> None:

@@ -5,6 +5,7 @@
 #include <cstdint>
 #include <cstring>
 #include <mutex>
+#include <unordered_map>
 #include <vector>
 
 #include "common.h"
@@ -21,28 +22,38 @@ struct ProfRec {
   long long rows;
   hipEvent_t e0, e1;
   double flops, bytes;
+  bool open;           // begun, end not yet recorded
 };
 static bool g_prof = false;
 static std::mutex g_prof_mu;
 static std::vector<ProfRec> g_recs;
+// Launches recorded while profiling is on and nobody reads: beyond this many the record stops
+// growing (further launches run unbracketed) until a read or mgrit_gru_profile_enable clears it.
+constexpr size_t MAX_PROF_RECS = 1u << 18;
+// set for the duration of a call that must create no runtime objects (the entry point that
+// allocates nothing): its launches are never bracketed
+static thread_local bool t_no_prof = false;
 
 void prof_begin(int kind, hipStream_t s, long long rows, int mode) {
-  if (!g_prof) return;
+  if (!g_prof || t_no_prof) return;
   std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (g_recs.size() >= MAX_PROF_RECS) return;
   ProfRec r;
   r.kind = kind;
   r.rows = rows;
   r.mode = mode;
   r.flops = r.bytes = 0;
+  r.open = true;
   if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) return;
   (void)hipEventRecord(r.e0, s);
   g_recs.push_back(r);
 }
 
 void prof_end(int kind, double flops, double bytes, hipStream_t s) {
-  if (!g_prof) return;
+  if (!g_prof || t_no_prof) return;
   std::lock_guard<std::mutex> lk(g_prof_mu);
-  if (g_recs.empty() || g_recs.back().kind != kind) return;
+  if (g_recs.empty() || g_recs.back().kind != kind || !g_recs.back().open) return;
+  g_recs.back().open = false;
   g_recs.back().flops = flops;
   g_recs.back().bytes = bytes;
   (void)hipEventRecord(g_recs.back().e1, s);
@@ -150,6 +161,67 @@ static bool misaligned(const void* p) { return ((uintptr_t)p & 15) != 0; }
   do {                                           \
     if ((expr) != hipSuccess) return MGRIT_E_LAUNCH; \
   } while (0)
+
+// ---------------------------------------------------------------------------
+// what a workspace holds (host-side record; no device read, no synchronisation)
+// ---------------------------------------------------------------------------
+// MGRIT_REUSE_PROJECTION and MGRIT_REUSE_COEFFS are promises about the contents of the
+// caller's workspace.  The call that leaves the projection / the coefficient vectors there
+// notes, under the workspace pointer, the problem they belong to; a call that asks to reuse
+// them is refused (MGRIT_E_STATE, before any launch) unless its own problem matches.  The
+// record cannot see a workspace that was overwritten by something else than this library, nor
+// input arrays whose contents changed in place: those stay the caller's promise.
+struct WsRecord {
+  bool have_proj = false, have_coeffs = false;
+  // projection: sizes, operand form, row width (3H, or H for the demonstration ODE) and the
+  // arrays it was computed from
+  int pT = 0, pB = 0, pD = 0, pH = 0, pdtype = 0, pwidth = 0;
+  const void *px = nullptr, *pW = nullptr, *pbi = nullptr;
+  // coefficient vectors: the configuration of the forward call that kept them and the state
+  // array they were linearised at
+  mgrit_gru_cfg ccfg{};
+  bool cserial = false;
+  const void* ch = nullptr;
+};
+static std::mutex g_ws_mu;
+static std::unordered_map<const void*, WsRecord> g_ws;
+constexpr size_t MAX_WS_RECORDS = 1024;   // beyond that the table starts over (reuse is then
+                                          // refused until the producing call runs again)
+
+static WsRecord ws_record_get(const void* ws) {
+  std::lock_guard<std::mutex> lk(g_ws_mu);
+  auto it = g_ws.find(ws);
+  return it == g_ws.end() ? WsRecord{} : it->second;
+}
+static void ws_record_put(const void* ws, const WsRecord& r) {
+  std::lock_guard<std::mutex> lk(g_ws_mu);
+  if (g_ws.size() >= MAX_WS_RECORDS && g_ws.find(ws) == g_ws.end()) g_ws.clear();
+  g_ws[ws] = r;
+}
+
+static bool proj_matches(const WsRecord& r, const mgrit_gru_cfg& c, int width, const void* x,
+                         const void* W, const void* b_i) {
+  return r.have_proj && r.pT == c.T && r.pB == c.B && r.pD == c.D && r.pH == c.H &&
+         r.pdtype == c.dtype && r.pwidth == width && r.px == x && r.pW == W && r.pbi == b_i;
+}
+static void proj_note(WsRecord& r, const mgrit_gru_cfg& c, int width, const void* x,
+                      const void* W, const void* b_i) {
+  // a projection of other sizes moves every later array of the layout
+  if (r.pT != c.T || r.pB != c.B || r.pD != c.D || r.pH != c.H || r.pdtype != c.dtype)
+    r.have_coeffs = false;
+  r.have_proj = true;
+  r.pT = c.T; r.pB = c.B; r.pD = c.D; r.pH = c.H;
+  r.pdtype = c.dtype; r.pwidth = width;
+  r.px = x; r.pW = W; r.pbi = b_i;
+}
+static bool coeffs_match(const WsRecord& r, const mgrit_gru_cfg& c, bool serial, const void* h) {
+  if (!r.have_coeffs || r.cserial != serial || r.ch != h) return false;
+  const mgrit_gru_cfg& k = r.ccfg;
+  if (k.T != c.T || k.B != c.B || k.D != c.D || k.H != c.H || k.dtype != c.dtype ||
+      k.propagator != c.propagator)
+    return false;
+  return serial || (k.cf == c.cf && k.levels == c.levels);
+}
 
 // ---------------------------------------------------------------------------
 // forward drivers
@@ -393,6 +465,19 @@ static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, co
   if (ws_bytes < lay.total) return MGRIT_E_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   char* base = (char*)ws;
+  const int pwidth = ode ? c.H : 3 * c.H;
+  WsRecord rec = ws_record_get(ws);
+  if ((c.flags & MGRIT_REUSE_PROJECTION) && !proj_matches(rec, c, pwidth, x, W, b_i))
+    return MGRIT_E_STATE;
+  if ((c.flags & MGRIT_KEEP_COEFFS) && c.iters < 1) return MGRIT_E_SIZE;
+  // from here on the workspace changes: note what it will hold when this call's work is done
+  if (!(c.flags & MGRIT_REUSE_PROJECTION)) proj_note(rec, c, pwidth, x, W, b_i);
+  rec.have_coeffs = (c.flags & MGRIT_KEEP_COEFFS) != 0;   // the states change: older vectors are stale
+  rec.ccfg = c;
+  rec.cserial = serial;
+  rec.ch = h;
+  ws_record_put(ws, rec);
+  (void)hipGetLastError();   // an error left by earlier, unrelated work is not this call's
 
   FwdCtx ctx;
   ctx.c = &c;
@@ -418,7 +503,6 @@ static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, co
   // MGRIT_KEEP_COEFFS: the closing F-relaxation of the last cycle (the serial scan, with
   // one level) also leaves the adjoint coefficient vectors of the steps it takes
   ctx.emit_kap = (c.flags & MGRIT_KEEP_COEFFS) ? (float*)(base + lay.kap[0]) : nullptr;
-  if (ctx.emit_kap && c.iters < 1) return MGRIT_E_SIZE;
   if (lay.L == 1 && !serial_scan_keeps_coeffs(c)) ctx.emit_kap = nullptr;
   for (int l = 0; l < MAX_LEVELS; ++l)
     ctx.emit_kapl[l] = (ctx.emit_kap && forward_leaves_coeffs(l, lay.L))
@@ -613,6 +697,19 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
   char* base = (char*)ws;
   const float* P = (const float*)(base + lay.P);
   const long long BH = (long long)c.B * c.H;
+  WsRecord rec = ws_record_get(ws);
+  if ((c.flags & MGRIT_REUSE_PROJECTION) && !proj_matches(rec, c, 3 * c.H, x, W, b_i))
+    return MGRIT_E_STATE;
+  if ((c.flags & MGRIT_REUSE_COEFFS) && !coeffs_match(rec, c, serial, h)) return MGRIT_E_STATE;
+  if (!(c.flags & MGRIT_REUSE_PROJECTION)) proj_note(rec, c, 3 * c.H, x, W, b_i);
+  // this call completes (or rebuilds) the vectors of every step for these states: they stay
+  // valid for a later backward call on the same problem
+  rec.have_coeffs = true;
+  rec.ccfg = c;
+  rec.cserial = serial;
+  rec.ch = h;
+  ws_record_put(ws, rec);
+  (void)hipGetLastError();   // an error left by earlier, unrelated work is not this call's
 
   if ((rc = run_projection(&c, lay, base, W, b_i, x, s))) return rc;
   const int bf16 = c.dtype == MGRIT_BF16;
@@ -804,13 +901,25 @@ const char* mgrit_gru_strerror(int code) {
     case MGRIT_E_ALIGN: return "width not a multiple of 4 (8 unless dtype is MGRIT_F32) or pointer not 16-byte aligned";
     case MGRIT_E_LAUNCH: return "HIP launch failed";
     case MGRIT_E_UNSUPPORTED: return "unsupported configuration";
+    case MGRIT_E_STATE:
+      return "workspace does not hold what MGRIT_REUSE_PROJECTION / MGRIT_REUSE_COEFFS asks for";
     default: return "unknown error";
   }
 }
 
 int mgrit_gru_profile_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);
+  const bool was = g_prof;
   g_prof = on != 0;
+  if (g_prof && !was) {
+    // switching on starts a fresh record (events of unread launches are released, not waited
+    // for); switching off keeps the record for the reads that follow
+    for (auto& r : g_recs) {
+      (void)hipEventDestroy(r.e0);
+      (void)hipEventDestroy(r.e1);
+    }
+    g_recs.clear();
+  }
   return MGRIT_OK;
 }
 

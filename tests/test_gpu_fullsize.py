@@ -9,7 +9,11 @@ iterate of the problem truncated to T' steps (T' a multiple of cf^(levels-1)).  
 adjoint cycle is the same statement in reversed time: its iterate on [T-T', T] equals that
 of the problem restricted to the last T' steps.  The linearisation states handed to the
 adjoint are seeded random values (the API accepts any states), so no oracle input comes
-from the HIP path."""
+from the HIP path.
+
+The last test follows single batch elements instead: batch elements never interact in any
+state tensor (every contraction is over the hidden width), so the oracle can run the full-length
+problem for a few sampled elements and compare every time step of every cycle."""
 import numpy as np
 import pytest
 import torch
@@ -133,3 +137,41 @@ def test_full_size_gradients_and_input_gradients_on_a_sparse_adjoint(gh, name, f
     mask[steps - 1] = False
     assert not np.any(gdx[mask])                     # steps with a zero adjoint contribute nothing
     assert n >= 90
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name,form", [("C3", None), ("C4", None), ("C5", None), ("C3", "fp32x3")])
+def test_full_size_bench_sequence_follows_sampled_batch_elements_over_all_steps(gh, name, form):
+    """The call sequence bench.py times, at full size: forward solve (all cycles in one call, zero
+    guess declared, coefficients kept), backward solve (projection and coefficients reused, zero
+    guess declared).  The oracle runs the same problem over the whole sequence for the first and
+    the last batch element (a row tile of any launch holds all batch elements of its intervals,
+    so every row tile and every column of every launch is sampled) and every time step of the
+    state and of the adjoint is compared, after the first cycle and after the workload's cycle
+    counts.  The adjoint's linearisation states are the oracle's own forward iterate on its side
+    and the HIP path's forward iterate on the other, as in a training step."""
+    wl = WORKLOADS[name]
+    d = make_inputs(wl)
+    tol = 1e-5 if wl.dtype == "fp32" else 2e-2
+    T, B, H = wl.T, wl.B, wl.H
+    bs = [0, B - 1]
+    nf, nb = wl.fwd_iters, wl.bwd_iters
+    run = gh.GpuRun(d, cf=wl.cf, levels=wl.levels, dtype=_dtype(wl, form))
+    xs = np.ascontiguousarray(d["x"][:, bs])
+    z = np.zeros((T + 1, len(bs), H))
+    print(f"{name} {form}: oracle forward, {nf} cycles", flush=True)
+    _, _, h_its = orc.mgrit_forward(*_P(d), xs, d["h0"][bs], z, wl.cf, wl.levels, nf,
+                                    keep_iterates=True)
+    print(f"{name} {form}: oracle backward, {nb} cycles", flush=True)
+    _, _, w_its = orc.mgrit_backward(*_P(d), xs, h_its[-1], d["dL_dhT"][bs], z, wl.cf, wl.levels,
+                                     nb, keep_iterates=True, with_gradients=False)
+    if nf > 1:
+        its, _ = run.forward_iterates(1, first_call_flags=gh.MGRIT_ZERO_STATE_GUESS)
+        assert gh.rel_err(its[-1][:, bs], h_its[0]) <= tol, ("h", 1)
+    for cycles in sorted({1, nb}):
+        print(f"{name} {form}: HIP path, {nf} forward / {cycles} backward cycles", flush=True)
+        out = run.forward_then_backward_reusing_coeffs(nf, cycles)
+        assert gh.rel_err(out[0][:, bs], h_its[-1]) <= tol, ("h", nf)
+        assert gh.rel_err(out[1][:, bs], w_its[cycles - 1]) <= tol, ("w", nf, cycles)
+        for g in out[2:]:
+            assert np.all(np.isfinite(g))

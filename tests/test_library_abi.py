@@ -153,3 +153,62 @@ def test_bench_refuses_more_than_one_gpu():
                        capture_output=True, text=True, timeout=120)
     assert r.returncode != 0
     assert "--gpus 1" in r.stderr
+
+
+def test_reuse_flags_are_refused_on_a_workspace_the_library_has_no_record_of():
+    """MGRIT_REUSE_PROJECTION / MGRIT_REUSE_COEFFS are checked against a host-side record keyed
+    by the workspace pointer; with no matching record the call is refused before any launch."""
+    L = mg.lib()
+    p = 4096
+    ws = 1 << 20                      # an address no call has used as a workspace
+    for flags in (mg.MGRIT_REUSE_PROJECTION, mg.MGRIT_REUSE_COEFFS,
+                  mg.MGRIT_REUSE_PROJECTION | mg.MGRIT_REUSE_COEFFS):
+        cfg = MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, iters=1, flags=flags)
+        assert L.mgrit_gru_backward(ctypes.byref(cfg), p, p, p, p, p, p, p, p, None, p, p, p, p,
+                                    ws, 1 << 30, None) == mg.MGRIT_E_STATE
+        assert L.gru_serial_scan_backward(ctypes.byref(cfg), p, p, p, p, p, p, p, p, p, p, p, p,
+                                          ws, 1 << 30, None) == mg.MGRIT_E_STATE
+    cfg = MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, iters=1, flags=mg.MGRIT_REUSE_PROJECTION)
+    assert L.mgrit_gru_forward(ctypes.byref(cfg), p, p, p, p, p, p, p, None, ws, 1 << 30,
+                               None) == mg.MGRIT_E_STATE
+    assert "REUSE" in mg.mgrit_gru_strerror(mg.MGRIT_E_STATE)
+
+
+def test_binding_rejects_tensors_whose_size_does_not_match_cfg():
+    """The C ABI takes plain pointers; the binding compares every tensor's shape with cfg and
+    raises before anything is launched (CPU tensors suffice to reach the shape checks)."""
+    import torch
+    T, B, D, H = 8, 2, 4, 8
+    cfg = MgritGruCfg(T, B, D, H, cf=2, levels=2, iters=3)
+    z = lambda *s: torch.zeros(*s)
+    good = dict(W=z(3 * H, D), U=z(3 * H, H), b_i=z(3 * H), b_h=z(3 * H), x=z(T, B, D))
+    states, ws = z(T + 1, B, H), torch.zeros(1 << 16, dtype=torch.uint8)
+    g = (z(3 * H, D), z(3 * H, H), z(3 * H), z(3 * H))
+
+    def fwd(**over):
+        a = dict(good, h0=z(B, H), h=states, res=z(3))
+        a.update(over)
+        mg.mgrit_gru_forward(cfg, a["W"], a["U"], a["b_i"], a["b_h"], a["x"], a["h0"], a["h"],
+                             a["res"], ws)
+
+    for over in (dict(h=z(T, B, H)), dict(res=z(2)), dict(x=z(T + 1, B, D)), dict(W=z(3 * H, H)),
+                 dict(U=z(H, H)), dict(b_i=z(H)), dict(b_h=z(3 * H + 1)), dict(h0=z(B, H + 1))):
+        with pytest.raises(ValueError):
+            fwd(**over)
+    with pytest.raises(TypeError):       # right sizes, but not device memory
+        fwd()
+    P = tuple(good.values())
+    with pytest.raises(ValueError):      # the step-loss entry point takes dL_dh[(T+1),B,H]
+        mg.mgrit_gru_backward_steps(cfg, *P, states, z(B, H), states, z(3), *g, z(T, B, D), ws)
+    with pytest.raises(ValueError):      # ... and the terminal-loss one dL_dhT[B,H]
+        mg.mgrit_gru_backward(cfg, *P, states, states, states, z(3), *g, ws)
+    with pytest.raises(ValueError):
+        mg.mgrit_gru_backward_steps(cfg, *P, states, states, states, z(3), *g, z(T, B, H), ws)
+    with pytest.raises(ValueError):
+        mg.mgrit_gru_backward(cfg, *P, states, z(B, H), states, z(3), g[1], g[1], g[2], g[3], ws)
+    with pytest.raises(ValueError):
+        mg.gru_serial_scan(cfg, *P, z(B, H), z(T, B, H), ws)
+    with pytest.raises(ValueError):
+        mg.gru_serial_scan_backward(cfg, *P, states, z(B, H), z(T, B, H), *g, ws)
+    with pytest.raises(ValueError):
+        mg.mgrit_ode_forward(cfg, 0.1, z(H, D), z(H, D), z(H), z(T, B, D), z(B, H), states, z(3), ws)

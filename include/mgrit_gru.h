@@ -240,6 +240,26 @@ MGRIT_API int mgrit_gru_backward_steps(const mgrit_gru_cfg* cfg, const void* W, 
                        float* dW, float* dU, float* db_i, float* db_h, float* dx,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* mgrit_gru_forward for callers that cannot allocate device memory or pass a
+ * workspace (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): the workspace is a fixed array of
+ * MGRIT_STATIC_SCRATCH_BYTES inside the library's code object, one copy per
+ * GPU, held until the process ends.  Same arguments (minus workspace), same
+ * kernels, same results as mgrit_gru_forward.
+ *   - cfg->flags: 0 or MGRIT_ZERO_STATE_GUESS (MGRIT_E_UNSUPPORTED otherwise:
+ *     nothing is kept in or reused from this workspace across calls).
+ *   - MGRIT_E_WORKSPACE if mgrit_gru_workspace_bytes(cfg) exceeds
+ *     MGRIT_STATIC_SCRATCH_BYTES; checked before anything is launched.
+ *   - Calls no hipMalloc / hipFree / event or stream creation; with profiling
+ *     enabled its launches are not bracketed.
+ *   - Every call on a GPU uses that GPU's one array: calls that overlap on one
+ *     GPU (different streams or threads) race.  Everything the cycle reads from
+ *     the array it has written earlier in the same call. */
+#define MGRIT_STATIC_SCRATCH_BYTES (64u << 20)
+MGRIT_API int mgrit_gru_forward_static(const mgrit_gru_cfg* cfg, const void* W, const void* U,
+                      const float* b_i, const float* b_h, const void* x,
+                      const float* h0, float* h_inout, float* resnorm_out, void* stream);
+
 /* A second propagator behind the same forward cycle: the demonstration ODE of the
  * appendix "Why does MGRIT work?" (Eq. 17),
  *     dh/dt = -h/2 + sigmoid(A h + B d(t) + b),

@@ -41,6 +41,7 @@ MGRIT_KEEP_COEFFS = 2
 MGRIT_REUSE_COEFFS = 4
 MGRIT_ZERO_ADJOINT_GUESS = 8
 MGRIT_ZERO_STATE_GUESS = 16
+MGRIT_STATIC_SCRATCH_BYTES = 64 << 20     # workspace limit of mgrit_gru_forward_static
 MGRIT_E_STATE = -9
 _lib = None
 
@@ -65,6 +66,7 @@ def lib() -> ctypes.CDLL:
     L.mgrit_gru_workspace_bytes.argtypes = [cfgp, ctypes.POINTER(sz)]
     L.gru_serial_scan.argtypes = [cfgp, vp, vp, fp, fp, vp, fp, fp, vp, sz, vp]
     L.mgrit_gru_forward.argtypes = [cfgp, vp, vp, fp, fp, vp, fp, fp, fp, vp, sz, vp]
+    L.mgrit_gru_forward_static.argtypes = [cfgp, vp, vp, fp, fp, vp, fp, fp, fp, vp]
     L.gru_serial_scan_backward.argtypes = [cfgp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, fp, fp,
                                            vp, sz, vp]
     L.mgrit_gru_backward.argtypes = [cfgp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, fp, fp, fp,
@@ -89,6 +91,7 @@ def lib() -> ctypes.CDLL:
                                                ctypes.POINTER(ctypes.c_double),
                                                ctypes.POINTER(ctypes.c_double)]
     for name in ("mgrit_gru_workspace_bytes", "gru_serial_scan", "mgrit_gru_forward",
+                 "mgrit_gru_forward_static",
                  "gru_serial_scan_backward", "mgrit_gru_backward",
                  "gru_serial_scan_backward_steps", "mgrit_gru_backward_steps",
                  "ode_serial_scan", "mgrit_ode_forward", "mgrit_gru_profile_enable", "mgrit_gru_profile_read_shape",
@@ -218,6 +221,11 @@ def gru_serial_scan(cfg, W, U, b_i, b_h, x, h0, h_out, workspace) -> None:
 def mgrit_gru_forward(cfg, W, U, b_i, b_h, x, h0, h_inout, resnorm_out, workspace) -> None:
     _call("mgrit_gru_forward", cfg, *_params(cfg, W, U, b_i, b_h, x), _row(cfg, h0, "h0"),
           _state(cfg, h_inout, "h_inout"), _res(cfg, resnorm_out), *_workspace(workspace))
+
+
+def mgrit_gru_forward_static(cfg, W, U, b_i, b_h, x, h0, h_inout, resnorm_out) -> None:
+    _call("mgrit_gru_forward_static", cfg, *_params(cfg, W, U, b_i, b_h, x), _row(cfg, h0, "h0"),
+          _state(cfg, h_inout, "h_inout"), _res(cfg, resnorm_out))
 
 
 def gru_serial_scan_backward(cfg, W, U, b_i, b_h, x, h, dL_dhT, w_out, dW, dU, db_i, db_h,

@@ -10,9 +10,31 @@
 
 #include "common.h"
 
+// Workspace of mgrit_gru_forward_static: one array per GPU, held from the moment the library's
+// code object is loaded on that GPU until the process ends.  In host code this name is only a
+// handle for hipGetSymbolAddress; kernels and fills take the address that call returns.
+static __device__ __align__(256) unsigned char scratch[MGRIT_STATIC_SCRATCH_BYTES];
+
 namespace mg {
 
 constexpr int MAX_LEVELS = 24;
+constexpr int MAX_DEVICES = 64;
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[MAX_DEVICES] = {};   // [device]: address of `scratch` on that GPU
+
+// Address of the current device's copy of `scratch` (looked up once per device).
+static int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return MGRIT_E_LAUNCH;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return MGRIT_E_LAUNCH;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return MGRIT_OK;
+}
 
 // ---------------------------------------------------------------------------
 // profiling brackets
@@ -835,6 +857,26 @@ int mgrit_gru_forward(const mgrit_gru_cfg* cfg, const void* W, const void* U, co
                       float* resnorm_out, void* workspace, size_t workspace_bytes, void* stream) {
   return forward_impl(cfg, false, W, U, b_i, b_h, x, h0, h_inout, resnorm_out, workspace,
                       workspace_bytes, stream);
+}
+
+int mgrit_gru_forward_static(const mgrit_gru_cfg* cfg, const void* W, const void* U,
+                             const float* b_i, const float* b_h, const void* x, const float* h0,
+                             float* h_inout, float* resnorm_out, void* stream) {
+  // everything that can be refused is refused before the device is touched
+  int rc = check_cfg(cfg, true);
+  if (rc) return rc;
+  if (cfg->flags & ~MGRIT_ZERO_STATE_GUESS) return MGRIT_E_UNSUPPORTED;
+  Layout lay;
+  make_layout(cfg, &lay);
+  if (lay.total > (size_t)MGRIT_STATIC_SCRATCH_BYTES) return MGRIT_E_WORKSPACE;
+  if (!W || !U || !b_i || !b_h || !x || !h0 || !h_inout) return MGRIT_E_NULL;
+  void* ws = nullptr;
+  if ((rc = static_scratch(&ws))) return rc;
+  t_no_prof = true;       // event objects are runtime allocations: none in this call
+  rc = forward_impl(cfg, false, W, U, b_i, b_h, x, h0, h_inout, resnorm_out, ws,
+                    (size_t)MGRIT_STATIC_SCRATCH_BYTES, stream);
+  t_no_prof = false;
+  return rc;
 }
 
 int ode_serial_scan(const mgrit_gru_cfg* cfg, float dt, const float* A, const float* Bw,

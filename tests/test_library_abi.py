@@ -174,6 +174,27 @@ def test_reuse_flags_are_refused_on_a_workspace_the_library_has_no_record_of():
     assert "REUSE" in mg.mgrit_gru_strerror(mg.MGRIT_E_STATE)
 
 
+def test_static_workspace_entry_point_validates_on_the_host():
+    L = mg.lib()
+    p = 4096
+    ok = MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, iters=1)
+    assert L.mgrit_gru_forward_static(ctypes.byref(ok), None, p, p, p, p, p, p, None, None) == -1
+    assert L.mgrit_gru_forward_static(None, p, p, p, p, p, p, p, None, None) == -1
+    # a problem whose workspace exceeds the fixed array: refused with the workspace code
+    big = MgritGruCfg(2048, 32, 1024, 512, cf=4, levels=3, iters=2)
+    assert mg.mgrit_gru_workspace_bytes(big) > mg.MGRIT_STATIC_SCRATCH_BYTES
+    assert L.mgrit_gru_forward_static(ctypes.byref(big), p, p, p, p, p, p, p, None, None) == -5
+    # nothing is kept in or reused from the fixed array across calls
+    for flags in (mg.MGRIT_REUSE_PROJECTION, mg.MGRIT_KEEP_COEFFS):
+        c = MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, iters=1, flags=flags)
+        assert L.mgrit_gru_forward_static(ctypes.byref(c), p, p, p, p, p, p, p, None, None) == -8
+    bad = MgritGruCfg(60, 2, 16, 32, cf=4, levels=3, iters=1)
+    assert L.mgrit_gru_forward_static(ctypes.byref(bad), p, p, p, p, p, p, p, None, None) == -3
+    text = open(os.path.join(ROOT, "include", "mgrit_gru.h")).read()
+    m = re.search(r"#define MGRIT_STATIC_SCRATCH_BYTES \((\d+)u << (\d+)\)", text)
+    assert int(m.group(1)) << int(m.group(2)) == mg.MGRIT_STATIC_SCRATCH_BYTES
+
+
 def test_binding_rejects_tensors_whose_size_does_not_match_cfg():
     """The C ABI takes plain pointers; the binding compares every tensor's shape with cfg and
     raises before anything is launched (CPU tensors suffice to reach the shape checks)."""
@@ -212,3 +233,5 @@ def test_binding_rejects_tensors_whose_size_does_not_match_cfg():
         mg.gru_serial_scan_backward(cfg, *P, states, z(B, H), z(T, B, H), *g, ws)
     with pytest.raises(ValueError):
         mg.mgrit_ode_forward(cfg, 0.1, z(H, D), z(H, D), z(H), z(T, B, D), z(B, H), states, z(3), ws)
+    with pytest.raises(ValueError):
+        mg.mgrit_gru_forward_static(cfg, *P, z(B, H), z(T, B, H), z(3))

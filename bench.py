@@ -58,23 +58,36 @@ def parse():
                          "terms each on the bf16 matrix pipe (same inputs, same parity bar)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-serial", action="store_true")
+    ap.add_argument("--no-side-workloads", action="store_true",
+                    help="default run only: do not time C4 and C5 after the C3 headline")
+    ap.add_argument("--print-kernel-sources-hash", action="store_true",
+                    help="print the hash that stamps the counter records under profiles/ and exit")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="run one 1 GiB device-to-device copy first: the known-size kernel that "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     return ap.parse_args()
 
 
+def kernel_sources_sha256():
+    """Hash of the sources the forward step kernel is built from (stamps the counter records)."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2203_04738_amd", "csrc")
+    for f in ("common.h", "gates.h", "gemm_core.h", "gemm_core_bf16.h", "kernels_forward.hip"):
+        h.update(open(os.path.join(csrc, f), "rb").read())
+    return h.hexdigest()
+
+
 def cpu_baseline(wl, fwd_iters, bwd_iters, fcf=True):
-    """The CPU oracle as it stands, timed on the reduced twin of the workload
-    (same B, D, H, cf, levels; T = 8*cf^(levels-1)); work is linear in T."""
+    """The CPU oracle as it stands, single-threaded (BLAS pool limited to one thread), timed on a
+    reduced twin of the workload (same B, D, H, cf, levels; T a multiple of cf^(levels-1)); work is
+    linear in T.  The same sample with the BLAS pool at its default size is reported beside it."""
     import numpy as np
+    from threadpoolctl import threadpool_info, threadpool_limits
     from oracle import mgrit_gru_oracle as orc
     from synthetic_inputs import make_inputs
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        cores = os.cpu_count() or 1
+    all_threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+
     def run(tw):
         d = make_inputs(tw)
         P = (d["W"], d["U"], d["b_i"], d["b_h"])
@@ -90,19 +103,22 @@ def cpu_baseline(wl, fwd_iters, bwd_iters, fcf=True):
 
     unit = wl.cf ** (wl.levels - 1)
     n_max = wl.T // unit
-    n = min(8, n_max)
-    tw = wl.twin(n)
-    dt = run(tw)
-    if dt < 8.0 and n < n_max:
-        # enlarge the sample towards ~15 s of CPU work (never beyond the full workload)
-        n = int(min(n_max, max(n + 1, n * 15.0 / max(dt, 1e-3))))
+    with threadpool_limits(limits=1):
+        n = min(2, n_max)
         tw = wl.twin(n)
         dt = run(tw)
-    return {"value": tw.T * tw.B / dt, "unit": "time-steps*batch/s", "cores": int(cores),
-            "kind": "oracle",
-            "sample": f"reduced-T twin of {wl.name}: T={tw.T} (of {wl.T}), B={tw.B}, D={tw.D}, "
-                      f"H={tw.H}, cf={tw.cf}, levels={tw.levels}, {fwd_iters} fwd + {bwd_iters} "
-                      f"bwd cycles, numpy float64, {dt:.1f} s"}
+        if dt < 8.0 and n < n_max:
+            # enlarge the sample towards ~15 s of CPU work (never beyond the full workload)
+            n = int(min(n_max, max(n + 1, n * 15.0 / max(dt, 1e-3))))
+            tw = wl.twin(n)
+            dt = run(tw)
+    dt_all = run(tw)
+    sample = (f"reduced-T twin of {wl.name}: T={tw.T} (of {wl.T}), B={tw.B}, D={tw.D}, H={tw.H}, "
+              f"cf={tw.cf}, levels={tw.levels}, {fwd_iters} fwd + {bwd_iters} bwd cycles, numpy float64")
+    return {"value": tw.T * tw.B / dt, "unit": "time-steps*batch/s", "cores": 1, "kind": "oracle",
+            "sample": sample + f", {dt:.1f} s",
+            "all_threads": {"value": tw.T * tw.B / dt_all, "cores": int(all_threads),
+                            "seconds": dt_all}}
 
 
 def stack_cpu_baseline(wl, layers, fwd_iters, bwd_iters, fcf=True):
@@ -626,6 +642,9 @@ def study_training(args):
 
 def main():
     args = parse()
+    if args.print_kernel_sources_hash:
+        print(kernel_sources_sha256())
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
               "use --gpus 1", file=sys.stderr)
@@ -638,6 +657,40 @@ def main():
         return study_ode(args)
     if args.layers > 1:
         return stack_main(args)
+    out = run_workload(args)
+    if (args.workload == "C3" and args.operands == "stored" and not args.until_converged
+            and not args.no_side_workloads and args.fwd_iters is None and args.bwd_iters is None):
+        # the other two workloads the report covers, in the same run: the image-sequence-shaped
+        # long input (C4: bf16 inputs and weights, fp32 state) and the stress configuration (C5)
+        out["workloads"] = {}
+        for name in ("C4", "C5"):
+            a = argparse.Namespace(**vars(args))
+            a.workload = name
+            a.steps, a.warmup = max(2, min(args.steps, 5)), max(1, min(args.warmup, 2))
+            r = run_workload(a, light=True)
+            rf = r["roofline"] or {}
+            out["workloads"][name] = {
+                "config": r["config"]["workload"], "dtype": r["dtype"], "steps": a.steps,
+                "ms_per_step": r["ms_per_step"], "value": r["value"], "unit": r["unit"],
+                "residual_fwd": r["residual_fwd"], "residual_bwd": r["residual_bwd"],
+                "serial_gpu_ms_per_step": r["serial_gpu"]["ms_per_step"],
+                "serial_gpu_value": r["serial_gpu"]["value"],
+                "speedup_over_serial_scan": r["serial_gpu"]["mgrit_speedup"],
+                "level0_step": {"bound": rf.get("bound"), "avg_launch_us": rf.get("avg_launch_us"),
+                                "achieved": rf.get("achieved"), "peak": rf.get("peak"),
+                                "unit": rf.get("unit"), "frac": rf.get("frac"),
+                                "launches_per_step": rf.get("launches_per_step")},
+                "few_row_steps": {k.split(" ")[0]: {"launches_per_step": v["launches_per_step"],
+                                                    "avg_launch_us": v["avg_launch_us"],
+                                                    "ms_per_step": v["ms_per_step"]}
+                                  for k, v in r["kernels"].items() if "skinny" in k},
+                "whole_step_frac_of_mfma_peak": r["whole_step"]["frac_of_mfma_peak"]}
+    print(json.dumps(out))
+
+
+def run_workload(args, light=False):
+    """Times one workload (MGRIT step, per-kernel event times, serial scan on the same GPU) and
+    returns the record.  light: no second operand form, no undeclared-guess timing, no CPU leg."""
     import numpy as np
     import torch
 
@@ -704,7 +757,7 @@ def main():
                                       else "cycle limit N_1/2")}
         del ws0, hs, hh
 
-    other = 2 if (wl.dtype == "fp32" and not x3) else None   # the form timed beside the main one
+    other = 2 if (wl.dtype == "fp32" and not x3 and not light) else None   # the form timed beside the main one
     ws = torch.empty(max(mg.mgrit_gru_workspace_bytes(cfg(max(fwd_iters, bwd_iters, 1), dtype=dt))
                          for dt in (None, other)), dtype=torch.uint8, device=dev)
     h = torch.zeros(T + 1, B, H, device=dev)
@@ -815,21 +868,30 @@ def main():
         dom = {"launches_per_step": dn / args.steps, "avg_launch_us": 1e3 * dms / dn,
                "TFLOPs": dfl / dms / 1e9, "flops_per_launch": dfl / dn, "bytes_per_launch": dby / dn}
     peak = MI355X_PEAK["fp32_TFLOPs"] if dtype_code == 0 else MI355X_PEAK["bf16_TFLOPs"]
-    # HBM traffic of the dominant kernel per launch: measured offline with rocprofv3 --pmc
-    # (FETCH_SIZE, WRITE_SIZE; scaled by a copy kernel of known size) and recorded in profiles/
-    traffic = None
+    # HBM traffic of the dominant kernel per launch: measured with rocprofv3 --pmc (FETCH_SIZE,
+    # WRITE_SIZE; scaled by a copy kernel of known size) and recorded in profiles/ together with
+    # a hash of the kernel's sources; a record made for other sources is not reported
+    traffic, traffic_note = None, "not measured for this workload / operand form"
     tf = os.path.join(ROOT, "profiles", f"phi_step_{wl.name}_hbm_traffic.txt")
     if os.path.exists(tf) and not x3:
+        rec = {}
         for line in open(tf):
-            if line.startswith("traffic_bytes_per_launch"):
-                traffic = int(line.split("=")[1].split("#")[0])
+            if "=" in line and not line.startswith("#"):
+                k, v = line.split("=", 1)
+                rec[k.strip()] = v.split("#")[0].strip()
+        if rec.get("kernel_sources_sha256") == kernel_sources_sha256():
+            traffic = int(rec["traffic_bytes_per_launch"])
+            traffic_note = ("bytes per launch at this launch shape, rocprofv3 counters "
+                            "(profiles/phi_step_%s_hbm_traffic.txt, same kernel sources)" % wl.name)
+        else:
+            traffic_note = ("profiles/phi_step_%s_hbm_traffic.txt was measured on other kernel "
+                            "sources: not reported" % wl.name)
     roofline = None
     if dom:
         roofline = {"kernel": names[0] + f", level-0 relaxation launches ({dom_rows} rows x H={H})",
                     "bound": "mfma", "achieved": dom["TFLOPs"], "peak": peak,
                     "unit": "TFLOP/s", "frac": dom["TFLOPs"] / peak, "traffic": traffic,
-                    "traffic_unit": "bytes per launch at this launch shape "
-                                    "(profiles/phi_step_%s_hbm_traffic.txt)" % wl.name,
+                    "traffic_unit": traffic_note,
                     "algorithmic_flops_per_launch": dom["flops_per_launch"],
                     "algorithmic_bytes_per_launch": dom["bytes_per_launch"],
                     "avg_launch_us": dom["avg_launch_us"],
@@ -845,7 +907,7 @@ def main():
     # the same step without declaring the zero initial guesses: every pass of the first cycles
     # then runs over all rows, those that only produce (or only read) zeros included
     undeclared = None
-    if bwd_iters > 0:
+    if bwd_iters > 0 and not light:
         usec = timed(lambda: mgrit_step(declare_zero_guess=False), args.steps, 1)
         undeclared = {"what": "same step without MGRIT_ZERO_STATE_GUESS / MGRIT_ZERO_ADJOINT_GUESS (the first "
                               "cycles also run the contractions whose result is exactly zero)",
@@ -927,9 +989,11 @@ def main():
         other_form["mgrit_speedup_vs_serial"] = (serial["ms_per_step"] / other_form["ms_per_step"]
                                                  if serial else None)
         out["bf16x3_operands"] = other_form
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not light:
         out["cpu_baseline"] = cpu_baseline(wl, fwd_iters, bwd_iters, fcf=bool(fine_relax))
-    print(json.dumps(out))
+    del ws, h, w, t, Wp
+    torch.cuda.empty_cache()
+    return out
 
 
 if __name__ == "__main__":

@@ -518,103 +518,32 @@ def study_training(args):
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    T, B, D, H, C, L = 128, 100, 12, 100, 6, 2
+    from paper_2203_04738_amd.training import GruStackTrainer
+    from synthetic_inputs import ClassificationTask, init_stack
+    task = ClassificationTask()                       # T = 128, B = 100, 9 channels, 6 classes
+    T, B, D, C, H, L = task.T, task.B, task.D, task.classes, 100, 2
     cf, levels = 4, 3
     fwd_iters = 2 if args.fwd_iters is None else args.fwd_iters
     bwd_iters = 1 if args.bwd_iters is None else max(1, args.bwd_iters)
-    rng = np.random.default_rng(0)
-    readout = rng.standard_normal((C, 9)).astype(np.float32)
-    decay = (0.97 ** np.arange(T - 1, -1, -1)).astype(np.float32)        # weight of step t
 
-    def batch(seed):
-        r = np.random.default_rng(1000 + seed)
-        x = np.zeros((T, B, D), dtype=np.float32)
-        x[:, :, :9] = r.standard_normal((T, B, 9))
-        score = np.einsum("t,tbd,cd->bc", decay, x[:, :, :9], readout)
-        return torch.from_numpy(x).to(dev), torch.from_numpy(np.argmax(score, axis=1)).to(dev)
+    def batch(index):
+        x, y = task.batch(index)
+        return torch.from_numpy(x).to(dev), torch.from_numpy(y).to(dev)
 
-    def init_params():
-        r = np.random.default_rng(7)
-        ps = []
-        for j in range(L):
-            Dj = D if j == 0 else H
-            bw, bu = np.sqrt(6.0 / (Dj + H)), np.sqrt(6.0 / (2 * H))
-            ps.append([torch.from_numpy(r.uniform(-bw, bw, (3 * H, Dj)).astype(np.float32)).to(dev),
-                       torch.from_numpy(r.uniform(-bu, bu, (3 * H, H)).astype(np.float32)).to(dev),
-                       torch.zeros(3 * H, device=dev), torch.zeros(3 * H, device=dev)])
-        bo = np.sqrt(6.0 / (H + C))
-        head = [torch.from_numpy(r.uniform(-bo, bo, (C, H)).astype(np.float32)).to(dev),
-                torch.zeros(C, device=dev)]
-        return ps, head
-
-    def cfg(Dj, iters, flags=0):
-        return MgritGruCfg(T, B, Dj, H, cf=cf, levels=levels, iters=iters, fine_relax=1,
-                           propagator=0, dtype=0, flags=flags)
-
-    dims = [D] + [H] * (L - 1)
-    wss = [torch.empty(mg.mgrit_gru_workspace_bytes(cfg(Dj, max(fwd_iters, bwd_iters))),
-                       dtype=torch.uint8, device=dev) for Dj in dims]
-    hs = [torch.zeros(T + 1, B, H, device=dev) for _ in range(L)]
-    ws_ = [torch.zeros(T + 1, B, H, device=dev) for _ in range(L)]
-    srcs = [torch.zeros(T + 1, B, H, device=dev) for _ in range(L)]
-    h0 = torch.zeros(B, H, device=dev)
-
-    def forward(ps, x, parallel):
-        for j in range(L):
-            xin = x if j == 0 else hs[j - 1][1:]
-            if parallel:
-                hs[j].zero_()
-                mg.mgrit_gru_forward(cfg(dims[j], fwd_iters), *ps[j], xin, h0, hs[j], None, wss[j])
-            else:
-                mg.gru_serial_scan(cfg(dims[j], 1), *ps[j], xin, h0, hs[j], wss[j])
-        return hs[-1][T]
-
-    def backward(ps, x, g_top, grads, parallel):
-        srcs[-1].zero_()
-        srcs[-1][T] = g_top
-        for j in range(L - 1, -1, -1):
-            xin = x if j == 0 else hs[j - 1][1:]
-            dx = srcs[j - 1][1:] if j > 0 else None
-            if j > 0:
-                srcs[j - 1][0].zero_()
-            if parallel:
-                ws_[j].zero_()
-                mg.mgrit_gru_backward_steps(cfg(dims[j], bwd_iters, MGRIT_REUSE_PROJECTION), *ps[j],
-                                            xin, hs[j], srcs[j], ws_[j], None, *grads[j], dx, wss[j])
-            else:
-                mg.gru_serial_scan_backward_steps(cfg(dims[j], 1, MGRIT_REUSE_PROJECTION), *ps[j],
-                                                  xin, hs[j], srcs[j], ws_[j], *grads[j], dx, wss[j])
-
-    def accuracy(ps, head, parallel, seeds):
+    def accuracy(tr, parallel, seeds):
         hit = 0
         for sd in seeds:
             x, y = batch(sd)
-            hT = forward(ps, x, parallel)
-            hit += int((torch.argmax(hT @ head[0].T + head[1], dim=1) == y).sum())
+            hit += int((tr.predict(x, parallel) == y).sum())
         return hit / (len(seeds) * B)
 
     def train(parallel):
-        ps, head = init_params()
-        flat = [p for lp in ps for p in lp] + head
-        grads = [[torch.zeros_like(p) for p in lp] for lp in ps]
-        opt = torch.optim.Adam(flat, lr=1e-3)
-        losses = []
-        for step in range(args.train_steps):
-            x, y = batch(step)
-            hT = forward(ps, x, parallel).clone().requires_grad_(True)
-            Wo, bo = head[0].requires_grad_(True), head[1].requires_grad_(True)
-            loss = torch.nn.functional.cross_entropy(hT @ Wo.T + bo, y)
-            gh, gW, gb = torch.autograd.grad(loss, (hT, Wo, bo))
-            head[0].requires_grad_(False)
-            head[1].requires_grad_(False)
-            backward(ps, x, gh, grads, parallel)
-            for lp, lg in zip(ps, grads):
-                for p_, g_ in zip(lp, lg):
-                    p_.grad = g_
-            head[0].grad, head[1].grad = gW, gb
-            opt.step()
-            losses.append(float(loss.detach()))
-        return ps, head, losses
+        params, head = init_stack(7, D, H, C, L)
+        tr = GruStackTrainer(T, B, [[torch.from_numpy(q).to(dev) for q in p] for p in params],
+                             [torch.from_numpy(q).to(dev) for q in head], cf=cf, levels=levels,
+                             fwd_iters=fwd_iters, bwd_iters=bwd_iters, lr=1e-3, parallel=parallel)
+        losses = [tr.step(*batch(step)) for step in range(args.train_steps)]
+        return tr, losses
 
     test_seeds = list(range(100000, 100010))
     out = {"study": "training",
@@ -624,7 +553,7 @@ def study_training(args):
            "runs": {}}
     for name, parallel in (("serial", False), ("mgrit", True)):
         t0 = time.perf_counter()
-        ps, head, losses = train(parallel)
+        tr, losses = train(parallel)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         k = max(1, args.train_steps // 10)
@@ -632,10 +561,10 @@ def study_training(args):
                "loss_last_%d" % k: float(np.mean(losses[-k:])),
                "loss_every_%d" % k: [float(np.mean(losses[i:i + k]))
                                      for i in range(0, args.train_steps, k)],
-               "test_accuracy_serial_inference": accuracy(ps, head, False, test_seeds),
+               "test_accuracy_serial_inference": accuracy(tr, False, test_seeds),
                "seconds": dt}
         if parallel:
-            run["test_accuracy_mgrit_inference"] = accuracy(ps, head, True, test_seeds)
+            run["test_accuracy_mgrit_inference"] = accuracy(tr, True, test_seeds)
         out["runs"][name] = run
     print(json.dumps(out))
 

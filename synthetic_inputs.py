@@ -175,3 +175,48 @@ def random_ode(seed: int, T: int, B: int, D: int, H: int, scale: Optional[float]
         "h0": (rng.standard_normal((B, H)) if h0_random else np.zeros((B, H))),
     }
     return {k: np.ascontiguousarray(v, dtype=np.float32) for k, v in out.items()}
+
+
+# ---------------------------------------------------------------------------
+# Synthetic classification task for the training loop (Alg. 3 of the paper)
+# ---------------------------------------------------------------------------
+# Stands in for the UCI-HAR traces (128 steps x 9 channels, 6 classes), which are not
+# available here: the label of a sequence is a fixed function of its inputs, so a GRU can
+# learn it.  Inputs and labels only; none of the method's arithmetic.
+
+@dataclass(frozen=True)
+class ClassificationTask:
+    T: int = 128
+    B: int = 100
+    D: int = 12            # input width seen by the GRU (channels padded with zeros)
+    channels: int = 9
+    classes: int = 6
+    seed: int = 0
+
+    def readout(self) -> np.ndarray:
+        return np.random.default_rng(self.seed).standard_normal(
+            (self.classes, self.channels)).astype(np.float32)
+
+    def batch(self, index: int):
+        """Batch `index`: x[T,B,D] float32 ~ N(0,1) in the first `channels` columns, labels[B] =
+        argmax_c sum_t 0.97^(T-t) <readout_c, x_t> (recent steps weigh more)."""
+        r = np.random.default_rng(1000 + index)
+        x = np.zeros((self.T, self.B, self.D), dtype=np.float32)
+        x[:, :, :self.channels] = r.standard_normal((self.T, self.B, self.channels))
+        decay = (0.97 ** np.arange(self.T - 1, -1, -1)).astype(np.float32)
+        score = np.einsum("t,tbd,cd->bc", decay, x[:, :, :self.channels], self.readout())
+        return x, np.argmax(score, axis=1).astype(np.int64)
+
+
+def init_stack(seed: int, D: int, H: int, classes: int, layers: int):
+    """Xavier-uniform parameters of a stack of GRU layers and a linear head, zero biases.
+    Returns (params, head): params[j] = [W, U, b_i, b_h] (layer 0 reads D features, the others
+    H), head = [W_o[classes,H], b_o[classes]]; all float32."""
+    r = np.random.default_rng(seed)
+    params = []
+    for j in range(layers):
+        Dj = D if j == 0 else H
+        params.append([_xavier(r, H, Dj, 3).astype(np.float32), _xavier(r, H, H, 3).astype(np.float32),
+                       np.zeros(3 * H, dtype=np.float32), np.zeros(3 * H, dtype=np.float32)])
+    head = [_xavier(r, classes, H, 1).astype(np.float32), np.zeros(classes, dtype=np.float32)]
+    return params, head

@@ -220,3 +220,32 @@ def init_stack(seed: int, D: int, H: int, classes: int, layers: int):
                        np.zeros(3 * H, dtype=np.float32), np.zeros(3 * H, dtype=np.float32)])
     head = [_xavier(r, classes, H, 1).astype(np.float32), np.zeros(classes, dtype=np.float32)]
     return params, head
+
+
+def random_lstm(seed: int, T: int, B: int, D: int, H: int, scale: float = 0.5,
+                u0_random: bool = True) -> Dict[str, np.ndarray]:
+    """Small dense random LSTM problem: x[T,B,D], W[4H,D], U[4H,H], b_i[4H], b_h[4H] (gate order
+    i, f, g, o) and the initial state pair u0[B,2H] = (h_0 | c_0)."""
+    rng = np.random.default_rng(seed)
+    d = {
+        "x": rng.standard_normal((T, B, D)),
+        "W": scale * rng.standard_normal((4 * H, D)),
+        "U": scale * rng.standard_normal((4 * H, H)),
+        "b_i": scale * rng.standard_normal(4 * H),
+        "b_h": scale * rng.standard_normal(4 * H),
+        "u0": (0.5 * rng.standard_normal((B, 2 * H)) if u0_random else np.zeros((B, 2 * H))),
+    }
+    return {k: np.ascontiguousarray(v, dtype=np.float32) for k, v in d.items()}
+
+
+def make_lstm_inputs(wl: Workload, seed: Optional[int] = None) -> Dict[str, np.ndarray]:
+    """LSTM inputs at the sizes of a workload: x as in make_inputs, Xavier-uniform weights per
+    gate matrix (four gates), zero biases, zero initial state pair."""
+    rng = np.random.default_rng(wl.seed if seed is None else seed)
+    T, B, D, H = wl.T, wl.B, wl.D, wl.H
+    x = rng.standard_normal((T, B, D))
+    if wl.x_dist == "relu_normal":
+        x = np.maximum(x, 0.0)
+    out = {"x": x, "W": _xavier(rng, H, D, 4), "U": _xavier(rng, H, H, 4),
+           "b_i": np.zeros(4 * H), "b_h": np.zeros(4 * H), "u0": np.zeros((B, 2 * H))}
+    return {k: np.ascontiguousarray(v, dtype=np.float32) for k, v in out.items()}

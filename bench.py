@@ -43,14 +43,15 @@ def parse():
     ap.add_argument("--layers", type=int, default=1,
                     help="2: a stack of two GRU layers (layer 2 reads the states of layer 1; "
                          "fp32 workloads only), each solved by its own MGRIT solve")
-    ap.add_argument("--study", choices=["convergence", "training", "ode"], default=None,
+    ap.add_argument("--study", choices=["convergence", "training", "ode", "lstm"], default=None,
                     help="convergence: residual per cycle, forward and backward, for the paper's "
                          "hierarchies at T = 128 (cf 2 / 4 / 8 with 6 / 3 / 2 levels) and for the "
                          "Classic coarse propagator.  training: the training loop of Alg. 3 with Adam "
                          "on a synthetic classification task, MGRIT (2 forward / 1 backward cycles) "
                          "against serial propagation from the same start.  ode: the appendix's "
                          "demonstration ODE (Eq. 17) as the propagator of the forward cycle, at the "
-                         "sizes of --workload, against its serial propagation.  One JSON line each")
+                         "sizes of --workload, against its serial propagation.  lstm: the same for the LSTM "
+                         "step.  One JSON line each")
     ap.add_argument("--train-steps", type=int, default=300)
     ap.add_argument("--operands", choices=["stored", "bf16x3"], default="stored",
                     help="stored: the workload's own form (fp32 or bf16 MFMA).  bf16x3 (fp32 "
@@ -500,6 +501,134 @@ def study_ode(args):
     print(json.dumps(out))
 
 
+def study_lstm(args):
+    """Forward MGRIT with the LSTM step (implicit in the decay terms) as propagator, at the sizes
+    and hierarchy of --workload, against serial propagation on the same GPU.  A step is one
+    forward solve (projection included) over one batch of synthetic data."""
+    import numpy as np
+    import torch
+
+    import paper_2203_04738_amd as mg
+    from paper_2203_04738_amd.binding import MgritGruCfg
+    from synthetic_inputs import WORKLOADS, make_lstm_inputs
+
+    wl = WORKLOADS[args.workload]
+    if wl.dtype != "fp32":
+        print("bench.py: --study lstm runs fp32 workloads", file=sys.stderr)
+        sys.exit(2)
+    T, B, D, H = wl.T, wl.B, wl.D, wl.H
+    iters = wl.fwd_iters if args.fwd_iters is None else args.fwd_iters
+    fine_relax = 1 if args.fine_relax == "FCF" else 0
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    d = make_lstm_inputs(wl)
+    t = {k: torch.from_numpy(v).to(dev) for k, v in d.items()}
+    P = (t["W"], t["U"], t["b_i"], t["b_h"], t["x"], t["u0"])
+
+    def cfg(n):
+        return MgritGruCfg(T, B, D, H, cf=wl.cf, levels=wl.levels, iters=n, fine_relax=fine_relax)
+
+    ws = torch.empty(mg.mgrit_lstm_workspace_bytes(cfg(max(iters, 1))), dtype=torch.uint8,
+                     device=dev)
+    u = torch.zeros(T + 1, B, 2 * H, device=dev)
+    us = torch.zeros(T + 1, B, 2 * H, device=dev)
+    res = torch.zeros(max(iters, 1), device=dev)
+
+    def mgrit_step():
+        u[1:].zero_()
+        mg.mgrit_lstm_forward(cfg(iters), *P, u, res, ws)
+
+    def serial_step():
+        mg.lstm_serial_scan(cfg(1), *P, us, ws)
+
+    def timed(fn, warmup, steps):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    sec = timed(mgrit_step, args.warmup, args.steps)
+    residuals = res.cpu().tolist()
+    ssec = None if args.no_serial else timed(serial_step, 1, max(2, args.steps // 3))
+    err = None
+    if ssec is not None:
+        err = float(torch.max(torch.abs(u - us)) / torch.max(torch.abs(us)))
+
+    rows0 = (T // wl.cf) * B
+    mg.mgrit_gru_profile_enable(True)
+    for _ in range(args.steps):
+        mgrit_step()
+    torch.cuda.synchronize()
+    mg.mgrit_gru_profile_enable(False)
+    n0, ms0, fl0, _ = mg.mgrit_gru_profile_read_shape(9, rows0, 0)
+    nall, msall, flall, _ = mg.mgrit_gru_profile_read(9)
+    npj, mspj, flpj, _ = mg.mgrit_gru_profile_read(2)
+    roof = None
+    if n0:
+        ach = fl0 / ms0 / 1e9
+        roof = {"kernel": f"lstm_step (fused LSTM level step, MFMA tiles), level-0 relaxation "
+                          f"launches ({rows0} rows x H={H})",
+                "bound": "mfma", "achieved": ach, "peak": MI355X_PEAK["fp32_TFLOPs"],
+                "unit": "TFLOP/s", "frac": ach / MI355X_PEAK["fp32_TFLOPs"], "traffic": None,
+                "algorithmic_flops_per_launch": fl0 / n0, "avg_launch_us": 1e3 * ms0 / n0,
+                "launches_per_step": n0 / args.steps}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from threadpoolctl import threadpool_limits
+        from oracle import lstm_oracle as lo
+        unit = wl.cf ** (wl.levels - 1)
+
+        def run(n):
+            q = make_lstm_inputs(wl.twin(n))
+            t0 = time.perf_counter()
+            lo.mgrit_lstm_forward(q["W"], q["U"], q["b_i"], q["b_h"], q["x"], q["u0"],
+                                  np.zeros((n * unit + 1, B, 2 * H)), wl.cf, wl.levels, iters,
+                                  fine_relax_fcf=bool(fine_relax))
+            return time.perf_counter() - t0
+
+        with threadpool_limits(limits=1):
+            n, n_max = min(2, T // unit), T // unit
+            el = run(n)
+            if el < 8.0 and n < n_max:     # enlarge the sample towards ~15 s of CPU work
+                n = int(min(n_max, max(n + 1, n * 15.0 / max(el, 1e-3))))
+                el = run(n)
+        cpu = {"value": n * unit * B / el, "unit": "time-steps*batch/s", "cores": 1,
+               "kind": "oracle",
+               "sample": f"T={n * unit} (of {T}), B={B}, D={D}, H={H}, cf={wl.cf}, "
+                         f"levels={wl.levels}, {iters} cycles, numpy float64, {el:.1f} s"}
+
+    out = {"study": "lstm",
+           "metric": "time-steps*batch/sec, MGRIT forward propagation of an LSTM layer vs serial "
+                     "propagation (1 GPU); % roofline",
+           "value": T * B / sec, "unit": "time-steps*batch/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": 1e3 * sec, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"LSTM layer, step implicit in the decay terms, sizes of "
+                                  f"{wl.name}: T={T} B={B} D={D} H={H} cf={wl.cf} "
+                                  f"levels={wl.levels} cycles={iters} fine-level "
+                                  f"{args.fine_relax} relaxation, zero initial guess",
+                      "seed": wl.seed},
+           "residual_fwd": residuals,
+           "max_rel_difference_from_serial_propagation": err,
+           "roofline": roof,
+           "lstm_step_all_launches": ({"launches_per_step": nall / args.steps,
+                                       "ms_per_step": msall / args.steps,
+                                       "TFLOPs": flall / msall / 1e9} if nall else None),
+           "projection": ({"ms_per_step": mspj / args.steps, "TFLOPs": flpj / mspj / 1e9}
+                          if npj else None),
+           "serial_gpu": (None if ssec is None else
+                          {"value": T * B / ssec, "unit": "time-steps*batch/s",
+                           "ms_per_step": 1e3 * ssec, "what": "lstm_serial_scan on the same GPU",
+                           "mgrit_speedup": ssec / sec}),
+           "cpu_baseline": cpu}
+    print(json.dumps(out))
+
+
 def study_training(args):
     """Alg. 3 as a training loop: a two-layer Implicit GRU with a linear head, trained
     with Adam (lr 1e-3, Sec. 3.4) on a synthetic sequence-classification task of the
@@ -584,6 +713,8 @@ def main():
         return study_training(args)
     if args.study == "ode":
         return study_ode(args)
+    if args.study == "lstm":
+        return study_lstm(args)
     if args.layers > 1:
         return stack_main(args)
     out = run_workload(args)

@@ -284,6 +284,36 @@ MGRIT_API int mgrit_ode_forward(const mgrit_gru_cfg* cfg, float dt, const float*
                       const float* h0, float* h_inout, float* resnorm_out,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* A third propagator behind the same forward cycle: an LSTM layer, the extension the
+ * paper's conclusion names.  The paper gives no equations for it; the step here is derived
+ * the way Sec. 3.3 derives the Implicit GRU.  With the gates i, f, o = sigmoid(.), g = tanh(.)
+ * of W x_t + b_i + U h_{t-1} + b_h (stacked in the order i, f, g, o), the standard cell
+ * c_t = f c_{t-1} + i g, h_t = o tanh(c_t) is a forward-Euler step of size 1 of
+ *     dc/dt = -(1 - f) c + i g,      dh/dt = -h + o tanh(c),
+ * and a level step of size gamma is, with the decay terms taken implicitly
+ * (cfg->propagator = MGRIT_PROP_IMPLICIT),
+ *     c' = (c + gamma i g) / (1 + gamma (1 - f)),    h' = (h + gamma o tanh(c')) / (1 + gamma),
+ * or explicitly (MGRIT_PROP_CLASSIC; gamma = 1 is the standard LSTM cell)
+ *     c' = c + gamma (-(1 - f) c + i g),             h' = h + gamma (-h + o tanh(c')).
+ * Level l uses gamma = cf^l and the inputs of its own points (Sec. 3.1, 3.3).  Forward
+ * propagation only.
+ *   cfg: as for the GRU entry points, H = hidden width; dtype must be MGRIT_F32 and flags 0
+ *     (MGRIT_E_UNSUPPORTED otherwise).
+ *   W[4H,D], U[4H,H], b_i[4H], b_h[4H], x[T,B,D]: device, float.
+ *   The state of the time integration is the pair (h, c): u0[B,2H] and the rows of
+ *   u_out / u_inout[(T+1),B,2H] hold h in columns 0..H-1 and c in columns H..2H-1.
+ *   resnorm_out[iters]: 2-norm of the level-0 residual over both halves, as in mgrit_gru_forward.
+ *   workspace: mgrit_lstm_workspace_bytes(cfg) bytes (host-only computation). */
+MGRIT_API int mgrit_lstm_workspace_bytes(const mgrit_gru_cfg* cfg, size_t* bytes);
+MGRIT_API int lstm_serial_scan(const mgrit_gru_cfg* cfg, const float* W, const float* U,
+                    const float* b_i, const float* b_h, const float* x,
+                    const float* u0, float* u_out,
+                    void* workspace, size_t workspace_bytes, void* stream);
+MGRIT_API int mgrit_lstm_forward(const mgrit_gru_cfg* cfg, const float* W, const float* U,
+                      const float* b_i, const float* b_h, const float* x,
+                      const float* u0, float* u_inout, float* resnorm_out,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
 /* Name of an error code (host string with static storage). */
 MGRIT_API const char* mgrit_gru_strerror(int code);
 
@@ -300,12 +330,13 @@ MGRIT_API const char* mgrit_gru_strerror(int code);
  *         2 = projection GEMM, 3 = weight-gradient GEMMs, 4 / 5 = forward / adjoint step
  *         in the few-row form used by the serial scan and the coarsest-level solve,
  *         6 = input-gradient GEMM, 7 = point copies (coarse-grid correction, terminal and
- *         initial conditions), 8 = step of the demonstration ODE (tile and few-row forms).
+ *         initial conditions), 8 = step of the demonstration ODE (tile and few-row forms),
+ *         9 = LSTM step (tile and few-row forms).
  * All out-pointers are host pointers. */
 MGRIT_API int mgrit_gru_profile_enable(int on);
 MGRIT_API int mgrit_gru_profile_read(int kind, int64_t* launches, double* ms,
                            double* flops, double* bytes);
-/* The same for one launch shape of a step kernel class (kind 0, 1, 4, 5, 8): only the
+/* The same for one launch shape of a step kernel class (kind 0, 1, 4, 5, 8, 9): only the
  * launches that advance `rows` rows (level points x batch) in epilogue mode `mode`
  * (0 = relaxation update, 1 = residual + restriction, 2 = coarse right-hand side,
  * 3 = coefficients, 4 = relaxation update that keeps the coefficients, 5 = relaxation

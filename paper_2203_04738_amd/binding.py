@@ -78,6 +78,9 @@ def lib() -> ctypes.CDLL:
     cf = ctypes.c_float
     L.ode_serial_scan.argtypes = [cfgp, cf, fp, fp, fp, fp, fp, fp, vp, sz, vp]
     L.mgrit_ode_forward.argtypes = [cfgp, cf, fp, fp, fp, fp, fp, fp, fp, vp, sz, vp]
+    L.mgrit_lstm_workspace_bytes.argtypes = [cfgp, ctypes.POINTER(sz)]
+    L.lstm_serial_scan.argtypes = [cfgp, fp, fp, fp, fp, fp, fp, fp, vp, sz, vp]
+    L.mgrit_lstm_forward.argtypes = [cfgp, fp, fp, fp, fp, fp, fp, fp, fp, vp, sz, vp]
     L.mgrit_gru_strerror.argtypes = [ctypes.c_int]
     L.mgrit_gru_strerror.restype = ctypes.c_char_p
     L.mgrit_gru_profile_enable.argtypes = [ctypes.c_int]
@@ -94,7 +97,8 @@ def lib() -> ctypes.CDLL:
                  "mgrit_gru_forward_static",
                  "gru_serial_scan_backward", "mgrit_gru_backward",
                  "gru_serial_scan_backward_steps", "mgrit_gru_backward_steps",
-                 "ode_serial_scan", "mgrit_ode_forward", "mgrit_gru_profile_enable", "mgrit_gru_profile_read_shape",
+                 "ode_serial_scan", "mgrit_ode_forward", "mgrit_lstm_workspace_bytes",
+                 "lstm_serial_scan", "mgrit_lstm_forward", "mgrit_gru_profile_enable", "mgrit_gru_profile_read_shape",
                  "mgrit_gru_profile_read"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
@@ -271,6 +275,36 @@ def ode_serial_scan(cfg, dt, A, Bw, b, d, h0, h_out, workspace) -> None:
 def mgrit_ode_forward(cfg, dt, A, Bw, b, d, h0, h_inout, resnorm_out, workspace) -> None:
     _call("mgrit_ode_forward", cfg, *_ode_params(cfg, dt, A, Bw, b, d), _row(cfg, h0, "h0"),
           _state(cfg, h_inout, "h_inout"), _res(cfg, resnorm_out), *_workspace(workspace))
+
+
+def mgrit_lstm_workspace_bytes(cfg: MgritGruCfg) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().mgrit_lstm_workspace_bytes(ctypes.byref(cfg), ctypes.byref(n)),
+           "mgrit_lstm_workspace_bytes")
+    return int(n.value)
+
+
+def _lstm_params(cfg, W, U, b_i, b_h, x):
+    f32 = _f32()
+    T, B, D, H = cfg.T, cfg.B, cfg.D, cfg.H
+    return (_Arg(W, "W", f32, (4 * H, D)), _Arg(U, "U", f32, (4 * H, H)),
+            _Arg(b_i, "b_i", f32, (4 * H,)), _Arg(b_h, "b_h", f32, (4 * H,)),
+            _Arg(x, "x", f32, (T, B, D)))
+
+
+def lstm_serial_scan(cfg, W, U, b_i, b_h, x, u0, u_out, workspace) -> None:
+    f32 = _f32()
+    _call("lstm_serial_scan", cfg, *_lstm_params(cfg, W, U, b_i, b_h, x),
+          _Arg(u0, "u0", f32, (cfg.B, 2 * cfg.H)),
+          _Arg(u_out, "u_out", f32, (cfg.T + 1, cfg.B, 2 * cfg.H)), *_workspace(workspace))
+
+
+def mgrit_lstm_forward(cfg, W, U, b_i, b_h, x, u0, u_inout, resnorm_out, workspace) -> None:
+    f32 = _f32()
+    _call("mgrit_lstm_forward", cfg, *_lstm_params(cfg, W, U, b_i, b_h, x),
+          _Arg(u0, "u0", f32, (cfg.B, 2 * cfg.H)),
+          _Arg(u_inout, "u_inout", f32, (cfg.T + 1, cfg.B, 2 * cfg.H)), _res(cfg, resnorm_out),
+          *_workspace(workspace))
 
 
 def mgrit_gru_profile_enable(on: bool) -> None:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmgrit_gru.so")
 SOURCES = ["api.hip", "kernels_forward.hip", "kernels_adjoint.hip", "kernels_ode.hip",
-           "kernels_misc.hip"]
+           "kernels_lstm.hip", "kernels_misc.hip"]
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
     # packed fp32 instructions are kept off on the test machines

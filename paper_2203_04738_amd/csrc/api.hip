@@ -343,7 +343,8 @@ static int relax_fwd(const FwdCtx& x, int l, bool include_c, bool f_points_curre
       a.dp2 = (cf * S - 1 - a.p.off) * x.c->B * 3LL * x.c->H;   // P row (i + 1) cf S - 1
     }
     if (zero_c && j == 1 && cf > 1) a.zero_from = x.c->B;   // rows of the intervals 1..
-    if (rhs_fused && j == 1 && cf > 1 && !include_c && a.mode == STEP_RELAX) {
+    if (rhs_fused && j == 1 && cf > 1 && !include_c && a.mode == STEP_RELAX &&
+        !prop_is_lstm(x.c->propagator)) {
       // interval i: coarse step from coarse point i to i + 1 (level point (i + 1) cf)
       a.mode = STEP_RELAX_RHS;
       a.gc = x.gl[l + 1];
@@ -449,7 +450,9 @@ static int run_projection(const mgrit_gru_cfg* c, const Layout& lay, char* base,
     CHECK_HIP(launch_split3((const float*)W, base + lay.W3, 3LL * c->H * c->D, s));
     W = base + lay.W3;
   }
-  const int width = c->propagator == PROP_ODE_DEMO ? c->H : 3 * c->H;
+  // GRU: three gates; demonstration ODE: one block; LSTM: four gates of the hidden width c->H / 2
+  const int width = c->propagator == PROP_ODE_DEMO ? c->H
+                    : prop_is_lstm(c->propagator) ? 2 * c->H : 3 * c->H;
   CHECK_HIP(launch_projection(x, W, b_i, (float*)(base + lay.P), (long long)c->T * c->B, width,
                               c->D, c->dtype, s));
   return MGRIT_OK;
@@ -457,10 +460,12 @@ static int run_projection(const mgrit_gru_cfg* c, const Layout& lay, char* base,
 
 // ode_dt != 0: the demonstration ODE (W = Bw[H,D], U = A[H,H], b_i = b, b_h unused) with
 // level-0 step size ode_dt; the propagator field of the caller's cfg is not read.
+// lstm: the LSTM step (W[4H,D], U[4H,H], b_i[4H], b_h[4H]; h0 and h are state pairs (h | c) of
+// width 2H); cfg->propagator selects its implicit or explicit form.
 static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, const void* U,
                         const float* b_i, const float* b_h, const void* x, const float* h0,
                         float* h, float* resnorm, void* ws, size_t ws_bytes, void* stream,
-                        float ode_dt = 0.f) {
+                        float ode_dt = 0.f, bool lstm = false) {
   if (!cin) return MGRIT_E_NULL;
   mgrit_gru_cfg c = *cin;
   const bool ode = ode_dt != 0.f;
@@ -470,12 +475,17 @@ static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, co
   }
   int rc = check_cfg(&c, !serial);
   if (rc) return rc;
-  if (ode && (c.dtype != MGRIT_F32 || c.flags != 0)) return MGRIT_E_UNSUPPORTED;
+  if ((ode || lstm) && (c.dtype != MGRIT_F32 || c.flags != 0)) return MGRIT_E_UNSUPPORTED;
   if (!W || !U || !b_i || !b_h || !x || !h0 || !h || !ws) return MGRIT_E_NULL;
   if (misaligned(W) || misaligned(U) || misaligned(x) || misaligned(h0) || misaligned(h) ||
       misaligned(ws))
     return MGRIT_E_ALIGN;
   if (ode) c.propagator = PROP_ODE_DEMO;
+  if (lstm) {
+    // the drivers move states of width 2H (h | c); the step kernels contract over the h half
+    c.propagator = c.propagator == MGRIT_PROP_IMPLICIT ? PROP_LSTM_IMPLICIT : PROP_LSTM_CLASSIC;
+    c.H *= 2;
+  }
   if (serial) {
     c.levels = 1;
     c.cf = 1;
@@ -487,7 +497,7 @@ static int forward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, co
   if (ws_bytes < lay.total) return MGRIT_E_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   char* base = (char*)ws;
-  const int pwidth = ode ? c.H : 3 * c.H;
+  const int pwidth = ode ? c.H : lstm ? 2 * c.H : 3 * c.H;
   WsRecord rec = ws_record_get(ws);
   if ((c.flags & MGRIT_REUSE_PROJECTION) && !proj_matches(rec, c, pwidth, x, W, b_i))
     return MGRIT_E_STATE;
@@ -877,6 +887,33 @@ int mgrit_gru_forward_static(const mgrit_gru_cfg* cfg, const void* W, const void
                     (size_t)MGRIT_STATIC_SCRATCH_BYTES, stream);
   t_no_prof = false;
   return rc;
+}
+
+int mgrit_lstm_workspace_bytes(const mgrit_gru_cfg* cfg, size_t* bytes) {
+  if (!bytes) return MGRIT_E_NULL;
+  int rc = check_cfg(cfg, true);
+  if (rc) return rc;
+  mgrit_gru_cfg c = *cfg;
+  c.H *= 2;                    // state pairs (h | c)
+  Layout lay;
+  make_layout(&c, &lay);
+  *bytes = lay.total;
+  return MGRIT_OK;
+}
+
+int lstm_serial_scan(const mgrit_gru_cfg* cfg, const float* W, const float* U, const float* b_i,
+                     const float* b_h, const float* x, const float* u0, float* u_out,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+  return forward_impl(cfg, true, W, U, b_i, b_h, x, u0, u_out, nullptr, workspace,
+                      workspace_bytes, stream, 0.f, true);
+}
+
+int mgrit_lstm_forward(const mgrit_gru_cfg* cfg, const float* W, const float* U,
+                       const float* b_i, const float* b_h, const float* x, const float* u0,
+                       float* u_inout, float* resnorm_out, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  return forward_impl(cfg, false, W, U, b_i, b_h, x, u0, u_inout, resnorm_out, workspace,
+                      workspace_bytes, stream, 0.f, true);
 }
 
 int ode_serial_scan(const mgrit_gru_cfg* cfg, float dt, const float* A, const float* Bw,

@@ -105,11 +105,20 @@ struct AdjArgs {
 // step of the appendix's demonstration ODE (Eq. 17).  PhiArgs then reads U = A[H,H],
 // P rows of width H (B d + b), gamma = step size of the level; b_h is unused.
 constexpr int PROP_ODE_DEMO = 100;
+// LSTM level step (kernels_lstm.hip), implicit in the decay terms / explicit.  PhiArgs then
+// reads H = state width (2 x hidden width: h | c), U = U[4H_h, H_h], P rows of width 4H_h.
+constexpr int PROP_LSTM_IMPLICIT = 101;
+constexpr int PROP_LSTM_CLASSIC = 102;
+__host__ __device__ inline bool prop_is_lstm(int p) {
+  return p == PROP_LSTM_IMPLICIT || p == PROP_LSTM_CLASSIC;
+}
 
-// (dispatches to launch_ode_step for PROP_ODE_DEMO)
+// (dispatches to launch_ode_step for PROP_ODE_DEMO, to launch_lstm_step for the LSTM codes)
 hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s);
 // modes STEP_RELAX, STEP_RESID, STEP_RHS; fp32 operands
 hipError_t launch_ode_step(const PhiArgs& a, hipStream_t s);
+// modes STEP_RELAX, STEP_RESID, STEP_RHS; fp32 operands
+hipError_t launch_lstm_step(const PhiArgs& a, hipStream_t s);
 hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s);
 
 // P[M,N] = X[M,K] W[N,K]^T + bias[N]

@@ -843,6 +843,7 @@ static void launch_phi_skinny(const PhiArgs& a, dim3 grid, hipStream_t s) {
 hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s) {
   if (a.nk <= 0) return hipSuccess;
   if (a.propagator == PROP_ODE_DEMO) return launch_ode_step(a, s);
+  if (prop_is_lstm(a.propagator)) return launch_lstm_step(a, s);
   const long long R = (long long)a.nk * a.B;
   auto tiles = [&](int tm, int tn) { return ((R + tm - 1) / tm) * ((a.H + tn - 1) / tn); };
   const int kind = R <= 2 * SK_MAXROWS ? 4 : 0;

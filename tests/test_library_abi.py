@@ -235,3 +235,31 @@ def test_binding_rejects_tensors_whose_size_does_not_match_cfg():
         mg.mgrit_ode_forward(cfg, 0.1, z(H, D), z(H, D), z(H), z(T, B, D), z(B, H), states, z(3), ws)
     with pytest.raises(ValueError):
         mg.mgrit_gru_forward_static(cfg, *P, z(B, H), z(T, B, H), z(3))
+
+
+def test_lstm_entry_points_validate_their_arguments_without_a_gpu():
+    L = mg.lib()
+    cfg = MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, iters=1)
+    p = 4096
+    # state pairs (h | c) double the state arrays: a larger workspace than the GRU's
+    assert mg.mgrit_lstm_workspace_bytes(cfg) > mg.mgrit_gru_workspace_bytes(cfg)
+    assert L.mgrit_lstm_forward(ctypes.byref(cfg), None, None, None, None, None, None, None, None,
+                                None, 0, None) == -1
+    assert L.lstm_serial_scan(ctypes.byref(cfg), p, p, p, p, p, p, p, p, 16, None) == -5
+    assert L.mgrit_lstm_forward(ctypes.byref(cfg), p, p, p, p, p, p, p, None, p, 16, None) == -5
+    for kw in ({"dtype": mg.MGRIT_BF16}, {"dtype": mg.MGRIT_F32_BF16X3},
+               {"flags": mg.MGRIT_ZERO_STATE_GUESS}):
+        c2 = MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, iters=1, **kw)
+        assert L.mgrit_lstm_forward(ctypes.byref(c2), p, p, p, p, p, p, p, None, p, 1 << 30,
+                                    None) == -8
+    c3 = MgritGruCfg(60, 2, 16, 32, cf=8, levels=2, iters=1)
+    assert L.mgrit_lstm_forward(ctypes.byref(c3), p, p, p, p, p, p, p, None, p, 1 << 30,
+                                None) == -3
+    c4 = MgritGruCfg(64, 2, 16, 30, cf=4, levels=2, iters=1)
+    assert L.mgrit_lstm_forward(ctypes.byref(c4), p, p, p, p, p, p, p, None, p, 1 << 30,
+                                None) == -6
+    import torch
+    z = lambda *s: torch.zeros(*s)
+    with pytest.raises(ValueError):       # the state arrays hold pairs: [(T+1), B, 2H]
+        mg.mgrit_lstm_forward(cfg, z(128, 16), z(128, 32), z(128), z(128), z(64, 2, 16), z(2, 64),
+                              z(65, 2, 32), z(1), torch.zeros(16, dtype=torch.uint8))

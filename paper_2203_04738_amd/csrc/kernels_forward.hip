@@ -3,6 +3,7 @@
 // (relaxation update of Alg. 1, residual + restriction of Alg. 2 lines 2-3, the
 // right-hand side of Eq. 11, and the adjoint coefficient vectors).
 #include <algorithm>
+#include <cstdlib>
 #include <type_traits>
 
 #include "common.h"
@@ -749,6 +750,118 @@ __global__ __launch_bounds__(PhiSkMaxNT<CT>::value) void phi_skinny_kernel(PhiAr
   if (MODE == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
 }
 
+// ---------------------------------------------------------------------------
+// Few-row step on the matrix pipe
+// ---------------------------------------------------------------------------
+// The same step for up to 64 rows with the contraction on v_mfma_f32_16x16x4_f32, which sums
+// over k inside the instruction: no partial sums travel between lanes, and a step needs a
+// quarter of the waves of the vector form above (a dependent step waits for its slowest wave).
+// A workgroup owns one block of 16 rows and FR_NC hidden columns; the three gates of those
+// columns are the 16 columns of the MFMA block (3 x 5, one idle).  Its waves split K: wave w
+// contracts k in [w kslice, (w + 1) kslice), every load of its slice issued before the first
+// MFMA, and the 16 x 16 partial blocks meet in LDS.  Operand layout of the instruction: lane l
+// supplies A[i = l % 16][k = l / 16] and B[k = l / 16][j = l % 16]; a lane loads four
+// consecutive k of its row (k = 16 s + 4 (l / 16) + e, e = 0..3) and feeds four MFMAs, so A and
+// B agree on the k each of them contracts; result register v of lane l is D[4 (l / 16) + v][l % 16].
+constexpr int FR_NC = 5;       // hidden columns per workgroup
+constexpr int FR_KB = 8;       // blocks of sixteen k whose loads a wave keeps in flight
+constexpr int FR_MAXW = 8;     // waves per workgroup at most
+
+template <int MODE, class WT>
+__global__ __launch_bounds__(64 * FR_MAXW) void phi_fewrow_kernel(PhiArgs a, int kslice) {
+  __shared__ float part[FR_MAXW][16][17];
+  const int H = a.H;
+  const int R = a.nk * a.B;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int nt = blockDim.x, nw = nt >> 6;
+  const int li = lane & 15, kq = lane >> 4;
+  const int j0 = blockIdx.x * FR_NC;
+  const int r0 = blockIdx.y * 16;
+  const int rows_here = min(16, R - r0);
+  const int aux_w =
+      (MODE == STEP_KAPPA || MODE == STEP_RELAX_KAPPA || MODE == STEP_RELAX_KAPPA2) ? a.kappa_width
+                                                                                    : H;
+  // this thread's output element (if any): its operands are requested first so that their
+  // latency overlaps the contraction
+  const int n_out = rows_here * FR_NC;
+  const bool epi = tid < n_out && j0 + tid % FR_NC < H;
+  int e_j = 0;
+  PhiRow ero = {};
+  PhiEpiIn ein = {};
+  PhiBias ebh = {};
+  if (epi) {
+    ero = phi_row(a, r0 + tid / FR_NC, aux_w);
+    e_j = j0 + tid % FR_NC;
+    ein = phi_epi_load<MODE>(a, ero, e_j);
+    ebh = phi_bias_load(a, e_j);
+  }
+
+  // A: state row of this lane (rows beyond the block are clamped; their sums are never used)
+  const int r = r0 + min(li, rows_here - 1);
+  const long long pt = (unsigned)r / (unsigned)a.B;   // rows < 2^31: 32-bit division
+  const int b = r - (int)pt * a.B;
+  const float* hrow = a.u_in + (a.in.at(pt) * a.B + b) * H;
+  // B: weight row of this lane's MFMA column: gate li / FR_NC, hidden column j0 + li % FR_NC
+  // (column 15 idles on a copy of column 14)
+  const int lc = min(li, 3 * FR_NC - 1);
+  const WT* urow = (const WT*)a.U +
+                   ((long long)(lc / FR_NC) * H + min(j0 + lc % FR_NC, H - 1)) * H;
+
+  // two accumulators: consecutive MFMAs do not wait for each other's result
+  floatx4 acc = zero4(), acc1 = zero4();
+  const int k_end = min(H, (wv + 1) * kslice);
+  for (int kb = wv * kslice; kb < k_end; kb += 16 * FR_KB) {
+    floatx4 av[FR_KB], bv[FR_KB];
+#pragma unroll
+    for (int s = 0; s < FR_KB; ++s) {
+      const int k = kb + 16 * s + 4 * kq;
+      const int kc = min(k, H - 4);                  // H is a multiple of 4
+      av[s] = ldg4(hrow + kc);
+      bv[s] = ldg4w(urow + kc);
+    }
+    // all loads of the slice are in flight before anything waits for one of them
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int s = 0; s < FR_KB; ++s) {
+      if (kb + 16 * s + 4 * kq >= k_end) av[s] = zero4();
+#pragma unroll
+      for (int e = 0; e < 4; e += 2) {
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s][e], bv[s][e], acc, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s][e + 1], bv[s][e + 1], acc1, 0, 0, 0);
+      }
+    }
+  }
+  acc += acc1;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) part[wv][4 * kq + v][li] = acc[v];
+  __syncthreads();
+
+  double nrm = 0.0;
+  for (int e = tid; e < n_out; e += nt) {
+    const int row = e / FR_NC, c = e % FR_NC;
+    const int j = j0 + c;
+    if (j >= H) continue;
+    float sr = 0.f, sz = 0.f, sn = 0.f;
+    for (int w = 0; w < nw; ++w) {
+      sr += part[w][row][c];
+      sz += part[w][row][FR_NC + c];
+      sn += part[w][row][2 * FR_NC + c];
+    }
+    if (e == tid && epi) {
+      phi_epi_finish<MODE>(a, ero, e_j, sr, sz, sn, ein, ebh, nrm,
+                           (MODE == STEP_RELAX_KAPPA2 || MODE == STEP_RELAX_CK)
+                               ? phi_row_coarse_kappa(a, r0 + row) : 0);
+    } else {   // more outputs than threads (one-wave workgroups only)
+      const PhiRow ro = phi_row(a, r0 + row, aux_w);
+      phi_epi_finish<MODE>(a, ro, j, sr, sz, sn, phi_epi_load<MODE>(a, ro, j), phi_bias_load(a, j),
+                           nrm,
+                           (MODE == STEP_RELAX_KAPPA2 || MODE == STEP_RELAX_CK)
+                               ? phi_row_coarse_kappa(a, r0 + row) : 0);
+    }
+  }
+  if (MODE == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
+}
+
 typedef TileCfg<2, 2, 2, 1, 3> PhiBig;    // 128 rows x 64 hidden columns (x3 gates), 256 threads
 typedef TileCfg<2, 2, 1, 1, 3> PhiMid;    //  64 rows x 64 hidden columns, 256 threads
 // few rows:  32 rows x 32 hidden columns, 4 waves splitting K (slices of 128)
@@ -826,6 +939,34 @@ static void launch_phi_skinny_mode(const PhiArgs& a, dim3 grid, hipStream_t s) {
     hipLaunchKernelGGL((phi_skinny_kernel<CT, MODE, float>), grid, block, 0, s, a, rb);
 }
 
+template <int MODE>
+static void launch_phi_fewrow_mode(const PhiArgs& a, hipStream_t s) {
+  const int R = a.nk * a.B;
+  // waves per workgroup: K slices of 128 (two blocks of loads in flight at most beyond that)
+  int nw = (a.H + 127) / 128;
+  nw = nw < 1 ? 1 : (nw > FR_MAXW ? FR_MAXW : nw);
+  const int kslice = ((a.H + nw - 1) / nw + 15) / 16 * 16;
+  const dim3 grid((unsigned)((a.H + FR_NC - 1) / FR_NC), (unsigned)((R + 15) / 16));
+  const dim3 block(64 * nw);
+  if (a.bf16 == 1)
+    hipLaunchKernelGGL((phi_fewrow_kernel<MODE, bf16_t>), grid, block, 0, s, a, kslice);
+  else
+    hipLaunchKernelGGL((phi_fewrow_kernel<MODE, float>), grid, block, 0, s, a, kslice);
+}
+
+static void launch_phi_fewrow(const PhiArgs& a, hipStream_t s) {
+  switch (a.mode) {
+    case STEP_RELAX: launch_phi_fewrow_mode<STEP_RELAX>(a, s); break;
+    case STEP_RESID: launch_phi_fewrow_mode<STEP_RESID>(a, s); break;
+    case STEP_RHS: launch_phi_fewrow_mode<STEP_RHS>(a, s); break;
+    case STEP_RELAX_KAPPA: launch_phi_fewrow_mode<STEP_RELAX_KAPPA>(a, s); break;
+    case STEP_RELAX_RHS: launch_phi_fewrow_mode<STEP_RELAX_RHS>(a, s); break;
+    case STEP_RELAX_KAPPA2: launch_phi_fewrow_mode<STEP_RELAX_KAPPA2>(a, s); break;
+    case STEP_RELAX_CK: launch_phi_fewrow_mode<STEP_RELAX_CK>(a, s); break;
+    default: launch_phi_fewrow_mode<STEP_KAPPA>(a, s);
+  }
+}
+
 template <int CT>
 static void launch_phi_skinny(const PhiArgs& a, dim3 grid, hipStream_t s) {
   switch (a.mode) {
@@ -838,6 +979,16 @@ static void launch_phi_skinny(const PhiArgs& a, dim3 grid, hipStream_t s) {
     case STEP_RELAX_CK: launch_phi_skinny_mode<CT, STEP_RELAX_CK>(a, grid, s); break;
     default: launch_phi_skinny_mode<CT, STEP_KAPPA>(a, grid, s);
   }
+}
+
+// MGRIT_FEWROW_VECTOR=1 in the environment selects the vector-FMA form of the few-row step
+// (kept for widths below 16 and for comparison)
+static bool getenv_vector_fewrow() {
+  static const bool v = [] {
+    const char* e = std::getenv("MGRIT_FEWROW_VECTOR");
+    return e && e[0] == '1';
+  }();
+  return v;
 }
 
 hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s) {
@@ -854,7 +1005,9 @@ hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s) {
   auto contracted = [&](int tm) {
     if (a.zero_from > 0) rows_done = std::min<long long>(R, (a.zero_from + tm - 1) / tm * tm);
   };
-  if (R <= 2 * SK_MAXROWS) {
+  if (R <= 2 * SK_MAXROWS && a.H >= 16 && !getenv_vector_fewrow()) {
+    launch_phi_fewrow(a, s);
+  } else if (R <= 2 * SK_MAXROWS) {
     // two hidden columns (six weight rows) per workgroup measured best from H = 512 up
     // (6.2 us per step at 32 rows x 512, 5.5 at 4 rows x 1024; four columns: +0.5 us)
     const int rb = phi_sk_rows(R);

@@ -127,33 +127,31 @@ def stack_cpu_baseline(wl, layers, fwd_iters, bwd_iters, fcf=True):
     import numpy as np
     from oracle import mgrit_gru_oracle as orc
     from synthetic_inputs import layer_workload, make_inputs
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        cores = os.cpu_count() or 1
+    from threadpoolctl import threadpool_limits
     tw = wl.twin(min(8, wl.T // wl.cf ** (wl.levels - 1)))
     ds = [make_inputs(layer_workload(tw, j)) for j in range(layers)]
     params = [(d["W"], d["U"], d["b_i"], d["b_h"]) for d in ds]
     z = np.zeros((tw.T + 1, tw.B, tw.H))
-    t0 = time.perf_counter()
-    hs = orc.stacked_forward(
-        params, ds[0]["x"], [d["h0"] for d in ds],
-        lambda j, W, U, bi, bh, x, h0: orc.mgrit_forward(W, U, bi, bh, x, h0, z, tw.cf, tw.levels,
-                                                         fwd_iters, fine_relax_fcf=fcf)[0])
-    top = ds[-1]
-    _, g = orc.cross_entropy_head(hs[-1][-1], top["W_o"], top["b_o"], top["labels"])
-    src = np.zeros_like(z)
-    src[-1] = g
 
     def bwd(j, W, U, bi, bh, x, h, s):
         out = orc.mgrit_backward(W, U, bi, bh, x, h, None, z, tw.cf, tw.levels, bwd_iters,
                                  fine_relax_fcf=fcf, dL_dh=s)
         return (out[0],) + tuple(out[2:7])
 
-    orc.stacked_backward(params, ds[0]["x"], hs, src, bwd)
-    dt = time.perf_counter() - t0
-    return {"value": tw.T * tw.B / dt, "unit": "time-steps*batch/s", "cores": int(cores),
+    with threadpool_limits(limits=1):      # one host thread, as the single-layer baseline
+        t0 = time.perf_counter()
+        hs = orc.stacked_forward(
+            params, ds[0]["x"], [d["h0"] for d in ds],
+            lambda j, W, U, bi, bh, x, h0: orc.mgrit_forward(W, U, bi, bh, x, h0, z, tw.cf,
+                                                             tw.levels, fwd_iters,
+                                                             fine_relax_fcf=fcf)[0])
+        top = ds[-1]
+        _, g = orc.cross_entropy_head(hs[-1][-1], top["W_o"], top["b_o"], top["labels"])
+        src = np.zeros_like(z)
+        src[-1] = g
+        orc.stacked_backward(params, ds[0]["x"], hs, src, bwd)
+        dt = time.perf_counter() - t0
+    return {"value": tw.T * tw.B / dt, "unit": "time-steps*batch/s", "cores": 1,
             "kind": "oracle",
             "sample": f"reduced-T twin of {wl.name}, {layers} layers: T={tw.T} (of {wl.T}), "
                       f"B={tw.B}, D={tw.D}, H={tw.H}, cf={tw.cf}, levels={tw.levels}, {fwd_iters} fwd + "
@@ -448,20 +446,17 @@ def study_ode(args):
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import demo_ode_oracle as ode
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([q.get("num_threads", 1) for q in threadpool_info()] or [1])
-        except Exception:
-            cores = os.cpu_count() or 1
+        from threadpoolctl import threadpool_limits
         unit = wl.cf ** (wl.levels - 1)
 
         def run(Tt):
             q = random_ode(0, Tt, B, D, H, h0_random=False)
-            t0 = time.perf_counter()
-            ode.ode_mgrit_forward(q["A"], q["Bw"], q["b"], q["d"], q["h0"],
-                                  np.zeros((Tt + 1, B, H)), dt, wl.cf, wl.levels, iters,
-                                  fine_relax_fcf=bool(fine_relax))
-            return time.perf_counter() - t0
+            with threadpool_limits(limits=1):      # one host thread, as the other baselines
+                t0 = time.perf_counter()
+                ode.ode_mgrit_forward(q["A"], q["Bw"], q["b"], q["d"], q["h0"],
+                                      np.zeros((Tt + 1, B, H)), dt, wl.cf, wl.levels, iters,
+                                      fine_relax_fcf=bool(fine_relax))
+                return time.perf_counter() - t0
 
         n, n_max = min(16, T // unit), T // unit
         Tt = n * unit
@@ -470,7 +465,7 @@ def study_ode(args):
             n = int(min(n_max, max(n + 1, n * 15.0 / max(el, 1e-3))))
             Tt = n * unit
             el = run(Tt)
-        cpu = {"value": Tt * B / el, "unit": "time-steps*batch/s", "cores": int(cores),
+        cpu = {"value": Tt * B / el, "unit": "time-steps*batch/s", "cores": 1,
                "kind": "oracle",
                "sample": f"T={Tt} (of {T}), B={B}, D={D}, H={H}, cf={wl.cf}, levels={wl.levels}, "
                          f"{iters} cycles, numpy float64, {el:.1f} s"}

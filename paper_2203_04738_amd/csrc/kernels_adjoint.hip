@@ -1036,6 +1036,213 @@ __global__ __launch_bounds__(256, 2) void grad_gemm_bf16_kernel(GradArgs a) {
       }
 }
 
+// Wide-tile form of the bf16 contraction above (128 x 256 outputs per workgroup, each wave 64 x 128),
+// used when the second operand has more than 128 columns.  The kernel above is bound by the bytes
+// it pulls through the vector-memory path (8 bytes of kappa and w per S element, re-read by every
+// column tile); twice the columns per tile take 40 % off those.  Both operands are written to LDS
+// in the order they have in memory, [k][column] (S after the product and the hi/lo split, eight
+// bytes per thread and row; the second operand as loaded), and the k-major MFMA fragments are
+// formed by the LDS transpose read (ds_read_b64_tr_b16): within 16 lanes, lane i receives element
+// i % 4 of what lanes 4e + i / 4 (e = 0..3) point at.  With lanes 4r..4r+3 of a block pointing at
+// sixteen consecutive columns of row k + r, lane i therefore gets column i of rows k..k+3; two
+// reads give the eight k of a 32x32x16 operand.  Row strides are 64 bytes modulo 256, so the four
+// rows of a read fall on different banks; the writes are contiguous.
+constexpr int TR_TK = 32;                  // k rows per slice
+constexpr int TR_GN = 256;                 // tile columns (second operand)
+constexpr int TR_LDA = GT + 32;            // row strides in elements: 320 and 576 bytes
+constexpr int TR_LDB = TR_GN + 32;
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef short short8v __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+
+// eight k (rows p .. p + 7 of the LDS tile, in the lane's own order) of this lane's column
+__device__ inline bf16x8 lds_tr8(const bf16_t* p, int ld) {
+  typedef __attribute__((address_space(3))) short4v* lptr;
+  const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)p);
+  const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p + 4 * ld));
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+__device__ inline void split_bf16_4(const floatx4& v, bf16x4& hi, bf16x4& lo) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    hi[i] = (__bf16)v[i];
+    lo[i] = (__bf16)(v[i] - (float)hi[i]);
+  }
+}
+
+template <bool B_BF16>
+__global__ __launch_bounds__(256, 2) void grad_gemm_tr_kernel(GradArgs a) {
+  constexpr int NBT = B_BF16 ? 1 : 2;     // tiles of the second operand in LDS (hi, lo)
+  __shared__ __attribute__((aligned(16))) bf16_t As[2][TR_TK * TR_LDA];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[NBT][TR_TK * TR_LDB];
+  const int H = a.H, N = a.N, M = 3 * a.H;
+  const int tiles = a.mtiles * a.ntiles;
+  int tile, z;
+  if (a.splits % NXCD == 0) {
+    const int j = blockIdx.x / NXCD;
+    tile = j % tiles;
+    z = (j / tiles) * NXCD + blockIdx.x % NXCD;
+  } else {
+    tile = blockIdx.x % tiles;
+    z = blockIdx.x / tiles;
+  }
+  const int nt = tile / a.mtiles;
+  const int m0 = (tile % a.mtiles) * GT, n0 = nt * TR_GN;
+  const long long kbeg = (long long)z * a.Kper;
+  long long kend = kbeg + a.Kper;
+  if (kend > a.Ktot) kend = a.Ktot;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1, li = lane & 31, lh = lane >> 5;
+  const long long rowoff = a.B;           // kap0 / w rows are one time point ahead
+
+  floatx16 acc[2][4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // staging of S: columns m4*4..+3, slice rows k8 + 8r (r = 0..3)
+  const int m4 = tid & 31, k8 = tid >> 5;
+  const int m = m0 + m4 * 4;
+  const bool m_ok = m < M;
+  const int mc = m_ok ? m : 0;
+  const int gate = mc / H, jcol = mc - gate * H;
+  const int src = gate == 2 ? a.third_off + jcol : mc;
+  // second operand: bf16: columns m4*8..+7, rows k8 + 8r (r = 0..3);
+  //                 fp32: columns c4*4..+3, rows kf + 4r (r = 0..7)
+  const int c4 = tid & 63, kf = tid >> 6;
+  const int n = n0 + (B_BF16 ? m4 * 8 : c4 * 4);
+  const bool n_ok = n < N;
+  const int nc = n_ok ? n : 0;
+  floatx4 rk[4], rw[4];
+  floatx4 rbf[B_BF16 ? 1 : 8];
+  bf16x8 rbh[B_BF16 ? 4 : 1];
+  floatx4 colsum = zero4();
+  auto fetch = [&](long long k0) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      long long k = k0 + k8 + 8 * r;
+      if (k >= kend) k = kend - 1;
+      rk[r] = ldg4(a.kap0 + (k + rowoff) * (5LL * H) + src);
+      rw[r] = ldg4(a.w + (k + rowoff) * H + jcol);
+      if constexpr (B_BF16) rbh[r] = ldg8h((const bf16_t*)a.Bm + k * N + nc);
+    }
+    if constexpr (!B_BF16) {
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        long long k = k0 + kf + 4 * r;
+        if (k >= kend) k = kend - 1;
+        rbf[r] = ldg4((const float*)a.Bm + k * N + nc);
+      }
+    }
+  };
+  auto stash = [&](long long k0) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int row = k8 + 8 * r;
+      const bool k_ok = k0 + row < kend;
+      const floatx4 p = (k_ok && m_ok) ? rk[r] * rw[r] : zero4();
+      colsum += p;
+      bf16x4 hi, lo;
+      split_bf16_4(p, hi, lo);
+      *reinterpret_cast<bf16x4*>(&As[0][row * TR_LDA + m4 * 4]) = hi;
+      *reinterpret_cast<bf16x4*>(&As[1][row * TR_LDA + m4 * 4]) = lo;
+      if constexpr (B_BF16) {
+        bf16x8 zv;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) zv[i] = (__bf16)0.f;
+        *reinterpret_cast<bf16x8*>(&Bs[0][row * TR_LDB + m4 * 8]) = (k_ok && n_ok) ? rbh[r] : zv;
+      }
+    }
+    if constexpr (!B_BF16) {
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        const int row = kf + 4 * r;
+        const floatx4 v = (k0 + row < kend && n_ok) ? rbf[r] : zero4();
+        bf16x4 hi, lo;
+        split_bf16_4(v, hi, lo);
+        *reinterpret_cast<bf16x4*>(&Bs[0][row * TR_LDB + c4 * 4]) = hi;
+        *reinterpret_cast<bf16x4*>(&Bs[NBT - 1][row * TR_LDB + c4 * 4]) = lo;
+      }
+    }
+  };
+  // transpose reads: lane (block b = lane / 16, i = lane % 16) points at row 8 * (b / 2) + i / 4,
+  // columns 16 * (b % 2) + 4 * (i % 4) .. + 3 of a 32-column block and receives column
+  // 16 * (b % 2) + i = lane % 32 of rows 8 * (lane / 32) .. + 3
+  const int i16 = lane & 15, half = (lane >> 4) & 1;
+  const int a_off = (lh * 8 + (i16 >> 2)) * TR_LDA + wm * 64 + half * 16 + 4 * (i16 & 3);
+  const int b_off = (lh * 8 + (i16 >> 2)) * TR_LDB + wn * 128 + half * 16 + 4 * (i16 & 3);
+
+  if (kbeg < kend) {
+    fetch(kbeg);
+    stash(kbeg);
+    __syncthreads();
+    for (long long k0 = kbeg; k0 < kend; k0 += TR_TK) {
+      const bool more = k0 + TR_TK < kend;
+      if (more) fetch(k0 + TR_TK);
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+      for (int c = 0; c < TR_TK / 16; ++c) {
+        bf16x8 fa[2][2], fb[NBT][4];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+            fa[t][i] = lds_tr8(&As[t][a_off + c * 16 * TR_LDA + i * 32], TR_LDA);
+#pragma unroll
+        for (int t = 0; t < NBT; ++t)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            fb[t][j] = lds_tr8(&Bs[t][b_off + c * 16 * TR_LDB + j * 32], TR_LDB);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int i = 0; i < 2; ++i) {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][i], fb[0][j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[0][j], acc[i][j], 0, 0, 0);
+            if constexpr (!B_BF16)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][i], fb[NBT - 1][j], acc[i][j], 0, 0, 0);
+          }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_setprio(0);
+      __syncthreads();
+      if (more) {
+        stash(k0 + TR_TK);
+        __syncthreads();
+      }
+    }
+  }
+  // column sums: the eight row groups of a column meet in LDS (the A tiles are free now)
+  float* red = reinterpret_cast<float*>(&As[0][0]);      // [8][GT] floats = 4 KB
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < 4; ++e) red[k8 * GT + m4 * 4 + e] = colsum[e];
+  __syncthreads();
+  if (tid < GT && m0 + tid < M) {
+    float sum = 0.f;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) sum += red[q * GT + tid];
+    // every column tile holds the same sums: the first one reports them
+    if (nt == 0) a.bpart[(long long)z * M + m0 + tid] = sum;
+  }
+  float* out = a.part + (long long)z * M * N;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int mm = m0 + wm * 64 + i * 32 + 8 * (e / 4) + 4 * lh + (e & 3);
+        const int nn = n0 + wn * 128 + j * 32 + li;
+        if (mm < M && nn < N) out[(long long)mm * N + nn] = acc[i][j][e];
+      }
+}
+
 // The same partial products for fp32 operands carried as three bf16 terms each (see
 // gemm_core_bf16.h): S and the second operand (h or x) are split on their way to LDS and six
 // of the nine term products are kept.  K-slices of 32 rows; waves 0-1 stage S (the product
@@ -1244,8 +1451,13 @@ bias_reduce_kernel(const float* __restrict__ pu, int nu, const float* __restrict
 // multiple of 8 (whole splits per XCD) unless fewer than 8 fill the slots as well, chosen
 // so that the grid is close to a whole number of rounds over the slots: a partly filled
 // last round costs as much time as a full one.
+// Tile columns of a gradient GEMM: the bf16 contraction takes 256 where the second operand is
+// wider than one 128-column tile.
+static int grad_tile_n(int N, int bf16) { return bf16 == 1 && N > GT ? TR_GN : GT; }
+
 static int grad_splits(long long Ktot, int M, int N, int bf16) {
-  const long long tiles = (long long)((M + GT - 1) / GT) * ((N + GT - 1) / GT);
+  const int gn = grad_tile_n(N, bf16);
+  const long long tiles = (long long)((M + GT - 1) / GT) * ((N + gn - 1) / gn);
   const long long slots = bf16 == 0 ? 768 : 512;
   long long maxs = (Ktot + 4 * GTK - 1) / (4 * GTK);   // at least 4 slices per split
   if (maxs > 256) maxs = 256;
@@ -1305,7 +1517,8 @@ hipError_t launch_param_grads(const float* kap0, const float* w, const float* h,
     const int slice = bf16 == 1 ? HB_TK : GTK;      // (both multiples of the 32 of bf16 = 2)
     a.Kper = (per + slice - 1) / slice * slice;
     a.mtiles = (M + GT - 1) / GT;
-    a.ntiles = (a.N + GT - 1) / GT;
+    const int gn = grad_tile_n(a.N, bf16);
+    a.ntiles = (a.N + gn - 1) / gn;
     a.splits = splits;
     a.bpart = bpart[which];
     nbpart[which] = splits;
@@ -1313,6 +1526,10 @@ hipError_t launch_param_grads(const float* kap0, const float* w, const float* h,
     dim3 grid((unsigned)((long long)a.mtiles * a.ntiles * splits));
     if (bf16 == 2)
       hipLaunchKernelGGL(grad_gemm_x3_kernel, grid, dim3(256), 0, s, a);
+    else if (bf16 && gn == TR_GN && which == 1)
+      hipLaunchKernelGGL(grad_gemm_tr_kernel<true>, grid, dim3(256), 0, s, a);
+    else if (bf16 && gn == TR_GN)
+      hipLaunchKernelGGL(grad_gemm_tr_kernel<false>, grid, dim3(256), 0, s, a);
     else if (bf16 && which == 1)
       hipLaunchKernelGGL(grad_gemm_bf16_kernel<true>, grid, dim3(256), 0, s, a);
     else if (bf16)

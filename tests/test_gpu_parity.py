@@ -353,6 +353,27 @@ def test_big_tiles_with_ragged_rows_columns_and_k(gh, dtype):
     assert e <= tol and e <= tight, e
 
 
+@pytest.mark.parametrize("dtype", ["fp32", "bf16", "fp32x3"])
+def test_gradient_gemms_with_ragged_tiles_and_row_tails(gh, dtype):
+    """Parameter gradients where every tile edge of the gradient GEMMs is ragged: 3H = 408 output
+    rows (three 128-row tiles and 24 rows), H = 136 and D = 264 output columns (one 128- or
+    256-column tile and 8 columns), T * B = 1176 summed rows (no multiple of the 32- or 64-row
+    slices, so every row split ends in a partial slice).  The bf16 form takes its 256-column
+    tiles here (second operand wider than 128 columns)."""
+    T, B, D, H, cf, levels = 24, 49, 264, 136, 4, 2
+    d = dict(random_small(77, T, B, D, H, scale=0.2))
+    tol = TOL_BF16 if dtype == "bf16" else TOL
+    if dtype == "bf16":
+        d = _bf16_inputs(d)
+    h = orc.serial_scan(*_P(d), d["x"], d["h0"]).astype(np.float32)
+    out = orc.mgrit_backward(*_P(d), d["x"], h, d["dL_dhT"], _zeros(d), cf, levels, 2)
+    run = gh.GpuRun(d, cf=cf, levels=levels, dtype=dtype)
+    its, _, grads = run.backward_iterates(h, 2, per_call=2)
+    assert gh.rel_err(its[-1], out[0]) <= tol
+    for name, g, r in zip(("dW", "dU", "db_i", "db_h"), grads, out[2:6]):
+        assert gh.rel_err(g, r) <= tol, name
+
+
 # ------------------------------------------------------------------ zero initial guess of the adjoint
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16", "fp32x3"])

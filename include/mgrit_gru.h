@@ -19,7 +19,16 @@
  *   r*(W_hn h + b_hn), so the two bias sets cannot be merged.
  * - dtype MGRIT_F32: x, W, U are float.  MGRIT_BF16: x, W, U are bf16 (uint16
  *   bit patterns); biases, states, projections, accumulation and every output
- *   stay float.  MGRIT_F32_BF16X3: arguments exactly as for MGRIT_F32 and
+ *   stay float.  The matrix pipe takes bf16 operands, so where a contraction's
+ *   left operand is an fp32 state (U h, U^T(kappa w), the gradient sums) it is
+ *   rounded to bf16 for that product only, as mixed-precision training does;
+ *   the state that is stored, updated and returned stays fp32.
+ *   MGRIT_BF16_STATE2: the same arguments, but the fp32 operand enters those
+ *   products as two bf16 terms (hi + lo, 16 mantissa bits, twice the matrix
+ *   work): results within ~1e-6 relative of fp64 arithmetic on the same bf16
+ *   weights, where MGRIT_BF16 is within ~1e-2.  (The few-row steps of the
+ *   coarsest level compute in fp32 on the bf16 weights under both.)
+ *   MGRIT_F32_BF16X3: arguments exactly as for MGRIT_F32 and
  *   results to the same accuracy; the tile kernels carry each fp32 operand of
  *   a contraction as the sum of three bf16 terms (3 x 8 mantissa bits, the
  *   exponent range of fp32) and keep six of the nine term products, accumulated
@@ -86,7 +95,7 @@ enum {
 
 enum { MGRIT_PROP_IMPLICIT = 0,   /* Eq. 16, the paper's propagator on all levels */
        MGRIT_PROP_CLASSIC = 1 };  /* Eq. 3 (explicit Euler; Classic GRU when step = 1) */
-enum { MGRIT_F32 = 0, MGRIT_BF16 = 1, MGRIT_F32_BF16X3 = 2 };
+enum { MGRIT_F32 = 0, MGRIT_BF16 = 1, MGRIT_F32_BF16X3 = 2, MGRIT_BF16_STATE2 = 3 };
 
 /* flags */
 enum {
@@ -148,7 +157,7 @@ typedef struct {
   int32_t fine_relax;   /* level-0 relaxation in Alg. 2 line 1: 0 = F, 1 = FCF
                            (Eq. 8); coarser levels always use FCF */
   int32_t propagator;   /* MGRIT_PROP_* */
-  int32_t dtype;        /* MGRIT_F32 / MGRIT_BF16 / MGRIT_F32_BF16X3 */
+  int32_t dtype;        /* MGRIT_F32 / MGRIT_BF16 / MGRIT_F32_BF16X3 / MGRIT_BF16_STATE2 */
   int32_t flags;        /* 0 or an OR of the flags above */
 } mgrit_gru_cfg;
 

@@ -35,7 +35,7 @@ class MgritGruCfg(ctypes.Structure):
         super().__init__(T, B, D, H, cf, levels, iters, fine_relax, propagator, dtype, flags)
 
 
-MGRIT_F32, MGRIT_BF16, MGRIT_F32_BF16X3 = 0, 1, 2   # cfg.dtype
+MGRIT_F32, MGRIT_BF16, MGRIT_F32_BF16X3, MGRIT_BF16_STATE2 = 0, 1, 2, 3   # cfg.dtype
 MGRIT_REUSE_PROJECTION = 1
 MGRIT_KEEP_COEFFS = 2
 MGRIT_REUSE_COEFFS = 4
@@ -182,7 +182,7 @@ def _params(cfg, W, U, b_i, b_h, x):
     """The five arguments every GRU entry point starts with."""
     import torch
     f32 = torch.float32
-    dt = torch.bfloat16 if cfg.dtype == MGRIT_BF16 else f32
+    dt = torch.bfloat16 if cfg.dtype in (MGRIT_BF16, MGRIT_BF16_STATE2) else f32
     T, B, D, H = cfg.T, cfg.B, cfg.D, cfg.H
     return (_Arg(W, "W", dt, (3 * H, D)), _Arg(U, "U", dt, (3 * H, H)),
             _Arg(b_i, "b_i", f32, (3 * H,)), _Arg(b_h, "b_h", f32, (3 * H,)),

@@ -101,6 +101,12 @@ struct Layout {
 
 static size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
+// Operand form handed to the kernels: 0 fp32, 1 bf16 inputs and weights, 2 three bf16 terms per
+// fp32 operand; both bf16 dtypes store alike and differ in how the tile kernels carry the fp32
+// state operand (one bf16 term, or two with MGRIT_BF16_STATE2).
+static int kform(int dtype) { return dtype == MGRIT_BF16_STATE2 ? 1 : dtype; }
+static int one_term(int dtype) { return dtype == MGRIT_BF16 ? 1 : 0; }
+
 static int check_cfg(const mgrit_gru_cfg* c, bool need_hierarchy) {
   if (!c) return MGRIT_E_NULL;
   if (c->T < 1 || c->B < 1 || c->D < 1 || c->H < 1) return MGRIT_E_SIZE;
@@ -108,7 +114,8 @@ static int check_cfg(const mgrit_gru_cfg* c, bool need_hierarchy) {
   if (c->iters < 0) return MGRIT_E_SIZE;
   if (c->propagator != MGRIT_PROP_IMPLICIT && c->propagator != MGRIT_PROP_CLASSIC)
     return MGRIT_E_ENUM;
-  if (c->dtype != MGRIT_F32 && c->dtype != MGRIT_BF16 && c->dtype != MGRIT_F32_BF16X3)
+  if (c->dtype != MGRIT_F32 && c->dtype != MGRIT_BF16 && c->dtype != MGRIT_F32_BF16X3 &&
+      c->dtype != MGRIT_BF16_STATE2)
     return MGRIT_E_ENUM;
   if (c->flags & ~(MGRIT_REUSE_PROJECTION | MGRIT_KEEP_COEFFS | MGRIT_REUSE_COEFFS |
                    MGRIT_ZERO_ADJOINT_GUESS | MGRIT_ZERO_STATE_GUESS))
@@ -159,7 +166,7 @@ static int make_layout(const mgrit_gru_cfg* c, Layout* lay) {
   lay->WT = off;
   off = align_up(off + (size_t)3 * c->H * c->D * sizeof(float));
   lay->part = off;
-  off = align_up(off + grad_partial_floats(c->T, c->B, c->D, c->H, c->dtype) * sizeof(float));
+  off = align_up(off + grad_partial_floats(c->T, c->B, c->D, c->H, kform(c->dtype)) * sizeof(float));
   if (c->dtype == MGRIT_F32_BF16X3) {
     lay->U3 = off;
     off = align_up(off + (size_t)3 * 3 * c->H * c->H * 2);
@@ -278,7 +285,8 @@ static PhiArgs phi_base(const FwdCtx& x, int l) {
   a.H = x.c->H;
   a.gamma = (float)x.lay->S[l] * x.dt;
   a.propagator = x.c->propagator;
-  a.bf16 = x.c->dtype;      // the enum values are the kernels' operand forms
+  a.bf16 = kform(x.c->dtype);
+  a.one_term = one_term(x.c->dtype);
   return a;
 }
 
@@ -454,7 +462,7 @@ static int run_projection(const mgrit_gru_cfg* c, const Layout& lay, char* base,
   const int width = c->propagator == PROP_ODE_DEMO ? c->H
                     : prop_is_lstm(c->propagator) ? 2 * c->H : 3 * c->H;
   CHECK_HIP(launch_projection(x, W, b_i, (float*)(base + lay.P), (long long)c->T * c->B, width,
-                              c->D, c->dtype, s));
+                              c->D, kform(c->dtype), s));
   return MGRIT_OK;
 }
 
@@ -581,7 +589,8 @@ static AdjArgs adj_base(const BwdCtx& x, int l) {
   a.g = x.gl[l];
   a.B = x.c->B;
   a.H = x.c->H;
-  a.bf16 = x.c->dtype;
+  a.bf16 = kform(x.c->dtype);
+  a.one_term = one_term(x.c->dtype);
   return a;
 }
 
@@ -744,7 +753,7 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
   (void)hipGetLastError();   // an error left by earlier, unrelated work is not this call's
 
   if ((rc = run_projection(&c, lay, base, W, b_i, x, s))) return rc;
-  const int bf16 = c.dtype == MGRIT_BF16;
+  const int bf16 = kform(c.dtype) == 1;
   CHECK_HIP(launch_transpose(U, base + lay.UT, 3 * c.H, c.H, bf16, s));
   if (c.dtype == MGRIT_F32_BF16X3) {
     CHECK_HIP(launch_split3((const float*)U, base + lay.U3, 3LL * c.H * c.H, s));
@@ -772,7 +781,8 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
     std::memset(&a, 0, sizeof(a));
     a.U = U;
     a.U3 = base + lay.U3;
-    a.bf16 = c.dtype;
+    a.bf16 = kform(c.dtype);
+    a.one_term = one_term(c.dtype);
     a.b_h = b_h;
     a.P = P;
     a.u_in = h;
@@ -823,7 +833,8 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
   if (resnorm && !serial) CHECK_HIP(launch_sqrt_to_float(norm, resnorm, c.iters, s));
   if (ngrad == 4)
     CHECK_HIP(launch_param_grads(ctx.kap[0], w, h, x, dW, dU, db_i, db_h,
-                                 (float*)(base + lay.part), c.T, c.B, c.D, c.H, c.dtype, s));
+                                 (float*)(base + lay.part), c.T, c.B, c.D, c.H, kform(c.dtype),
+                                 one_term(c.dtype), s));
   if (dx) {
     CHECK_HIP(launch_transpose(W, base + lay.WT, 3 * c.H, c.D, bf16, s));
     const void* WT = base + lay.WT;
@@ -831,7 +842,8 @@ static int backward_impl(const mgrit_gru_cfg* cin, bool serial, const void* W, c
       CHECK_HIP(launch_split3((const float*)WT, base + lay.W3, 3LL * c.H * c.D, s));
       WT = base + lay.W3;
     }
-    CHECK_HIP(launch_input_grads(ctx.kap[0], w, WT, dx, c.T, c.B, c.D, c.H, c.dtype, s));
+    CHECK_HIP(launch_input_grads(ctx.kap[0], w, WT, dx, c.T, c.B, c.D, c.H, kform(c.dtype),
+                                 one_term(c.dtype), s));
   }
   return MGRIT_OK;
 }

@@ -78,6 +78,8 @@ struct PhiArgs {
   // Phi_c(R u')_k + g_k = (R u')_k - (R r)_k by the definition of g (Eq. 11): no evaluation
   // of Phi is needed for it.
   int ff_cf, ff_rem;
+  int one_term;        // bf16 == 1: the fp32 state operand goes to the MFMAs as one bf16 term
+                       // (rounded) instead of two (hi + lo); tile kernels only
 };
 
 // One launch of the fused adjoint step  w_out = (dPhi/dh)^T w_in  over nk points.
@@ -99,6 +101,7 @@ struct AdjArgs {
                        // coarse error equation, except at the coarse points of index ff_rem
                        // modulo ff_cf (ff_cf > 0), which receive -r: the value the coarse level's
                        // first relaxation sub-step gives from that guess
+  int one_term;        // as in PhiArgs (the operand kappa * w)
 };
 
 // Internal propagator code (beside the public MGRIT_PROP_* values): the forward-Euler
@@ -133,16 +136,17 @@ hipError_t launch_transpose(const void* U, void* UT, int rows, int cols, int bf1
 // (row t = step t), the adjoint w[(T+1),B,H], the states h[(T+1),B,H] and x[T,B,D].
 // part: scratch of grad_partial_floats(...) floats.
 size_t grad_partial_floats(int T, int B, int D, int H, int bf16);
-// x: float (bf16 = 0) or bf16 (bf16 = 1)
+// x: float (bf16 = 0) or bf16 (bf16 = 1); one_term: as in PhiArgs (the wide bf16 kernel only;
+// the narrow one keeps two terms)
 hipError_t launch_param_grads(const float* kap0, const float* w, const float* h, const void* x,
                               float* dW, float* dU, float* db_i, float* db_h, float* part,
-                              int T, int B, int D, int H, int bf16, hipStream_t s);
+                              int T, int B, int D, int H, int bf16, int one_term, hipStream_t s);
 
 // Input gradients dx[T,B,D] from the level-0 coefficients, the adjoint w and the
 // transposed input weights WT[D,3H] (float, or bf16 with bf16 = 1, or its three bf16 terms
 // [3][D,3H] with bf16 = 2).
 hipError_t launch_input_grads(const float* kap0, const float* w, const void* WT, float* dx, int T,
-                              int B, int D, int H, int bf16, hipStream_t s);
+                              int B, int D, int H, int bf16, int one_term, hipStream_t s);
 
 // dst[t][i] (t = 0..2, bf16) = t-th term of src[i]: src = dst[0] + dst[1] + dst[2] exactly
 // unless a term underflows; n a multiple of 4

@@ -297,6 +297,7 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void adj_step_kernel_bf16(AdjArgs 
 // ---------------------------------------------------------------------------
 typedef TileCfg<2, 2, 2, 2, 1> DxCfg;            // 128 x 128 tile
 typedef TileCfgB<2, 2, 2, 2, 1, true> DxCfgB;
+typedef TileCfgB<2, 2, 2, 2, 1, true, 1, 1, 2, 1, 64, false, false> DxCfgF;   // kappa * w as one bf16 term
 typedef TileCfgB<4, 2, 1, 2, 1, true, 1, 1, 2, 3, 32> DxCfgS;     // 8 waves of 32 x 64
 
 // Stores one accumulator tile of a plain GEMM: out[m, n], leading dimension N.
@@ -422,11 +423,16 @@ __global__ __launch_bounds__(C::NT, C::NT > 256 ? 2 : 1) void input_grad_kernel_
 }
 
 hipError_t launch_input_grads(const float* kap0, const float* w, const void* WT, float* dx, int T,
-                              int B, int D, int H, int bf16, hipStream_t s) {
+                              int B, int D, int H, int bf16, int one_term, hipStream_t s) {
   const long long R = (long long)T * B;
   prof_begin(6, s);
   if (bf16 == 2) {
     typedef DxCfgS C;
+    dim3 grid((unsigned)xcd_grid((R + C::TM - 1) / C::TM, (D + C::TN - 1) / C::TN));
+    hipLaunchKernelGGL(input_grad_kernel_bf16<C>, grid, dim3(C::NT), 0, s, kap0, w,
+                       (const bf16_t*)WT, dx, R, B, H, D);
+  } else if (bf16 && one_term) {
+    typedef DxCfgF C;
     dim3 grid((unsigned)xcd_grid((R + C::TM - 1) / C::TM, (D + C::TN - 1) / C::TN));
     hipLaunchKernelGGL(input_grad_kernel_bf16<C>, grid, dim3(C::NT), 0, s, kap0, w,
                        (const bf16_t*)WT, dx, R, B, H, D);
@@ -525,6 +531,10 @@ typedef TileCfg<1, 1, 1, 1, 1, 128, 1, 4> AdjSmall;  //  32 x 32, 4 waves splitt
 typedef TileCfgB<4, 2, 1, 2, 1, true, 1, 1, 2> AdjBigB;
 typedef TileCfgB<2, 2, 1, 1, 1, true> AdjMidB;
 typedef TileCfgB<1, 1, 1, 1, 1, true, 4> AdjSmallB;
+// the same tiles with kappa * w as one bf16 term
+typedef TileCfgB<4, 2, 1, 2, 1, true, 1, 1, 2, 1, 64, false, false> AdjBigF;
+typedef TileCfgB<2, 2, 1, 1, 1, true, 1, 1, 2, 1, 64, false, false> AdjMidF;
+typedef TileCfgB<1, 1, 1, 1, 1, true, 4, 1, 2, 1, 64, false, false> AdjSmallF;
 // three-term operands (K-slices of 32)
 typedef TileCfgB<2, 2, 2, 2, 1, true, 1, 1, 2, 3, 32> AdjBigS;
 // the same tile with 8 waves of 32 x 64 each: half the accumulators per wave, so that two
@@ -534,11 +544,12 @@ typedef TileCfgB<4, 2, 1, 2, 1, true, 1, 1, 2, 3, 32> AdjBigS8;
 typedef TileCfgB<2, 2, 1, 1, 1, true, 1, 1, 2, 3, 32> AdjMidS;
 typedef TileCfgB<1, 1, 1, 1, 1, true, 4, 1, 2, 3, 32> AdjSmallS;
 
-template <class C, class CB, class CS>
+template <class C, class CB, class CS, class CF>
 static void launch_adj_cfg(const AdjArgs& a, hipStream_t s) {
   const long long R = (long long)a.nk * a.B;
   dim3 grid((unsigned)xcd_grid((R + C::TM - 1) / C::TM, (a.H + C::TN - 1) / C::TN));
   dim3 block(a.bf16 == 2 ? CS::NT : a.bf16 ? CB::NT : C::NT);
+  static_assert(CF::TM == CB::TM && CF::TN == CB::TN && CF::NT == CB::NT, "tile shapes must agree");
   static_assert(C::TM == CB::TM && C::TN == CB::TN, "tile shapes must agree");
   static_assert(C::TM == CS::TM && C::TN == CS::TN, "tile shapes must agree");
   static_assert(AdjBigS8::TM == AdjBigS::TM && AdjBigS8::TN == AdjBigS::TN, "tile shapes must agree");
@@ -550,6 +561,11 @@ static void launch_adj_cfg(const AdjArgs& a, hipStream_t s) {
       hipLaunchKernelGGL((adj_step_kernel_bf16<CS, STEP_RELAX>), grid, block, 0, s, a);
     else
       hipLaunchKernelGGL((adj_step_kernel_bf16<CS, STEP_RESID>), grid, block, 0, s, a);
+  } else if (a.bf16 && a.one_term) {
+    if (a.mode == STEP_RELAX)
+      hipLaunchKernelGGL((adj_step_kernel_bf16<CF, STEP_RELAX>), grid, block, 0, s, a);
+    else
+      hipLaunchKernelGGL((adj_step_kernel_bf16<CF, STEP_RESID>), grid, block, 0, s, a);
   } else if (a.bf16) {
     if (a.mode == STEP_RELAX)
       hipLaunchKernelGGL((adj_step_kernel_bf16<CB, STEP_RELAX>), grid, block, 0, s, a);
@@ -611,11 +627,11 @@ hipError_t launch_adj_step(const AdjArgs& a, hipStream_t s) {
     else
       launch_adj_skinny<1>(a, grid, s);
   } else if (tiles(AdjBig::TM, AdjBig::TN) >= (a.bf16 == 1 ? 256 : 384))
-    launch_adj_cfg<AdjBig, AdjBigB, AdjBigS>(a, s);
+    launch_adj_cfg<AdjBig, AdjBigB, AdjBigS, AdjBigF>(a, s);
   else if (R > 32 && tiles(AdjMid::TM, AdjMid::TN) >= 256)
-    launch_adj_cfg<AdjMid, AdjMidB, AdjMidS>(a, s);
+    launch_adj_cfg<AdjMid, AdjMidB, AdjMidS, AdjMidF>(a, s);
   else
-    launch_adj_cfg<AdjSmall, AdjSmallB, AdjSmallS>(a, s);
+    launch_adj_cfg<AdjSmall, AdjSmallB, AdjSmallS, AdjSmallF>(a, s);
   prof_end(kind, 6.0 * (double)R * a.H * a.H, 28.0 * (double)R * a.H, s);
   return hipGetLastError();
 }
@@ -1071,10 +1087,13 @@ __device__ inline void split_bf16_4(const floatx4& v, bf16x4& hi, bf16x4& lo) {
   }
 }
 
-template <bool B_BF16>
+// ONE: S and an fp32 second operand enter as one bf16 term each (dtype MGRIT_BF16); otherwise as
+// hi + lo, with the products S_hi B_hi + S_lo B_hi (+ S_hi B_lo for an fp32 second operand).
+template <bool B_BF16, bool ONE>
 __global__ __launch_bounds__(256, 2) void grad_gemm_tr_kernel(GradArgs a) {
-  constexpr int NBT = B_BF16 ? 1 : 2;     // tiles of the second operand in LDS (hi, lo)
-  __shared__ __attribute__((aligned(16))) bf16_t As[2][TR_TK * TR_LDA];
+  constexpr int NBT = (B_BF16 || ONE) ? 1 : 2;     // tiles of the second operand in LDS (hi, lo)
+  constexpr int NAT = ONE ? 1 : 2;                 // tiles of S
+  __shared__ __attribute__((aligned(16))) bf16_t As[NAT][TR_TK * TR_LDA];
   __shared__ __attribute__((aligned(16))) bf16_t Bs[NBT][TR_TK * TR_LDB];
   const int H = a.H, N = a.N, M = 3 * a.H;
   const int tiles = a.mtiles * a.ntiles;
@@ -1149,7 +1168,7 @@ __global__ __launch_bounds__(256, 2) void grad_gemm_tr_kernel(GradArgs a) {
       bf16x4 hi, lo;
       split_bf16_4(p, hi, lo);
       *reinterpret_cast<bf16x4*>(&As[0][row * TR_LDA + m4 * 4]) = hi;
-      *reinterpret_cast<bf16x4*>(&As[1][row * TR_LDA + m4 * 4]) = lo;
+      if constexpr (!ONE) *reinterpret_cast<bf16x4*>(&As[NAT - 1][row * TR_LDA + m4 * 4]) = lo;
       if constexpr (B_BF16) {
         bf16x8 zv;
 #pragma unroll
@@ -1165,7 +1184,7 @@ __global__ __launch_bounds__(256, 2) void grad_gemm_tr_kernel(GradArgs a) {
         bf16x4 hi, lo;
         split_bf16_4(v, hi, lo);
         *reinterpret_cast<bf16x4*>(&Bs[0][row * TR_LDB + c4 * 4]) = hi;
-        *reinterpret_cast<bf16x4*>(&Bs[NBT - 1][row * TR_LDB + c4 * 4]) = lo;
+        if constexpr (!ONE) *reinterpret_cast<bf16x4*>(&Bs[NBT - 1][row * TR_LDB + c4 * 4]) = lo;
       }
     }
   };
@@ -1187,9 +1206,9 @@ __global__ __launch_bounds__(256, 2) void grad_gemm_tr_kernel(GradArgs a) {
       __builtin_amdgcn_s_setprio(2);
 #pragma unroll
       for (int c = 0; c < TR_TK / 16; ++c) {
-        bf16x8 fa[2][2], fb[NBT][4];
+        bf16x8 fa[NAT][2], fb[NBT][4];
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < NAT; ++t)
 #pragma unroll
           for (int i = 0; i < 2; ++i)
             fa[t][i] = lds_tr8(&As[t][a_off + c * 16 * TR_LDA + i * 32], TR_LDA);
@@ -1203,8 +1222,9 @@ __global__ __launch_bounds__(256, 2) void grad_gemm_tr_kernel(GradArgs a) {
 #pragma unroll
           for (int i = 0; i < 2; ++i) {
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][i], fb[0][j], acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[1][i], fb[0][j], acc[i][j], 0, 0, 0);
-            if constexpr (!B_BF16)
+            if constexpr (!ONE)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[NAT - 1][i], fb[0][j], acc[i][j], 0, 0, 0);
+            if constexpr (!B_BF16 && !ONE)
               acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][i], fb[NBT - 1][j], acc[i][j], 0, 0, 0);
           }
       }
@@ -1492,7 +1512,7 @@ size_t grad_partial_floats(int T, int B, int D, int H, int bf16) {
 
 hipError_t launch_param_grads(const float* kap0, const float* w, const float* h, const void* x,
                               float* dW, float* dU, float* db_i, float* db_h, float* part,
-                              int T, int B, int D, int H, int bf16, hipStream_t s) {
+                              int T, int B, int D, int H, int bf16, int one_term, hipStream_t s) {
   const long long Ktot = (long long)T * B;
   const int M = 3 * H;
   prof_begin(3, s);
@@ -1526,10 +1546,14 @@ hipError_t launch_param_grads(const float* kap0, const float* w, const float* h,
     dim3 grid((unsigned)((long long)a.mtiles * a.ntiles * splits));
     if (bf16 == 2)
       hipLaunchKernelGGL(grad_gemm_x3_kernel, grid, dim3(256), 0, s, a);
+    else if (bf16 && gn == TR_GN && which == 1 && one_term)
+      hipLaunchKernelGGL((grad_gemm_tr_kernel<true, true>), grid, dim3(256), 0, s, a);
+    else if (bf16 && gn == TR_GN && one_term)
+      hipLaunchKernelGGL((grad_gemm_tr_kernel<false, true>), grid, dim3(256), 0, s, a);
     else if (bf16 && gn == TR_GN && which == 1)
-      hipLaunchKernelGGL(grad_gemm_tr_kernel<true>, grid, dim3(256), 0, s, a);
+      hipLaunchKernelGGL((grad_gemm_tr_kernel<true, false>), grid, dim3(256), 0, s, a);
     else if (bf16 && gn == TR_GN)
-      hipLaunchKernelGGL(grad_gemm_tr_kernel<false>, grid, dim3(256), 0, s, a);
+      hipLaunchKernelGGL((grad_gemm_tr_kernel<false, false>), grid, dim3(256), 0, s, a);
     else if (bf16 && which == 1)
       hipLaunchKernelGGL(grad_gemm_bf16_kernel<true>, grid, dim3(256), 0, s, a);
     else if (bf16)

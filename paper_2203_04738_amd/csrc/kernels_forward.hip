@@ -869,6 +869,10 @@ typedef TileCfg<1, 1, 1, 1, 3, 128, 1, 4> PhiSmall;
 typedef TileCfgB<2, 2, 2, 1, 3, true> PhiBigB;
 typedef TileCfgB<2, 2, 1, 1, 3, true> PhiMidB;
 typedef TileCfgB<1, 1, 1, 1, 3, true, 4> PhiSmallB;
+// the same tiles with the state as one bf16 term
+typedef TileCfgB<2, 2, 2, 1, 3, true, 1, 1, 2, 1, 64, false, false> PhiBigF;
+typedef TileCfgB<2, 2, 1, 1, 3, true, 1, 1, 2, 1, 64, false, false> PhiMidF;
+typedef TileCfgB<1, 1, 1, 1, 3, true, 4, 1, 2, 1, 64, false, false> PhiSmallF;
 // three-term operands: K-slices of 32 keep two workgroups' tiles in a CU's LDS
 typedef TileCfgB<2, 2, 2, 1, 3, true, 1, 1, 2, 3, 32> PhiBigS;
 typedef TileCfgB<2, 2, 1, 1, 3, true, 1, 1, 2, 3, 32> PhiMidS;
@@ -907,13 +911,18 @@ typedef TileCfgB<1, 1, 1, 1, 3, true, 4, 1, 2, 3, 32> PhiSmallS;
       hipLaunchKernelGGL((KERNEL<__VA_ARGS__, STEP_KAPPA>), grid, block, 0, s, a);       \
   }
 
-template <class C, class CB, class CS>
+template <class C, class CB, class CS, class CF>
 static void launch_phi_cfg(const PhiArgs& a, hipStream_t s) {
   const long long R = (long long)a.nk * a.B;
+  static_assert(CF::TM == CB::TM && CF::TN == CB::TN, "tile shapes must agree");
   if (a.bf16 == 2) {
     dim3 grid((unsigned)xcd_grid((R + CS::TM - 1) / CS::TM, (a.H + CS::TN - 1) / CS::TN));
     dim3 block(CS::NT);
     MG_LAUNCH_BY_MODE(phi_step_kernel_bf16, CS)
+  } else if (a.bf16 && a.one_term) {
+    dim3 grid((unsigned)xcd_grid((R + CF::TM - 1) / CF::TM, (a.H + CF::TN - 1) / CF::TN));
+    dim3 block(CF::NT);
+    MG_LAUNCH_BY_MODE(phi_step_kernel_bf16, CF)
   } else if (a.bf16) {
     dim3 grid((unsigned)xcd_grid((R + CB::TM - 1) / CB::TM, (a.H + CB::TN - 1) / CB::TN));
     dim3 block(CB::NT);
@@ -1020,13 +1029,13 @@ hipError_t launch_phi_step(const PhiArgs& a, hipStream_t s) {
       launch_phi_skinny<1>(a, grid, s);
   } else if (tiles(PhiBig::TM, PhiBig::TN) >= 384) {
     contracted(PhiBig::TM);
-    launch_phi_cfg<PhiBig, PhiBigB, PhiBigS>(a, s);
+    launch_phi_cfg<PhiBig, PhiBigB, PhiBigS, PhiBigF>(a, s);
   } else if (R > 32 && tiles(PhiMid::TM, PhiMid::TN) >= 128) {
     contracted(PhiMid::TM);
-    launch_phi_cfg<PhiMid, PhiMidB, PhiMidS>(a, s);
+    launch_phi_cfg<PhiMid, PhiMidB, PhiMidS, PhiMidF>(a, s);
   } else {
     contracted(PhiSmall::TM);
-    launch_phi_cfg<PhiSmall, PhiSmallB, PhiSmallS>(a, s);
+    launch_phi_cfg<PhiSmall, PhiSmallB, PhiSmallS, PhiSmallF>(a, s);
   }
   prof_end(kind, 6.0 * (double)rows_done * a.H * a.H, 20.0 * (double)R * a.H, s);
   return hipGetLastError();

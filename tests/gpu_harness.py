@@ -19,7 +19,7 @@ def to_dev(d, dtype="fp32"):
         if k == "labels":
             continue
         tv = torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(DEV)
-        if dtype == "bf16" and k in ("x", "W", "U"):
+        if dtype in ("bf16", "bf16s2") and k in ("x", "W", "U"):
             tv = tv.to(torch.bfloat16)
         t[k] = tv
     return t
@@ -32,7 +32,7 @@ class GpuRun:
         H = d["U"].shape[1]
         self.T, self.B, self.D, self.H = T, B, D, H
         self.kw = dict(cf=cf, levels=levels, fine_relax=fine_relax, propagator=propagator,
-                       dtype={"fp32": 0, "bf16": 1, "fp32x3": 2}[dtype])
+                       dtype={"fp32": 0, "bf16": 1, "fp32x3": 2, "bf16s2": 3}[dtype])
         cfg = self.cfg(iters=64)
         self.ws = torch.empty(mg.mgrit_gru_workspace_bytes(cfg), dtype=torch.uint8, device=DEV)
 

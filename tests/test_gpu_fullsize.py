@@ -36,13 +36,14 @@ def _P(d):
 
 def _dtype(wl, form):
     """Operand form of the run: the workload's own, or fp32 values contracted as three bf16
-    terms ("fp32x3": same inputs and the same bar as fp32)."""
+    terms ("fp32x3": same inputs and the same bar as fp32), or the bf16 workload with its fp32
+    state operand as two bf16 terms ("bf16s2": same inputs and the same bar as "bf16")."""
     return form or wl.dtype
 
 
 @pytest.mark.parametrize("name,window,form", [("C2", 1024, None), ("C3", 128, None), ("C4", 128, None),
                                               ("C5", 256, None), ("C3", 128, "fp32x3"),
-                                              ("C5", 256, "fp32x3")])
+                                              ("C5", 256, "fp32x3"), ("C4", 128, "bf16s2")])
 def test_full_size_forward_window_and_serial_prefix(gh, name, window, form):
     wl = WORKLOADS[name]
     d = make_inputs(wl)
@@ -70,7 +71,8 @@ def test_full_size_forward_window_and_serial_prefix(gh, name, window, form):
 
 
 @pytest.mark.parametrize("name,window,form", [("C3", 128, None), ("C4", 128, None), ("C5", 256, None),
-                                              ("C3", 128, "fp32x3"), ("C5", 256, "fp32x3")])
+                                              ("C3", 128, "fp32x3"), ("C5", 256, "fp32x3"),
+                                              ("C4", 128, "bf16s2")])
 def test_full_size_backward_window(gh, name, window, form):
     wl = WORKLOADS[name]
     d = make_inputs(wl)
@@ -92,7 +94,7 @@ def test_full_size_backward_window(gh, name, window, form):
 
 
 @pytest.mark.parametrize("name,form", [("C3", None), ("C4", None), ("C5", None), ("C3", "fp32x3"),
-                                       ("C5", "fp32x3")])
+                                       ("C5", "fp32x3"), ("C4", "bf16s2")])
 def test_full_size_gradients_and_input_gradients_on_a_sparse_adjoint(gh, name, form):
     """Gradient GEMMs, bias sums and the input-gradient GEMM at full size, element by
     element.  With zero cycles the entry point forms the gradients from the adjoint it is

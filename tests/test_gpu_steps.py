@@ -129,15 +129,17 @@ def test_mgrit_backward_with_source_several_cycles_per_call_and_mfma_rows(gh):
     _check_mgrit_steps(gh, d, _source(8, T, B, H, scale=0.1), 4, 3, 2, per_call=2)
 
 
-def test_bf16_backward_with_source_and_dx(gh):
+@pytest.mark.parametrize("form", ["bf16", "bf16s2"])
+def test_bf16_backward_with_source_and_dx(gh, form):
     T, B, D, H = 48, 3, 24, 40
+    TIGHT_BF16 = 1e-4 if form == "bf16s2" else TOL_BF16
     d = dict(random_small(43, T, B, D, H, scale=0.3))
     for k in ("x", "W", "U"):
         d[k] = round_to_bf16(d[k])      # the oracle sees exactly the stored bf16 values
     src = _source(5, T, B, H)
     h = orc.serial_scan(*_P(d), d["x"], d["h0"]).astype(np.float32)
     ref = orc.serial_bptt_steps(*_P(d), d["x"], h, src)
-    run = gh.GpuRun(d, cf=4, levels=2, dtype="bf16")
+    run = gh.GpuRun(d, cf=4, levels=2, dtype=form)
     got = run.serial_backward_steps(h, src)
     for name, g, r in zip(NAMES, got, ref):
         e = gh.rel_err(g, r)
@@ -223,7 +225,7 @@ def test_two_layer_stack_forward_and_backward(gh):
             s[1:] = got[5]
 
 
-@pytest.mark.parametrize("dtype", ["fp32", "bf16", "fp32x3"])
+@pytest.mark.parametrize("dtype", ["fp32", "bf16", "bf16s2", "fp32x3"])
 def test_step_loss_backward_reusing_projection_and_coefficients(gh, dtype):
     """The call sequence of the stacked training step: the forward solve keeps the
     projection and the coefficients of its closing relaxation in the workspace, the
@@ -234,8 +236,8 @@ def test_step_loss_backward_reusing_projection_and_coefficients(gh, dtype):
                                               MGRIT_REUSE_PROJECTION)
     T, B, D, H, cf, levels = 96, 5, 24, 40, 4, 3
     d = dict(random_small(47, T, B, D, H, scale=0.3))
-    tol, tight = (TOL_BF16, TIGHT_BF16) if dtype == "bf16" else (TOL, TOL)
-    if dtype == "bf16":
+    tol, tight = (TOL_BF16, TIGHT_BF16 if dtype == "bf16s2" else TOL_BF16) if dtype.startswith("bf16") else (TOL, TOL)
+    if dtype.startswith("bf16"):
         for k in ("x", "W", "U"):
             d[k] = round_to_bf16(d[k])
     src = _source(13, T, B, H)

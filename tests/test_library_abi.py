@@ -65,7 +65,12 @@ def test_workspace_size_and_validation_codes():
     assert _ws(MgritGruCfg(64, 2, 16, 36, cf=4, levels=2, dtype=2))[0] == -6
     rc2, n2 = _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, iters=3, dtype=2))
     assert rc2 == 0 and n2 >= n + 18 * 32 * (2 * 32 + 16)
-    assert _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, dtype=3))[0] == -4
+    # both bf16 forms: the same workspace, widths in multiples of 8
+    rc3, n3 = _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, iters=3, dtype=3))
+    rc1, n1 = _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, iters=3, dtype=1))
+    assert rc3 == 0 and rc1 == 0 and n3 == n1
+    assert _ws(MgritGruCfg(64, 2, 16, 36, cf=4, levels=2, dtype=3))[0] == -6
+    assert _ws(MgritGruCfg(64, 2, 16, 32, cf=4, levels=2, dtype=4))[0] == -4
     assert mg.lib().mgrit_gru_workspace_bytes(None, None) == -1
 
 

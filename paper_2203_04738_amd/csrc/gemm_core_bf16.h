@@ -76,15 +76,11 @@ __device__ inline void split_bf16(const F32x8& v, bf16x8& hi, bf16x8& lo) {
 // is planned for.
 // NP: 1 = operands as stored (A optionally in two terms), 3 = three terms per operand.
 // TKB: elements per K-slice and K-split group.
-// DB: two LDS slice sets.  The slice after the current one is split and written into the other
-// set while the MFMAs of the current one run (the staging instructions are spread between the
-// MFMAs of the same wave), and a slice needs one barrier instead of two.
 // A2: an fp32 operand A goes to the MFMAs as two bf16 terms (hi + lo); false: as one, rounded
 // to nearest (what mixed-precision training feeds its matrix pipe).
 template <int WM_, int WN_, int BM_, int BN_, int NG_, bool SPLIT_A_, int KS_ = 1, int DEPTH_ = 1,
-          int MINWG_ = 2, int NP_ = 1, int TKB_ = 64, bool DB_ = false, bool A2_ = true>
+          int MINWG_ = 2, int NP_ = 1, int TKB_ = 64, bool A2_ = true>
 struct TileCfgB {
-  static constexpr bool DB = DB_;
   static constexpr int WM = WM_, WN = WN_, BM = BM_, BN = BN_, NG = NG_;
   static constexpr bool SPLIT_A = SPLIT_A_;
   static constexpr int DEPTH = DEPTH_, MINWG = MINWG_;
@@ -108,9 +104,7 @@ struct TileCfgB {
   static constexpr int CPR = TK / 8;            // 16-byte chunks per tile row
   static constexpr int A_CHUNKS = (TM * CPR) / NT;
   static constexpr int B_CHUNKS = (BROWS * CPR) / NT;
-  static constexpr int BUF_ELEMS = (NA * TM + NBP * BROWS) * LD;   // one slice set
-  static constexpr int LDS_ELEMS = (DB ? 2 : 1) * BUF_ELEMS;
-  static_assert(!DB || (NP == 1 && KS == 1 && DEPTH <= 2), "two slice sets: plain operands, no K-split");
+  static constexpr int LDS_ELEMS = (NA * TM + NBP * BROWS) * LD;
   static_assert(SPLIT_A || NP == 1, "three-term operands are fp32 in memory");
   static_assert((TM * CPR) % NT == 0 && (BROWS * CPR) % NT == 0, "tile rows must divide evenly");
 };
@@ -150,34 +144,28 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
   decltype(loadA(0, 0)) ra[DP][C::A_CHUNKS];
   decltype(loadB(0, 0)) rb[DP][C::B_CHUNKS];
 
-  auto fetch_part = [&](int d, int k0, int part, int nparts) {
+  auto fetch = [&](int d, int k0) {
 #pragma unroll
     for (int s = 0; s < C::A_CHUNKS; ++s) {
-      if (s % nparts != part) continue;
       int k = k0 + ((tid + s * C::NT) % C::CPR) * 8;
       if (KTAIL && k >= K) k = K - 8;
       ra[d][s] = loadA(s, k);
     }
 #pragma unroll
     for (int s = 0; s < C::B_CHUNKS; ++s) {
-      if (s % nparts != part) continue;
       int k = k0 + ((tid + s * C::NT) % C::CPR) * 8;
       if (KTAIL && k >= K) k = K - 8;
       rb[d][s] = loadB(s, k);
     }
   };
-  auto fetch = [&](int d, int k0) { fetch_part(d, k0, 0, 1); };
   bf16_t* As = lds;                               // hi (or only) A tile, then lo tile
   bf16_t* Bs = lds + C::NA * C::TM * C::LD;
-  // part / nparts: only the chunks s with s % nparts == part (the two-set loop spreads the
-  // staging of a slice over the k-groups of the one before it)
-  auto stash_part = [&](int d, int k0, bf16_t* As, bf16_t* Bs, int part, int nparts) {
+  auto stash = [&](int d, int k0) {
     bf16x8 z;
 #pragma unroll
     for (int i = 0; i < 8; ++i) z[i] = (__bf16)0.f;
 #pragma unroll
     for (int s = 0; s < C::A_CHUNKS; ++s) {
-      if (s % nparts != part) continue;
       const int q = tid + s * C::NT;
       const int off = (q / C::CPR) * C::LD + swz_chunk<C>(q / C::CPR, q % C::CPR) * 8;
       const bool dead = KTAIL && k0 + (q % C::CPR) * 8 >= K;
@@ -199,7 +187,6 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
     }
 #pragma unroll
     for (int s = 0; s < C::B_CHUNKS; ++s) {
-      if (s % nparts != part) continue;
       const int q = tid + s * C::NT;
       const bool dead = KTAIL && k0 + (q % C::CPR) * 8 >= K;
 #pragma unroll
@@ -209,7 +196,6 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
             dead ? z : operand_term(rb[d][s], u);
     }
   };
-  auto stash = [&](int d, int k0) { stash_part(d, k0, As, Bs, 0, 1); };
   const int a_off = ((wm * C::BM) * 32 + li) * C::LD + lh * 8 + ks * NC * 16;
   const int b_off = ((wn * C::BN) * 32 + li) * C::LD + lh * 8 + ks * NC * 16;
   auto read_frags = [&](int c, bf16x8 (&fa)[NFA], bf16x8 (&fb)[NFB]) {
@@ -246,80 +232,6 @@ __device__ inline void gemm_nt_tile_bf16(Acc<C>& acc, int K, LoadA loadA, LoadB 
   };
 
   const int nkt = (K + C::TK - 1) / C::TK;
-  if constexpr (C::DB) {
-    constexpr int ABUF = C::NA * C::TM * C::LD;
-    auto frags_of = [&](const bf16_t* base, int c, bf16x8 (&fa)[NFA], bf16x8 (&fb)[NFB]) {
-#pragma unroll
-      for (int t = 0; t < C::NA; ++t)
-#pragma unroll
-        for (int a = 0; a < C::BM; ++a)
-          fa[t * C::BM + a] = *reinterpret_cast<const bf16x8*>(
-              &base[t * C::TM * C::LD + a_off + a * 32 * C::LD + c * 16]);
-#pragma unroll
-      for (int g = 0; g < C::NG; ++g)
-#pragma unroll
-        for (int b = 0; b < C::BN; ++b)
-          fb[g * C::BN + b] = *reinterpret_cast<const bf16x8*>(
-              &base[ABUF + b_off + (g * C::TN + b * 32) * C::LD + c * 16]);
-    };
-#pragma unroll
-    for (int d = 0; d < DP; ++d)
-      if (d < nkt) fetch(d, d * C::TK);
-    stash(0, 0);                                   // slice 0 -> set 0
-    if (DP < nkt) fetch(0, DP * C::TK);            // its registers are free again
-    __syncthreads();
-    for (int kt0 = 0; kt0 < nkt; kt0 += 2) {
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int kt = kt0 + u;
-        if (kt < nkt) {
-        bf16_t* cur = lds + u * C::BUF_ELEMS;
-        bf16_t* nxt = lds + (u ^ 1) * C::BUF_ELEMS;
-        constexpr int NM = C::NA * C::BM * NB;      // MFMAs of a k-group
-        const int dn = (u + 1) % DP;                // registers of slice kt + 1
-        bf16x8 fa[2][NFA];
-        bf16x8 fb[2][NFB];
-        __builtin_amdgcn_sched_barrier(0);
-        frags_of(cur, 0, fa[0], fb[0]);
-        // The k-groups of the first half also stage slice kt + 1 (registers -> LDS), those of
-        // the second half request slice kt + 1 + DP into the registers just freed: the loads are
-        // issued one at a time between the MFMAs instead of as a burst that queues at the
-        // CU's address unit and holds the wave (and its MFMAs) back.
-        constexpr int NCS = NC / 2 > 0 ? NC / 2 : 1;    // k-groups that stage
-        constexpr int NCF = NC - NCS > 0 ? NC - NCS : 1;
-        // Staging and loads are unconditional, so that they share a basic block with the MFMAs:
-        // past the end the last slice is loaded again and staged into the set nobody reads.
-        const int kst = (kt + 1 < nkt ? kt + 1 : nkt - 1) * C::TK;
-        const int kld = (kt + 1 + DP < nkt ? kt + 1 + DP : nkt - 1) * C::TK;
-#pragma unroll
-        for (int c = 0; c < NC; ++c) {
-          if (c + 1 < NC) frags_of(cur, c + 1, fa[(c + 1) & 1], fb[(c + 1) & 1]);
-          mma(fa[c & 1], fb[c & 1]);
-          if (c < NCS) {
-            stash_part(dn, kst, nxt, nxt + ABUF, c, NCS);
-            if (NC == 1) fetch(dn, kld);
-          } else {
-            fetch_part(dn, kld, c - NCS, NCF);
-          }
-#pragma unroll
-          for (int i = 0; i < NM; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x080, 1, 0);
-            if (c < NCS) {
-              __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
-            } else {
-              __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
-              __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-            }
-          }
-          __builtin_amdgcn_sched_barrier(0);
-        }
-        __syncthreads();
-        }
-      }
-    }
-    return;
-  }
 #pragma unroll
   for (int d = 0; d < DP; ++d)
     if (d < nkt) fetch(d, d * C::TK);

@@ -297,7 +297,7 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void adj_step_kernel_bf16(AdjArgs 
 // ---------------------------------------------------------------------------
 typedef TileCfg<2, 2, 2, 2, 1> DxCfg;            // 128 x 128 tile
 typedef TileCfgB<2, 2, 2, 2, 1, true> DxCfgB;
-typedef TileCfgB<2, 2, 2, 2, 1, true, 1, 1, 2, 1, 64, false, false> DxCfgF;   // kappa * w as one bf16 term
+typedef TileCfgB<2, 2, 2, 2, 1, true, 1, 1, 2, 1, 64, false> DxCfgF;   // kappa * w as one bf16 term
 typedef TileCfgB<4, 2, 1, 2, 1, true, 1, 1, 2, 3, 32> DxCfgS;     // 8 waves of 32 x 64
 
 // Stores one accumulator tile of a plain GEMM: out[m, n], leading dimension N.
@@ -532,9 +532,9 @@ typedef TileCfgB<4, 2, 1, 2, 1, true, 1, 1, 2> AdjBigB;
 typedef TileCfgB<2, 2, 1, 1, 1, true> AdjMidB;
 typedef TileCfgB<1, 1, 1, 1, 1, true, 4> AdjSmallB;
 // the same tiles with kappa * w as one bf16 term
-typedef TileCfgB<4, 2, 1, 2, 1, true, 1, 1, 2, 1, 64, false, false> AdjBigF;
-typedef TileCfgB<2, 2, 1, 1, 1, true, 1, 1, 2, 1, 64, false, false> AdjMidF;
-typedef TileCfgB<1, 1, 1, 1, 1, true, 4, 1, 2, 1, 64, false, false> AdjSmallF;
+typedef TileCfgB<4, 2, 1, 2, 1, true, 1, 1, 2, 1, 64, false> AdjBigF;
+typedef TileCfgB<2, 2, 1, 1, 1, true, 1, 1, 2, 1, 64, false> AdjMidF;
+typedef TileCfgB<1, 1, 1, 1, 1, true, 4, 1, 2, 1, 64, false> AdjSmallF;
 // three-term operands (K-slices of 32)
 typedef TileCfgB<2, 2, 2, 2, 1, true, 1, 1, 2, 3, 32> AdjBigS;
 // the same tile with 8 waves of 32 x 64 each: half the accumulators per wave, so that two

@@ -870,9 +870,9 @@ typedef TileCfgB<2, 2, 2, 1, 3, true> PhiBigB;
 typedef TileCfgB<2, 2, 1, 1, 3, true> PhiMidB;
 typedef TileCfgB<1, 1, 1, 1, 3, true, 4> PhiSmallB;
 // the same tiles with the state as one bf16 term
-typedef TileCfgB<2, 2, 2, 1, 3, true, 1, 1, 2, 1, 64, false, false> PhiBigF;
-typedef TileCfgB<2, 2, 1, 1, 3, true, 1, 1, 2, 1, 64, false, false> PhiMidF;
-typedef TileCfgB<1, 1, 1, 1, 3, true, 4, 1, 2, 1, 64, false, false> PhiSmallF;
+typedef TileCfgB<2, 2, 2, 1, 3, true, 1, 1, 2, 1, 64, false> PhiBigF;
+typedef TileCfgB<2, 2, 1, 1, 3, true, 1, 1, 2, 1, 64, false> PhiMidF;
+typedef TileCfgB<1, 1, 1, 1, 3, true, 4, 1, 2, 1, 64, false> PhiSmallF;
 // three-term operands: K-slices of 32 keep two workgroups' tiles in a CU's LDS
 typedef TileCfgB<2, 2, 2, 1, 3, true, 1, 1, 2, 3, 32> PhiBigS;
 typedef TileCfgB<2, 2, 1, 1, 3, true, 1, 1, 2, 3, 32> PhiMidS;

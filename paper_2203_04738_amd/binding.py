@@ -222,7 +222,20 @@ def gru_serial_scan(cfg, W, U, b_i, b_h, x, h0, h_out, workspace) -> None:
           _state(cfg, h_out, "h_out"), *_workspace(workspace))
 
 
+def _check_declared_zero(cfg, flag, tensor, rows, what):
+    """Opt-in check of a zero-guess declaration (environment MGRIT_CHECK_ZERO_GUESS=1): the
+    library trusts MGRIT_ZERO_STATE_GUESS / MGRIT_ZERO_ADJOINT_GUESS; with the variable set the
+    binding looks at the rows the flag declares zero before the call (this reads the tensor
+    back, so it synchronises; meant for debugging a harness, not for timed runs)."""
+    if not (cfg.flags & flag) or os.environ.get("MGRIT_CHECK_ZERO_GUESS") != "1":
+        return
+    import torch
+    if tensor is not None and tensor.is_cuda and int(torch.count_nonzero(tensor[rows])) != 0:
+        raise ValueError(f"{what}: declared zero by the flags, but holds non-zero values")
+
+
 def mgrit_gru_forward(cfg, W, U, b_i, b_h, x, h0, h_inout, resnorm_out, workspace) -> None:
+    _check_declared_zero(cfg, MGRIT_ZERO_STATE_GUESS, h_inout, slice(1, None), "h_inout rows 1..T")
     _call("mgrit_gru_forward", cfg, *_params(cfg, W, U, b_i, b_h, x), _row(cfg, h0, "h0"),
           _state(cfg, h_inout, "h_inout"), _res(cfg, resnorm_out), *_workspace(workspace))
 
@@ -241,6 +254,7 @@ def gru_serial_scan_backward(cfg, W, U, b_i, b_h, x, h, dL_dhT, w_out, dW, dU, d
 
 def mgrit_gru_backward(cfg, W, U, b_i, b_h, x, h, dL_dhT, w_inout, resnorm_out, dW, dU, db_i,
                        db_h, workspace) -> None:
+    _check_declared_zero(cfg, MGRIT_ZERO_ADJOINT_GUESS, w_inout, slice(0, -1), "w_inout rows 0..T-1")
     _call("mgrit_gru_backward", cfg, *_params(cfg, W, U, b_i, b_h, x), _state(cfg, h, "h"),
           _row(cfg, dL_dhT, "dL_dhT"), _state(cfg, w_inout, "w_inout"), _res(cfg, resnorm_out),
           *_grads(cfg, dW, dU, db_i, db_h), *_workspace(workspace))
@@ -255,6 +269,8 @@ def gru_serial_scan_backward_steps(cfg, W, U, b_i, b_h, x, h, dL_dh, w_out, dW, 
 
 def mgrit_gru_backward_steps(cfg, W, U, b_i, b_h, x, h, dL_dh, w_inout, resnorm_out, dW, dU,
                              db_i, db_h, dx, workspace) -> None:
+    _check_declared_zero(cfg, MGRIT_ZERO_ADJOINT_GUESS, w_inout, slice(0, -1), "w_inout rows 0..T-1")
+    _check_declared_zero(cfg, MGRIT_ZERO_ADJOINT_GUESS, dL_dh, slice(0, -1), "dL_dh rows 0..T-1")
     _call("mgrit_gru_backward_steps", cfg, *_params(cfg, W, U, b_i, b_h, x), _state(cfg, h, "h"),
           _state(cfg, dL_dh, "dL_dh"), _state(cfg, w_inout, "w_inout"), _res(cfg, resnorm_out),
           *_grads(cfg, dW, dU, db_i, db_h), _dx(cfg, dx), *_workspace(workspace))

@@ -453,6 +453,26 @@ def test_zero_state_guess_flag_changes_no_bit(gh, dtype, cf, levels, fcf, shape)
         assert np.allclose(a_res, b_res, rtol=1e-6, atol=0)
 
 
+def test_opt_in_check_of_the_zero_guess_declarations(gh, monkeypatch):
+    """With MGRIT_CHECK_ZERO_GUESS=1 the binding refuses a zero-guess flag on tensors that are not
+    zero where the flag says they are (the library itself trusts the declaration)."""
+    import torch
+    import paper_2203_04738_amd as mg
+    from paper_2203_04738_amd.binding import MGRIT_ZERO_ADJOINT_GUESS, MGRIT_ZERO_STATE_GUESS
+    d = random_small(5, 16, 3, 16, 40, scale=0.3)
+    run = gh.GpuRun(d, cf=4, levels=2)
+    monkeypatch.setenv("MGRIT_CHECK_ZERO_GUESS", "1")
+    h = torch.zeros(17, 3, 40, device=gh.DEV)
+    mg.mgrit_gru_forward(run.cfg(1, MGRIT_ZERO_STATE_GUESS), *run._p(), run.t["h0"], h, None, run.ws)
+    torch.cuda.synchronize()
+    with pytest.raises(ValueError):      # h now holds the first iterate
+        mg.mgrit_gru_forward(run.cfg(1, MGRIT_ZERO_STATE_GUESS), *run._p(), run.t["h0"], h, None, run.ws)
+    w = torch.ones(17, 3, 40, device=gh.DEV)
+    with pytest.raises(ValueError):
+        mg.mgrit_gru_backward(run.cfg(1, MGRIT_ZERO_ADJOINT_GUESS), *run._p(), h, run.t["dL_dhT"], w,
+                              None, *run._grads(), run.ws)
+
+
 # ------------------------------------------------------------------ launch structure of a cycle
 
 def test_launch_counts_of_two_fcf_cycles(gh):

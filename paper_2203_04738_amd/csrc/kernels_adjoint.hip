@@ -210,7 +210,8 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void adj_step_kernel(AdjArgs a) {
   }
 }
 
-// bf16 weights: the fp32 products kappa*w are split into hi + lo bf16 tiles.
+// bf16 weights: the fp32 products kappa*w go to LDS as one bf16 tile or as hi + lo tiles
+// (the configuration's A2, see gemm_core_bf16.h).
 struct KapW8 {
   floatx4 k0, k1, w0, w1;
 };

@@ -577,8 +577,8 @@ __global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel(PhiArgs a) {
   }
 }
 
-// bf16 weights: the fp32 state rows are split into hi + lo bf16 tiles (see
-// gemm_core_bf16.h); gates, update and outputs stay fp32.  With a three-term
+// bf16 weights: the fp32 state rows go to LDS as one bf16 tile or as hi + lo tiles (the
+// configuration's A2, see gemm_core_bf16.h); gates, update and outputs stay fp32.  With a three-term
 // configuration the weights are fp32 values held as three bf16 arrays.
 template <class C, int MODE, bool ZS = false>
 __global__ __launch_bounds__(C::NT, C::MINWG) void phi_step_kernel_bf16(PhiArgs a) {

@@ -70,12 +70,18 @@ def parse():
 
 
 def kernel_sources_sha256():
-    """Hash of the sources the forward step kernel is built from (stamps the counter records)."""
+    """Hash of the code the forward step kernel is built from (stamps the counter records):
+    the sources with comments and white space taken out, so that an edited comment does not
+    disown a measurement."""
     import hashlib
+    import re
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2203_04738_amd", "csrc")
     for f in ("common.h", "gates.h", "gemm_core.h", "gemm_core_bf16.h", "kernels_forward.hip"):
-        h.update(open(os.path.join(csrc, f), "rb").read())
+        text = open(os.path.join(csrc, f), "r").read()
+        text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)
+        text = re.sub(r"//[^\n]*", " ", text)
+        h.update("".join(text.split()).encode())
     return h.hexdigest()
 
 

@@ -237,6 +237,7 @@ def test_invalid_call_leaves_buffers_untouched(gh):
 
 TOL_BF16 = 2e-2       # stated bar of the bf16-input / fp32-state variant
 TIGHT_BF16 = 1e-4     # what the hi+lo split of the fp32 operand is expected to reach
+ONE_TERM_SAME_ROUNDING = 1e-3   # one-term form against the oracle fed the same rounded operands
 BF16_FORMS = ["bf16", "bf16s2"]   # state operand as one bf16 term / as two (MGRIT_BF16_STATE2)
 
 
@@ -309,6 +310,44 @@ def test_bf16_mgrit_c4_reduced_twin(gh, form):
     wl = WORKLOADS["C4"].twin()
     d = make_inputs(wl)                 # x, W, U already bf16-representable
     _check_bf16_mgrit(gh, d, wl.cf, wl.levels, 2, form)
+
+
+def test_bf16_one_term_form_against_the_oracle_with_the_same_operand_rounding(gh, monkeypatch):
+    """MGRIT_BF16 rounds the fp32 left operand of the tile kernels' contractions (h in U h,
+    kappa * w in U^T(kappa * w)) to bf16; the stated bar of 2e-2 leaves room for that rounding and
+    would also leave room for a small mistake.  With 70 batch rows every level step of a
+    two-level hierarchy runs in the tile kernels, so applying the same rounding to the left
+    operand of the oracle's contractions (here, in the test: the oracle module is untouched)
+    must reproduce the HIP path far more closely; what remains is fp32 rounding and the few
+    elements whose bf16 rounding flips between the fp32 state and the oracle's fp64 one."""
+    from synthetic_inputs import round_to_bf16
+    T, B, D, H, cf, levels = 32, 70, 16, 40, 4, 2
+    d = _bf16_inputs(random_small(44, T, B, D, H, scale=0.3))
+    plain = orc._rows_times
+
+    def rounded(a, M):
+        return plain(round_to_bf16(np.asarray(a, dtype=np.float32)).astype(np.float64), M)
+
+    run = gh.GpuRun(d, cf=cf, levels=levels, dtype="bf16")
+    gits, _ = run.forward_iterates(2)
+    _, _, exact = orc.mgrit_forward(*_P(d), d["x"], d["h0"], _zeros(d), cf, levels, 2,
+                                    keep_iterates=True)
+    monkeypatch.setattr(orc, "_rows_times", rounded)
+    _, _, rits = orc.mgrit_forward(*_P(d), d["x"], d["h0"], _zeros(d), cf, levels, 2,
+                                   keep_iterates=True)
+    h = gits[-1]
+    out = orc.mgrit_backward(*_P(d), d["x"], h, d["dL_dhT"], _zeros(d), cf, levels, 2,
+                             keep_iterates=True, with_gradients=False)
+    monkeypatch.setattr(orc, "_rows_times", plain)
+    wits, _, _ = run.backward_iterates(h, 2)
+    for i, (g, r, e) in enumerate(zip(gits, rits, exact)):
+        same, plain_err = gh.rel_err(g, r), gh.rel_err(g, e)
+        print("h", i, same, plain_err)
+        assert same <= ONE_TERM_SAME_ROUNDING and plain_err <= TOL_BF16, ("h", i, same, plain_err)
+    for i, (g, r) in enumerate(zip(wits, out[-1])):
+        same = gh.rel_err(g, r)
+        print("w", i, same)
+        assert same <= ONE_TERM_SAME_ROUNDING, ("w", i, same)
 
 
 def test_bf16_rejects_widths_not_multiple_of_8(gh):

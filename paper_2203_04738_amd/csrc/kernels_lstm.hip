@@ -317,6 +317,110 @@ __global__ __launch_bounds__(SK_MAXNT) void lstm_skinny_kernel(PhiArgs a,
   if (MODE == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
 }
 
+// The few-row step on the matrix pipe (v_mfma_f32_16x16x4_f32), as the GRU's phi_fewrow_kernel: a
+// workgroup owns 16 rows and four hidden columns, whose four gates are the 16 columns of the
+// MFMA block; its waves split K (the h half of the state rows), each wave with all loads of its
+// slice in flight before its first MFMA; the partial blocks meet in LDS and thread
+// (row, column) applies the cell.  Lane l supplies A[i = l % 16][k = l / 16] and
+// B[k = l / 16][j = l % 16]; result register v of lane l is D[4 (l / 16) + v][l % 16].
+constexpr int LFR_NC = 4;      // hidden columns per workgroup
+constexpr int LFR_KB = 8;      // blocks of sixteen k whose loads a wave keeps in flight
+constexpr int LFR_MAXW = 8;    // waves per workgroup at most
+
+template <int MODE>
+__global__ __launch_bounds__(64 * LFR_MAXW) void lstm_fewrow_kernel(PhiArgs a, int kslice) {
+  __shared__ float part[LFR_MAXW][16][17];
+  const int S = a.H, H = S / 2;
+  const int R = a.nk * a.B;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int nt = blockDim.x, nw = nt >> 6;
+  const int li = lane & 15, kq = lane >> 4;
+  const int j0 = blockIdx.x * LFR_NC;
+  const int r0 = blockIdx.y * 16;
+  const int rows_here = min(16, R - r0);
+
+  // this thread's output element (if any): its operands are requested before the contraction
+  const int n_out = rows_here * LFR_NC;
+  const bool epi = tid < n_out && j0 + tid % LFR_NC < H;
+  int e_j = 0;
+  LstmRow ero = {};
+  LstmEpiIn ein = {};
+  if (epi) {
+    ero = lstm_row(a, r0 + tid / LFR_NC);
+    e_j = j0 + tid % LFR_NC;
+    ein = lstm_epi_load<MODE>(a, ero, e_j);
+  }
+
+  // A: the h half of this lane's state row (rows beyond the block are clamped)
+  const int r = r0 + min(li, rows_here - 1);
+  const long long pt = (unsigned)r / (unsigned)a.B;
+  const int b = r - (int)pt * a.B;
+  const float* hrow = a.u_in + (a.in.at(pt) * a.B + b) * S;
+  // B: weight row of this lane's MFMA column: gate li / 4, hidden column j0 + li % 4
+  const float* urow = (const float*)a.U +
+                      ((long long)(li / LFR_NC) * H + min(j0 + li % LFR_NC, H - 1)) * H;
+
+  floatx4 acc = zero4(), acc1 = zero4();
+  const int k_end = min(H, (wv + 1) * kslice);
+  for (int kb = wv * kslice; kb < k_end; kb += 16 * LFR_KB) {
+    floatx4 av[LFR_KB], bv[LFR_KB];
+#pragma unroll
+    for (int s = 0; s < LFR_KB; ++s) {
+      const int k = kb + 16 * s + 4 * kq;
+      const int kc = min(k, H - 4);                  // H is a multiple of 4
+      av[s] = ldg4(hrow + kc);
+      bv[s] = ldg4(urow + kc);
+    }
+    __builtin_amdgcn_sched_barrier(0);               // all loads in flight before the first wait
+#pragma unroll
+    for (int s = 0; s < LFR_KB; ++s) {
+      if (kb + 16 * s + 4 * kq >= k_end) av[s] = zero4();
+#pragma unroll
+      for (int e = 0; e < 4; e += 2) {
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s][e], bv[s][e], acc, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s][e + 1], bv[s][e + 1], acc1, 0, 0, 0);
+      }
+    }
+  }
+  acc += acc1;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) part[wv][4 * kq + v][li] = acc[v];
+  __syncthreads();
+
+  double nrm = 0.0;
+  for (int e = tid; e < n_out; e += nt) {
+    const int row = e / LFR_NC, c = e % LFR_NC;
+    const int j = j0 + c;
+    if (j >= H) continue;
+    float sg[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int w = 0; w < nw; ++w)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) sg[g] += part[w][row][g * LFR_NC + c];
+    if (e == tid && epi) {
+      lstm_epi_finish<MODE>(a, ero, e_j, sg, ein, nrm);
+    } else {   // more outputs than threads (one-wave workgroups only)
+      const LstmRow ro = lstm_row(a, r0 + row);
+      lstm_epi_finish<MODE>(a, ro, j, sg, lstm_epi_load<MODE>(a, ro, j), nrm);
+    }
+  }
+  if (MODE == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
+}
+
+static void launch_lstm_fewrow(const PhiArgs& a, hipStream_t s) {
+  const int R = a.nk * a.B, H = a.H / 2;
+  int nw = (H + 127) / 128;
+  nw = nw < 1 ? 1 : (nw > LFR_MAXW ? LFR_MAXW : nw);
+  const int kslice = ((H + nw - 1) / nw + 15) / 16 * 16;
+  const dim3 grid((unsigned)((H + LFR_NC - 1) / LFR_NC), (unsigned)((R + 15) / 16));
+  const dim3 block(64 * nw);
+  if (a.mode == STEP_RELAX)
+    hipLaunchKernelGGL(lstm_fewrow_kernel<STEP_RELAX>, grid, block, 0, s, a, kslice);
+  else if (a.mode == STEP_RESID)
+    hipLaunchKernelGGL(lstm_fewrow_kernel<STEP_RESID>, grid, block, 0, s, a, kslice);
+  else
+    hipLaunchKernelGGL(lstm_fewrow_kernel<STEP_RHS>, grid, block, 0, s, a, kslice);
+}
+
 template <int CT>
 static void launch_lstm_skinny(const PhiArgs& a, dim3 grid, int rb, hipStream_t s) {
   int nt = sk_geom(rb, a.H / 2).nt;
@@ -358,7 +462,9 @@ hipError_t launch_lstm_step(const PhiArgs& a, hipStream_t s) {
   const int H = a.H / 2;
   auto tiles = [&](int tm, int tn) { return ((R + tm - 1) / tm) * ((H + tn - 1) / tn); };
   prof_begin(9, s, R, a.mode);
-  if (R <= 2 * SK_MAXROWS) {
+  if (R <= 2 * SK_MAXROWS && H >= 16) {
+    launch_lstm_fewrow(a, s);
+  } else if (R <= 2 * SK_MAXROWS) {
     const int rb = R < LSTM_SK_ROWS ? (int)R : LSTM_SK_ROWS;
     const int nrb = (int)((R + rb - 1) / rb);
     const int ct = H * nrb >= 512 ? 2 : 1;

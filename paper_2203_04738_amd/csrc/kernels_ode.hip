@@ -281,6 +281,107 @@ __global__ __launch_bounds__(SK_MAXNT) void ode_skinny_kernel(PhiArgs a, int row
   if (MODE == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
 }
 
+// The few-row step on the matrix pipe (v_mfma_f32_16x16x4_f32), as the GRU's phi_fewrow_kernel: a
+// workgroup owns 16 rows and OFR_NC columns of A h (the other MFMA columns idle on copies of
+// the last one: the step is bound by latency, not by the pipe); its waves split K, each wave
+// with all loads of its slice in flight before its first MFMA; the partial blocks meet in LDS
+// and thread (row, column) applies the update.  Lane l supplies A[i = l % 16][k = l / 16] and
+// B[k = l / 16][j = l % 16]; result register v of lane l is D[4 (l / 16) + v][l % 16].
+constexpr int OFR_NC = 5;      // columns per workgroup (as many workgroups as the GRU's step has)
+constexpr int OFR_KB = 8;      // blocks of sixteen k whose loads a wave keeps in flight
+constexpr int OFR_MAXW = 8;    // waves per workgroup at most
+
+template <int MODE>
+__global__ __launch_bounds__(64 * OFR_MAXW) void ode_fewrow_kernel(PhiArgs a, int kslice) {
+  __shared__ float part[OFR_MAXW][16][17];
+  const int H = a.H;
+  const int R = a.nk * a.B;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int nt = blockDim.x, nw = nt >> 6;
+  const int li = lane & 15, kq = lane >> 4;
+  const int j0 = blockIdx.x * OFR_NC;
+  const int r0 = blockIdx.y * 16;
+  const int rows_here = min(16, R - r0);
+
+  // this thread's output element (if any): its operands are requested before the contraction
+  const int n_out = rows_here * OFR_NC;
+  const bool epi = tid < n_out && j0 + tid % OFR_NC < H;
+  int e_j = 0;
+  OdeRow ero = {};
+  OdeEpiIn ein = {};
+  if (epi) {
+    ero = ode_row(a, r0 + tid / OFR_NC);
+    e_j = j0 + tid % OFR_NC;
+    ein = ode_epi_load<MODE>(a, ero, e_j);
+  }
+
+  const int r = r0 + min(li, rows_here - 1);         // rows beyond the block are clamped
+  const long long pt = (unsigned)r / (unsigned)a.B;
+  const int b = r - (int)pt * a.B;
+  const float* hrow = a.u_in + (a.in.at(pt) * a.B + b) * H;
+  const float* urow = (const float*)a.U + (long long)min(j0 + min(li, OFR_NC - 1), H - 1) * H;
+
+  floatx4 acc = zero4(), acc1 = zero4();
+  const int k_end = min(H, (wv + 1) * kslice);
+  for (int kb = wv * kslice; kb < k_end; kb += 16 * OFR_KB) {
+    floatx4 av[OFR_KB], bv[OFR_KB];
+#pragma unroll
+    for (int s = 0; s < OFR_KB; ++s) {
+      const int k = kb + 16 * s + 4 * kq;
+      const int kc = min(k, H - 4);                  // H is a multiple of 4
+      av[s] = ldg4(hrow + kc);
+      bv[s] = ldg4(urow + kc);
+    }
+    __builtin_amdgcn_sched_barrier(0);               // all loads in flight before the first wait
+#pragma unroll
+    for (int s = 0; s < OFR_KB; ++s) {
+      if (kb + 16 * s + 4 * kq >= k_end) av[s] = zero4();
+#pragma unroll
+      for (int e = 0; e < 4; e += 2) {
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s][e], bv[s][e], acc, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[s][e + 1], bv[s][e + 1], acc1, 0, 0, 0);
+      }
+    }
+  }
+  acc += acc1;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) part[wv][4 * kq + v][li] = acc[v];
+  __syncthreads();
+
+  double nrm = 0.0;
+  for (int e = tid; e < n_out; e += nt) {
+    const int row = e / OFR_NC, c = e % OFR_NC;
+    const int j = j0 + c;
+    if (j >= H) continue;
+    float dot = 0.f;
+    for (int w = 0; w < nw; ++w) dot += part[w][row][c];
+    if (e == tid && epi) {
+      ode_epi_finish<MODE>(a, ero, e_j, dot, ein, nrm);
+    } else {   // more outputs than threads (one-wave workgroups only)
+      const OdeRow ro = ode_row(a, r0 + row);
+      ode_epi_finish<MODE>(a, ro, j, dot, ode_epi_load<MODE>(a, ro, j), nrm);
+    }
+  }
+  if (MODE == STEP_RESID && a.norm && nrm != 0.0) atomicAdd(a.norm, nrm);
+}
+
+static void launch_ode_fewrow(const PhiArgs& a, hipStream_t s) {
+  const int R = a.nk * a.B, H = a.H;
+  int nw = (H + 127) / 128;
+  nw = nw < 1 ? 1 : (nw > OFR_MAXW ? OFR_MAXW : nw);
+  const int kslice = ((H + nw - 1) / nw + 15) / 16 * 16;
+  const dim3 grid((unsigned)((H + OFR_NC - 1) / OFR_NC), (unsigned)((R + 15) / 16));
+  const dim3 block(64 * nw);
+  if (a.mode == STEP_RELAX)
+    hipLaunchKernelGGL(ode_fewrow_kernel<STEP_RELAX>, grid, block, 0, s, a, kslice);
+  else if (a.mode == STEP_RELAX_RHS)
+    hipLaunchKernelGGL(ode_fewrow_kernel<STEP_RELAX_RHS>, grid, block, 0, s, a, kslice);
+  else if (a.mode == STEP_RESID)
+    hipLaunchKernelGGL(ode_fewrow_kernel<STEP_RESID>, grid, block, 0, s, a, kslice);
+  else
+    hipLaunchKernelGGL(ode_fewrow_kernel<STEP_RHS>, grid, block, 0, s, a, kslice);
+}
+
 template <int CT>
 static void launch_ode_skinny(const PhiArgs& a, dim3 grid, int rb, hipStream_t s) {
   const dim3 block(sk_geom(rb, a.H).nt);
@@ -324,7 +425,9 @@ hipError_t launch_ode_step(const PhiArgs& a, hipStream_t s) {
   const long long R = (long long)a.nk * a.B;
   auto tiles = [&](int tm, int tn) { return ((R + tm - 1) / tm) * ((a.H + tn - 1) / tn); };
   prof_begin(8, s, R, a.mode);
-  if (R <= 2 * SK_MAXROWS) {
+  if (R <= 2 * SK_MAXROWS && a.H >= 16) {
+    launch_ode_fewrow(a, s);
+  } else if (R <= 2 * SK_MAXROWS) {
     // as many workgroups as the GRU's few-row step has at the same width: H / 2 there
     // (two columns of three gates), H / 4 or H / 2 here
     const int rb = R < ODE_SK_ROWS ? (int)R : ODE_SK_ROWS;
